@@ -1,0 +1,167 @@
+/*
+ * mg_gemm.h  --  C ABI of the MI355X (gfx950) GEMM / batched-GEMM library.
+ *
+ * The routines implement the BLAS GEMM problem the paper builds its library around
+ * (Section 1: GEMM as the core of BLAS and of deep-learning layers; Section 3.1 "Library
+ * Design": the main interface takes pointers to DEVICE memory and leaves all transfers to
+ * the caller), in single precision and in half-precision storage (Section 4.4), plus the
+ * generic batched form of Section 4.6 (batch count, per-instance offsets, per-instance
+ * alpha and beta).  The run-time parameter override of Section 3.3 is exposed too.
+ *
+ *      C  <-  alpha * op(A) * op(B)  +  beta * C          op(X) = X  or  X^T
+ *
+ * op(A) is m x k, op(B) is k x n, C is m x n.  With MG_COL_MAJOR a stored matrix element
+ * (r,c) lives at X[r + c*ld]; with MG_ROW_MAJOR at X[r*ld + c].  Stored A is m x k
+ * (MG_NO_TRANS) or k x m (MG_TRANS); stored B is k x n or n x k.  A leading dimension must
+ * be >= max(1, number of stored rows) for column-major, >= max(1, stored columns) for
+ * row-major.
+ *
+ * Conventions shared by every entry point
+ *   - Every matrix / array pointer is a DEVICE pointer owned by the caller.  The library
+ *     never allocates, frees, copies between host and device, or synchronises; each call
+ *     only enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = the default
+ *     stream) and returns.  Scratch memory, when a configuration needs it, is the caller's
+ *     `workspace` (device memory, 256-byte aligned, at least mg_gemm_workspace_bytes()).
+ *   - Arithmetic: products are accumulated in FP32 (also for FP16 storage); the result
+ *     alpha*acc + beta*C_old is formed in FP32 and rounded once (round-to-nearest-even) to
+ *     the storage type.  beta == 0 means C is not read (NaN/Inf in it do not propagate);
+ *     alpha == 0 or k == 0 means A and B are not read.
+ *   - C must not overlap A or B.  Bytes of C outside the m x n matrix (leading-dimension
+ *     padding, gaps between batched instances) are never written.
+ *   - Return value: MG_OK or a negative mg_status; nothing throws or aborts.  Arguments
+ *     are checked on the host, in the order of the status codes below, before any GPU
+ *     work; device-side contents (offset values, NaNs) are not checked.  When m == 0 or
+ *     n == 0 (or batch_count == 0) the call returns MG_OK without launching anything.
+ *   - The configuration override is process-global and not thread-safe; everything else
+ *     may be called from several host threads.
+ */
+#ifndef MG_GEMM_H
+#define MG_GEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int mg_status;
+
+enum {
+    MG_OK = 0,
+    MG_ERR_LAYOUT = -1,       /* layout is neither MG_ROW_MAJOR nor MG_COL_MAJOR            */
+    MG_ERR_TRANS_A = -2,      /* transA not one of MG_NO_TRANS / MG_TRANS / MG_CONJ_TRANS   */
+    MG_ERR_TRANS_B = -3,
+    MG_ERR_DIM = -4,          /* m, n or k negative, or a matrix too large to index         */
+    MG_ERR_LDA = -5,          /* leading dimension smaller than the stored extent           */
+    MG_ERR_LDB = -6,
+    MG_ERR_LDC = -7,
+    MG_ERR_NULL = -8,         /* a required pointer is NULL while there is work to do       */
+    MG_ERR_BATCH = -9,        /* batch_count negative                                       */
+    MG_ERR_WORKSPACE = -10,   /* workspace NULL/misaligned/too small for the configuration  */
+    MG_ERR_CONFIG = -11,      /* unknown kernel id, or configuration illegal for this call  */
+    MG_ERR_LAUNCH = -12,      /* the HIP runtime refused the launch (see hipGetLastError)   */
+    MG_ERR_NO_DEVICE = -13    /* no usable gfx950 device / HIP runtime error before launch  */
+};
+
+typedef enum { MG_ROW_MAJOR = 101, MG_COL_MAJOR = 102 } mg_layout;
+/* MG_CONJ_TRANS is accepted and equals MG_TRANS for these real types. */
+typedef enum { MG_NO_TRANS = 111, MG_TRANS = 112, MG_CONJ_TRANS = 113 } mg_trans;
+
+typedef enum { MG_F32 = 0, MG_F16 = 1 } mg_dtype;
+
+/* Kernel families (how a problem is mapped onto the GPU). */
+enum {
+    MG_FAMILY_DIRECT = 0,   /* one bounds-checked kernel, any shape/stride/alignment         */
+    MG_FAMILY_MFMA = 1,     /* LDS-staged MFMA macro-tile kernel (the dense-contraction path) */
+    MG_FAMILY_GEMV = 2,     /* m == 1 or n == 1: streaming dot-product kernel                */
+    MG_FAMILY_SCALE = 3,    /* alpha == 0 or k == 0: C <- beta*C only                        */
+    MG_FAMILY_BATCHED = 4   /* many small GEMMs per launch                                   */
+};
+
+/* One kernel configuration: which compiled kernel runs and with which launch-time choices.
+ * kernel_id indexes the library's table of compiled kernels (mg_kernel_count/mg_kernel_info);
+ * the remaining fields describe it and are filled in by the library. */
+typedef struct mg_config {
+    int32_t kernel_id;
+    int32_t family;
+    int32_t dtype;                 /* mg_dtype                                               */
+    int32_t tile_m, tile_n, tile_k;/* work-group macro tile (0 where not applicable)         */
+    int32_t waves_m, waves_n;      /* wavefront grid inside the work-group                   */
+    int32_t split_k;               /* >= 1; > 1 needs workspace                              */
+    int32_t threads;               /* work-group size                                        */
+    int32_t lds_bytes;             /* LDS per work-group                                     */
+    int32_t reserved;
+} mg_config;
+
+/* ---- GEMM (paper Section 1 / Section 3.1) --------------------------------------------
+ * FP32 storage.  alpha, beta: host scalars.  A, B (read) and C (read if beta != 0, written):
+ * device pointers, any 4-byte alignment.  workspace may be NULL when
+ * mg_gemm_workspace_bytes() for the same arguments returns 0. */
+mg_status mg_sgemm(int layout, int trans_a, int trans_b, int64_t m, int64_t n, int64_t k,
+                   float alpha, const float *A, int64_t lda, const float *B, int64_t ldb,
+                   float beta, float *C, int64_t ldc,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/* FP16 storage (paper Section 4.4; here with FP32 accumulation): A, B, C hold IEEE binary16
+ * values (2-byte aligned device pointers); alpha, beta are FP32 host scalars. */
+mg_status mg_hgemm(int layout, int trans_a, int trans_b, int64_t m, int64_t n, int64_t k,
+                   float alpha, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
+                   float beta, uint16_t *C, int64_t ldc,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---- generic batched GEMM (paper Section 4.6) -----------------------------------------
+ * batch_count independent GEMMs of one shape.  Instance b uses A + a_offsets[b],
+ * B + b_offsets[b], C + c_offsets[b] (offsets in ELEMENTS from the base pointer, >= 0),
+ * alphas[b], betas[b].  alphas, betas, *_offsets are DEVICE arrays of batch_count entries.
+ * layout, ops, m, n, k and leading dimensions are shared by all instances.  C regions of
+ * different instances must not overlap; A and B regions may.  Per instance, beta == 0 means
+ * C is not read. */
+mg_status mg_sgemm_batched(int layout, int trans_a, int trans_b, int64_t m, int64_t n, int64_t k,
+                           const float *alphas,
+                           const float *A, const int64_t *a_offsets, int64_t lda,
+                           const float *B, const int64_t *b_offsets, int64_t ldb,
+                           const float *betas,
+                           float *C, const int64_t *c_offsets, int64_t ldc,
+                           int64_t batch_count, void *stream);
+
+/* Bytes of workspace the currently selected configuration needs for this problem
+ * (0 for most).  dtype is an mg_dtype.  Returns 0 for invalid arguments. */
+size_t mg_gemm_workspace_bytes(int dtype, int layout, int trans_a, int trans_b,
+                               int64_t m, int64_t n, int64_t k,
+                               int64_t lda, int64_t ldb, int64_t ldc);
+
+/* ---- configuration table, selection and override (paper Section 3.3) ------------------
+ * Every compiled kernel is result-neutral: any legal configuration gives the same result up
+ * to summation order. */
+int32_t mg_kernel_count(void);
+/* Describes compiled kernel `kernel_id` (split_k = 1). MG_ERR_CONFIG if out of range. */
+mg_status mg_kernel_info(int32_t kernel_id, mg_config *out);
+/* Short static name of a kernel ("?" if out of range). */
+const char *mg_kernel_name(int32_t kernel_id);
+
+/* Which configuration a non-batched call with these arguments would run right now
+ * (honours an active override).  pointer_alignment: the smallest alignment in bytes of
+ * A, B, C (pass 256 when unknown-but-aligned). */
+mg_status mg_query_selected(int dtype, int layout, int trans_a, int trans_b,
+                            int64_t m, int64_t n, int64_t k,
+                            int64_t lda, int64_t ldb, int64_t ldc, float alpha, float beta,
+                            int64_t pointer_alignment, mg_config *out);
+
+/* Force kernel `kernel_id` with `split_k` for later non-batched calls of that kernel's
+ * dtype.  A call for which the forced kernel is illegal (alignment, shape, workspace)
+ * returns MG_ERR_CONFIG / MG_ERR_WORKSPACE instead of falling back silently. */
+mg_status mg_override_config(int32_t kernel_id, int32_t split_k);
+/* Same for the batched routine: kernel_id must be of family MG_FAMILY_BATCHED. */
+mg_status mg_override_batched_config(int32_t kernel_id);
+/* Back to automatic selection (both overrides). */
+void mg_clear_override(void);
+
+const char *mg_status_string(mg_status status);
+/* "major.minor" of this ABI. */
+const char *mg_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MG_GEMM_H */

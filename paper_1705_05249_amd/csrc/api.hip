@@ -1,0 +1,297 @@
+// Host-side boundary: argument validation, canonicalisation to the column-major form,
+// configuration selection / override, and launch.  No allocation, no synchronisation, no
+// host<->device copies happen here (paper Section 3.1: device pointers in, transfers left
+// to the caller).  Validation touches no HIP API, so every error path can be exercised on
+// a machine without a GPU.
+#include <mutex>
+
+#include "internal.h"
+#include "select.h"
+
+namespace mg {
+namespace {
+
+std::vector<KernelEntry> g_table;
+std::once_flag g_once;
+
+int32_t g_override_kernel[2] = {-1, -1};   // per dtype
+int32_t g_override_split[2] = {1, 1};
+int32_t g_override_batched = -1;
+
+const std::vector<KernelEntry> &table()
+{
+    std::call_once(g_once, [] {
+        register_direct(g_table);
+        register_mfma(g_table);
+        register_gemv(g_table);
+        register_batched(g_table);
+        for (size_t i = 0; i < g_table.size(); ++i) g_table[i].cfg.kernel_id = static_cast<int32_t>(i);
+    });
+    return g_table;
+}
+
+bool valid_trans(int t) { return t == MG_NO_TRANS || t == MG_TRANS || t == MG_CONJ_TRANS; }
+
+// Checks everything that does not need the pointers, in status-code order.
+mg_status check_shape(int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, int64_t lda, int64_t ldb,
+                      int64_t ldc)
+{
+    if (layout != MG_ROW_MAJOR && layout != MG_COL_MAJOR) return MG_ERR_LAYOUT;
+    if (!valid_trans(ta)) return MG_ERR_TRANS_A;
+    if (!valid_trans(tb)) return MG_ERR_TRANS_B;
+    if (m < 0 || n < 0 || k < 0) return MG_ERR_DIM;
+    const int64_t lim = int64_t(1) << 31;          // each extent and each matrix must stay indexable
+    if (m >= lim || n >= lim || k >= lim) return MG_ERR_DIM;
+    const bool col = layout == MG_COL_MAJOR;
+    const bool at = ta != MG_NO_TRANS, bt = tb != MG_NO_TRANS;
+    // leading extent of each stored matrix
+    const int64_t a_lead = col ? (at ? k : m) : (at ? m : k);
+    const int64_t b_lead = col ? (bt ? n : k) : (bt ? k : n);
+    const int64_t c_lead = col ? m : n;
+    if (lda < (a_lead > 1 ? a_lead : 1)) return MG_ERR_LDA;
+    if (ldb < (b_lead > 1 ? b_lead : 1)) return MG_ERR_LDB;
+    if (ldc < (c_lead > 1 ? c_lead : 1)) return MG_ERR_LDC;
+    const int64_t a_other = col ? (at ? m : k) : (at ? k : m);
+    const int64_t b_other = col ? (bt ? k : n) : (bt ? n : k);
+    const int64_t c_other = col ? n : m;
+    const __int128 cap = __int128(1) << 40;        // elements; far beyond 288 GB, guards overflow
+    if (__int128(lda) * a_other > cap || __int128(ldb) * b_other > cap || __int128(ldc) * c_other > cap)
+        return MG_ERR_DIM;
+    return MG_OK;
+}
+
+// Row-major C = op(A) op(B) is column-major C^T = op(B)^T op(A)^T on the same bytes:
+// swap the operands and the roles of m and n.
+Problem canonical(int dtype, int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, float alpha,
+                  const void *A, int64_t lda, const void *B, int64_t ldb, float beta, void *C, int64_t ldc,
+                  void *ws, size_t ws_bytes, void *stream)
+{
+    Problem p{};
+    p.dtype = dtype;
+    p.k = k;
+    p.alpha = alpha;
+    p.beta = beta;
+    p.C = C;
+    p.ldc = ldc;
+    p.workspace = ws;
+    p.workspace_bytes = ws_bytes;
+    p.stream = static_cast<hipStream_t>(stream);
+    const bool at = ta != MG_NO_TRANS, bt = tb != MG_NO_TRANS;
+    if (layout == MG_COL_MAJOR) {
+        p.m = m; p.n = n;
+        p.A = A; p.lda = lda; p.a_trans = at;
+        p.B = B; p.ldb = ldb; p.b_trans = bt;
+    } else {
+        p.m = n; p.n = m;
+        p.A = B; p.lda = ldb; p.a_trans = bt;
+        p.B = A; p.ldb = lda; p.b_trans = at;
+    }
+    return p;
+}
+
+int64_t problem_alignment(const Problem &p)
+{
+    int64_t a = pointer_alignment(p.A), b = pointer_alignment(p.B), c = pointer_alignment(p.C);
+    int64_t r = a < b ? a : b;
+    return r < c ? r : c;
+}
+
+// Picks the configuration for a canonical problem: the override if one is active, else the
+// heuristic table.  Returns MG_OK and fills kernel/split, or an error.
+mg_status choose(const Problem &p, int64_t alignment, int32_t *kernel, int32_t *split)
+{
+    const auto &t = table();
+    const int32_t forced = g_override_kernel[p.dtype];
+    if (forced >= 0) {
+        const KernelEntry &e = t[forced];
+        if (!e.legal || !e.legal(p, g_override_split[p.dtype], alignment)) return MG_ERR_CONFIG;
+        *kernel = forced;
+        *split = g_override_split[p.dtype];
+        return MG_OK;
+    }
+    select_config(t, p, alignment, kernel, split);
+    if (*kernel < 0) return MG_ERR_CONFIG;
+    return MG_OK;
+}
+
+mg_status run_gemm(int dtype, int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, float alpha,
+                   const void *A, int64_t lda, const void *B, int64_t ldb, float beta, void *C, int64_t ldc,
+                   void *ws, size_t ws_bytes, void *stream)
+{
+    mg_status s = check_shape(layout, ta, tb, m, n, k, lda, ldb, ldc);
+    if (s != MG_OK) return s;
+    if (m == 0 || n == 0) return MG_OK;
+    const bool reads_ab = alpha != 0.f && k != 0;
+    if (C == nullptr || (reads_ab && (A == nullptr || B == nullptr))) return MG_ERR_NULL;
+    Problem p = canonical(dtype, layout, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, ws, ws_bytes, stream);
+    int32_t kernel = -1, split = 1;
+    s = choose(p, problem_alignment(p), &kernel, &split);
+    if (s != MG_OK) return s;
+    const KernelEntry &e = table()[kernel];
+    const size_t need = e.workspace(p, split);
+    if (need > 0 && (ws == nullptr || ws_bytes < need || pointer_alignment(ws) < 256)) return MG_ERR_WORKSPACE;
+    return e.launch(p, split) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
+}
+
+}  // namespace
+}  // namespace mg
+
+using namespace mg;
+
+extern "C" {
+
+mg_status mg_sgemm(int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, float alpha, const float *A,
+                   int64_t lda, const float *B, int64_t ldb, float beta, float *C, int64_t ldc, void *workspace,
+                   size_t workspace_bytes, void *stream)
+{
+    return run_gemm(MG_F32, layout, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, workspace,
+                    workspace_bytes, stream);
+}
+
+mg_status mg_hgemm(int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, float alpha, const uint16_t *A,
+                   int64_t lda, const uint16_t *B, int64_t ldb, float beta, uint16_t *C, int64_t ldc,
+                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_gemm(MG_F16, layout, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, workspace,
+                    workspace_bytes, stream);
+}
+
+mg_status mg_sgemm_batched(int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, const float *alphas,
+                           const float *A, const int64_t *a_offsets, int64_t lda, const float *B,
+                           const int64_t *b_offsets, int64_t ldb, const float *betas, float *C,
+                           const int64_t *c_offsets, int64_t ldc, int64_t batch_count, void *stream)
+{
+    mg_status s = check_shape(layout, ta, tb, m, n, k, lda, ldb, ldc);
+    if (s != MG_OK) return s;
+    if (batch_count < 0) return MG_ERR_BATCH;
+    if (batch_count >= (int64_t(1) << 31)) return MG_ERR_BATCH;
+    if (m == 0 || n == 0 || batch_count == 0) return MG_OK;
+    if (!alphas || !betas || !a_offsets || !b_offsets || !c_offsets || !C) return MG_ERR_NULL;
+    if (k != 0 && (!A || !B)) return MG_ERR_NULL;
+    BatchedProblem p{};
+    const bool at = ta != MG_NO_TRANS, bt = tb != MG_NO_TRANS;
+    p.k = k;
+    p.C = C; p.c_off = c_offsets; p.ldc = ldc;
+    p.alphas = alphas; p.betas = betas;
+    p.batch = batch_count;
+    p.stream = static_cast<hipStream_t>(stream);
+    if (layout == MG_COL_MAJOR) {
+        p.m = m; p.n = n;
+        p.A = A; p.a_off = a_offsets; p.lda = lda; p.a_trans = at;
+        p.B = B; p.b_off = b_offsets; p.ldb = ldb; p.b_trans = bt;
+    } else {
+        p.m = n; p.n = m;
+        p.A = B; p.a_off = b_offsets; p.lda = ldb; p.a_trans = bt;
+        p.B = A; p.b_off = a_offsets; p.ldb = lda; p.b_trans = at;
+    }
+    const auto &t = table();
+    int32_t kernel = -1;
+    if (g_override_batched >= 0) {
+        const KernelEntry &e = t[g_override_batched];
+        if (!e.legal_batched || !e.legal_batched(p)) return MG_ERR_CONFIG;
+        kernel = g_override_batched;
+    } else {
+        kernel = select_batched(t, p);
+        if (kernel < 0) return MG_ERR_CONFIG;
+    }
+    return t[kernel].launch_batched(p) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
+}
+
+size_t mg_gemm_workspace_bytes(int dtype, int layout, int ta, int tb, int64_t m, int64_t n, int64_t k,
+                               int64_t lda, int64_t ldb, int64_t ldc)
+{
+    if (dtype != MG_F32 && dtype != MG_F16) return 0;
+    if (check_shape(layout, ta, tb, m, n, k, lda, ldb, ldc) != MG_OK || m == 0 || n == 0) return 0;
+    // scalars do not change the need except through the scale-only path, which needs none
+    Problem p = canonical(dtype, layout, ta, tb, m, n, k, 1.f, nullptr, lda, nullptr, ldb, 1.f, nullptr, ldc,
+                          nullptr, 0, nullptr);
+    int32_t kernel = -1, split = 1;
+    if (choose(p, 256, &kernel, &split) != MG_OK) return 0;
+    return table()[kernel].workspace(p, split);
+}
+
+int32_t mg_kernel_count(void) { return static_cast<int32_t>(table().size()); }
+
+mg_status mg_kernel_info(int32_t kernel_id, mg_config *out)
+{
+    if (kernel_id < 0 || kernel_id >= mg_kernel_count() || out == nullptr) return MG_ERR_CONFIG;
+    *out = table()[kernel_id].cfg;
+    return MG_OK;
+}
+
+const char *mg_kernel_name(int32_t kernel_id)
+{
+    if (kernel_id < 0 || kernel_id >= mg_kernel_count()) return "?";
+    return table()[kernel_id].name;
+}
+
+mg_status mg_query_selected(int dtype, int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, int64_t lda,
+                            int64_t ldb, int64_t ldc, float alpha, float beta, int64_t pointer_alignment_bytes,
+                            mg_config *out)
+{
+    if ((dtype != MG_F32 && dtype != MG_F16) || out == nullptr) return MG_ERR_CONFIG;
+    mg_status s = check_shape(layout, ta, tb, m, n, k, lda, ldb, ldc);
+    if (s != MG_OK) return s;
+    if (m == 0 || n == 0) return MG_ERR_CONFIG;     // nothing would run
+    Problem p = canonical(dtype, layout, ta, tb, m, n, k, alpha, nullptr, lda, nullptr, ldb, beta, nullptr, ldc,
+                          nullptr, 0, nullptr);
+    int64_t al = pointer_alignment_bytes;
+    if (al <= 0 || (al & (al - 1)) != 0) return MG_ERR_CONFIG;
+    if (al > 256) al = 256;
+    int32_t kernel = -1, split = 1;
+    s = choose(p, al, &kernel, &split);
+    if (s != MG_OK) return s;
+    *out = table()[kernel].cfg;
+    out->split_k = split;
+    return MG_OK;
+}
+
+mg_status mg_override_config(int32_t kernel_id, int32_t split_k)
+{
+    if (kernel_id < 0 || kernel_id >= mg_kernel_count() || split_k < 1 || split_k > 256) return MG_ERR_CONFIG;
+    const KernelEntry &e = table()[kernel_id];
+    if (e.launch == nullptr) return MG_ERR_CONFIG;
+    g_override_kernel[e.cfg.dtype] = kernel_id;
+    g_override_split[e.cfg.dtype] = split_k;
+    return MG_OK;
+}
+
+mg_status mg_override_batched_config(int32_t kernel_id)
+{
+    if (kernel_id < 0 || kernel_id >= mg_kernel_count()) return MG_ERR_CONFIG;
+    if (table()[kernel_id].launch_batched == nullptr) return MG_ERR_CONFIG;
+    g_override_batched = kernel_id;
+    return MG_OK;
+}
+
+void mg_clear_override(void)
+{
+    g_override_kernel[0] = g_override_kernel[1] = -1;
+    g_override_split[0] = g_override_split[1] = 1;
+    g_override_batched = -1;
+}
+
+const char *mg_status_string(mg_status status)
+{
+    switch (status) {
+        case MG_OK: return "ok";
+        case MG_ERR_LAYOUT: return "invalid layout";
+        case MG_ERR_TRANS_A: return "invalid transA";
+        case MG_ERR_TRANS_B: return "invalid transB";
+        case MG_ERR_DIM: return "negative or too large dimension";
+        case MG_ERR_LDA: return "lda too small";
+        case MG_ERR_LDB: return "ldb too small";
+        case MG_ERR_LDC: return "ldc too small";
+        case MG_ERR_NULL: return "null pointer";
+        case MG_ERR_BATCH: return "invalid batch count";
+        case MG_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case MG_ERR_CONFIG: return "unknown or illegal kernel configuration";
+        case MG_ERR_LAUNCH: return "kernel launch failed";
+        case MG_ERR_NO_DEVICE: return "no usable device";
+        default: return "unknown status";
+    }
+}
+
+const char *mg_version(void) { return "0.1"; }
+
+}  // extern "C"

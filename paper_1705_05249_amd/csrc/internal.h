@@ -1,0 +1,90 @@
+// Internal declarations shared by the host-side boundary and the kernel translation units.
+// Everything past the C ABI works on one canonical problem form: column-major storage,
+// row-major calls having been turned into the transposed product C^T = op(B)^T op(A)^T.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "../../include/mg_gemm.h"
+
+namespace mg {
+
+// Canonical (column-major) GEMM problem.  Element access:
+//   op(A)(i,l) = A[i*a_sm + l*a_sk]   (a_sm == 1: contiguous along m; a_sk == 1: along k)
+//   op(B)(l,j) = B[l*b_sk + j*b_sn]
+//   C(i,j)     = C[i + j*ldc]
+struct Problem {
+    int dtype;                 // mg_dtype
+    int64_t m, n, k;
+    const void *A;
+    int64_t lda;
+    bool a_trans;              // true: stored k x m, contiguous along k
+    const void *B;
+    int64_t ldb;
+    bool b_trans;              // false: stored k x n, contiguous along k; true: contiguous along n
+    void *C;
+    int64_t ldc;
+    float alpha, beta;
+    void *workspace;
+    size_t workspace_bytes;
+    hipStream_t stream;
+
+    int64_t a_sm() const { return a_trans ? lda : 1; }
+    int64_t a_sk() const { return a_trans ? 1 : lda; }
+    int64_t b_sk() const { return b_trans ? ldb : 1; }
+    int64_t b_sn() const { return b_trans ? 1 : ldb; }
+    size_t elem() const { return dtype == MG_F32 ? 4 : 2; }
+};
+
+// Canonical batched problem (FP32): per-instance scalars and element offsets live on the device.
+struct BatchedProblem {
+    int64_t m, n, k;
+    const float *A;
+    const int64_t *a_off;
+    int64_t lda;
+    bool a_trans;
+    const float *B;
+    const int64_t *b_off;
+    int64_t ldb;
+    bool b_trans;
+    float *C;
+    const int64_t *c_off;
+    int64_t ldc;
+    const float *alphas, *betas;
+    int64_t batch;
+    hipStream_t stream;
+};
+
+// One compiled kernel (or kernel family instance) in the configuration table.
+struct KernelEntry {
+    const char *name;
+    mg_config cfg;                                           // kernel_id filled in at registration
+    // alignment: smallest alignment in bytes of the three base pointers (power of two, <= 256)
+    bool (*legal)(const Problem &, int split_k, int64_t alignment);
+    size_t (*workspace)(const Problem &, int split_k);        // bytes needed (0 if none)
+    hipError_t (*launch)(const Problem &, int split_k);
+    bool (*legal_batched)(const BatchedProblem &);
+    hipError_t (*launch_batched)(const BatchedProblem &);
+};
+
+// Registration functions, one per translation unit; called once, in this order.
+void register_direct(std::vector<KernelEntry> &table);
+void register_mfma(std::vector<KernelEntry> &table);
+void register_gemv(std::vector<KernelEntry> &table);
+void register_batched(std::vector<KernelEntry> &table);
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+inline int64_t pointer_alignment(const void *p)
+{
+    uintptr_t v = reinterpret_cast<uintptr_t>(p);
+    if (v == 0) return 256;
+    int64_t a = static_cast<int64_t>(v & (~v + 1));
+    return a > 256 ? 256 : a;
+}
+
+}  // namespace mg

@@ -1,0 +1,204 @@
+"""Thin ctypes binding of libmg_gemm.so: same names and argument order as include/mg_gemm.h.
+
+Argument marshalling only -- every step of the computation runs in the HIP kernels.  Matrix
+arguments may be torch tensors on the GPU (their data_ptr() is passed) or raw integer device
+addresses.  The stream defaults to torch's current HIP stream.  If the shared library has not
+been built the import of this module's functions raises: there is no CPU fallback.
+"""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libmg_gemm.so")
+
+MG_ROW_MAJOR, MG_COL_MAJOR = 101, 102
+MG_NO_TRANS, MG_TRANS, MG_CONJ_TRANS = 111, 112, 113
+MG_F32, MG_F16 = 0, 1
+MG_OK = 0
+MG_FAMILY_DIRECT, MG_FAMILY_MFMA, MG_FAMILY_GEMV, MG_FAMILY_SCALE, MG_FAMILY_BATCHED = 0, 1, 2, 3, 4
+
+EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemm_batched", "mg_gemm_workspace_bytes", "mg_kernel_count",
+           "mg_kernel_info", "mg_kernel_name", "mg_query_selected", "mg_override_config",
+           "mg_override_batched_config", "mg_clear_override", "mg_status_string", "mg_version")
+
+
+class mg_config(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_int32) for name in
+                ("kernel_id", "family", "dtype", "tile_m", "tile_n", "tile_k", "waves_m", "waves_n",
+                 "split_k", "threads", "lds_bytes", "reserved")]
+
+    def as_dict(self):
+        return {name: getattr(self, name) for name, _ in self._fields_}
+
+
+class MgError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library (loads it on first use; raises if it was never built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it first "
+                               "(python -c 'import __graft_entry__ as g; g.build()')")
+        L = ctypes.CDLL(LIB_PATH)
+        i32, i64, f32, vp, sz = ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
+        gemm_args = [i32, i32, i32, i64, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64, vp, sz, vp]
+        L.mg_sgemm.argtypes = gemm_args
+        L.mg_sgemm.restype = i32
+        L.mg_hgemm.argtypes = gemm_args
+        L.mg_hgemm.restype = i32
+        L.mg_sgemm_batched.argtypes = [i32, i32, i32, i64, i64, i64, vp, vp, vp, i64, vp, vp, i64, vp, vp, vp, i64,
+                                       i64, vp]
+        L.mg_sgemm_batched.restype = i32
+        L.mg_gemm_workspace_bytes.argtypes = [i32, i32, i32, i32, i64, i64, i64, i64, i64, i64]
+        L.mg_gemm_workspace_bytes.restype = sz
+        L.mg_kernel_count.argtypes = []
+        L.mg_kernel_count.restype = ctypes.c_int32
+        L.mg_kernel_info.argtypes = [ctypes.c_int32, ctypes.POINTER(mg_config)]
+        L.mg_kernel_info.restype = i32
+        L.mg_kernel_name.argtypes = [ctypes.c_int32]
+        L.mg_kernel_name.restype = ctypes.c_char_p
+        L.mg_query_selected.argtypes = [i32, i32, i32, i32, i64, i64, i64, i64, i64, i64, f32, f32, i64,
+                                        ctypes.POINTER(mg_config)]
+        L.mg_query_selected.restype = i32
+        L.mg_override_config.argtypes = [ctypes.c_int32, ctypes.c_int32]
+        L.mg_override_config.restype = i32
+        L.mg_override_batched_config.argtypes = [ctypes.c_int32]
+        L.mg_override_batched_config.restype = i32
+        L.mg_clear_override.argtypes = []
+        L.mg_clear_override.restype = None
+        L.mg_status_string.argtypes = [i32]
+        L.mg_status_string.restype = ctypes.c_char_p
+        L.mg_version.argtypes = []
+        L.mg_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _addr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()          # torch tensor
+
+
+def _stream(stream):
+    if stream is not None:
+        return _addr(stream) if not hasattr(stream, "cuda_stream") else stream.cuda_stream
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+def status_string(status: int) -> str:
+    return lib().mg_status_string(status).decode()
+
+
+def mg_sgemm(layout, trans_a, trans_b, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, workspace=None, stream=None,
+             check=True) -> int:
+    ws, ws_bytes = _ws(workspace)
+    st = lib().mg_sgemm(layout, trans_a, trans_b, m, n, k, alpha, _addr(A), lda, _addr(B), ldb, beta, _addr(C),
+                        ldc, ws, ws_bytes, _stream(stream))
+    if check and st != MG_OK:
+        raise MgError(st, "mg_sgemm")
+    return st
+
+
+def mg_hgemm(layout, trans_a, trans_b, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, workspace=None, stream=None,
+             check=True) -> int:
+    ws, ws_bytes = _ws(workspace)
+    st = lib().mg_hgemm(layout, trans_a, trans_b, m, n, k, alpha, _addr(A), lda, _addr(B), ldb, beta, _addr(C),
+                        ldc, ws, ws_bytes, _stream(stream))
+    if check and st != MG_OK:
+        raise MgError(st, "mg_hgemm")
+    return st
+
+
+def mg_sgemm_batched(layout, trans_a, trans_b, m, n, k, alphas, A, a_offsets, lda, B, b_offsets, ldb, betas, C,
+                     c_offsets, ldc, batch_count, stream=None, check=True) -> int:
+    st = lib().mg_sgemm_batched(layout, trans_a, trans_b, m, n, k, _addr(alphas), _addr(A), _addr(a_offsets), lda,
+                                _addr(B), _addr(b_offsets), ldb, _addr(betas), _addr(C), _addr(c_offsets), ldc,
+                                batch_count, _stream(stream))
+    if check and st != MG_OK:
+        raise MgError(st, "mg_sgemm_batched")
+    return st
+
+
+def mg_gemm_workspace_bytes(dtype, layout, trans_a, trans_b, m, n, k, lda, ldb, ldc) -> int:
+    return int(lib().mg_gemm_workspace_bytes(dtype, layout, trans_a, trans_b, m, n, k, lda, ldb, ldc))
+
+
+def mg_kernel_count() -> int:
+    return int(lib().mg_kernel_count())
+
+
+def mg_kernel_info(kernel_id: int) -> dict:
+    cfg = mg_config()
+    st = lib().mg_kernel_info(kernel_id, ctypes.byref(cfg))
+    if st != MG_OK:
+        raise MgError(st, "mg_kernel_info")
+    d = cfg.as_dict()
+    d["name"] = mg_kernel_name(kernel_id)
+    return d
+
+
+def mg_kernel_name(kernel_id: int) -> str:
+    return lib().mg_kernel_name(kernel_id).decode()
+
+
+def mg_query_selected(dtype, layout, trans_a, trans_b, m, n, k, lda, ldb, ldc, alpha=1.0, beta=0.0,
+                      pointer_alignment=256) -> dict:
+    cfg = mg_config()
+    st = lib().mg_query_selected(dtype, layout, trans_a, trans_b, m, n, k, lda, ldb, ldc, alpha, beta,
+                                 pointer_alignment, ctypes.byref(cfg))
+    if st != MG_OK:
+        raise MgError(st, "mg_query_selected")
+    d = cfg.as_dict()
+    d["name"] = mg_kernel_name(cfg.kernel_id)
+    return d
+
+
+def mg_override_config(kernel_id: int, split_k: int = 1, check=True) -> int:
+    st = lib().mg_override_config(kernel_id, split_k)
+    if check and st != MG_OK:
+        raise MgError(st, "mg_override_config")
+    return st
+
+
+def mg_override_batched_config(kernel_id: int, check=True) -> int:
+    st = lib().mg_override_batched_config(kernel_id)
+    if check and st != MG_OK:
+        raise MgError(st, "mg_override_batched_config")
+    return st
+
+
+def mg_clear_override() -> None:
+    lib().mg_clear_override()
+
+
+def mg_version() -> str:
+    return lib().mg_version().decode()
+
+
+def kernel_table():
+    return [mg_kernel_info(i) for i in range(mg_kernel_count())]
+
+
+def kernel_id(name: str) -> int:
+    for i in range(mg_kernel_count()):
+        if mg_kernel_name(i) == name:
+            return i
+    raise KeyError(name)

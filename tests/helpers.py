@@ -1,0 +1,123 @@
+"""Shared plumbing of the GPU parity tests: move a seeded case to the GPU, call the C ABI through
+the Python binding, bring C back, compare with the CPU oracle element by element."""
+import numpy as np
+
+from paper_1705_05249_amd import workloads as W
+
+TOL = {"f32": 1e-5, "f16": 2e-3}        # max |C - C_ref| / (|alpha| |A||B| + |beta| |C|)
+
+
+def to_gpu(arr):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(arr)).cuda()
+
+
+def workspace_for(case):
+    import torch
+    from paper_1705_05249_amd import gemm as G
+    need = G.mg_gemm_workspace_bytes(G.MG_F32 if case.dtype == "f32" else G.MG_F16, case.layout, case.ta, case.tb,
+                                     case.m, case.n, case.k, case.lda, case.ldb, case.ldc)
+    return torch.empty(max(need, 256), dtype=torch.uint8, device="cuda") if need else None
+
+
+def run_gpu(case, workspace="auto", check=True, offset_elems=(0, 0, 0)):
+    """Runs one GemmCase; returns (status, flat C buffer after the call as numpy).
+    offset_elems shifts the three base pointers inside larger allocations (alignment tests)."""
+    import torch
+    from paper_1705_05249_amd import gemm as G
+    fn = G.mg_sgemm if case.dtype == "f32" else G.mg_hgemm
+    bufs = []
+    for arr, off in zip((case.A, case.B, case.C), offset_elems):
+        host = arr if arr.size else np.zeros(1, dtype=arr.dtype)
+        if off:
+            host = np.concatenate([np.zeros(off, dtype=arr.dtype), host])
+        bufs.append(to_gpu(host))
+    views = [b[off:] for b, off in zip(bufs, offset_elems)]
+    ws = workspace_for(case) if isinstance(workspace, str) else workspace
+    st = fn(case.layout, case.ta, case.tb, case.m, case.n, case.k, case.alpha, views[0], case.lda, views[1],
+            case.ldb, case.beta, views[2], case.ldc, ws, None, check=check)
+    torch.cuda.synchronize()
+    out = views[2].cpu().numpy()[: case.C.size]
+    return st, out
+
+
+def bits(a):
+    return a.view(np.uint32 if a.dtype == np.float32 else np.uint16)
+
+
+def assert_padding_untouched(case, out):
+    mask = W.padding_mask(case.layout, case.m, case.n, case.ldc, case.C.size)
+    assert np.array_equal(bits(out)[mask], bits(case.C)[mask]), f"{case.name}: bytes outside C were written"
+
+
+def rel_error(got, c_ref, d_ref):
+    """max |got - ref| / D over entries with D > 0; entries with D == 0 must be exactly 0"""
+    got = got.astype(np.float64)
+    zero = d_ref == 0
+    assert np.all(got[zero] == 0), "entries with zero denominator must be exactly zero"
+    if np.all(zero):
+        return 0.0
+    err = np.abs(got[~zero] - c_ref[~zero]) / d_ref[~zero]
+    assert not np.any(np.isnan(err)), "NaN in result"
+    return float(err.max())
+
+
+def check_case(case, oracle, sampled=False, workspace="auto", offset_elems=(0, 0, 0), seed=1):
+    """Full (or sampled) element-by-element comparison of one case against the oracle."""
+    st, out = run_gpu(case, workspace=workspace, offset_elems=offset_elems)
+    assert st == 0
+    assert_padding_untouched(case, out)
+    got = W.unpack(out, case.layout, case.m, case.n, case.ldc)
+    args = (case.dtype, case.layout, case.ta, case.tb, case.m, case.n, case.k, case.alpha, case.A, case.lda,
+            case.B, case.ldb, case.beta, case.C, case.ldc)
+    if sampled:
+        rows, cols = W.sample_entries(case.m, case.n, seed=seed)
+        c_ref, d_ref = oracle.gemm_entries(*args, rows, cols)
+        got = got[rows, cols]
+    else:
+        c_ref, d_ref = oracle.gemm(*args)
+    if case.exact:
+        assert np.array_equal(got.astype(np.float64), c_ref), f"{case.name}: not bit-exact on integer inputs"
+        return 0.0
+    err = rel_error(got, c_ref, d_ref)
+    assert err <= TOL[case.dtype], f"{case.name}: relative error {err:.3e} > {TOL[case.dtype]:.1e}"
+    return err
+
+
+def run_batched_gpu(bc, check=True):
+    import torch
+    from paper_1705_05249_amd import gemm as G
+    t = {name: to_gpu(getattr(bc, name)) for name in ("A", "B", "C", "a_off", "b_off", "c_off", "alphas", "betas")}
+    st = G.mg_sgemm_batched(bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, t["alphas"], t["A"], t["a_off"], bc.lda,
+                            t["B"], t["b_off"], bc.ldb, t["betas"], t["C"], t["c_off"], bc.ldc, bc.batch,
+                            check=check)
+    torch.cuda.synchronize()
+    return st, t["C"].cpu().numpy()
+
+
+def batched_outputs(bc, out):
+    """(batch, m, n) array of the C matrices inside the flat buffer, plus mask of bytes outside them"""
+    mask = np.ones(out.size, dtype=bool)
+    major, minor = (bc.n, bc.m) if bc.layout == W.COL_MAJOR else (bc.m, bc.n)
+    idx = (np.arange(major, dtype=np.int64)[:, None] * bc.ldc + np.arange(minor, dtype=np.int64)[None, :])
+    full = bc.c_off[:, None, None] + idx[None, :, :]                    # (batch, major, minor)
+    mask[full.reshape(-1)] = False
+    mats = out[full]
+    if bc.layout == W.COL_MAJOR:
+        mats = mats.transpose(0, 2, 1)
+    return mats, mask
+
+
+def check_batched(bc, oracle, exact=False):
+    st, out = run_batched_gpu(bc)
+    assert st == 0
+    mats, mask = batched_outputs(bc, out)
+    assert np.array_equal(bits(out)[mask], bits(bc.C)[mask]), f"{bc.name}: gap / padding bytes were written"
+    c_ref, d_ref = oracle.sgemm_batched(bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, bc.alphas, bc.A, bc.a_off,
+                                        bc.lda, bc.B, bc.b_off, bc.ldb, bc.betas, bc.C, bc.c_off, bc.ldc)
+    if exact:
+        assert np.array_equal(mats.astype(np.float64), c_ref), f"{bc.name}: not bit-exact on integer inputs"
+        return 0.0
+    err = rel_error(mats, c_ref, d_ref)
+    assert err <= TOL["f32"], f"{bc.name}: relative error {err:.3e}"
+    return err

@@ -1,0 +1,143 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and turns every invalid argument into its status code before touching HIP."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1705_05249_amd import gemm as G
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+R, C, N, T = G.MG_ROW_MAJOR, G.MG_COL_MAJOR, G.MG_NO_TRANS, G.MG_TRANS
+FAKE = 0x1000          # never dereferenced: every call below fails validation or returns early
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mg_gemm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mg_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    names = declared_symbols()
+    assert set(names) == set(G.EXPORTS)
+    lib = G.lib()
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def sgemm(layout=C, ta=N, tb=N, m=4, n=5, k=6, lda=None, ldb=None, ldc=None, A=FAKE, B=FAKE, Cp=FAKE,
+          alpha=1.0, beta=0.0, fn=None):
+    col = layout == C
+    lda = lda if lda is not None else max(1, (m if ta == N else k) if col else (k if ta == N else m))
+    ldb = ldb if ldb is not None else max(1, (k if tb == N else n) if col else (n if tb == N else k))
+    ldc = ldc if ldc is not None else max(1, m if col else n)
+    fn = fn or G.mg_sgemm
+    return fn(layout, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, Cp, ldc, None, 0, check=False)
+
+
+@pytest.mark.parametrize("fn", [G.mg_sgemm, G.mg_hgemm])
+def test_argument_errors(fn):
+    assert sgemm(layout=100, fn=fn) == -1
+    assert sgemm(ta=110, fn=fn) == -2
+    assert sgemm(tb=114, fn=fn) == -3
+    assert sgemm(layout=100, ta=0, fn=fn) == -1            # reported in status-code order
+    assert sgemm(m=-1, fn=fn) == -4
+    assert sgemm(n=-1, fn=fn) == -4
+    assert sgemm(k=-1, fn=fn) == -4
+    assert sgemm(m=2 ** 31, lda=2 ** 31, ldc=2 ** 31, fn=fn) == -4
+    for layout in (R, C):
+        for ta in (N, T):
+            for tb in (N, T):
+                col = layout == C
+                a_lead = (4 if ta == N else 6) if col else (6 if ta == N else 4)
+                b_lead = (6 if tb == N else 5) if col else (5 if tb == N else 6)
+                c_lead = 4 if col else 5
+                assert sgemm(layout, ta, tb, lda=a_lead - 1, fn=fn) == -5
+                assert sgemm(layout, ta, tb, ldb=b_lead - 1, fn=fn) == -6
+                assert sgemm(layout, ta, tb, ldc=c_lead - 1, fn=fn) == -7
+    assert sgemm(lda=0, m=0, fn=fn) == -5                  # ld >= 1 even for empty matrices
+    assert sgemm(A=None, fn=fn) == -8
+    assert sgemm(B=None, fn=fn) == -8
+    assert sgemm(Cp=None, fn=fn) == -8
+    assert sgemm(ta=G.MG_CONJ_TRANS, m=0, fn=fn) == 0       # conj-trans accepted
+
+
+@pytest.mark.parametrize("fn", [G.mg_sgemm, G.mg_hgemm])
+def test_quick_returns_launch_nothing(fn):
+    assert sgemm(m=0, A=None, B=None, Cp=None, fn=fn) == 0
+    assert sgemm(n=0, A=None, B=None, Cp=None, fn=fn) == 0
+
+
+def batched(m=4, n=4, k=4, batch=3, alphas=FAKE, betas=FAKE, A=FAKE, B=FAKE, Cp=FAKE, ao=FAKE, bo=FAKE, co=FAKE,
+            layout=C, ta=N, tb=N, lda=4, ldb=4, ldc=4):
+    return G.mg_sgemm_batched(layout, ta, tb, m, n, k, alphas, A, ao, lda, B, bo, ldb, betas, Cp, co, ldc, batch, stream=0,
+                              check=False)
+
+
+def test_batched_argument_errors():
+    assert batched(layout=7) == -1
+    assert batched(ta=1) == -2
+    assert batched(tb=1) == -3
+    assert batched(k=-2) == -4
+    assert batched(lda=3) == -5
+    assert batched(ldb=3) == -6
+    assert batched(ldc=3) == -7
+    assert batched(batch=-1) == -9
+    for name in ("alphas", "betas", "A", "B", "Cp", "ao", "bo", "co"):
+        assert batched(**{name: None}) == -8
+    assert batched(batch=0, alphas=None, A=None) == 0
+    assert batched(m=0, alphas=None, A=None) == 0
+
+
+def test_status_strings_and_version():
+    seen = set()
+    for code in range(0, -14, -1):
+        s = G.status_string(code)
+        assert s and s != "unknown status" and s not in seen
+        seen.add(s)
+    assert G.status_string(-99) == "unknown status"
+    assert re.fullmatch(r"\d+\.\d+", G.mg_version())
+
+
+def test_kernel_table_and_override_validation():
+    table = G.kernel_table()
+    assert len(table) == G.mg_kernel_count() >= 5
+    assert len({t["name"] for t in table}) == len(table)
+    for i, t in enumerate(table):
+        assert t["kernel_id"] == i and t["dtype"] in (G.MG_F32, G.MG_F16) and t["split_k"] == 1
+    assert G.mg_kernel_name(-1) == "?" and G.mg_kernel_name(10 ** 6) == "?"
+    cfg = G.mg_config()
+    assert G.lib().mg_kernel_info(len(table), ctypes.byref(cfg)) == -11
+    assert G.mg_override_config(-1, 1, check=False) == -11
+    assert G.mg_override_config(0, 0, check=False) == -11
+    batched_ids = [t["kernel_id"] for t in table if t["family"] == G.MG_FAMILY_BATCHED]
+    plain_ids = [t["kernel_id"] for t in table if t["family"] != G.MG_FAMILY_BATCHED]
+    assert G.mg_override_config(batched_ids[0], 1, check=False) == -11
+    assert G.mg_override_batched_config(plain_ids[0], check=False) == -11
+    G.mg_clear_override()
+
+
+def test_query_selected_and_override_roundtrip():
+    try:
+        sel = G.mg_query_selected(G.MG_F32, C, N, N, 256, 256, 256, 256, 256, 256, 1.5, 0.5)
+        assert sel["dtype"] == G.MG_F32 and sel["family"] in (G.MG_FAMILY_DIRECT, G.MG_FAMILY_MFMA)
+        scale = G.mg_query_selected(G.MG_F16, R, T, N, 64, 64, 64, 64, 64, 64, 0.0, 2.0)
+        assert scale["family"] == G.MG_FAMILY_SCALE and scale["dtype"] == G.MG_F16
+        direct = G.kernel_id("direct_f32_64x64x16")
+        G.mg_override_config(direct, 1)
+        forced = G.mg_query_selected(G.MG_F32, C, N, N, 4096, 4096, 4096, 4096, 4096, 4096)
+        assert forced["kernel_id"] == direct
+        # the FP32 override does not leak into FP16 calls
+        other = G.mg_query_selected(G.MG_F16, C, N, N, 4096, 4096, 4096, 4096, 4096, 4096)
+        assert other["dtype"] == G.MG_F16
+        # a forced kernel that is illegal for the call is an error, not a silent fallback
+        assert G.mg_override_config(direct, 4, check=False) == 0
+        cfg = G.mg_config()
+        st = G.lib().mg_query_selected(G.MG_F32, C, N, N, 64, 64, 64, 64, 64, 64, 1.0, 0.0, 256, ctypes.byref(cfg))
+        assert st == -11
+    finally:
+        G.mg_clear_override()
+    assert G.mg_gemm_workspace_bytes(G.MG_F32, C, N, N, 256, 256, 256, 256, 256, 256) == 0
+    assert G.mg_gemm_workspace_bytes(G.MG_F32, 0, N, N, 256, 256, 256, 256, 256, 256) == 0

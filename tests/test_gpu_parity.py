@@ -1,0 +1,299 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bar: bit-exact on integer-valued inputs; max |C - C_ref| / (|alpha| |A||B| + |beta| |C|) <= 1e-5 (FP32)
+and <= 2e-3 (FP16 storage, FP32 accumulation) on random inputs.  Bytes outside the C matrix (leading
+dimension padding, gaps between batched instances) must come back unchanged.
+"""
+import ctypes
+import sys
+
+import numpy as np
+import pytest
+
+from paper_1705_05249_amd import workloads as W
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+R, C, N, T = W.ROW_MAJOR, W.COL_MAJOR, W.NO_TRANS, W.TRANS
+VARIANTS = [(lay, ta, tb) for lay in (R, C) for ta in (N, T) for tb in (N, T)]
+
+
+def announce(*what):
+    print("[case]", *what, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def G():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_1705_05249_amd import gemm
+    gemm.lib()
+    gemm.mg_clear_override()
+    yield gemm
+    gemm.mg_clear_override()
+
+
+# ------------------------------------------------------------------ group 1: 256^3
+
+@pytest.mark.parametrize("integer", [True, False])
+def test_config1(G, oracle, integer):
+    case = W.config1(integer)
+    announce(case.name)
+    H.check_case(case, oracle)
+
+
+# ------------------------------------------------------------------ group 2: squares, 8 storage variants
+
+@pytest.mark.parametrize("layout,ta,tb", VARIANTS)
+@pytest.mark.parametrize("size,beta,integer", [(192, 0.7, False), (200, 0.0, False), (321, 0.7, True), (512, 0.0, True)])
+def test_config2_oracle_sized(G, oracle, layout, ta, tb, size, beta, integer):
+    case = W.config2_like(size, layout, ta, tb, beta, seed_case=size, integer=integer)
+    announce(case.name, layout, ta, tb, beta, "int" if integer else "rand")
+    H.check_case(case, oracle)
+
+
+@pytest.mark.parametrize("size", W.CONFIG2_SIZES)
+def test_config2_full_sizes_sampled(G, oracle, size):
+    """all 8 storage variants x beta in {0, 0.7} of one size must match the same logical result
+    (the oracle is evaluated on complete sampled rows/columns and scattered entries)"""
+    logical = W.config2_logical(size)
+    for beta in W.CONFIG2_BETAS:
+        for layout, ta, tb in VARIANTS:
+            case = W.config2_variant(size, layout, ta, tb, beta, logical)
+            announce(case.name)
+            H.check_case(case, oracle, sampled=True, seed=size)
+
+
+# ------------------------------------------------------------------ group 3: FP16 storage
+
+@pytest.mark.parametrize("index", range(len(W.CONFIG3_SHAPES)))
+@pytest.mark.parametrize("integer", [False, True])
+def test_config3(G, oracle, index, integer):
+    m, n, k = W.CONFIG3_SHAPES[index]
+    if integer and k > 512:
+        # keep |sum| <= 2048 so the FP16 result is exact: shrink k only
+        case = W.hgemm_case(m, n, 512, case=100 + index, integer=True, name=f"c3int_{m}x{n}x512")
+    else:
+        case = W.config3(index, integer)
+    announce(case.name)
+    H.check_case(case, oracle, sampled=(m * n * case.k > 2 ** 31))
+
+
+@pytest.mark.parametrize("layout,ta,tb", VARIANTS)
+@pytest.mark.parametrize("shape,alpha,beta", [((130, 72, 200), 1.0, 0.0), ((64, 257, 96), 0.5, 2.0), ((256, 256, 64), 1.0, 1.0)])
+def test_hgemm_variants(G, oracle, layout, ta, tb, shape, alpha, beta):
+    m, n, k = shape
+    case = W.hgemm_case(m, n, k, case=m + n + k, layout=layout, ta=ta, tb=tb, alpha=alpha, beta=beta)
+    announce(case.name, layout, ta, tb)
+    H.check_case(case, oracle)
+
+
+def test_hgemm_subnormal_inputs_are_not_flushed(G, oracle):
+    m = n = 64
+    k = 32
+    A = np.full((m, k), 2.0 ** -24, dtype=np.float16)
+    B = np.full((k, n), 1024.0, dtype=np.float16)
+    case = W.make_case("subnormal", "f16", C, N, N, A, B, np.zeros((m, n), np.float16), 1.0, 0.0)
+    _, out = H.run_gpu(case)
+    assert np.all(out.astype(np.float64) == k * 2.0 ** -14)
+
+
+# ------------------------------------------------------------------ group 4: batched
+
+@pytest.mark.parametrize("size", W.CONFIG4_SIZES)
+@pytest.mark.parametrize("batch", W.CONFIG4_BATCHES)
+def test_config4(G, oracle, size, batch):
+    bc = W.config4_fast(size, batch) if batch > 1000 else W.config4(size, batch)
+    announce(bc.name)
+    H.check_batched(bc, oracle)
+
+
+@pytest.mark.parametrize("layout,ta,tb", VARIANTS)
+def test_batched_variants_ragged_exact(G, oracle, layout, ta, tb):
+    for (m, n, k, batch, pad) in ((5, 7, 6, 9, 0), (16, 16, 16, 33, 0), (33, 17, 70, 5, 3), (64, 64, 64, 3, 1),
+                                  (70, 130, 9, 2, 0), (1, 1, 1, 4, 0)):
+        bc = W.batched_case(m, n, k, batch, case=m * n + k, layout=layout, ta=ta, tb=tb, integer=True,
+                            shuffle_offsets=True,
+                            lda=W.tight_ld(layout, ta, m, k) + pad, ldb=W.tight_ld(layout, tb, k, n) + 2 * pad,
+                            ldc=W.tight_ld(layout, N, m, n) + pad)
+        announce(bc.name, layout, ta, tb)
+        H.check_batched(bc, oracle, exact=True)
+
+
+def test_batched_equals_loop_of_singles(G, oracle):
+    """the batched routine and a loop of non-batched calls agree (both within tolerance of the oracle,
+    and with each other to a few ulps of the denominator)"""
+    import torch
+    bc = W.batched_case(16, 16, 16, 20, case=5)
+    _, out = H.run_batched_gpu(bc)
+    mats, _ = H.batched_outputs(bc, out)
+    A, B, Cd = H.to_gpu(bc.A), H.to_gpu(bc.B), H.to_gpu(bc.C)
+    for i in range(bc.batch):
+        G.mg_sgemm(bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, float(bc.alphas[i]), A[int(bc.a_off[i]):], bc.lda,
+                   B[int(bc.b_off[i]):], bc.ldb, float(bc.betas[i]), Cd[int(bc.c_off[i]):], bc.ldc)
+    torch.cuda.synchronize()
+    singles, _ = H.batched_outputs(bc, Cd.cpu().numpy())
+    _, d_ref = oracle.sgemm_batched(bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, bc.alphas, bc.A, bc.a_off, bc.lda,
+                                    bc.B, bc.b_off, bc.ldb, bc.betas, bc.C, bc.c_off, bc.ldc)
+    assert np.max(np.abs(mats.astype(np.float64) - singles.astype(np.float64)) / d_ref) <= 2e-6
+
+
+def test_batched_alpha_zero_and_beta_zero_per_instance(G, oracle):
+    bc = W.batched_case(16, 16, 16, 6, case=9)
+    bc.alphas[1] = 0.0
+    bc.betas[2] = 0.0
+    la = 256
+    bc.A[bc.a_off[1]: bc.a_off[1] + la] = np.nan         # must not be used: alpha == 0
+    bc.C[bc.c_off[2]: bc.c_off[2] + la] = np.nan         # must not be read: beta == 0
+    st, out = H.run_batched_gpu(bc)
+    mats, _ = H.batched_outputs(bc, out)
+    c_ref, d_ref = oracle.sgemm_batched(bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, bc.alphas, bc.A, bc.a_off,
+                                        bc.lda, bc.B, bc.b_off, bc.ldb, bc.betas, bc.C, bc.c_off, bc.ldc)
+    assert H.rel_error(mats, c_ref, d_ref) <= H.TOL["f32"]
+
+
+# ------------------------------------------------------------------ group 5: odd and skinny
+
+@pytest.mark.parametrize("index", range(len(W.CONFIG5_SHAPES)))
+@pytest.mark.parametrize("integer", [False, True])
+def test_config5(G, oracle, index, integer):
+    case = W.config5(index, integer)
+    announce(case.name, "int" if integer else "rand")
+    H.check_case(case, oracle, sampled=(case.m * case.n * case.k > 3 * 2 ** 30), seed=index)
+
+
+@pytest.mark.parametrize("layout,ta,tb", VARIANTS)
+@pytest.mark.parametrize("shape", [(1, 1, 1), (1, 300, 257), (300, 1, 257), (129, 130, 131), (279, 32, 100),
+                                   (32, 32, 32), (65, 63, 17), (2, 3, 1000)])
+def test_small_and_skinny_shapes_exact(G, oracle, layout, ta, tb, shape):
+    m, n, k = shape
+    case = W.skinny_case(m, n, k, case=m * 7 + n * 3 + k, integer=True, layout=layout, ta=ta, tb=tb,
+                         alpha=2.0, beta=-1.0)
+    announce(case.name, layout, ta, tb)
+    H.check_case(case, oracle)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_unaligned_base_pointers(G, oracle, dtype):
+    """operands that start 1..3 elements into an allocation (no 16-byte alignment anywhere)"""
+    for (m, n, k), offs in (((256, 256, 128), (1, 2, 3)), ((130, 70, 90), (3, 1, 1)), ((512, 256, 256), (0, 4, 0))):
+        for layout, ta, tb in ((C, N, N), (C, T, N), (R, N, T)):
+            if dtype == "f32":
+                case = W.make_case(
+                    f"unal_{m}x{n}x{k}", "f32", layout, ta, tb,
+                    W.small_ints(W.rng_for(6, m), (m, k)), W.small_ints(W.rng_for(6, n), (k, n)),
+                    W.small_ints(W.rng_for(6, k), (m, n)), 1.0, 1.0, exact=True)
+            else:
+                case = W.hgemm_case(m, n, k, case=m, layout=layout, ta=ta, tb=tb, beta=1.0)
+            announce(case.name, dtype, layout, ta, tb, offs)
+            H.check_case(case, oracle, offset_elems=offs)
+
+
+# ------------------------------------------------------------------ special scalars and empty problems
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_alpha_zero_ignores_nan_in_a_b(G, oracle, dtype):
+    m, n, k = 70, 50, 40
+    t = np.float32 if dtype == "f32" else np.float16
+    Cm = W.small_ints(W.rng_for(7, 1), (m, n), dtype=t)
+    case = W.make_case("alpha0", dtype, C, N, T, np.full((m, k), np.nan, t), np.full((k, n), np.inf, t), Cm,
+                       0.0, 0.5, exact=True)
+    H.check_case(case, oracle)
+    case = W.make_case("alpha0beta0", dtype, R, T, N, np.full((m, k), np.nan, t), np.full((k, n), np.nan, t),
+                       np.full((m, n), np.nan, t), 0.0, 0.0, exact=True)
+    H.check_case(case, oracle)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_beta_zero_ignores_nan_in_c(G, oracle, dtype):
+    for m, n, k in ((70, 50, 40), (256, 256, 256), (1, 200, 300)):
+        t = np.float32 if dtype == "f32" else np.float16
+        g = W.rng_for(7, 2)
+        case = W.make_case("beta0", dtype, C, N, N, W.small_ints(g, (m, k), 2, t), W.small_ints(g, (k, n), 2, t),
+                           np.full((m, n), np.nan, t), 1.0, 0.0, exact=True)
+        announce(case.name, dtype, m, n, k)
+        H.check_case(case, oracle)
+
+
+def test_k_zero_and_empty(G, oracle):
+    Cm = W.small_ints(W.rng_for(7, 3), (33, 20))
+    case = W.make_case("k0", "f32", C, N, N, np.zeros((33, 0), np.float32), np.zeros((0, 20), np.float32), Cm,
+                       3.0, 2.0, exact=True)
+    H.check_case(case, oracle)
+    import torch
+    buf = torch.zeros(64, device="cuda")
+    assert G.mg_sgemm(C, N, N, 0, 5, 5, 1.0, buf, 1, buf, 5, 0.0, buf, 1) == 0
+    assert G.mg_sgemm(C, N, N, 5, 0, 5, 1.0, buf, 5, buf, 5, 0.0, buf, 5) == 0
+    assert torch.all(buf == 0)
+
+
+# ------------------------------------------------------------------ every compiled configuration is result-neutral
+
+def _probe_cases(dtype):
+    """small problems that together make every compiled kernel legal at least once"""
+    cases = []
+    for layout, ta, tb in ((C, N, N), (C, T, N), (C, N, T), (R, N, N)):
+        if dtype == "f32":
+            for (m, n, k) in ((512, 512, 256), (260, 250, 100)):
+                g = W.rng_for(8, m + k)
+                cases.append(W.make_case(f"probe_f32_{m}x{n}x{k}", "f32", layout, ta, tb, W.small_ints(g, (m, k)),
+                                         W.small_ints(g, (k, n)), W.small_ints(g, (m, n)), 1.5, 0.5, exact=True))
+            cases.append(W.skinny_case(1, 512, 768, case=1, integer=True, layout=layout, ta=ta, tb=tb))
+            cases.append(W.skinny_case(512, 1, 768, case=2, integer=True, layout=layout, ta=ta, tb=tb))
+        else:
+            for (m, n, k) in ((512, 512, 256), (260, 250, 100)):
+                cases.append(W.hgemm_case(m, n, k, case=m + k, layout=layout, ta=ta, tb=tb, beta=1.0, integer=True))
+            cases.append(W.hgemm_case(512, 512, 256, case=3, layout=layout, ta=ta, tb=tb, beta=0.5))
+    return cases
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_every_kernel_configuration_gives_parity(G, oracle, dtype):
+    import torch
+    code = G.MG_F32 if dtype == "f32" else G.MG_F16
+    kernels = [t for t in G.kernel_table() if t["dtype"] == code and t["family"] != G.MG_FAMILY_BATCHED
+               and t["family"] != G.MG_FAMILY_SCALE]
+    ran = {t["name"]: 0 for t in kernels}
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    try:
+        for case in _probe_cases(dtype):
+            for t in kernels:
+                for split in (1, 2, 3):
+                    G.mg_override_config(t["kernel_id"], split)
+                    # legality is asked first so that an illegal combination is skipped, not launched
+                    cfg = G.mg_config()
+                    q = G.lib().mg_query_selected(code, case.layout, case.ta, case.tb, case.m, case.n, case.k,
+                                                  case.lda, case.ldb, case.ldc, case.alpha, case.beta, 256,
+                                                  ctypes.byref(cfg))
+                    if q != 0:
+                        continue
+                    announce(t["name"], "split", split, case.name, case.layout, case.ta, case.tb)
+                    H.check_case(case, oracle, workspace=ws)
+                    ran[t["name"]] += 1
+    finally:
+        G.mg_clear_override()
+    never = [name for name, count in ran.items() if count == 0]
+    assert not never, f"kernels never exercised: {never}"
+
+
+def test_every_batched_configuration_gives_parity(G, oracle):
+    kernels = [t for t in G.kernel_table() if t["family"] == G.MG_FAMILY_BATCHED]
+    ran = {t["name"]: 0 for t in kernels}
+    try:
+        for (s, batch) in ((8, 50), (16, 70), (32, 20), (64, 9), (24, 5)):
+            for layout, ta, tb in ((C, N, N), (R, N, N), (C, T, T)):
+                bc = W.batched_case(s, s, s, batch, case=s, layout=layout, ta=ta, tb=tb, integer=True)
+                for t in kernels:
+                    G.mg_override_batched_config(t["kernel_id"])
+                    announce(t["name"], bc.name, layout, ta, tb)
+                    try:
+                        H.check_batched(bc, oracle, exact=True)
+                        ran[t["name"]] += 1
+                    except G.MgError as e:
+                        assert e.status == -11          # this kernel does not take this shape
+    finally:
+        G.mg_clear_override()
+    never = [name for name, count in ran.items() if count == 0]
+    assert not never, f"batched kernels never exercised: {never}"
