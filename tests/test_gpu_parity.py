@@ -47,7 +47,7 @@ def test_config1(G, oracle, integer):
 # ------------------------------------------------------------------ group 2: squares, 8 storage variants
 
 @pytest.mark.parametrize("layout,ta,tb", VARIANTS)
-@pytest.mark.parametrize("size,beta,integer", [(192, 0.7, False), (200, 0.0, False), (321, 0.7, True), (512, 0.0, True)])
+@pytest.mark.parametrize("size,beta,integer", [(192, 0.7, False), (200, 0.0, False), (321, 0.5, True), (512, 0.0, True)])
 def test_config2_oracle_sized(G, oracle, layout, ta, tb, size, beta, integer):
     case = W.config2_like(size, layout, ta, tb, beta, seed_case=size, integer=integer)
     announce(case.name, layout, ta, tb, beta, "int" if integer else "rand")
