@@ -1,0 +1,101 @@
+// Host-side launch, legality and registration helpers of the MFMA macro-tile kernels.
+#pragma once
+
+#include "mfma_kernel.h"
+
+namespace mg {
+
+template <typename T, int BM, int BN, int BK, int WM, int WN, bool AK, bool BKC, bool EDGE> struct MfmaConfig {
+    static constexpr int CH = ElemTraits<T>::CH;
+    static constexpr int NT = WM * WN * 64;
+    static constexpr int LDS = 2 * (BM + BN) * 128;
+    static constexpr int DTYPE = sizeof(T) == 4 ? MG_F32 : MG_F16;
+
+    static int k_per_split(const Problem &p, int split)
+    {
+        const int64_t ktiles = ceil_div(p.k, BK);
+        return static_cast<int>(ceil_div(ktiles, split) * BK);
+    }
+
+    static bool legal(const Problem &p, int split, int64_t alignment)
+    {
+        if (p.dtype != DTYPE || p.a_trans != AK || p.b_trans == BKC) return false;
+        if (p.alpha == 0.f || p.k == 0) return false;
+        if (split < 1 || split > 256 || split > ceil_div(p.k, BK)) return false;
+        if (p.m >= (int64_t(1) << 31) || p.n >= (int64_t(1) << 31) || p.k >= (int64_t(1) << 31)) return false;
+        if (ceil_div(p.m, BM) * ceil_div(p.n, BN) >= (int64_t(1) << 31)) return false;
+        if (split > 1 && static_cast<int64_t>(k_per_split(p, split)) * (split - 1) >= p.k) return false;  // empty slice
+        if (!EDGE) {
+            if (p.m % BM || p.n % BN || p.k % BK) return false;
+            if (p.lda % CH || p.ldb % CH) return false;
+            // A and B need 16-byte alignment; `alignment` is the minimum over A, B and C
+            if (pointer_alignment(p.A) < 16 || pointer_alignment(p.B) < 16) return false;
+            if (p.A == nullptr && alignment < 16) return false;      // query without pointers
+        }
+        return true;
+    }
+
+    static size_t workspace(const Problem &p, int split)
+    {
+        return split > 1 ? static_cast<size_t>(split) * p.m * p.n * sizeof(float) : 0;
+    }
+
+    static hipError_t launch(const Problem &p, int split)
+    {
+        static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; races are harmless
+        auto kernel = mfma_gemm_kernel<T, BM, BN, BK, WM, WN, AK, BKC, EDGE>;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        MfmaArgs a{};
+        a.A = p.A; a.B = p.B; a.C = p.C;
+        a.partial = split > 1 ? static_cast<float *>(p.workspace) : nullptr;
+        a.lda = p.lda; a.ldb = p.ldb; a.ldc = p.ldc;
+        a.m = static_cast<int>(p.m); a.n = static_cast<int>(p.n); a.k = static_cast<int>(p.k);
+        a.alpha = p.alpha; a.beta = p.beta;
+        a.tiles_m = static_cast<int>(ceil_div(p.m, BM));
+        a.tiles_n = static_cast<int>(ceil_div(p.n, BN));
+        a.k_per_split = k_per_split(p, split);
+        a.group_m = 8;
+        hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(a.tiles_m) * a.tiles_n, 1, split), dim3(NT), LDS,
+                           p.stream, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess || split == 1) return e;
+        const int64_t total = p.m * p.n;
+        const unsigned blocks = static_cast<unsigned>(total / 256 + 1 < 4096 ? total / 256 + 1 : 4096);
+        hipLaunchKernelGGL(splitk_reduce_kernel<T>, dim3(blocks), dim3(256), 0, p.stream, a.partial, split, a.m, a.n,
+                           static_cast<T *>(p.C), p.ldc, p.alpha, p.beta);
+        return hipGetLastError();
+    }
+
+    static KernelEntry entry(const char *name)
+    {
+        mg_config c{};
+        c.family = MG_FAMILY_MFMA;
+        c.dtype = DTYPE;
+        c.tile_m = BM; c.tile_n = BN; c.tile_k = BK;
+        c.waves_m = WM; c.waves_n = WN;
+        c.split_k = 1;
+        c.threads = NT;
+        c.lds_bytes = LDS;
+        return KernelEntry{name, c, legal, workspace, launch, nullptr, nullptr};
+    }
+};
+
+// The four operand-contiguity cases of one tile shape, in the fast (aligned, whole tiles) and the
+// edge (anything) flavour.  Names: <t>mfma_<BM>x<BN>x<BK>_w<WM>x<WN>_<a><b>[_edge], a/b = k or m/n:
+// which direction the operand is contiguous in.
+#define MG_MFMA_REGISTER(table, T, tag, BM, BN, BK, WM, WN)                                                        \
+    table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, false, true, false>::entry(tag "_mk"));                      \
+    table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, true, true, false>::entry(tag "_kk"));                       \
+    table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, false, false, false>::entry(tag "_mn"));                     \
+    table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, true, false, false>::entry(tag "_kn"));                      \
+    table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, false, true, true>::entry(tag "_mk_edge"));                  \
+    table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, true, true, true>::entry(tag "_kk_edge"));                   \
+    table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, false, false, true>::entry(tag "_mn_edge"));                 \
+    table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, true, false, true>::entry(tag "_kn_edge"));
+
+}  // namespace mg

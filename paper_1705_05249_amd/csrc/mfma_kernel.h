@@ -1,0 +1,435 @@
+// LDS-staged MFMA macro-tile GEMM kernel for gfx950, FP32 and FP16 storage (FP32 accumulate).
+//
+// The work-group tile / register tile / K-unroll structure follows the parameterised gemm
+// kernel the paper sketches in Section 3.2 (work-group tile M_wg x N_wg, per-thread register
+// tile, K loop staged through local memory); what is specific to CDNA4:
+//   * the register tile is a grid of 32x32 MFMA accumulators per 64-lane wavefront
+//     (v_mfma_f32_32x32x16_f16 / v_mfma_f32_32x32x2_f32);
+//   * both operands sit in LDS as [row][k] with k contiguous (row = m index for A, n index for
+//     B), 128 bytes per row, the eight 16-byte chunks of a row XOR-swizzled with the row
+//     number (chunk ^ ((row ^ row/8) % 8)): every MFMA operand is one 16-byte LDS read per
+//     lane, and the fragment reads (32 consecutive rows, one chunk), the row-wise stores
+//     (8 chunks of one row) and the stores after a register transpose (rows CH apart, one
+//     chunk) all spread over all banks;
+//   * an operand whose memory is contiguous along m (or n) is transposed in registers
+//     (CH x CH blocks, CH = elements per 16 bytes) between the 16-byte global loads (consecutive
+//     lanes read consecutive addresses) and the 16-byte LDS stores -- this replaces the paper's pre-transposition pass, which
+//     would cost a sizeable fraction of an FP16 GEMM's run time at this machine's flop/byte;
+//   * software pipeline over K-tiles t and K-steps s (one K-step = one 16-byte fragment per
+//     lane and operand): while the MFMAs of step s run, the LDS reads of step s+1 are issued;
+//     the global loads of tile t+2 are issued during the last step of tile t and stay in
+//     registers until the second-to-last step of tile t+1, where they go to the other LDS
+//     buffer; the single barrier per tile sits between the last two steps, so the first
+//     fragments of the next tile are read behind it while MFMAs still run;
+//   * the issue order is written out slot by slot (one MFMA group plus its share of the
+//     memory instructions) and pinned with scheduling barriers;
+//   * the MFMA's lane index is mapped to the m direction, so a store instruction writes 32
+//     consecutive elements of a C column.
+//
+// Within one K-step the lanes of an operand fragment cover 2*CH values of k: lane group g
+// (= lane / 32) holds the CH values of chunk 2*step + g.  Both operands use the same mapping,
+// and a sum over k does not care about the order, so no further shuffling is needed.
+#pragma once
+
+#include <utility>
+
+#include "internal.h"
+
+namespace mg {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct MfmaArgs {
+    const void *A;
+    const void *B;
+    void *C;
+    float *partial;        // split-K partial sums [split][n][m] (FP32), or nullptr
+    int64_t lda, ldb, ldc;
+    int m, n, k;
+    float alpha, beta;
+    int tiles_m, tiles_n;
+    int k_per_split;       // multiple of the K tile
+    int group_m;           // tile rasterisation: tiles are walked in column groups of this many rows
+};
+
+template <typename T> struct ElemTraits;
+template <> struct ElemTraits<_Float16> { static constexpr int CH = 8; };
+template <> struct ElemTraits<float> { static constexpr int CH = 4; };
+
+// compile-time loop: f(std::integral_constant<int, 0>{}) ... f(<N-1>)
+template <typename F, int... I> __device__ inline void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F> __device__ inline void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// ---- row i of a transposed CH x CH block -------------------------------------------------------
+// in[j] = CH consecutive row elements (m or n direction) for k = j; result = CH consecutive k for row i.
+template <int I> __device__ inline u32x4 transposed_row(const u32x4 *in, _Float16)
+{
+    constexpr uint32_t sel = (I & 1) ? 0x07060302u : 0x05040100u;
+    u32x4 out;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) out[d] = __builtin_amdgcn_perm(in[2 * d + 1][I >> 1], in[2 * d][I >> 1], sel);
+    return out;
+}
+template <int I> __device__ inline u32x4 transposed_row(const u32x4 *in, float)
+{
+    u32x4 out;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) out[d] = in[d][I];
+    return out;
+}
+
+template <typename T> __device__ inline uint32_t elem_bits(T v);
+template <> __device__ inline uint32_t elem_bits<float>(float v) { return __builtin_bit_cast(uint32_t, v); }
+template <> __device__ inline uint32_t elem_bits<_Float16>(_Float16 v) { return __builtin_bit_cast(uint16_t, v); }
+
+// CH consecutive elements starting at p, element e valid iff e < valid; missing ones are zero.
+template <typename T> __device__ inline u32x4 gather_chunk(const T *p, int valid)
+{
+    constexpr int CH = ElemTraits<T>::CH;
+    u32x4 r = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int e = 0; e < CH; ++e) {
+        uint32_t b = 0;
+        if (e < valid) b = elem_bits<T>(p[e]);
+        if (sizeof(T) == 4) r[e] = b; else r[e >> 1] |= b << (16 * (e & 1));
+    }
+    return r;
+}
+
+// ---- one operand tile: global -> registers -> LDS ---------------------------------------------
+// The tile has ROWS rows (m or n index) and BK values of k.  Global element (row r, k index l) is at
+// X[l + r*ld] when KCONTIG, else at X[r + l*ld].  Each thread moves COUNT 16-byte pieces; piece Q can
+// be loaded and stored on its own so that the kernel can place every instruction in its pipeline.
+template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct TileLoader {
+    static constexpr int CH = ElemTraits<T>::CH;
+    static constexpr int CPR = BK / CH;                                // 16-byte chunks per LDS row
+    static constexpr int RS = 128;                                      // LDS row stride in bytes
+    static constexpr int RCH = ROWS / CH;                               // row chunks per tile column
+    static constexpr int CHUNKS = ROWS * CPR;
+    static constexpr int BLOCKS = CHUNKS / CH;                         // CH x CH blocks (transposing path)
+    static constexpr int COUNT = KCONTIG ? (CHUNKS + NT - 1) / NT : ((BLOCKS + NT - 1) / NT) * CH;
+    static constexpr bool PARTIAL = KCONTIG ? (CHUNKS % NT != 0) : (BLOCKS % NT != 0);
+    static constexpr int LDS_BYTES = ROWS * RS;
+    static_assert(CPR == 8 && ROWS % 8 == 0, "LDS rows are 128 bytes (eight swizzled 16-byte chunks)");
+
+    // byte offset of logical chunk c of row r inside the operand's LDS tile
+    __device__ static inline int lds_offset(int r, int c) { return r * RS + ((c ^ ((r ^ (r >> 3)) & 7)) << 4); }
+
+    u32x4 regs[COUNT];
+
+    // Tile position for the loads that follow.  rows_left / k_left: rows / k values from (r0, l0) on that
+    // are inside the matrix (used by EDGE only); vec_ok: 16-byte loads are allowed.
+    const T *base;
+    int64_t ld;
+    int rows_left, k_left;
+    bool vec_ok;
+
+    __device__ inline void aim(const T *X, int64_t ld_, int64_t r0, int64_t l0, int rows_left_, int k_left_,
+                               bool vec_ok_)
+    {
+        base = KCONTIG ? X + r0 * ld_ + l0 : X + r0 + l0 * ld_;
+        ld = ld_;
+        rows_left = rows_left_;
+        k_left = k_left_;
+        vec_ok = vec_ok_;
+    }
+
+    template <int Q> __device__ inline void load_one()
+    {
+        const int t = threadIdx.x;
+        if constexpr (KCONTIG) {
+            const int idx = t + Q * NT;
+            const int c = idx % CPR, r = idx / CPR;
+            if (PARTIAL && idx >= CHUNKS) return;
+            const T *p = base + r * ld + c * CH;
+            if constexpr (!EDGE) {
+                regs[Q] = *reinterpret_cast<const u32x4 *>(p);
+            } else {
+                const int kv = k_left - c * CH;
+                if (r >= rows_left || kv <= 0) regs[Q] = u32x4{0u, 0u, 0u, 0u};
+                else if (vec_ok && kv >= CH) regs[Q] = *reinterpret_cast<const u32x4 *>(p);
+                else regs[Q] = gather_chunk<T>(p, kv);
+            }
+        } else {
+            constexpr int b = Q / CH, j = Q % CH;
+            const int idx = t + b * NT;
+            const int mc = idx % RCH, kc = idx / RCH;
+            if (PARTIAL && idx >= BLOCKS) return;
+            const T *p = base + mc * CH + (kc * CH + j) * ld;
+            if constexpr (!EDGE) {
+                regs[Q] = *reinterpret_cast<const u32x4 *>(p);
+            } else {
+                const int rv = rows_left - mc * CH;
+                if (kc * CH + j >= k_left || rv <= 0) regs[Q] = u32x4{0u, 0u, 0u, 0u};
+                else if (vec_ok && rv >= CH) regs[Q] = *reinterpret_cast<const u32x4 *>(p);
+                else regs[Q] = gather_chunk<T>(p, rv);
+            }
+        }
+    }
+
+    // Piece Q -> LDS.  On the transposing path piece Q = b*CH + i is row i of block b after the turn.
+    template <int Q> __device__ inline void store_one(char *lds) const
+    {
+        const int t = threadIdx.x;
+        if constexpr (KCONTIG) {
+            const int idx = t + Q * NT;
+            const int c = idx % CPR, r = idx / CPR;
+            if (PARTIAL && idx >= CHUNKS) return;
+            *reinterpret_cast<u32x4 *>(lds + lds_offset(r, c)) = regs[Q];
+        } else {
+            constexpr int b = Q / CH, i = Q % CH;
+            const int idx = t + b * NT;
+            const int mc = idx % RCH, kc = idx / RCH;
+            if (PARTIAL && idx >= BLOCKS) return;
+            *reinterpret_cast<u32x4 *>(lds + lds_offset(mc * CH + i, kc)) = transposed_row<i>(&regs[b * CH], T{});
+        }
+    }
+
+    __device__ inline void load_all() { static_for<COUNT>([&](auto q) { load_one<decltype(q)::value>(); }); }
+    __device__ inline void store_all(char *lds) const
+    {
+        static_for<COUNT>([&](auto q) { store_one<decltype(q)::value>(lds); });
+    }
+};
+
+// ---- MFMA on one pair of 16-byte fragments ---------------------------------------------------------
+// frag_n: rows of the B tile (n index) -> MFMA source A (output register index);
+// frag_m: rows of the A tile (m index) -> MFMA source B (output lane index).
+__device__ inline void mma(floatx16 &acc, const u32x4 &frag_n, const u32x4 &frag_m, _Float16)
+{
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, frag_n),
+                                                 __builtin_bit_cast(halfx8, frag_m), acc, 0, 0, 0);
+}
+__device__ inline void mma(floatx16 &acc, const u32x4 &frag_n, const u32x4 &frag_m, float)
+{
+    // (whole-vector casts and named components: indexing the uint vector inside a bit cast picked
+    // component 0 four times with this compiler)
+    const floatx4 a = __builtin_bit_cast(floatx4, frag_n), b = __builtin_bit_cast(floatx4, frag_m);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
+}
+
+template <typename T> __device__ inline float load_as_float(const T *p) { return static_cast<float>(*p); }
+template <typename T> __device__ inline void store_from_float(T *p, float v) { *p = static_cast<T>(v); }
+
+// Work-group id -> tile coordinates.  Work-groups are dealt round-robin to the 8 XCDs (each with its
+// own L2), so ids that share an XCD are first made consecutive, then walked in column groups of
+// group_m tile rows so that concurrently running tiles share A and B panels.
+__device__ inline void tile_coords(int wg, int tiles_m, int tiles_n, int group_m, int &tm, int &tn)
+{
+    const int total = tiles_m * tiles_n;
+    const int xcd = wg % 8, local = wg / 8;
+    const int q = total / 8, rem = total % 8;
+    const int id = xcd * q + (xcd < rem ? xcd : rem) + local;
+    const int per_group = group_m * tiles_n;
+    const int group = id / per_group;
+    const int first = group * group_m;
+    const int size = (tiles_m - first) < group_m ? (tiles_m - first) : group_m;
+    const int in_group = id % per_group;
+    tm = first + in_group % size;
+    tn = in_group / size;
+}
+
+// first of `total` items that falls into slot `slot` of `slots` when spread evenly
+constexpr int share_begin(int slot, int total, int slots) { return slot * total / slots; }
+
+template <typename T, int BM, int BN, int BK, int WM, int WN, bool A_KCONTIG, bool B_KCONTIG, bool EDGE>
+__global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs args)
+{
+    constexpr int NT = WM * WN * 64;
+    constexpr int WTM = BM / WM, WTN = BN / WN;        // wavefront tile
+    constexpr int FM = WTM / 32, FN = WTN / 32;        // 32x32 accumulators per wavefront
+    constexpr int CH = ElemTraits<T>::CH;
+    constexpr int KSTEPS = BK / (2 * CH);
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % (4 * CH) == 0 && KSTEPS >= 2, "tile shape");
+    using LoadA = TileLoader<T, BM, BK, NT, A_KCONTIG, EDGE>;
+    using LoadB = TileLoader<T, BN, BK, NT, B_KCONTIG, EDGE>;
+    constexpr int STAGE = LoadA::LDS_BYTES + LoadB::LDS_BYTES;
+    constexpr int SLOTS = FM * FN;                      // MFMA groups per K-step
+    constexpr int FRAGS = FM + FN;
+    constexpr int PIECES = LoadA::COUNT + LoadB::COUNT;
+
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+
+    int tm, tn;
+    tile_coords(blockIdx.x, args.tiles_m, args.tiles_n, args.group_m, tm, tn);
+    const int64_t m0 = static_cast<int64_t>(tm) * BM, n0 = static_cast<int64_t>(tn) * BN;
+    const int kb = blockIdx.z * args.k_per_split;
+    const int ke = (kb + args.k_per_split < args.k) ? kb + args.k_per_split : args.k;
+
+    const T *__restrict__ A = static_cast<const T *>(args.A);
+    const T *__restrict__ B = static_cast<const T *>(args.B);
+    const int rows_a = static_cast<int>(args.m - m0 < BM ? args.m - m0 : BM);
+    const int rows_b = static_cast<int>(args.n - n0 < BN ? args.n - n0 : BN);
+    bool vec_a = true, vec_b = true;
+    if constexpr (EDGE) {
+        vec_a = (args.lda % CH == 0) && (reinterpret_cast<uintptr_t>(A) % 16 == 0);
+        vec_b = (args.ldb % CH == 0) && (reinterpret_cast<uintptr_t>(B) % 16 == 0);
+    }
+
+    const int lane = threadIdx.x % 64;
+    const int wave = threadIdx.x / 64;
+    const int wm = wave % WM, wn = wave / WM;
+    // Fragment f of K-step s: row = wave row + 32 f + lane % 32, logical chunk 2 s + lane / 32.  With the
+    // swizzle, the chunk's byte offset inside the row is (x ^ K): x is per lane, and K = 32 s ^ 64 (f & 1)
+    // takes four values only, so four addresses per operand cover every fragment (the rest is an
+    // immediate offset of f * 32 rows).
+    const int lr = lane % 32;
+    const int xa = ((lane / 32) ^ (lr & 7) ^ (lr >> 3) ^ (4 * ((wm * FM) & 1))) << 4;
+    const int xb = ((lane / 32) ^ (lr & 7) ^ (lr >> 3) ^ (4 * ((wn * FN) & 1))) << 4;
+    int frag_a[4], frag_b[4];
+#pragma unroll
+    for (int kx = 0; kx < 4; ++kx) {
+        frag_a[kx] = (wm * WTM + lr) * 128 + (xa ^ (32 * kx));
+        frag_b[kx] = LoadA::LDS_BYTES + (wn * WTN + lr) * 128 + (xb ^ (32 * kx));
+    }
+
+    floatx16 acc[FN][FM];
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
+
+    LoadA la;
+    LoadB lb;
+    const int ktiles = (ke - kb + BK - 1) / BK;
+    // K offset of tile t; the fast path clamps to the last tile (a harmless reload), the edge path lets
+    // the loaders' guards turn out-of-range tiles into zeros without touching memory
+    auto aim_tile = [&](int t) {
+        int l0 = kb + t * BK;
+        if constexpr (!EDGE) l0 = l0 < ke ? l0 : ke - BK;
+        la.aim(A, args.lda, m0, l0, rows_a, ke - l0, vec_a);
+        lb.aim(B, args.ldb, n0, l0, rows_b, ke - l0, vec_b);
+    };
+
+    u32x4 fa[2][FM], fb[2][FN];
+    // fragment F of K-step s: F < FM -> A fragment F, else B fragment F - FM
+    auto read_frag = [&](auto F, const char *stage, int s, int buf) {
+        constexpr int f = decltype(F)::value;
+        if constexpr (f < FM)
+            fa[buf][f] = *reinterpret_cast<const u32x4 *>(stage + frag_a[(s ^ (2 * (f & 1))) & 3] + f * 32 * 128);
+        else
+            fb[buf][f - FM] = *reinterpret_cast<const u32x4 *>(stage + frag_b[(s ^ (2 * ((f - FM) & 1))) & 3] +
+                                                               (f - FM) * 32 * 128);
+    };
+    auto load_piece = [&](auto P) {
+        constexpr int p = decltype(P)::value;
+        if constexpr (p < LoadA::COUNT) la.template load_one<p>(); else lb.template load_one<p - LoadA::COUNT>();
+    };
+    auto store_piece = [&](auto P, char *stage) {
+        constexpr int p = decltype(P)::value;
+        if constexpr (p < LoadA::COUNT) la.template store_one<p>(stage);
+        else lb.template store_one<p - LoadA::COUNT>(stage + LoadA::LDS_BYTES);
+    };
+
+    if (ktiles > 0) {
+        // prologue: tile 0 -> LDS buffer 0, tile 1 -> registers, first fragments -> registers
+        aim_tile(0);
+        la.load_all();
+        lb.load_all();
+        la.store_all(lds);
+        lb.store_all(lds + LoadA::LDS_BYTES);
+        aim_tile(1);
+        la.load_all();
+        lb.load_all();
+        __syncthreads();
+        static_for<FRAGS>([&](auto F) { read_frag(F, lds, 0, 0); });
+    }
+
+    for (int t = 0; t < ktiles; ++t) {
+        const char *cur = lds + (t & 1) * STAGE;
+        char *nxt = lds + ((t + 1) & 1) * STAGE;
+        aim_tile(t + 2);
+        static_for<KSTEPS>([&](auto S) {
+            constexpr int s = decltype(S)::value;
+            if constexpr (s == KSTEPS - 1) __syncthreads();      // tile t+1 is complete in `nxt`
+            static_for<SLOTS>([&](auto Q) {
+                constexpr int q = decltype(Q)::value;
+                mma(acc[q / FM][q % FM], fb[s & 1][q / FM], fa[s & 1][q % FM], T{});
+                // this slot's share of the LDS reads for the next K-step (of this tile, or step 0 of the next)
+                static_for<share_begin(q + 1, FRAGS, SLOTS) - share_begin(q, FRAGS, SLOTS)>([&](auto R) {
+                    constexpr int f = share_begin(q, FRAGS, SLOTS) + decltype(R)::value;
+                    if constexpr (s + 1 < KSTEPS) read_frag(std::integral_constant<int, f>{}, cur, s + 1, (s + 1) & 1);
+                    else read_frag(std::integral_constant<int, f>{}, nxt, 0, 0);
+                });
+                // second-to-last step: registers (tile t+1) -> other LDS buffer
+                if constexpr (s == KSTEPS - 2)
+                    static_for<share_begin(q + 1, PIECES, SLOTS) - share_begin(q, PIECES, SLOTS)>([&](auto R) {
+                        store_piece(std::integral_constant<int, share_begin(q, PIECES, SLOTS) + decltype(R)::value>{}, nxt);
+                    });
+                // last step: global loads of tile t+2 -> registers
+                if constexpr (s == KSTEPS - 1)
+                    static_for<share_begin(q + 1, PIECES, SLOTS) - share_begin(q, PIECES, SLOTS)>([&](auto R) {
+                        load_piece(std::integral_constant<int, share_begin(q, PIECES, SLOTS) + decltype(R)::value>{});
+                    });
+                if constexpr (!EDGE) __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+    }
+
+    // ---- epilogue: accumulator register r of lane l is C(m, n) with
+    //      m = lane % 32,  n = 8*(r/4) + 4*(lane/32) + r%4   inside its 32x32 block.
+    // One per-lane base pointer; everything added to it is wave-uniform, and the three output modes
+    // (split-K partials / beta == 0 / beta != 0) are separate loops so that no store sits behind a branch.
+    const int lm = lane % 32, ln = 4 * (lane / 32);
+    const int wm_u = __builtin_amdgcn_readfirstlane(wm), wn_u = __builtin_amdgcn_readfirstlane(wn);
+    const int64_t gm0 = m0 + wm_u * WTM, gn0 = n0 + wn_u * WTN;     // wave-uniform corner of the wavefront tile
+    auto write_out = [&](auto *base, int64_t ld, auto &&emit) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int dn = j * 32 + 8 * (r / 4) + (r % 4), dm = i * 32;
+                    if constexpr (EDGE) {
+                        if (gm0 + dm + lm >= args.m || gn0 + dn + ln >= args.n) continue;
+                    }
+                    emit(base + (dm + dn * ld), acc[j][i][r]);
+                }
+    };
+    if (args.partial != nullptr) {
+        float *base = args.partial + (static_cast<int64_t>(blockIdx.z) * args.n + gn0 + ln) * args.m + gm0 + lm;
+        write_out(base, static_cast<int64_t>(args.m), [](float *p, float v) { *p = v; });
+    } else {
+        T *base = static_cast<T *>(args.C) + (gn0 + ln) * args.ldc + gm0 + lm;
+        const float alpha = args.alpha, beta = args.beta;
+        if (beta == 0.f)
+            write_out(base, args.ldc, [alpha](T *p, float v) { store_from_float(p, alpha * v); });
+        else
+            write_out(base, args.ldc,
+                      [alpha, beta](T *p, float v) { store_from_float(p, fmaf(beta, load_as_float(p), alpha * v)); });
+    }
+}
+
+// C <- alpha * sum_z partial[z] + beta * C   (finishes a split-K product)
+template <typename T>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partial, int split, int m, int n,
+                                                             T *__restrict__ C, int64_t ldc, float alpha, float beta)
+{
+    const int64_t total = static_cast<int64_t>(m) * n;
+    for (int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; e < total;
+         e += static_cast<int64_t>(gridDim.x) * 256) {
+        float s = 0.f;
+        for (int z = 0; z < split; ++z) s += partial[z * total + e];
+        T *p = C + (e % m) + (e / m) * ldc;
+        float o = alpha * s;
+        if (beta != 0.f) o = fmaf(beta, load_as_float(p), o);
+        store_from_float(p, o);
+    }
+}
+
+}  // namespace mg

@@ -234,7 +234,7 @@ def test_k_zero_and_empty(G, oracle):
 def _probe_cases(dtype):
     """small problems that together make every compiled kernel legal at least once"""
     cases = []
-    for layout, ta, tb in ((C, N, N), (C, T, N), (C, N, T), (R, N, N)):
+    for layout, ta, tb in ((C, N, N), (C, T, N), (C, N, T), (C, T, T), (R, N, N)):
         if dtype == "f32":
             for (m, n, k) in ((512, 512, 256), (260, 250, 100)):
                 g = W.rng_for(8, m + k)
