@@ -1,5 +1,186 @@
+// Batched small GEMM (paper Section 4.6): one 64-lane wavefront per instance, no LDS.
+//
+// The whole instance lives in registers in the operand layout of v_mfma_f32_16x16x4_f32: for a
+// 16-row block of an operand and a 16-wide block of k, lane (r = lane % 16, g = lane / 16) holds
+// the four values X[r][4g + s], s = 0..3, and MFMA number s of that k block multiplies the
+// values with the same s.  (The sum over k does not care which k meets which MFMA step, as long
+// as A and B agree.)  With that choice
+//   * an operand that is contiguous along k is ONE 16-byte load per lane and block -- for a
+//     16 x 16 column-major B the wavefront reads its 1 KB in one instruction;
+//   * an operand that is contiguous along m (or n) is four 4-byte loads per lane, each of them
+//     four 64-byte runs across the wavefront;
+//   * the accumulator of a 16 x 16 block of C puts four consecutive rows of one column into one
+//     lane, so C is read and written 16 bytes per lane.
+// Per-instance offsets and scalars are wave-uniform and come in through scalar loads; this is
+// the overhead the paper points out when it compares the generic with the strided interface.
+// Instances only need 4-byte alignment (16-byte accesses are issued as align-4 vector loads).
+// Shapes up to 64 x 64 x 64 are covered by three register-block sizes; anything larger goes to
+// the direct batched kernel.
 #include "internal.h"
 
 namespace mg {
-void register_batched(std::vector<KernelEntry> &) {}
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+struct __attribute__((packed, aligned(4))) Float4U {   // 16 bytes at 4-byte alignment
+    float x, y, z, w;
+};
+
+struct BatchedArgs {
+    const float *A, *B;
+    float *C;
+    const int64_t *a_off, *b_off, *c_off;
+    const float *alphas, *betas;
+    int64_t lda, ldb, ldc;
+    int m, n, k;
+    int64_t batch;
+};
+
+// four values X[row][k0 .. k0+3] of an operand block; KC: contiguous along k (X[k + row*ld]) or
+// along the row index (X[row + k*ld]).  FULL: no bounds checks needed.
+template <bool KC, bool FULL>
+__device__ inline floatx4 load4(const float *__restrict__ X, int64_t ld, int row, int k0, int rows, int ks)
+{
+    floatx4 v = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (KC) {
+        const float *p = X + k0 + row * ld;
+        if (FULL || (row < rows && k0 + 3 < ks)) {
+            const Float4U u = *reinterpret_cast<const Float4U *>(p);
+            v = floatx4{u.x, u.y, u.z, u.w};
+        } else if (row < rows) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                if (k0 + s < ks) v[s] = p[s];
+        }
+    } else {
+        const float *p = X + row + k0 * ld;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+            if (FULL || (row < rows && k0 + s < ks)) v[s] = p[s * ld];
+    }
+    return v;
+}
+
+template <int MB, int NB, int KB, bool A_KC, bool B_KC, bool FULL>
+__global__ __launch_bounds__(256) void batched_wave_kernel(const BatchedArgs a)
+{
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+    const int64_t inst = static_cast<int64_t>(blockIdx.x) * 4 + wave;
+    if (inst >= a.batch) return;
+    const float alpha = a.alphas[inst], beta = a.betas[inst];
+    const float *__restrict__ A = a.A + a.a_off[inst];
+    const float *__restrict__ B = a.B + a.b_off[inst];
+    float *__restrict__ C = a.C + a.c_off[inst];
+    const int lane = threadIdx.x % 64, r16 = lane % 16, g = lane / 16;
+
+    floatx4 acc[NB][MB];
+#pragma unroll
+    for (int bj = 0; bj < NB; ++bj)
+#pragma unroll
+        for (int bi = 0; bi < MB; ++bi) acc[bj][bi] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // C_old first (longest latency chain ends in the store), then the operands
+    floatx4 cold[NB][MB];
+    if (beta != 0.f) {
+#pragma unroll
+        for (int bj = 0; bj < NB; ++bj)
+#pragma unroll
+            for (int bi = 0; bi < MB; ++bi) cold[bj][bi] = load4<true, FULL>(C, a.ldc, bj * 16 + r16, bi * 16 + 4 * g, a.n, a.m);
+    }
+
+    if (alpha != 0.f) {     // alpha == 0: A and B are not read at all
+        floatx4 av[MB][KB], bv[NB][KB];
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+#pragma unroll
+            for (int bi = 0; bi < MB; ++bi) av[bi][kb] = load4<A_KC, FULL>(A, a.lda, bi * 16 + r16, kb * 16 + 4 * g, a.m, a.k);
+#pragma unroll
+            for (int bj = 0; bj < NB; ++bj) bv[bj][kb] = load4<B_KC, FULL>(B, a.ldb, bj * 16 + r16, kb * 16 + 4 * g, a.n, a.k);
+        }
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int bj = 0; bj < NB; ++bj)
+#pragma unroll
+                for (int bi = 0; bi < MB; ++bi) {
+                    floatx4 c = acc[bj][bi];
+                    const floatx4 x = av[bi][kb], y = bv[bj][kb];
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.x, y.x, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.y, y.y, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.z, y.z, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.w, y.w, c, 0, 0, 0);
+                    acc[bj][bi] = c;
+                }
+    }
+
+    // lane (r16, g) holds C(i = 16 bi + 4g + r, j = 16 bj + r16), r = 0..3: four consecutive rows of one column
+#pragma unroll
+    for (int bj = 0; bj < NB; ++bj)
+#pragma unroll
+        for (int bi = 0; bi < MB; ++bi) {
+            const int j = bj * 16 + r16, i0 = bi * 16 + 4 * g;
+            floatx4 o = alpha * acc[bj][bi];
+            if (beta != 0.f) o += beta * cold[bj][bi];
+            float *p = C + i0 + j * a.ldc;
+            if (FULL || (j < a.n && i0 + 3 < a.m)) {
+                *reinterpret_cast<Float4U *>(p) = Float4U{o.x, o.y, o.z, o.w};
+            } else if (j < a.n) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (i0 + r < a.m) p[r] = o[r];
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------------- host side
+
+template <int MB, int NB, int KB, bool A_KC, bool B_KC, bool FULL> struct WaveConfig {
+    static bool legal(const BatchedProblem &p)
+    {
+        if (p.a_trans != A_KC || p.b_trans == B_KC) return false;
+        if (p.m > 16 * MB || p.n > 16 * NB || p.k > 16 * KB) return false;
+        if (FULL && (p.m != 16 * MB || p.n != 16 * NB || p.k != 16 * KB)) return false;
+        if (p.batch >= (int64_t(1) << 32)) return false;
+        // offsets inside one instance are 32-bit in the kernel
+        const int64_t lim = int64_t(1) << 24;
+        return p.lda < lim && p.ldb < lim && p.ldc < lim;
+    }
+    static hipError_t launch(const BatchedProblem &p)
+    {
+        BatchedArgs a{p.A, p.B, p.C, p.a_off, p.b_off, p.c_off, p.alphas, p.betas, p.lda, p.ldb, p.ldc,
+                      static_cast<int>(p.m), static_cast<int>(p.n), static_cast<int>(p.k), p.batch};
+        hipLaunchKernelGGL((batched_wave_kernel<MB, NB, KB, A_KC, B_KC, FULL>),
+                           dim3(static_cast<unsigned>(ceil_div(p.batch, 4))), dim3(256), 0, p.stream, a);
+        return hipGetLastError();
+    }
+    static KernelEntry entry(const char *name)
+    {
+        mg_config c{};
+        c.family = MG_FAMILY_BATCHED;
+        c.dtype = MG_F32;
+        c.tile_m = 16 * MB; c.tile_n = 16 * NB; c.tile_k = 16 * KB;
+        c.waves_m = 1; c.waves_n = 1;
+        c.split_k = 1;
+        c.threads = 256;
+        c.lds_bytes = 0;
+        return KernelEntry{name, c, nullptr, nullptr, nullptr, legal, launch};
+    }
+};
+
+#define MG_BATCHED_REGISTER(table, tag, B)                                                        \
+    table.push_back(WaveConfig<B, B, B, false, true, true>::entry(tag "_mk_full"));               \
+    table.push_back(WaveConfig<B, B, B, false, true, false>::entry(tag "_mk"));                   \
+    table.push_back(WaveConfig<B, B, B, true, true, false>::entry(tag "_kk"));                    \
+    table.push_back(WaveConfig<B, B, B, false, false, false>::entry(tag "_mn"));                  \
+    table.push_back(WaveConfig<B, B, B, true, false, false>::entry(tag "_kn"));
+
+}  // namespace
+
+void register_batched(std::vector<KernelEntry> &table)
+{
+    MG_BATCHED_REGISTER(table, "batched_wave_16", 1)
+    MG_BATCHED_REGISTER(table, "batched_wave_32", 2)
+    MG_BATCHED_REGISTER(table, "batched_wave_64", 4)
+}
+
 }  // namespace mg

@@ -283,7 +283,7 @@ def test_every_batched_configuration_gives_parity(G, oracle):
     ran = {t["name"]: 0 for t in kernels}
     try:
         for (s, batch) in ((8, 50), (16, 70), (32, 20), (64, 9), (24, 5)):
-            for layout, ta, tb in ((C, N, N), (R, N, N), (C, T, T)):
+            for layout, ta, tb in ((C, N, N), (R, N, N), (C, T, T), (C, T, N), (C, N, T)):
                 bc = W.batched_case(s, s, s, batch, case=s, layout=layout, ta=ta, tb=tb, integer=True)
                 for t in kernels:
                     G.mg_override_batched_config(t["kernel_id"])
