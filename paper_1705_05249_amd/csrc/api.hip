@@ -98,7 +98,7 @@ int64_t problem_alignment(const Problem &p)
 
 // Picks the configuration for a canonical problem: the override if one is active, else the
 // heuristic table.  Returns MG_OK and fills kernel/split, or an error.
-mg_status choose(const Problem &p, int64_t alignment, int32_t *kernel, int32_t *split)
+mg_status choose(const Problem &p, int64_t alignment, size_t workspace_bytes, int32_t *kernel, int32_t *split)
 {
     const auto &t = table();
     const int32_t forced = g_override_kernel[p.dtype];
@@ -109,7 +109,7 @@ mg_status choose(const Problem &p, int64_t alignment, int32_t *kernel, int32_t *
         *split = g_override_split[p.dtype];
         return MG_OK;
     }
-    select_config(t, p, alignment, kernel, split);
+    select_config(t, p, alignment, workspace_bytes, kernel, split);
     if (*kernel < 0) return MG_ERR_CONFIG;
     return MG_OK;
 }
@@ -125,7 +125,8 @@ mg_status run_gemm(int dtype, int layout, int ta, int tb, int64_t m, int64_t n, 
     if (C == nullptr || (reads_ab && (A == nullptr || B == nullptr))) return MG_ERR_NULL;
     Problem p = canonical(dtype, layout, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, ws, ws_bytes, stream);
     int32_t kernel = -1, split = 1;
-    s = choose(p, problem_alignment(p), &kernel, &split);
+    const bool ws_usable = ws != nullptr && pointer_alignment(ws) >= 256;
+    s = choose(p, problem_alignment(p), ws_usable ? ws_bytes : 0, &kernel, &split);
     if (s != MG_OK) return s;
     const KernelEntry &e = table()[kernel];
     const size_t need = e.workspace(p, split);
@@ -206,7 +207,7 @@ size_t mg_gemm_workspace_bytes(int dtype, int layout, int ta, int tb, int64_t m,
     Problem p = canonical(dtype, layout, ta, tb, m, n, k, 1.f, nullptr, lda, nullptr, ldb, 1.f, nullptr, ldc,
                           nullptr, 0, nullptr);
     int32_t kernel = -1, split = 1;
-    if (choose(p, 256, &kernel, &split) != MG_OK) return 0;
+    if (choose(p, 256, ~size_t(0), &kernel, &split) != MG_OK) return 0;
     return table()[kernel].workspace(p, split);
 }
 
@@ -239,7 +240,7 @@ mg_status mg_query_selected(int dtype, int layout, int ta, int tb, int64_t m, in
     if (al <= 0 || (al & (al - 1)) != 0) return MG_ERR_CONFIG;
     if (al > 256) al = 256;
     int32_t kernel = -1, split = 1;
-    s = choose(p, al, &kernel, &split);
+    s = choose(p, al, ~size_t(0), &kernel, &split);
     if (s != MG_OK) return s;
     *out = table()[kernel].cfg;
     out->split_k = split;

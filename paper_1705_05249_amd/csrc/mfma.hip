@@ -1,16 +1,31 @@
+// Registration order of the compiled MFMA tile configurations (one translation unit per tile shape).
 #include "internal.h"
 
 namespace mg {
-void register_mfma_f16_a(std::vector<KernelEntry> &table);
-void register_mfma_f16_b(std::vector<KernelEntry> &table);
-void register_mfma_f16_c(std::vector<KernelEntry> &table);
-void register_mfma_f32_a(std::vector<KernelEntry> &table);
+void register_hmfma_256x256x64_w2x2(std::vector<KernelEntry> &table);
+void register_hmfma_256x256x64_w2x4(std::vector<KernelEntry> &table);
+void register_hmfma_256x128x64_w2x2(std::vector<KernelEntry> &table);
+void register_hmfma_128x128x64_w2x2(std::vector<KernelEntry> &table);
+void register_hmfma_128x64x64_w2x2(std::vector<KernelEntry> &table);
+void register_hmfma_64x64x64_w2x2(std::vector<KernelEntry> &table);
+void register_smfma_256x256x32_w2x2(std::vector<KernelEntry> &table);
+void register_smfma_256x128x32_w2x2(std::vector<KernelEntry> &table);
+void register_smfma_128x128x32_w2x2(std::vector<KernelEntry> &table);
+void register_smfma_128x64x32_w2x2(std::vector<KernelEntry> &table);
+void register_smfma_64x64x32_w2x2(std::vector<KernelEntry> &table);
 
 void register_mfma(std::vector<KernelEntry> &table)
 {
-    register_mfma_f16_a(table);
-    register_mfma_f16_b(table);
-    register_mfma_f16_c(table);
-    register_mfma_f32_a(table);
+    register_hmfma_256x256x64_w2x2(table);
+    register_hmfma_256x256x64_w2x4(table);
+    register_hmfma_256x128x64_w2x2(table);
+    register_hmfma_128x128x64_w2x2(table);
+    register_hmfma_128x64x64_w2x2(table);
+    register_hmfma_64x64x64_w2x2(table);
+    register_smfma_256x256x32_w2x2(table);
+    register_smfma_256x128x32_w2x2(table);
+    register_smfma_128x128x32_w2x2(table);
+    register_smfma_128x64x32_w2x2(table);
+    register_smfma_64x64x32_w2x2(table);
 }
 }  // namespace mg

@@ -1,0 +1,8 @@
+// MFMA macro-tile kernels, tile 128 x 128 x 64, 2 x 2 wavefronts, f16 storage.
+#include "mfma_host.h"
+namespace mg {
+void register_hmfma_128x128x64_w2x2(std::vector<KernelEntry> &table)
+{
+    MG_MFMA_REGISTER(table, _Float16, "hmfma_128x128x64_w2x2", 128, 128, 64, 2, 2)
+}
+}  // namespace mg

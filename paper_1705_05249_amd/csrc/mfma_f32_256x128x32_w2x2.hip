@@ -1,0 +1,8 @@
+// MFMA macro-tile kernels, tile 256 x 128 x 32, 2 x 2 wavefronts, f32 storage.
+#include "mfma_host.h"
+namespace mg {
+void register_smfma_256x128x32_w2x2(std::vector<KernelEntry> &table)
+{
+    MG_MFMA_REGISTER(table, float, "smfma_256x128x32_w2x2", 256, 128, 32, 2, 2)
+}
+}  // namespace mg

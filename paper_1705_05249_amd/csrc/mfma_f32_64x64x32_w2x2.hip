@@ -1,0 +1,8 @@
+// MFMA macro-tile kernels, tile 64 x 64 x 32, 2 x 2 wavefronts, f32 storage.
+#include "mfma_host.h"
+namespace mg {
+void register_smfma_64x64x32_w2x2(std::vector<KernelEntry> &table)
+{
+    MG_MFMA_REGISTER(table, float, "smfma_64x64x32_w2x2", 64, 64, 32, 2, 2)
+}
+}  // namespace mg

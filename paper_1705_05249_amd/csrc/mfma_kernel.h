@@ -91,6 +91,16 @@ template <typename T> __device__ inline uint32_t elem_bits(T v);
 template <> __device__ inline uint32_t elem_bits<float>(float v) { return __builtin_bit_cast(uint32_t, v); }
 template <> __device__ inline uint32_t elem_bits<_Float16>(_Float16 v) { return __builtin_bit_cast(uint16_t, v); }
 
+// 16 bytes at element alignment only (rows of a matrix with an odd leading dimension): one vector load,
+// which the memory pipeline splits as needed.
+template <typename T> struct __attribute__((packed, aligned(sizeof(T)))) UnalignedChunk {
+    T v[ElemTraits<T>::CH];
+};
+template <typename T> __device__ inline u32x4 load_unaligned_chunk(const T *p)
+{
+    return __builtin_bit_cast(u32x4, *reinterpret_cast<const UnalignedChunk<T> *>(p));
+}
+
 // CH consecutive elements starting at p, element e valid iff e < valid; missing ones are zero.
 template <typename T> __device__ inline u32x4 gather_chunk(const T *p, int valid)
 {
@@ -157,6 +167,7 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
                 const int kv = k_left - c * CH;
                 if (r >= rows_left || kv <= 0) regs[Q] = u32x4{0u, 0u, 0u, 0u};
                 else if (vec_ok && kv >= CH) regs[Q] = *reinterpret_cast<const u32x4 *>(p);
+                else if (kv >= CH) regs[Q] = load_unaligned_chunk<T>(p);
                 else regs[Q] = gather_chunk<T>(p, kv);
             }
         } else {
@@ -171,6 +182,7 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
                 const int rv = rows_left - mc * CH;
                 if (kc * CH + j >= k_left || rv <= 0) regs[Q] = u32x4{0u, 0u, 0u, 0u};
                 else if (vec_ok && rv >= CH) regs[Q] = *reinterpret_cast<const u32x4 *>(p);
+                else if (rv >= CH) regs[Q] = load_unaligned_chunk<T>(p);
                 else regs[Q] = gather_chunk<T>(p, rv);
             }
         }

@@ -6,9 +6,10 @@
 
 namespace mg {
 
-// Sets *kernel (-1 if nothing applies) and *split.
-void select_config(const std::vector<KernelEntry> &table, const Problem &p, int64_t alignment, int32_t *kernel,
-                   int32_t *split);
+// Sets *kernel (-1 if nothing applies) and *split.  workspace_bytes: what the caller can offer for split-K
+// partial sums (a configuration that needs more is not chosen).
+void select_config(const std::vector<KernelEntry> &table, const Problem &p, int64_t alignment, size_t workspace_bytes,
+                   int32_t *kernel, int32_t *split);
 // Returns the kernel id for a batched problem, or -1.
 int32_t select_batched(const std::vector<KernelEntry> &table, const BatchedProblem &p);
 

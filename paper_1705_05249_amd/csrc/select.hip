@@ -38,15 +38,34 @@ bool try_mfma(const std::vector<KernelEntry> &table, const Problem &p, int64_t a
 
 struct TileChoice {
     const char *tag;
-    int bm, bn;
+    int bm, bn, bk;
 };
 
 constexpr int kComputeUnits = 256;
 
+// Split-K factor for a grid of `blocks` work-groups that each walk `ktiles` K-tiles.  From the sweep:
+// a handful of blocks should be split until every compute unit has one (when K has >= 16 tiles and each
+// slice keeps >= 4 of them); a grid that fills the chip less than four times over gains from splitting only when K
+// is long (each slice keeps >= 24 K-tiles), because the reduce pass costs a launch and a round trip of
+// the partial sums; otherwise no split.
+int pick_split(int64_t blocks, int64_t ktiles)
+{
+    int64_t split = 1;
+    if (blocks <= 64 && ktiles >= 16) {
+        split = ceil_div(kComputeUnits, blocks);
+        if (split > ktiles / 4) split = ktiles / 4;
+    } else if (blocks < 4 * kComputeUnits && ktiles >= 48) {
+        split = ceil_div(4 * kComputeUnits, blocks);
+        if (split > ktiles / 24) split = ktiles / 24;
+    }
+    if (split > 16) split = 16;
+    return split < 1 ? 1 : static_cast<int>(split);
+}
+
 }  // namespace
 
-void select_config(const std::vector<KernelEntry> &table, const Problem &p, int64_t alignment, int32_t *kernel,
-                   int32_t *split)
+void select_config(const std::vector<KernelEntry> &table, const Problem &p, int64_t alignment, size_t workspace_bytes,
+                   int32_t *kernel, int32_t *split)
 {
     *kernel = -1;
     *split = 1;
@@ -55,17 +74,31 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
         try_pick(table, p, alignment, f32 ? "scale_f32" : "scale_f16", 1, kernel, split);
         return;
     }
-    if (p.m >= 64 && p.n >= 64) {
-        // largest macro tile that still gives most compute units a tile of their own
-        static const TileChoice f16_tiles[] = {{"hmfma_256x256x64_w2x2", 256, 256}, {"hmfma_128x128x64_w2x2", 128, 128}};
-        static const TileChoice f32_tiles[] = {{"smfma_128x128x32_w2x2", 128, 128}};
+    if (p.m == 1 || p.n == 1) {
+        if (try_pick(table, p, alignment, f32 ? "gemv_dot_f32" : "gemv_dot_f16", 1, kernel, split)) return;
+        if (try_pick(table, p, alignment, f32 ? "gemv_axpy_f32" : "gemv_axpy_f16", 1, kernel, split)) return;
+    }
+    if (p.m >= 16 && p.n >= 16) {
+        // Largest macro tile that still gives (nearly) every compute unit a tile of its own; short K goes
+        // to the smallest tile, whose many resident work-groups keep more of the C traffic in flight.
+        static const TileChoice f16_tiles[] = {{"hmfma_256x256x64_w2x2", 256, 256, 64},
+                                               {"hmfma_128x128x64_w2x2", 128, 128, 64},
+                                               {"hmfma_64x64x64_w2x2", 64, 64, 64}};
+        static const TileChoice f32_tiles[] = {{"smfma_256x256x32_w2x2", 256, 256, 32},
+                                               {"smfma_128x128x32_w2x2", 128, 128, 32},
+                                               {"smfma_64x64x32_w2x2", 64, 64, 32}};
         const TileChoice *tiles = f32 ? f32_tiles : f16_tiles;
-        const int count = f32 ? 1 : 2;
+        const int count = 3;
         for (int i = 0; i < count; ++i) {
-            const int64_t n_tiles = ceil_div(p.m, tiles[i].bm) * ceil_div(p.n, tiles[i].bn);
-            if (n_tiles >= (kComputeUnits * 3) / 4 || i == count - 1) {
-                if (try_mfma(table, p, alignment, tiles[i].tag, 1, kernel, split)) return;
-            }
+            const int64_t blocks = ceil_div(p.m, tiles[i].bm) * ceil_div(p.n, tiles[i].bn);
+            const int64_t ktiles = ceil_div(p.k, tiles[i].bk);
+            const bool last = i == count - 1;
+            if (!last && (blocks < (kComputeUnits * 3) / 4 || ktiles <= 8)) continue;
+            int want = last ? pick_split(blocks, ktiles) : 1;
+            // split-K needs the caller's workspace: without enough of it, run unsplit
+            while (want > 1 && static_cast<size_t>(want) * p.m * p.n * sizeof(float) > workspace_bytes) want = 1;
+            if (try_mfma(table, p, alignment, tiles[i].tag, want, kernel, split)) return;
+            if (want > 1 && try_mfma(table, p, alignment, tiles[i].tag, 1, kernel, split)) return;
         }
     }
     try_pick(table, p, alignment, f32 ? "direct_f32_64x64x16" : "direct_f16_64x64x16", 1, kernel, split);

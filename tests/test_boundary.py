@@ -139,5 +139,9 @@ def test_query_selected_and_override_roundtrip():
         assert st == -11
     finally:
         G.mg_clear_override()
-    assert G.mg_gemm_workspace_bytes(G.MG_F32, C, N, N, 256, 256, 256, 256, 256, 256) == 0
+    assert G.mg_gemm_workspace_bytes(G.MG_F32, C, N, N, 4096, 4096, 4096, 4096, 4096, 4096) == 0
+    # few tiles and a long K: split-K is selected, and the query says how much scratch it needs
+    sel = G.mg_query_selected(G.MG_F16, C, N, N, 512, 196, 2304, 512, 2304, 512)
+    need = G.mg_gemm_workspace_bytes(G.MG_F16, C, N, N, 512, 196, 2304, 512, 2304, 512)
+    assert sel["split_k"] > 1 and need == sel["split_k"] * 512 * 196 * 4
     assert G.mg_gemm_workspace_bytes(G.MG_F32, 0, N, N, 256, 256, 256, 256, 256, 256) == 0

@@ -100,6 +100,20 @@ def test_hgemm_subnormal_inputs_are_not_flushed(G, oracle):
     assert np.all(out.astype(np.float64) == k * 2.0 ** -14)
 
 
+def test_split_k_runs_only_with_workspace(G, oracle):
+    """a shape for which split-K is selected: with the workspace the query asks for it runs split, without
+    any workspace it silently runs unsplit; both give parity"""
+    case = W.config3(3)
+    code = G.MG_F16
+    sel = G.mg_query_selected(code, case.layout, case.ta, case.tb, case.m, case.n, case.k, case.lda, case.ldb, case.ldc)
+    assert sel["split_k"] > 1
+    H.check_case(case, oracle)                      # workspace sized by mg_gemm_workspace_bytes
+    H.check_case(case, oracle, workspace=None)      # no workspace: unsplit fallback
+    import torch
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    H.check_case(case, oracle, workspace=small)     # too small a workspace: unsplit fallback as well
+
+
 # ------------------------------------------------------------------ group 4: batched
 
 @pytest.mark.parametrize("size", W.CONFIG4_SIZES)
@@ -246,6 +260,8 @@ def _probe_cases(dtype):
             for (m, n, k) in ((512, 512, 256), (260, 250, 100)):
                 cases.append(W.hgemm_case(m, n, k, case=m + k, layout=layout, ta=ta, tb=tb, beta=1.0, integer=True))
             cases.append(W.hgemm_case(512, 512, 256, case=3, layout=layout, ta=ta, tb=tb, beta=0.5))
+            cases.append(W.hgemm_case(1, 512, 768, case=4, layout=layout, ta=ta, tb=tb, beta=1.0, integer=True))
+            cases.append(W.hgemm_case(512, 1, 768, case=5, layout=layout, ta=ta, tb=tb, beta=1.0, integer=True))
     return cases
 
 
