@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
 # counters read for a plain copy kernel of known size (profiles/ holds the summaries these come from).
-MEASURED_TRAFFIC_BYTES = {"hgemm_4096": None, "sgemm_4096": None, "batched_16x10000": None}
+MEASURED_TRAFFIC_BYTES = {"hgemm_4096": 240919833, "sgemm_4096": 474798550, "batched_16x10000": 44435167}
 
 
 def timed(fn, steps, warmup):
@@ -78,7 +78,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
-    ap.add_argument("--only", default=None, help="hgemm | sgemm | batched: run a single workload (profiling runs)")
+    ap.add_argument("--only", default=None, help="hgemm | sgemm | batched | copy: run a single workload (profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -93,6 +93,17 @@ def main():
     G.mg_clear_override()
     steps, warmup = args.steps, args.warmup
     extra = []
+
+    if args.only == "copy":
+        # calibration for the FETCH_SIZE / WRITE_SIZE counters: a plain device copy of known size
+        # (1 GiB read + 1 GiB written, far beyond the 256 MB last-level cache)
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": dst.numel() * 4, "launches": 3}))
+        return
 
     # ---- headline: HGEMM 4096^3 ------------------------------------------------------------------
     head = None

@@ -17,14 +17,16 @@
 //     would cost a sizeable fraction of an FP16 GEMM's run time at this machine's flop/byte;
 //   * software pipeline over K-tiles t and K-steps s (one K-step = one 16-byte fragment per
 //     lane and operand): while the MFMAs of step s run, the LDS reads of step s+1 are issued;
-//     the global loads of tile t+2 are issued during the last step of tile t and stay in
-//     registers until the second-to-last step of tile t+1, where they go to the other LDS
-//     buffer; the single barrier per tile sits between the last two steps, so the first
-//     fragments of the next tile are read behind it while MFMAs still run;
+//     each staging register goes to the other LDS buffer (tile t+1) and is at once reloaded from
+//     global memory (tile t+2), these store/load pairs being spread evenly over all steps but
+//     the last so that neither the LDS port nor the vector-memory path sees a burst; the single
+//     barrier per tile sits between the last two steps, so the first fragments of the next tile
+//     are read behind it while MFMAs still run;
 //   * the issue order is written out slot by slot (one MFMA group plus its share of the
 //     memory instructions) and pinned with scheduling barriers;
-//   * the MFMA's lane index is mapped to the m direction, so a store instruction writes 32
-//     consecutive elements of a C column.
+//   * FP32: the MFMA's lane index is mapped to the m direction, so a store instruction writes 32
+//     consecutive elements of a C column; FP16: it is mapped to n, so that a lane holds four
+//     consecutive m and stores them as one 8-byte piece (a quarter of the store instructions).
 //
 // Within one K-step the lanes of an operand fragment cover 2*CH values of k: lane group g
 // (= lane / 32) holds the CH values of chunk 2*step + g.  Both operands use the same mapping,
@@ -214,12 +216,15 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
 };
 
 // ---- MFMA on one pair of 16-byte fragments ---------------------------------------------------------
-// frag_n: rows of the B tile (n index) -> MFMA source A (output register index);
-// frag_m: rows of the A tile (m index) -> MFMA source B (output lane index).
+// The MFMA's source A indexes the output registers, source B the output lanes.
+//   FP32: source A = rows of the B tile (n), source B = rows of the A tile (m): lane <-> m
+//   FP16: source A = rows of the A tile (m), source B = rows of the B tile (n): lane <-> n
+template <typename T> struct LaneIsN { static constexpr bool value = sizeof(T) == 2; };
+
 __device__ inline void mma(floatx16 &acc, const u32x4 &frag_n, const u32x4 &frag_m, _Float16)
 {
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, frag_n),
-                                                 __builtin_bit_cast(halfx8, frag_m), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, frag_m),
+                                                 __builtin_bit_cast(halfx8, frag_n), acc, 0, 0, 0);
 }
 __device__ inline void mma(floatx16 &acc, const u32x4 &frag_n, const u32x4 &frag_m, float)
 {
@@ -231,6 +236,11 @@ __device__ inline void mma(floatx16 &acc, const u32x4 &frag_n, const u32x4 &frag
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
 }
+
+// four elements at element alignment
+template <typename U> struct __attribute__((packed, aligned(sizeof(U)))) Quad {
+    U v[4];
+};
 
 template <typename T> __device__ inline float load_as_float(const T *p) { return static_cast<float>(*p); }
 template <typename T> __device__ inline void store_from_float(T *p, float v) { *p = static_cast<T>(v); }
@@ -361,6 +371,26 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
         static_for<FRAGS>([&](auto F) { read_frag(F, lds, 0, 0); });
     }
 
+    // Event e of an operand's loader: the store of a staged piece (tile t+1) or its reload (tile t+2).
+    // Row-wise loader: store 0, load 0, store 1, load 1, ...; transposing loader: the CH stores of a block
+    // (each needs all CH registers of the block), then its CH loads.
+    constexpr int EV_A = 2 * LoadA::COUNT, EVENTS = 2 * PIECES;
+    constexpr int EVENT_SLOTS = (KSTEPS - 1) * SLOTS;
+    auto run_event = [&](auto E, char *stage) {
+        constexpr int e = decltype(E)::value;
+        constexpr bool is_a = e < EV_A;
+        constexpr int le = is_a ? e : e - EV_A;
+        constexpr bool kcontig = is_a ? A_KCONTIG : B_KCONTIG;
+        constexpr bool is_load = kcontig ? (le & 1) : (le % (2 * CH) >= CH);
+        constexpr int piece = kcontig ? (le >> 1) : (le / (2 * CH)) * CH + (le % CH);
+        if constexpr (is_a) {
+            if constexpr (is_load) la.template load_one<piece>(); else la.template store_one<piece>(stage);
+        } else {
+            if constexpr (is_load) lb.template load_one<piece>();
+            else lb.template store_one<piece>(stage + LoadA::LDS_BYTES);
+        }
+    };
+
     for (int t = 0; t < ktiles; ++t) {
         const char *cur = lds + (t & 1) * STAGE;
         char *nxt = lds + ((t + 1) & 1) * STAGE;
@@ -377,53 +407,104 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
                     if constexpr (s + 1 < KSTEPS) read_frag(std::integral_constant<int, f>{}, cur, s + 1, (s + 1) & 1);
                     else read_frag(std::integral_constant<int, f>{}, nxt, 0, 0);
                 });
-                // second-to-last step: registers (tile t+1) -> other LDS buffer
-                if constexpr (s == KSTEPS - 2)
-                    static_for<share_begin(q + 1, PIECES, SLOTS) - share_begin(q, PIECES, SLOTS)>([&](auto R) {
-                        store_piece(std::integral_constant<int, share_begin(q, PIECES, SLOTS) + decltype(R)::value>{}, nxt);
+                // this slot's share of the staging traffic: registers (tile t+1) -> other LDS buffer, global
+                // memory (tile t+2) -> the same registers
+                if constexpr (s < KSTEPS - 1) {
+                    constexpr int g = s * SLOTS + q;
+                    static_for<share_begin(g + 1, EVENTS, EVENT_SLOTS) - share_begin(g, EVENTS, EVENT_SLOTS)>([&](auto R) {
+                        run_event(std::integral_constant<int, share_begin(g, EVENTS, EVENT_SLOTS) + decltype(R)::value>{}, nxt);
                     });
-                // last step: global loads of tile t+2 -> registers
-                if constexpr (s == KSTEPS - 1)
-                    static_for<share_begin(q + 1, PIECES, SLOTS) - share_begin(q, PIECES, SLOTS)>([&](auto R) {
-                        load_piece(std::integral_constant<int, share_begin(q, PIECES, SLOTS) + decltype(R)::value>{});
-                    });
+                }
                 if constexpr (!EDGE) __builtin_amdgcn_sched_barrier(0);
             });
         });
     }
 
-    // ---- epilogue: accumulator register r of lane l is C(m, n) with
-    //      m = lane % 32,  n = 8*(r/4) + 4*(lane/32) + r%4   inside its 32x32 block.
-    // One per-lane base pointer; everything added to it is wave-uniform, and the three output modes
-    // (split-K partials / beta == 0 / beta != 0) are separate loops so that no store sits behind a branch.
-    const int lm = lane % 32, ln = 4 * (lane / 32);
+    // ---- epilogue.  One per-lane base pointer; everything added to it is wave-uniform, and the three
+    // output modes (split-K partials / beta == 0 / beta != 0) are separate loops so that no store sits
+    // behind a branch.
     const int wm_u = __builtin_amdgcn_readfirstlane(wm), wn_u = __builtin_amdgcn_readfirstlane(wn);
     const int64_t gm0 = m0 + wm_u * WTM, gn0 = n0 + wn_u * WTN;     // wave-uniform corner of the wavefront tile
-    auto write_out = [&](auto *base, int64_t ld, auto &&emit) {
+    const float alpha = args.alpha, beta = args.beta;
+    if constexpr (!LaneIsN<T>::value) {
+        // accumulator register r of lane l is C(m, n) with m = lane % 32, n = 8*(r/4) + 4*(lane/32) + r%4
+        const int lm = lane % 32, ln = 4 * (lane / 32);
+        auto write_out = [&](auto *base, int64_t ld, auto &&emit) {
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
+            for (int j = 0; j < FN; ++j)
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
+                for (int i = 0; i < FM; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int dn = j * 32 + 8 * (r / 4) + (r % 4), dm = i * 32;
-                    if constexpr (EDGE) {
-                        if (gm0 + dm + lm >= args.m || gn0 + dn + ln >= args.n) continue;
+                    for (int r = 0; r < 16; ++r) {
+                        const int dn = j * 32 + 8 * (r / 4) + (r % 4), dm = i * 32;
+                        if constexpr (EDGE) {
+                            if (gm0 + dm + lm >= args.m || gn0 + dn + ln >= args.n) continue;
+                        }
+                        emit(base + (dm + dn * ld), acc[j][i][r]);
                     }
-                    emit(base + (dm + dn * ld), acc[j][i][r]);
-                }
-    };
-    if (args.partial != nullptr) {
-        float *base = args.partial + (static_cast<int64_t>(blockIdx.z) * args.n + gn0 + ln) * args.m + gm0 + lm;
-        write_out(base, static_cast<int64_t>(args.m), [](float *p, float v) { *p = v; });
+        };
+        if (args.partial != nullptr) {
+            float *base = args.partial + (static_cast<int64_t>(blockIdx.z) * args.n + gn0 + ln) * args.m + gm0 + lm;
+            write_out(base, static_cast<int64_t>(args.m), [](float *p, float v) { *p = v; });
+        } else {
+            T *base = static_cast<T *>(args.C) + (gn0 + ln) * args.ldc + gm0 + lm;
+            if (beta == 0.f)
+                write_out(base, args.ldc, [alpha](T *p, float v) { store_from_float(p, alpha * v); });
+            else
+                write_out(base, args.ldc, [alpha, beta](T *p, float v) {
+                    store_from_float(p, fmaf(beta, load_as_float(p), alpha * v));
+                });
+        }
     } else {
-        T *base = static_cast<T *>(args.C) + (gn0 + ln) * args.ldc + gm0 + lm;
-        const float alpha = args.alpha, beta = args.beta;
-        if (beta == 0.f)
-            write_out(base, args.ldc, [alpha](T *p, float v) { store_from_float(p, alpha * v); });
-        else
-            write_out(base, args.ldc,
-                      [alpha, beta](T *p, float v) { store_from_float(p, fmaf(beta, load_as_float(p), alpha * v)); });
+        // accumulator register r of lane l is C(m, n) with n = lane % 32, m = 8*(r/4) + 4*(lane/32) + r%4:
+        // registers 4q .. 4q+3 are four consecutive m of one column -> one 8-byte (FP16) / 16-byte (FP32) piece
+        const int ln = lane % 32, lm = 4 * (lane / 32);
+        auto write_out = [&](auto *base, int64_t ld, auto &&emit) {
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int dn = j * 32, dm = i * 32 + 8 * q;
+                        int valid = 4;
+                        if constexpr (EDGE) {
+                            const int64_t left = args.m - (gm0 + dm + lm);
+                            valid = gn0 + dn + ln >= args.n ? 0 : (left >= 4 ? 4 : (left > 0 ? static_cast<int>(left) : 0));
+                            if (valid == 0) continue;
+                        }
+                        const float v[4] = {acc[j][i][4 * q], acc[j][i][4 * q + 1], acc[j][i][4 * q + 2],
+                                            acc[j][i][4 * q + 3]};
+                        emit(base + (dm + dn * ld), v, valid);
+                    }
+        };
+        if (args.partial != nullptr) {
+            float *base = args.partial + (static_cast<int64_t>(blockIdx.z) * args.n + gn0 + ln) * args.m + gm0 + lm;
+            write_out(base, static_cast<int64_t>(args.m), [](float *p, const float (&v)[4], int valid) {
+                if (valid == 4) *reinterpret_cast<Quad<float> *>(p) = Quad<float>{{v[0], v[1], v[2], v[3]}};
+                else for (int e = 0; e < valid; ++e) p[e] = v[e];
+            });
+        } else {
+            T *base = static_cast<T *>(args.C) + (gn0 + ln) * args.ldc + gm0 + lm;
+            write_out(base, args.ldc, [alpha, beta](T *p, const float (&v)[4], int valid) {
+                if (valid == 4) {
+                    float o[4] = {alpha * v[0], alpha * v[1], alpha * v[2], alpha * v[3]};
+                    if (beta != 0.f) {
+                        const Quad<T> c = *reinterpret_cast<const Quad<T> *>(p);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = fmaf(beta, static_cast<float>(c.v[e]), o[e]);
+                    }
+                    *reinterpret_cast<Quad<T> *>(p) = Quad<T>{{static_cast<T>(o[0]), static_cast<T>(o[1]),
+                                                               static_cast<T>(o[2]), static_cast<T>(o[3])}};
+                } else {
+                    for (int e = 0; e < valid; ++e) {
+                        float o = alpha * v[e];
+                        if (beta != 0.f) o = fmaf(beta, load_as_float(p + e), o);
+                        store_from_float(p + e, o);
+                    }
+                }
+            });
+        }
     }
 }
 
