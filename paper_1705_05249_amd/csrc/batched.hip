@@ -15,7 +15,10 @@
 // the overhead the paper points out when it compares the generic with the strided interface.
 // Instances only need 4-byte alignment (16-byte accesses are issued as align-4 vector loads).
 // Shapes up to 64 x 64 x 64 are covered by three register-block sizes; anything larger goes to
-// the direct batched kernel.
+// the direct batched kernel.  The 64-wide block splits an instance's columns over the four
+// wavefronts of a work-group (each re-reads A, which the L1 serves): a quarter of the registers
+// per wavefront means four times the resident wavefronts, so loads of some instances overlap
+// the MFMAs of others.
 #include "internal.h"
 
 namespace mg {
@@ -61,11 +64,15 @@ __device__ inline floatx4 load4(const float *__restrict__ X, int64_t ld, int row
     return v;
 }
 
-template <int MB, int NB, int KB, bool A_KC, bool B_KC, bool FULL>
+// NS: wavefronts per instance (each takes NB_ALL / NS of the 16-column blocks)
+template <int MB, int NB_ALL, int KB, int NS, bool A_KC, bool B_KC, bool FULL>
 __global__ __launch_bounds__(256) void batched_wave_kernel(const BatchedArgs a)
 {
+    constexpr int NB = NB_ALL / NS;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
-    const int64_t inst = static_cast<int64_t>(blockIdx.x) * 4 + wave;
+    const int64_t gw = static_cast<int64_t>(blockIdx.x) * 4 + wave;
+    const int64_t inst = gw / NS;
+    const int col0 = static_cast<int>(gw % NS) * NB * 16;       // first column of this wavefront's share
     if (inst >= a.batch) return;
     const float alpha = a.alphas[inst], beta = a.betas[inst];
     const float *__restrict__ A = a.A + a.a_off[inst];
@@ -85,7 +92,7 @@ __global__ __launch_bounds__(256) void batched_wave_kernel(const BatchedArgs a)
 #pragma unroll
         for (int bj = 0; bj < NB; ++bj)
 #pragma unroll
-            for (int bi = 0; bi < MB; ++bi) cold[bj][bi] = load4<true, FULL>(C, a.ldc, bj * 16 + r16, bi * 16 + 4 * g, a.n, a.m);
+            for (int bi = 0; bi < MB; ++bi) cold[bj][bi] = load4<true, FULL>(C, a.ldc, col0 + bj * 16 + r16, bi * 16 + 4 * g, a.n, a.m);
     }
 
     if (alpha != 0.f) {     // alpha == 0: A and B are not read at all
@@ -95,7 +102,7 @@ __global__ __launch_bounds__(256) void batched_wave_kernel(const BatchedArgs a)
 #pragma unroll
             for (int bi = 0; bi < MB; ++bi) av[bi][kb] = load4<A_KC, FULL>(A, a.lda, bi * 16 + r16, kb * 16 + 4 * g, a.m, a.k);
 #pragma unroll
-            for (int bj = 0; bj < NB; ++bj) bv[bj][kb] = load4<B_KC, FULL>(B, a.ldb, bj * 16 + r16, kb * 16 + 4 * g, a.n, a.k);
+            for (int bj = 0; bj < NB; ++bj) bv[bj][kb] = load4<B_KC, FULL>(B, a.ldb, col0 + bj * 16 + r16, kb * 16 + 4 * g, a.n, a.k);
         }
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
@@ -118,7 +125,7 @@ __global__ __launch_bounds__(256) void batched_wave_kernel(const BatchedArgs a)
     for (int bj = 0; bj < NB; ++bj)
 #pragma unroll
         for (int bi = 0; bi < MB; ++bi) {
-            const int j = bj * 16 + r16, i0 = bi * 16 + 4 * g;
+            const int j = col0 + bj * 16 + r16, i0 = bi * 16 + 4 * g;
             floatx4 o = alpha * acc[bj][bi];
             if (beta != 0.f) o += beta * cold[bj][bi];
             float *p = C + i0 + j * a.ldc;
@@ -134,13 +141,13 @@ __global__ __launch_bounds__(256) void batched_wave_kernel(const BatchedArgs a)
 
 // ---------------------------------------------------------------------------------- host side
 
-template <int MB, int NB, int KB, bool A_KC, bool B_KC, bool FULL> struct WaveConfig {
+template <int MB, int NB, int KB, int NS, bool A_KC, bool B_KC, bool FULL> struct WaveConfig {
     static bool legal(const BatchedProblem &p)
     {
         if (p.a_trans != A_KC || p.b_trans == B_KC) return false;
         if (p.m > 16 * MB || p.n > 16 * NB || p.k > 16 * KB) return false;
         if (FULL && (p.m != 16 * MB || p.n != 16 * NB || p.k != 16 * KB)) return false;
-        if (p.batch >= (int64_t(1) << 32)) return false;
+        if (p.batch * NS >= (int64_t(1) << 32)) return false;
         // offsets inside one instance are 32-bit in the kernel
         const int64_t lim = int64_t(1) << 24;
         return p.lda < lim && p.ldb < lim && p.ldc < lim;
@@ -149,8 +156,8 @@ template <int MB, int NB, int KB, bool A_KC, bool B_KC, bool FULL> struct WaveCo
     {
         BatchedArgs a{p.A, p.B, p.C, p.a_off, p.b_off, p.c_off, p.alphas, p.betas, p.lda, p.ldb, p.ldc,
                       static_cast<int>(p.m), static_cast<int>(p.n), static_cast<int>(p.k), p.batch};
-        hipLaunchKernelGGL((batched_wave_kernel<MB, NB, KB, A_KC, B_KC, FULL>),
-                           dim3(static_cast<unsigned>(ceil_div(p.batch, 4))), dim3(256), 0, p.stream, a);
+        hipLaunchKernelGGL((batched_wave_kernel<MB, NB, KB, NS, A_KC, B_KC, FULL>),
+                           dim3(static_cast<unsigned>(ceil_div(p.batch * NS, 4))), dim3(256), 0, p.stream, a);
         return hipGetLastError();
     }
     static KernelEntry entry(const char *name)
@@ -159,7 +166,7 @@ template <int MB, int NB, int KB, bool A_KC, bool B_KC, bool FULL> struct WaveCo
         c.family = MG_FAMILY_BATCHED;
         c.dtype = MG_F32;
         c.tile_m = 16 * MB; c.tile_n = 16 * NB; c.tile_k = 16 * KB;
-        c.waves_m = 1; c.waves_n = 1;
+        c.waves_m = 1; c.waves_n = NS;
         c.split_k = 1;
         c.threads = 256;
         c.lds_bytes = 0;
@@ -167,20 +174,21 @@ template <int MB, int NB, int KB, bool A_KC, bool B_KC, bool FULL> struct WaveCo
     }
 };
 
-#define MG_BATCHED_REGISTER(table, tag, B)                                                        \
-    table.push_back(WaveConfig<B, B, B, false, true, true>::entry(tag "_mk_full"));               \
-    table.push_back(WaveConfig<B, B, B, false, true, false>::entry(tag "_mk"));                   \
-    table.push_back(WaveConfig<B, B, B, true, true, false>::entry(tag "_kk"));                    \
-    table.push_back(WaveConfig<B, B, B, false, false, false>::entry(tag "_mn"));                  \
-    table.push_back(WaveConfig<B, B, B, true, false, false>::entry(tag "_kn"));
+#define MG_BATCHED_REGISTER(table, tag, B, NS)                                                    \
+    table.push_back(WaveConfig<B, B, B, NS, false, true, true>::entry(tag "_mk_full"));           \
+    table.push_back(WaveConfig<B, B, B, NS, false, true, false>::entry(tag "_mk"));               \
+    table.push_back(WaveConfig<B, B, B, NS, true, true, false>::entry(tag "_kk"));                \
+    table.push_back(WaveConfig<B, B, B, NS, false, false, false>::entry(tag "_mn"));              \
+    table.push_back(WaveConfig<B, B, B, NS, true, false, false>::entry(tag "_kn"));
 
 }  // namespace
 
 void register_batched(std::vector<KernelEntry> &table)
 {
-    MG_BATCHED_REGISTER(table, "batched_wave_16", 1)
-    MG_BATCHED_REGISTER(table, "batched_wave_32", 2)
-    MG_BATCHED_REGISTER(table, "batched_wave_64", 4)
+    MG_BATCHED_REGISTER(table, "batched_wave_16", 1, 1)
+    MG_BATCHED_REGISTER(table, "batched_wave_32", 2, 1)
+    MG_BATCHED_REGISTER(table, "batched_wave_64", 4, 4)
+    MG_BATCHED_REGISTER(table, "batched_wave_64w1", 4, 1)
 }
 
 }  // namespace mg

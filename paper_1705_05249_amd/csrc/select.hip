@@ -107,7 +107,7 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
 int32_t select_batched(const std::vector<KernelEntry> &table, const BatchedProblem &p)
 {
     // one wavefront per instance while the instance fits the register blocks (<= 64 in every extent)
-    static const char *const tags[] = {"batched_wave_16", "batched_wave_32", "batched_wave_64"};
+    static const char *const tags[] = {"batched_wave_16", "batched_wave_32", "batched_wave_64w1"};
     const char *contig = p.a_trans ? (p.b_trans ? "kn" : "kk") : (p.b_trans ? "mn" : "mk");
     for (const char *tag : tags) {
         char name[96];

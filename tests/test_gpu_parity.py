@@ -313,3 +313,43 @@ def test_every_batched_configuration_gives_parity(G, oracle):
         G.mg_clear_override()
     never = [name for name, count in ran.items() if count == 0]
     assert not never, f"batched kernels never exercised: {never}"
+
+
+# ------------------------------------------------------------------ HIP graph capture of the library's launches
+
+def test_calls_can_be_captured_in_a_hip_graph(G, oracle):
+    """the library only enqueues kernels (no memset, no allocation), so its calls can be captured; every
+    replay, with eager work and synchronisations in between, reproduces the eager result"""
+    import torch
+    case = W.hgemm_case(512, 384, 256, case=21, beta=0.5)
+    bc = W.batched_case(16, 16, 16, 40, case=22)
+    A, B, C0 = H.to_gpu(case.A), H.to_gpu(case.B), H.to_gpu(case.C)
+    t = {name: H.to_gpu(getattr(bc, name)) for name in ("A", "B", "C", "a_off", "b_off", "c_off", "alphas", "betas")}
+    Cb0 = t["C"].clone()
+    C = C0.clone()
+
+    def calls():
+        G.mg_hgemm(case.layout, case.ta, case.tb, case.m, case.n, case.k, case.alpha, A, case.lda, B, case.ldb,
+                   case.beta, C, case.ldc)
+        G.mg_sgemm_batched(bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, t["alphas"], t["A"], t["a_off"], bc.lda,
+                           t["B"], t["b_off"], bc.ldb, t["betas"], t["C"], t["c_off"], bc.ldc, bc.batch)
+
+    calls()
+    torch.cuda.synchronize()
+    eager_c, eager_b = C.clone(), t["C"].clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        C.copy_(C0); t["C"].copy_(Cb0)
+        calls()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    C.copy_(C0); t["C"].copy_(Cb0)
+    with torch.cuda.graph(graph):
+        calls()
+    for _ in range(3):
+        C.copy_(C0); t["C"].copy_(Cb0)
+        (A.float().sum() + 1).item()              # unrelated eager work and a synchronisation between replays
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(C, eager_c) and torch.equal(t["C"], eager_b)
