@@ -8,7 +8,9 @@ namespace mg {
 template <typename T, int BM, int BN, int BK, int WM, int WN, bool AK, bool BKC, bool EDGE> struct MfmaConfig {
     static constexpr int CH = ElemTraits<T>::CH;
     static constexpr int NT = WM * WN * 64;
-    static constexpr int LDS = 2 * (BM + BN) * 128;
+    static constexpr int STAGES_LDS = 2 * (BM + BN) * 128;                    // two operand stages
+    static constexpr int EPILOGUE_LDS = WM * WN * 32 * ((BM / WM) * 4 + 16);   // one 32-column staging block per wavefront
+    static constexpr int LDS = STAGES_LDS > EPILOGUE_LDS ? STAGES_LDS : EPILOGUE_LDS;
     static constexpr int DTYPE = sizeof(T) == 4 ? MG_F32 : MG_F16;
 
     static int k_per_split(const Problem &p, int split)

@@ -20,22 +20,31 @@
 //     each staging register goes to the other LDS buffer (tile t+1) and is at once reloaded from
 //     global memory (tile t+2), these store/load pairs being spread evenly over all steps but
 //     the last so that neither the LDS port nor the vector-memory path sees a burst; the single
-//     barrier per tile sits between the last two steps, so the first fragments of the next tile
-//     are read behind it while MFMAs still run;
+//     barrier per tile sits inside the last step, so the first fragments of the next tile are read
+//     behind it while MFMAs still run;
 //   * the issue order is written out slot by slot (one MFMA group plus its share of the
 //     memory instructions) and pinned with scheduling barriers;
-//   * FP32: the MFMA's lane index is mapped to the m direction, so a store instruction writes 32
-//     consecutive elements of a C column; FP16: it is mapped to n, so that a lane holds four
-//     consecutive m and stores them as one 8-byte piece (a quarter of the store instructions).
+//   * the MFMA's lane index is mapped to n, so a lane holds four consecutive m of one column; the
+//     epilogue turns each 32-column block of a wavefront's tile through LDS (16-byte writes of
+//     those quads, then 16/32-byte reads along m), so that C is read (beta != 0) and written in
+//     16-byte pieces per lane that form whole contiguous column segments per instruction.
 //
 // Within one K-step the lanes of an operand fragment cover 2*CH values of k: lane group g
 // (= lane / 32) holds the CH values of chunk 2*step + g.  Both operands use the same mapping,
 // and a sum over k does not care about the order, so no further shuffling is needed.
 #pragma once
 
+#include <type_traits>
 #include <utility>
 
 #include "internal.h"
+
+#ifndef MG_TAIL_SIXTEENTHS
+#define MG_TAIL_SIXTEENTHS 4   // share (in 1/16) of the last K-step that runs behind the per-tile barrier
+#endif
+#ifndef MG_TOUCH_AHEAD
+#define MG_TOUCH_AHEAD 0        // K-tiles between an L2 touch and the tile the MFMAs work on
+#endif
 
 namespace mg {
 
@@ -208,6 +217,23 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
         }
     }
 
+    // Touches this thread's 128-byte line of the tile at (r0, l0) -- ROWS lines in all -- with a 4-byte load
+    // whose result nobody waits for: it only pulls the line into the L2 ahead of the real loads.  `sink`
+    // must stay allocated until the caller has waited for all vector-memory loads.
+    __device__ static inline void touch(const T *X, int64_t ld, int64_t r0, int64_t l0, uint32_t &sink)
+    {
+        const int t = threadIdx.x;
+        if (NT > ROWS && t >= ROWS) return;
+        const T *p;
+        if constexpr (KCONTIG) {
+            p = X + (r0 + t) * ld + l0;
+        } else {
+            constexpr int LPC = ROWS * static_cast<int>(sizeof(T)) / 128;      // lines per tile column
+            p = X + r0 + (t % LPC) * (128 / static_cast<int>(sizeof(T))) + (l0 + t / LPC) * ld;
+        }
+        asm volatile("global_load_dword %0, %1, off" : "+v"(sink) : "v"(p) : "memory");
+    }
+
     __device__ inline void load_all() { static_for<COUNT>([&](auto q) { load_one<decltype(q)::value>(); }); }
     __device__ inline void store_all(char *lds) const
     {
@@ -216,11 +242,9 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
 };
 
 // ---- MFMA on one pair of 16-byte fragments ---------------------------------------------------------
-// The MFMA's source A indexes the output registers, source B the output lanes.
-//   FP32: source A = rows of the B tile (n), source B = rows of the A tile (m): lane <-> m
-//   FP16: source A = rows of the A tile (m), source B = rows of the B tile (n): lane <-> n
-template <typename T> struct LaneIsN { static constexpr bool value = sizeof(T) == 2; };
-
+// The MFMA's source A indexes the output registers, source B the output lanes: source A = rows of the A
+// tile (m), source B = rows of the B tile (n), so that accumulator register r of lane l is C(m, n) with
+// n = l % 32 and m = 8*(r/4) + 4*(l/32) + r%4 inside its 32x32 block.
 __device__ inline void mma(floatx16 &acc, const u32x4 &frag_n, const u32x4 &frag_m, _Float16)
 {
     acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, frag_m),
@@ -230,16 +254,16 @@ __device__ inline void mma(floatx16 &acc, const u32x4 &frag_n, const u32x4 &frag
 {
     // (whole-vector casts and named components: indexing the uint vector inside a bit cast picked
     // component 0 four times with this compiler)
-    const floatx4 a = __builtin_bit_cast(floatx4, frag_n), b = __builtin_bit_cast(floatx4, frag_m);
+    const floatx4 a = __builtin_bit_cast(floatx4, frag_m), b = __builtin_bit_cast(floatx4, frag_n);
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
 }
 
-// four elements at element alignment
-template <typename U> struct __attribute__((packed, aligned(sizeof(U)))) Quad {
-    U v[4];
+// N elements at element alignment
+template <typename U, int N> struct __attribute__((packed, aligned(sizeof(U)))) Pack {
+    U v[N];
 };
 
 template <typename T> __device__ inline float load_as_float(const T *p) { return static_cast<float>(*p); }
@@ -375,7 +399,9 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
     // Row-wise loader: store 0, load 0, store 1, load 1, ...; transposing loader: the CH stores of a block
     // (each needs all CH registers of the block), then its CH loads.
     constexpr int EV_A = 2 * LoadA::COUNT, EVENTS = 2 * PIECES;
-    constexpr int EVENT_SLOTS = (KSTEPS - 1) * SLOTS;
+    // the last TAIL slots of the K-tile come behind the barrier and carry no staging traffic
+    constexpr int TAIL = (SLOTS * MG_TAIL_SIXTEENTHS / 16) > 0 ? (SLOTS * MG_TAIL_SIXTEENTHS / 16) : 1;
+    constexpr int EVENT_SLOTS = KSTEPS * SLOTS - TAIL;
     auto run_event = [&](auto E, char *stage) {
         constexpr int e = decltype(E)::value;
         constexpr bool is_a = e < EV_A;
@@ -391,26 +417,45 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
         }
     };
 
+    // The fast path also touches the lines of a tile a few K-tiles ahead: the work-groups of an XCD walk K
+    // in step, so without this every first use of a line is an L2 miss that all its users wait for, and the
+    // staging registers cannot cover that latency.
+    constexpr int TOUCH_AHEAD = EDGE ? 0 : MG_TOUCH_AHEAD;
+    uint32_t touch_sink = 0;
     for (int t = 0; t < ktiles; ++t) {
         const char *cur = lds + (t & 1) * STAGE;
         char *nxt = lds + ((t + 1) & 1) * STAGE;
         aim_tile(t + 2);
+        if constexpr (TOUCH_AHEAD > 0) {
+            int l0 = kb + (t + TOUCH_AHEAD) * BK;
+            l0 = l0 < ke ? l0 : ke - BK;
+            LoadA::touch(A, args.lda, m0, l0, touch_sink);
+            LoadB::touch(B, args.ldb, n0, l0, touch_sink);
+        }
         static_for<KSTEPS>([&](auto S) {
             constexpr int s = decltype(S)::value;
-            if constexpr (s == KSTEPS - 1) __syncthreads();      // tile t+1 is complete in `nxt`
             static_for<SLOTS>([&](auto Q) {
                 constexpr int q = decltype(Q)::value;
+                constexpr int g = s * SLOTS + q;                 // slot number inside the K-tile
+                if constexpr (g == EVENT_SLOTS) __syncthreads();  // tile t+1 is complete in `nxt`
                 mma(acc[q / FM][q % FM], fb[s & 1][q / FM], fa[s & 1][q % FM], T{});
-                // this slot's share of the LDS reads for the next K-step (of this tile, or step 0 of the next)
-                static_for<share_begin(q + 1, FRAGS, SLOTS) - share_begin(q, FRAGS, SLOTS)>([&](auto R) {
-                    constexpr int f = share_begin(q, FRAGS, SLOTS) + decltype(R)::value;
-                    if constexpr (s + 1 < KSTEPS) read_frag(std::integral_constant<int, f>{}, cur, s + 1, (s + 1) & 1);
-                    else read_frag(std::integral_constant<int, f>{}, nxt, 0, 0);
-                });
+                if constexpr (s + 1 < KSTEPS) {
+                    // this slot's share of the LDS reads for the next K-step
+                    static_for<share_begin(q + 1, FRAGS, SLOTS) - share_begin(q, FRAGS, SLOTS)>([&](auto R) {
+                        constexpr int f = share_begin(q, FRAGS, SLOTS) + decltype(R)::value;
+                        read_frag(std::integral_constant<int, f>{}, cur, s + 1, (s + 1) & 1);
+                    });
+                } else if constexpr (g >= EVENT_SLOTS) {
+                    // behind the barrier: the first fragments of the next tile
+                    constexpr int h = g - EVENT_SLOTS;
+                    static_for<share_begin(h + 1, FRAGS, TAIL) - share_begin(h, FRAGS, TAIL)>([&](auto R) {
+                        constexpr int f = share_begin(h, FRAGS, TAIL) + decltype(R)::value;
+                        read_frag(std::integral_constant<int, f>{}, nxt, 0, 0);
+                    });
+                }
                 // this slot's share of the staging traffic: registers (tile t+1) -> other LDS buffer, global
                 // memory (tile t+2) -> the same registers
-                if constexpr (s < KSTEPS - 1) {
-                    constexpr int g = s * SLOTS + q;
+                if constexpr (g < EVENT_SLOTS) {
                     static_for<share_begin(g + 1, EVENTS, EVENT_SLOTS) - share_begin(g, EVENTS, EVENT_SLOTS)>([&](auto R) {
                         run_event(std::integral_constant<int, share_begin(g, EVENTS, EVENT_SLOTS) + decltype(R)::value>{}, nxt);
                     });
@@ -420,90 +465,104 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
         });
     }
 
-    // ---- epilogue.  One per-lane base pointer; everything added to it is wave-uniform, and the three
-    // output modes (split-K partials / beta == 0 / beta != 0) are separate loops so that no store sits
-    // behind a branch.
+    // ---- epilogue.  Per 32-column block j of the wavefront's tile: accumulators -> this wavefront's own LDS
+    // region as [column][m] floats (16-byte writes of the four consecutive m a lane holds), then every lane
+    // reads PER = 16 / sizeof(output element) consecutive m of one column and handles them as one 16-byte
+    // piece of C (or of the split-K partial sums).  A wavefront instruction thus covers whole contiguous
+    // column segments.  Only this wavefront touches its region and the LDS executes a wavefront's operations
+    // in order, so the two phases need no barrier, only a fence that keeps the compiler from moving one
+    // lane's reads across the writes other lanes depend on.
+    __syncthreads();                                   // every wavefront is done reading the operand stages
+    if constexpr (TOUCH_AHEAD > 0) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("" ::"v"(touch_sink));             // the touch loads may write their register until here
+    }
     const int wm_u = __builtin_amdgcn_readfirstlane(wm), wn_u = __builtin_amdgcn_readfirstlane(wn);
     const int64_t gm0 = m0 + wm_u * WTM, gn0 = n0 + wn_u * WTN;     // wave-uniform corner of the wavefront tile
     const float alpha = args.alpha, beta = args.beta;
-    if constexpr (!LaneIsN<T>::value) {
-        // accumulator register r of lane l is C(m, n) with m = lane % 32, n = 8*(r/4) + 4*(lane/32) + r%4
-        const int lm = lane % 32, ln = 4 * (lane / 32);
-        auto write_out = [&](auto *base, int64_t ld, auto &&emit) {
+    constexpr int ROWB = WTM * 4 + 16;                 // staging row stride in bytes (16 lanes x 16 B hit all banks)
+    char *region = lds + __builtin_amdgcn_readfirstlane(wave) * (32 * ROWB);
+    const int ln = lane % 32, lg = lane / 32;
+
+    auto wave_fence = [] {
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
+    auto stage_block = [&](int j) {
+        wave_fence();
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
+        for (int i = 0; i < FM; ++i)
 #pragma unroll
-                for (int i = 0; i < FM; ++i)
+            for (int q = 0; q < 4; ++q) {
+                const floatx4 v = {acc[j][i][4 * q], acc[j][i][4 * q + 1], acc[j][i][4 * q + 2], acc[j][i][4 * q + 3]};
+                *reinterpret_cast<floatx4 *>(region + ln * ROWB + (i * 32 + 8 * q + 4 * lg) * 4) = v;
+            }
+        wave_fence();
+    };
+    // U: output element type (T for C, float for partial sums); emit(pointer to PER elements, values, valid count)
+    auto drain_block = [&](auto *base, int64_t ld, int j, auto &&emit) {
+        using U = std::remove_pointer_t<decltype(base)>;
+        constexpr int PER = 16 / static_cast<int>(sizeof(U));
+        constexpr int CPRW = WTM / PER;                // pieces per column
+        constexpr int COLS = 64 / CPRW;                // columns per wavefront instruction
+        static_assert(CPRW <= 64 && 64 % CPRW == 0, "wavefront tile rows");
+        const int c = lane % CPRW, r0 = lane / CPRW;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int dn = j * 32 + 8 * (r / 4) + (r % 4), dm = i * 32;
-                        if constexpr (EDGE) {
-                            if (gm0 + dm + lm >= args.m || gn0 + dn + ln >= args.n) continue;
-                        }
-                        emit(base + (dm + dn * ld), acc[j][i][r]);
-                    }
-        };
-        if (args.partial != nullptr) {
-            float *base = args.partial + (static_cast<int64_t>(blockIdx.z) * args.n + gn0 + ln) * args.m + gm0 + lm;
-            write_out(base, static_cast<int64_t>(args.m), [](float *p, float v) { *p = v; });
-        } else {
-            T *base = static_cast<T *>(args.C) + (gn0 + ln) * args.ldc + gm0 + lm;
-            if (beta == 0.f)
-                write_out(base, args.ldc, [alpha](T *p, float v) { store_from_float(p, alpha * v); });
-            else
-                write_out(base, args.ldc, [alpha, beta](T *p, float v) {
-                    store_from_float(p, fmaf(beta, load_as_float(p), alpha * v));
-                });
+        for (int pass = 0; pass < 32 / COLS; ++pass) {
+            const int r = r0 + pass * COLS;            // column inside the 32-column block
+            const int64_t gn = gn0 + j * 32 + r, gm = gm0 + c * PER;
+            int valid = PER;
+            if constexpr (EDGE) {
+                const int64_t left = args.m - gm;
+                valid = gn >= args.n ? 0 : (left >= PER ? PER : (left > 0 ? static_cast<int>(left) : 0));
+            }
+            float v[PER];
+#pragma unroll
+            for (int h = 0; h < PER / 4; ++h) {
+                const floatx4 x = *reinterpret_cast<const floatx4 *>(region + r * ROWB + (c * PER + 4 * h) * 4);
+                v[4 * h] = x.x; v[4 * h + 1] = x.y; v[4 * h + 2] = x.z; v[4 * h + 3] = x.w;
+            }
+            if (valid > 0) emit(base + gm + gn * ld, v, valid);
         }
-    } else {
-        // accumulator register r of lane l is C(m, n) with n = lane % 32, m = 8*(r/4) + 4*(lane/32) + r%4:
-        // registers 4q .. 4q+3 are four consecutive m of one column -> one 8-byte (FP16) / 16-byte (FP32) piece
-        const int ln = lane % 32, lm = 4 * (lane / 32);
-        auto write_out = [&](auto *base, int64_t ld, auto &&emit) {
+    };
+
+    if (args.partial != nullptr) {
+        float *base = args.partial + static_cast<int64_t>(blockIdx.z) * args.n * args.m;
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-#pragma unroll
-                for (int i = 0; i < FM; ++i)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int dn = j * 32, dm = i * 32 + 8 * q;
-                        int valid = 4;
-                        if constexpr (EDGE) {
-                            const int64_t left = args.m - (gm0 + dm + lm);
-                            valid = gn0 + dn + ln >= args.n ? 0 : (left >= 4 ? 4 : (left > 0 ? static_cast<int>(left) : 0));
-                            if (valid == 0) continue;
-                        }
-                        const float v[4] = {acc[j][i][4 * q], acc[j][i][4 * q + 1], acc[j][i][4 * q + 2],
-                                            acc[j][i][4 * q + 3]};
-                        emit(base + (dm + dn * ld), v, valid);
-                    }
-        };
-        if (args.partial != nullptr) {
-            float *base = args.partial + (static_cast<int64_t>(blockIdx.z) * args.n + gn0 + ln) * args.m + gm0 + lm;
-            write_out(base, static_cast<int64_t>(args.m), [](float *p, const float (&v)[4], int valid) {
-                if (valid == 4) *reinterpret_cast<Quad<float> *>(p) = Quad<float>{{v[0], v[1], v[2], v[3]}};
+        for (int j = 0; j < FN; ++j) {
+            stage_block(j);
+            drain_block(base, static_cast<int64_t>(args.m), j, [](float *p, const float (&v)[4], int valid) {
+                if (valid == 4) *reinterpret_cast<Pack<float, 4> *>(p) = Pack<float, 4>{{v[0], v[1], v[2], v[3]}};
                 else for (int e = 0; e < valid; ++e) p[e] = v[e];
             });
-        } else {
-            T *base = static_cast<T *>(args.C) + (gn0 + ln) * args.ldc + gm0 + lm;
-            write_out(base, args.ldc, [alpha, beta](T *p, const float (&v)[4], int valid) {
-                if (valid == 4) {
-                    float o[4] = {alpha * v[0], alpha * v[1], alpha * v[2], alpha * v[3]};
-                    if (beta != 0.f) {
-                        const Quad<T> c = *reinterpret_cast<const Quad<T> *>(p);
+        }
+    } else {
+        constexpr int PER = 16 / static_cast<int>(sizeof(T));
+        T *base = static_cast<T *>(args.C);
+        auto emit = [alpha, beta](T *p, const float (&v)[PER], int valid) {
+            if (valid == PER) {
+                Pack<T, PER> o;
+                if (beta != 0.f) {
+                    const Pack<T, PER> c = *reinterpret_cast<const Pack<T, PER> *>(p);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = fmaf(beta, static_cast<float>(c.v[e]), o[e]);
-                    }
-                    *reinterpret_cast<Quad<T> *>(p) = Quad<T>{{static_cast<T>(o[0]), static_cast<T>(o[1]),
-                                                               static_cast<T>(o[2]), static_cast<T>(o[3])}};
+                    for (int e = 0; e < PER; ++e) o.v[e] = static_cast<T>(fmaf(beta, static_cast<float>(c.v[e]), alpha * v[e]));
                 } else {
-                    for (int e = 0; e < valid; ++e) {
-                        float o = alpha * v[e];
-                        if (beta != 0.f) o = fmaf(beta, load_as_float(p + e), o);
-                        store_from_float(p + e, o);
-                    }
+#pragma unroll
+                    for (int e = 0; e < PER; ++e) o.v[e] = static_cast<T>(alpha * v[e]);
                 }
-            });
+                *reinterpret_cast<Pack<T, PER> *>(p) = o;
+            } else {
+                for (int e = 0; e < valid; ++e) {
+                    float o = alpha * v[e];
+                    if (beta != 0.f) o = fmaf(beta, load_as_float(p + e), o);
+                    store_from_float(p + e, o);
+                }
+            }
+        };
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            stage_block(j);
+            drain_block(base, args.ldc, j, emit);
         }
     }
 }
