@@ -45,6 +45,37 @@ def timed(fn, steps, warmup):
     return dev, wall
 
 
+def graph_timed(call, c_buffer, steps, warmup, per_graph=20):
+    """Device time per call of a microsecond-scale launch: shorter than the host can issue launches (about
+    8 us per call from Python), so the call is captured once into a HIP graph of `per_graph` launches and the
+    graph is replayed; the events then bracket back-to-back kernels.  Every replay of a one-launch graph is
+    first checked against the eager result.  Returns (seconds per call from replays, from eager launches)."""
+    import torch
+    c0 = c_buffer.clone()
+    call()
+    eager = c_buffer.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call()                                       # warm-up on a capture-capable stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(per_graph):
+            call()
+    one = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(one):
+        call()
+    for _ in range(3):
+        c_buffer.copy_(c0)
+        one.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(c_buffer, eager), "graph replay differs from the eager call"
+    dev, _ = timed(graph.replay, max(1, steps // 2), max(1, warmup // 4))
+    dev_eager, _ = timed(call, steps, warmup)
+    return dev / per_graph, dev_eager
+
+
 def gemm_workload(G, case, steps, warmup):
     import torch
     from tests import helpers as H
@@ -142,46 +173,29 @@ def main():
     if args.only in (None, "batched"):
         bc = W.config4_fast(16, 10000)
         t = {name: H.to_gpu(getattr(bc, name)) for name in ("A", "B", "C", "a_off", "b_off", "c_off", "alphas", "betas")}
+        stride = int(bc.a_off[1] - bc.a_off[0])
 
-        def call():
+        def generic():
             G.mg_sgemm_batched(bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, t["alphas"], t["A"], t["a_off"], bc.lda,
                                t["B"], t["b_off"], bc.ldb, t["betas"], t["C"], t["c_off"], bc.ldc, bc.batch)
 
-        # A 7 us kernel is shorter than the host can issue launches (about 8 us per call from Python), so the
-        # calls are captured once into a HIP graph of 20 launches and the graph is replayed: the events then
-        # bracket back-to-back kernels.  The captured graph is checked against an eager call first.
-        c0 = t["C"].clone()
-        call()
-        eager = t["C"].clone()
-        per_graph = 20
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            call()                                   # warm-up on the capture stream
-        torch.cuda.current_stream().wait_stream(side)
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            for _ in range(per_graph):
-                call()
-        one = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(one):
-            call()
-        for _ in range(3):                           # every replay must reproduce the eager result
-            t["C"].copy_(c0)
-            one.replay()
-            torch.cuda.synchronize()
-            assert torch.equal(t["C"], eager), "graph replay differs from the eager call"
-        dev, wall = timed(graph.replay, max(1, steps // 2), max(1, warmup // 4))
-        dev, wall = dev / per_graph, wall / per_graph
-        dev_eager, _ = timed(call, steps, warmup)
-        gbs = bc.algorithmic_bytes / dev / 1e9
-        extra.append({"workload": "sgemm_batched_f32_10000x16x16x16_gap7", "gflops": round(bc.flops / dev / 1e9, 1),
-                      "ms": round(dev * 1e3, 5), "ms_eager_launches": round(dev_eager * 1e3, 5),
-                      "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                   "frac": round(gbs / PEAK_HBM_GBS, 4),
-                                   "traffic": MEASURED_TRAFFIC_BYTES.get("batched_16x10000")},
-                      "note": "timed as replays of a HIP graph of 20 launches (host launch rate is ~8 us/call); "
-                              "41 MB working set: repeated calls are served by the 256 MB last-level cache"})
+        def strided():
+            G.mg_sgemm_strided_batched(bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, 1.25, t["A"], bc.lda, stride, t["B"],
+                                       bc.ldb, stride, 0.75, t["C"], bc.ldc, stride, bc.batch)
+
+        note = ("timed as replays of a HIP graph of 20 launches (host launch rate is ~8 us/call); "
+                "41 MB working set: repeated calls are served by the 256 MB last-level cache")
+        for label, call, scalar_bytes in (("sgemm_batched_f32_10000x16x16x16_gap7", generic, 32),
+                                          ("sgemm_strided_batched_f32_10000x16x16x16_gap7", strided, 0)):
+            dev, dev_eager = graph_timed(call, t["C"], steps, warmup)
+            nbytes = bc.algorithmic_bytes - bc.batch * (32 - scalar_bytes)
+            gbs = nbytes / dev / 1e9
+            extra.append({"workload": label, "gflops": round(bc.flops / dev / 1e9, 1), "ms": round(dev * 1e3, 5),
+                          "ms_eager_launches": round(dev_eager * 1e3, 5),
+                          "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                       "frac": round(gbs / PEAK_HBM_GBS, 4),
+                                       "traffic": MEASURED_TRAFFIC_BYTES.get("batched_16x10000") if scalar_bytes else None},
+                          "note": note})
 
     if head is None:
         print(json.dumps({"workloads": extra}))

@@ -61,7 +61,8 @@ enum {
     MG_ERR_WORKSPACE = -10,   /* workspace NULL/misaligned/too small for the configuration  */
     MG_ERR_CONFIG = -11,      /* unknown kernel id, or configuration illegal for this call  */
     MG_ERR_LAUNCH = -12,      /* the HIP runtime refused the launch (see hipGetLastError)   */
-    MG_ERR_NO_DEVICE = -13    /* no usable gfx950 device / HIP runtime error before launch  */
+    MG_ERR_NO_DEVICE = -13,   /* no usable gfx950 device / HIP runtime error before launch  */
+    MG_ERR_STRIDE = -14       /* a batch stride is negative                                 */
 };
 
 typedef enum { MG_ROW_MAJOR = 101, MG_COL_MAJOR = 102 } mg_layout;
@@ -124,6 +125,20 @@ mg_status mg_sgemm_batched(int layout, int trans_a, int trans_b, int64_t m, int6
                            const float *betas,
                            float *C, const int64_t *c_offsets, int64_t ldc,
                            int64_t batch_count, void *stream);
+
+/* ---- strided batched GEMM (paper Section 4.6) ------------------------------------------
+ * The less generic batched form: no offset arrays and no scalar arrays.  Instance b uses
+ * A + b*stride_a, B + b*stride_b, C + b*stride_c (strides in ELEMENTS, >= 0) and the same
+ * host scalars alpha, beta for the whole batch.  Otherwise as mg_sgemm_batched: it computes
+ * exactly what the generic routine computes with offsets b*stride and constant scalars.
+ * Checks, in addition to those of mg_sgemm_batched: MG_ERR_STRIDE for a negative stride. */
+mg_status mg_sgemm_strided_batched(int layout, int trans_a, int trans_b, int64_t m, int64_t n, int64_t k,
+                                   float alpha,
+                                   const float *A, int64_t lda, int64_t stride_a,
+                                   const float *B, int64_t ldb, int64_t stride_b,
+                                   float beta,
+                                   float *C, int64_t ldc, int64_t stride_c,
+                                   int64_t batch_count, void *stream);
 
 /* Bytes of workspace the currently selected configuration needs for this problem
  * (0 for most).  dtype is an mg_dtype.  Returns 0 for invalid arguments. */

@@ -131,6 +131,16 @@ def sgemm_batched(layout, ta, tb, m, n, k, alphas, A, a_off, lda, B, b_off, ldb,
     return c_ref, d_ref
 
 
+def sgemm_strided_batched(layout, ta, tb, m, n, k, alpha, A, lda, stride_a, B, ldb, stride_b, beta, C, ldc,
+                          stride_c, batch):
+    """Strided batched oracle.  Section 4.6 defines the strided routine as the generic one without the
+    offset and scalar arrays: instance b sits at b*stride and every instance uses the same alpha, beta.
+    That definition is written out here: the arrays are built and the generic oracle is called."""
+    idx = np.arange(batch, dtype=np.int64)
+    return sgemm_batched(layout, ta, tb, m, n, k, np.full(batch, alpha, dtype=np.float32), A, idx * stride_a, lda,
+                         B, idx * stride_b, ldb, np.full(batch, beta, dtype=np.float32), C, idx * stride_c, ldc)
+
+
 def half_to_double(bits):
     bits = _flat(bits, np.uint16)
     out = np.empty(bits.size, dtype=np.float64)

@@ -134,6 +134,39 @@ mg_status run_gemm(int dtype, int layout, int ta, int tb, int64_t m, int64_t n, 
     return e.launch(p, split) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
 }
 
+// Canonicalises a (generic or strided) batched call to column-major and launches it.
+mg_status run_batched(BatchedProblem &p, int layout, int ta, int tb, int64_t m, int64_t n, int64_t k,
+                      const float *A, const int64_t *a_off, int64_t stride_a, int64_t lda, const float *B,
+                      const int64_t *b_off, int64_t stride_b, int64_t ldb, float *C, const int64_t *c_off,
+                      int64_t stride_c, int64_t ldc, int64_t batch, void *stream)
+{
+    const bool at = ta != MG_NO_TRANS, bt = tb != MG_NO_TRANS;
+    p.k = k;
+    p.C = C; p.c_off = c_off; p.stride_c = stride_c; p.ldc = ldc;
+    p.batch = batch;
+    p.stream = static_cast<hipStream_t>(stream);
+    if (layout == MG_COL_MAJOR) {
+        p.m = m; p.n = n;
+        p.A = A; p.a_off = a_off; p.stride_a = stride_a; p.lda = lda; p.a_trans = at;
+        p.B = B; p.b_off = b_off; p.stride_b = stride_b; p.ldb = ldb; p.b_trans = bt;
+    } else {
+        p.m = n; p.n = m;
+        p.A = B; p.a_off = b_off; p.stride_a = stride_b; p.lda = ldb; p.a_trans = bt;
+        p.B = A; p.b_off = a_off; p.stride_b = stride_a; p.ldb = lda; p.b_trans = at;
+    }
+    const auto &t = table();
+    int32_t kernel = -1;
+    if (g_override_batched >= 0) {
+        const KernelEntry &e = t[g_override_batched];
+        if (!e.legal_batched || !e.legal_batched(p)) return MG_ERR_CONFIG;
+        kernel = g_override_batched;
+    } else {
+        kernel = select_batched(t, p);
+        if (kernel < 0) return MG_ERR_CONFIG;
+    }
+    return t[kernel].launch_batched(p) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
+}
+
 }  // namespace
 }  // namespace mg
 
@@ -164,38 +197,33 @@ mg_status mg_sgemm_batched(int layout, int ta, int tb, int64_t m, int64_t n, int
 {
     mg_status s = check_shape(layout, ta, tb, m, n, k, lda, ldb, ldc);
     if (s != MG_OK) return s;
-    if (batch_count < 0) return MG_ERR_BATCH;
-    if (batch_count >= (int64_t(1) << 31)) return MG_ERR_BATCH;
+    if (batch_count < 0 || batch_count >= (int64_t(1) << 31)) return MG_ERR_BATCH;
     if (m == 0 || n == 0 || batch_count == 0) return MG_OK;
     if (!alphas || !betas || !a_offsets || !b_offsets || !c_offsets || !C) return MG_ERR_NULL;
     if (k != 0 && (!A || !B)) return MG_ERR_NULL;
     BatchedProblem p{};
-    const bool at = ta != MG_NO_TRANS, bt = tb != MG_NO_TRANS;
-    p.k = k;
-    p.C = C; p.c_off = c_offsets; p.ldc = ldc;
     p.alphas = alphas; p.betas = betas;
-    p.batch = batch_count;
-    p.stream = static_cast<hipStream_t>(stream);
-    if (layout == MG_COL_MAJOR) {
-        p.m = m; p.n = n;
-        p.A = A; p.a_off = a_offsets; p.lda = lda; p.a_trans = at;
-        p.B = B; p.b_off = b_offsets; p.ldb = ldb; p.b_trans = bt;
-    } else {
-        p.m = n; p.n = m;
-        p.A = B; p.a_off = b_offsets; p.lda = ldb; p.a_trans = bt;
-        p.B = A; p.b_off = a_offsets; p.ldb = lda; p.b_trans = at;
-    }
-    const auto &t = table();
-    int32_t kernel = -1;
-    if (g_override_batched >= 0) {
-        const KernelEntry &e = t[g_override_batched];
-        if (!e.legal_batched || !e.legal_batched(p)) return MG_ERR_CONFIG;
-        kernel = g_override_batched;
-    } else {
-        kernel = select_batched(t, p);
-        if (kernel < 0) return MG_ERR_CONFIG;
-    }
-    return t[kernel].launch_batched(p) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
+    return run_batched(p, layout, ta, tb, m, n, k, A, a_offsets, 0, lda, B, b_offsets, 0, ldb, C, c_offsets, 0, ldc,
+                       batch_count, stream);
+}
+
+mg_status mg_sgemm_strided_batched(int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, float alpha,
+                                   const float *A, int64_t lda, int64_t stride_a, const float *B, int64_t ldb,
+                                   int64_t stride_b, float beta, float *C, int64_t ldc, int64_t stride_c,
+                                   int64_t batch_count, void *stream)
+{
+    mg_status s = check_shape(layout, ta, tb, m, n, k, lda, ldb, ldc);
+    if (s != MG_OK) return s;
+    if (batch_count < 0 || batch_count >= (int64_t(1) << 31)) return MG_ERR_BATCH;
+    if (stride_a < 0 || stride_b < 0 || stride_c < 0) return MG_ERR_STRIDE;
+    if (m == 0 || n == 0 || batch_count == 0) return MG_OK;
+    if (!C) return MG_ERR_NULL;
+    if (k != 0 && alpha != 0.f && (!A || !B)) return MG_ERR_NULL;
+    BatchedProblem p{};
+    p.strided = true;
+    p.alpha = alpha; p.beta = beta;
+    return run_batched(p, layout, ta, tb, m, n, k, A, nullptr, stride_a, lda, B, nullptr, stride_b, ldb, C, nullptr,
+                       stride_c, ldc, batch_count, stream);
 }
 
 size_t mg_gemm_workspace_bytes(int dtype, int layout, int ta, int tb, int64_t m, int64_t n, int64_t k,
@@ -289,10 +317,11 @@ const char *mg_status_string(mg_status status)
         case MG_ERR_CONFIG: return "unknown or illegal kernel configuration";
         case MG_ERR_LAUNCH: return "kernel launch failed";
         case MG_ERR_NO_DEVICE: return "no usable device";
+        case MG_ERR_STRIDE: return "negative batch stride";
         default: return "unknown status";
     }
 }
 
-const char *mg_version(void) { return "0.1"; }
+const char *mg_version(void) { return "0.2"; }
 
 }  // extern "C"

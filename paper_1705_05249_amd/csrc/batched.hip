@@ -37,6 +37,10 @@ struct BatchedArgs {
     int64_t lda, ldb, ldc;
     int m, n, k;
     int64_t batch;
+    // strided form: offsets are instance * stride and the scalars are kernel arguments
+    int strided;
+    int64_t stride_a, stride_b, stride_c;
+    float alpha, beta;
 };
 
 // four values X[row][k0 .. k0+3] of an operand block; KC: contiguous along k (X[k + row*ld]) or
@@ -74,10 +78,11 @@ __global__ __launch_bounds__(256) void batched_wave_kernel(const BatchedArgs a)
     const int64_t inst = gw / NS;
     const int col0 = static_cast<int>(gw % NS) * NB * 16;       // first column of this wavefront's share
     if (inst >= a.batch) return;
-    const float alpha = a.alphas[inst], beta = a.betas[inst];
-    const float *__restrict__ A = a.A + a.a_off[inst];
-    const float *__restrict__ B = a.B + a.b_off[inst];
-    float *__restrict__ C = a.C + a.c_off[inst];
+    // generic form: five wave-uniform scalar loads per instance; strided form: none
+    const float alpha = a.strided ? a.alpha : a.alphas[inst], beta = a.strided ? a.beta : a.betas[inst];
+    const float *__restrict__ A = a.A + (a.strided ? inst * a.stride_a : a.a_off[inst]);
+    const float *__restrict__ B = a.B + (a.strided ? inst * a.stride_b : a.b_off[inst]);
+    float *__restrict__ C = a.C + (a.strided ? inst * a.stride_c : a.c_off[inst]);
     const int lane = threadIdx.x % 64, r16 = lane % 16, g = lane / 16;
 
     floatx4 acc[NB][MB];
@@ -155,7 +160,8 @@ template <int MB, int NB, int KB, int NS, bool A_KC, bool B_KC, bool FULL> struc
     static hipError_t launch(const BatchedProblem &p)
     {
         BatchedArgs a{p.A, p.B, p.C, p.a_off, p.b_off, p.c_off, p.alphas, p.betas, p.lda, p.ldb, p.ldc,
-                      static_cast<int>(p.m), static_cast<int>(p.n), static_cast<int>(p.k), p.batch};
+                      static_cast<int>(p.m), static_cast<int>(p.n), static_cast<int>(p.k), p.batch,
+                      p.strided ? 1 : 0, p.stride_a, p.stride_b, p.stride_c, p.alpha, p.beta};
         hipLaunchKernelGGL((batched_wave_kernel<MB, NB, KB, NS, A_KC, B_KC, FULL>),
                            dim3(static_cast<unsigned>(ceil_div(p.batch * NS, 4))), dim3(256), 0, p.stream, a);
         return hipGetLastError();

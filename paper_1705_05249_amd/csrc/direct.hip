@@ -113,14 +113,19 @@ __global__ __launch_bounds__(256) void direct_batched_kernel(int64_t m, int64_t 
                                                               const int64_t *__restrict__ c_off, int64_t ldc,
                                                               const float *__restrict__ alphas,
                                                               const float *__restrict__ betas, int64_t tiles_m,
-                                                              int64_t tiles)
+                                                              int64_t tiles, int strided, int64_t stride_a,
+                                                              int64_t stride_b, int64_t stride_c, float alpha_all,
+                                                              float beta_all)
 {
     const int64_t inst = blockIdx.x / tiles;
     const int64_t t = blockIdx.x % tiles;
-    const float alpha = alphas[inst], beta = betas[inst];
+    const float alpha = strided ? alpha_all : alphas[inst], beta = strided ? beta_all : betas[inst];
+    const int64_t oa = strided ? inst * stride_a : a_off[inst];
+    const int64_t ob = strided ? inst * stride_b : b_off[inst];
+    const int64_t oc = strided ? inst * stride_c : c_off[inst];
     // alpha == 0: A and B must not contribute (they may hold NaN/Inf) -> run with k = 0
-    direct_tile<float>(m, n, alpha == 0.f ? 0 : k, A + a_off[inst], a_sm, a_sk, B + b_off[inst], b_sk, b_sn,
-                       C + c_off[inst], ldc, alpha, beta, t % tiles_m, t / tiles_m);
+    direct_tile<float>(m, n, alpha == 0.f ? 0 : k, A + oa, a_sm, a_sk, B + ob, b_sk, b_sn, C + oc, ldc, alpha, beta,
+                       t % tiles_m, t / tiles_m);
 }
 
 // ---------------------------------------------------------------------------------- host side
@@ -166,7 +171,7 @@ hipError_t launch_batched_direct(const BatchedProblem &p)
     hipLaunchKernelGGL(direct_batched_kernel, dim3(static_cast<unsigned>(tiles * p.batch)), dim3(256), 0, p.stream,
                        p.m, p.n, p.k, p.A, p.a_off, p.a_trans ? p.lda : 1, p.a_trans ? 1 : p.lda, p.B, p.b_off,
                        p.b_trans ? p.ldb : 1, p.b_trans ? 1 : p.ldb, p.C, p.c_off, p.ldc, p.alphas, p.betas,
-                       tiles_m, tiles);
+                       tiles_m, tiles, p.strided ? 1 : 0, p.stride_a, p.stride_b, p.stride_c, p.alpha, p.beta);
     return hipGetLastError();
 }
 

@@ -40,7 +40,9 @@ struct Problem {
     size_t elem() const { return dtype == MG_F32 ? 4 : 2; }
 };
 
-// Canonical batched problem (FP32): per-instance scalars and element offsets live on the device.
+// Canonical batched problem (FP32).  Generic form: per-instance scalars and element offsets live on the
+// device.  Strided form (strided == true): the offset and scalar arrays are null, instance b sits at
+// b * stride_x and uses the host scalars alpha, beta.
 struct BatchedProblem {
     int64_t m, n, k;
     const float *A;
@@ -57,6 +59,9 @@ struct BatchedProblem {
     const float *alphas, *betas;
     int64_t batch;
     hipStream_t stream;
+    bool strided;
+    int64_t stride_a, stride_b, stride_c;
+    float alpha, beta;
 };
 
 // One compiled kernel (or kernel family instance) in the configuration table.

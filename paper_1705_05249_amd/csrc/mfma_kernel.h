@@ -42,9 +42,6 @@
 #ifndef MG_TAIL_SIXTEENTHS
 #define MG_TAIL_SIXTEENTHS 4   // share (in 1/16) of the last K-step that runs behind the per-tile barrier
 #endif
-#ifndef MG_TOUCH_AHEAD
-#define MG_TOUCH_AHEAD 0        // K-tiles between an L2 touch and the tile the MFMAs work on
-#endif
 
 namespace mg {
 
@@ -215,23 +212,6 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
             if (PARTIAL && idx >= BLOCKS) return;
             *reinterpret_cast<u32x4 *>(lds + lds_offset(mc * CH + i, kc)) = transposed_row<i>(&regs[b * CH], T{});
         }
-    }
-
-    // Touches this thread's 128-byte line of the tile at (r0, l0) -- ROWS lines in all -- with a 4-byte load
-    // whose result nobody waits for: it only pulls the line into the L2 ahead of the real loads.  `sink`
-    // must stay allocated until the caller has waited for all vector-memory loads.
-    __device__ static inline void touch(const T *X, int64_t ld, int64_t r0, int64_t l0, uint32_t &sink)
-    {
-        const int t = threadIdx.x;
-        if (NT > ROWS && t >= ROWS) return;
-        const T *p;
-        if constexpr (KCONTIG) {
-            p = X + (r0 + t) * ld + l0;
-        } else {
-            constexpr int LPC = ROWS * static_cast<int>(sizeof(T)) / 128;      // lines per tile column
-            p = X + r0 + (t % LPC) * (128 / static_cast<int>(sizeof(T))) + (l0 + t / LPC) * ld;
-        }
-        asm volatile("global_load_dword %0, %1, off" : "+v"(sink) : "v"(p) : "memory");
     }
 
     __device__ inline void load_all() { static_for<COUNT>([&](auto q) { load_one<decltype(q)::value>(); }); }
@@ -417,21 +397,10 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
         }
     };
 
-    // The fast path also touches the lines of a tile a few K-tiles ahead: the work-groups of an XCD walk K
-    // in step, so without this every first use of a line is an L2 miss that all its users wait for, and the
-    // staging registers cannot cover that latency.
-    constexpr int TOUCH_AHEAD = EDGE ? 0 : MG_TOUCH_AHEAD;
-    uint32_t touch_sink = 0;
     for (int t = 0; t < ktiles; ++t) {
         const char *cur = lds + (t & 1) * STAGE;
         char *nxt = lds + ((t + 1) & 1) * STAGE;
         aim_tile(t + 2);
-        if constexpr (TOUCH_AHEAD > 0) {
-            int l0 = kb + (t + TOUCH_AHEAD) * BK;
-            l0 = l0 < ke ? l0 : ke - BK;
-            LoadA::touch(A, args.lda, m0, l0, touch_sink);
-            LoadB::touch(B, args.ldb, n0, l0, touch_sink);
-        }
         static_for<KSTEPS>([&](auto S) {
             constexpr int s = decltype(S)::value;
             static_for<SLOTS>([&](auto Q) {
@@ -473,10 +442,6 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
     // in order, so the two phases need no barrier, only a fence that keeps the compiler from moving one
     // lane's reads across the writes other lanes depend on.
     __syncthreads();                                   // every wavefront is done reading the operand stages
-    if constexpr (TOUCH_AHEAD > 0) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        asm volatile("" ::"v"(touch_sink));             // the touch loads may write their register until here
-    }
     const int wm_u = __builtin_amdgcn_readfirstlane(wm), wn_u = __builtin_amdgcn_readfirstlane(wn);
     const int64_t gm0 = m0 + wm_u * WTM, gn0 = n0 + wn_u * WTN;     // wave-uniform corner of the wavefront tile
     const float alpha = args.alpha, beta = args.beta;

@@ -17,7 +17,7 @@ MG_F32, MG_F16 = 0, 1
 MG_OK = 0
 MG_FAMILY_DIRECT, MG_FAMILY_MFMA, MG_FAMILY_GEMV, MG_FAMILY_SCALE, MG_FAMILY_BATCHED = 0, 1, 2, 3, 4
 
-EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemm_batched", "mg_gemm_workspace_bytes", "mg_kernel_count",
+EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemm_batched", "mg_sgemm_strided_batched", "mg_gemm_workspace_bytes", "mg_kernel_count",
            "mg_kernel_info", "mg_kernel_name", "mg_query_selected", "mg_override_config",
            "mg_override_batched_config", "mg_clear_override", "mg_status_string", "mg_version")
 
@@ -57,6 +57,9 @@ def lib():
         L.mg_sgemm_batched.argtypes = [i32, i32, i32, i64, i64, i64, vp, vp, vp, i64, vp, vp, i64, vp, vp, vp, i64,
                                        i64, vp]
         L.mg_sgemm_batched.restype = i32
+        L.mg_sgemm_strided_batched.argtypes = [i32, i32, i32, i64, i64, i64, f32, vp, i64, i64, vp, i64, i64, f32, vp,
+                                               i64, i64, i64, vp]
+        L.mg_sgemm_strided_batched.restype = i32
         L.mg_gemm_workspace_bytes.argtypes = [i32, i32, i32, i32, i64, i64, i64, i64, i64, i64]
         L.mg_gemm_workspace_bytes.restype = sz
         L.mg_kernel_count.argtypes = []
@@ -134,6 +137,15 @@ def mg_sgemm_batched(layout, trans_a, trans_b, m, n, k, alphas, A, a_offsets, ld
                                 batch_count, _stream(stream))
     if check and st != MG_OK:
         raise MgError(st, "mg_sgemm_batched")
+    return st
+
+
+def mg_sgemm_strided_batched(layout, trans_a, trans_b, m, n, k, alpha, A, lda, stride_a, B, ldb, stride_b, beta, C,
+                             ldc, stride_c, batch_count, stream=None, check=True) -> int:
+    st = lib().mg_sgemm_strided_batched(layout, trans_a, trans_b, m, n, k, alpha, _addr(A), lda, stride_a, _addr(B),
+                                        ldb, stride_b, beta, _addr(C), ldc, stride_c, batch_count, _stream(stream))
+    if check and st != MG_OK:
+        raise MgError(st, "mg_sgemm_strided_batched")
     return st
 
 

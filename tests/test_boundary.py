@@ -91,9 +91,30 @@ def test_batched_argument_errors():
     assert batched(m=0, alphas=None, A=None) == 0
 
 
+def strided(m=4, n=4, k=4, batch=3, A=FAKE, B=FAKE, Cp=FAKE, sa=16, sb=16, sc=16, layout=C, ta=N, tb=N, lda=4, ldb=4,
+            ldc=4, alpha=1.0, beta=1.0):
+    return G.mg_sgemm_strided_batched(layout, ta, tb, m, n, k, alpha, A, lda, sa, B, ldb, sb, beta, Cp, ldc, sc, batch,
+                                      stream=0, check=False)
+
+
+def test_strided_batched_argument_errors():
+    assert strided(layout=7) == -1
+    assert strided(ta=1) == -2
+    assert strided(tb=1) == -3
+    assert strided(m=-1) == -4
+    assert strided(lda=3) == -5
+    assert strided(ldb=3) == -6
+    assert strided(ldc=3) == -7
+    assert strided(batch=-1) == -9
+    assert strided(sa=-1) == -14 and strided(sb=-1) == -14 and strided(sc=-1) == -14
+    assert strided(A=None) == -8 and strided(B=None) == -8 and strided(Cp=None) == -8
+    assert strided(batch=0, A=None, Cp=None) == 0
+    assert strided(n=0, A=None, Cp=None) == 0
+
+
 def test_status_strings_and_version():
     seen = set()
-    for code in range(0, -14, -1):
+    for code in range(0, -15, -1):
         s = G.status_string(code)
         assert s and s != "unknown status" and s not in seen
         seen.add(s)

@@ -168,6 +168,54 @@ def test_batched_alpha_zero_and_beta_zero_per_instance(G, oracle):
     assert H.rel_error(mats, c_ref, d_ref) <= H.TOL["f32"]
 
 
+# ------------------------------------------------------------------ strided batched (same data as the generic form)
+
+@pytest.mark.parametrize("layout,ta,tb", VARIANTS)
+@pytest.mark.parametrize("shape", [(16, 16, 16, 300), (8, 8, 8, 77), (33, 20, 70, 9), (64, 64, 64, 5), (70, 130, 9, 3)])
+def test_strided_batched(G, oracle, layout, ta, tb, shape):
+    """strided == generic with offsets b*stride and constant scalars: against the oracle (bit-exact on
+    integers), against the generic routine on the same buffers (bitwise), gaps untouched"""
+    import torch
+    m, n, k, batch = shape
+    bc = W.batched_case(m, n, k, batch, case=m + n + k, layout=layout, ta=ta, tb=tb, integer=True)
+    sa, sb, sc = (int(x[1] - x[0]) for x in (bc.a_off, bc.b_off, bc.c_off))
+    alpha, beta = 1.5, 0.5
+    A, B, Cs = H.to_gpu(bc.A), H.to_gpu(bc.B), H.to_gpu(bc.C)
+    announce("strided", bc.name, layout, ta, tb)
+    G.mg_sgemm_strided_batched(layout, ta, tb, m, n, k, alpha, A, bc.lda, sa, B, bc.ldb, sb, beta, Cs, bc.ldc, sc, batch)
+    torch.cuda.synchronize()
+    out = Cs.cpu().numpy()
+    mats, mask = H.batched_outputs(bc, out)
+    assert np.array_equal(H.bits(out)[mask], H.bits(bc.C)[mask])
+    c_ref, _ = oracle.sgemm_strided_batched(layout, ta, tb, m, n, k, alpha, bc.A, bc.lda, sa, bc.B, bc.ldb, sb, beta,
+                                            bc.C, bc.ldc, sc, batch)
+    assert np.array_equal(mats.astype(np.float64), c_ref)
+    # the generic routine on the same data
+    bc.alphas[:] = alpha
+    bc.betas[:] = beta
+    _, out_generic = H.run_batched_gpu(bc)
+    assert np.array_equal(H.bits(out), H.bits(out_generic))
+
+
+def test_strided_batched_scalars_and_random(G, oracle):
+    import torch
+    bc = W.batched_case(16, 16, 16, 50, case=31)
+    stride = int(bc.a_off[1] - bc.a_off[0])
+    for alpha, beta in ((0.0, 2.0), (1.25, 0.0), (0.7, 1.3)):
+        A, B, Cs = H.to_gpu(bc.A), H.to_gpu(bc.B), H.to_gpu(bc.C)
+        if alpha == 0.0:
+            A = torch.full_like(A, float("nan"))           # must not be read
+        if beta == 0.0:
+            Cs = torch.where(Cs == float(W.GAP_FILL), Cs, torch.full_like(Cs, float("nan")))   # C_old must not be read
+        G.mg_sgemm_strided_batched(bc.layout, bc.ta, bc.tb, 16, 16, 16, alpha, A, 16, stride, B, 16, stride, beta, Cs,
+                                   16, stride, bc.batch)
+        torch.cuda.synchronize()
+        mats, _ = H.batched_outputs(bc, Cs.cpu().numpy())
+        c_ref, d_ref = oracle.sgemm_strided_batched(bc.layout, bc.ta, bc.tb, 16, 16, 16, alpha, bc.A, 16, stride, bc.B,
+                                                    16, stride, beta, bc.C, 16, stride, bc.batch)
+        assert H.rel_error(mats, c_ref, d_ref) <= H.TOL["f32"]
+
+
 # ------------------------------------------------------------------ group 5: odd and skinny
 
 @pytest.mark.parametrize("index", range(len(W.CONFIG5_SHAPES)))

@@ -355,6 +355,21 @@ def test_batched_distinct_offset_arrays(oracle):
         assert np.array_equal(c_ref[i], want)
 
 
+def test_strided_batched_is_the_generic_one_with_regular_offsets(oracle):
+    """pins the strided wrapper: per instance it equals numpy's product of the data found at b*stride"""
+    g = W.rng_for(90, 12)
+    m, n, k, batch = 4, 3, 5, 6
+    sa, sb, sc = m * k + 2, k * n + 1, m * n + 4
+    A = W.small_ints(g, batch * sa); B = W.small_ints(g, batch * sb); C0 = W.small_ints(g, batch * sc)
+    c_ref, d_ref = oracle.sgemm_strided_batched(Cm, N, T, m, n, k, 1.5, A, m, sa, B, n, sb, -0.5, C0, m, sc, batch)
+    for b in range(batch):
+        a = W.unpack(A[b * sa:], Cm, m, k, m).astype(np.float64)
+        bt = W.unpack(B[b * sb:], Cm, n, k, n).astype(np.float64)          # stored n x k, op = transpose
+        c = W.unpack(C0[b * sc:], Cm, m, n, m).astype(np.float64)
+        assert np.array_equal(c_ref[b], 1.5 * (a @ bt.T) - 0.5 * c)
+        assert np.array_equal(d_ref[b], 1.5 * (np.abs(a) @ np.abs(bt.T)) + 0.5 * np.abs(c))
+
+
 # ---------------------------------------------------------------- input generator sanity
 
 def test_padded_ld_reading():
