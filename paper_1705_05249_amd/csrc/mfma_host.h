@@ -28,6 +28,9 @@ template <typename T, int BM, int BN, int BK, int WM, int WN, bool AK, bool BKC,
         if (ceil_div(p.m, BM) * ceil_div(p.n, BN) >= (int64_t(1) << 31)) return false;
         if (split > 1 && static_cast<int64_t>(k_per_split(p, split)) * (split - 1) >= p.k) return false;  // empty slice
         if (!EDGE) {
+            // lane offsets inside a tile are 32-bit byte offsets
+            const int64_t span = (BM > BN ? BM : BN) > BK ? (BM > BN ? BM : BN) : BK;
+            if ((p.lda > p.ldb ? p.lda : p.ldb) * span * static_cast<int64_t>(sizeof(T)) >= (int64_t(1) << 31)) return false;
             if (p.m % BM || p.n % BN || p.k % BK) return false;
             if (p.lda % CH || p.ldb % CH) return false;
             // A and B need 16-byte alignment; `alignment` is the minimum over A, B and C

@@ -40,7 +40,7 @@
 #include "internal.h"
 
 #ifndef MG_TAIL_SIXTEENTHS
-#define MG_TAIL_SIXTEENTHS 4   // share (in 1/16) of the last K-step that runs behind the per-tile barrier
+#define MG_TAIL_SIXTEENTHS 8   // share (in 1/16) of the last K-step that runs behind the per-tile barrier
 #endif
 
 namespace mg {
@@ -143,6 +143,26 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
     __device__ static inline int lds_offset(int r, int c) { return r * RS + ((c ^ ((r ^ (r >> 3)) & 7)) << 4); }
 
     u32x4 regs[COUNT];
+    // fast path: byte offset of each piece from the tile's first element, fixed for the whole kernel, so that a
+    // load is "uniform tile base + 32-bit lane offset" and costs no address arithmetic inside the K loop
+    uint32_t goff[EDGE ? 1 : COUNT];
+
+    __device__ inline void prepare(int64_t ld_)
+    {
+        if constexpr (!EDGE) {
+            const int t = threadIdx.x;
+            static_for<COUNT>([&](auto Qc) {
+                constexpr int Q = decltype(Qc)::value;
+                if constexpr (KCONTIG) {
+                    const int idx = t + Q * NT;
+                    goff[Q] = static_cast<uint32_t>(((idx / CPR) * ld_ + (idx % CPR) * CH) * sizeof(T));
+                } else {
+                    const int idx = t + (Q / CH) * NT;
+                    goff[Q] = static_cast<uint32_t>(((idx % RCH) * CH + ((idx / RCH) * CH + Q % CH) * ld_) * sizeof(T));
+                }
+            });
+        }
+    }
 
     // Tile position for the loads that follow.  rows_left / k_left: rows / k values from (r0, l0) on that
     // are inside the matrix (used by EDGE only); vec_ok: 16-byte loads are allowed.
@@ -170,7 +190,7 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
             if (PARTIAL && idx >= CHUNKS) return;
             const T *p = base + r * ld + c * CH;
             if constexpr (!EDGE) {
-                regs[Q] = *reinterpret_cast<const u32x4 *>(p);
+                regs[Q] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(base) + goff[Q]);
             } else {
                 const int kv = k_left - c * CH;
                 if (r >= rows_left || kv <= 0) regs[Q] = u32x4{0u, 0u, 0u, 0u};
@@ -185,7 +205,7 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
             if (PARTIAL && idx >= BLOCKS) return;
             const T *p = base + mc * CH + (kc * CH + j) * ld;
             if constexpr (!EDGE) {
-                regs[Q] = *reinterpret_cast<const u32x4 *>(p);
+                regs[Q] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(base) + goff[Q]);
             } else {
                 const int rv = rows_left - mc * CH;
                 if (kc * CH + j >= k_left || rv <= 0) regs[Q] = u32x4{0u, 0u, 0u, 0u};
@@ -281,7 +301,8 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
     static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % (4 * CH) == 0 && KSTEPS >= 2, "tile shape");
     using LoadA = TileLoader<T, BM, BK, NT, A_KCONTIG, EDGE>;
     using LoadB = TileLoader<T, BN, BK, NT, B_KCONTIG, EDGE>;
-    constexpr int STAGE = LoadA::LDS_BYTES + LoadB::LDS_BYTES;
+    // LDS: [A stage 0][A stage 1][B stage 0][B stage 1]; stage offsets are compile-time in the unrolled K loop
+    constexpr int A_BYTES = LoadA::LDS_BYTES, B_BYTES = LoadB::LDS_BYTES;
     constexpr int SLOTS = FM * FN;                      // MFMA groups per K-step
     constexpr int FRAGS = FM + FN;
     constexpr int PIECES = LoadA::COUNT + LoadB::COUNT;
@@ -318,7 +339,7 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
 #pragma unroll
     for (int kx = 0; kx < 4; ++kx) {
         frag_a[kx] = (wm * WTM + lr) * 128 + (xa ^ (32 * kx));
-        frag_b[kx] = LoadA::LDS_BYTES + (wn * WTN + lr) * 128 + (xb ^ (32 * kx));
+        frag_b[kx] = 2 * A_BYTES + (wn * WTN + lr) * 128 + (xb ^ (32 * kx));
     }
 
     floatx16 acc[FN][FM];
@@ -340,26 +361,21 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
         la.aim(A, args.lda, m0, l0, rows_a, ke - l0, vec_a);
         lb.aim(B, args.ldb, n0, l0, rows_b, ke - l0, vec_b);
     };
+    la.prepare(args.lda);
+    lb.prepare(args.ldb);
 
     u32x4 fa[2][FM], fb[2][FN];
-    // fragment F of K-step s: F < FM -> A fragment F, else B fragment F - FM
-    auto read_frag = [&](auto F, const char *stage, int s, int buf) {
-        constexpr int f = decltype(F)::value;
+    // fragment F of K-step s in LDS stage `par`: F < FM -> A fragment F, else B fragment F - FM
+    auto read_frag = [&](auto F, auto PAR, int s, int buf) {
+        constexpr int f = decltype(F)::value, par = decltype(PAR)::value;
         if constexpr (f < FM)
-            fa[buf][f] = *reinterpret_cast<const u32x4 *>(stage + frag_a[(s ^ (2 * (f & 1))) & 3] + f * 32 * 128);
+            fa[buf][f] = *reinterpret_cast<const u32x4 *>(lds + frag_a[(s ^ (2 * (f & 1))) & 3] + f * 32 * 128 + par * A_BYTES);
         else
-            fb[buf][f - FM] = *reinterpret_cast<const u32x4 *>(stage + frag_b[(s ^ (2 * ((f - FM) & 1))) & 3] +
-                                                               (f - FM) * 32 * 128);
+            fb[buf][f - FM] = *reinterpret_cast<const u32x4 *>(lds + frag_b[(s ^ (2 * ((f - FM) & 1))) & 3] +
+                                                               (f - FM) * 32 * 128 + par * B_BYTES);
     };
-    auto load_piece = [&](auto P) {
-        constexpr int p = decltype(P)::value;
-        if constexpr (p < LoadA::COUNT) la.template load_one<p>(); else lb.template load_one<p - LoadA::COUNT>();
-    };
-    auto store_piece = [&](auto P, char *stage) {
-        constexpr int p = decltype(P)::value;
-        if constexpr (p < LoadA::COUNT) la.template store_one<p>(stage);
-        else lb.template store_one<p - LoadA::COUNT>(stage + LoadA::LDS_BYTES);
-    };
+    using Stage0 = std::integral_constant<int, 0>;
+    using Stage1 = std::integral_constant<int, 1>;
 
     if (ktiles > 0) {
         // prologue: tile 0 -> LDS buffer 0, tile 1 -> registers, first fragments -> registers
@@ -367,72 +383,93 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
         la.load_all();
         lb.load_all();
         la.store_all(lds);
-        lb.store_all(lds + LoadA::LDS_BYTES);
+        lb.store_all(lds + 2 * A_BYTES);
         aim_tile(1);
         la.load_all();
         lb.load_all();
         __syncthreads();
-        static_for<FRAGS>([&](auto F) { read_frag(F, lds, 0, 0); });
+        static_for<FRAGS>([&](auto F) { read_frag(F, Stage0{}, 0, 0); });
     }
 
-    // Event e of an operand's loader: the store of a staged piece (tile t+1) or its reload (tile t+2).
-    // Row-wise loader: store 0, load 0, store 1, load 1, ...; transposing loader: the CH stores of a block
-    // (each needs all CH registers of the block), then its CH loads.
+    // Event e of an operand's loader: the store of a staged piece (tile t+1) or its reload (tile t+2), in
+    // groups: the stores of a few pieces, then their reloads.  Transposing loader: a group is a CH x CH block
+    // (each store needs all CH registers of the block).
     constexpr int EV_A = 2 * LoadA::COUNT, EVENTS = 2 * PIECES;
     // the last TAIL slots of the K-tile come behind the barrier and carry no staging traffic
     constexpr int TAIL = (SLOTS * MG_TAIL_SIXTEENTHS / 16) > 0 ? (SLOTS * MG_TAIL_SIXTEENTHS / 16) : 1;
     constexpr int EVENT_SLOTS = KSTEPS * SLOTS - TAIL;
-    auto run_event = [&](auto E, char *stage) {
-        constexpr int e = decltype(E)::value;
+    constexpr int READ_SLOTS = SLOTS >= 4 ? SLOTS * 3 / 4 : SLOTS;           // slots of a step that issue LDS reads
+    constexpr int TAIL_READ_SLOTS = TAIL >= 4 ? TAIL * 3 / 4 : TAIL;
+    auto run_event = [&](auto E, auto PAR) {              // PAR: the LDS stage the stores go to
+        constexpr int e = decltype(E)::value, par = decltype(PAR)::value;
         constexpr bool is_a = e < EV_A;
         constexpr int le = is_a ? e : e - EV_A;
         constexpr bool kcontig = is_a ? A_KCONTIG : B_KCONTIG;
-        constexpr bool is_load = kcontig ? (le & 1) : (le % (2 * CH) >= CH);
-        constexpr int piece = kcontig ? (le >> 1) : (le / (2 * CH)) * CH + (le % CH);
+        constexpr int count = is_a ? LoadA::COUNT : LoadB::COUNT;
+        // group size of the row-wise loader: GK stores (youngest piece first, so that the one wait in front
+        // of the first store covers the whole group: loads return in order), then the GK reloads
+        constexpr int GK = kcontig ? (count % 4 == 0 ? 4 : (count % 2 == 0 ? 2 : 1)) : CH;
+        constexpr int w = le % (2 * GK);
+        constexpr bool is_load = w >= GK;
+        constexpr int piece = (le / (2 * GK)) * GK + (is_load ? w - GK : (kcontig ? GK - 1 - w : w));
         if constexpr (is_a) {
-            if constexpr (is_load) la.template load_one<piece>(); else la.template store_one<piece>(stage);
+            if constexpr (is_load) la.template load_one<piece>();
+            else la.template store_one<piece>(lds + par * A_BYTES);
         } else {
             if constexpr (is_load) lb.template load_one<piece>();
-            else lb.template store_one<piece>(stage + LoadA::LDS_BYTES);
+            else lb.template store_one<piece>(lds + 2 * A_BYTES + par * B_BYTES);
         }
     };
 
-    for (int t = 0; t < ktiles; ++t) {
-        const char *cur = lds + (t & 1) * STAGE;
-        char *nxt = lds + ((t + 1) & 1) * STAGE;
+    // One K-tile.  CUR: the LDS stage the MFMAs read (compile time, the K loop being unrolled by two, so that
+    // every LDS address is a loop-invariant register plus an immediate); the other stage receives tile t+1.
+    auto tile_body = [&](auto CUR, int t) {
+        using Cur = decltype(CUR);
+        using Nxt = std::integral_constant<int, 1 - Cur::value>;
         aim_tile(t + 2);
         static_for<KSTEPS>([&](auto S) {
             constexpr int s = decltype(S)::value;
             static_for<SLOTS>([&](auto Q) {
                 constexpr int q = decltype(Q)::value;
                 constexpr int g = s * SLOTS + q;                 // slot number inside the K-tile
-                if constexpr (g == EVENT_SLOTS) __syncthreads();  // tile t+1 is complete in `nxt`
+                if constexpr (g == EVENT_SLOTS) __syncthreads();  // tile t+1 is complete in the other stage
                 mma(acc[q / FM][q % FM], fb[s & 1][q / FM], fa[s & 1][q % FM], T{});
+                // LDS reads of the next K-step: issued during the first READ_SLOTS slots, A fragments first and
+                // B fragments last-to-first, so that the first MFMA of the next step (which uses B fragment 0)
+                // waits once for the youngest read and every later MFMA of that step finds its operands ready
                 if constexpr (s + 1 < KSTEPS) {
-                    // this slot's share of the LDS reads for the next K-step
-                    static_for<share_begin(q + 1, FRAGS, SLOTS) - share_begin(q, FRAGS, SLOTS)>([&](auto R) {
-                        constexpr int f = share_begin(q, FRAGS, SLOTS) + decltype(R)::value;
-                        read_frag(std::integral_constant<int, f>{}, cur, s + 1, (s + 1) & 1);
-                    });
-                } else if constexpr (g >= EVENT_SLOTS) {
+                    if constexpr (q < READ_SLOTS)
+                        static_for<share_begin(q + 1, FRAGS, READ_SLOTS) - share_begin(q, FRAGS, READ_SLOTS)>([&](auto R) {
+                            constexpr int o = share_begin(q, FRAGS, READ_SLOTS) + decltype(R)::value;
+                            constexpr int f = o < FM ? o : FM + (FRAGS - 1 - o);
+                            read_frag(std::integral_constant<int, f>{}, Cur{}, s + 1, (s + 1) & 1);
+                        });
+                } else if constexpr (g >= EVENT_SLOTS && g - EVENT_SLOTS < TAIL_READ_SLOTS) {
                     // behind the barrier: the first fragments of the next tile
                     constexpr int h = g - EVENT_SLOTS;
-                    static_for<share_begin(h + 1, FRAGS, TAIL) - share_begin(h, FRAGS, TAIL)>([&](auto R) {
-                        constexpr int f = share_begin(h, FRAGS, TAIL) + decltype(R)::value;
-                        read_frag(std::integral_constant<int, f>{}, nxt, 0, 0);
+                    static_for<share_begin(h + 1, FRAGS, TAIL_READ_SLOTS) - share_begin(h, FRAGS, TAIL_READ_SLOTS)>([&](auto R) {
+                        constexpr int o = share_begin(h, FRAGS, TAIL_READ_SLOTS) + decltype(R)::value;
+                        constexpr int f = o < FM ? o : FM + (FRAGS - 1 - o);
+                        read_frag(std::integral_constant<int, f>{}, Nxt{}, 0, 0);
                     });
                 }
-                // this slot's share of the staging traffic: registers (tile t+1) -> other LDS buffer, global
+                // this slot's share of the staging traffic: registers (tile t+1) -> other LDS stage, global
                 // memory (tile t+2) -> the same registers
                 if constexpr (g < EVENT_SLOTS) {
                     static_for<share_begin(g + 1, EVENTS, EVENT_SLOTS) - share_begin(g, EVENTS, EVENT_SLOTS)>([&](auto R) {
-                        run_event(std::integral_constant<int, share_begin(g, EVENTS, EVENT_SLOTS) + decltype(R)::value>{}, nxt);
+                        run_event(std::integral_constant<int, share_begin(g, EVENTS, EVENT_SLOTS) + decltype(R)::value>{}, Nxt{});
                     });
                 }
                 if constexpr (!EDGE) __builtin_amdgcn_sched_barrier(0);
             });
         });
+    };
+    int t = 0;
+    for (; t + 1 < ktiles; t += 2) {
+        tile_body(Stage0{}, t);
+        tile_body(Stage1{}, t + 1);
     }
+    if (t < ktiles) tile_body(Stage0{}, t);
 
     // ---- epilogue.  Per 32-column block j of the wavefront's tile: accumulators -> this wavefront's own LDS
     // region as [column][m] floats (16-byte writes of the four consecutive m a lane holds), then every lane
