@@ -143,9 +143,11 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
     __device__ static inline int lds_offset(int r, int c) { return r * RS + ((c ^ ((r ^ (r >> 3)) & 7)) << 4); }
 
     u32x4 regs[COUNT];
-    // fast path: byte offset of each piece from the tile's first element, fixed for the whole kernel, so that a
-    // load is "uniform tile base + 32-bit lane offset" and costs no address arithmetic inside the K loop
+    // fast path: byte offset of each piece from the tile's first element, fixed for the whole kernel; a load is
+    // a buffer load "tile descriptor (scalar registers) + 32-bit lane offset" and costs no vector arithmetic
+    // inside the K loop
     uint32_t goff[EDGE ? 1 : COUNT];
+    __amdgpu_buffer_rsrc_t rsrc;
 
     __device__ inline void prepare(int64_t ld_)
     {
@@ -175,6 +177,9 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
                                bool vec_ok_)
     {
         base = KCONTIG ? X + r0 * ld_ + l0 : X + r0 + l0 * ld_;
+        // raw buffer descriptor over the tile (no stride, no effective range limit: the fast path is in bounds
+        // by construction; 0x00020000 = untyped 32-bit data format of this GPU family)
+        if constexpr (!EDGE) rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(base), 0, 0x7fffffff, 0x00020000);
         ld = ld_;
         rows_left = rows_left_;
         k_left = k_left_;
@@ -190,7 +195,7 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
             if (PARTIAL && idx >= CHUNKS) return;
             const T *p = base + r * ld + c * CH;
             if constexpr (!EDGE) {
-                regs[Q] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(base) + goff[Q]);
+                regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
             } else {
                 const int kv = k_left - c * CH;
                 if (r >= rows_left || kv <= 0) regs[Q] = u32x4{0u, 0u, 0u, 0u};
@@ -205,7 +210,7 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
             if (PARTIAL && idx >= BLOCKS) return;
             const T *p = base + mc * CH + (kc * CH + j) * ld;
             if constexpr (!EDGE) {
-                regs[Q] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(base) + goff[Q]);
+                regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
             } else {
                 const int rv = rows_left - mc * CH;
                 if (kc * CH + j >= k_left || rv <= 0) regs[Q] = u32x4{0u, 0u, 0u, 0u};
