@@ -1,0 +1,261 @@
+// FP16 macro-tile GEMM kernel for gfx950 whose operand tiles go from global memory straight into LDS
+// (buffer loads with the LDS modifier): no staging registers, no LDS store instructions.  Whole tiles and
+// 16-byte aligned operands only; everything else runs on the register-staged kernel of mfma_kernel.h, whose
+// work-group tile / wavefront tile / K-step structure (the parameterised gemm kernel of the paper's
+// Section 3.2), rasterisation and epilogue this kernel shares.
+//
+// A direct-to-LDS load writes, per wavefront instruction, 64 x 16 bytes to consecutive LDS addresses (base in
+// M0 + immediate offset + lane * 16) while every lane names its own global address; the immediate offset is
+// added on both sides.  Any permutation of 16-byte chunks inside such a 1 KB block is therefore made on the
+// global side, by choosing which chunk a lane fetches.
+//
+// LDS layout per operand and stage (ROWS x 64 halves = ROWS * 128 bytes), by the operand's memory order:
+//   * contiguous along k: [row][k], 128 bytes per row, chunk c of row r at slot c ^ ((r ^ r/8) % 8) -- the
+//     layout of the register-staged kernel; an MFMA operand is one 16-byte read per lane;
+//   * contiguous along its row index (m for A, n for B): [k][row] as in memory, 2 * ROWS bytes per k, the
+//     16-byte chunk c of line k at slot c ^ (2 * (k % 4)); an MFMA operand is two transposing 8-byte reads
+//     (ds_read_b64_tr_b16): in each group of 16 lanes, lane 4a + b receives element b of what lanes a, a + 4,
+//     a + 8, a + 12 fetched, so when those four lanes fetch the same four rows at four consecutive k, lane
+//     4a + b ends up with four consecutive k of row 4a + b.  The swizzle puts the four k lines of a group into
+//     four different 32-byte bank ranges.
+// Both forms give lane l the eight k values 16 s + 8 (l / 32) + 0..7 of row l % 32 in K-step s.
+//
+// Pipeline: two LDS stages.  During K-tile t (read from stage t % 2) the loads of tile t + 1 into the other
+// stage are issued in the first slots; every wavefront waits for its own loads just before the single barrier
+// of the tile, which sits inside the last K-step: at that point every wavefront has finished reading stage
+// t % 2 (the operands of the last step are in registers), so the loads of tile t + 2 may overwrite it right
+// after the barrier, and the first fragments of tile t + 1 are read behind the barrier while MFMAs still run.
+#pragma once
+
+#include "mfma_kernel.h"
+
+#ifndef MG_DMA_SPACING
+#define MG_DMA_SPACING 1   // one direct-to-LDS load every this many slots from the start of a K-tile
+#endif
+
+namespace mg {
+
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef short shortx8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) char lds_char;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
+
+// One operand tile (ROWS rows x 64 k, FP16): global -> LDS.  A wavefront owns COUNT consecutive 1 KB blocks.
+template <int ROWS, int NT, bool KCONTIG> struct DmaLoader {
+    static constexpr int LDS_BYTES = ROWS * 128;
+    static constexpr int COUNT = LDS_BYTES / (NT * 16);
+    static_assert(COUNT >= 1 && COUNT * NT * 16 == LDS_BYTES && (COUNT % 4 == 0 || COUNT < 4), "tile / work-group size");
+    static constexpr int imm(int q) { return (q % 4) * 1024; }      // the 12-bit immediate reaches four blocks
+
+    uint32_t goff[COUNT];      // lane's global byte offset inside the tile, less the immediate
+    __amdgpu_buffer_rsrc_t rsrc;
+
+    __device__ inline void prepare(int64_t ld, int wave, int lane)
+    {
+        static_for<COUNT>([&](auto Qc) {
+            constexpr int Q = decltype(Qc)::value;
+            const int o = (wave * COUNT + Q) * 1024 + lane * 16;       // LDS byte offset inside the operand stage
+            int64_t g;
+            if constexpr (KCONTIG) {
+                const int r = o / 128, slot = (o / 16) % 8;
+                g = r * ld * 2 + ((slot ^ ((r ^ (r >> 3)) & 7)) << 4);
+            } else {
+                const int kl = o / (2 * ROWS), slot = (o / 16) % (ROWS / 8);
+                g = kl * ld * 2 + ((slot ^ (2 * (kl & 3))) << 4);
+            }
+            goff[Q] = static_cast<uint32_t>(g - imm(Q));
+        });
+    }
+
+    __device__ inline void aim(const _Float16 *X, int64_t ld, int64_t r0, int64_t l0)
+    {
+        const _Float16 *base = KCONTIG ? X + r0 * ld + l0 : X + r0 + l0 * ld;
+        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16 *>(base), 0, 0x7fffffff, 0x00020000);
+    }
+
+    // mine: this wavefront's first block in the destination stage (wave-uniform)
+    template <int Q> __device__ inline void issue(lds_char *mine) const
+    {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, reinterpret_cast<lds_void *>(mine + (Q / 4) * 4096), 16, goff[Q], 0,
+                                                 imm(Q), 0);
+    }
+};
+
+// MFMA operand of fragment F (32 rows), K-step s, from an operand stage at byte offset `stage`; frag: the
+// lane's addresses prepared by the kernel (four for the k-contiguous layout, two for the other)
+template <bool KCONTIG, int ROWS, int F, int RB>
+__device__ inline u32x4 read_operand(lds_char *lds3, const int (&frag)[4], int s, int stage)
+{
+    if constexpr (KCONTIG) {
+        return *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(
+            lds3 + frag[frag_select<RB>(F, s)] + F * RB * 128 + stage);
+    } else {
+        static_assert(RB == 32, "the transposing reads are laid out for 32-row fragments");
+        constexpr int LINE = 2 * ROWS;                                    // bytes per k line
+        lds_char *at = lds3 + frag[F & 1] + (F >> 1) * 128 + s * (16 * LINE) + stage;
+        const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_shortx4 *>(at));
+        const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_shortx4 *>(at + 4 * LINE));
+        return __builtin_bit_cast(u32x4, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    }
+}
+
+template <int BM, int BN, int WM, int WN, bool A_KCONTIG, bool B_KCONTIG, int RB = 32>
+__global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs args)
+{
+#if defined(__HIP_DEVICE_COMPILE__)      // the host pass needs the kernel's symbol only (LDS address-space code is device code)
+    using T = _Float16;
+    constexpr int BK = 64, NT = WM * WN * 64;
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    constexpr int FM = WTM / RB, FN = WTN / RB;
+    constexpr int KSTEPS = BK / ((64 / RB) * 8);
+    static_assert(WTM % 64 == 0 && WTN % 64 == 0, "wavefront tile: an even number of 32-row fragments per side");
+    using LoadA = DmaLoader<BM, NT, A_KCONTIG>;
+    using LoadB = DmaLoader<BN, NT, B_KCONTIG>;
+    constexpr int A_BYTES = LoadA::LDS_BYTES, B_BYTES = LoadB::LDS_BYTES;   // LDS: [A stage 0][A stage 1][B stage 0][B stage 1]
+    constexpr int SLOTS = FM * FN, FRAGS = FM + FN;
+    constexpr int PIECES = LoadA::COUNT + LoadB::COUNT;
+
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    lds_char *const lds3 = (lds_char *)lds;
+
+    int tm, tn;
+    tile_coords(blockIdx.x, args.tiles_m, args.tiles_n, args.group_m, tm, tn);
+    const int64_t m0 = static_cast<int64_t>(tm) * BM, n0 = static_cast<int64_t>(tn) * BN;
+    const int kb = blockIdx.z * args.k_per_split;
+    const int ke = (kb + args.k_per_split < args.k) ? kb + args.k_per_split : args.k;
+    const T *__restrict__ A = static_cast<const T *>(args.A);
+    const T *__restrict__ B = static_cast<const T *>(args.B);
+
+    const int lane = threadIdx.x % 64;
+    const int wave = threadIdx.x / 64;
+    const int wm = wave % WM, wn = wave / WM;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+
+    // ---- fragment addresses (bytes from the start of the LDS, stage 0); see the layouts above
+    int frag_a[4], frag_b[4];          // k-contiguous form: four addresses cover every (fragment, step); else [0], [1]
+    auto frag_setup = [&](bool kcontig, int wrow, int operand_base, int rows, int (&frag)[4]) {
+        if (kcontig) {
+            const int x = frag_lane_x<RB>(lane, wrow);
+            for (int kx = 0; kx < 4; ++kx) frag[kx] = operand_base + (wrow + lane % RB) * 128 + (x ^ (32 * kx));
+        } else {
+            // fetch role inside the group of 16 lanes: rows 4a .. 4a+3 of the group's 16 rows, k line j
+            const int i = lane % 16, a = i % 4, j = i / 4, g = lane / 16;
+            const int kl = 8 * (g / 2) + j;                                   // + 16 s + 4 h
+            const int slot = (wrow / 8 + 2 * (g % 2) + a / 2) ^ (2 * j);     // + 4 f by XOR: f odd flips byte bit 6
+            const int p = operand_base + kl * (2 * rows) + slot * 16 + 8 * (a % 2);
+            frag[0] = p;
+            frag[1] = p ^ 64;
+            frag[2] = frag[3] = 0;
+        }
+    };
+    frag_setup(A_KCONTIG, wm * WTM, 0, BM, frag_a);
+    frag_setup(B_KCONTIG, wn * WTN, 2 * A_BYTES, BN, frag_b);
+
+    using Acc = typename BlockAcc<RB>::type;
+    Acc acc[FN][FM];
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int r = 0; r < static_cast<int>(sizeof(Acc) / 4); ++r) acc[j][i][r] = 0.f;
+
+    LoadA la;
+    LoadB lb;
+    la.prepare(args.lda, wave, lane);
+    lb.prepare(args.ldb, wave, lane);
+    const int ktiles = (ke - kb) / BK;
+    auto aim_tile = [&](int t) {
+        int l0 = kb + t * BK;
+        l0 = l0 < ke ? l0 : ke - BK;            // past the end: reload the last tile into a stage nobody reads
+        la.aim(A, args.lda, m0, l0);
+        lb.aim(B, args.ldb, n0, l0);
+    };
+    lds_char *const mine_a = lds3 + wave_u * (LoadA::COUNT * 1024);
+    lds_char *const mine_b = lds3 + 2 * A_BYTES + wave_u * (LoadB::COUNT * 1024);
+    auto issue_piece = [&](auto P, auto PAR) {          // piece P of the tile aimed at, into stage PAR
+        constexpr int p = decltype(P)::value, par = decltype(PAR)::value;
+        if constexpr (p < LoadA::COUNT) {
+            la.template issue<p>(mine_a + par * A_BYTES);
+        } else {
+            constexpr int pb = p - LoadA::COUNT;
+            lb.template issue<pb>(mine_b + par * B_BYTES);
+        }
+    };
+    auto wait_loads = [] { __builtin_amdgcn_s_waitcnt(0x0F70); };    // vmcnt(0): this wavefront's loads are in LDS
+
+    u32x4 fa[2][FM], fb[2][FN];
+    // fragment F of K-step s in stage `par`: F < FM -> A fragment F, else B fragment F - FM
+    auto read_frag = [&](auto F, auto PAR, int s, int buf) {
+        constexpr int f = decltype(F)::value, par = decltype(PAR)::value;
+        if constexpr (f < FM) fa[buf][f] = read_operand<A_KCONTIG, BM, f, RB>(lds3, frag_a, s, par * A_BYTES);
+        else fb[buf][f - FM] = read_operand<B_KCONTIG, BN, f - FM, RB>(lds3, frag_b, s, par * B_BYTES);
+    };
+    using Stage0 = std::integral_constant<int, 0>;
+    using Stage1 = std::integral_constant<int, 1>;
+
+    if (ktiles > 0) {
+        aim_tile(0);
+        static_for<PIECES>([&](auto P) { issue_piece(P, Stage0{}); });
+        wait_loads();
+        __syncthreads();
+        static_for<FRAGS>([&](auto F) { read_frag(F, Stage0{}, 0, 0); });
+    }
+
+    constexpr int TAIL = (SLOTS * MG_TAIL_SIXTEENTHS / 16) > 0 ? (SLOTS * MG_TAIL_SIXTEENTHS / 16) : 1;
+    constexpr int BARRIER_SLOT = KSTEPS * SLOTS - TAIL;
+    constexpr int READ_SLOTS = SLOTS >= 4 ? SLOTS * 3 / 4 : SLOTS;
+    constexpr int TAIL_READ_SLOTS = TAIL >= 4 ? TAIL * 3 / 4 : TAIL;
+    static_assert(PIECES * MG_DMA_SPACING <= BARRIER_SLOT, "loads must be issued before the barrier");
+
+    auto tile_body = [&](auto CUR, int t) {
+        using Cur = decltype(CUR);
+        using Nxt = std::integral_constant<int, 1 - Cur::value>;
+        aim_tile(t + 1);
+        static_for<KSTEPS>([&](auto S) {
+            constexpr int s = decltype(S)::value;
+            static_for<SLOTS>([&](auto Q) {
+                constexpr int q = decltype(Q)::value;
+                constexpr int g = s * SLOTS + q;
+                if constexpr (g == BARRIER_SLOT) {
+                    wait_loads();
+                    __syncthreads();                     // tile t+1 is complete in the other stage
+                }
+                mma(acc[q / FM][q % FM], fb[s & 1][q / FM], fa[s & 1][q % FM], T{});
+                if constexpr (s + 1 < KSTEPS) {
+                    if constexpr (q < READ_SLOTS)
+                        static_for<share_begin(q + 1, FRAGS, READ_SLOTS) - share_begin(q, FRAGS, READ_SLOTS)>([&](auto R) {
+                            constexpr int o = share_begin(q, FRAGS, READ_SLOTS) + decltype(R)::value;
+                            constexpr int f = o < FM ? o : FM + (FRAGS - 1 - o);
+                            read_frag(std::integral_constant<int, f>{}, Cur{}, s + 1, (s + 1) & 1);
+                        });
+                } else if constexpr (g >= BARRIER_SLOT && g - BARRIER_SLOT < TAIL_READ_SLOTS) {
+                    constexpr int h = g - BARRIER_SLOT;
+                    static_for<share_begin(h + 1, FRAGS, TAIL_READ_SLOTS) - share_begin(h, FRAGS, TAIL_READ_SLOTS)>([&](auto R) {
+                        constexpr int o = share_begin(h, FRAGS, TAIL_READ_SLOTS) + decltype(R)::value;
+                        constexpr int f = o < FM ? o : FM + (FRAGS - 1 - o);
+                        read_frag(std::integral_constant<int, f>{}, Nxt{}, 0, 0);
+                    });
+                }
+                if constexpr (g % MG_DMA_SPACING == 0 && g / MG_DMA_SPACING < PIECES)
+                    issue_piece(std::integral_constant<int, g / MG_DMA_SPACING>{}, Nxt{});
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+    };
+    int t = 0;
+    for (; t + 1 < ktiles; t += 2) {
+        tile_body(Stage0{}, t);
+        tile_body(Stage1{}, t + 1);
+    }
+    if (t < ktiles) tile_body(Stage0{}, t);
+
+    __syncthreads();        // all loads have landed (waited for before the last barrier) and all fragment reads are done
+    tile_epilogue<T, RB, FM, FN, WTM, WTN, false>(acc, args, lds, m0, n0, wm, wn, wave, lane);
+#else
+    (void)args;
+#endif
+}
+
+}  // namespace mg

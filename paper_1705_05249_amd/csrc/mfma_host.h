@@ -5,7 +5,7 @@
 
 namespace mg {
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, bool AK, bool BKC, bool EDGE> struct MfmaConfig {
+template <typename T, int BM, int BN, int BK, int WM, int WN, bool AK, bool BKC, bool EDGE, int RB = 32> struct MfmaConfig {
     static constexpr int CH = ElemTraits<T>::CH;
     static constexpr int NT = WM * WN * 64;
     static constexpr int STAGES_LDS = 2 * (BM + BN) * 128;                    // two operand stages
@@ -48,7 +48,7 @@ template <typename T, int BM, int BN, int BK, int WM, int WN, bool AK, bool BKC,
     static hipError_t launch(const Problem &p, int split)
     {
         static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; races are harmless
-        auto kernel = mfma_gemm_kernel<T, BM, BN, BK, WM, WN, AK, BKC, EDGE>;
+        auto kernel = mfma_gemm_kernel<T, BM, BN, BK, WM, WN, AK, BKC, EDGE, RB>;
         if (!attr_set) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -102,5 +102,12 @@ template <typename T, int BM, int BN, int BK, int WM, int WN, bool AK, bool BKC,
     table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, true, true, true>::entry(tag "_kk_edge"));                   \
     table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, false, false, true>::entry(tag "_mn_edge"));                 \
     table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, true, false, true>::entry(tag "_kn_edge"));
+
+// The fast flavours of an FP16 tile shape built on 16x16 MFMA blocks (names: hmfma16_...).
+#define MG_MFMA16_REGISTER(table, tag, BM, BN, BK, WM, WN)                                                         \
+    table.push_back(MfmaConfig<_Float16, BM, BN, BK, WM, WN, false, true, false, 16>::entry(tag "_mk"));           \
+    table.push_back(MfmaConfig<_Float16, BM, BN, BK, WM, WN, true, true, false, 16>::entry(tag "_kk"));            \
+    table.push_back(MfmaConfig<_Float16, BM, BN, BK, WM, WN, false, false, false, 16>::entry(tag "_mn"));          \
+    table.push_back(MfmaConfig<_Float16, BM, BN, BK, WM, WN, true, false, false, 16>::entry(tag "_kn"));
 
 }  // namespace mg

@@ -29,9 +29,10 @@
 //     those quads, then 16/32-byte reads along m), so that C is read (beta != 0) and written in
 //     16-byte pieces per lane that form whole contiguous column segments per instruction.
 //
-// Within one K-step the lanes of an operand fragment cover 2*CH values of k: lane group g
-// (= lane / 32) holds the CH values of chunk 2*step + g.  Both operands use the same mapping,
-// and a sum over k does not care about the order, so no further shuffling is needed.
+// Within one K-step the lanes of an operand fragment of RB rows cover 64 / RB chunks of CH values of k: lane
+// l holds row l % RB, chunk (64 / RB) * step + l / RB.  Both operands use the same mapping, and a sum over k
+// does not care about the order, so no further shuffling is needed.  RB = 32 (32x32 MFMA blocks) everywhere
+// except the FP16 variants built on 16x16x32 blocks.
 #pragma once
 
 #include <type_traits>
@@ -266,6 +267,34 @@ __device__ inline void mma(floatx16 &acc, const u32x4 &frag_n, const u32x4 &frag
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
 }
 
+// FP16 with 16x16 output blocks (v_mfma_f32_16x16x32_f16): register r of lane l is C(m, n) with n = l % 16 and
+// m = 4*(l/16) + r; a fragment is 16 rows x 32 k (lane l: row l % 16, the 8 k values of chunk l / 16).
+__device__ inline void mma(floatx4 &acc, const u32x4 &frag_n, const u32x4 &frag_m, _Float16)
+{
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(halfx8, frag_m),
+                                                 __builtin_bit_cast(halfx8, frag_n), acc, 0, 0, 0);
+}
+
+// ---- MFMA block shape RB x RB (32, or 16 for FP16) ---------------------------------------------------
+// A fragment covers RB rows and 64 / RB chunks of k (one K-step); lane l reads row l % RB, chunk l / RB.
+template <int RB> struct BlockAcc;
+template <> struct BlockAcc<32> { using type = floatx16; };
+template <> struct BlockAcc<16> { using type = floatx4; };
+
+// Fragment f of K-step s: row = wrow + RB f + l % RB, logical chunk (64/RB) s + l / RB.  With the swizzle the
+// chunk's byte offset inside the row is frag_lane_x ^ (32 * frag_select): the first is per lane, the second
+// takes four values only, so four addresses per operand cover every fragment (the rest is an immediate
+// offset of f * RB rows).  wrow: first row of the wavefront's tile, a multiple of its power-of-two height.
+template <int RB> __device__ inline int frag_lane_x(int lane, int wrow)
+{
+    const int lr = lane % RB;
+    return ((lane / RB) ^ (lr & 7) ^ (lr >> 3) ^ ((wrow >> 3) & 7)) << 4;
+}
+template <int RB> constexpr int frag_select(int f, int s)
+{
+    return RB == 32 ? ((s ^ (2 * (f & 1))) & 3) : (((2 * s) ^ (f & 3)) & 3);
+}
+
 // N elements at element alignment
 template <typename U, int N> struct __attribute__((packed, aligned(sizeof(U)))) Pack {
     U v[N];
@@ -295,15 +324,129 @@ __device__ inline void tile_coords(int wg, int tiles_m, int tiles_n, int group_m
 // first of `total` items that falls into slot `slot` of `slots` when spread evenly
 constexpr int share_begin(int slot, int total, int slots) { return slot * total / slots; }
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, bool A_KCONTIG, bool B_KCONTIG, bool EDGE>
+// ---- epilogue of one work-group tile --------------------------------------------------------------
+// Per 32-column block j of the wavefront's tile: accumulators -> this wavefront's own LDS region as
+// [column][m] floats (16-byte writes of the four consecutive m a lane holds), then every lane reads
+// PER = 16 / sizeof(output element) consecutive m of one column and handles them as one 16-byte piece of C
+// (or of the split-K partial sums).  A wavefront instruction thus covers whole contiguous column segments.
+// Only this wavefront touches its region and the LDS executes a wavefront's operations in order, so the
+// two phases need no barrier, only a fence that keeps the compiler from moving one lane's reads across
+// the writes other lanes depend on.  The caller has made sure that nobody still uses the LDS.
+template <typename T, int RB, int FM, int FN, int WTM, int WTN, bool EDGE>
+__device__ inline void tile_epilogue(typename BlockAcc<RB>::type (&acc)[FN][FM], const MfmaArgs &args, char *lds,
+                                     int64_t m0, int64_t n0, int wm, int wn, int wave, int lane)
+{
+    constexpr int NBLK = WTN / 32;                     // 32-column blocks of the wavefront tile
+    const int wm_u = __builtin_amdgcn_readfirstlane(wm), wn_u = __builtin_amdgcn_readfirstlane(wn);
+    const int64_t gm0 = m0 + wm_u * WTM, gn0 = n0 + wn_u * WTN;     // wave-uniform corner of the wavefront tile
+    const float alpha = args.alpha, beta = args.beta;
+    constexpr int ROWB = WTM * 4 + 16;                 // staging row stride in bytes (16 lanes x 16 B hit all banks)
+    char *region = lds + __builtin_amdgcn_readfirstlane(wave) * (32 * ROWB);
+    const int ln = lane % 32, lg = lane / 32;
+
+    auto wave_fence = [] {
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
+    auto stage_block = [&](int j) {
+        wave_fence();
+        if constexpr (RB == 32) {
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const floatx4 v = {acc[j][i][4 * q], acc[j][i][4 * q + 1], acc[j][i][4 * q + 2], acc[j][i][4 * q + 3]};
+                    *reinterpret_cast<floatx4 *>(region + ln * ROWB + (i * 32 + 8 * q + 4 * lg) * 4) = v;
+                }
+        } else {
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+                    *reinterpret_cast<floatx4 *>(region + (16 * jj + lane % 16) * ROWB + (i * 16 + 4 * (lane / 16)) * 4) =
+                        acc[2 * j + jj][i];
+        }
+        wave_fence();
+    };
+    // U: output element type (T for C, float for partial sums); emit(pointer to PER elements, values, valid count)
+    auto drain_block = [&](auto *base, int64_t ld, int j, auto &&emit) {
+        using U = std::remove_pointer_t<decltype(base)>;
+        constexpr int PER = 16 / static_cast<int>(sizeof(U));
+        constexpr int CPRW = WTM / PER;                // pieces per column
+        constexpr int COLS = 64 / CPRW;                // columns per wavefront instruction
+        static_assert(CPRW <= 64 && 64 % CPRW == 0, "wavefront tile rows");
+        const int c = lane % CPRW, r0 = lane / CPRW;
+#pragma unroll
+        for (int pass = 0; pass < 32 / COLS; ++pass) {
+            const int r = r0 + pass * COLS;            // column inside the 32-column block
+            const int64_t gn = gn0 + j * 32 + r, gm = gm0 + c * PER;
+            int valid = PER;
+            if constexpr (EDGE) {
+                const int64_t left = args.m - gm;
+                valid = gn >= args.n ? 0 : (left >= PER ? PER : (left > 0 ? static_cast<int>(left) : 0));
+            }
+            float v[PER];
+#pragma unroll
+            for (int h = 0; h < PER / 4; ++h) {
+                const floatx4 x = *reinterpret_cast<const floatx4 *>(region + r * ROWB + (c * PER + 4 * h) * 4);
+                v[4 * h] = x.x; v[4 * h + 1] = x.y; v[4 * h + 2] = x.z; v[4 * h + 3] = x.w;
+            }
+            if (valid > 0) emit(base + gm + gn * ld, v, valid);
+        }
+    };
+
+    if (args.partial != nullptr) {
+        float *base = args.partial + static_cast<int64_t>(blockIdx.z) * args.n * args.m;
+#pragma unroll
+        for (int j = 0; j < NBLK; ++j) {
+            stage_block(j);
+            drain_block(base, static_cast<int64_t>(args.m), j, [](float *p, const float (&v)[4], int valid) {
+                if (valid == 4) *reinterpret_cast<Pack<float, 4> *>(p) = Pack<float, 4>{{v[0], v[1], v[2], v[3]}};
+                else for (int e = 0; e < valid; ++e) p[e] = v[e];
+            });
+        }
+    } else {
+        constexpr int PER = 16 / static_cast<int>(sizeof(T));
+        T *base = static_cast<T *>(args.C);
+        auto emit = [alpha, beta](T *p, const float (&v)[PER], int valid) {
+            if (valid == PER) {
+                Pack<T, PER> o;
+                if (beta != 0.f) {
+                    const Pack<T, PER> c = *reinterpret_cast<const Pack<T, PER> *>(p);
+#pragma unroll
+                    for (int e = 0; e < PER; ++e) o.v[e] = static_cast<T>(fmaf(beta, static_cast<float>(c.v[e]), alpha * v[e]));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < PER; ++e) o.v[e] = static_cast<T>(alpha * v[e]);
+                }
+                *reinterpret_cast<Pack<T, PER> *>(p) = o;
+            } else {
+                for (int e = 0; e < valid; ++e) {
+                    float o = alpha * v[e];
+                    if (beta != 0.f) o = fmaf(beta, load_as_float(p + e), o);
+                    store_from_float(p + e, o);
+                }
+            }
+        };
+#pragma unroll
+        for (int j = 0; j < NBLK; ++j) {
+            stage_block(j);
+            drain_block(base, args.ldc, j, emit);
+        }
+    }
+}
+
+template <typename T, int BM, int BN, int BK, int WM, int WN, bool A_KCONTIG, bool B_KCONTIG, bool EDGE, int RB = 32>
 __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs args)
 {
     constexpr int NT = WM * WN * 64;
     constexpr int WTM = BM / WM, WTN = BN / WN;        // wavefront tile
-    constexpr int FM = WTM / 32, FN = WTN / 32;        // 32x32 accumulators per wavefront
+    constexpr int FM = WTM / RB, FN = WTN / RB;        // RB x RB accumulators per wavefront
     constexpr int CH = ElemTraits<T>::CH;
-    constexpr int KSTEPS = BK / (2 * CH);
-    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % (4 * CH) == 0 && KSTEPS >= 2, "tile shape");
+    constexpr int KSTEPS = BK / ((64 / RB) * CH);      // a K-step: one 16-byte fragment per lane and operand
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % ((128 / RB) * CH) == 0 && KSTEPS >= 2, "tile shape");
+    static_assert(RB == 32 || (RB == 16 && sizeof(T) == 2 && WTM % 64 == 0 && WTN % 64 == 0), "MFMA block shape");
+    static_assert((WTM & (WTM - 1)) == 0 && (WTN & (WTN - 1)) == 0, "wavefront tile sides are powers of two");
     using LoadA = TileLoader<T, BM, BK, NT, A_KCONTIG, EDGE>;
     using LoadB = TileLoader<T, BN, BK, NT, B_KCONTIG, EDGE>;
     // LDS: [A stage 0][A stage 1][B stage 0][B stage 1]; stage offsets are compile-time in the unrolled K loop
@@ -333,27 +476,24 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
     const int lane = threadIdx.x % 64;
     const int wave = threadIdx.x / 64;
     const int wm = wave % WM, wn = wave / WM;
-    // Fragment f of K-step s: row = wave row + 32 f + lane % 32, logical chunk 2 s + lane / 32.  With the
-    // swizzle, the chunk's byte offset inside the row is (x ^ K): x is per lane, and K = 32 s ^ 64 (f & 1)
-    // takes four values only, so four addresses per operand cover every fragment (the rest is an
-    // immediate offset of f * 32 rows).
-    const int lr = lane % 32;
-    const int xa = ((lane / 32) ^ (lr & 7) ^ (lr >> 3) ^ (4 * ((wm * FM) & 1))) << 4;
-    const int xb = ((lane / 32) ^ (lr & 7) ^ (lr >> 3) ^ (4 * ((wn * FN) & 1))) << 4;
     int frag_a[4], frag_b[4];
+    {
+        const int xa = frag_lane_x<RB>(lane, wm * WTM), xb = frag_lane_x<RB>(lane, wn * WTN);
 #pragma unroll
-    for (int kx = 0; kx < 4; ++kx) {
-        frag_a[kx] = (wm * WTM + lr) * 128 + (xa ^ (32 * kx));
-        frag_b[kx] = 2 * A_BYTES + (wn * WTN + lr) * 128 + (xb ^ (32 * kx));
+        for (int kx = 0; kx < 4; ++kx) {
+            frag_a[kx] = (wm * WTM + lane % RB) * 128 + (xa ^ (32 * kx));
+            frag_b[kx] = 2 * A_BYTES + (wn * WTN + lane % RB) * 128 + (xb ^ (32 * kx));
+        }
     }
 
-    floatx16 acc[FN][FM];
+    using Acc = typename BlockAcc<RB>::type;
+    Acc acc[FN][FM];
 #pragma unroll
     for (int j = 0; j < FN; ++j)
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
+            for (int r = 0; r < static_cast<int>(sizeof(Acc) / 4); ++r) acc[j][i][r] = 0.f;
 
     LoadA la;
     LoadB lb;
@@ -374,10 +514,10 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
     auto read_frag = [&](auto F, auto PAR, int s, int buf) {
         constexpr int f = decltype(F)::value, par = decltype(PAR)::value;
         if constexpr (f < FM)
-            fa[buf][f] = *reinterpret_cast<const u32x4 *>(lds + frag_a[(s ^ (2 * (f & 1))) & 3] + f * 32 * 128 + par * A_BYTES);
+            fa[buf][f] = *reinterpret_cast<const u32x4 *>(lds + frag_a[frag_select<RB>(f, s)] + f * RB * 128 + par * A_BYTES);
         else
-            fb[buf][f - FM] = *reinterpret_cast<const u32x4 *>(lds + frag_b[(s ^ (2 * ((f - FM) & 1))) & 3] +
-                                                               (f - FM) * 32 * 128 + par * B_BYTES);
+            fb[buf][f - FM] = *reinterpret_cast<const u32x4 *>(lds + frag_b[frag_select<RB>(f - FM, s)] +
+                                                               (f - FM) * RB * 128 + par * B_BYTES);
     };
     using Stage0 = std::integral_constant<int, 0>;
     using Stage1 = std::integral_constant<int, 1>;
@@ -476,102 +616,8 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
     }
     if (t < ktiles) tile_body(Stage0{}, t);
 
-    // ---- epilogue.  Per 32-column block j of the wavefront's tile: accumulators -> this wavefront's own LDS
-    // region as [column][m] floats (16-byte writes of the four consecutive m a lane holds), then every lane
-    // reads PER = 16 / sizeof(output element) consecutive m of one column and handles them as one 16-byte
-    // piece of C (or of the split-K partial sums).  A wavefront instruction thus covers whole contiguous
-    // column segments.  Only this wavefront touches its region and the LDS executes a wavefront's operations
-    // in order, so the two phases need no barrier, only a fence that keeps the compiler from moving one
-    // lane's reads across the writes other lanes depend on.
     __syncthreads();                                   // every wavefront is done reading the operand stages
-    const int wm_u = __builtin_amdgcn_readfirstlane(wm), wn_u = __builtin_amdgcn_readfirstlane(wn);
-    const int64_t gm0 = m0 + wm_u * WTM, gn0 = n0 + wn_u * WTN;     // wave-uniform corner of the wavefront tile
-    const float alpha = args.alpha, beta = args.beta;
-    constexpr int ROWB = WTM * 4 + 16;                 // staging row stride in bytes (16 lanes x 16 B hit all banks)
-    char *region = lds + __builtin_amdgcn_readfirstlane(wave) * (32 * ROWB);
-    const int ln = lane % 32, lg = lane / 32;
-
-    auto wave_fence = [] {
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-    };
-    auto stage_block = [&](int j) {
-        wave_fence();
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const floatx4 v = {acc[j][i][4 * q], acc[j][i][4 * q + 1], acc[j][i][4 * q + 2], acc[j][i][4 * q + 3]};
-                *reinterpret_cast<floatx4 *>(region + ln * ROWB + (i * 32 + 8 * q + 4 * lg) * 4) = v;
-            }
-        wave_fence();
-    };
-    // U: output element type (T for C, float for partial sums); emit(pointer to PER elements, values, valid count)
-    auto drain_block = [&](auto *base, int64_t ld, int j, auto &&emit) {
-        using U = std::remove_pointer_t<decltype(base)>;
-        constexpr int PER = 16 / static_cast<int>(sizeof(U));
-        constexpr int CPRW = WTM / PER;                // pieces per column
-        constexpr int COLS = 64 / CPRW;                // columns per wavefront instruction
-        static_assert(CPRW <= 64 && 64 % CPRW == 0, "wavefront tile rows");
-        const int c = lane % CPRW, r0 = lane / CPRW;
-#pragma unroll
-        for (int pass = 0; pass < 32 / COLS; ++pass) {
-            const int r = r0 + pass * COLS;            // column inside the 32-column block
-            const int64_t gn = gn0 + j * 32 + r, gm = gm0 + c * PER;
-            int valid = PER;
-            if constexpr (EDGE) {
-                const int64_t left = args.m - gm;
-                valid = gn >= args.n ? 0 : (left >= PER ? PER : (left > 0 ? static_cast<int>(left) : 0));
-            }
-            float v[PER];
-#pragma unroll
-            for (int h = 0; h < PER / 4; ++h) {
-                const floatx4 x = *reinterpret_cast<const floatx4 *>(region + r * ROWB + (c * PER + 4 * h) * 4);
-                v[4 * h] = x.x; v[4 * h + 1] = x.y; v[4 * h + 2] = x.z; v[4 * h + 3] = x.w;
-            }
-            if (valid > 0) emit(base + gm + gn * ld, v, valid);
-        }
-    };
-
-    if (args.partial != nullptr) {
-        float *base = args.partial + static_cast<int64_t>(blockIdx.z) * args.n * args.m;
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            stage_block(j);
-            drain_block(base, static_cast<int64_t>(args.m), j, [](float *p, const float (&v)[4], int valid) {
-                if (valid == 4) *reinterpret_cast<Pack<float, 4> *>(p) = Pack<float, 4>{{v[0], v[1], v[2], v[3]}};
-                else for (int e = 0; e < valid; ++e) p[e] = v[e];
-            });
-        }
-    } else {
-        constexpr int PER = 16 / static_cast<int>(sizeof(T));
-        T *base = static_cast<T *>(args.C);
-        auto emit = [alpha, beta](T *p, const float (&v)[PER], int valid) {
-            if (valid == PER) {
-                Pack<T, PER> o;
-                if (beta != 0.f) {
-                    const Pack<T, PER> c = *reinterpret_cast<const Pack<T, PER> *>(p);
-#pragma unroll
-                    for (int e = 0; e < PER; ++e) o.v[e] = static_cast<T>(fmaf(beta, static_cast<float>(c.v[e]), alpha * v[e]));
-                } else {
-#pragma unroll
-                    for (int e = 0; e < PER; ++e) o.v[e] = static_cast<T>(alpha * v[e]);
-                }
-                *reinterpret_cast<Pack<T, PER> *>(p) = o;
-            } else {
-                for (int e = 0; e < valid; ++e) {
-                    float o = alpha * v[e];
-                    if (beta != 0.f) o = fmaf(beta, load_as_float(p + e), o);
-                    store_from_float(p + e, o);
-                }
-            }
-        };
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            stage_block(j);
-            drain_block(base, args.ldc, j, emit);
-        }
-    }
+    tile_epilogue<T, RB, FM, FN, WTM, WTN, EDGE>(acc, args, lds, m0, n0, wm, wn, wave, lane);
 }
 
 // C <- alpha * sum_z partial[z] + beta * C   (finishes a split-K product)

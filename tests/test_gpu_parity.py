@@ -342,6 +342,26 @@ def test_every_kernel_configuration_gives_parity(G, oracle, dtype):
     assert not never, f"kernels never exercised: {never}"
 
 
+@pytest.mark.parametrize("shape", [(256, 256, 64), (256, 512, 128), (768, 256, 448), (512, 512, 1024)])
+def test_direct_to_lds_kernels(G, oracle, shape):
+    """every direct-to-LDS kernel, all operand orders: one K-tile, an odd number of K-tiles, several tiles of C;
+    bit-exact on integers (beta = 1) and within tolerance on random data"""
+    m, n, k = shape
+    names = [t["name"] for t in G.kernel_table() if t["name"].startswith("hdma")]
+    assert names
+    orders = {"mk": (N, N), "kk": (T, N), "mn": (N, T), "kn": (T, T)}
+    try:
+        for name in names:
+            ta, tb = orders[name.rsplit("_", 1)[1]]
+            for integer in (True, False):
+                case = W.hgemm_case(m, n, k, case=7, ta=ta, tb=tb, beta=1.0 if integer else 0.0, integer=integer)
+                G.mg_override_config(G.kernel_id(name), 1)
+                announce(name, case.name, "integer" if integer else "random")
+                H.check_case(case, oracle)
+    finally:
+        G.mg_clear_override()
+
+
 def test_every_batched_configuration_gives_parity(G, oracle):
     kernels = [t for t in G.kernel_table() if t["family"] == G.MG_FAMILY_BATCHED]
     ran = {t["name"]: 0 for t in kernels}
