@@ -44,7 +44,7 @@ struct TileChoice {
 constexpr int kComputeUnits = 256;
 
 // Split-K factor for a grid of `blocks` work-groups that each walk `ktiles` K-tiles.  From the sweep:
-// a handful of blocks should be split until every compute unit has one (when K has >= 16 tiles and each
+// a handful of blocks should be split until every compute unit has two (when K has >= 16 tiles and each
 // slice keeps >= 4 of them); a grid that fills the chip less than four times over gains from splitting only when K
 // is long (each slice keeps >= 24 K-tiles), because the reduce pass costs a launch and a round trip of
 // the partial sums; otherwise no split.
@@ -52,7 +52,7 @@ int pick_split(int64_t blocks, int64_t ktiles)
 {
     int64_t split = 1;
     if (blocks <= 64 && ktiles >= 16) {
-        split = ceil_div(kComputeUnits, blocks);
+        split = ceil_div(2 * kComputeUnits, blocks);
         if (split > ktiles / 4) split = ktiles / 4;
     } else if (blocks < 4 * kComputeUnits && ktiles >= 48) {
         split = ceil_div(4 * kComputeUnits, blocks);
