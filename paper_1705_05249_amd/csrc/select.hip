@@ -98,9 +98,9 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
             // split-K needs the caller's workspace: without enough of it, run unsplit
             while (want > 1 && static_cast<size_t>(want) * p.m * p.n * sizeof(float) > workspace_bytes) want = 1;
             // FP16 with both operands contiguous along k and whole 256 x 256 tiles: the direct-to-LDS kernel with
-            // two wavefronts per SIMD measured fastest
+            // two wavefronts per SIMD and 16x16x32 MFMA blocks measured fastest
             if (!f32 && i == 0 && p.a_trans && !p.b_trans &&
-                try_pick(table, p, alignment, "hdma_256x256x64_w2x4_kk", want, kernel, split))
+                try_pick(table, p, alignment, "hdma16_256x256x64_w2x4_kk", want, kernel, split))
                 return;
             if (try_mfma(table, p, alignment, tiles[i].tag, want, kernel, split)) return;
             if (want > 1 && try_mfma(table, p, alignment, tiles[i].tag, 1, kernel, split)) return;
