@@ -39,22 +39,7 @@
 #define ORA_NO_TRANS 111
 #define ORA_TRANS 112
 
-/* IEEE binary16 bit pattern -> double, by fields (no half arithmetic anywhere). */
-static double half_bits_to_double(uint16_t h)
-{
-    int sign = (h >> 15) & 1;
-    int expo = (h >> 10) & 0x1f;
-    int frac = h & 0x3ff;
-    double v;
-    if (expo == 0) {
-        v = ldexp((double)frac, -24);              /* zero and subnormals: frac * 2^-24 */
-    } else if (expo == 31) {
-        v = frac ? NAN : INFINITY;
-    } else {
-        v = ldexp((double)(1024 + frac), expo - 25); /* (1 + frac/1024) * 2^(expo-15) */
-    }
-    return sign ? -v : v;
-}
+#include "half_bits.h"
 
 static inline double load_f32(const void *base, size_t at) { return (double)((const float *)base)[at]; }
 static inline double load_f16(const void *base, size_t at) { return half_bits_to_double(((const uint16_t *)base)[at]); }
