@@ -109,7 +109,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
-    ap.add_argument("--only", default=None, help="hgemm | sgemm | batched | copy: run a single workload (profiling runs)")
+    ap.add_argument("--only", default=None, help="hgemm | sgemm | batched | conv | copy: run a single workload (profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -196,6 +196,30 @@ def main():
                                        "frac": round(gbs / PEAK_HBM_GBS, 4),
                                        "traffic": MEASURED_TRAFFIC_BYTES.get("batched_16x10000") if scalar_bytes else None},
                           "note": note})
+
+    # ---- next row: convolution as IM2COL + GEMM on the layers whose GEMMs are the FP16 shapes of the metric's
+    # workload list; microsecond-scale, so graph-timed like the batched calls
+    if args.only in (None, "conv"):
+        for index in range(len(W.CONV_LAYERS)):
+            cc = W.conv_layer(index, "f16")
+            geo = (cc.channels, cc.height, cc.width, cc.kernel, cc.pad, cc.stride, cc.dilation)
+            im, wt, out = H.to_gpu(cc.im), H.to_gpu(cc.weights), H.to_gpu(cc.out)
+            oh, ow = cc.out_hw
+            col = torch.empty(cc.k * oh * ow, dtype=torch.float16, device="cuda")
+            ws = torch.empty(max(G.mg_conv2d_workspace_bytes(G.MG_F16, *geo, cc.filters), 256), dtype=torch.uint8, device="cuda")
+            t_unfold, _ = graph_timed(lambda: G.mg_him2col(*geo, im, col), col, steps, warmup)
+            t_conv, t_conv_eager = graph_timed(lambda: G.mg_hconv2d(*geo, cc.filters, 1.0, im, wt, 0.0, out, ws), out,
+                                               steps, warmup)
+            unfold_bytes = 2 * (cc.k * oh * ow + cc.channels * cc.height * cc.width)
+            gbs = unfold_bytes / t_unfold / 1e9
+            flops = 2.0 * cc.filters * oh * ow * cc.k
+            extra.append({"workload": f"hconv2d_f16_c{cc.channels}_{cc.height}x{cc.width}_k{cc.kernel[0]}_s{cc.stride[0]}_f{cc.filters}"
+                                      f" (GEMM {cc.filters}x{oh * ow}x{cc.k})",
+                          "gflops": round(flops / t_conv / 1e9, 1), "ms": round(t_conv * 1e3, 5),
+                          "ms_eager_launches": round(t_conv_eager * 1e3, 5), "ms_im2col": round(t_unfold * 1e3, 5),
+                          "roofline_im2col": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                              "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None},
+                          "note": "graph-timed; working set of a few MB, served by the last-level cache"})
 
     if head is None:
         print(json.dumps({"workloads": extra}))

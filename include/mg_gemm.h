@@ -62,7 +62,8 @@ enum {
     MG_ERR_CONFIG = -11,      /* unknown kernel id, or configuration illegal for this call  */
     MG_ERR_LAUNCH = -12,      /* the HIP runtime refused the launch (see hipGetLastError)   */
     MG_ERR_NO_DEVICE = -13,   /* no usable gfx950 device / HIP runtime error before launch  */
-    MG_ERR_STRIDE = -14       /* a batch stride is negative                                 */
+    MG_ERR_STRIDE = -14,      /* a batch stride is negative                                 */
+    MG_ERR_CONV = -15         /* convolution geometry: an extent < 1, a pad < 0, stride or dilation < 1 */
 };
 
 typedef enum { MG_ROW_MAJOR = 101, MG_COL_MAJOR = 102 } mg_layout;
@@ -145,6 +146,46 @@ mg_status mg_sgemm_strided_batched(int layout, int trans_a, int trans_b, int64_t
 size_t mg_gemm_workspace_bytes(int dtype, int layout, int trans_a, int trans_b,
                                int64_t m, int64_t n, int64_t k,
                                int64_t lda, int64_t ldb, int64_t ldc);
+
+/* ---- IM2COL and convolution as GEMM ----------------------------------------------------
+ * The paper lists IM2COL among its extra routines (Section 3.1, routine table) and motivates
+ * GEMM by the convolution layers that can be expressed with it (Section 1, Section 6); it
+ * gives no formula.  Used here: the cross-correlation of neural networks (the filter is not
+ * flipped) of ONE image with zero padding, stride and dilation per direction.  All arrays are
+ * dense and row-major: im[channels][height][width], weights[filters][channels][kernel_h]
+ * [kernel_w], out[filters][OH][OW], col[K][OH*OW] with K = channels*kernel_h*kernel_w and
+ *     OH = (height + 2*pad_h - dilation_h*(kernel_h-1) - 1) / stride_h + 1   (0 if negative; OW likewise)
+ *     col[(c*kernel_h + kh)*kernel_w + kw][oh*OW + ow] = im[c][oh*stride_h - pad_h + kh*dilation_h]
+ *                                                          [ow*stride_w - pad_w + kw*dilation_w]   or 0 outside
+ *     out = alpha * weights (filters x K) * col (K x OH*OW) + beta * out
+ * with the GEMM conventions above (FP32 accumulation, one rounding, beta == 0: out not read,
+ * alpha == 0: im and weights not read).  Errors: MG_ERR_CONV for an extent < 1 (channels,
+ * height, width, kernel), a negative pad, a stride or dilation < 1 or filters < 0; MG_ERR_DIM
+ * when the column matrix has 2^31 or more elements; MG_ERR_NULL; MG_ERR_WORKSPACE.  An empty
+ * output (OH, OW or filters zero) returns MG_OK without launching anything. */
+#define MG_CONV_GEOMETRY                                                                       \
+    int64_t channels, int64_t height, int64_t width, int64_t kernel_h, int64_t kernel_w,     \
+    int64_t pad_h, int64_t pad_w, int64_t stride_h, int64_t stride_w,                         \
+    int64_t dilation_h, int64_t dilation_w
+
+/* Writes the K x OH*OW column matrix.  im and col must not overlap. */
+mg_status mg_sim2col(MG_CONV_GEOMETRY, const float *im, float *col, void *stream);
+mg_status mg_him2col(MG_CONV_GEOMETRY, const uint16_t *im, uint16_t *col, void *stream);
+
+/* Convolution = IM2COL into the workspace, then the GEMM of this library on it.  The
+ * workspace (device, 256-byte aligned) must hold mg_conv2d_workspace_bytes(); a 1x1 filter
+ * with unit stride and no padding needs no column matrix (the image is the matrix). */
+mg_status mg_sconv2d(MG_CONV_GEOMETRY, int64_t filters, float alpha, const float *im,
+                     const float *weights, float beta, float *out,
+                     void *workspace, size_t workspace_bytes, void *stream);
+mg_status mg_hconv2d(MG_CONV_GEOMETRY, int64_t filters, float alpha, const uint16_t *im,
+                     const uint16_t *weights, float beta, uint16_t *out,
+                     void *workspace, size_t workspace_bytes, void *stream);
+/* Column matrix (rounded up to 256 bytes) plus what the GEMM's configuration needs; 0 for
+ * invalid arguments or an empty output.  dtype is an mg_dtype. */
+size_t mg_conv2d_workspace_bytes(int dtype, MG_CONV_GEOMETRY, int64_t filters);
+/* OH (or OW) of the formula above; -1 for invalid arguments. */
+int64_t mg_conv2d_out_extent(int64_t size, int64_t kernel, int64_t pad, int64_t stride, int64_t dilation);
 
 /* ---- configuration table, selection and override (paper Section 3.3) ------------------
  * Every compiled kernel is result-neutral: any legal configuration gives the same result up

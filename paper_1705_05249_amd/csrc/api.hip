@@ -167,6 +167,71 @@ mg_status run_batched(BatchedProblem &p, int layout, int ta, int tb, int64_t m, 
     return t[kernel].launch_batched(p) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
 }
 
+
+// Checks a convolution geometry; fills the output extents and K = channels * kernel_h * kernel_w.
+mg_status check_conv(const ConvShape &s, int64_t filters, int64_t *out_h, int64_t *out_w, int64_t *k)
+{
+    if (s.channels < 1 || s.height < 1 || s.width < 1 || s.kernel_h < 1 || s.kernel_w < 1 || s.pad_h < 0 ||
+        s.pad_w < 0 || s.stride_h < 1 || s.stride_w < 1 || s.dilation_h < 1 || s.dilation_w < 1 || filters < 0)
+        return MG_ERR_CONV;
+    const int64_t lim = int64_t(1) << 31;
+    if (s.channels >= lim || s.height >= lim || s.width >= lim || s.kernel_h >= lim || s.kernel_w >= lim ||
+        s.pad_h >= lim || s.pad_w >= lim || s.stride_h >= lim || s.stride_w >= lim || s.dilation_h >= lim ||
+        s.dilation_w >= lim || filters >= lim)
+        return MG_ERR_DIM;
+    *out_h = conv_out_extent(s.height, s.kernel_h, s.pad_h, s.stride_h, s.dilation_h);
+    *out_w = conv_out_extent(s.width, s.kernel_w, s.pad_w, s.stride_w, s.dilation_w);
+    const __int128 kk = __int128(s.channels) * s.kernel_h * s.kernel_w;
+    const __int128 total = kk * *out_h * *out_w;
+    if (kk >= lim || total >= lim || __int128(s.channels) * s.height * s.width >= (__int128(1) << 40)) return MG_ERR_DIM;
+    *k = static_cast<int64_t>(kk);
+    return MG_OK;
+}
+
+// a 1x1 filter with unit stride and no padding: the column matrix is the image itself
+bool conv_is_plain_gemm(const ConvShape &s)
+{
+    return s.kernel_h == 1 && s.kernel_w == 1 && s.pad_h == 0 && s.pad_w == 0 && s.stride_h == 1 && s.stride_w == 1;
+}
+
+size_t round_up_256(size_t v) { return (v + 255) / 256 * 256; }
+
+mg_status run_im2col(int dtype, const ConvShape &s, const void *im, void *col, void *stream)
+{
+    int64_t out_h, out_w, k;
+    mg_status st = check_conv(s, 0, &out_h, &out_w, &k);
+    if (st != MG_OK) return st;
+    if (out_h == 0 || out_w == 0) return MG_OK;
+    if (im == nullptr || col == nullptr) return MG_ERR_NULL;
+    return launch_im2col(dtype, s, im, col, static_cast<hipStream_t>(stream)) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
+}
+
+// out (filters x OH*OW) = alpha * weights (filters x K) * col (K x OH*OW) + beta * out, all row-major; the
+// column matrix sits at the start of the workspace, the GEMM's own scratch (split-K) behind it
+mg_status run_conv2d(int dtype, const ConvShape &s, int64_t filters, float alpha, const void *im, const void *weights,
+                     float beta, void *out, void *ws, size_t ws_bytes, void *stream)
+{
+    int64_t out_h, out_w, k;
+    mg_status st = check_conv(s, filters, &out_h, &out_w, &k);
+    if (st != MG_OK) return st;
+    const int64_t n = out_h * out_w;
+    if (filters == 0 || n == 0) return MG_OK;
+    if (out == nullptr || (alpha != 0.f && (im == nullptr || weights == nullptr))) return MG_ERR_NULL;
+    const size_t elem = dtype == MG_F32 ? 4 : 2;
+    const void *col = im;
+    size_t col_bytes = 0;
+    if (alpha != 0.f && !conv_is_plain_gemm(s)) {
+        col_bytes = round_up_256(static_cast<size_t>(k) * n * elem);
+        if (ws == nullptr || pointer_alignment(ws) < 256 || ws_bytes < col_bytes) return MG_ERR_WORKSPACE;
+        if (launch_im2col(dtype, s, im, ws, static_cast<hipStream_t>(stream)) != hipSuccess) return MG_ERR_LAUNCH;
+        col = ws;
+    }
+    void *rest = ws == nullptr ? nullptr : static_cast<char *>(ws) + col_bytes;
+    const size_t rest_bytes = ws_bytes > col_bytes ? ws_bytes - col_bytes : 0;
+    return run_gemm(dtype, MG_ROW_MAJOR, MG_NO_TRANS, MG_NO_TRANS, filters, n, k, alpha, weights, k, col, n, beta, out,
+                    n, rest_bytes ? rest : nullptr, rest_bytes, stream);
+}
+
 }  // namespace
 }  // namespace mg
 
@@ -237,6 +302,51 @@ size_t mg_gemm_workspace_bytes(int dtype, int layout, int ta, int tb, int64_t m,
     int32_t kernel = -1, split = 1;
     if (choose(p, 256, ~size_t(0), &kernel, &split) != MG_OK) return 0;
     return table()[kernel].workspace(p, split);
+}
+
+#define MG_CONV_SHAPE_ARGS                                                                                      \
+    int64_t channels, int64_t height, int64_t width, int64_t kernel_h, int64_t kernel_w, int64_t pad_h,          \
+        int64_t pad_w, int64_t stride_h, int64_t stride_w, int64_t dilation_h, int64_t dilation_w
+#define MG_CONV_SHAPE                                                                                           \
+    ConvShape { channels, height, width, kernel_h, kernel_w, pad_h, pad_w, stride_h, stride_w, dilation_h, dilation_w }
+
+mg_status mg_sim2col(MG_CONV_SHAPE_ARGS, const float *im, float *col, void *stream)
+{
+    return run_im2col(MG_F32, MG_CONV_SHAPE, im, col, stream);
+}
+
+mg_status mg_him2col(MG_CONV_SHAPE_ARGS, const uint16_t *im, uint16_t *col, void *stream)
+{
+    return run_im2col(MG_F16, MG_CONV_SHAPE, im, col, stream);
+}
+
+mg_status mg_sconv2d(MG_CONV_SHAPE_ARGS, int64_t filters, float alpha, const float *im, const float *weights,
+                     float beta, float *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_conv2d(MG_F32, MG_CONV_SHAPE, filters, alpha, im, weights, beta, out, workspace, workspace_bytes, stream);
+}
+
+mg_status mg_hconv2d(MG_CONV_SHAPE_ARGS, int64_t filters, float alpha, const uint16_t *im, const uint16_t *weights,
+                     float beta, uint16_t *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_conv2d(MG_F16, MG_CONV_SHAPE, filters, alpha, im, weights, beta, out, workspace, workspace_bytes, stream);
+}
+
+size_t mg_conv2d_workspace_bytes(int dtype, MG_CONV_SHAPE_ARGS, int64_t filters)
+{
+    if (dtype != MG_F32 && dtype != MG_F16) return 0;
+    const ConvShape s = MG_CONV_SHAPE;
+    int64_t out_h, out_w, k;
+    if (check_conv(s, filters, &out_h, &out_w, &k) != MG_OK || filters == 0 || out_h * out_w == 0) return 0;
+    const int64_t n = out_h * out_w;
+    const size_t col = conv_is_plain_gemm(s) ? 0 : round_up_256(static_cast<size_t>(k) * n * (dtype == MG_F32 ? 4 : 2));
+    return col + mg_gemm_workspace_bytes(dtype, MG_ROW_MAJOR, MG_NO_TRANS, MG_NO_TRANS, filters, n, k, k, n, n);
+}
+
+int64_t mg_conv2d_out_extent(int64_t size, int64_t kernel, int64_t pad, int64_t stride, int64_t dilation)
+{
+    if (size < 1 || kernel < 1 || pad < 0 || stride < 1 || dilation < 1) return -1;
+    return conv_out_extent(size, kernel, pad, stride, dilation);
 }
 
 int32_t mg_kernel_count(void) { return static_cast<int32_t>(table().size()); }
@@ -318,10 +428,11 @@ const char *mg_status_string(mg_status status)
         case MG_ERR_LAUNCH: return "kernel launch failed";
         case MG_ERR_NO_DEVICE: return "no usable device";
         case MG_ERR_STRIDE: return "negative batch stride";
+        case MG_ERR_CONV: return "invalid convolution geometry";
         default: return "unknown status";
     }
 }
 
-const char *mg_version(void) { return "0.2"; }
+const char *mg_version(void) { return "0.3"; }
 
 }  // extern "C"

@@ -64,6 +64,15 @@ struct BatchedProblem {
     float alpha, beta;
 };
 
+// Geometry of a 2-D convolution of one image (all extents in elements).
+struct ConvShape {
+    int64_t channels, height, width, kernel_h, kernel_w, pad_h, pad_w, stride_h, stride_w, dilation_h, dilation_w;
+};
+// (size + 2 pad - dilation (kernel - 1) - 1) / stride + 1, or 0 when the filter does not fit
+int64_t conv_out_extent(int64_t size, int64_t kernel, int64_t pad, int64_t stride, int64_t dilation);
+// dtype: mg_dtype.  The column matrix must have fewer than 2^31 elements.
+hipError_t launch_im2col(int dtype, const ConvShape &s, const void *im, void *col, hipStream_t stream);
+
 // One compiled kernel (or kernel family instance) in the configuration table.
 struct KernelEntry {
     const char *name;

@@ -17,7 +17,9 @@ MG_F32, MG_F16 = 0, 1
 MG_OK = 0
 MG_FAMILY_DIRECT, MG_FAMILY_MFMA, MG_FAMILY_GEMV, MG_FAMILY_SCALE, MG_FAMILY_BATCHED = 0, 1, 2, 3, 4
 
-EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemm_batched", "mg_sgemm_strided_batched", "mg_gemm_workspace_bytes", "mg_kernel_count",
+EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemm_batched", "mg_sgemm_strided_batched", "mg_gemm_workspace_bytes",
+           "mg_sim2col", "mg_him2col", "mg_sconv2d", "mg_hconv2d", "mg_conv2d_workspace_bytes", "mg_conv2d_out_extent",
+           "mg_kernel_count",
            "mg_kernel_info", "mg_kernel_name", "mg_query_selected", "mg_override_config",
            "mg_override_batched_config", "mg_clear_override", "mg_status_string", "mg_version")
 
@@ -47,6 +49,13 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it first "
                                "(python -c 'import __graft_entry__ as g; g.build()')")
+        # PyTorch ships its own copy of the HIP runtime.  A process must talk to one runtime only (kernels are
+        # registered with the runtime the library was loaded against, streams and pointers come from torch's),
+        # so torch's copy is loaded first and the library binds to it.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(LIB_PATH)
         i32, i64, f32, vp, sz = ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
         gemm_args = [i32, i32, i32, i64, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64, vp, sz, vp]
@@ -62,6 +71,20 @@ def lib():
         L.mg_sgemm_strided_batched.restype = i32
         L.mg_gemm_workspace_bytes.argtypes = [i32, i32, i32, i32, i64, i64, i64, i64, i64, i64]
         L.mg_gemm_workspace_bytes.restype = sz
+        geometry = [i64] * 11
+        L.mg_sim2col.argtypes = geometry + [vp, vp, vp]
+        L.mg_sim2col.restype = i32
+        L.mg_him2col.argtypes = geometry + [vp, vp, vp]
+        L.mg_him2col.restype = i32
+        conv_args = geometry + [i64, f32, vp, vp, f32, vp, vp, sz, vp]
+        L.mg_sconv2d.argtypes = conv_args
+        L.mg_sconv2d.restype = i32
+        L.mg_hconv2d.argtypes = conv_args
+        L.mg_hconv2d.restype = i32
+        L.mg_conv2d_workspace_bytes.argtypes = [i32] + geometry + [i64]
+        L.mg_conv2d_workspace_bytes.restype = sz
+        L.mg_conv2d_out_extent.argtypes = [i64] * 5
+        L.mg_conv2d_out_extent.restype = i64
         L.mg_kernel_count.argtypes = []
         L.mg_kernel_count.restype = ctypes.c_int32
         L.mg_kernel_info.argtypes = [ctypes.c_int32, ctypes.POINTER(mg_config)]
@@ -147,6 +170,58 @@ def mg_sgemm_strided_batched(layout, trans_a, trans_b, m, n, k, alpha, A, lda, s
     if check and st != MG_OK:
         raise MgError(st, "mg_sgemm_strided_batched")
     return st
+
+
+def _geometry(channels, height, width, kernel, pad, stride, dilation):
+    return (channels, height, width, kernel[0], kernel[1], pad[0], pad[1], stride[0], stride[1], dilation[0], dilation[1])
+
+
+def _im2col(name, channels, height, width, kernel, pad, stride, dilation, im, col, stream, check):
+    st = getattr(lib(), name)(*_geometry(channels, height, width, kernel, pad, stride, dilation), _addr(im), _addr(col),
+                              _stream(stream))
+    if check and st != MG_OK:
+        raise MgError(st, name)
+    return st
+
+
+def mg_sim2col(channels, height, width, kernel, pad, stride, dilation, im, col, stream=None, check=True) -> int:
+    """kernel, pad, stride, dilation: (h, w) pairs"""
+    return _im2col("mg_sim2col", channels, height, width, kernel, pad, stride, dilation, im, col, stream, check)
+
+
+def mg_him2col(channels, height, width, kernel, pad, stride, dilation, im, col, stream=None, check=True) -> int:
+    return _im2col("mg_him2col", channels, height, width, kernel, pad, stride, dilation, im, col, stream, check)
+
+
+def _conv2d(name, channels, height, width, kernel, pad, stride, dilation, filters, alpha, im, weights, beta, out,
+            workspace, stream, check):
+    ws, ws_bytes = _ws(workspace)
+    st = getattr(lib(), name)(*_geometry(channels, height, width, kernel, pad, stride, dilation), filters, alpha,
+                              _addr(im), _addr(weights), beta, _addr(out), ws, ws_bytes, _stream(stream))
+    if check and st != MG_OK:
+        raise MgError(st, name)
+    return st
+
+
+def mg_sconv2d(channels, height, width, kernel, pad, stride, dilation, filters, alpha, im, weights, beta, out,
+               workspace=None, stream=None, check=True) -> int:
+    return _conv2d("mg_sconv2d", channels, height, width, kernel, pad, stride, dilation, filters, alpha, im, weights,
+                   beta, out, workspace, stream, check)
+
+
+def mg_hconv2d(channels, height, width, kernel, pad, stride, dilation, filters, alpha, im, weights, beta, out,
+               workspace=None, stream=None, check=True) -> int:
+    return _conv2d("mg_hconv2d", channels, height, width, kernel, pad, stride, dilation, filters, alpha, im, weights,
+                   beta, out, workspace, stream, check)
+
+
+def mg_conv2d_workspace_bytes(dtype, channels, height, width, kernel, pad, stride, dilation, filters) -> int:
+    return int(lib().mg_conv2d_workspace_bytes(dtype, *_geometry(channels, height, width, kernel, pad, stride, dilation),
+                                               filters))
+
+
+def mg_conv2d_out_extent(size, kernel, pad, stride, dilation) -> int:
+    return int(lib().mg_conv2d_out_extent(size, kernel, pad, stride, dilation))
 
 
 def mg_gemm_workspace_bytes(dtype, layout, trans_a, trans_b, m, n, k, lda, ldb, ldc) -> int:

@@ -222,6 +222,72 @@ def config2_like(size, layout, ta, tb, beta, seed_case=0, integer=False) -> Gemm
                      gen(g, (size, size)), 1.0, beta, exact=integer)
 
 
+# ----------------------------------------------------------------------------- convolutions
+
+@dataclass
+class ConvCase:
+    """one image, dense row-major arrays: im (C,H,W), weights (F,C,KH,KW), out (F,OH,OW) holding the old values"""
+    name: str
+    dtype: str
+    channels: int
+    height: int
+    width: int
+    kernel: tuple
+    pad: tuple
+    stride: tuple
+    dilation: tuple
+    filters: int
+    alpha: float
+    beta: float
+    im: np.ndarray
+    weights: np.ndarray
+    out: np.ndarray
+    exact: bool = False
+
+    @property
+    def out_hw(self):
+        return tuple(conv_out_extent(s, k, p, st, d) for s, k, p, st, d in
+                     zip((self.height, self.width), self.kernel, self.pad, self.stride, self.dilation))
+
+    @property
+    def k(self):
+        return self.channels * self.kernel[0] * self.kernel[1]
+
+
+def conv_out_extent(size, kernel, pad, stride, dilation) -> int:
+    span = size + 2 * pad - dilation * (kernel - 1) - 1
+    return 0 if span < 0 else span // stride + 1
+
+
+# the layers whose im2col GEMMs are the FP16 shapes of group 3: (C, H, W, kernel, pad, stride, filters)
+CONV_LAYERS = ((3, 224, 224, 7, 3, 2, 64), (64, 56, 56, 3, 1, 1, 128), (128, 28, 28, 3, 1, 1, 256),
+               (256, 14, 14, 3, 1, 1, 512))
+
+
+def conv_case(dtype, channels, height, width, kernel, pad, stride, dilation, filters, alpha=1.0, beta=0.0, case=0,
+              integer=False, name=None) -> ConvCase:
+    """entries N(0, K^-1/2) like group 3 (or small integers for bit-exact checks)"""
+    g = rng_for(6, case)
+    np_t = np.float32 if dtype == "f32" else np.float16
+    oh = conv_out_extent(height, kernel[0], pad[0], stride[0], dilation[0])
+    ow = conv_out_extent(width, kernel[1], pad[1], stride[1], dilation[1])
+    shapes = ((channels, height, width), (filters, channels, kernel[0], kernel[1]), (filters, oh, ow))
+    if integer:
+        im, w, out = (small_ints(g, s, 2, np_t) for s in shapes)
+    else:
+        sigma = float(channels * kernel[0] * kernel[1]) ** -0.5
+        im, w, out = (g.normal(0.0, sigma, size=s).astype(np.float32).astype(np_t) for s in shapes)
+    return ConvCase(name or f"conv_{dtype}_{channels}x{height}x{width}_k{kernel[0]}x{kernel[1]}_f{filters}", dtype,
+                    channels, height, width, tuple(kernel), tuple(pad), tuple(stride), tuple(dilation), filters, alpha,
+                    beta, im, w, out, integer)
+
+
+def conv_layer(index, dtype="f16", integer=False, beta=0.0) -> ConvCase:
+    c, h, w, k, p, s, f = CONV_LAYERS[index]
+    return conv_case(dtype, c, h, w, (k, k), (p, p), (s, s), (1, 1), f, 1.0, beta, case=index, integer=integer,
+                     name=f"layer{index}_{dtype}")
+
+
 # ----------------------------------------------------------------------------- group 3
 
 CONFIG3_SHAPES = ((64, 12544, 147), (128, 3136, 576), (256, 784, 1152), (512, 196, 2304), (4096, 4096, 4096))

@@ -121,3 +121,41 @@ def check_batched(bc, oracle, exact=False):
     err = rel_error(mats, c_ref, d_ref)
     assert err <= TOL["f32"], f"{bc.name}: relative error {err:.3e}"
     return err
+
+
+# ------------------------------------------------------------------ convolution (IM2COL + GEMM)
+
+def conv_geometry(case):
+    return (case.channels, case.height, case.width, case.kernel, case.pad, case.stride, case.dilation)
+
+
+def run_conv(case, workspace="auto"):
+    """Runs one ConvCase through mg_sconv2d / mg_hconv2d; returns out (filters, OH, OW) as numpy."""
+    import torch
+    from paper_1705_05249_amd import gemm as G
+    fn = G.mg_sconv2d if case.dtype == "f32" else G.mg_hconv2d
+    code = G.MG_F32 if case.dtype == "f32" else G.MG_F16
+    im, w, out = to_gpu(case.im), to_gpu(case.weights), to_gpu(case.out)
+    if isinstance(workspace, str):
+        need = G.mg_conv2d_workspace_bytes(code, *conv_geometry(case), case.filters)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda") if need else None
+    fn(*conv_geometry(case), case.filters, case.alpha, im, w, case.beta, out, workspace)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def check_conv(case, conv_oracle):
+    """GPU convolution against the direct-loop oracle; returns the relative error (0 for exact cases)."""
+    from paper_1705_05249_amd import gemm as G
+    ref, den = conv_oracle.conv2d(case.dtype, *conv_geometry(case), case.filters, case.alpha, case.im, case.weights,
+                                  case.beta, case.out)
+    assert ref.shape[1:] == case.out_hw
+    assert tuple(G.mg_conv2d_out_extent(s, k, p, st, d) for s, k, p, st, d in
+                 zip((case.height, case.width), case.kernel, case.pad, case.stride, case.dilation)) == case.out_hw
+    got = run_conv(case)
+    if case.exact:
+        assert np.array_equal(got.astype(np.float64), ref), f"{case.name}: not bit-exact on integer inputs"
+        return 0.0
+    err = rel_error(got, ref, den)
+    assert err <= TOL[case.dtype], f"{case.name}: relative error {err:.3e}"
+    return err

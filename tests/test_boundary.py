@@ -112,9 +112,57 @@ def test_strided_batched_argument_errors():
     assert strided(n=0, A=None, Cp=None) == 0
 
 
+GEOM = dict(channels=3, height=8, width=9, kernel=(3, 3), pad=(1, 1), stride=(1, 1), dilation=(1, 1))
+
+
+def conv(fn=None, filters=4, im=FAKE, weights=FAKE, out=FAKE, ws=None, ws_bytes=None, alpha=1.0, beta=0.0, **over):
+    g = dict(GEOM, **over)
+    name = fn or "mg_sconv2d"
+    args = G._geometry(g["channels"], g["height"], g["width"], g["kernel"], g["pad"], g["stride"], g["dilation"])
+    need = G.mg_conv2d_workspace_bytes(G.MG_F32, g["channels"], g["height"], g["width"], g["kernel"], g["pad"],
+                                       g["stride"], g["dilation"], filters)
+    ws_addr = (256 if ws is None else ws)
+    return getattr(G.lib(), name)(*args, filters, alpha, im, weights, beta, out, ws_addr,
+                                  need if ws_bytes is None else ws_bytes, 0)
+
+
+@pytest.mark.parametrize("fn", ["mg_sconv2d", "mg_hconv2d"])
+def test_conv_argument_errors(fn):
+    """geometry and pointer errors are reported before any GPU work (no GPU here)"""
+    for bad in (dict(channels=0), dict(height=0), dict(width=-1), dict(kernel=(0, 3)), dict(kernel=(3, 0)),
+                dict(pad=(-1, 0)), dict(pad=(0, -1)), dict(stride=(0, 1)), dict(stride=(1, 0)),
+                dict(dilation=(0, 1)), dict(dilation=(1, 0))):
+        assert conv(fn, **bad) == -15, bad
+    assert conv(fn, filters=-1) == -15
+    assert conv(fn, height=1 << 20, width=1 << 20) == -4                  # column matrix beyond 2^31 elements
+    assert conv(fn, im=None) == -8 and conv(fn, weights=None) == -8 and conv(fn, out=None) == -8
+    assert conv(fn, ws=0) == -10 and conv(fn, ws=264) == -10 and conv(fn, ws_bytes=255) == -10
+    # empty outputs launch nothing: no filters, or a filter that does not fit the image
+    assert conv(fn, filters=0, im=None, weights=None, out=None) == 0
+    assert conv(fn, kernel=(9, 3), pad=(0, 0), im=None, weights=None, out=None) == 0
+
+
+def test_im2col_argument_errors_and_geometry_queries():
+    L = G.lib()
+    args = G._geometry(**GEOM)
+    for fn in (L.mg_sim2col, L.mg_him2col):
+        assert fn(*args, None, FAKE, 0) == -8 and fn(*args, FAKE, None, 0) == -8
+        assert fn(*G._geometry(**dict(GEOM, stride=(0, 1))), FAKE, FAKE, 0) == -15
+        assert fn(*G._geometry(**dict(GEOM, kernel=(9, 9), pad=(0, 0))), None, None, 0) == 0      # empty output
+    assert G.mg_conv2d_out_extent(224, 7, 3, 2, 1) == 112 and G.mg_conv2d_out_extent(5, 3, 0, 2, 1) == 2
+    assert G.mg_conv2d_out_extent(2, 5, 0, 1, 1) == 0 and G.mg_conv2d_out_extent(5, 3, 0, 0, 1) == -1
+    # workspace: the column matrix rounded up to 256 bytes (+ split-K scratch of the GEMM, none here)
+    assert G.mg_conv2d_workspace_bytes(G.MG_F16, 3, 224, 224, (7, 7), (3, 3), (2, 2), (1, 1), 64) == 147 * 12544 * 2
+    assert G.mg_conv2d_workspace_bytes(G.MG_F32, 3, 8, 9, (3, 3), (1, 1), (1, 1), (1, 1), 4) == 7936      # 27 * 72 * 4 = 7776, rounded up to a multiple of 256
+    # a 1x1 filter with unit stride and no padding needs no column matrix
+    assert G.mg_conv2d_workspace_bytes(G.MG_F32, 16, 8, 8, (1, 1), (0, 0), (1, 1), (1, 1), 8) == 0
+    assert G.mg_conv2d_workspace_bytes(G.MG_F32, 16, 8, 8, (1, 1), (0, 0), (2, 1), (1, 1), 8) > 0
+    assert G.mg_conv2d_workspace_bytes(7, 3, 8, 9, (3, 3), (1, 1), (1, 1), (1, 1), 4) == 0
+
+
 def test_status_strings_and_version():
     seen = set()
-    for code in range(0, -15, -1):
+    for code in range(0, -16, -1):
         s = G.status_string(code)
         assert s and s != "unknown status" and s not in seen
         seen.add(s)

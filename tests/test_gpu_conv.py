@@ -1,0 +1,135 @@
+"""GPU parity of IM2COL and convolution-as-GEMM against the CPU oracle (direct loops in FP64), through the C ABI.
+IM2COL is data movement: bit-exact.  Convolution: bit-exact on integer inputs, else within the GEMM tolerances
+max |out - ref| / (|alpha| sum |w||x| + |beta||out_old|) <= 1e-5 (FP32), 2e-3 (FP16 storage)."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_1705_05249_amd import workloads as W
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def announce(*what):
+    print("[case]", *what, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def G():
+    from paper_1705_05249_amd import gemm as G
+    return G
+
+
+@pytest.fixture(scope="module")
+def CO():
+    from oracle import conv_oracle
+    return conv_oracle
+
+
+geometry = H.conv_geometry
+
+
+def run_im2col(G, case, guard=64):
+    """returns the column matrix as numpy (K, OH*OW); elements behind its end must stay untouched"""
+    import torch
+    oh, ow = case.out_hw
+    total = case.k * oh * ow
+    im = H.to_gpu(case.im)
+    col = torch.full((total + guard,), -77.0, dtype=im.dtype, device="cuda")
+    fn = G.mg_sim2col if case.dtype == "f32" else G.mg_him2col
+    fn(*geometry(case), im, col)
+    torch.cuda.synchronize()
+    host = col.cpu().numpy()
+    assert np.all(host[total:] == -77.0), f"{case.name}: written past the column matrix"
+    return host[:total].reshape(case.k, oh * ow)
+
+
+def run_conv(G, case, workspace="auto"):
+    return H.run_conv(case, workspace)
+
+
+def check_conv(G, CO, case):
+    return H.check_conv(case, CO)
+
+
+SMALL = [  # channels, height, width, kernel, pad, stride, dilation, filters
+    (3, 9, 11, (3, 3), (1, 1), (1, 1), (1, 1), 5),
+    (2, 7, 5, (3, 2), (0, 1), (2, 1), (1, 2), 3),         # asymmetric everything
+    (5, 13, 17, (5, 5), (2, 2), (3, 2), (1, 1), 7),
+    (4, 10, 10, (3, 3), (4, 4), (1, 1), (3, 3), 6),        # padding wider than the image border, dilation 3
+    (1, 1, 1, (1, 1), (0, 0), (1, 1), (1, 1), 1),          # single element
+    (6, 20, 33, (1, 1), (0, 0), (1, 1), (1, 1), 9),        # 1x1: the image is the column matrix
+    (6, 20, 33, (1, 1), (0, 0), (2, 3), (1, 1), 9),        # 1x1 with stride: needs the unfold
+    (8, 32, 32, (3, 3), (1, 1), (1, 1), (1, 1), 64),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("geo", SMALL)
+def test_im2col_bit_exact(G, CO, dtype, geo):
+    case = W.conv_case(dtype, *geo, case=1)
+    announce("im2col", case.name, geo)
+    want = CO.im2col(dtype, *geometry(case), case.im)
+    got = run_im2col(G, case)
+    assert got.shape == want.shape and np.array_equal(got.astype(np.float64), want)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("index", [0, 1, 2, 3])
+def test_im2col_layers_bit_exact(G, CO, dtype, index):
+    case = W.conv_layer(index, dtype)
+    announce("im2col", case.name)
+    want = CO.im2col(dtype, *geometry(case), case.im)
+    assert np.array_equal(run_im2col(G, case).astype(np.float64), want)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("integer", [True, False])
+@pytest.mark.parametrize("geo", SMALL)
+def test_conv_small(G, CO, dtype, integer, geo):
+    case = W.conv_case(dtype, *geo, alpha=1.0 if integer else -1.25, beta=1.0 if integer else 0.5, case=2, integer=integer)
+    announce("conv", case.name, geo, "integer" if integer else "random")
+    check_conv(G, CO, case)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+@pytest.mark.parametrize("index", [0, 1, 2, 3])
+@pytest.mark.parametrize("integer", [True, False])
+def test_conv_layers(G, CO, dtype, index, integer):
+    """the four layers whose unfolded GEMMs are the FP16 shapes (64,12544,147) ... (512,196,2304)"""
+    case = W.conv_layer(index, dtype, integer=integer)
+    announce("conv", case.name, "integer" if integer else "random")
+    assert (case.filters, case.out_hw[0] * case.out_hw[1], case.k) == W.CONFIG3_SHAPES[index]
+    if integer and dtype == "f16":
+        # keep every sum exactly representable in the FP16 output: |sum| <= 2048 needs |w||x| <= 1 on most taps
+        case.weights = np.sign(case.weights).astype(case.weights.dtype)
+        case.im = np.sign(case.im).astype(case.im.dtype)
+    check_conv(G, CO, case)
+
+
+def test_conv_conventions(G, CO):
+    """beta == 0 ignores NaN in out; alpha == 0 ignores NaN in im and weights and needs no workspace"""
+    case = W.conv_case("f32", 3, 9, 11, (3, 3), (1, 1), (1, 1), (1, 1), 5, alpha=1.0, beta=0.0, case=3)
+    ref, den = CO.conv2d("f32", *geometry(case), case.filters, 1.0, case.im, case.weights, 0.0, case.out)
+    case.out = np.full_like(case.out, np.nan)
+    assert H.rel_error(run_conv(G, case), ref, den) <= H.TOL["f32"]
+    case = W.conv_case("f32", 3, 9, 11, (3, 3), (1, 1), (1, 1), (1, 1), 5, alpha=0.0, beta=2.0, case=4, integer=True)
+    want = 2.0 * case.out.astype(np.float64)
+    case.im, case.weights = np.full_like(case.im, np.nan), np.full_like(case.weights, np.nan)
+    assert np.array_equal(run_conv(G, case, workspace=None).astype(np.float64), want)
+
+
+def test_conv_reports_a_short_workspace(G):
+    import torch
+    case = W.conv_case("f32", 3, 9, 11, (3, 3), (1, 1), (1, 1), (1, 1), 5, case=5)
+    im, w, out = H.to_gpu(case.im), H.to_gpu(case.weights), H.to_gpu(case.out)
+    need = G.mg_conv2d_workspace_bytes(G.MG_F32, *geometry(case), case.filters)
+    short = torch.empty(need - 256, dtype=torch.uint8, device="cuda")
+    before = out.clone()
+    assert G.mg_sconv2d(*geometry(case), case.filters, 1.0, im, w, 0.0, out, short, check=False) == -10
+    assert G.mg_sconv2d(*geometry(case), case.filters, 1.0, im, w, 0.0, out, None, check=False) == -10
+    torch.cuda.synchronize()
+    assert torch.equal(out, before)
