@@ -144,6 +144,24 @@ void oracle_sgemm_batched(int layout, int ta, int tb, int64_t m, int64_t n, int6
     }
 }
 
+/* Batched FP16 storage: the same per instance; A, B, C hold binary16 bit patterns, offsets are in
+ * elements, alphas and betas are FP32 (the scalar type of the FP16 routines). */
+void oracle_hgemm_batched(int layout, int ta, int tb, int64_t m, int64_t n, int64_t k,
+                          const float *alphas, const uint16_t *A, const int64_t *a_off, int64_t lda,
+                          const uint16_t *B, const int64_t *b_off, int64_t ldb,
+                          const float *betas, const uint16_t *C, const int64_t *c_off, int64_t ldc,
+                          int64_t batch, double *c_ref, double *d_ref)
+{
+    int64_t per = m * n;
+#pragma omp parallel for schedule(static)
+    for (int64_t q = 0; q < batch * per; ++q) {
+        int64_t b = q / per, p = q % per;
+        int64_t i = p / n, j = p % n;
+        one_entry(1, layout, ta, tb, k, (double)alphas[b], A + a_off[b], lda, B + b_off[b], ldb,
+                  (double)betas[b], C + c_off[b], ldc, i, j, &c_ref[q], &d_ref[q]);
+    }
+}
+
 /* binary16 -> double for arrays (lets tests pin the converter on all 65536 patterns) */
 void oracle_half_to_double(const uint16_t *src, int64_t count, double *dst)
 {

@@ -38,6 +38,8 @@ def lib():
         _lib.oracle_sgemm_batched.argtypes = [ci, ci, ci, i64, i64, i64, vp, vp, vp, i64, vp, vp, i64,
                                               vp, vp, vp, i64, i64, vp, vp]
         _lib.oracle_sgemm_batched.restype = None
+        _lib.oracle_hgemm_batched.argtypes = _lib.oracle_sgemm_batched.argtypes
+        _lib.oracle_hgemm_batched.restype = None
         _lib.oracle_half_to_double.argtypes = [vp, i64, vp]
         _lib.oracle_half_to_double.restype = None
         _lib.oracle_threads.argtypes = []
@@ -113,7 +115,14 @@ def gemm_entries(dtype, layout, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C,
 
 def sgemm_batched(layout, ta, tb, m, n, k, alphas, A, a_off, lda, B, b_off, ldb, betas, C, c_off, ldc):
     """Batched FP32 oracle.  Returns (C_ref, D) of shape (batch, m, n)."""
-    A, B, C = _flat(A, np.float32), _flat(B, np.float32), _flat(C, np.float32)
+    return gemm_batched("f32", layout, ta, tb, m, n, k, alphas, A, a_off, lda, B, b_off, ldb, betas, C, c_off, ldc)
+
+
+def gemm_batched(dtype, layout, ta, tb, m, n, k, alphas, A, a_off, lda, B, b_off, ldb, betas, C, c_off, ldc):
+    """Batched oracle for FP32 ("f32") or FP16 storage ("f16", float16 arrays).  Returns (C_ref, D) of shape
+    (batch, m, n)."""
+    np_t = np.float32 if dtype == "f32" else np.float16
+    A, B, C = _flat(A, np_t), _flat(B, np_t), _flat(C, np_t)
     alphas, betas = _flat(alphas, np.float32), _flat(betas, np.float32)
     a_off, b_off, c_off = (_flat(x, np.int64) for x in (a_off, b_off, c_off))
     batch = alphas.size
@@ -125,10 +134,18 @@ def sgemm_batched(layout, ta, tb, m, n, k, alphas, A, a_off, lda, B, b_off, ldb,
         assert c_off.max() + _need(layout, NO_TRANS, m, n, ldc) <= C.size, "C too short"
     c_ref = np.empty((batch, m, n), dtype=np.float64)
     d_ref = np.empty((batch, m, n), dtype=np.float64)
-    lib().oracle_sgemm_batched(layout, ta, tb, m, n, k, _ptr(alphas), _ptr(A), _ptr(a_off), lda,
-                               _ptr(B), _ptr(b_off), ldb, _ptr(betas), _ptr(C), _ptr(c_off), ldc,
-                               batch, _ptr(c_ref), _ptr(d_ref))
+    fn = lib().oracle_sgemm_batched if dtype == "f32" else lib().oracle_hgemm_batched
+    fn(layout, ta, tb, m, n, k, _ptr(alphas), _ptr(A), _ptr(a_off), lda, _ptr(B), _ptr(b_off), ldb, _ptr(betas),
+       _ptr(C), _ptr(c_off), ldc, batch, _ptr(c_ref), _ptr(d_ref))
     return c_ref, d_ref
+
+
+def gemm_strided_batched(dtype, layout, ta, tb, m, n, k, alpha, A, lda, stride_a, B, ldb, stride_b, beta, C, ldc,
+                         stride_c, batch):
+    """Strided batched oracle for either storage type (see sgemm_strided_batched)."""
+    idx = np.arange(batch, dtype=np.int64)
+    return gemm_batched(dtype, layout, ta, tb, m, n, k, np.full(batch, alpha, dtype=np.float32), A, idx * stride_a,
+                        lda, B, idx * stride_b, ldb, np.full(batch, beta, dtype=np.float32), C, idx * stride_c, ldc)
 
 
 def sgemm_strided_batched(layout, ta, tb, m, n, k, alpha, A, lda, stride_a, B, ldb, stride_b, beta, C, ldc,

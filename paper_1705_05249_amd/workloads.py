@@ -145,6 +145,7 @@ class BatchedCase:
     c_off: np.ndarray
     ldc: int
     batch: int = field(default=0)
+    dtype: str = "f32"
 
     @property
     def flops(self) -> float:
@@ -152,8 +153,9 @@ class BatchedCase:
 
     @property
     def algorithmic_bytes(self) -> float:
-        # A, B, C_old read + C written (FP32), two FP32 scalars, three int64 offsets
-        return self.batch * (4.0 * (self.m * self.k + self.k * self.n + 2 * self.m * self.n) + 8 + 24)
+        # A, B, C_old read + C written, two FP32 scalars, three int64 offsets
+        e = 4.0 if self.dtype == "f32" else 2.0
+        return self.batch * (e * (self.m * self.k + self.k * self.n + 2 * self.m * self.n) + 8 + 24)
 
 
 def _np_dtype(dtype: str):
@@ -324,7 +326,7 @@ GAP_FILL = np.float32(-12345.0)   # sentinel kept in the gaps of C (NaN would no
 
 def batched_case(s_m, s_n, s_k, batch, case=0, layout=COL_MAJOR, ta=NO_TRANS, tb=NO_TRANS,
                  integer=False, lda=None, ldb=None, ldc=None, gap=GAP, name=None,
-                 shuffle_offsets=False) -> BatchedCase:
+                 shuffle_offsets=False, dtype="f32") -> BatchedCase:
     """`batch` independent GEMMs in single A/B/C buffers; instance i starts at i*(size+gap);
     alpha_i, beta_i ~ U[0.5, 2]; entries U[-1,1] (or small integers with alpha,beta in {0.5,1,1.5,2})"""
     g = rng_for(4, case)
@@ -338,10 +340,16 @@ def batched_case(s_m, s_n, s_k, batch, case=0, layout=COL_MAJOR, ta=NO_TRANS, tb
     a_off = (order * (la + gap)).astype(np.int64)
     b_off = (order * (lb + gap)).astype(np.int64)
     c_off = (order * (lc + gap)).astype(np.int64)
-    A = np.full(batch * (la + gap), np.nan, dtype=np.float32)
-    B = np.full(batch * (lb + gap), np.nan, dtype=np.float32)
-    C = np.full(batch * (lc + gap), GAP_FILL, dtype=np.float32)
-    gen = small_ints if integer else uniform
+    np_t = _np_dtype(dtype)
+    A = np.full(batch * (la + gap), np.nan, dtype=np_t)
+    B = np.full(batch * (lb + gap), np.nan, dtype=np_t)
+    C = np.full(batch * (lc + gap), GAP_FILL, dtype=np_t)
+    if integer and dtype == "f16":
+        # entries in [-2,2]: with alpha, beta <= 2 every result stays an exactly representable FP16 number
+        gen = lambda rng, shape: small_ints(rng, shape, 2, np_t)
+    else:
+        gen = (lambda rng, shape: small_ints(rng, shape, 4, np_t)) if integer else \
+              (lambda rng, shape: uniform(rng, shape, dtype=np.float32).astype(np_t))
     for i in range(batch):
         opA, opB, Cm = gen(g, (s_m, s_k)), gen(g, (s_k, s_n)), gen(g, (s_m, s_n))
         A[a_off[i]: a_off[i] + la] = pack(opA, layout, ta, lda)[:la]
@@ -353,8 +361,8 @@ def batched_case(s_m, s_n, s_k, batch, case=0, layout=COL_MAJOR, ta=NO_TRANS, tb
     else:
         alphas = g.uniform(0.5, 2.0, size=batch).astype(np.float32)
         betas = g.uniform(0.5, 2.0, size=batch).astype(np.float32)
-    return BatchedCase(name or f"c4_s{s_m}x{s_n}x{s_k}_b{batch}", layout, ta, tb, s_m, s_n, s_k,
-                       alphas, betas, A, a_off, lda, B, b_off, ldb, C, c_off, ldc, batch)
+    return BatchedCase(name or f"c4_{dtype}_s{s_m}x{s_n}x{s_k}_b{batch}", layout, ta, tb, s_m, s_n, s_k,
+                       alphas, betas, A, a_off, lda, B, b_off, ldb, C, c_off, ldc, batch, dtype)
 
 
 def config4(size: int, batch: int) -> BatchedCase:

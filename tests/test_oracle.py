@@ -330,6 +330,32 @@ def test_batched_equals_loop_of_singles_bitwise(oracle):
         assert np.array_equal(c_ref[i], c1) and np.array_equal(d_ref[i], d1)
 
 
+def test_half_batched_equals_loop_of_singles_bitwise(oracle):
+    """FP16 storage: the batched oracle is the FP16 single-call oracle per instance (offsets in elements of
+    the 2-byte type, FP32 scalars), bit for bit"""
+    for layout, ta, tb in ((Cm, N, N), (R, T, N), (Cm, T, T)):
+        bc = W.batched_case(7, 5, 9, 11, case=3, layout=layout, ta=ta, tb=tb, shuffle_offsets=True, dtype="f16")
+        assert bc.A.dtype == np.float16
+        c_ref, d_ref = oracle.gemm_batched("f16", bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, bc.alphas, bc.A, bc.a_off,
+                                           bc.lda, bc.B, bc.b_off, bc.ldb, bc.betas, bc.C, bc.c_off, bc.ldc)
+        for i in range(bc.batch):
+            c1, d1 = oracle.gemm("f16", bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, float(bc.alphas[i]),
+                                 bc.A[bc.a_off[i]:], bc.lda, bc.B[bc.b_off[i]:], bc.ldb, float(bc.betas[i]),
+                                 bc.C[bc.c_off[i]:], bc.ldc)
+            assert np.array_equal(c_ref[i], c1) and np.array_equal(d_ref[i], d1)
+        # and an instance against numpy on the widened data
+        rA, cA = W.stored_extents(ta, bc.m, bc.k)
+        rB, cB = W.stored_extents(tb, bc.k, bc.n)
+        i = 4
+        SA = W.unpack(bc.A[bc.a_off[i]:], layout, rA, cA, bc.lda).astype(np.float64)
+        SB = W.unpack(bc.B[bc.b_off[i]:], layout, rB, cB, bc.ldb).astype(np.float64)
+        C0 = W.unpack(bc.C[bc.c_off[i]:], layout, bc.m, bc.n, bc.ldc).astype(np.float64)
+        a = SA if ta == N else SA.T
+        b = SB if tb == N else SB.T
+        want = float(bc.alphas[i]) * (a @ b) + float(bc.betas[i]) * C0
+        assert np.max(np.abs(c_ref[i] - want)) <= 1e-13
+
+
 def test_batched_distinct_offset_arrays(oracle):
     """A, B and C use their own offset arrays (a mix-up between them changes the result)"""
     g = W.rng_for(90, 9)
