@@ -141,6 +141,24 @@ mg_status mg_sgemm_strided_batched(int layout, int trans_a, int trans_b, int64_t
                                    float *C, int64_t ldc, int64_t stride_c,
                                    int64_t batch_count, void *stream);
 
+/* FP16 storage (IEEE binary16), FP32 accumulation, one rounding; offsets and strides count
+ * 2-byte elements; alphas, betas, alpha, beta are FP32.  Otherwise as the FP32 routines above
+ * (the paper's batched routines exist per precision, Sections 4.4 and 4.6). */
+mg_status mg_hgemm_batched(int layout, int trans_a, int trans_b, int64_t m, int64_t n, int64_t k,
+                           const float *alphas,
+                           const uint16_t *A, const int64_t *a_offsets, int64_t lda,
+                           const uint16_t *B, const int64_t *b_offsets, int64_t ldb,
+                           const float *betas,
+                           uint16_t *C, const int64_t *c_offsets, int64_t ldc,
+                           int64_t batch_count, void *stream);
+mg_status mg_hgemm_strided_batched(int layout, int trans_a, int trans_b, int64_t m, int64_t n, int64_t k,
+                                   float alpha,
+                                   const uint16_t *A, int64_t lda, int64_t stride_a,
+                                   const uint16_t *B, int64_t ldb, int64_t stride_b,
+                                   float beta,
+                                   uint16_t *C, int64_t ldc, int64_t stride_c,
+                                   int64_t batch_count, void *stream);
+
 /* Bytes of workspace the currently selected configuration needs for this problem
  * (0 for most).  dtype is an mg_dtype.  Returns 0 for invalid arguments. */
 size_t mg_gemm_workspace_bytes(int dtype, int layout, int trans_a, int trans_b,

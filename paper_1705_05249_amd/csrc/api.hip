@@ -136,8 +136,8 @@ mg_status run_gemm(int dtype, int layout, int ta, int tb, int64_t m, int64_t n, 
 
 // Canonicalises a (generic or strided) batched call to column-major and launches it.
 mg_status run_batched(BatchedProblem &p, int layout, int ta, int tb, int64_t m, int64_t n, int64_t k,
-                      const float *A, const int64_t *a_off, int64_t stride_a, int64_t lda, const float *B,
-                      const int64_t *b_off, int64_t stride_b, int64_t ldb, float *C, const int64_t *c_off,
+                      const void *A, const int64_t *a_off, int64_t stride_a, int64_t lda, const void *B,
+                      const int64_t *b_off, int64_t stride_b, int64_t ldb, void *C, const int64_t *c_off,
                       int64_t stride_c, int64_t ldc, int64_t batch, void *stream)
 {
     const bool at = ta != MG_NO_TRANS, bt = tb != MG_NO_TRANS;
@@ -167,6 +167,43 @@ mg_status run_batched(BatchedProblem &p, int layout, int ta, int tb, int64_t m, 
     return t[kernel].launch_batched(p) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
 }
 
+
+mg_status generic_batched(int dtype, int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, const float *alphas,
+                          const void *A, const int64_t *a_offsets, int64_t lda, const void *B,
+                          const int64_t *b_offsets, int64_t ldb, const float *betas, void *C,
+                          const int64_t *c_offsets, int64_t ldc, int64_t batch_count, void *stream)
+{
+    mg_status s = check_shape(layout, ta, tb, m, n, k, lda, ldb, ldc);
+    if (s != MG_OK) return s;
+    if (batch_count < 0 || batch_count >= (int64_t(1) << 31)) return MG_ERR_BATCH;
+    if (m == 0 || n == 0 || batch_count == 0) return MG_OK;
+    if (!alphas || !betas || !a_offsets || !b_offsets || !c_offsets || !C) return MG_ERR_NULL;
+    if (k != 0 && (!A || !B)) return MG_ERR_NULL;
+    BatchedProblem p{};
+    p.dtype = dtype;
+    p.alphas = alphas; p.betas = betas;
+    return run_batched(p, layout, ta, tb, m, n, k, A, a_offsets, 0, lda, B, b_offsets, 0, ldb, C, c_offsets, 0, ldc,
+                       batch_count, stream);
+}
+
+mg_status strided_batched(int dtype, int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, float alpha,
+                          const void *A, int64_t lda, int64_t stride_a, const void *B, int64_t ldb, int64_t stride_b,
+                          float beta, void *C, int64_t ldc, int64_t stride_c, int64_t batch_count, void *stream)
+{
+    mg_status s = check_shape(layout, ta, tb, m, n, k, lda, ldb, ldc);
+    if (s != MG_OK) return s;
+    if (batch_count < 0 || batch_count >= (int64_t(1) << 31)) return MG_ERR_BATCH;
+    if (stride_a < 0 || stride_b < 0 || stride_c < 0) return MG_ERR_STRIDE;
+    if (m == 0 || n == 0 || batch_count == 0) return MG_OK;
+    if (!C) return MG_ERR_NULL;
+    if (k != 0 && alpha != 0.f && (!A || !B)) return MG_ERR_NULL;
+    BatchedProblem p{};
+    p.dtype = dtype;
+    p.strided = true;
+    p.alpha = alpha; p.beta = beta;
+    return run_batched(p, layout, ta, tb, m, n, k, A, nullptr, stride_a, lda, B, nullptr, stride_b, ldb, C, nullptr,
+                       stride_c, ldc, batch_count, stream);
+}
 
 // Checks a convolution geometry; fills the output extents and K = channels * kernel_h * kernel_w.
 mg_status check_conv(const ConvShape &s, int64_t filters, int64_t *out_h, int64_t *out_w, int64_t *k)
@@ -260,16 +297,17 @@ mg_status mg_sgemm_batched(int layout, int ta, int tb, int64_t m, int64_t n, int
                            const int64_t *b_offsets, int64_t ldb, const float *betas, float *C,
                            const int64_t *c_offsets, int64_t ldc, int64_t batch_count, void *stream)
 {
-    mg_status s = check_shape(layout, ta, tb, m, n, k, lda, ldb, ldc);
-    if (s != MG_OK) return s;
-    if (batch_count < 0 || batch_count >= (int64_t(1) << 31)) return MG_ERR_BATCH;
-    if (m == 0 || n == 0 || batch_count == 0) return MG_OK;
-    if (!alphas || !betas || !a_offsets || !b_offsets || !c_offsets || !C) return MG_ERR_NULL;
-    if (k != 0 && (!A || !B)) return MG_ERR_NULL;
-    BatchedProblem p{};
-    p.alphas = alphas; p.betas = betas;
-    return run_batched(p, layout, ta, tb, m, n, k, A, a_offsets, 0, lda, B, b_offsets, 0, ldb, C, c_offsets, 0, ldc,
-                       batch_count, stream);
+    return generic_batched(MG_F32, layout, ta, tb, m, n, k, alphas, A, a_offsets, lda, B, b_offsets, ldb, betas, C,
+                           c_offsets, ldc, batch_count, stream);
+}
+
+mg_status mg_hgemm_batched(int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, const float *alphas,
+                           const uint16_t *A, const int64_t *a_offsets, int64_t lda, const uint16_t *B,
+                           const int64_t *b_offsets, int64_t ldb, const float *betas, uint16_t *C,
+                           const int64_t *c_offsets, int64_t ldc, int64_t batch_count, void *stream)
+{
+    return generic_batched(MG_F16, layout, ta, tb, m, n, k, alphas, A, a_offsets, lda, B, b_offsets, ldb, betas, C,
+                           c_offsets, ldc, batch_count, stream);
 }
 
 mg_status mg_sgemm_strided_batched(int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, float alpha,
@@ -277,18 +315,17 @@ mg_status mg_sgemm_strided_batched(int layout, int ta, int tb, int64_t m, int64_
                                    int64_t stride_b, float beta, float *C, int64_t ldc, int64_t stride_c,
                                    int64_t batch_count, void *stream)
 {
-    mg_status s = check_shape(layout, ta, tb, m, n, k, lda, ldb, ldc);
-    if (s != MG_OK) return s;
-    if (batch_count < 0 || batch_count >= (int64_t(1) << 31)) return MG_ERR_BATCH;
-    if (stride_a < 0 || stride_b < 0 || stride_c < 0) return MG_ERR_STRIDE;
-    if (m == 0 || n == 0 || batch_count == 0) return MG_OK;
-    if (!C) return MG_ERR_NULL;
-    if (k != 0 && alpha != 0.f && (!A || !B)) return MG_ERR_NULL;
-    BatchedProblem p{};
-    p.strided = true;
-    p.alpha = alpha; p.beta = beta;
-    return run_batched(p, layout, ta, tb, m, n, k, A, nullptr, stride_a, lda, B, nullptr, stride_b, ldb, C, nullptr,
-                       stride_c, ldc, batch_count, stream);
+    return strided_batched(MG_F32, layout, ta, tb, m, n, k, alpha, A, lda, stride_a, B, ldb, stride_b, beta, C, ldc,
+                           stride_c, batch_count, stream);
+}
+
+mg_status mg_hgemm_strided_batched(int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, float alpha,
+                                   const uint16_t *A, int64_t lda, int64_t stride_a, const uint16_t *B, int64_t ldb,
+                                   int64_t stride_b, float beta, uint16_t *C, int64_t ldc, int64_t stride_c,
+                                   int64_t batch_count, void *stream)
+{
+    return strided_batched(MG_F16, layout, ta, tb, m, n, k, alpha, A, lda, stride_a, B, ldb, stride_b, beta, C, ldc,
+                           stride_c, batch_count, stream);
 }
 
 size_t mg_gemm_workspace_bytes(int dtype, int layout, int ta, int tb, int64_t m, int64_t n, int64_t k,

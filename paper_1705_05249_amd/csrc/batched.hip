@@ -1,19 +1,20 @@
-// Batched small GEMM (paper Section 4.6): one 64-lane wavefront per instance, no LDS.
+// Batched small GEMM (paper Section 4.6): one 64-lane wavefront per instance, no LDS; FP32, and FP16
+// storage with FP32 accumulation.
 //
-// The whole instance lives in registers in the operand layout of v_mfma_f32_16x16x4_f32: for a
-// 16-row block of an operand and a 16-wide block of k, lane (r = lane % 16, g = lane / 16) holds
-// the four values X[r][4g + s], s = 0..3, and MFMA number s of that k block multiplies the
-// values with the same s.  (The sum over k does not care which k meets which MFMA step, as long
-// as A and B agree.)  With that choice
-//   * an operand that is contiguous along k is ONE 16-byte load per lane and block -- for a
-//     16 x 16 column-major B the wavefront reads its 1 KB in one instruction;
-//   * an operand that is contiguous along m (or n) is four 4-byte loads per lane, each of them
-//     four 64-byte runs across the wavefront;
+// The whole instance lives in registers: for a 16-row block of an operand and a 16-wide block of k,
+// lane (r = lane % 16, g = lane / 16) holds the four values X[r][4g + s], s = 0..3.  For FP16 that is
+// the operand layout of v_mfma_f32_16x16x16_f16 (one MFMA per block).  For FP32 the four values feed
+// four v_mfma_f32_16x16x4_f32, MFMA number s multiplying the values with the same s.  (The sum over
+// k does not care which k meets which MFMA step, as long as A and B agree.)  With that choice
+//   * an operand that is contiguous along k is ONE 16-byte (FP16: 8-byte) load per lane and block --
+//     for a 16 x 16 column-major FP32 B the wavefront reads its 1 KB in one instruction;
+//   * an operand that is contiguous along m (or n) is four element loads per lane, each of them
+//     four contiguous runs of 16 elements across the wavefront;
 //   * the accumulator of a 16 x 16 block of C puts four consecutive rows of one column into one
-//     lane, so C is read and written 16 bytes per lane.
+//     lane, so C is read and written as one vector of four elements per lane.
 // Per-instance offsets and scalars are wave-uniform and come in through scalar loads; this is
 // the overhead the paper points out when it compares the generic with the strided interface.
-// Instances only need 4-byte alignment (16-byte accesses are issued as align-4 vector loads).
+// Instances only need element alignment (the vector accesses are issued at element alignment).
 // Shapes up to 64 x 64 x 64 are covered by three register-block sizes; anything larger goes to
 // the direct batched kernel.  The 64-wide block splits an instance's columns over the four
 // wavefronts of a work-group (each re-reads A, which the L1 serves): a quarter of the registers
@@ -25,13 +26,33 @@ namespace mg {
 namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-struct __attribute__((packed, aligned(4))) Float4U {   // 16 bytes at 4-byte alignment
-    float x, y, z, w;
+typedef _Float16 halfx4 __attribute__((ext_vector_type(4)));
+template <typename T> struct __attribute__((packed, aligned(sizeof(T)))) Quad {   // four elements at element alignment
+    T x, y, z, w;
 };
+template <typename T> struct Vec4;
+template <> struct Vec4<float> { using type = floatx4; };
+template <> struct Vec4<_Float16> { using type = halfx4; };
+
+__device__ inline floatx4 widen(floatx4 v) { return v; }
+__device__ inline floatx4 widen(halfx4 v) { return floatx4{static_cast<float>(v.x), static_cast<float>(v.y), static_cast<float>(v.z), static_cast<float>(v.w)}; }
+
+// acc += X * Y over the 16 values of k the two fragments hold
+__device__ inline floatx4 block_mma(floatx4 x, floatx4 y, floatx4 c)
+{
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.x, y.x, c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.y, y.y, c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.z, y.z, c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(x.w, y.w, c, 0, 0, 0);
+}
+__device__ inline floatx4 block_mma(halfx4 x, halfx4 y, floatx4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(x, y, c, 0, 0, 0);
+}
 
 struct BatchedArgs {
-    const float *A, *B;
-    float *C;
+    const void *A, *B;
+    void *C;
     const int64_t *a_off, *b_off, *c_off;
     const float *alphas, *betas;
     int64_t lda, ldb, ldc;
@@ -45,22 +66,24 @@ struct BatchedArgs {
 
 // four values X[row][k0 .. k0+3] of an operand block; KC: contiguous along k (X[k + row*ld]) or
 // along the row index (X[row + k*ld]).  FULL: no bounds checks needed.
-template <bool KC, bool FULL>
-__device__ inline floatx4 load4(const float *__restrict__ X, int64_t ld, int row, int k0, int rows, int ks)
+template <typename T, bool KC, bool FULL>
+__device__ inline typename Vec4<T>::type load4(const T *__restrict__ X, int64_t ld, int row, int k0, int rows, int ks)
 {
-    floatx4 v = {0.f, 0.f, 0.f, 0.f};
+    using V = typename Vec4<T>::type;
+    const T zero = static_cast<T>(0.f);
+    V v = {zero, zero, zero, zero};
     if constexpr (KC) {
-        const float *p = X + k0 + row * ld;
+        const T *p = X + k0 + row * ld;
         if (FULL || (row < rows && k0 + 3 < ks)) {
-            const Float4U u = *reinterpret_cast<const Float4U *>(p);
-            v = floatx4{u.x, u.y, u.z, u.w};
+            const Quad<T> u = *reinterpret_cast<const Quad<T> *>(p);
+            v = V{u.x, u.y, u.z, u.w};
         } else if (row < rows) {
 #pragma unroll
             for (int s = 0; s < 4; ++s)
                 if (k0 + s < ks) v[s] = p[s];
         }
     } else {
-        const float *p = X + row + k0 * ld;
+        const T *p = X + row + k0 * ld;
 #pragma unroll
         for (int s = 0; s < 4; ++s)
             if (FULL || (row < rows && k0 + s < ks)) v[s] = p[s * ld];
@@ -69,9 +92,10 @@ __device__ inline floatx4 load4(const float *__restrict__ X, int64_t ld, int row
 }
 
 // NS: wavefronts per instance (each takes NB_ALL / NS of the 16-column blocks)
-template <int MB, int NB_ALL, int KB, int NS, bool A_KC, bool B_KC, bool FULL>
+template <typename T, int MB, int NB_ALL, int KB, int NS, bool A_KC, bool B_KC, bool FULL>
 __global__ __launch_bounds__(256) void batched_wave_kernel(const BatchedArgs a)
 {
+    using V = typename Vec4<T>::type;
     constexpr int NB = NB_ALL / NS;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
     const int64_t gw = static_cast<int64_t>(blockIdx.x) * 4 + wave;
@@ -80,9 +104,9 @@ __global__ __launch_bounds__(256) void batched_wave_kernel(const BatchedArgs a)
     if (inst >= a.batch) return;
     // generic form: five wave-uniform scalar loads per instance; strided form: none
     const float alpha = a.strided ? a.alpha : a.alphas[inst], beta = a.strided ? a.beta : a.betas[inst];
-    const float *__restrict__ A = a.A + (a.strided ? inst * a.stride_a : a.a_off[inst]);
-    const float *__restrict__ B = a.B + (a.strided ? inst * a.stride_b : a.b_off[inst]);
-    float *__restrict__ C = a.C + (a.strided ? inst * a.stride_c : a.c_off[inst]);
+    const T *__restrict__ A = static_cast<const T *>(a.A) + (a.strided ? inst * a.stride_a : a.a_off[inst]);
+    const T *__restrict__ B = static_cast<const T *>(a.B) + (a.strided ? inst * a.stride_b : a.b_off[inst]);
+    T *__restrict__ C = static_cast<T *>(a.C) + (a.strided ? inst * a.stride_c : a.c_off[inst]);
     const int lane = threadIdx.x % 64, r16 = lane % 16, g = lane / 16;
 
     floatx4 acc[NB][MB];
@@ -92,37 +116,29 @@ __global__ __launch_bounds__(256) void batched_wave_kernel(const BatchedArgs a)
         for (int bi = 0; bi < MB; ++bi) acc[bj][bi] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     // C_old first (longest latency chain ends in the store), then the operands
-    floatx4 cold[NB][MB];
+    V cold[NB][MB];
     if (beta != 0.f) {
 #pragma unroll
         for (int bj = 0; bj < NB; ++bj)
 #pragma unroll
-            for (int bi = 0; bi < MB; ++bi) cold[bj][bi] = load4<true, FULL>(C, a.ldc, col0 + bj * 16 + r16, bi * 16 + 4 * g, a.n, a.m);
+            for (int bi = 0; bi < MB; ++bi) cold[bj][bi] = load4<T, true, FULL>(C, a.ldc, col0 + bj * 16 + r16, bi * 16 + 4 * g, a.n, a.m);
     }
 
     if (alpha != 0.f) {     // alpha == 0: A and B are not read at all
-        floatx4 av[MB][KB], bv[NB][KB];
+        V av[MB][KB], bv[NB][KB];
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
 #pragma unroll
-            for (int bi = 0; bi < MB; ++bi) av[bi][kb] = load4<A_KC, FULL>(A, a.lda, bi * 16 + r16, kb * 16 + 4 * g, a.m, a.k);
+            for (int bi = 0; bi < MB; ++bi) av[bi][kb] = load4<T, A_KC, FULL>(A, a.lda, bi * 16 + r16, kb * 16 + 4 * g, a.m, a.k);
 #pragma unroll
-            for (int bj = 0; bj < NB; ++bj) bv[bj][kb] = load4<B_KC, FULL>(B, a.ldb, col0 + bj * 16 + r16, kb * 16 + 4 * g, a.n, a.k);
+            for (int bj = 0; bj < NB; ++bj) bv[bj][kb] = load4<T, B_KC, FULL>(B, a.ldb, col0 + bj * 16 + r16, kb * 16 + 4 * g, a.n, a.k);
         }
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
             for (int bj = 0; bj < NB; ++bj)
 #pragma unroll
-                for (int bi = 0; bi < MB; ++bi) {
-                    floatx4 c = acc[bj][bi];
-                    const floatx4 x = av[bi][kb], y = bv[bj][kb];
-                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.x, y.x, c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.y, y.y, c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.z, y.z, c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.w, y.w, c, 0, 0, 0);
-                    acc[bj][bi] = c;
-                }
+                for (int bi = 0; bi < MB; ++bi) acc[bj][bi] = block_mma(av[bi][kb], bv[bj][kb], acc[bj][bi]);
     }
 
     // lane (r16, g) holds C(i = 16 bi + 4g + r, j = 16 bj + r16), r = 0..3: four consecutive rows of one column
@@ -132,24 +148,25 @@ __global__ __launch_bounds__(256) void batched_wave_kernel(const BatchedArgs a)
         for (int bi = 0; bi < MB; ++bi) {
             const int j = col0 + bj * 16 + r16, i0 = bi * 16 + 4 * g;
             floatx4 o = alpha * acc[bj][bi];
-            if (beta != 0.f) o += beta * cold[bj][bi];
-            float *p = C + i0 + j * a.ldc;
+            if (beta != 0.f) o += beta * widen(cold[bj][bi]);
+            T *p = C + i0 + j * a.ldc;
             if (FULL || (j < a.n && i0 + 3 < a.m)) {
-                *reinterpret_cast<Float4U *>(p) = Float4U{o.x, o.y, o.z, o.w};
+                *reinterpret_cast<Quad<T> *>(p) = Quad<T>{static_cast<T>(o.x), static_cast<T>(o.y), static_cast<T>(o.z), static_cast<T>(o.w)};
             } else if (j < a.n) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    if (i0 + r < a.m) p[r] = o[r];
+                    if (i0 + r < a.m) p[r] = static_cast<T>(o[r]);
             }
         }
 }
 
 // ---------------------------------------------------------------------------------- host side
 
-template <int MB, int NB, int KB, int NS, bool A_KC, bool B_KC, bool FULL> struct WaveConfig {
+template <typename T, int MB, int NB, int KB, int NS, bool A_KC, bool B_KC, bool FULL> struct WaveConfig {
+    static constexpr int DTYPE = sizeof(T) == 4 ? MG_F32 : MG_F16;
     static bool legal(const BatchedProblem &p)
     {
-        if (p.a_trans != A_KC || p.b_trans == B_KC) return false;
+        if (p.dtype != DTYPE || p.a_trans != A_KC || p.b_trans == B_KC) return false;
         if (p.m > 16 * MB || p.n > 16 * NB || p.k > 16 * KB) return false;
         if (FULL && (p.m != 16 * MB || p.n != 16 * NB || p.k != 16 * KB)) return false;
         if (p.batch * NS >= (int64_t(1) << 32)) return false;
@@ -162,7 +179,7 @@ template <int MB, int NB, int KB, int NS, bool A_KC, bool B_KC, bool FULL> struc
         BatchedArgs a{p.A, p.B, p.C, p.a_off, p.b_off, p.c_off, p.alphas, p.betas, p.lda, p.ldb, p.ldc,
                       static_cast<int>(p.m), static_cast<int>(p.n), static_cast<int>(p.k), p.batch,
                       p.strided ? 1 : 0, p.stride_a, p.stride_b, p.stride_c, p.alpha, p.beta};
-        hipLaunchKernelGGL((batched_wave_kernel<MB, NB, KB, NS, A_KC, B_KC, FULL>),
+        hipLaunchKernelGGL((batched_wave_kernel<T, MB, NB, KB, NS, A_KC, B_KC, FULL>),
                            dim3(static_cast<unsigned>(ceil_div(p.batch * NS, 4))), dim3(256), 0, p.stream, a);
         return hipGetLastError();
     }
@@ -170,7 +187,7 @@ template <int MB, int NB, int KB, int NS, bool A_KC, bool B_KC, bool FULL> struc
     {
         mg_config c{};
         c.family = MG_FAMILY_BATCHED;
-        c.dtype = MG_F32;
+        c.dtype = DTYPE;
         c.tile_m = 16 * MB; c.tile_n = 16 * NB; c.tile_k = 16 * KB;
         c.waves_m = 1; c.waves_n = NS;
         c.split_k = 1;
@@ -180,21 +197,24 @@ template <int MB, int NB, int KB, int NS, bool A_KC, bool B_KC, bool FULL> struc
     }
 };
 
-#define MG_BATCHED_REGISTER(table, tag, B, NS)                                                    \
-    table.push_back(WaveConfig<B, B, B, NS, false, true, true>::entry(tag "_mk_full"));           \
-    table.push_back(WaveConfig<B, B, B, NS, false, true, false>::entry(tag "_mk"));               \
-    table.push_back(WaveConfig<B, B, B, NS, true, true, false>::entry(tag "_kk"));                \
-    table.push_back(WaveConfig<B, B, B, NS, false, false, false>::entry(tag "_mn"));              \
-    table.push_back(WaveConfig<B, B, B, NS, true, false, false>::entry(tag "_kn"));
+#define MG_BATCHED_REGISTER(table, T, tag, B, NS)                                                    \
+    table.push_back(WaveConfig<T, B, B, B, NS, false, true, true>::entry(tag "_mk_full"));           \
+    table.push_back(WaveConfig<T, B, B, B, NS, false, true, false>::entry(tag "_mk"));               \
+    table.push_back(WaveConfig<T, B, B, B, NS, true, true, false>::entry(tag "_kk"));                \
+    table.push_back(WaveConfig<T, B, B, B, NS, false, false, false>::entry(tag "_mn"));              \
+    table.push_back(WaveConfig<T, B, B, B, NS, true, false, false>::entry(tag "_kn"));
 
 }  // namespace
 
 void register_batched(std::vector<KernelEntry> &table)
 {
-    MG_BATCHED_REGISTER(table, "batched_wave_16", 1, 1)
-    MG_BATCHED_REGISTER(table, "batched_wave_32", 2, 1)
-    MG_BATCHED_REGISTER(table, "batched_wave_64", 4, 4)
-    MG_BATCHED_REGISTER(table, "batched_wave_64w1", 4, 1)
+    MG_BATCHED_REGISTER(table, float, "batched_wave_16", 1, 1)
+    MG_BATCHED_REGISTER(table, float, "batched_wave_32", 2, 1)
+    MG_BATCHED_REGISTER(table, float, "batched_wave_64", 4, 4)
+    MG_BATCHED_REGISTER(table, float, "batched_wave_64w1", 4, 1)
+    MG_BATCHED_REGISTER(table, _Float16, "hbatched_wave_16", 1, 1)
+    MG_BATCHED_REGISTER(table, _Float16, "hbatched_wave_32", 2, 1)
+    MG_BATCHED_REGISTER(table, _Float16, "hbatched_wave_64w1", 4, 1)
 }
 
 }  // namespace mg

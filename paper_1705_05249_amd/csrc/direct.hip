@@ -104,12 +104,13 @@ __global__ __launch_bounds__(256) void scale_kernel(int64_t m, int64_t n, T *__r
     }
 }
 
+template <typename T>
 __global__ __launch_bounds__(256) void direct_batched_kernel(int64_t m, int64_t n, int64_t k,
-                                                              const float *__restrict__ A,
+                                                              const T *__restrict__ A,
                                                               const int64_t *__restrict__ a_off, int64_t a_sm,
-                                                              int64_t a_sk, const float *__restrict__ B,
+                                                              int64_t a_sk, const T *__restrict__ B,
                                                               const int64_t *__restrict__ b_off, int64_t b_sk,
-                                                              int64_t b_sn, float *__restrict__ C,
+                                                              int64_t b_sn, T *__restrict__ C,
                                                               const int64_t *__restrict__ c_off, int64_t ldc,
                                                               const float *__restrict__ alphas,
                                                               const float *__restrict__ betas, int64_t tiles_m,
@@ -124,7 +125,7 @@ __global__ __launch_bounds__(256) void direct_batched_kernel(int64_t m, int64_t 
     const int64_t ob = strided ? inst * stride_b : b_off[inst];
     const int64_t oc = strided ? inst * stride_c : c_off[inst];
     // alpha == 0: A and B must not contribute (they may hold NaN/Inf) -> run with k = 0
-    direct_tile<float>(m, n, alpha == 0.f ? 0 : k, A + oa, a_sm, a_sk, B + ob, b_sk, b_sn, C + oc, ldc, alpha, beta,
+    direct_tile<T>(m, n, alpha == 0.f ? 0 : k, A + oa, a_sm, a_sk, B + ob, b_sk, b_sn, C + oc, ldc, alpha, beta,
                        t % tiles_m, t / tiles_m);
 }
 
@@ -159,18 +160,19 @@ bool scale_legal(const Problem &p, int split_k, int64_t)
     return split_k == 1 && (p.alpha == 0.f || p.k == 0) && ceil_div(p.m, 256) < (int64_t(1) << 31);
 }
 
-bool batched_direct_legal(const BatchedProblem &p)
+template <typename T> bool batched_direct_legal(const BatchedProblem &p)
 {
-    return ceil_div(p.m, DT) * ceil_div(p.n, DT) * p.batch < (int64_t(1) << 31);
+    return p.dtype == (sizeof(T) == 4 ? MG_F32 : MG_F16) && ceil_div(p.m, DT) * ceil_div(p.n, DT) * p.batch < (int64_t(1) << 31);
 }
 
-hipError_t launch_batched_direct(const BatchedProblem &p)
+template <typename T> hipError_t launch_batched_direct(const BatchedProblem &p)
 {
     const int64_t tiles_m = ceil_div(p.m, DT), tiles_n = ceil_div(p.n, DT);
     const int64_t tiles = tiles_m * tiles_n;
-    hipLaunchKernelGGL(direct_batched_kernel, dim3(static_cast<unsigned>(tiles * p.batch)), dim3(256), 0, p.stream,
-                       p.m, p.n, p.k, p.A, p.a_off, p.a_trans ? p.lda : 1, p.a_trans ? 1 : p.lda, p.B, p.b_off,
-                       p.b_trans ? p.ldb : 1, p.b_trans ? 1 : p.ldb, p.C, p.c_off, p.ldc, p.alphas, p.betas,
+    hipLaunchKernelGGL(direct_batched_kernel<T>, dim3(static_cast<unsigned>(tiles * p.batch)), dim3(256), 0, p.stream,
+                       p.m, p.n, p.k, static_cast<const T *>(p.A), p.a_off, p.a_trans ? p.lda : 1, p.a_trans ? 1 : p.lda,
+                       static_cast<const T *>(p.B), p.b_off, p.b_trans ? p.ldb : 1, p.b_trans ? 1 : p.ldb,
+                       static_cast<T *>(p.C), p.c_off, p.ldc, p.alphas, p.betas,
                        tiles_m, tiles, p.strided ? 1 : 0, p.stride_a, p.stride_b, p.stride_c, p.alpha, p.beta);
     return hipGetLastError();
 }
@@ -205,7 +207,9 @@ void register_direct(std::vector<KernelEntry> &table)
     table.push_back({"scale_f16", make_cfg(MG_FAMILY_SCALE, MG_F16, 256, 1, 0, 0), scale_legal, no_workspace,
                      launch_scale<_Float16>, nullptr, nullptr});
     table.push_back({"batched_direct_f32_64x64x16", make_cfg(MG_FAMILY_BATCHED, MG_F32, DT, DT, DK, lds), nullptr,
-                     nullptr, nullptr, batched_direct_legal, launch_batched_direct});
+                     nullptr, nullptr, batched_direct_legal<float>, launch_batched_direct<float>});
+    table.push_back({"batched_direct_f16_64x64x16", make_cfg(MG_FAMILY_BATCHED, MG_F16, DT, DT, DK, lds), nullptr,
+                     nullptr, nullptr, batched_direct_legal<_Float16>, launch_batched_direct<_Float16>});
 }
 
 }  // namespace mg

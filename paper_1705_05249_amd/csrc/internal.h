@@ -40,20 +40,21 @@ struct Problem {
     size_t elem() const { return dtype == MG_F32 ? 4 : 2; }
 };
 
-// Canonical batched problem (FP32).  Generic form: per-instance scalars and element offsets live on the
+// Canonical batched problem.  Generic form: per-instance scalars and element offsets live on the
 // device.  Strided form (strided == true): the offset and scalar arrays are null, instance b sits at
 // b * stride_x and uses the host scalars alpha, beta.
 struct BatchedProblem {
+    int dtype;                 // mg_dtype of A, B, C (scalars are FP32 either way)
     int64_t m, n, k;
-    const float *A;
+    const void *A;
     const int64_t *a_off;
     int64_t lda;
     bool a_trans;
-    const float *B;
+    const void *B;
     const int64_t *b_off;
     int64_t ldb;
     bool b_trans;
-    float *C;
+    void *C;
     const int64_t *c_off;
     int64_t ldc;
     const float *alphas, *betas;

@@ -113,17 +113,18 @@ int32_t select_batched(const std::vector<KernelEntry> &table, const BatchedProbl
 {
     // one wavefront per instance while the instance fits the register blocks (<= 64 in every extent)
     static const char *const tags[] = {"batched_wave_16", "batched_wave_32", "batched_wave_64w1"};
+    const char *prefix = p.dtype == MG_F32 ? "" : "h";
     const char *contig = p.a_trans ? (p.b_trans ? "kn" : "kk") : (p.b_trans ? "mn" : "mk");
     for (const char *tag : tags) {
         char name[96];
-        snprintf(name, sizeof name, "%s_%s_full", tag, contig);
+        snprintf(name, sizeof name, "%s%s_%s_full", prefix, tag, contig);
         int32_t id = find(table, name);
         if (id >= 0 && table[id].legal_batched(p)) return id;
-        snprintf(name, sizeof name, "%s_%s", tag, contig);
+        snprintf(name, sizeof name, "%s%s_%s", prefix, tag, contig);
         id = find(table, name);
         if (id >= 0 && table[id].legal_batched(p)) return id;
     }
-    const int32_t id = find(table, "batched_direct_f32_64x64x16");
+    const int32_t id = find(table, p.dtype == MG_F32 ? "batched_direct_f32_64x64x16" : "batched_direct_f16_64x64x16");
     if (id >= 0 && table[id].legal_batched(p)) return id;
     return -1;
 }

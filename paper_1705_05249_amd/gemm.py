@@ -17,7 +17,8 @@ MG_F32, MG_F16 = 0, 1
 MG_OK = 0
 MG_FAMILY_DIRECT, MG_FAMILY_MFMA, MG_FAMILY_GEMV, MG_FAMILY_SCALE, MG_FAMILY_BATCHED = 0, 1, 2, 3, 4
 
-EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemm_batched", "mg_sgemm_strided_batched", "mg_gemm_workspace_bytes",
+EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemm_batched", "mg_sgemm_strided_batched", "mg_hgemm_batched",
+           "mg_hgemm_strided_batched", "mg_gemm_workspace_bytes",
            "mg_sim2col", "mg_him2col", "mg_sconv2d", "mg_hconv2d", "mg_conv2d_workspace_bytes", "mg_conv2d_out_extent",
            "mg_kernel_count",
            "mg_kernel_info", "mg_kernel_name", "mg_query_selected", "mg_override_config",
@@ -69,6 +70,10 @@ def lib():
         L.mg_sgemm_strided_batched.argtypes = [i32, i32, i32, i64, i64, i64, f32, vp, i64, i64, vp, i64, i64, f32, vp,
                                                i64, i64, i64, vp]
         L.mg_sgemm_strided_batched.restype = i32
+        L.mg_hgemm_batched.argtypes = L.mg_sgemm_batched.argtypes
+        L.mg_hgemm_batched.restype = i32
+        L.mg_hgemm_strided_batched.argtypes = L.mg_sgemm_strided_batched.argtypes
+        L.mg_hgemm_strided_batched.restype = i32
         L.mg_gemm_workspace_bytes.argtypes = [i32, i32, i32, i32, i64, i64, i64, i64, i64, i64]
         L.mg_gemm_workspace_bytes.restype = sz
         geometry = [i64] * 11
@@ -160,6 +165,25 @@ def mg_sgemm_batched(layout, trans_a, trans_b, m, n, k, alphas, A, a_offsets, ld
                                 batch_count, _stream(stream))
     if check and st != MG_OK:
         raise MgError(st, "mg_sgemm_batched")
+    return st
+
+
+def mg_hgemm_batched(layout, trans_a, trans_b, m, n, k, alphas, A, a_offsets, lda, B, b_offsets, ldb, betas, C,
+                     c_offsets, ldc, batch_count, stream=None, check=True) -> int:
+    st = lib().mg_hgemm_batched(layout, trans_a, trans_b, m, n, k, _addr(alphas), _addr(A), _addr(a_offsets), lda,
+                                _addr(B), _addr(b_offsets), ldb, _addr(betas), _addr(C), _addr(c_offsets), ldc,
+                                batch_count, _stream(stream))
+    if check and st != MG_OK:
+        raise MgError(st, "mg_hgemm_batched")
+    return st
+
+
+def mg_hgemm_strided_batched(layout, trans_a, trans_b, m, n, k, alpha, A, lda, stride_a, B, ldb, stride_b, beta, C,
+                             ldc, stride_c, batch_count, stream=None, check=True) -> int:
+    st = lib().mg_hgemm_strided_batched(layout, trans_a, trans_b, m, n, k, alpha, _addr(A), lda, stride_a, _addr(B),
+                                        ldb, stride_b, beta, _addr(C), ldc, stride_c, batch_count, _stream(stream))
+    if check and st != MG_OK:
+        raise MgError(st, "mg_hgemm_strided_batched")
     return st
 
 

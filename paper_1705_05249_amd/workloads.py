@@ -369,7 +369,7 @@ def config4(size: int, batch: int) -> BatchedCase:
     return batched_case(size, size, size, batch, case=size * 100000 + batch, name=f"c4_s{size}_b{batch}")
 
 
-def config4_fast(size: int, batch: int) -> BatchedCase:
+def config4_fast(size: int, batch: int, dtype: str = "f32") -> BatchedCase:
     """same layout and distributions as config4, drawn with whole-array calls (for the
     benchmark, where 10000 per-instance draws would dominate set-up time)"""
     g = rng_for(4, size * 100000 + batch + 7)
@@ -378,14 +378,14 @@ def config4_fast(size: int, batch: int) -> BatchedCase:
     off = (np.arange(batch, dtype=np.int64) * stride)
     bufs = []
     for fill in (np.nan, np.nan, GAP_FILL):
-        buf = np.full((batch, stride), fill, dtype=np.float32)
-        buf[:, :per] = g.uniform(-1.0, 1.0, size=(batch, per)).astype(np.float32)
+        buf = np.full((batch, stride), fill, dtype=_np_dtype(dtype))
+        buf[:, :per] = g.uniform(-1.0, 1.0, size=(batch, per)).astype(np.float32).astype(_np_dtype(dtype))
         bufs.append(buf.reshape(-1))
     alphas = g.uniform(0.5, 2.0, size=batch).astype(np.float32)
     betas = g.uniform(0.5, 2.0, size=batch).astype(np.float32)
-    return BatchedCase(f"c4_s{size}_b{batch}", COL_MAJOR, NO_TRANS, NO_TRANS, size, size, size,
-                       alphas, betas, bufs[0], off.copy(), size, bufs[1], off.copy(), size,
-                       bufs[2], off.copy(), size, batch)
+    return BatchedCase(f"c4_s{size}_b{batch}" + ("" if dtype == "f32" else "_f16"), COL_MAJOR, NO_TRANS, NO_TRANS, size,
+                       size, size, alphas, betas, bufs[0], off.copy(), size, bufs[1], off.copy(), size,
+                       bufs[2], off.copy(), size, batch, dtype)
 
 
 # ----------------------------------------------------------------------------- group 5

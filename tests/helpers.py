@@ -88,9 +88,9 @@ def run_batched_gpu(bc, check=True):
     import torch
     from paper_1705_05249_amd import gemm as G
     t = {name: to_gpu(getattr(bc, name)) for name in ("A", "B", "C", "a_off", "b_off", "c_off", "alphas", "betas")}
-    st = G.mg_sgemm_batched(bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, t["alphas"], t["A"], t["a_off"], bc.lda,
-                            t["B"], t["b_off"], bc.ldb, t["betas"], t["C"], t["c_off"], bc.ldc, bc.batch,
-                            check=check)
+    fn = G.mg_sgemm_batched if bc.dtype == "f32" else G.mg_hgemm_batched
+    st = fn(bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, t["alphas"], t["A"], t["a_off"], bc.lda, t["B"], t["b_off"],
+            bc.ldb, t["betas"], t["C"], t["c_off"], bc.ldc, bc.batch, check=check)
     torch.cuda.synchronize()
     return st, t["C"].cpu().numpy()
 
@@ -113,13 +113,13 @@ def check_batched(bc, oracle, exact=False):
     assert st == 0
     mats, mask = batched_outputs(bc, out)
     assert np.array_equal(bits(out)[mask], bits(bc.C)[mask]), f"{bc.name}: gap / padding bytes were written"
-    c_ref, d_ref = oracle.sgemm_batched(bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, bc.alphas, bc.A, bc.a_off,
-                                        bc.lda, bc.B, bc.b_off, bc.ldb, bc.betas, bc.C, bc.c_off, bc.ldc)
+    c_ref, d_ref = oracle.gemm_batched(bc.dtype, bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, bc.alphas, bc.A, bc.a_off,
+                                       bc.lda, bc.B, bc.b_off, bc.ldb, bc.betas, bc.C, bc.c_off, bc.ldc)
     if exact:
         assert np.array_equal(mats.astype(np.float64), c_ref), f"{bc.name}: not bit-exact on integer inputs"
         return 0.0
     err = rel_error(mats, c_ref, d_ref)
-    assert err <= TOL["f32"], f"{bc.name}: relative error {err:.3e}"
+    assert err <= TOL[bc.dtype], f"{bc.name}: relative error {err:.3e}"
     return err
 
 

@@ -168,6 +168,58 @@ def test_batched_alpha_zero_and_beta_zero_per_instance(G, oracle):
     assert H.rel_error(mats, c_ref, d_ref) <= H.TOL["f32"]
 
 
+# ------------------------------------------------------------------ FP16-storage batched GEMM
+
+@pytest.mark.parametrize("size", W.CONFIG4_SIZES)
+def test_half_batched_workload_sizes(G, oracle, size):
+    """the batched workload's shapes (s = 8, 16, 32, 64; 1000 instances, 7-element gaps) in FP16 storage"""
+    bc = W.batched_case(size, size, size, 1000, case=size, dtype="f16")
+    announce(bc.name)
+    H.check_batched(bc, oracle)
+
+
+@pytest.mark.parametrize("layout,ta,tb", VARIANTS)
+def test_half_batched_variants_ragged_exact(G, oracle, layout, ta, tb):
+    for (m, n, k, batch, pad) in ((5, 7, 6, 9, 0), (16, 16, 16, 33, 0), (33, 17, 70, 5, 3), (64, 64, 64, 3, 1),
+                                  (70, 130, 9, 2, 0), (1, 1, 1, 4, 0)):
+        bc = W.batched_case(m, n, k, batch, case=m * n + k, layout=layout, ta=ta, tb=tb, integer=True,
+                            shuffle_offsets=True, dtype="f16",
+                            lda=W.tight_ld(layout, ta, m, k) + pad, ldb=W.tight_ld(layout, tb, k, n) + 2 * pad,
+                            ldc=W.tight_ld(layout, N, m, n) + pad)
+        announce(bc.name, layout, ta, tb)
+        H.check_batched(bc, oracle, exact=True)
+
+
+@pytest.mark.parametrize("layout,ta,tb", [(C, N, N), (R, T, N), (C, T, T)])
+@pytest.mark.parametrize("shape", [(16, 16, 16, 300), (33, 20, 70, 9), (64, 64, 64, 5)])
+def test_half_strided_batched(G, oracle, layout, ta, tb, shape):
+    import torch
+    m, n, k, batch = shape
+    bc = W.batched_case(m, n, k, batch, case=m + n + k, layout=layout, ta=ta, tb=tb, integer=True, dtype="f16")
+    sa, sb, sc = (int(x[1] - x[0]) for x in (bc.a_off, bc.b_off, bc.c_off))
+    alpha, beta = 1.5, 0.5
+    A, B, Cs = H.to_gpu(bc.A), H.to_gpu(bc.B), H.to_gpu(bc.C)
+    announce("strided f16", bc.name, layout, ta, tb)
+    G.mg_hgemm_strided_batched(layout, ta, tb, m, n, k, alpha, A, bc.lda, sa, B, bc.ldb, sb, beta, Cs, bc.ldc, sc, batch)
+    torch.cuda.synchronize()
+    out = Cs.cpu().numpy()
+    mats, mask = H.batched_outputs(bc, out)
+    assert np.array_equal(H.bits(out)[mask], H.bits(bc.C)[mask])
+    c_ref, _ = oracle.gemm_strided_batched("f16", layout, ta, tb, m, n, k, alpha, bc.A, bc.lda, sa, bc.B, bc.ldb, sb,
+                                           beta, bc.C, bc.ldc, sc, batch)
+    assert np.array_equal(mats.astype(np.float64), c_ref)
+
+
+def test_half_batched_per_instance_conventions(G, oracle):
+    """alpha_i == 0 skips A and B (NaN there), beta_i == 0 skips C (NaN there), per instance"""
+    bc = W.batched_case(16, 16, 16, 6, case=77, integer=True, dtype="f16")
+    bc.alphas[1] = 0.0
+    bc.A[bc.a_off[1]: bc.a_off[1] + 256] = np.nan
+    bc.betas[2] = 0.0
+    bc.C[bc.c_off[2]: bc.c_off[2] + 256] = np.nan
+    H.check_batched(bc, oracle, exact=True)
+
+
 # ------------------------------------------------------------------ strided batched (same data as the generic form)
 
 @pytest.mark.parametrize("layout,ta,tb", VARIANTS)
@@ -367,9 +419,12 @@ def test_every_batched_configuration_gives_parity(G, oracle):
     ran = {t["name"]: 0 for t in kernels}
     try:
         for (s, batch) in ((8, 50), (16, 70), (32, 20), (64, 9), (24, 5)):
-            for layout, ta, tb in ((C, N, N), (R, N, N), (C, T, T), (C, T, N), (C, N, T)):
-                bc = W.batched_case(s, s, s, batch, case=s, layout=layout, ta=ta, tb=tb, integer=True)
+            for layout, ta, tb, dtype in [(*v, d) for v in ((C, N, N), (R, N, N), (C, T, T), (C, T, N), (C, N, T))
+                                          for d in ("f32", "f16")]:
+                bc = W.batched_case(s, s, s, batch, case=s, layout=layout, ta=ta, tb=tb, integer=True, dtype=dtype)
                 for t in kernels:
+                    if t["dtype"] != (G.MG_F32 if dtype == "f32" else G.MG_F16):
+                        continue
                     G.mg_override_batched_config(t["kernel_id"])
                     announce(t["name"], bc.name, layout, ta, tb)
                     try:
