@@ -71,12 +71,14 @@ def test_quick_returns_launch_nothing(fn):
 
 
 def batched(m=4, n=4, k=4, batch=3, alphas=FAKE, betas=FAKE, A=FAKE, B=FAKE, Cp=FAKE, ao=FAKE, bo=FAKE, co=FAKE,
-            layout=C, ta=N, tb=N, lda=4, ldb=4, ldc=4):
-    return G.mg_sgemm_batched(layout, ta, tb, m, n, k, alphas, A, ao, lda, B, bo, ldb, betas, Cp, co, ldc, batch, stream=0,
+            layout=C, ta=N, tb=N, lda=4, ldb=4, ldc=4, fn=None):
+    return (fn or G.mg_sgemm_batched)(layout, ta, tb, m, n, k, alphas, A, ao, lda, B, bo, ldb, betas, Cp, co, ldc, batch, stream=0,
                               check=False)
 
 
-def test_batched_argument_errors():
+@pytest.mark.parametrize("fn", [G.mg_sgemm_batched, G.mg_hgemm_batched])
+def test_batched_argument_errors(fn):
+    batched = lambda **kw: globals()["batched"](fn=fn, **kw)
     assert batched(layout=7) == -1
     assert batched(ta=1) == -2
     assert batched(tb=1) == -3
@@ -92,12 +94,14 @@ def test_batched_argument_errors():
 
 
 def strided(m=4, n=4, k=4, batch=3, A=FAKE, B=FAKE, Cp=FAKE, sa=16, sb=16, sc=16, layout=C, ta=N, tb=N, lda=4, ldb=4,
-            ldc=4, alpha=1.0, beta=1.0):
-    return G.mg_sgemm_strided_batched(layout, ta, tb, m, n, k, alpha, A, lda, sa, B, ldb, sb, beta, Cp, ldc, sc, batch,
+            ldc=4, alpha=1.0, beta=1.0, fn=None):
+    return (fn or G.mg_sgemm_strided_batched)(layout, ta, tb, m, n, k, alpha, A, lda, sa, B, ldb, sb, beta, Cp, ldc, sc, batch,
                                       stream=0, check=False)
 
 
-def test_strided_batched_argument_errors():
+@pytest.mark.parametrize("fn", [G.mg_sgemm_strided_batched, G.mg_hgemm_strided_batched])
+def test_strided_batched_argument_errors(fn):
+    strided = lambda **kw: globals()["strided"](fn=fn, **kw)
     assert strided(layout=7) == -1
     assert strided(ta=1) == -2
     assert strided(tb=1) == -3
