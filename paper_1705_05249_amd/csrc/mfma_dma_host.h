@@ -11,40 +11,26 @@ template <int BM, int BN, int WM, int WN, bool AK, bool BKC, int RB = 32> struct
     static constexpr int NT = WM * WN * 64;
     static constexpr int LDS = Staged::LDS;
 
+    // the direct-to-LDS loads keep the 16-byte alignment of whole chunks
+    static bool legal(const Problem &p, int split, int64_t alignment)
+    {
+        if (!Staged::legal(p, split, alignment)) return false;
+        if (p.lda % 8 || p.ldb % 8) return false;
+        if (pointer_alignment(p.A) < 16 || pointer_alignment(p.B) < 16) return false;
+        return p.A != nullptr || alignment >= 16;
+    }
+
     static hipError_t launch(const Problem &p, int split)
     {
         static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; races are harmless
-        auto kernel = hgemm_dma_kernel<BM, BN, WM, WN, AK, BKC, RB>;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
-        MfmaArgs a{};
-        a.A = p.A; a.B = p.B; a.C = p.C;
-        a.partial = split > 1 ? static_cast<float *>(p.workspace) : nullptr;
-        a.lda = p.lda; a.ldb = p.ldb; a.ldc = p.ldc;
-        a.m = static_cast<int>(p.m); a.n = static_cast<int>(p.n); a.k = static_cast<int>(p.k);
-        a.alpha = p.alpha; a.beta = p.beta;
-        a.tiles_m = static_cast<int>(ceil_div(p.m, BM));
-        a.tiles_n = static_cast<int>(ceil_div(p.n, BN));
-        a.k_per_split = Staged::k_per_split(p, split);
-        a.group_m = 8;
-        hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(a.tiles_m) * a.tiles_n, 1, split), dim3(NT), LDS,
-                           p.stream, a);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess || split == 1) return e;
-        const int64_t total = p.m * p.n;
-        const unsigned blocks = static_cast<unsigned>(total / 256 + 1 < 4096 ? total / 256 + 1 : 4096);
-        hipLaunchKernelGGL(splitk_reduce_kernel<_Float16>, dim3(blocks), dim3(256), 0, p.stream, a.partial, split, a.m,
-                           a.n, static_cast<_Float16 *>(p.C), p.ldc, p.alpha, p.beta);
-        return hipGetLastError();
+        return launch_tile_kernel<_Float16>(hgemm_dma_kernel<BM, BN, WM, WN, AK, BKC, RB>, &attr_set, LDS, NT, BM, BN,
+                                            Staged::k_per_split(p, split), p, split);
     }
 
     static KernelEntry entry(const char *name)
     {
         KernelEntry e = Staged::entry(name);
+        e.legal = legal;
         e.launch = launch;
         return e;
     }

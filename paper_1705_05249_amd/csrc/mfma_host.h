@@ -5,6 +5,39 @@
 
 namespace mg {
 
+// Launches a macro-tile kernel over ceil(m/BM) x ceil(n/BN) tiles and `split` K slices, then (split > 1) the
+// kernel that sums the FP32 partials in the workspace and applies alpha and beta.
+template <typename T, typename Kernel>
+hipError_t launch_tile_kernel(Kernel kernel, bool *attr_set, int lds_bytes, int threads, int bm, int bn, int k_per_split,
+                              const Problem &p, int split)
+{
+    if (!*attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        *attr_set = true;
+    }
+    MfmaArgs a{};
+    a.A = p.A; a.B = p.B; a.C = p.C;
+    a.partial = split > 1 ? static_cast<float *>(p.workspace) : nullptr;
+    a.lda = p.lda; a.ldb = p.ldb; a.ldc = p.ldc;
+    a.m = static_cast<int>(p.m); a.n = static_cast<int>(p.n); a.k = static_cast<int>(p.k);
+    a.alpha = p.alpha; a.beta = p.beta;
+    a.tiles_m = static_cast<int>(ceil_div(p.m, bm));
+    a.tiles_n = static_cast<int>(ceil_div(p.n, bn));
+    a.k_per_split = k_per_split;
+    a.group_m = 8;
+    hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(a.tiles_m) * a.tiles_n, 1, split), dim3(threads), lds_bytes,
+                       p.stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || split == 1) return e;
+    const int64_t total = p.m * p.n;
+    const unsigned blocks = static_cast<unsigned>(total / 256 + 1 < 4096 ? total / 256 + 1 : 4096);
+    hipLaunchKernelGGL(splitk_reduce_kernel<T>, dim3(blocks), dim3(256), 0, p.stream, a.partial, split, a.m, a.n,
+                       static_cast<T *>(p.C), p.ldc, p.alpha, p.beta);
+    return hipGetLastError();
+}
+
 template <typename T, int BM, int BN, int BK, int WM, int WN, bool AK, bool BKC, bool EDGE, int RB = 32> struct MfmaConfig {
     static constexpr int CH = ElemTraits<T>::CH;
     static constexpr int NT = WM * WN * 64;
@@ -32,10 +65,11 @@ template <typename T, int BM, int BN, int BK, int WM, int WN, bool AK, bool BKC,
             const int64_t span = (BM > BN ? BM : BN) > BK ? (BM > BN ? BM : BN) : BK;
             if ((p.lda > p.ldb ? p.lda : p.ldb) * span * static_cast<int64_t>(sizeof(T)) >= (int64_t(1) << 31)) return false;
             if (p.m % BM || p.n % BN || p.k % BK) return false;
-            if (p.lda % CH || p.ldb % CH) return false;
-            // A and B need 16-byte alignment; `alignment` is the minimum over A, B and C
-            if (pointer_alignment(p.A) < 16 || pointer_alignment(p.B) < 16) return false;
-            if (p.A == nullptr && alignment < 16) return false;      // query without pointers
+            // the 16-byte buffer loads need 4-byte aligned addresses only: rows may start anywhere on a dword
+            // boundary (odd leading dimensions of FP32 matrices, even ones of FP16 matrices)
+            if ((p.lda * sizeof(T)) % 4 || (p.ldb * sizeof(T)) % 4) return false;
+            if (pointer_alignment(p.A) < 4 || pointer_alignment(p.B) < 4) return false;
+            if (p.A == nullptr && alignment < 4) return false;       // query without pointers
         }
         return true;
     }
@@ -48,32 +82,8 @@ template <typename T, int BM, int BN, int BK, int WM, int WN, bool AK, bool BKC,
     static hipError_t launch(const Problem &p, int split)
     {
         static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; races are harmless
-        auto kernel = mfma_gemm_kernel<T, BM, BN, BK, WM, WN, AK, BKC, EDGE, RB>;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
-        MfmaArgs a{};
-        a.A = p.A; a.B = p.B; a.C = p.C;
-        a.partial = split > 1 ? static_cast<float *>(p.workspace) : nullptr;
-        a.lda = p.lda; a.ldb = p.ldb; a.ldc = p.ldc;
-        a.m = static_cast<int>(p.m); a.n = static_cast<int>(p.n); a.k = static_cast<int>(p.k);
-        a.alpha = p.alpha; a.beta = p.beta;
-        a.tiles_m = static_cast<int>(ceil_div(p.m, BM));
-        a.tiles_n = static_cast<int>(ceil_div(p.n, BN));
-        a.k_per_split = k_per_split(p, split);
-        a.group_m = 8;
-        hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(a.tiles_m) * a.tiles_n, 1, split), dim3(NT), LDS,
-                           p.stream, a);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess || split == 1) return e;
-        const int64_t total = p.m * p.n;
-        const unsigned blocks = static_cast<unsigned>(total / 256 + 1 < 4096 ? total / 256 + 1 : 4096);
-        hipLaunchKernelGGL(splitk_reduce_kernel<T>, dim3(blocks), dim3(256), 0, p.stream, a.partial, split, a.m, a.n,
-                           static_cast<T *>(p.C), p.ldc, p.alpha, p.beta);
-        return hipGetLastError();
+        return launch_tile_kernel<T>(mfma_gemm_kernel<T, BM, BN, BK, WM, WN, AK, BKC, EDGE, RB>, &attr_set, LDS, NT, BM, BN,
+                                     k_per_split(p, split), p, split);
     }
 
     static KernelEntry entry(const char *name)
