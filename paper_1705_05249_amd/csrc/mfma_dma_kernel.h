@@ -13,11 +13,13 @@
 //   * contiguous along k: [row][k], 128 bytes per row, chunk c of row r at slot c ^ ((r ^ r/8) % 8) -- the
 //     layout of the register-staged kernel; an MFMA operand is one 16-byte read per lane;
 //   * contiguous along its row index (m for A, n for B): [k][row] as in memory, 2 * ROWS bytes per k, the
-//     16-byte chunk c of line k at slot c ^ (2 * (k % 4)); an MFMA operand is two transposing 8-byte reads
+//     16-byte chunk c of line k at slot c ^ (4 * (k % 4)); an MFMA operand is two transposing 8-byte reads
 //     (ds_read_b64_tr_b16): in each group of 16 lanes, lane 4a + b receives element b of what lanes a, a + 4,
 //     a + 8, a + 12 fetched, so when those four lanes fetch the same four rows at four consecutive k, lane
-//     4a + b ends up with four consecutive k of row 4a + b.  The swizzle puts the four k lines of a group into
-//     four different 32-byte bank ranges.
+//     4a + b ends up with four consecutive k of row 4a + b.  The LDS serves 256 bytes per clock (64 banks),
+//     i.e. 32 lanes of such a read: two row groups of 32 bytes each at four k lines; the swizzle puts these
+//     eight 32-byte pieces on eight different bank ranges (with c ^ 2 (k % 4) the counters showed as many
+//     conflict cycles as useful ones).
 // Both forms give lane l the eight k values 16 s + 8 (l / 32) + 0..7 of row l % 32 in K-step s.
 //
 // Pipeline: two LDS stages.  During K-tile t (read from stage t % 2) the loads of tile t + 1 into the other
@@ -62,7 +64,7 @@ template <int ROWS, int NT, bool KCONTIG> struct DmaLoader {
                 g = r * ld * 2 + ((slot ^ ((r ^ (r >> 3)) & 7)) << 4);
             } else {
                 const int kl = o / (2 * ROWS), slot = (o / 16) % (ROWS / 8);
-                g = kl * ld * 2 + ((slot ^ (2 * (kl & 3))) << 4);
+                g = kl * ld * 2 + ((slot ^ (4 * (kl & 3))) << 4);
             }
             goff[Q] = static_cast<uint32_t>(g - imm(Q));
         });
@@ -82,20 +84,32 @@ template <int ROWS, int NT, bool KCONTIG> struct DmaLoader {
     }
 };
 
-// MFMA operand of fragment F (32 rows), K-step s, from an operand stage at byte offset `stage`; frag: the
-// lane's addresses prepared by the kernel (four for the k-contiguous layout, two for the other)
-template <bool KCONTIG, int ROWS, int F, int RB>
-__device__ inline u32x4 read_operand(lds_char *lds3, const int (&frag)[4], int s, int stage)
+// MFMA operand of fragment F (32 rows), K-step S, from an operand stage at byte offset STAGE; frag: the
+// lane's addresses prepared by the kernel (k-contiguous layout: one per swizzle phase; the other: one per fragment).
+//
+// The transposing reads are written as inline assembly: as a builtin, every one of them that follows a
+// direct-to-LDS load in program order gets an `s_waitcnt vmcnt(0)` from the compiler (it cannot tell that the
+// read does not touch the stage the load writes), which put the full memory latency of every load into the K
+// loop.  The price: the compiler does not know that these registers are written later, by the LDS, so the
+// kernel itself waits (wait_fragments) before the first MFMA of every K-step.
+template <bool KCONTIG, int ROWS, int F, int RB, int S, int STAGE>
+__device__ inline u32x4 read_operand(lds_char *lds3, const int (&frag)[4])
 {
     if constexpr (KCONTIG) {
         return *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(
-            lds3 + frag[frag_select<RB>(F, s)] + F * RB * 128 + stage);
+            lds3 + frag[frag_select<RB>(F, S)] + F * RB * 128 + STAGE);
     } else {
         static_assert(RB == 32, "the transposing reads are laid out for 32-row fragments");
+        static_assert(F < 4, "one address per fragment");
         constexpr int LINE = 2 * ROWS;                                    // bytes per k line
-        lds_char *at = lds3 + frag[F & 1] + (F >> 1) * 128 + s * (16 * LINE) + stage;
-        const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_shortx4 *>(at));
-        const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_shortx4 *>(at + 4 * LINE));
+        constexpr int OFFSET = S * (16 * LINE) + STAGE;
+        static_assert(OFFSET + 4 * LINE < 65536, "LDS instruction offsets have 16 bits");
+        const uint32_t at = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds3)) + static_cast<uint32_t>(frag[F]);
+        shortx4 lo, hi;
+        asm volatile("ds_read_b64_tr_b16 %0, %2 offset:%3\n\tds_read_b64_tr_b16 %1, %2 offset:%4"
+                     : "=&v"(lo), "=&v"(hi)
+                     : "v"(at), "n"(OFFSET), "n"(OFFSET + 4 * LINE)
+                     : "memory");
         return __builtin_bit_cast(u32x4, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     }
 }
@@ -133,7 +147,7 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 
     // ---- fragment addresses (bytes from the start of the LDS, stage 0); see the layouts above
-    int frag_a[4], frag_b[4];          // k-contiguous form: four addresses cover every (fragment, step); else [0], [1]
+    int frag_a[4], frag_b[4];          // k-contiguous form: four addresses cover every (fragment, step); else one per fragment
     auto frag_setup = [&](bool kcontig, int wrow, int operand_base, int rows, int (&frag)[4]) {
         if (kcontig) {
             const int x = frag_lane_x<RB>(lane, wrow);
@@ -142,11 +156,9 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
             // fetch role inside the group of 16 lanes: rows 4a .. 4a+3 of the group's 16 rows, k line j
             const int i = lane % 16, a = i % 4, j = i / 4, g = lane / 16;
             const int kl = 8 * (g / 2) + j;                                   // + 16 s + 4 h
-            const int slot = (wrow / 8 + 2 * (g % 2) + a / 2) ^ (2 * j);     // + 4 f by XOR: f odd flips byte bit 6
+            const int slot = (wrow / 8 + 2 * (g % 2) + a / 2) ^ (4 * j);     // fragment f adds 4 f under the same XOR
             const int p = operand_base + kl * (2 * rows) + slot * 16 + 8 * (a % 2);
-            frag[0] = p;
-            frag[1] = p ^ 64;
-            frag[2] = frag[3] = 0;
+            for (int f = 0; f < 4; ++f) frag[f] = p ^ (64 * f);
         }
     };
     frag_setup(A_KCONTIG, wm * WTM, 0, BM, frag_a);
@@ -187,11 +199,20 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
 
     u32x4 fa[2][FM], fb[2][FN];
     // fragment F of K-step s in stage `par`: F < FM -> A fragment F, else B fragment F - FM
-    auto read_frag = [&](auto F, auto PAR, int s, int buf) {
-        constexpr int f = decltype(F)::value, par = decltype(PAR)::value;
-        if constexpr (f < FM) fa[buf][f] = read_operand<A_KCONTIG, BM, f, RB>(lds3, frag_a, s, par * A_BYTES);
-        else fb[buf][f - FM] = read_operand<B_KCONTIG, BN, f - FM, RB>(lds3, frag_b, s, par * B_BYTES);
+    auto read_frag = [&](auto F, auto PAR, auto S, int buf) {
+        constexpr int f = decltype(F)::value, par = decltype(PAR)::value, s = decltype(S)::value;
+        if constexpr (f < FM) fa[buf][f] = read_operand<A_KCONTIG, BM, f, RB, s, par * A_BYTES>(lds3, frag_a);
+        else fb[buf][f - FM] = read_operand<B_KCONTIG, BN, f - FM, RB, s, par * B_BYTES>(lds3, frag_b);
     };
+    // the transposing reads are invisible to the compiler's wait-count bookkeeping (see read_operand)
+    constexpr bool MANUAL_WAIT = !A_KCONTIG || !B_KCONTIG;
+    auto wait_fragments = [] {
+        if constexpr (MANUAL_WAIT) {
+            __builtin_amdgcn_s_waitcnt(0xC07F);            // lgkmcnt(0)
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    using Step0 = std::integral_constant<int, 0>;
     using Stage0 = std::integral_constant<int, 0>;
     using Stage1 = std::integral_constant<int, 1>;
 
@@ -200,7 +221,7 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
         static_for<PIECES>([&](auto P) { issue_piece(P, Stage0{}); });
         wait_loads();
         __syncthreads();
-        static_for<FRAGS>([&](auto F) { read_frag(F, Stage0{}, 0, 0); });
+        static_for<FRAGS>([&](auto F) { read_frag(F, Stage0{}, Step0{}, 0); });
     }
 
     constexpr int TAIL = (SLOTS * MG_TAIL_SIXTEENTHS / 16) > 0 ? (SLOTS * MG_TAIL_SIXTEENTHS / 16) : 1;
@@ -222,20 +243,21 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
                     wait_loads();
                     __syncthreads();                     // tile t+1 is complete in the other stage
                 }
+                if constexpr (q == 0) wait_fragments();  // this step's operands, read during the previous step
                 mma(acc[q / FM][q % FM], fb[s & 1][q / FM], fa[s & 1][q % FM], T{});
                 if constexpr (s + 1 < KSTEPS) {
                     if constexpr (q < READ_SLOTS)
                         static_for<share_begin(q + 1, FRAGS, READ_SLOTS) - share_begin(q, FRAGS, READ_SLOTS)>([&](auto R) {
                             constexpr int o = share_begin(q, FRAGS, READ_SLOTS) + decltype(R)::value;
                             constexpr int f = o < FM ? o : FM + (FRAGS - 1 - o);
-                            read_frag(std::integral_constant<int, f>{}, Cur{}, s + 1, (s + 1) & 1);
+                            read_frag(std::integral_constant<int, f>{}, Cur{}, std::integral_constant<int, s + 1>{}, (s + 1) & 1);
                         });
                 } else if constexpr (g >= BARRIER_SLOT && g - BARRIER_SLOT < TAIL_READ_SLOTS) {
                     constexpr int h = g - BARRIER_SLOT;
                     static_for<share_begin(h + 1, FRAGS, TAIL_READ_SLOTS) - share_begin(h, FRAGS, TAIL_READ_SLOTS)>([&](auto R) {
                         constexpr int o = share_begin(h, FRAGS, TAIL_READ_SLOTS) + decltype(R)::value;
                         constexpr int f = o < FM ? o : FM + (FRAGS - 1 - o);
-                        read_frag(std::integral_constant<int, f>{}, Nxt{}, 0, 0);
+                        read_frag(std::integral_constant<int, f>{}, Nxt{}, Step0{}, 0);
                     });
                 }
                 if constexpr (g % MG_DMA_SPACING == 0 && g / MG_DMA_SPACING < PIECES)
