@@ -13,14 +13,15 @@
 //   * contiguous along k: [row][k], 128 bytes per row, chunk c of row r at slot c ^ ((r ^ r/8) % 8) -- the
 //     layout of the register-staged kernel; an MFMA operand is one 16-byte read per lane;
 //   * contiguous along its row index (m for A, n for B): [k][row] as in memory, 2 * ROWS bytes per k, the
-//     16-byte chunk c of line k at slot c ^ (4 * (k % 4)); an MFMA operand is two transposing 8-byte reads
+//     16-byte chunk c of line k at slot c ^ (4 * (k % 4) + 2 * (k / 8 % 2)); an MFMA operand is two transposing 8-byte reads
 //     (ds_read_b64_tr_b16): in each group of 16 lanes, lane 4a + b receives element b of what lanes a, a + 4,
 //     a + 8, a + 12 fetched, so when those four lanes fetch the same four rows at four consecutive k, lane
 //     4a + b ends up with four consecutive k of row 4a + b.  The LDS serves 256 bytes per clock (64 banks),
-//     i.e. 32 lanes of such a read: two row groups of 32 bytes each at four k lines; the swizzle puts these
-//     eight 32-byte pieces on eight different bank ranges (with c ^ 2 (k % 4) the counters showed as many
-//     conflict cycles as useful ones).
-// Both forms give lane l the eight k values 16 s + 8 (l / 32) + 0..7 of row l % 32 in K-step s.
+//     i.e. 32 lanes of such a read: eight 32-byte pieces -- with 32-row fragments two row groups at four k
+//     lines, with 16-row fragments one row group at k lines j and 8 + j -- which the swizzle puts on eight
+//     different bank ranges (with c ^ 2 (k % 4) the counters showed as many conflict cycles as useful ones).
+// Both forms give lane l the eight k values (512 / RB) s + 8 (l / RB) + 0..7 of row l % RB in K-step s (RB = 32 or
+// 16 rows per fragment).
 //
 // Pipeline: two LDS stages.  During K-tile t (read from stage t % 2) the loads of tile t + 1 into the other
 // stage are issued in the first slots; every wavefront waits for its own loads just before the single barrier
@@ -64,7 +65,7 @@ template <int ROWS, int NT, bool KCONTIG> struct DmaLoader {
                 g = r * ld * 2 + ((slot ^ ((r ^ (r >> 3)) & 7)) << 4);
             } else {
                 const int kl = o / (2 * ROWS), slot = (o / 16) % (ROWS / 8);
-                g = kl * ld * 2 + ((slot ^ (4 * (kl & 3))) << 4);
+                g = kl * ld * 2 + ((slot ^ (4 * (kl & 3) + 2 * ((kl >> 3) & 1))) << 4);
             }
             goff[Q] = static_cast<uint32_t>(g - imm(Q));
         });
@@ -93,16 +94,15 @@ template <int ROWS, int NT, bool KCONTIG> struct DmaLoader {
 // loop.  The price: the compiler does not know that these registers are written later, by the LDS, so the
 // kernel itself waits (wait_fragments) before the first MFMA of every K-step.
 template <bool KCONTIG, int ROWS, int F, int RB, int S, int STAGE>
-__device__ inline u32x4 read_operand(lds_char *lds3, const int (&frag)[4])
+__device__ inline u32x4 read_operand(lds_char *lds3, const int (&frag)[8])
 {
     if constexpr (KCONTIG) {
         return *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(
             lds3 + frag[frag_select<RB>(F, S)] + F * RB * 128 + STAGE);
     } else {
-        static_assert(RB == 32, "the transposing reads are laid out for 32-row fragments");
-        static_assert(F < 4, "one address per fragment");
+        static_assert(F < 8, "one address per fragment");
         constexpr int LINE = 2 * ROWS;                                    // bytes per k line
-        constexpr int OFFSET = S * (16 * LINE) + STAGE;
+        constexpr int OFFSET = S * ((512 / RB) * LINE) + STAGE;          // a K-step is 16 (RB = 32) or 32 k lines
         static_assert(OFFSET + 4 * LINE < 65536, "LDS instruction offsets have 16 bits");
         const uint32_t at = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds3)) + static_cast<uint32_t>(frag[F]);
         shortx4 lo, hi;
@@ -147,18 +147,22 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
 
     // ---- fragment addresses (bytes from the start of the LDS, stage 0); see the layouts above
-    int frag_a[4], frag_b[4];          // k-contiguous form: four addresses cover every (fragment, step); else one per fragment
-    auto frag_setup = [&](bool kcontig, int wrow, int operand_base, int rows, int (&frag)[4]) {
+    int frag_a[8], frag_b[8];          // k-contiguous form: four addresses cover every (fragment, step); else one per fragment
+    auto frag_setup = [&](bool kcontig, int wrow, int operand_base, int rows, int (&frag)[8]) {
         if (kcontig) {
             const int x = frag_lane_x<RB>(lane, wrow);
             for (int kx = 0; kx < 4; ++kx) frag[kx] = operand_base + (wrow + lane % RB) * 128 + (x ^ (32 * kx));
+            for (int kx = 4; kx < 8; ++kx) frag[kx] = 0;
         } else {
-            // fetch role inside the group of 16 lanes: rows 4a .. 4a+3 of the group's 16 rows, k line j
+            // fetch role inside the group of 16 lanes: rows 4a .. 4a+3 of the group's 16 rows, k line j.
+            // RB = 32: groups 2c, 2c+1 are the two row halves of k chunk c; RB = 16: group g is k chunk g.
             const int i = lane % 16, a = i % 4, j = i / 4, g = lane / 16;
-            const int kl = 8 * (g / 2) + j;                                   // + 16 s + 4 h
-            const int slot = (wrow / 8 + 2 * (g % 2) + a / 2) ^ (4 * j);     // fragment f adds 4 f under the same XOR
+            const int chunk = RB == 32 ? g / 2 : g;
+            const int kl = 8 * chunk + j;                                     // + (512 / RB) s + 4 h
+            const int row8 = wrow / 8 + (RB == 32 ? 2 * (g % 2) : 0) + a / 2; // 16-byte slot of the rows; + (RB / 8) f
+            const int slot = row8 ^ (4 * j + 2 * (chunk & 1));
             const int p = operand_base + kl * (2 * rows) + slot * 16 + 8 * (a % 2);
-            for (int f = 0; f < 4; ++f) frag[f] = p ^ (64 * f);
+            for (int f = 0; f < 8; ++f) frag[f] = p ^ (2 * RB * f);           // fragment f: (RB / 8) f under the same XOR
         }
     };
     frag_setup(A_KCONTIG, wm * WTM, 0, BM, frag_a);

@@ -97,13 +97,12 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
             int want = last ? pick_split(blocks, ktiles) : 1;
             // split-K needs the caller's workspace: without enough of it, run unsplit
             while (want > 1 && static_cast<size_t>(want) * p.m * p.n * sizeof(float) > workspace_bytes) want = 1;
-            // FP16 and whole 256 x 256 tiles: the direct-to-LDS kernels with two wavefronts per SIMD measured
-            // fastest for every operand order (16x16x32 MFMA blocks when both operands are contiguous along k)
+            // FP16 and whole 256 x 256 tiles: the direct-to-LDS kernels with two wavefronts per SIMD and 16x16x32
+            // MFMA blocks measured fastest for every operand order
             if (!f32 && i == 0) {
                 char name[96];
                 const char *contig = p.a_trans ? (p.b_trans ? "kn" : "kk") : (p.b_trans ? "mn" : "mk");
-                snprintf(name, sizeof name, "%s_%s", p.a_trans && !p.b_trans ? "hdma16_256x256x64_w2x4" : "hdma_256x256x64_w2x4",
-                         contig);
+                snprintf(name, sizeof name, "hdma16_256x256x64_w2x4_%s", contig);
                 if (try_pick(table, p, alignment, name, want, kernel, split)) return;
             }
             if (try_mfma(table, p, alignment, tiles[i].tag, want, kernel, split)) return;
