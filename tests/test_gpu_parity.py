@@ -343,6 +343,23 @@ def test_k_zero_and_empty(G, oracle):
     assert torch.all(buf == 0)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("layout,ta,tb", VARIANTS)
+def test_one_or_two_beyond_a_tile_multiple(G, oracle, dtype, layout, ta, tb):
+    """shapes one or two rows / columns beyond a multiple of 64 (the 129 = 128 + 1 pattern of the irregular
+    workload group): nearly empty last tiles; exact on integers, padding untouched"""
+    for (m, n, k) in ((129, 320, 256), (320, 130, 300), (257, 258, 260), (65, 600, 512)):
+        if dtype == "f32":
+            g = W.rng_for(9, m + n)
+            case = W.make_case(f"strip_{m}x{n}x{k}", "f32", layout, ta, tb, W.small_ints(g, (m, k)), W.small_ints(g, (k, n)),
+                               W.small_ints(g, (m, n)), 1.5, 0.5, lda=W.tight_ld(layout, ta, m, k) + 3,
+                               ldb=W.tight_ld(layout, tb, k, n) + 1, ldc=W.tight_ld(layout, N, m, n) + 2, exact=True)
+        else:
+            case = W.hgemm_case(m, n, k, case=m + n, layout=layout, ta=ta, tb=tb, alpha=1.0, beta=1.0, integer=True)
+        announce(case.name, layout, ta, tb)
+        H.check_case(case, oracle)
+
+
 # ------------------------------------------------------------------ every compiled configuration is result-neutral
 
 def _probe_cases(dtype):
