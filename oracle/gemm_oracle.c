@@ -20,6 +20,9 @@
  * The batched form (Section 4.6 "Batched BLAS Routines") repeats the same thing per
  * instance with per-instance element offsets into A, B, C and per-instance alpha, beta.
  *
+ * The matrix-vector product (Section 4.2 benchmarks it beside GEMM) is the same sum with a
+ * single output column and strided vectors; it has a loop of its own, oracle_gemv.
+ *
  * Outputs are dense FP64 arrays indexed [i*n + j] (and [b*m*n + i*n + j] when batched);
  * nothing is rounded to the storage type.  D is the denominator of the relative error
  * the parity tests use.
@@ -159,6 +162,37 @@ void oracle_hgemm_batched(int layout, int ta, int tb, int64_t m, int64_t n, int6
         int64_t i = p / n, j = p % n;
         one_entry(1, layout, ta, tb, k, (double)alphas[b], A + a_off[b], lda, B + b_off[b], ldb,
                   (double)betas[b], C + c_off[b], ldc, i, j, &c_ref[q], &d_ref[q]);
+    }
+}
+
+/* Matrix-vector product (the level-2 routine the paper benchmarks next to GEMM, Section 4.2), BLAS GEMV:
+ *     y(i) = alpha * sum_l op(A)(i,l) * x(l) + beta * y(i),     op(A) is M x K with (M, K) = (m, n) or (n, m)
+ * A is m x n in the given layout with leading dimension lda; x(l) lives at x[l*incx], y(i) at y[i*incy]
+ * (positive increments).  beta == 0: y is not read; alpha == 0: A and x are not read.
+ * y_ref, d_ref: M doubles; d = |alpha| sum |op(A)(i,l)||x(l)| + |beta||y(i)|. */
+void oracle_gemv(int is_half, int layout, int trans, int64_t m, int64_t n, double alpha, const void *A, int64_t lda,
+                 const void *x, int64_t incx, double beta, const void *y, int64_t incy, double *y_ref, double *d_ref)
+{
+    const int64_t rows = trans == ORA_NO_TRANS ? m : n, len = trans == ORA_NO_TRANS ? n : m;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i) {
+        double acc = 0.0, mag = 0.0;
+        if (alpha != 0.0)
+            for (int64_t l = 0; l < len; ++l) {
+                const size_t pa = trans == ORA_NO_TRANS ? at(layout, i, l, lda) : at(layout, l, i, lda);
+                const double a = is_half ? load_f16(A, pa) : load_f32(A, pa);
+                const double v = is_half ? load_f16(x, (size_t)(l * incx)) : load_f32(x, (size_t)(l * incx));
+                acc += a * v;
+                mag += fabs(a) * fabs(v);
+            }
+        double r = alpha * acc, d = fabs(alpha) * mag;
+        if (beta != 0.0) {
+            const double o = is_half ? load_f16(y, (size_t)(i * incy)) : load_f32(y, (size_t)(i * incy));
+            r += beta * o;
+            d += fabs(beta) * fabs(o);
+        }
+        y_ref[i] = r;
+        d_ref[i] = d;
     }
 }
 

@@ -40,6 +40,8 @@ def lib():
         _lib.oracle_sgemm_batched.restype = None
         _lib.oracle_hgemm_batched.argtypes = _lib.oracle_sgemm_batched.argtypes
         _lib.oracle_hgemm_batched.restype = None
+        _lib.oracle_gemv.argtypes = [ci, ci, ci, i64, i64, dbl, vp, i64, vp, i64, dbl, vp, i64, vp, vp]
+        _lib.oracle_gemv.restype = None
         _lib.oracle_half_to_double.argtypes = [vp, i64, vp]
         _lib.oracle_half_to_double.restype = None
         _lib.oracle_threads.argtypes = []
@@ -156,6 +158,24 @@ def sgemm_strided_batched(layout, ta, tb, m, n, k, alpha, A, lda, stride_a, B, l
     idx = np.arange(batch, dtype=np.int64)
     return sgemm_batched(layout, ta, tb, m, n, k, np.full(batch, alpha, dtype=np.float32), A, idx * stride_a, lda,
                          B, idx * stride_b, ldb, np.full(batch, beta, dtype=np.float32), C, idx * stride_c, ldc)
+
+
+def gemv(dtype, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy):
+    """BLAS GEMV oracle: y_ref, d_ref (float64, length m or n).  A is m x n as stored; x, y flat with increments."""
+    np_t = np.float32 if dtype == "f32" else np.float16
+    rows, length = (m, n) if trans == NO_TRANS else (n, m)
+    A, x, y = _flat(A, np_t), _flat(x, np_t), _flat(y, np_t)
+    assert incx >= 1 and incy >= 1
+    if alpha != 0 and rows and length:
+        assert A.size >= _need(layout, NO_TRANS, m, n, lda), "A too short"
+        assert x.size >= (length - 1) * incx + 1, "x too short"
+    if beta != 0 and rows:
+        assert y.size >= (rows - 1) * incy + 1, "y too short"
+    y_ref = np.empty(rows, dtype=np.float64)
+    d_ref = np.empty(rows, dtype=np.float64)
+    lib().oracle_gemv(int(dtype == "f16"), layout, trans, m, n, float(alpha), _ptr(A), lda, _ptr(x), incx, float(beta),
+                      _ptr(y), incy, _ptr(y_ref), _ptr(d_ref))
+    return y_ref, d_ref
 
 
 def half_to_double(bits):

@@ -424,3 +424,42 @@ def test_config_shapes_follow_the_recipe():
     h = W.config3(0)
     assert h.A.dtype == np.float16 and (h.m, h.n, h.k, h.lda, h.ldb, h.ldc) == (64, 12544, 147, 64, 147, 64)
     assert abs(float(np.std(h.B.astype(np.float64))) - 147 ** -0.5) < 2e-3
+
+
+# ---------------------------------------------------------------- matrix-vector product
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("layout", [Cm, R])
+@pytest.mark.parametrize("trans", [N, T])
+def test_gemv_against_numpy_and_the_gemm_oracle(oracle, dtype, layout, trans):
+    """y = alpha op(A) x + beta y with strided x and y: numpy on the widened data, and the GEMM oracle on the
+    same problem written as an n = 1 product (bit for bit: same summation order)"""
+    m, n, lda, incx, incy = 7, 5, 9, 3, 2
+    g = np.random.default_rng(31)
+    np_t = np.float32 if dtype == "f32" else np.float16
+    Am = g.uniform(-1, 1, size=(m, n)).astype(np_t)
+    A = W.pack(Am, layout, N, lda)
+    rows, length = (m, n) if trans == N else (n, m)
+    xs = g.uniform(-1, 1, size=length).astype(np_t)
+    ys = g.uniform(-1, 1, size=rows).astype(np_t)
+    x = np.full((length - 1) * incx + 1, np.nan, np_t); x[::incx] = xs
+    y = np.full((rows - 1) * incy + 1, np.nan, np_t); y[::incy] = ys
+    y_ref, d_ref = oracle.gemv(dtype, layout, trans, m, n, -1.5, A, lda, x, incx, 0.75, y, incy)
+    op = Am.astype(np.float64) if trans == N else Am.astype(np.float64).T
+    want = -1.5 * (op @ xs.astype(np.float64)) + 0.75 * ys.astype(np.float64)
+    den = 1.5 * (np.abs(op) @ np.abs(xs.astype(np.float64))) + 0.75 * np.abs(ys.astype(np.float64))
+    assert np.max(np.abs(y_ref - want)) <= 1e-14 and np.max(np.abs(d_ref - den)) <= 1e-14
+    c_ref, dd = oracle.gemm(dtype, layout, trans, N, rows, 1, length, -1.5, A, lda,
+                            W.pack(xs.reshape(length, 1), layout, N), W.tight_ld(layout, N, length, 1), 0.75,
+                            W.pack(ys.reshape(rows, 1), layout, N), W.tight_ld(layout, N, rows, 1))
+    assert np.array_equal(c_ref[:, 0], y_ref) and np.array_equal(dd[:, 0], d_ref)
+
+
+def test_gemv_conventions(oracle):
+    A = np.full(12, np.nan, np.float32)
+    y = np.arange(1, 4, dtype=np.float32)
+    y_ref, d_ref = oracle.gemv("f32", Cm, N, 3, 4, 0.0, A, 3, np.full(4, np.nan, np.float32), 1, 2.0, y, 1)
+    assert np.array_equal(y_ref, 2.0 * y) and np.array_equal(d_ref, 2.0 * y)          # alpha == 0: A, x not read
+    A = np.ones(12, np.float32)
+    y_ref, d_ref = oracle.gemv("f32", Cm, N, 3, 4, 1.0, A, 3, np.ones(4, np.float32), 1, 0.0, np.full(3, np.nan, np.float32), 1)
+    assert np.array_equal(y_ref, np.full(3, 4.0)) and np.array_equal(d_ref, np.full(3, 4.0))   # beta == 0: y not read
