@@ -63,7 +63,8 @@ enum {
     MG_ERR_LAUNCH = -12,      /* the HIP runtime refused the launch (see hipGetLastError)   */
     MG_ERR_NO_DEVICE = -13,   /* no usable gfx950 device / HIP runtime error before launch  */
     MG_ERR_STRIDE = -14,      /* a batch stride is negative                                 */
-    MG_ERR_CONV = -15         /* convolution geometry: an extent < 1, a pad < 0, stride or dilation < 1 */
+    MG_ERR_CONV = -15,        /* convolution geometry: an extent < 1, a pad < 0, stride or dilation < 1 */
+    MG_ERR_INC = -16          /* a vector increment below 1                                  */
 };
 
 typedef enum { MG_ROW_MAJOR = 101, MG_COL_MAJOR = 102 } mg_layout;
@@ -111,6 +112,19 @@ mg_status mg_hgemm(int layout, int trans_a, int trans_b, int64_t m, int64_t n, i
                    float alpha, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
                    float beta, uint16_t *C, int64_t ldc,
                    void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---- GEMV: matrix-vector product (the level-2 routine of paper Section 4.2) ----------
+ *     y = alpha * op(A) * x + beta * y
+ * A is m x n as stored (layout, lda as for GEMM); op(A) = A (MG_NO_TRANS: x has n elements, y has m)
+ * or A^T (x has m, y has n).  Element l of x is x[l*incx], element i of y is y[i*incy]; increments
+ * must be >= 1 (MG_ERR_INC otherwise; the BLAS's negative increments are not supported).  A, x, y:
+ * device pointers aligned to their element size; y is read only if beta != 0, A and x only if
+ * alpha != 0.  FP32 accumulation, one rounding to the storage type.  No workspace is needed.
+ * Errors: MG_ERR_LAYOUT, MG_ERR_TRANS_A, MG_ERR_DIM, MG_ERR_LDA, MG_ERR_INC, MG_ERR_NULL. */
+mg_status mg_sgemv(int layout, int trans_a, int64_t m, int64_t n, float alpha, const float *A, int64_t lda,
+                   const float *x, int64_t incx, float beta, float *y, int64_t incy, void *stream);
+mg_status mg_hgemv(int layout, int trans_a, int64_t m, int64_t n, float alpha, const uint16_t *A, int64_t lda,
+                   const uint16_t *x, int64_t incx, float beta, uint16_t *y, int64_t incy, void *stream);
 
 /* ---- generic batched GEMM (paper Section 4.6) -----------------------------------------
  * batch_count independent GEMMs of one shape.  Instance b uses A + a_offsets[b],

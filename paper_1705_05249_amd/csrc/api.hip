@@ -114,6 +114,19 @@ mg_status choose(const Problem &p, int64_t alignment, size_t workspace_bytes, in
     return MG_OK;
 }
 
+// Selects and launches the configuration for a canonical problem with at least one output.
+mg_status run_canonical(const Problem &p)
+{
+    int32_t kernel = -1, split = 1;
+    const bool ws_usable = p.workspace != nullptr && pointer_alignment(p.workspace) >= 256;
+    const mg_status s = choose(p, problem_alignment(p), ws_usable ? p.workspace_bytes : 0, &kernel, &split);
+    if (s != MG_OK) return s;
+    const KernelEntry &e = table()[kernel];
+    const size_t need = e.workspace(p, split);
+    if (need > 0 && !(ws_usable && p.workspace_bytes >= need)) return MG_ERR_WORKSPACE;
+    return e.launch(p, split) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
+}
+
 mg_status run_gemm(int dtype, int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, float alpha,
                    const void *A, int64_t lda, const void *B, int64_t ldb, float beta, void *C, int64_t ldc,
                    void *ws, size_t ws_bytes, void *stream)
@@ -124,14 +137,38 @@ mg_status run_gemm(int dtype, int layout, int ta, int tb, int64_t m, int64_t n, 
     const bool reads_ab = alpha != 0.f && k != 0;
     if (C == nullptr || (reads_ab && (A == nullptr || B == nullptr))) return MG_ERR_NULL;
     Problem p = canonical(dtype, layout, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, ws, ws_bytes, stream);
-    int32_t kernel = -1, split = 1;
-    const bool ws_usable = ws != nullptr && pointer_alignment(ws) >= 256;
-    s = choose(p, problem_alignment(p), ws_usable ? ws_bytes : 0, &kernel, &split);
-    if (s != MG_OK) return s;
-    const KernelEntry &e = table()[kernel];
-    const size_t need = e.workspace(p, split);
-    if (need > 0 && (ws == nullptr || ws_bytes < need || pointer_alignment(ws) < 256)) return MG_ERR_WORKSPACE;
-    return e.launch(p, split) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
+    return run_canonical(p);
+}
+
+// Matrix-vector product as the one-row canonical problem  y^T = x^T op(A)^T: x is the 1 x K operand
+// with leading dimension incx, op(A)^T the K x M operand read in place, y the 1 x M result with leading
+// dimension incy.  The matrix-vector kernels take all three strides as they are.
+mg_status run_gemv(int dtype, int layout, int trans, int64_t m, int64_t n, float alpha, const void *A, int64_t lda,
+                   const void *x, int64_t incx, float beta, void *y, int64_t incy, void *stream)
+{
+    if (layout != MG_ROW_MAJOR && layout != MG_COL_MAJOR) return MG_ERR_LAYOUT;
+    if (!valid_trans(trans)) return MG_ERR_TRANS_A;
+    const int64_t lim = int64_t(1) << 31;
+    if (m < 0 || n < 0 || m >= lim || n >= lim) return MG_ERR_DIM;
+    const int64_t lead = layout == MG_COL_MAJOR ? m : n;
+    if (lda < (lead > 1 ? lead : 1)) return MG_ERR_LDA;
+    if (incx < 1 || incy < 1 || incx >= lim || incy >= lim) return MG_ERR_INC;
+    const bool t = trans != MG_NO_TRANS;
+    const int64_t outputs = t ? n : m, length = t ? m : n;
+    if (outputs == 0) return MG_OK;
+    const bool reads = alpha != 0.f && length != 0;
+    if (y == nullptr || (reads && (A == nullptr || x == nullptr))) return MG_ERR_NULL;
+    Problem p{};
+    p.dtype = dtype;
+    p.m = 1; p.n = outputs; p.k = length;
+    p.A = x; p.lda = incx; p.a_trans = false;
+    // op(A)^T (l, j) = op(A)(j, l): contiguous along the outputs exactly when the stored matrix has its
+    // unit stride along op(A)'s rows
+    p.B = A; p.ldb = lda; p.b_trans = (layout == MG_COL_MAJOR) != t;
+    p.C = y; p.ldc = incy;
+    p.alpha = alpha; p.beta = beta;
+    p.stream = static_cast<hipStream_t>(stream);
+    return run_canonical(p);
 }
 
 // Canonicalises a (generic or strided) batched call to column-major and launches it.
@@ -290,6 +327,18 @@ mg_status mg_hgemm(int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, 
 {
     return run_gemm(MG_F16, layout, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, workspace,
                     workspace_bytes, stream);
+}
+
+mg_status mg_sgemv(int layout, int trans_a, int64_t m, int64_t n, float alpha, const float *A, int64_t lda,
+                   const float *x, int64_t incx, float beta, float *y, int64_t incy, void *stream)
+{
+    return run_gemv(MG_F32, layout, trans_a, m, n, alpha, A, lda, x, incx, beta, y, incy, stream);
+}
+
+mg_status mg_hgemv(int layout, int trans_a, int64_t m, int64_t n, float alpha, const uint16_t *A, int64_t lda,
+                   const uint16_t *x, int64_t incx, float beta, uint16_t *y, int64_t incy, void *stream)
+{
+    return run_gemv(MG_F16, layout, trans_a, m, n, alpha, A, lda, x, incx, beta, y, incy, stream);
 }
 
 mg_status mg_sgemm_batched(int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, const float *alphas,
@@ -466,10 +515,11 @@ const char *mg_status_string(mg_status status)
         case MG_ERR_NO_DEVICE: return "no usable device";
         case MG_ERR_STRIDE: return "negative batch stride";
         case MG_ERR_CONV: return "invalid convolution geometry";
+        case MG_ERR_INC: return "vector increment below one";
         default: return "unknown status";
     }
 }
 
-const char *mg_version(void) { return "0.3"; }
+const char *mg_version(void) { return "0.4"; }
 
 }  // extern "C"

@@ -419,6 +419,58 @@ def skinny_case(m, n, k, case=0, integer=False, name=None, layout=COL_MAJOR, ta=
                      padded_ld(ra), padded_ld(rb), padded_ld(rc), exact=integer)
 
 
+# ----------------------------------------------------------------------------- matrix-vector cases
+
+@dataclass
+class GemvCase:
+    """One GEMV call: y = alpha op(A) x + beta y.  A is m x n as stored; x, y are flat buffers with increments
+    (the slots between the elements hold a sentinel that must survive the call)."""
+    name: str
+    dtype: str
+    layout: int
+    trans: int
+    m: int
+    n: int
+    alpha: float
+    beta: float
+    A: np.ndarray
+    lda: int
+    x: np.ndarray
+    incx: int
+    y: np.ndarray
+    incy: int
+    exact: bool = False
+
+    @property
+    def outputs(self) -> int:
+        return self.m if self.trans == NO_TRANS else self.n
+
+    @property
+    def length(self) -> int:
+        return self.n if self.trans == NO_TRANS else self.m
+
+
+def gemv_case(dtype, layout, trans, m, n, incx=1, incy=1, alpha=1.0, beta=0.0, case=0, integer=False, pad=0,
+              name=None) -> GemvCase:
+    g = rng_for(6, case)
+    np_t = _np_dtype(dtype)
+    gen = small_ints if integer else uniform
+    if integer and (max(m, n) > 1024 or dtype == "f16"):
+        gen = lambda gg, s, dtype=np.float32: small_ints(gg, s, 2, dtype=dtype)   # results stay exactly representable
+    Am = gen(g, (m, n), dtype=np_t)
+    lda = tight_ld(layout, NO_TRANS, m, n) + pad
+    A = pack(Am, layout, NO_TRANS, lda)
+    rows, length = (m, n) if trans == NO_TRANS else (n, m)
+    x = np.full(max((length - 1) * incx + 1, 1), GAP_FILL, dtype=np_t)
+    y = np.full(max((rows - 1) * incy + 1, 1), GAP_FILL, dtype=np_t)
+    if length:
+        x[::incx] = gen(g, (length,), dtype=np_t)
+    if rows:
+        y[::incy] = gen(g, (rows,), dtype=np_t)
+    return GemvCase(name or f"gemv_{dtype}_{m}x{n}", dtype, layout, trans, m, n, alpha, beta, A, lda, x, incx, y,
+                    incy, exact=integer)
+
+
 # ----------------------------------------------------------------------------- sampling plan
 
 def sample_entries(m: int, n: int, seed: int, rows: int = 16, cols: int = 16, tile: int = 128,

@@ -159,3 +159,36 @@ def check_conv(case, conv_oracle):
     err = rel_error(got, ref, den)
     assert err <= TOL[case.dtype], f"{case.name}: relative error {err:.3e}"
     return err
+
+
+def run_gemv(case, check=True):
+    """Runs one GemvCase through the C ABI; returns (status, flat y buffer after the call)."""
+    import torch
+    from paper_1705_05249_amd import gemm as G
+    fn = G.mg_sgemv if case.dtype == "f32" else G.mg_hgemv
+    A = to_gpu(case.A if case.A.size else np.zeros(1, dtype=case.A.dtype))
+    x, y = to_gpu(case.x), to_gpu(case.y)
+    st = fn(case.layout, case.trans, case.m, case.n, case.alpha, A, case.lda, x, case.incx, case.beta, y,
+            case.incy, None, check=check)
+    torch.cuda.synchronize()
+    return st, y.cpu().numpy()
+
+
+def check_gemv(case, oracle):
+    """Element-by-element comparison of a GEMV call with the oracle; the slots between the elements of y
+    must keep their bytes.  Returns the error."""
+    y_ref, d_ref = oracle.gemv(case.dtype, case.layout, case.trans, case.m, case.n, case.alpha, case.A, case.lda,
+                               case.x, case.incx, case.beta, case.y, case.incy)
+    _, out = run_gemv(case)
+    rows = case.outputs
+    got = out[: (rows - 1) * case.incy + 1: case.incy] if rows else out[:0]
+    mask = np.ones(out.size, dtype=bool)
+    if rows:
+        mask[: (rows - 1) * case.incy + 1: case.incy] = False
+    assert np.array_equal(bits(out)[mask], bits(case.y)[mask]), f"{case.name}: bytes outside y were written"
+    if case.exact:
+        assert np.array_equal(got.astype(np.float64), y_ref), f"{case.name}: integer-valued case must be exact"
+        return 0.0
+    err = rel_error(got, y_ref, d_ref)
+    assert err <= TOL[case.dtype], f"{case.name}: relative error {err:.3e}"
+    return err

@@ -164,9 +164,27 @@ def test_im2col_argument_errors_and_geometry_queries():
     assert G.mg_conv2d_workspace_bytes(7, 3, 8, 9, (3, 3), (1, 1), (1, 1), (1, 1), 4) == 0
 
 
+@pytest.mark.parametrize("fn", ["mg_sgemv", "mg_hgemv"])
+def test_gemv_argument_errors(fn):
+    """every rejected call returns before anything touches a device"""
+    f = getattr(G.lib(), fn)
+
+    def call(layout=C, trans=N, m=4, n=3, A=FAKE, lda=4, x=FAKE, incx=1, y=FAKE, incy=1, alpha=1.0, beta=0.0):
+        return f(layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy, None)
+
+    assert call(layout=7) == -1 and call(trans=5) == -2
+    assert call(m=-1) == -4 and call(n=-1) == -4 and call(m=1 << 31) == -4
+    assert call(lda=3) == -5 and call(layout=R, lda=2) == -5 and call(layout=R, lda=3, m=0) == 0
+    assert call(incx=0) == -16 and call(incy=0) == -16 and call(incx=-1) == -16
+    assert call(y=None) == -8 and call(A=None) == -8 and call(x=None) == -8
+    # no output: nothing to do, whatever the pointers are
+    assert call(m=0, lda=1, A=None, x=None, y=None) == 0
+    assert call(trans=T, n=0, A=None, x=None, y=None) == 0
+
+
 def test_status_strings_and_version():
     seen = set()
-    for code in range(0, -16, -1):
+    for code in range(0, -17, -1):
         s = G.status_string(code)
         assert s and s != "unknown status" and s not in seen
         seen.add(s)
