@@ -109,7 +109,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
-    ap.add_argument("--only", default=None, help="hgemm | sgemm | batched | conv | copy: run a single workload (profiling runs)")
+    ap.add_argument("--only", default=None, help="hgemm | sgemm | batched | conv | gemv | copy: run a single workload (profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -237,6 +237,25 @@ def main():
                           "roofline_im2col": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                               "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None},
                           "note": "graph-timed; working set of a few MB, served by the last-level cache"})
+
+    # ---- next row: the stand-alone matrix-vector product, a 1 GiB FP32 matrix (four times the last-level
+    # cache) read once per call, in both operand orders
+    if args.only in (None, "gemv"):
+        size = 16384
+        gen = torch.Generator(device="cuda").manual_seed(W.SEED_BASE)
+        mat = torch.rand(size * size, dtype=torch.float32, device="cuda", generator=gen) - 0.5
+        x = torch.rand(size, dtype=torch.float32, device="cuda", generator=gen) - 0.5
+        y = torch.zeros(size, dtype=torch.float32, device="cuda")
+        for trans, tag in ((W.NO_TRANS, "N"), (W.TRANS, "T")):
+            need = G.mg_gemv_workspace_bytes(G.MG_F32, W.COL_MAJOR, trans, size, size, size)
+            ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda") if need else None
+            dev, _ = timed(lambda: G.mg_sgemv(W.COL_MAJOR, trans, size, size, 1.0, mat, size, x, 1, 0.0, y, 1, ws),
+                           steps, warmup)
+            gbs = 4.0 * size * size / dev / 1e9
+            extra.append({"workload": f"sgemv_f32_{size}x{size}_colmajor_{tag}", "gflops": round(2.0 * size * size / dev / 1e9, 1),
+                          "ms": round(dev * 1e3, 5),
+                          "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                       "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None}})
 
     if head is None:
         print(json.dumps({"workloads": extra}))

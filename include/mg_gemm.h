@@ -119,12 +119,21 @@ mg_status mg_hgemm(int layout, int trans_a, int trans_b, int64_t m, int64_t n, i
  * or A^T (x has m, y has n).  Element l of x is x[l*incx], element i of y is y[i*incy]; increments
  * must be >= 1 (MG_ERR_INC otherwise; the BLAS's negative increments are not supported).  A, x, y:
  * device pointers aligned to their element size; y is read only if beta != 0, A and x only if
- * alpha != 0.  FP32 accumulation, one rounding to the storage type.  No workspace is needed.
+ * alpha != 0.  FP32 accumulation, one rounding to the storage type.
+ * workspace: device scratch as for GEMM (256-byte aligned, caller-owned, may be NULL).  With few
+ * outputs and a long sum the library cuts the sum into slices, which needs
+ * mg_gemv_workspace_bytes() bytes; with a smaller (or no) workspace it uses fewer slices (or none):
+ * slower for such shapes, same result up to summation order, never an error.
  * Errors: MG_ERR_LAYOUT, MG_ERR_TRANS_A, MG_ERR_DIM, MG_ERR_LDA, MG_ERR_INC, MG_ERR_NULL. */
 mg_status mg_sgemv(int layout, int trans_a, int64_t m, int64_t n, float alpha, const float *A, int64_t lda,
-                   const float *x, int64_t incx, float beta, float *y, int64_t incy, void *stream);
+                   const float *x, int64_t incx, float beta, float *y, int64_t incy,
+                   void *workspace, size_t workspace_bytes, void *stream);
 mg_status mg_hgemv(int layout, int trans_a, int64_t m, int64_t n, float alpha, const uint16_t *A, int64_t lda,
-                   const uint16_t *x, int64_t incx, float beta, uint16_t *y, int64_t incy, void *stream);
+                   const uint16_t *x, int64_t incx, float beta, uint16_t *y, int64_t incy,
+                   void *workspace, size_t workspace_bytes, void *stream);
+/* Bytes of workspace with which mg_?gemv runs its preferred configuration (0 for most shapes;
+ * 0 for invalid arguments). */
+size_t mg_gemv_workspace_bytes(int dtype, int layout, int trans_a, int64_t m, int64_t n, int64_t lda);
 
 /* ---- generic batched GEMM (paper Section 4.6) -----------------------------------------
  * batch_count independent GEMMs of one shape.  Instance b uses A + a_offsets[b],

@@ -143,8 +143,7 @@ mg_status run_gemm(int dtype, int layout, int ta, int tb, int64_t m, int64_t n, 
 // Matrix-vector product as the one-row canonical problem  y^T = x^T op(A)^T: x is the 1 x K operand
 // with leading dimension incx, op(A)^T the K x M operand read in place, y the 1 x M result with leading
 // dimension incy.  The matrix-vector kernels take all three strides as they are.
-mg_status run_gemv(int dtype, int layout, int trans, int64_t m, int64_t n, float alpha, const void *A, int64_t lda,
-                   const void *x, int64_t incx, float beta, void *y, int64_t incy, void *stream)
+mg_status check_gemv(int layout, int trans, int64_t m, int64_t n, int64_t lda, int64_t incx, int64_t incy)
 {
     if (layout != MG_ROW_MAJOR && layout != MG_COL_MAJOR) return MG_ERR_LAYOUT;
     if (!valid_trans(trans)) return MG_ERR_TRANS_A;
@@ -153,21 +152,38 @@ mg_status run_gemv(int dtype, int layout, int trans, int64_t m, int64_t n, float
     const int64_t lead = layout == MG_COL_MAJOR ? m : n;
     if (lda < (lead > 1 ? lead : 1)) return MG_ERR_LDA;
     if (incx < 1 || incy < 1 || incx >= lim || incy >= lim) return MG_ERR_INC;
+    return MG_OK;
+}
+
+Problem gemv_problem(int dtype, int layout, int trans, int64_t m, int64_t n, float alpha, const void *A, int64_t lda,
+                     const void *x, int64_t incx, float beta, void *y, int64_t incy, void *ws, size_t ws_bytes,
+                     void *stream)
+{
     const bool t = trans != MG_NO_TRANS;
-    const int64_t outputs = t ? n : m, length = t ? m : n;
-    if (outputs == 0) return MG_OK;
-    const bool reads = alpha != 0.f && length != 0;
-    if (y == nullptr || (reads && (A == nullptr || x == nullptr))) return MG_ERR_NULL;
     Problem p{};
     p.dtype = dtype;
-    p.m = 1; p.n = outputs; p.k = length;
+    p.m = 1; p.n = t ? n : m; p.k = t ? m : n;
     p.A = x; p.lda = incx; p.a_trans = false;
     // op(A)^T (l, j) = op(A)(j, l): contiguous along the outputs exactly when the stored matrix has its
     // unit stride along op(A)'s rows
     p.B = A; p.ldb = lda; p.b_trans = (layout == MG_COL_MAJOR) != t;
     p.C = y; p.ldc = incy;
     p.alpha = alpha; p.beta = beta;
+    p.workspace = ws; p.workspace_bytes = ws_bytes;
     p.stream = static_cast<hipStream_t>(stream);
+    return p;
+}
+
+mg_status run_gemv(int dtype, int layout, int trans, int64_t m, int64_t n, float alpha, const void *A, int64_t lda,
+                   const void *x, int64_t incx, float beta, void *y, int64_t incy, void *ws, size_t ws_bytes,
+                   void *stream)
+{
+    const mg_status s = check_gemv(layout, trans, m, n, lda, incx, incy);
+    if (s != MG_OK) return s;
+    const Problem p = gemv_problem(dtype, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy, ws, ws_bytes, stream);
+    if (p.n == 0) return MG_OK;
+    const bool reads = alpha != 0.f && p.k != 0;
+    if (y == nullptr || (reads && (A == nullptr || x == nullptr))) return MG_ERR_NULL;
     return run_canonical(p);
 }
 
@@ -330,15 +346,31 @@ mg_status mg_hgemm(int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, 
 }
 
 mg_status mg_sgemv(int layout, int trans_a, int64_t m, int64_t n, float alpha, const float *A, int64_t lda,
-                   const float *x, int64_t incx, float beta, float *y, int64_t incy, void *stream)
+                   const float *x, int64_t incx, float beta, float *y, int64_t incy, void *workspace,
+                   size_t workspace_bytes, void *stream)
 {
-    return run_gemv(MG_F32, layout, trans_a, m, n, alpha, A, lda, x, incx, beta, y, incy, stream);
+    return run_gemv(MG_F32, layout, trans_a, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace, workspace_bytes,
+                    stream);
 }
 
 mg_status mg_hgemv(int layout, int trans_a, int64_t m, int64_t n, float alpha, const uint16_t *A, int64_t lda,
-                   const uint16_t *x, int64_t incx, float beta, uint16_t *y, int64_t incy, void *stream)
+                   const uint16_t *x, int64_t incx, float beta, uint16_t *y, int64_t incy, void *workspace,
+                   size_t workspace_bytes, void *stream)
 {
-    return run_gemv(MG_F16, layout, trans_a, m, n, alpha, A, lda, x, incx, beta, y, incy, stream);
+    return run_gemv(MG_F16, layout, trans_a, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace, workspace_bytes,
+                    stream);
+}
+
+size_t mg_gemv_workspace_bytes(int dtype, int layout, int trans_a, int64_t m, int64_t n, int64_t lda)
+{
+    if (dtype != MG_F32 && dtype != MG_F16) return 0;
+    if (check_gemv(layout, trans_a, m, n, lda, 1, 1) != MG_OK) return 0;
+    const Problem p = gemv_problem(dtype, layout, trans_a, m, n, 1.f, nullptr, lda, nullptr, 1, 1.f, nullptr, 1, nullptr,
+                                   0, nullptr);
+    if (p.n == 0) return 0;
+    int32_t kernel = -1, split = 1;
+    if (choose(p, 256, ~size_t(0), &kernel, &split) != MG_OK) return 0;
+    return table()[kernel].workspace(p, split);
 }
 
 mg_status mg_sgemm_batched(int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, const float *alphas,

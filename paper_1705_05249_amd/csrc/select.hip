@@ -62,6 +62,24 @@ int pick_split(int64_t blocks, int64_t ktiles)
     return split < 1 ? 1 : static_cast<int>(split);
 }
 
+// Slices of the sum for a matrix-vector product.  Measured: the axpy kernel (32 KB of loads in flight per
+// work-group) is fastest with about two work-groups per compute unit, the dot kernel (16 KB) with four; more
+// gain nothing and the reduce pass costs.  Each slice keeps at least four rounds of loads, and the partial
+// sums must fit the workspace.
+int pick_gemv_split(const mg_config &cfg, int64_t outputs, int64_t k, size_t workspace_bytes)
+{
+    const bool dot = cfg.lds_bytes == 0;
+    const int64_t wanted = (dot ? 4 : 2) * kComputeUnits;
+    const int64_t groups = ceil_div(outputs, cfg.tile_m);
+    if (2 * groups > wanted) return 1;
+    int64_t split = ceil_div(wanted, groups);
+    if (split > k / (4 * cfg.tile_k)) split = k / (4 * cfg.tile_k);
+    if (split > 256) split = 256;
+    const int64_t fits = static_cast<int64_t>(workspace_bytes / (static_cast<size_t>(outputs) * sizeof(float)));
+    if (split > fits) split = fits;
+    return split < 1 ? 1 : static_cast<int>(split);
+}
+
 }  // namespace
 
 void select_config(const std::vector<KernelEntry> &table, const Problem &p, int64_t alignment, size_t workspace_bytes,
@@ -75,8 +93,17 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
         return;
     }
     if (p.m == 1 || p.n == 1) {
-        if (try_pick(table, p, alignment, f32 ? "gemv_dot_f32" : "gemv_dot_f16", 1, kernel, split)) return;
-        if (try_pick(table, p, alignment, f32 ? "gemv_axpy_f32" : "gemv_axpy_f16", 1, kernel, split)) return;
+        // short rows, thousands of them: four rows per wavefront keep enough loads in flight (long rows a power
+        // of two apart are slower that way than one by one)
+        const bool many = p.m * p.n >= 16 * kComputeUnits && p.k * static_cast<int64_t>(p.elem()) <= 4096;
+        const char *names[2] = {f32 ? (many ? "gemv_dot4_f32" : "gemv_dot_f32") : (many ? "gemv_dot4_f16" : "gemv_dot_f16"),
+                                f32 ? "gemv_axpy_f32" : "gemv_axpy_f16"};
+        for (const char *name : names) {
+            if (!try_pick(table, p, alignment, name, 1, kernel, split)) continue;
+            const int want = pick_gemv_split(table[*kernel].cfg, p.m * p.n, p.k, workspace_bytes);
+            if (want > 1) try_pick(table, p, alignment, name, want, kernel, split);
+            return;
+        }
     }
     if (p.m >= 16 && p.n >= 16) {
         // Largest macro tile that still gives (nearly) every compute unit a tile of its own; short K goes

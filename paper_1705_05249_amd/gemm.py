@@ -17,7 +17,7 @@ MG_F32, MG_F16 = 0, 1
 MG_OK = 0
 MG_FAMILY_DIRECT, MG_FAMILY_MFMA, MG_FAMILY_GEMV, MG_FAMILY_SCALE, MG_FAMILY_BATCHED = 0, 1, 2, 3, 4
 
-EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemv", "mg_hgemv", "mg_sgemm_batched", "mg_sgemm_strided_batched", "mg_hgemm_batched",
+EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemv", "mg_hgemv", "mg_gemv_workspace_bytes", "mg_sgemm_batched", "mg_sgemm_strided_batched", "mg_hgemm_batched",
            "mg_hgemm_strided_batched", "mg_gemm_workspace_bytes",
            "mg_sim2col", "mg_him2col", "mg_sconv2d", "mg_hconv2d", "mg_conv2d_workspace_bytes", "mg_conv2d_out_extent",
            "mg_kernel_count",
@@ -64,11 +64,13 @@ def lib():
         L.mg_sgemm.restype = i32
         L.mg_hgemm.argtypes = gemm_args
         L.mg_hgemm.restype = i32
-        gemv_args = [i32, i32, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64, vp]
+        gemv_args = [i32, i32, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64, vp, sz, vp]
         L.mg_sgemv.argtypes = gemv_args
         L.mg_sgemv.restype = i32
         L.mg_hgemv.argtypes = gemv_args
         L.mg_hgemv.restype = i32
+        L.mg_gemv_workspace_bytes.argtypes = [i32, i32, i32, i64, i64, i64]
+        L.mg_gemv_workspace_bytes.restype = sz
         L.mg_sgemm_batched.argtypes = [i32, i32, i32, i64, i64, i64, vp, vp, vp, i64, vp, vp, i64, vp, vp, vp, i64,
                                        i64, vp]
         L.mg_sgemm_batched.restype = i32
@@ -163,20 +165,28 @@ def mg_hgemm(layout, trans_a, trans_b, m, n, k, alpha, A, lda, B, ldb, beta, C, 
     return st
 
 
-def mg_sgemv(layout, trans_a, m, n, alpha, A, lda, x, incx, beta, y, incy, stream=None, check=True) -> int:
-    st = lib().mg_sgemv(layout, trans_a, m, n, alpha, _addr(A), lda, _addr(x), incx, beta, _addr(y), incy,
+def mg_sgemv(layout, trans_a, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None,
+             check=True) -> int:
+    ws, ws_bytes = _ws(workspace)
+    st = lib().mg_sgemv(layout, trans_a, m, n, alpha, _addr(A), lda, _addr(x), incx, beta, _addr(y), incy, ws, ws_bytes,
                         _stream(stream))
     if check and st != MG_OK:
         raise MgError(st, "mg_sgemv")
     return st
 
 
-def mg_hgemv(layout, trans_a, m, n, alpha, A, lda, x, incx, beta, y, incy, stream=None, check=True) -> int:
-    st = lib().mg_hgemv(layout, trans_a, m, n, alpha, _addr(A), lda, _addr(x), incx, beta, _addr(y), incy,
+def mg_hgemv(layout, trans_a, m, n, alpha, A, lda, x, incx, beta, y, incy, workspace=None, stream=None,
+             check=True) -> int:
+    ws, ws_bytes = _ws(workspace)
+    st = lib().mg_hgemv(layout, trans_a, m, n, alpha, _addr(A), lda, _addr(x), incx, beta, _addr(y), incy, ws, ws_bytes,
                         _stream(stream))
     if check and st != MG_OK:
         raise MgError(st, "mg_hgemv")
     return st
+
+
+def mg_gemv_workspace_bytes(dtype, layout, trans_a, m, n, lda) -> int:
+    return lib().mg_gemv_workspace_bytes(dtype, layout, trans_a, m, n, lda)
 
 
 def mg_sgemm_batched(layout, trans_a, trans_b, m, n, k, alphas, A, a_offsets, lda, B, b_offsets, ldb, betas, C,

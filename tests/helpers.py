@@ -161,25 +161,29 @@ def check_conv(case, conv_oracle):
     return err
 
 
-def run_gemv(case, check=True):
+def run_gemv(case, check=True, workspace="auto"):
     """Runs one GemvCase through the C ABI; returns (status, flat y buffer after the call)."""
     import torch
     from paper_1705_05249_amd import gemm as G
     fn = G.mg_sgemv if case.dtype == "f32" else G.mg_hgemv
+    if isinstance(workspace, str):
+        need = G.mg_gemv_workspace_bytes(G.MG_F32 if case.dtype == "f32" else G.MG_F16, case.layout, case.trans,
+                                         case.m, case.n, case.lda)
+        workspace = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
     A = to_gpu(case.A if case.A.size else np.zeros(1, dtype=case.A.dtype))
     x, y = to_gpu(case.x), to_gpu(case.y)
     st = fn(case.layout, case.trans, case.m, case.n, case.alpha, A, case.lda, x, case.incx, case.beta, y,
-            case.incy, None, check=check)
+            case.incy, workspace, None, check=check)
     torch.cuda.synchronize()
     return st, y.cpu().numpy()
 
 
-def check_gemv(case, oracle):
+def check_gemv(case, oracle, workspace="auto"):
     """Element-by-element comparison of a GEMV call with the oracle; the slots between the elements of y
     must keep their bytes.  Returns the error."""
     y_ref, d_ref = oracle.gemv(case.dtype, case.layout, case.trans, case.m, case.n, case.alpha, case.A, case.lda,
                                case.x, case.incx, case.beta, case.y, case.incy)
-    _, out = run_gemv(case)
+    _, out = run_gemv(case, workspace=workspace)
     rows = case.outputs
     got = out[: (rows - 1) * case.incy + 1: case.incy] if rows else out[:0]
     mask = np.ones(out.size, dtype=bool)

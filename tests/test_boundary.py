@@ -170,7 +170,7 @@ def test_gemv_argument_errors(fn):
     f = getattr(G.lib(), fn)
 
     def call(layout=C, trans=N, m=4, n=3, A=FAKE, lda=4, x=FAKE, incx=1, y=FAKE, incy=1, alpha=1.0, beta=0.0):
-        return f(layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy, None)
+        return f(layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy, None, 0, None)
 
     assert call(layout=7) == -1 and call(trans=5) == -2
     assert call(m=-1) == -4 and call(n=-1) == -4 and call(m=1 << 31) == -4
@@ -180,6 +180,16 @@ def test_gemv_argument_errors(fn):
     # no output: nothing to do, whatever the pointers are
     assert call(m=0, lda=1, A=None, x=None, y=None) == 0
     assert call(trans=T, n=0, A=None, x=None, y=None) == 0
+
+
+def test_gemv_workspace_query():
+    """few outputs and a long sum ask for room for the partial sums; many outputs, or bad arguments, for none"""
+    assert G.mg_gemv_workspace_bytes(G.MG_F32, C, N, 1 << 17, 1 << 12, 1 << 17) == 0
+    few = G.mg_gemv_workspace_bytes(G.MG_F32, C, N, 4096, 1 << 15, 4096)
+    assert few > 0 and few % (4096 * 4) == 0 and few <= 256 * 4096 * 4
+    assert G.mg_gemv_workspace_bytes(G.MG_F16, C, T, 1 << 16, 16, 1 << 16) == 32 * 16 * 4     # 65536 / (4 * 512): 32 slices of four rounds each
+    assert G.mg_gemv_workspace_bytes(G.MG_F32, C, N, 4096, 1 << 15, 100) == 0
+    assert G.mg_gemv_workspace_bytes(9, C, N, 4096, 1 << 15, 4096) == 0
 
 
 def test_status_strings_and_version():

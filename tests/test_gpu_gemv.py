@@ -64,11 +64,33 @@ def test_large_matrices(oracle, dtype, shape, layout, trans):
     H.check_gemv(case, oracle)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("layout,trans", [(C, N), (C, T), (R, N), (R, T)])
+@pytest.mark.parametrize("shape", [(40, 9000), (9000, 40), (700, 5000), (1, 70000), (70000, 1), (3, 4099)])
+@pytest.mark.parametrize("workspace", ["auto", None, 4096])
+def test_few_outputs_and_a_long_sum(oracle, dtype, layout, trans, shape, workspace):
+    """shapes whose sum is cut into slices when the workspace allows: full, none, and room for a few slices only"""
+    import torch
+    m, n = shape
+    case = W.gemv_case(dtype, layout, trans, m, n, incx=1, incy=2, alpha=0.5, beta=2.0, pad=1, case=m + n)
+    ws = torch.empty(workspace, dtype=torch.uint8, device="cuda") if isinstance(workspace, int) else workspace
+    H.check_gemv(case, oracle, workspace=ws)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_sliced_sum_of_integers_is_exact(oracle, dtype):
+    for layout, trans in ((C, N), (C, T)):
+        case = W.gemv_case(dtype, layout, trans, 50, 8200, alpha=1.0, beta=1.0, integer=True, case=5)
+        case2 = W.gemv_case(dtype, layout, trans, 8200, 50, alpha=1.0, beta=1.0, integer=True, case=6)
+        H.check_gemv(case, oracle)
+        H.check_gemv(case2, oracle)
+
+
 def test_same_result_as_the_gemm_entry_point_with_one_column(oracle):
     """the stand-alone call and the n = 1 GEMM run the same kernel: same bits"""
     import torch
     case = W.gemv_case("f32", C, N, 777, 333, alpha=1.5, beta=0.25, case=31)
-    _, out = H.run_gemv(case)
+    _, out = H.run_gemv(case, workspace=None)
     A, x, y = H.to_gpu(case.A), H.to_gpu(case.x), H.to_gpu(case.y)
     G.mg_sgemm(C, N, N, 777, 1, 333, 1.5, A, case.lda, x, 333, 0.25, y, 777)
     torch.cuda.synchronize()
