@@ -7,7 +7,7 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "gemm_oracle.c")
-SOURCES = [SRC, os.path.join(HERE, "conv_oracle.c")]
+SOURCES = [SRC, os.path.join(HERE, "conv_oracle.c"), os.path.join(HERE, "level3_oracle.c")]
 HEADERS = [os.path.join(HERE, "half_bits.h")]
 LIB = os.path.join(HERE, "libgemm_oracle.so")
 
