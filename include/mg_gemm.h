@@ -64,12 +64,18 @@ enum {
     MG_ERR_NO_DEVICE = -13,   /* no usable gfx950 device / HIP runtime error before launch  */
     MG_ERR_STRIDE = -14,      /* a batch stride is negative                                 */
     MG_ERR_CONV = -15,        /* convolution geometry: an extent < 1, a pad < 0, stride or dilation < 1 */
-    MG_ERR_INC = -16          /* a vector increment below 1                                  */
+    MG_ERR_INC = -16,         /* a vector increment below 1                                  */
+    MG_ERR_SIDE = -17,        /* side is neither MG_LEFT nor MG_RIGHT                        */
+    MG_ERR_UPLO = -18,        /* uplo is neither MG_UPPER nor MG_LOWER                       */
+    MG_ERR_DIAG = -19         /* diag is neither MG_NON_UNIT nor MG_UNIT                     */
 };
 
 typedef enum { MG_ROW_MAJOR = 101, MG_COL_MAJOR = 102 } mg_layout;
 /* MG_CONJ_TRANS is accepted and equals MG_TRANS for these real types. */
 typedef enum { MG_NO_TRANS = 111, MG_TRANS = 112, MG_CONJ_TRANS = 113 } mg_trans;
+typedef enum { MG_UPPER = 121, MG_LOWER = 122 } mg_uplo;
+typedef enum { MG_NON_UNIT = 131, MG_UNIT = 132 } mg_diag;
+typedef enum { MG_LEFT = 141, MG_RIGHT = 142 } mg_side;
 
 typedef enum { MG_F32 = 0, MG_F16 = 1 } mg_dtype;
 
@@ -134,6 +140,47 @@ mg_status mg_hgemv(int layout, int trans_a, int64_t m, int64_t n, float alpha, c
 /* Bytes of workspace with which mg_?gemv runs its preferred configuration (0 for most shapes;
  * 0 for invalid arguments). */
 size_t mg_gemv_workspace_bytes(int dtype, int layout, int trans_a, int64_t m, int64_t n, int64_t lda);
+
+/* ---- GEMM-derived level-3 routines: SYMM, SYRK, TRMM ------------------------------------
+ * The paper's routine table lists them and Section 3.1 says the gemm kernel family serves them with
+ * the help of support kernels; the definitions are the BLAS ones.  Same conventions as GEMM (layout,
+ * leading dimensions, FP32 accumulation, one rounding, alpha == 0 / beta == 0 rules, device
+ * pointers, asynchronous on `stream`).  Each call first writes the special operand out as a dense
+ * matrix in the workspace and then runs the GEMM kernels, so unlike GEMM the workspace is REQUIRED:
+ * 256-byte aligned and at least mg_<routine>_workspace_bytes() for the same arguments
+ * (MG_ERR_WORKSPACE otherwise; 0 is returned for invalid arguments or empty problems).
+ *
+ *   SYMM  C = alpha*A*B + beta*C (MG_LEFT, A m x m) or alpha*B*A + beta*C (MG_RIGHT, A n x n);
+ *         B, C m x n.  A symmetric; only its `uplo` triangle is read.
+ *   SYRK  C = alpha*A*A^T + beta*C (MG_NO_TRANS, A n x k) or alpha*A^T*A + beta*C (MG_TRANS, A k x n);
+ *         C n x n; only its `uplo` triangle is changed (the rest keeps its bytes; it is read and
+ *         written back unchanged, so it must be valid memory).  The product is computed for all of
+ *         C: twice the minimal arithmetic.
+ *   TRMM  B = alpha*op(A)*B (MG_LEFT, A m x m) or alpha*B*op(A) (MG_RIGHT, A n x n); B m x n, in
+ *         place.  A triangular: entries outside its `uplo` triangle are not read and count as zero,
+ *         with MG_UNIT the diagonal is not read and counts as one.  The zeros take part in the
+ *         product as numbers (0 * Inf = NaN, unlike a reference BLAS that skips them).
+ * Errors: MG_ERR_LAYOUT, MG_ERR_SIDE, MG_ERR_UPLO, MG_ERR_TRANS_A, MG_ERR_DIAG, MG_ERR_DIM,
+ * MG_ERR_LDA/LDB/LDC, MG_ERR_NULL, MG_ERR_WORKSPACE. */
+mg_status mg_ssymm(int layout, int side, int uplo, int64_t m, int64_t n, float alpha, const float *A, int64_t lda,
+                   const float *B, int64_t ldb, float beta, float *C, int64_t ldc,
+                   void *workspace, size_t workspace_bytes, void *stream);
+mg_status mg_hsymm(int layout, int side, int uplo, int64_t m, int64_t n, float alpha, const uint16_t *A, int64_t lda,
+                   const uint16_t *B, int64_t ldb, float beta, uint16_t *C, int64_t ldc,
+                   void *workspace, size_t workspace_bytes, void *stream);
+mg_status mg_ssyrk(int layout, int uplo, int trans, int64_t n, int64_t k, float alpha, const float *A, int64_t lda,
+                   float beta, float *C, int64_t ldc, void *workspace, size_t workspace_bytes, void *stream);
+mg_status mg_hsyrk(int layout, int uplo, int trans, int64_t n, int64_t k, float alpha, const uint16_t *A, int64_t lda,
+                   float beta, uint16_t *C, int64_t ldc, void *workspace, size_t workspace_bytes, void *stream);
+mg_status mg_strmm(int layout, int side, int uplo, int trans_a, int diag, int64_t m, int64_t n, float alpha,
+                   const float *A, int64_t lda, float *B, int64_t ldb,
+                   void *workspace, size_t workspace_bytes, void *stream);
+mg_status mg_htrmm(int layout, int side, int uplo, int trans_a, int diag, int64_t m, int64_t n, float alpha,
+                   const uint16_t *A, int64_t lda, uint16_t *B, int64_t ldb,
+                   void *workspace, size_t workspace_bytes, void *stream);
+size_t mg_symm_workspace_bytes(int dtype, int layout, int side, int64_t m, int64_t n);
+size_t mg_syrk_workspace_bytes(int dtype, int layout, int trans, int64_t n, int64_t k);
+size_t mg_trmm_workspace_bytes(int dtype, int layout, int side, int trans_a, int64_t m, int64_t n);
 
 /* ---- generic batched GEMM (paper Section 4.6) -----------------------------------------
  * batch_count independent GEMMs of one shape.  Instance b uses A + a_offsets[b],

@@ -322,6 +322,163 @@ mg_status run_conv2d(int dtype, const ConvShape &s, int64_t filters, float alpha
                     n, rest_bytes ? rest : nullptr, rest_bytes, stream);
 }
 
+// ---- GEMM-derived level-3 routines: a support kernel makes the special operand general (or sets the
+// untouched part of C aside), then the product is run_gemm.  Workspace layout: the dense operand(s) first,
+// each rounded up to 256 bytes, the GEMM's own scratch (split-K) behind them.
+
+bool valid_side(int v) { return v == MG_LEFT || v == MG_RIGHT; }
+bool valid_uplo(int v) { return v == MG_UPPER || v == MG_LOWER; }
+bool valid_diag(int v) { return v == MG_NON_UNIT || v == MG_UNIT; }
+
+// the stored triangle as it appears in the column-major view of the bytes
+bool lower_in_view(int layout, int uplo) { return (layout == MG_COL_MAJOR) == (uplo == MG_LOWER); }
+
+struct Carve {
+    char *at;
+    size_t left;
+    bool ok;
+    Carve(void *ws, size_t bytes) : at(static_cast<char *>(ws)), left(bytes), ok(ws != nullptr && pointer_alignment(ws) >= 256) {}
+    void *take(size_t bytes)
+    {
+        bytes = round_up_256(bytes);
+        if (!ok || left < bytes) { ok = false; return nullptr; }
+        void *p = at;
+        at += bytes;
+        left -= bytes;
+        return p;
+    }
+    void *rest() const { return ok && left > 0 ? at : nullptr; }
+};
+
+mg_status check_symm(int layout, int side, int uplo, int64_t m, int64_t n, int64_t lda, int64_t ldb, int64_t ldc)
+{
+    if (layout != MG_ROW_MAJOR && layout != MG_COL_MAJOR) return MG_ERR_LAYOUT;
+    if (!valid_side(side)) return MG_ERR_SIDE;
+    if (!valid_uplo(uplo)) return MG_ERR_UPLO;
+    const int64_t lim = int64_t(1) << 31;
+    if (m < 0 || n < 0 || m >= lim || n >= lim) return MG_ERR_DIM;
+    const int64_t ka = side == MG_LEFT ? m : n, lead = layout == MG_COL_MAJOR ? m : n;
+    if (lda < (ka > 1 ? ka : 1)) return MG_ERR_LDA;
+    if (ldb < (lead > 1 ? lead : 1)) return MG_ERR_LDB;
+    if (ldc < (lead > 1 ? lead : 1)) return MG_ERR_LDC;
+    if (ka > 32 * 65535) return MG_ERR_DIM;
+    return MG_OK;
+}
+
+mg_status run_symm(int dtype, int layout, int side, int uplo, int64_t m, int64_t n, float alpha, const void *A, int64_t lda,
+                   const void *B, int64_t ldb, float beta, void *C, int64_t ldc, void *ws, size_t ws_bytes, void *stream)
+{
+    const mg_status s = check_symm(layout, side, uplo, m, n, lda, ldb, ldc);
+    if (s != MG_OK) return s;
+    if (m == 0 || n == 0) return MG_OK;
+    if (C == nullptr || (alpha != 0.f && (A == nullptr || B == nullptr))) return MG_ERR_NULL;
+    if (alpha == 0.f) {     // C <- beta * C: an empty product (the unused leading dimensions only have to be legal)
+        const int64_t any = m > n ? m : n;
+        return run_gemm(dtype, layout, MG_NO_TRANS, MG_NO_TRANS, m, n, 0, 0.f, nullptr, any, nullptr, any, beta, C, ldc,
+                        nullptr, 0, stream);
+    }
+    const int64_t ka = side == MG_LEFT ? m : n;
+    const size_t elem = dtype == MG_F32 ? 4 : 2;
+    Carve carve(ws, ws_bytes);
+    void *full = carve.take(static_cast<size_t>(ka) * ka * elem);
+    if (full == nullptr) return MG_ERR_WORKSPACE;
+    if (launch_expand_symmetric(dtype, ka, A, lda, lower_in_view(layout, uplo), full, static_cast<hipStream_t>(stream)) !=
+        hipSuccess)
+        return MG_ERR_LAUNCH;
+    // a symmetric dense matrix with leading dimension ka reads the same in either layout
+    if (side == MG_LEFT)
+        return run_gemm(dtype, layout, MG_NO_TRANS, MG_NO_TRANS, m, n, m, alpha, full, ka, B, ldb, beta, C, ldc, carve.rest(),
+                        carve.left, stream);
+    return run_gemm(dtype, layout, MG_NO_TRANS, MG_NO_TRANS, m, n, n, alpha, B, ldb, full, ka, beta, C, ldc, carve.rest(),
+                    carve.left, stream);
+}
+
+mg_status check_syrk(int layout, int uplo, int trans, int64_t n, int64_t k, int64_t lda, int64_t ldc)
+{
+    if (layout != MG_ROW_MAJOR && layout != MG_COL_MAJOR) return MG_ERR_LAYOUT;
+    if (!valid_uplo(uplo)) return MG_ERR_UPLO;
+    if (!valid_trans(trans)) return MG_ERR_TRANS_A;
+    const int64_t lim = int64_t(1) << 31;
+    if (n < 0 || k < 0 || n >= lim || k >= lim) return MG_ERR_DIM;
+    // A is n x k (no transpose) or k x n as stored
+    const bool rows_are_n = trans == MG_NO_TRANS;
+    const int64_t lead = (layout == MG_COL_MAJOR) == rows_are_n ? n : k;
+    if (lda < (lead > 1 ? lead : 1)) return MG_ERR_LDA;
+    if (ldc < (n > 1 ? n : 1)) return MG_ERR_LDC;
+    return MG_OK;
+}
+
+mg_status run_syrk(int dtype, int layout, int uplo, int trans, int64_t n, int64_t k, float alpha, const void *A, int64_t lda,
+                   float beta, void *C, int64_t ldc, void *ws, size_t ws_bytes, void *stream)
+{
+    const mg_status s = check_syrk(layout, uplo, trans, n, k, lda, ldc);
+    if (s != MG_OK) return s;
+    if (n == 0) return MG_OK;
+    const bool reads_a = alpha != 0.f && k != 0;
+    if (C == nullptr || (reads_a && A == nullptr)) return MG_ERR_NULL;
+    const size_t elem = dtype == MG_F32 ? 4 : 2;
+    Carve carve(ws, ws_bytes);
+    void *aside = carve.take(static_cast<size_t>(n) * n * elem);
+    if (aside == nullptr) return MG_ERR_WORKSPACE;
+    // the GEMM below writes all of C: the entries outside the referenced triangle are set aside first and
+    // put back afterwards, bit for bit
+    const bool other_is_lower = !lower_in_view(layout, uplo);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (launch_copy_triangle(dtype, n, C, ldc, aside, n, other_is_lower, st) != hipSuccess) return MG_ERR_LAUNCH;
+    const bool nt = trans == MG_NO_TRANS;
+    const mg_status g = run_gemm(dtype, layout, nt ? MG_NO_TRANS : MG_TRANS, nt ? MG_TRANS : MG_NO_TRANS, n, n, k, alpha, A, lda,
+                                 A, lda, beta, C, ldc, carve.rest(), carve.left, stream);
+    // put the other triangle back even if the product failed to launch: C is then as it was there
+    if (launch_copy_triangle(dtype, n, aside, n, C, ldc, other_is_lower, st) != hipSuccess) return MG_ERR_LAUNCH;
+    return g;
+}
+
+mg_status check_trmm(int layout, int side, int uplo, int trans, int diag, int64_t m, int64_t n, int64_t lda, int64_t ldb)
+{
+    if (layout != MG_ROW_MAJOR && layout != MG_COL_MAJOR) return MG_ERR_LAYOUT;
+    if (!valid_side(side)) return MG_ERR_SIDE;
+    if (!valid_uplo(uplo)) return MG_ERR_UPLO;
+    if (!valid_trans(trans)) return MG_ERR_TRANS_A;
+    if (!valid_diag(diag)) return MG_ERR_DIAG;
+    const int64_t lim = int64_t(1) << 31;
+    if (m < 0 || n < 0 || m >= lim || n >= lim) return MG_ERR_DIM;
+    const int64_t ka = side == MG_LEFT ? m : n, lead = layout == MG_COL_MAJOR ? m : n;
+    if (lda < (ka > 1 ? ka : 1)) return MG_ERR_LDA;
+    if (ldb < (lead > 1 ? lead : 1)) return MG_ERR_LDB;
+    return MG_OK;
+}
+
+mg_status run_trmm(int dtype, int layout, int side, int uplo, int trans, int diag, int64_t m, int64_t n, float alpha,
+                   const void *A, int64_t lda, void *B, int64_t ldb, void *ws, size_t ws_bytes, void *stream)
+{
+    const mg_status s = check_trmm(layout, side, uplo, trans, diag, m, n, lda, ldb);
+    if (s != MG_OK) return s;
+    if (m == 0 || n == 0) return MG_OK;
+    if (B == nullptr || (alpha != 0.f && A == nullptr)) return MG_ERR_NULL;
+    if (alpha == 0.f) {     // B <- 0: an empty product with beta == 0
+        const int64_t any = m > n ? m : n;
+        return run_gemm(dtype, layout, MG_NO_TRANS, MG_NO_TRANS, m, n, 0, 0.f, nullptr, any, nullptr, any, 0.f, B, ldb,
+                        nullptr, 0, stream);
+    }
+    const int64_t ka = side == MG_LEFT ? m : n;
+    const size_t elem = dtype == MG_F32 ? 4 : 2;
+    Carve carve(ws, ws_bytes);
+    void *full = carve.take(static_cast<size_t>(ka) * ka * elem);
+    void *copy = carve.take(static_cast<size_t>(m) * n * elem);
+    if (full == nullptr || copy == nullptr) return MG_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (launch_expand_triangular(dtype, ka, A, lda, lower_in_view(layout, uplo), diag == MG_UNIT, full, st) != hipSuccess)
+        return MG_ERR_LAUNCH;
+    // the product cannot run in place: B is copied (tightly packed, same layout) and then overwritten
+    const int64_t minor = layout == MG_COL_MAJOR ? m : n, major = layout == MG_COL_MAJOR ? n : m;
+    if (launch_copy_matrix(dtype, minor, major, B, ldb, copy, minor, st) != hipSuccess) return MG_ERR_LAUNCH;
+    if (side == MG_LEFT)
+        return run_gemm(dtype, layout, trans, MG_NO_TRANS, m, n, m, alpha, full, ka, copy, minor, 0.f, B, ldb, carve.rest(),
+                        carve.left, stream);
+    return run_gemm(dtype, layout, MG_NO_TRANS, trans, m, n, n, alpha, copy, minor, full, ka, 0.f, B, ldb, carve.rest(),
+                    carve.left, stream);
+}
+
 }  // namespace
 }  // namespace mg
 
@@ -407,6 +564,96 @@ mg_status mg_hgemm_strided_batched(int layout, int ta, int tb, int64_t m, int64_
 {
     return strided_batched(MG_F16, layout, ta, tb, m, n, k, alpha, A, lda, stride_a, B, ldb, stride_b, beta, C, ldc,
                            stride_c, batch_count, stream);
+}
+
+mg_status mg_ssymm(int layout, int side, int uplo, int64_t m, int64_t n, float alpha, const float *A, int64_t lda,
+                   const float *B, int64_t ldb, float beta, float *C, int64_t ldc, void *workspace, size_t workspace_bytes,
+                   void *stream)
+{
+    return run_symm(MG_F32, layout, side, uplo, m, n, alpha, A, lda, B, ldb, beta, C, ldc, workspace, workspace_bytes, stream);
+}
+
+mg_status mg_hsymm(int layout, int side, int uplo, int64_t m, int64_t n, float alpha, const uint16_t *A, int64_t lda,
+                   const uint16_t *B, int64_t ldb, float beta, uint16_t *C, int64_t ldc, void *workspace,
+                   size_t workspace_bytes, void *stream)
+{
+    return run_symm(MG_F16, layout, side, uplo, m, n, alpha, A, lda, B, ldb, beta, C, ldc, workspace, workspace_bytes, stream);
+}
+
+mg_status mg_ssyrk(int layout, int uplo, int trans, int64_t n, int64_t k, float alpha, const float *A, int64_t lda, float beta,
+                   float *C, int64_t ldc, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_syrk(MG_F32, layout, uplo, trans, n, k, alpha, A, lda, beta, C, ldc, workspace, workspace_bytes, stream);
+}
+
+mg_status mg_hsyrk(int layout, int uplo, int trans, int64_t n, int64_t k, float alpha, const uint16_t *A, int64_t lda,
+                   float beta, uint16_t *C, int64_t ldc, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_syrk(MG_F16, layout, uplo, trans, n, k, alpha, A, lda, beta, C, ldc, workspace, workspace_bytes, stream);
+}
+
+mg_status mg_strmm(int layout, int side, int uplo, int trans_a, int diag, int64_t m, int64_t n, float alpha, const float *A,
+                   int64_t lda, float *B, int64_t ldb, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_trmm(MG_F32, layout, side, uplo, trans_a, diag, m, n, alpha, A, lda, B, ldb, workspace, workspace_bytes, stream);
+}
+
+mg_status mg_htrmm(int layout, int side, int uplo, int trans_a, int diag, int64_t m, int64_t n, float alpha,
+                   const uint16_t *A, int64_t lda, uint16_t *B, int64_t ldb, void *workspace, size_t workspace_bytes,
+                   void *stream)
+{
+    return run_trmm(MG_F16, layout, side, uplo, trans_a, diag, m, n, alpha, A, lda, B, ldb, workspace, workspace_bytes, stream);
+}
+
+enum { MG_ROUTINE_SYMM, MG_ROUTINE_SYRK, MG_ROUTINE_TRMM };
+
+static size_t level3_workspace_bytes(int routine, int dtype, int layout, int side, int trans, int64_t m, int64_t n, int64_t k)
+{
+    if (dtype != MG_F32 && dtype != MG_F16) return 0;
+    if (layout != MG_ROW_MAJOR && layout != MG_COL_MAJOR) return 0;
+    const int64_t lim = int64_t(1) << 31;
+    if (m < 0 || n < 0 || k < 0 || m >= lim || n >= lim || k >= lim) return 0;
+    const size_t elem = dtype == MG_F32 ? 4 : 2;
+    const int64_t lead = layout == MG_COL_MAJOR ? m : n;
+    if (routine == MG_ROUTINE_SYRK) {
+        if (!valid_trans(trans) || n == 0) return 0;
+        const bool nt = trans == MG_NO_TRANS;
+        const int64_t la = (layout == MG_COL_MAJOR) == nt ? n : k;
+        return round_up_256(static_cast<size_t>(n) * n * elem) +
+               mg_gemm_workspace_bytes(dtype, layout, nt ? MG_NO_TRANS : MG_TRANS, nt ? MG_TRANS : MG_NO_TRANS, n, n, k,
+                                       la > 1 ? la : 1, la > 1 ? la : 1, n);
+    }
+    if (!valid_side(side) || m == 0 || n == 0) return 0;
+    const int64_t ka = side == MG_LEFT ? m : n;
+    const size_t dense = round_up_256(static_cast<size_t>(ka) * ka * elem);
+    if (routine == MG_ROUTINE_SYMM) {
+        const size_t gemm = side == MG_LEFT
+                                ? mg_gemm_workspace_bytes(dtype, layout, MG_NO_TRANS, MG_NO_TRANS, m, n, m, ka, lead, lead)
+                                : mg_gemm_workspace_bytes(dtype, layout, MG_NO_TRANS, MG_NO_TRANS, m, n, n, lead, ka, lead);
+        return dense + gemm;
+    }
+    if (routine == MG_ROUTINE_TRMM) {
+        if (!valid_trans(trans)) return 0;
+        const size_t gemm = side == MG_LEFT ? mg_gemm_workspace_bytes(dtype, layout, trans, MG_NO_TRANS, m, n, m, ka, lead, lead)
+                                            : mg_gemm_workspace_bytes(dtype, layout, MG_NO_TRANS, trans, m, n, n, lead, ka, lead);
+        return dense + round_up_256(static_cast<size_t>(m) * n * elem) + gemm;
+    }
+    return 0;
+}
+
+size_t mg_symm_workspace_bytes(int dtype, int layout, int side, int64_t m, int64_t n)
+{
+    return level3_workspace_bytes(MG_ROUTINE_SYMM, dtype, layout, side, MG_NO_TRANS, m, n, 0);
+}
+
+size_t mg_syrk_workspace_bytes(int dtype, int layout, int trans, int64_t n, int64_t k)
+{
+    return level3_workspace_bytes(MG_ROUTINE_SYRK, dtype, layout, MG_LEFT, trans, n, n, k);
+}
+
+size_t mg_trmm_workspace_bytes(int dtype, int layout, int side, int trans_a, int64_t m, int64_t n)
+{
+    return level3_workspace_bytes(MG_ROUTINE_TRMM, dtype, layout, side, trans_a, m, n, 0);
 }
 
 size_t mg_gemm_workspace_bytes(int dtype, int layout, int ta, int tb, int64_t m, int64_t n, int64_t k,
@@ -548,10 +795,13 @@ const char *mg_status_string(mg_status status)
         case MG_ERR_STRIDE: return "negative batch stride";
         case MG_ERR_CONV: return "invalid convolution geometry";
         case MG_ERR_INC: return "vector increment below one";
+        case MG_ERR_SIDE: return "invalid side";
+        case MG_ERR_UPLO: return "invalid uplo";
+        case MG_ERR_DIAG: return "invalid diag";
         default: return "unknown status";
     }
 }
 
-const char *mg_version(void) { return "0.4"; }
+const char *mg_version(void) { return "0.5"; }
 
 }  // extern "C"

@@ -74,6 +74,21 @@ int64_t conv_out_extent(int64_t size, int64_t kernel, int64_t pad, int64_t strid
 // dtype: mg_dtype.  The column matrix must have fewer than 2^31 elements.
 hipError_t launch_im2col(int dtype, const ConvShape &s, const void *im, void *col, hipStream_t stream);
 
+// Support kernels of the GEMM-derived level-3 routines.  Matrices are seen in the column-major view of
+// their bytes (element (i, j) at p[i + j*ld]); dtype: mg_dtype; dense outputs have leading dimension n.
+// dst <- the whole symmetric n x n matrix from its stored lower (i >= j) or upper triangle
+hipError_t launch_expand_symmetric(int dtype, int64_t n, const void *src, int64_t ld, bool lower, void *dst,
+                                   hipStream_t stream);
+// dst <- the triangular n x n matrix with zeros outside the triangle and ones on a unit diagonal
+hipError_t launch_expand_triangular(int dtype, int64_t n, const void *src, int64_t ld, bool lower, bool unit, void *dst,
+                                    hipStream_t stream);
+// dst <- src: `major` runs of `minor` contiguous elements
+hipError_t launch_copy_matrix(int dtype, int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
+                              hipStream_t stream);
+// dst <- src on the strictly lower (i > j) or strictly upper entries of an n x n matrix
+hipError_t launch_copy_triangle(int dtype, int64_t n, const void *src, int64_t lds, void *dst, int64_t ldd, bool lower,
+                                hipStream_t stream);
+
 // One compiled kernel (or kernel family instance) in the configuration table.
 struct KernelEntry {
     const char *name;

@@ -14,10 +14,15 @@ LIB_PATH = os.path.join(HERE, "libmg_gemm.so")
 MG_ROW_MAJOR, MG_COL_MAJOR = 101, 102
 MG_NO_TRANS, MG_TRANS, MG_CONJ_TRANS = 111, 112, 113
 MG_F32, MG_F16 = 0, 1
+MG_UPPER, MG_LOWER = 121, 122
+MG_NON_UNIT, MG_UNIT = 131, 132
+MG_LEFT, MG_RIGHT = 141, 142
 MG_OK = 0
 MG_FAMILY_DIRECT, MG_FAMILY_MFMA, MG_FAMILY_GEMV, MG_FAMILY_SCALE, MG_FAMILY_BATCHED = 0, 1, 2, 3, 4
 
-EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemv", "mg_hgemv", "mg_gemv_workspace_bytes", "mg_sgemm_batched", "mg_sgemm_strided_batched", "mg_hgemm_batched",
+EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemv", "mg_hgemv", "mg_gemv_workspace_bytes",
+           "mg_ssymm", "mg_hsymm", "mg_ssyrk", "mg_hsyrk", "mg_strmm", "mg_htrmm", "mg_symm_workspace_bytes",
+           "mg_syrk_workspace_bytes", "mg_trmm_workspace_bytes", "mg_sgemm_batched", "mg_sgemm_strided_batched", "mg_hgemm_batched",
            "mg_hgemm_strided_batched", "mg_gemm_workspace_bytes",
            "mg_sim2col", "mg_him2col", "mg_sconv2d", "mg_hconv2d", "mg_conv2d_workspace_bytes", "mg_conv2d_out_extent",
            "mg_kernel_count",
@@ -71,6 +76,19 @@ def lib():
         L.mg_hgemv.restype = i32
         L.mg_gemv_workspace_bytes.argtypes = [i32, i32, i32, i64, i64, i64]
         L.mg_gemv_workspace_bytes.restype = sz
+        symm_args = [i32, i32, i32, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64, vp, sz, vp]
+        syrk_args = [i32, i32, i32, i64, i64, f32, vp, i64, f32, vp, i64, vp, sz, vp]
+        trmm_args = [i32, i32, i32, i32, i32, i64, i64, f32, vp, i64, vp, i64, vp, sz, vp]
+        for name, args in (("mg_ssymm", symm_args), ("mg_hsymm", symm_args), ("mg_ssyrk", syrk_args),
+                           ("mg_hsyrk", syrk_args), ("mg_strmm", trmm_args), ("mg_htrmm", trmm_args)):
+            getattr(L, name).argtypes = args
+            getattr(L, name).restype = i32
+        L.mg_symm_workspace_bytes.argtypes = [i32, i32, i32, i64, i64]
+        L.mg_symm_workspace_bytes.restype = sz
+        L.mg_syrk_workspace_bytes.argtypes = [i32, i32, i32, i64, i64]
+        L.mg_syrk_workspace_bytes.restype = sz
+        L.mg_trmm_workspace_bytes.argtypes = [i32, i32, i32, i32, i64, i64]
+        L.mg_trmm_workspace_bytes.restype = sz
         L.mg_sgemm_batched.argtypes = [i32, i32, i32, i64, i64, i64, vp, vp, vp, i64, vp, vp, i64, vp, vp, vp, i64,
                                        i64, vp]
         L.mg_sgemm_batched.restype = i32
@@ -183,6 +201,69 @@ def mg_hgemv(layout, trans_a, m, n, alpha, A, lda, x, incx, beta, y, incy, works
     if check and st != MG_OK:
         raise MgError(st, "mg_hgemv")
     return st
+
+
+def _symm(name, layout, side, uplo, m, n, alpha, A, lda, B, ldb, beta, C, ldc, workspace, stream, check):
+    ws, ws_bytes = _ws(workspace)
+    st = getattr(lib(), name)(layout, side, uplo, m, n, alpha, _addr(A), lda, _addr(B), ldb, beta, _addr(C), ldc, ws,
+                              ws_bytes, _stream(stream))
+    if check and st != MG_OK:
+        raise MgError(st, name)
+    return st
+
+
+def mg_ssymm(layout, side, uplo, m, n, alpha, A, lda, B, ldb, beta, C, ldc, workspace=None, stream=None, check=True) -> int:
+    return _symm("mg_ssymm", layout, side, uplo, m, n, alpha, A, lda, B, ldb, beta, C, ldc, workspace, stream, check)
+
+
+def mg_hsymm(layout, side, uplo, m, n, alpha, A, lda, B, ldb, beta, C, ldc, workspace=None, stream=None, check=True) -> int:
+    return _symm("mg_hsymm", layout, side, uplo, m, n, alpha, A, lda, B, ldb, beta, C, ldc, workspace, stream, check)
+
+
+def _syrk(name, layout, uplo, trans, n, k, alpha, A, lda, beta, C, ldc, workspace, stream, check):
+    ws, ws_bytes = _ws(workspace)
+    st = getattr(lib(), name)(layout, uplo, trans, n, k, alpha, _addr(A), lda, beta, _addr(C), ldc, ws, ws_bytes,
+                              _stream(stream))
+    if check and st != MG_OK:
+        raise MgError(st, name)
+    return st
+
+
+def mg_ssyrk(layout, uplo, trans, n, k, alpha, A, lda, beta, C, ldc, workspace=None, stream=None, check=True) -> int:
+    return _syrk("mg_ssyrk", layout, uplo, trans, n, k, alpha, A, lda, beta, C, ldc, workspace, stream, check)
+
+
+def mg_hsyrk(layout, uplo, trans, n, k, alpha, A, lda, beta, C, ldc, workspace=None, stream=None, check=True) -> int:
+    return _syrk("mg_hsyrk", layout, uplo, trans, n, k, alpha, A, lda, beta, C, ldc, workspace, stream, check)
+
+
+def _trmm(name, layout, side, uplo, trans_a, diag, m, n, alpha, A, lda, B, ldb, workspace, stream, check):
+    ws, ws_bytes = _ws(workspace)
+    st = getattr(lib(), name)(layout, side, uplo, trans_a, diag, m, n, alpha, _addr(A), lda, _addr(B), ldb, ws, ws_bytes,
+                              _stream(stream))
+    if check and st != MG_OK:
+        raise MgError(st, name)
+    return st
+
+
+def mg_strmm(layout, side, uplo, trans_a, diag, m, n, alpha, A, lda, B, ldb, workspace=None, stream=None, check=True) -> int:
+    return _trmm("mg_strmm", layout, side, uplo, trans_a, diag, m, n, alpha, A, lda, B, ldb, workspace, stream, check)
+
+
+def mg_htrmm(layout, side, uplo, trans_a, diag, m, n, alpha, A, lda, B, ldb, workspace=None, stream=None, check=True) -> int:
+    return _trmm("mg_htrmm", layout, side, uplo, trans_a, diag, m, n, alpha, A, lda, B, ldb, workspace, stream, check)
+
+
+def mg_symm_workspace_bytes(dtype, layout, side, m, n) -> int:
+    return lib().mg_symm_workspace_bytes(dtype, layout, side, m, n)
+
+
+def mg_syrk_workspace_bytes(dtype, layout, trans, n, k) -> int:
+    return lib().mg_syrk_workspace_bytes(dtype, layout, trans, n, k)
+
+
+def mg_trmm_workspace_bytes(dtype, layout, side, trans_a, m, n) -> int:
+    return lib().mg_trmm_workspace_bytes(dtype, layout, side, trans_a, m, n)
 
 
 def mg_gemv_workspace_bytes(dtype, layout, trans_a, m, n, lda) -> int:

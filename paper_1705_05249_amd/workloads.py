@@ -471,6 +471,82 @@ def gemv_case(dtype, layout, trans, m, n, incx=1, incy=1, alpha=1.0, beta=0.0, c
                     incy, exact=integer)
 
 
+# ----------------------------------------------------------------------------- level-3 derivative cases
+
+UPPER, LOWER = 121, 122
+NON_UNIT, UNIT = 131, 132
+LEFT, RIGHT = 141, 142
+
+
+@dataclass
+class Level3Case:
+    """One SYMM ('symm'), SYRK ('syrk') or TRMM ('trmm') call in BLAS storage.  Whatever the routine must not
+    read holds NaN: the unreferenced triangle of a symmetric or triangular A, the diagonal of a unit-triangular
+    A, and (SYRK) the triangle of C that is not updated.  Padding holds NaN (inputs) or a sentinel (output)."""
+    name: str
+    routine: str
+    dtype: str
+    layout: int
+    side: int
+    uplo: int
+    trans: int
+    diag: int
+    m: int
+    n: int
+    k: int
+    alpha: float
+    beta: float
+    A: np.ndarray
+    lda: int
+    B: Optional[np.ndarray]
+    ldb: int
+    C: Optional[np.ndarray]
+    ldc: int
+    exact: bool = False
+
+
+def _blank_triangle(mat, uplo, unit=False):
+    out = mat.copy()
+    i, j = np.indices(mat.shape)
+    out[(i > j) if uplo == UPPER else (i < j)] = np.nan
+    if unit:
+        out[i == j] = np.nan
+    return out
+
+
+def level3_case(routine, dtype, layout, m, n, k=0, side=LEFT, uplo=UPPER, trans=NO_TRANS, diag=NON_UNIT, alpha=1.0,
+                beta=0.0, pad=(0, 0, 0), case=0, integer=False) -> Level3Case:
+    g = rng_for(7, case)
+    np_t = _np_dtype(dtype)
+    lim = 1 if dtype == "f16" or max(m, n, k) > 512 else 2          # integer results stay exactly representable
+    gen = (lambda shape: small_ints(g, shape, lim, dtype=np_t)) if integer else (lambda shape: uniform(g, shape, dtype=np_t))
+
+    def store(mat, extra, fill):
+        ld = tight_ld(layout, NO_TRANS, *mat.shape) + extra
+        return pack(mat, layout, NO_TRANS, ld, fill=fill), ld
+
+    B = C = None
+    ldb = ldc = 1
+    if routine == "symm":
+        ka = m if side == LEFT else n
+        A, lda = store(_blank_triangle(gen((ka, ka)), uplo), pad[0], np.nan)
+        B, ldb = store(gen((m, n)), pad[1], np.nan)
+        C, ldc = store(gen((m, n)), pad[2], GAP_FILL)
+    elif routine == "syrk":
+        A, lda = store(gen((n, k) if trans == NO_TRANS else (k, n)), pad[0], np.nan)
+        C, ldc = store(_blank_triangle(gen((n, n)), uplo), pad[2], GAP_FILL)
+        m = n
+    elif routine == "trmm":
+        ka = m if side == LEFT else n
+        A, lda = store(_blank_triangle(gen((ka, ka)), uplo, unit=diag == UNIT), pad[0], np.nan)
+        B, ldb = store(gen((m, n)), pad[1], GAP_FILL)
+    else:
+        raise ValueError(routine)
+    name = f"{routine}_{dtype}_{m}x{n}" + (f"x{k}" if routine == "syrk" else "")
+    return Level3Case(name, routine, dtype, layout, side, uplo, trans, diag, m, n, k, alpha, beta, A, lda, B, ldb, C, ldc,
+                      exact=integer)
+
+
 # ----------------------------------------------------------------------------- sampling plan
 
 def sample_entries(m: int, n: int, seed: int, rows: int = 16, cols: int = 16, tile: int = 128,

@@ -17,3 +17,10 @@ def oracle():
     from oracle import gemm_oracle
     gemm_oracle.lib()
     return gemm_oracle
+
+
+@pytest.fixture(scope="session")
+def level3_oracle():
+    from oracle import gemm_oracle, level3_oracle
+    gemm_oracle.lib()
+    return level3_oracle

@@ -196,3 +196,76 @@ def check_gemv(case, oracle, workspace="auto"):
     err = rel_error(got, y_ref, d_ref)
     assert err <= TOL[case.dtype], f"{case.name}: relative error {err:.3e}"
     return err
+
+
+def level3_workspace(case):
+    import torch
+    from paper_1705_05249_amd import gemm as G
+    code = G.MG_F32 if case.dtype == "f32" else G.MG_F16
+    if case.routine == "symm":
+        need = G.mg_symm_workspace_bytes(code, case.layout, case.side, case.m, case.n)
+    elif case.routine == "syrk":
+        need = G.mg_syrk_workspace_bytes(code, case.layout, case.trans, case.n, case.k)
+    else:
+        need = G.mg_trmm_workspace_bytes(code, case.layout, case.side, case.trans, case.m, case.n)
+    return torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+
+
+def run_level3(case, workspace="auto", check=True):
+    """Runs one Level3Case through the C ABI; returns (status, flat output buffer after the call)."""
+    import torch
+    from paper_1705_05249_amd import gemm as G
+    half = case.dtype == "f16"
+    ws = level3_workspace(case) if isinstance(workspace, str) else workspace
+    A = to_gpu(case.A if case.A.size else np.zeros(1, dtype=case.A.dtype))
+    if case.routine == "symm":
+        B, out = to_gpu(case.B), to_gpu(case.C)
+        st = (G.mg_hsymm if half else G.mg_ssymm)(case.layout, case.side, case.uplo, case.m, case.n, case.alpha, A, case.lda,
+                                                  B, case.ldb, case.beta, out, case.ldc, ws, None, check=check)
+    elif case.routine == "syrk":
+        out = to_gpu(case.C)
+        st = (G.mg_hsyrk if half else G.mg_ssyrk)(case.layout, case.uplo, case.trans, case.n, case.k, case.alpha, A, case.lda,
+                                                  case.beta, out, case.ldc, ws, None, check=check)
+    else:
+        out = to_gpu(case.B)
+        st = (G.mg_htrmm if half else G.mg_strmm)(case.layout, case.side, case.uplo, case.trans, case.diag, case.m, case.n,
+                                                  case.alpha, A, case.lda, out, case.ldb, ws, None, check=check)
+    torch.cuda.synchronize()
+    return st, out.cpu().numpy()
+
+
+def check_level3(case, level3_oracle, workspace="auto"):
+    """Element-by-element comparison with the oracle; bytes outside the result (padding, SYRK's other
+    triangle) must be untouched.  Returns the error."""
+    L3 = level3_oracle
+    if case.routine == "symm":
+        ref, den = L3.symm(case.dtype, case.layout, case.side, case.uplo, case.m, case.n, case.alpha, case.A, case.lda,
+                           case.B, case.ldb, case.beta, case.C, case.ldc)
+        before, ld = case.C, case.ldc
+    elif case.routine == "syrk":
+        ref, den = L3.syrk(case.dtype, case.layout, case.uplo, case.trans, case.n, case.k, case.alpha, case.A, case.lda,
+                           case.beta, case.C, case.ldc)
+        before, ld = case.C, case.ldc
+    else:
+        ref, den = L3.trmm(case.dtype, case.layout, case.side, case.uplo, case.trans, case.diag, case.m, case.n, case.alpha,
+                           case.A, case.lda, case.B, case.ldb)
+        before, ld = case.B, case.ldb
+    st, out = run_level3(case, workspace=workspace)
+    assert st == 0
+    pad = W.padding_mask(case.layout, case.m, case.n, ld, before.size)
+    assert np.array_equal(bits(out)[pad], bits(before)[pad]), f"{case.name}: bytes outside the matrix were written"
+    got = W.unpack(out, case.layout, case.m, case.n, ld)
+    live = np.ones((case.m, case.n), dtype=bool)
+    if case.routine == "syrk":
+        i, j = np.indices((case.n, case.n))
+        live = (i <= j) if case.uplo == W.UPPER else (i >= j)
+        old = W.unpack(before, case.layout, case.n, case.n, ld)
+        assert np.array_equal(bits(np.ascontiguousarray(got[~live])), bits(np.ascontiguousarray(old[~live]))), \
+            f"{case.name}: the other triangle of C changed"
+    got, ref, den = got[live], ref[live], den[live]
+    if case.exact:
+        assert np.array_equal(got.astype(np.float64), ref), f"{case.name}: not bit-exact on integer inputs"
+        return 0.0
+    err = rel_error(got, ref, den)
+    assert err <= TOL[case.dtype], f"{case.name}: relative error {err:.3e} > {TOL[case.dtype]:.1e}"
+    return err

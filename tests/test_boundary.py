@@ -192,9 +192,49 @@ def test_gemv_workspace_query():
     assert G.mg_gemv_workspace_bytes(9, C, N, 4096, 1 << 15, 4096) == 0
 
 
+def test_level3_argument_errors():
+    """SYMM / SYRK / TRMM: every rejected call returns before anything touches a device"""
+    L = G.lib()
+    UP, LO, LEFT, RIGHT, NU, UN = G.MG_UPPER, G.MG_LOWER, G.MG_LEFT, G.MG_RIGHT, G.MG_NON_UNIT, G.MG_UNIT
+    for fn in (L.mg_ssymm, L.mg_hsymm):
+        def symm(layout=C, side=LEFT, uplo=UP, m=4, n=3, A=FAKE, lda=4, B=FAKE, ldb=4, Cp=FAKE, ldc=4, alpha=1.0, ws=None):
+            return fn(layout, side, uplo, m, n, alpha, A, lda, B, ldb, 0.0, Cp, ldc, ws, 0, None)
+        assert symm(layout=5) == -1 and symm(side=7) == -17 and symm(uplo=0) == -18
+        assert symm(m=-1) == -4 and symm(lda=3) == -5 and symm(side=RIGHT, lda=2) == -5 and symm(side=RIGHT, lda=3) == -10
+        assert symm(ldb=3) == -6 and symm(ldc=3) == -7 and symm(layout=R, ldb=3, ldc=3) == -10
+        assert symm(Cp=None) == -8 and symm(A=None) == -8 and symm(B=None) == -8
+        assert symm(m=0, A=None, B=None, Cp=None, lda=1, ldb=1, ldc=1) == 0
+        assert symm() == -10 and symm(ws=FAKE) == -10        # no workspace / misaligned and too small
+    for fn in (L.mg_ssyrk, L.mg_hsyrk):
+        def syrk(layout=C, uplo=LO, trans=N, n=4, k=3, A=FAKE, lda=4, Cp=FAKE, ldc=4, ws=None):
+            return fn(layout, uplo, trans, n, k, 1.0, A, lda, 0.0, Cp, ldc, ws, 0, None)
+        assert syrk(layout=5) == -1 and syrk(uplo=9) == -18 and syrk(trans=0) == -2 and syrk(n=-1) == -4 and syrk(k=-1) == -4
+        assert syrk(lda=3) == -5 and syrk(trans=T, lda=3) == -10 and syrk(trans=T, lda=2) == -5
+        assert syrk(layout=R, lda=3) == -10 and syrk(layout=R, lda=2) == -5 and syrk(ldc=3) == -7
+        assert syrk(Cp=None) == -8 and syrk(A=None) == -8 and syrk(n=0, A=None, Cp=None, lda=1, ldc=1) == 0
+    for fn in (L.mg_strmm, L.mg_htrmm):
+        def trmm(layout=C, side=LEFT, uplo=UP, trans=N, diag=NU, m=4, n=3, A=FAKE, lda=4, B=FAKE, ldb=4, ws=None):
+            return fn(layout, side, uplo, trans, diag, m, n, 1.0, A, lda, B, ldb, ws, 0, None)
+        assert trmm(layout=5) == -1 and trmm(side=0) == -17 and trmm(uplo=0) == -18 and trmm(trans=0) == -2 and trmm(diag=0) == -19
+        assert trmm(m=-1) == -4 and trmm(lda=3) == -5 and trmm(ldb=3) == -6 and trmm(diag=UN) == -10
+        assert trmm(B=None) == -8 and trmm(A=None) == -8 and trmm(n=0, A=None, B=None) == 0
+
+
+def test_level3_workspace_queries():
+    F32, F16 = G.MG_F32, G.MG_F16
+    assert G.mg_symm_workspace_bytes(F32, C, G.MG_LEFT, 100, 7) == 40192          # 100 * 100 * 4 = 40000 rounded up to 256
+    assert G.mg_symm_workspace_bytes(F16, R, G.MG_RIGHT, 100, 7) == 256            # 7 * 7 * 2
+    assert G.mg_syrk_workspace_bytes(F16, C, N, 64, 5) == 64 * 64 * 2
+    assert G.mg_trmm_workspace_bytes(F32, C, G.MG_LEFT, T, 64, 32) == 64 * 64 * 4 + 64 * 32 * 4
+    assert G.mg_symm_workspace_bytes(F32, C, 0, 100, 7) == 0 and G.mg_symm_workspace_bytes(9, C, G.MG_LEFT, 100, 7) == 0
+    assert G.mg_syrk_workspace_bytes(F32, C, N, 0, 5) == 0 and G.mg_trmm_workspace_bytes(F32, 3, G.MG_LEFT, N, 4, 4) == 0
+    # a short, wide product adds room for the split sum of the GEMM behind it
+    assert G.mg_syrk_workspace_bytes(F32, C, N, 64, 1 << 16) > 64 * 64 * 4
+
+
 def test_status_strings_and_version():
     seen = set()
-    for code in range(0, -17, -1):
+    for code in range(0, -20, -1):
         s = G.status_string(code)
         assert s and s != "unknown status" and s not in seen
         seen.add(s)

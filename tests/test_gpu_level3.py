@@ -1,0 +1,104 @@
+"""GPU parity of the GEMM-derived level-3 routines (SYMM, SYRK, TRMM; paper Section 3.1, routine table)
+against the CPU oracle, element by element, through the C ABI."""
+import itertools
+
+import numpy as np
+import pytest
+
+import helpers as H
+from paper_1705_05249_amd import gemm as G
+from paper_1705_05249_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+R, C, N, T = W.ROW_MAJOR, W.COL_MAJOR, W.NO_TRANS, W.TRANS
+UP, LO, LEFT, RIGHT, UNIT, NONUNIT = W.UPPER, W.LOWER, W.LEFT, W.RIGHT, W.UNIT, W.NON_UNIT
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("layout,side,uplo", list(itertools.product([C, R], [LEFT, RIGHT], [UP, LO])))
+@pytest.mark.parametrize("shape", [(1, 1), (33, 70), (200, 131), (256, 256)])
+def test_symm_every_option(level3_oracle, dtype, layout, side, uplo, shape):
+    m, n = shape
+    case = W.level3_case("symm", dtype, layout, m, n, side=side, uplo=uplo, alpha=1.25, beta=-0.5, pad=(1, 2, 3),
+                         case=m + n)
+    H.check_level3(case, level3_oracle)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("layout,uplo,trans", list(itertools.product([C, R], [UP, LO], [N, T])))
+@pytest.mark.parametrize("shape", [(1, 1), (70, 33), (131, 200), (256, 64)])
+def test_syrk_every_option(level3_oracle, dtype, layout, uplo, trans, shape):
+    n, k = shape
+    case = W.level3_case("syrk", dtype, layout, n, n, k=k, uplo=uplo, trans=trans, alpha=-0.75, beta=1.5, pad=(2, 0, 1),
+                         case=n + k)
+    H.check_level3(case, level3_oracle)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("layout,side,uplo,trans,diag",
+                         list(itertools.product([C, R], [LEFT, RIGHT], [UP, LO], [N, T], [NONUNIT, UNIT])))
+@pytest.mark.parametrize("shape", [(1, 1), (45, 83), (256, 192)])
+def test_trmm_every_option(level3_oracle, dtype, layout, side, uplo, trans, diag, shape):
+    m, n = shape
+    case = W.level3_case("trmm", dtype, layout, m, n, side=side, uplo=uplo, trans=trans, diag=diag, alpha=0.5,
+                         pad=(3, 1, 0), case=m + n)
+    H.check_level3(case, level3_oracle)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("routine", ["symm", "syrk", "trmm"])
+def test_integer_inputs_are_exact(level3_oracle, dtype, routine):
+    for layout, uplo, side in ((C, LO, LEFT), (R, UP, RIGHT)):
+        case = W.level3_case(routine, dtype, layout, 130, 130 if routine == "syrk" else 97, k=77, side=side, uplo=uplo,
+                             trans=T, alpha=2.0, beta=-1.0, pad=(1, 1, 1), integer=True, case=5)
+        H.check_level3(case, level3_oracle)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_scalar_conventions(level3_oracle, dtype):
+    """alpha == 0: A (and B) may hold NaN everywhere; beta == 0: C is overwritten even where it held NaN;
+    k == 0: the rank-k update scales the triangle"""
+    case = W.level3_case("symm", dtype, C, 40, 50, alpha=0.0, beta=0.5, case=1)
+    case.A[:] = np.nan
+    case.B[:] = np.nan
+    H.check_level3(case, level3_oracle)
+    case = W.level3_case("symm", dtype, R, 40, 50, side=RIGHT, uplo=LO, alpha=1.0, beta=0.0, case=2)
+    case.C[~W.padding_mask(R, 40, 50, case.ldc, case.C.size)] = np.nan
+    H.check_level3(case, level3_oracle)
+    case = W.level3_case("syrk", dtype, C, 60, 60, k=0, uplo=LO, alpha=1.0, beta=2.0, case=3)
+    H.check_level3(case, level3_oracle)
+    case = W.level3_case("syrk", dtype, C, 60, 60, k=20, uplo=UP, alpha=0.0, beta=2.0, case=4)
+    case.A[:] = np.nan
+    H.check_level3(case, level3_oracle)
+    case = W.level3_case("trmm", dtype, C, 30, 20, alpha=0.0, case=5)
+    case.A[:] = np.nan
+    H.check_level3(case, level3_oracle)
+
+
+@pytest.mark.parametrize("routine,dtype,shape", [("symm", "f16", (1024, 768)), ("syrk", "f16", (1024, 512)),
+                                                 ("trmm", "f16", (768, 1024)), ("symm", "f32", (1000, 333)),
+                                                 ("syrk", "f32", (777, 1200)), ("trmm", "f32", (515, 640))])
+def test_sizes_that_span_many_tiles(level3_oracle, routine, dtype, shape):
+    a, b = shape
+    for layout, side, uplo, trans in ((C, LEFT, LO, N), (R, RIGHT, UP, T)):
+        if routine == "syrk":
+            case = W.level3_case("syrk", dtype, layout, a, a, k=b, uplo=uplo, trans=trans, alpha=1.0, beta=1.0, case=a)
+        else:
+            case = W.level3_case(routine, dtype, layout, a, b, side=side, uplo=uplo, trans=trans, alpha=1.0, beta=1.0, case=a)
+        H.check_level3(case, level3_oracle)
+
+
+def test_workspace_is_required():
+    import torch
+    case = W.level3_case("symm", "f32", C, 64, 64, alpha=1.0, beta=0.0)
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    st, out = H.run_level3(case, workspace=small, check=False)
+    assert st == -10 and np.array_equal(H.bits(out), H.bits(case.C))
+    case = W.level3_case("trmm", "f32", C, 64, 64, alpha=1.0)
+    only_a = torch.empty(64 * 64 * 4, dtype=torch.uint8, device="cuda")
+    st, out = H.run_level3(case, workspace=only_a, check=False)
+    assert st == -10 and np.array_equal(H.bits(out), H.bits(case.B))
+    case = W.level3_case("syrk", "f16", C, 64, 64, k=8, alpha=1.0)
+    st, out = H.run_level3(case, workspace=None, check=False)
+    assert st == -10 and np.array_equal(H.bits(out), H.bits(case.C))
