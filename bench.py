@@ -109,7 +109,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
-    ap.add_argument("--only", default=None, help="hgemm | sgemm | batched | conv | gemv | copy: run a single workload (profiling runs)")
+    ap.add_argument("--only", default=None, help="hgemm | sgemm | batched | conv | gemv | level3 | copy: run a single workload (profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -256,6 +256,35 @@ def main():
                           "ms": round(dev * 1e3, 5),
                           "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                        "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None}})
+
+    # ---- next row: the GEMM-derived level-3 routines at the size of the headline product (FP16 storage);
+    # flops are the useful ones of each routine (SYRK and TRMM compute a full product: twice that)
+    if args.only in (None, "level3"):
+        size = 4096
+        l3 = {"symm": W.level3_case("symm", "f16", W.COL_MAJOR, size, size, side=W.LEFT, uplo=W.LOWER, case=1),
+              "syrk": W.level3_case("syrk", "f16", W.COL_MAJOR, size, size, k=size, uplo=W.LOWER, case=2),
+              "trmm": W.level3_case("trmm", "f16", W.COL_MAJOR, size, size, side=W.LEFT, uplo=W.LOWER, case=3)}
+        useful = {"symm": 2.0 * size ** 3, "syrk": 1.0 * size ** 3, "trmm": 1.0 * size ** 3}
+        for routine, lc in l3.items():
+            A = H.to_gpu(lc.A)
+            ws = H.level3_workspace(lc)
+            if routine == "symm":
+                B, Cd = H.to_gpu(lc.B), H.to_gpu(lc.C)
+                call = lambda: G.mg_hsymm(lc.layout, lc.side, lc.uplo, size, size, 1.0, A, lc.lda, B, lc.ldb, 0.0, Cd, lc.ldc, ws)
+            elif routine == "syrk":
+                Cd = H.to_gpu(lc.C)
+                call = lambda: G.mg_hsyrk(lc.layout, lc.uplo, lc.trans, size, size, 1.0, A, lc.lda, 0.0, Cd, lc.ldc, ws)
+            else:
+                # in place: the operand shrinks or grows from call to call; the time does not depend on the values
+                B = H.to_gpu(lc.B)
+                call = lambda: G.mg_htrmm(lc.layout, lc.side, lc.uplo, lc.trans, lc.diag, size, size, 1.0, A, lc.lda, B, lc.ldb, ws)
+            dev, _ = timed(call, steps, warmup)
+            tf = useful[routine] / dev / 1e12
+            extra.append({"workload": f"h{routine}_f16_{size}_colmajor_lower" + ("_left" if routine != "syrk" else f"_k{size}"),
+                          "gflops": round(tf * 1e3, 1), "ms": round(dev * 1e3, 5),
+                          "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_TFLOPS["f16"], "unit": "TFLOP/s",
+                                       "frac": round(tf / PEAK_TFLOPS["f16"], 4), "traffic": None},
+                          "note": "useful flops of the routine; includes the support kernels"})
 
     if head is None:
         print(json.dumps({"workloads": extra}))

@@ -361,7 +361,7 @@ mg_status check_symm(int layout, int side, int uplo, int64_t m, int64_t n, int64
     if (lda < (ka > 1 ? ka : 1)) return MG_ERR_LDA;
     if (ldb < (lead > 1 ? lead : 1)) return MG_ERR_LDB;
     if (ldc < (lead > 1 ? lead : 1)) return MG_ERR_LDC;
-    if (ka > 32 * 65535) return MG_ERR_DIM;
+    if (ka > 64 * 65535) return MG_ERR_DIM;
     return MG_OK;
 }
 

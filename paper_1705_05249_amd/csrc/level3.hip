@@ -13,83 +13,160 @@ namespace mg {
 namespace {
 
 constexpr int kMaxGridY = 65535;
+constexpr int kColumnsPerLaunchRow = 1024;   // grid.y of the column-wise kernels: each thread then walks several columns
 
-// dst (n x n, leading dimension n) <- the whole symmetric matrix of which src stores the lower
-// (i >= j) or the upper triangle; the other triangle of src is never read.  One work-group takes the
-// 32 x 32 tile (ti, tj), ti >= tj, of the lower half through LDS and writes it twice: in place and
-// mirrored, both with consecutive lanes on consecutive addresses.
-template <typename U>
+// V elements (16 bytes) moved as one access
+template <typename U, int V> struct alignas(sizeof(U) * V) Pack {
+    U v[V];
+};
+
+// dst (n x n, leading dimension n) <- the whole symmetric matrix S of which src stores the lower
+// (i >= j) or the upper triangle; what src holds in its other triangle is never used.  One work-group
+// takes the tile (ti, tj), ti >= tj, of the lower half through LDS and writes it twice: in place and
+// mirrored, both as runs of E contiguous elements per lane, LPC lanes side by side.  E x element size is
+// 16 bytes when n, ld and the pointers allow it (LPC = 16), else E = 1 (LPC = 64); the tile edge is
+// LPC * E.  LDS is written and read element by element (an odd pitch in words keeps the transposed
+// reads spread over the banks).
+template <typename U, int E, int LPC>
 __global__ __launch_bounds__(256) void expand_symmetric_kernel(int n, const U *__restrict__ src, int64_t ld, bool lower,
                                                                U *__restrict__ dst)
 {
-    __shared__ U tile[32][33];                       // tile[a][b] = S(ti*32 + a, tj*32 + b) where that lies in the lower half
+    constexpr int TS = LPC * E;
+    constexpr int PITCH = TS + (sizeof(U) == 4 ? 1 : 2);
+    constexpr int STEP = 256 / LPC;
+    struct alignas(sizeof(U) * E) Run { U v[E]; };
+    __shared__ U tile[TS][PITCH];                    // tile[b][a] = S(ti*TS + a, tj*TS + b), used where a >= b globally
     const int ti = blockIdx.x, tj = blockIdx.y;
     if (ti < tj) return;
-    const int tx = threadIdx.x % 32, ty0 = threadIdx.x / 32;
-    for (int ty = ty0; ty < 32; ty += 8) {
+    const int tx = threadIdx.x % LPC, ty0 = threadIdx.x / LPC;
+    const int r0 = ti * TS, c0 = tj * TS;
+#pragma unroll 4
+    for (int ty = ty0; ty < TS; ty += STEP) {
         if (lower) {
-            const int r = ti * 32 + tx, c = tj * 32 + ty;
-            if (r < n && c < n && r >= c) tile[tx][ty] = src[r + c * ld];
+            // rows a .. a+E-1 of column b: contiguous in src
+            const int a = E * tx, b = ty;
+            if (r0 + a < n && c0 + b < n && r0 + a + E - 1 >= c0 + b) {
+                const Run w = *reinterpret_cast<const Run *>(src + (r0 + a) + (c0 + b) * ld);
+#pragma unroll
+                for (int e = 0; e < E; ++e) tile[b][a + e] = w.v[e];
+            }
         } else {
-            // S(r, c) with r >= c is stored as the upper entry (c, r): lanes run along c
-            const int r = ti * 32 + ty, c = tj * 32 + tx;
-            if (r < n && c < n && r >= c) tile[ty][tx] = src[c + r * ld];
+            // S(r, c) with r >= c is stored as the upper entry (c, r): columns b .. b+E-1 of row a are contiguous
+            const int a = ty, b = E * tx;
+            if (r0 + a < n && c0 + b < n && r0 + a >= c0 + b) {
+                const Run w = *reinterpret_cast<const Run *>(src + (c0 + b) + (r0 + a) * ld);
+#pragma unroll
+                for (int e = 0; e < E; ++e) tile[b + e][a] = w.v[e];
+            }
         }
     }
     __syncthreads();
     const int64_t nn = n;
-    for (int ty = ty0; ty < 32; ty += 8) {
-        const int r = ti * 32 + tx, c = tj * 32 + ty;
-        // above the diagonal (diagonal tile only) the value is the mirrored entry of the same tile
-        if (r < n && c < n) dst[r + c * nn] = r >= c ? tile[tx][ty] : tile[ty][tx];
-        if (ti != tj) {
-            const int mr = tj * 32 + tx, mc = ti * 32 + ty;      // mirrored tile: S(mr, mc) = S(mc, mr)
-            if (mr < n && mc < n) dst[mr + mc * nn] = tile[ty][tx];
+#pragma unroll 4
+    for (int ty = ty0; ty < TS; ty += STEP) {
+        const int a = E * tx, b = ty;
+        if (r0 + a < n && c0 + b < n) {
+            Run w;
+#pragma unroll
+            for (int e = 0; e < E; ++e)     // above the diagonal (diagonal tile only): the mirrored entry of the same tile
+                w.v[e] = r0 + a + e >= c0 + b ? tile[b][a + e] : tile[a + e][b];
+            *reinterpret_cast<Run *>(dst + (r0 + a) + (c0 + b) * nn) = w;
+        }
+        if (ti != tj && c0 + a < n && r0 + b < n) {
+            // mirrored tile (tj, ti): S(c0 + a + e, r0 + b) = S(r0 + b, c0 + a + e) = tile[a + e][b]
+            Run w;
+#pragma unroll
+            for (int e = 0; e < E; ++e) w.v[e] = tile[a + e][b];
+            *reinterpret_cast<Run *>(dst + (c0 + a) + (r0 + b) * nn) = w;
         }
     }
 }
 
+// The column-wise kernels below come in two flavours: V == 1 moves single elements; V == 16 bytes /
+// element size moves aligned 16-byte runs of V rows (the host checks that every run is aligned and
+// that the row count is a multiple of V).  A thread owns rows [i, i + V) and walks columns
+// j = blockIdx.y, blockIdx.y + gridDim.y, ...
+
 // dst (n x n, leading dimension n) <- the triangular matrix: zero outside the stored triangle, one on
 // a unit diagonal; neither the other triangle of src nor (unit) its diagonal is read
-template <typename T>
+template <typename T, int V>
 __global__ __launch_bounds__(256) void expand_triangular_kernel(int n, const T *__restrict__ src, int64_t ld, bool lower,
                                                                 bool unit, T *__restrict__ dst)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    using P = Pack<T, V>;
+    const int i = (blockIdx.x * 256 + threadIdx.x) * V;
     if (i >= n) return;
+#pragma unroll 4
     for (int j = blockIdx.y; j < n; j += gridDim.y) {
-        const bool in = lower ? i >= j : i <= j;
-        T v = static_cast<T>(0.f);
-        if (in) v = (unit && i == j) ? static_cast<T>(1.f) : src[i + j * ld];
-        dst[i + static_cast<int64_t>(j) * n] = v;
+        P out;
+        const bool all_in = lower ? i > j : i + V - 1 < j;            // strictly inside: no diagonal element either
+        const bool all_out = lower ? i + V - 1 < j : i > j;
+        if (all_in) {
+            out = *reinterpret_cast<const P *>(src + i + j * ld);
+        } else {
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const int r = i + e;
+                const bool in = lower ? r >= j : r <= j;
+                T v = static_cast<T>(0.f);
+                if (!all_out && in) v = (unit && r == j) ? static_cast<T>(1.f) : src[r + j * ld];
+                out.v[e] = v;
+            }
+        }
+        *reinterpret_cast<P *>(dst + i + static_cast<int64_t>(j) * n) = out;
     }
 }
 
 // dst (leading dimension ldd) <- src (leading dimension lds), `minor` contiguous elements in each of
 // `major` runs
-template <typename U>
+template <typename U, int V>
 __global__ __launch_bounds__(256) void copy_matrix_kernel(int minor, int major, const U *__restrict__ src, int64_t lds,
                                                           U *__restrict__ dst, int64_t ldd)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    using P = Pack<U, V>;
+    const int i = (blockIdx.x * 256 + threadIdx.x) * V;
     if (i >= minor) return;
-    for (int j = blockIdx.y; j < major; j += gridDim.y) dst[i + j * ldd] = src[i + j * lds];
+#pragma unroll 4
+    for (int j = blockIdx.y; j < major; j += gridDim.y)
+        *reinterpret_cast<P *>(dst + i + j * ldd) = *reinterpret_cast<const P *>(src + i + j * lds);
 }
 
 // the strictly lower (i > j) or strictly upper entries of an n x n matrix, src -> dst
-template <typename U>
+template <typename U, int V>
 __global__ __launch_bounds__(256) void copy_triangle_kernel(int n, const U *__restrict__ src, int64_t lds,
                                                             U *__restrict__ dst, int64_t ldd, bool lower)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    using P = Pack<U, V>;
+    const int i = (blockIdx.x * 256 + threadIdx.x) * V;
     if (i >= n) return;
-    for (int j = blockIdx.y; j < n; j += gridDim.y)
-        if (lower ? i > j : i < j) dst[i + j * ldd] = src[i + j * lds];
+#pragma unroll 4
+    for (int j = blockIdx.y; j < n; j += gridDim.y) {
+        const bool all_in = lower ? i > j : i + V - 1 < j;
+        const bool all_out = lower ? i + V - 1 <= j : i >= j;
+        if (all_in) {
+            *reinterpret_cast<P *>(dst + i + j * ldd) = *reinterpret_cast<const P *>(src + i + j * lds);
+        } else if (!all_out) {
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const int r = i + e;
+                if (lower ? r > j : r < j) dst[r + j * ldd] = src[r + j * lds];
+            }
+        }
+    }
 }
 
-dim3 column_grid(int64_t minor, int64_t major)
+dim3 column_grid(int64_t minor, int64_t major, int v)
 {
-    return dim3(static_cast<unsigned>(ceil_div(minor, 256)), static_cast<unsigned>(major < kMaxGridY ? major : kMaxGridY));
+    const int64_t rows = major < kColumnsPerLaunchRow ? major : kColumnsPerLaunchRow;
+    return dim3(static_cast<unsigned>(ceil_div(minor, 256 * v)), static_cast<unsigned>(rows < 1 ? 1 : rows));
+}
+
+// 16-byte runs are usable when the row count is a multiple of V and every column of both matrices starts
+// on a 16-byte boundary
+bool runs_aligned(int64_t minor, const void *a, int64_t lda, const void *b, int64_t ldb, int elem)
+{
+    const int v = 16 / elem;
+    return minor % v == 0 && lda % v == 0 && ldb % v == 0 && pointer_alignment(a) >= 16 && pointer_alignment(b) >= 16;
 }
 
 }  // namespace
@@ -97,52 +174,91 @@ dim3 column_grid(int64_t minor, int64_t major)
 hipError_t launch_expand_symmetric(int dtype, int64_t n, const void *src, int64_t ld, bool lower, void *dst,
                                    hipStream_t stream)
 {
-    const unsigned tiles = static_cast<unsigned>(ceil_div(n, 32));
+    const int elem = dtype == MG_F32 ? 4 : 2;
+    const bool wide = runs_aligned(n, src, ld, dst, n, elem);
+    const int edge = wide ? 16 * (16 / elem) : 64;
+    const unsigned tiles = static_cast<unsigned>(ceil_div(n, edge));
     if (tiles > kMaxGridY) return hipErrorInvalidValue;
-    if (dtype == MG_F32)
-        hipLaunchKernelGGL(expand_symmetric_kernel<uint32_t>, dim3(tiles, tiles), dim3(256), 0, stream, static_cast<int>(n),
-                           static_cast<const uint32_t *>(src), ld, lower, static_cast<uint32_t *>(dst));
-    else
-        hipLaunchKernelGGL(expand_symmetric_kernel<uint16_t>, dim3(tiles, tiles), dim3(256), 0, stream, static_cast<int>(n),
-                           static_cast<const uint16_t *>(src), ld, lower, static_cast<uint16_t *>(dst));
+    const dim3 grid(tiles, tiles);
+    const int nn = static_cast<int>(n);
+    if (dtype == MG_F32) {
+        const uint32_t *s = static_cast<const uint32_t *>(src);
+        uint32_t *d = static_cast<uint32_t *>(dst);
+        if (wide) hipLaunchKernelGGL((expand_symmetric_kernel<uint32_t, 4, 16>), grid, dim3(256), 0, stream, nn, s, ld, lower, d);
+        else hipLaunchKernelGGL((expand_symmetric_kernel<uint32_t, 1, 64>), grid, dim3(256), 0, stream, nn, s, ld, lower, d);
+    } else {
+        const uint16_t *s = static_cast<const uint16_t *>(src);
+        uint16_t *d = static_cast<uint16_t *>(dst);
+        if (wide) hipLaunchKernelGGL((expand_symmetric_kernel<uint16_t, 8, 16>), grid, dim3(256), 0, stream, nn, s, ld, lower, d);
+        else hipLaunchKernelGGL((expand_symmetric_kernel<uint16_t, 1, 64>), grid, dim3(256), 0, stream, nn, s, ld, lower, d);
+    }
     return hipGetLastError();
 }
+
+// picks the 16-byte or the single-element flavour of a column-wise kernel template
+#define MG_LAUNCH_COLUMNWISE(KERNEL, T32, T16, MINOR, MAJOR, ALIGNED, ...)                                            \
+    do {                                                                                                              \
+        if (dtype == MG_F32) {                                                                                        \
+            if (ALIGNED)                                                                                              \
+                hipLaunchKernelGGL((KERNEL<T32, 4>), column_grid(MINOR, MAJOR, 4), dim3(256), 0, stream, __VA_ARGS__); \
+            else                                                                                                      \
+                hipLaunchKernelGGL((KERNEL<T32, 1>), column_grid(MINOR, MAJOR, 1), dim3(256), 0, stream, __VA_ARGS__); \
+        } else {                                                                                                      \
+            if (ALIGNED)                                                                                              \
+                hipLaunchKernelGGL((KERNEL<T16, 8>), column_grid(MINOR, MAJOR, 8), dim3(256), 0, stream, __VA_ARGS__); \
+            else                                                                                                      \
+                hipLaunchKernelGGL((KERNEL<T16, 1>), column_grid(MINOR, MAJOR, 1), dim3(256), 0, stream, __VA_ARGS__); \
+        }                                                                                                             \
+    } while (0)
 
 hipError_t launch_expand_triangular(int dtype, int64_t n, const void *src, int64_t ld, bool lower, bool unit, void *dst,
                                     hipStream_t stream)
 {
-    if (dtype == MG_F32)
-        hipLaunchKernelGGL(expand_triangular_kernel<float>, column_grid(n, n), dim3(256), 0, stream, static_cast<int>(n),
-                           static_cast<const float *>(src), ld, lower, unit, static_cast<float *>(dst));
-    else
-        hipLaunchKernelGGL(expand_triangular_kernel<_Float16>, column_grid(n, n), dim3(256), 0, stream, static_cast<int>(n),
-                           static_cast<const _Float16 *>(src), ld, lower, unit, static_cast<_Float16 *>(dst));
+    const bool aligned = runs_aligned(n, src, ld, dst, n, dtype == MG_F32 ? 4 : 2);
+    if (dtype == MG_F32) {
+        const float *s = static_cast<const float *>(src);
+        float *d = static_cast<float *>(dst);
+        MG_LAUNCH_COLUMNWISE(expand_triangular_kernel, float, float, n, n, aligned, static_cast<int>(n), s, ld, lower, unit, d);
+    } else {
+        const _Float16 *s = static_cast<const _Float16 *>(src);
+        _Float16 *d = static_cast<_Float16 *>(dst);
+        MG_LAUNCH_COLUMNWISE(expand_triangular_kernel, _Float16, _Float16, n, n, aligned, static_cast<int>(n), s, ld, lower,
+                             unit, d);
+    }
     return hipGetLastError();
 }
 
 hipError_t launch_copy_matrix(int dtype, int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
                               hipStream_t stream)
 {
-    if (dtype == MG_F32)
-        hipLaunchKernelGGL(copy_matrix_kernel<uint32_t>, column_grid(minor, major), dim3(256), 0, stream,
-                           static_cast<int>(minor), static_cast<int>(major), static_cast<const uint32_t *>(src), lds,
-                           static_cast<uint32_t *>(dst), ldd);
-    else
-        hipLaunchKernelGGL(copy_matrix_kernel<uint16_t>, column_grid(minor, major), dim3(256), 0, stream,
-                           static_cast<int>(minor), static_cast<int>(major), static_cast<const uint16_t *>(src), lds,
-                           static_cast<uint16_t *>(dst), ldd);
+    const bool aligned = runs_aligned(minor, src, lds, dst, ldd, dtype == MG_F32 ? 4 : 2);
+    if (dtype == MG_F32) {
+        const uint32_t *s = static_cast<const uint32_t *>(src);
+        uint32_t *d = static_cast<uint32_t *>(dst);
+        MG_LAUNCH_COLUMNWISE(copy_matrix_kernel, uint32_t, uint32_t, minor, major, aligned, static_cast<int>(minor),
+                             static_cast<int>(major), s, lds, d, ldd);
+    } else {
+        const uint16_t *s = static_cast<const uint16_t *>(src);
+        uint16_t *d = static_cast<uint16_t *>(dst);
+        MG_LAUNCH_COLUMNWISE(copy_matrix_kernel, uint16_t, uint16_t, minor, major, aligned, static_cast<int>(minor),
+                             static_cast<int>(major), s, lds, d, ldd);
+    }
     return hipGetLastError();
 }
 
 hipError_t launch_copy_triangle(int dtype, int64_t n, const void *src, int64_t lds, void *dst, int64_t ldd, bool lower,
                                 hipStream_t stream)
 {
-    if (dtype == MG_F32)
-        hipLaunchKernelGGL(copy_triangle_kernel<uint32_t>, column_grid(n, n), dim3(256), 0, stream, static_cast<int>(n),
-                           static_cast<const uint32_t *>(src), lds, static_cast<uint32_t *>(dst), ldd, lower);
-    else
-        hipLaunchKernelGGL(copy_triangle_kernel<uint16_t>, column_grid(n, n), dim3(256), 0, stream, static_cast<int>(n),
-                           static_cast<const uint16_t *>(src), lds, static_cast<uint16_t *>(dst), ldd, lower);
+    const bool aligned = runs_aligned(n, src, lds, dst, ldd, dtype == MG_F32 ? 4 : 2);
+    if (dtype == MG_F32) {
+        const uint32_t *s = static_cast<const uint32_t *>(src);
+        uint32_t *d = static_cast<uint32_t *>(dst);
+        MG_LAUNCH_COLUMNWISE(copy_triangle_kernel, uint32_t, uint32_t, n, n, aligned, static_cast<int>(n), s, lds, d, ldd, lower);
+    } else {
+        const uint16_t *s = static_cast<const uint16_t *>(src);
+        uint16_t *d = static_cast<uint16_t *>(dst);
+        MG_LAUNCH_COLUMNWISE(copy_triangle_kernel, uint16_t, uint16_t, n, n, aligned, static_cast<int>(n), s, lds, d, ldd, lower);
+    }
     return hipGetLastError();
 }
 

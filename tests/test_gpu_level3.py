@@ -78,7 +78,9 @@ def test_scalar_conventions(level3_oracle, dtype):
 
 @pytest.mark.parametrize("routine,dtype,shape", [("symm", "f16", (1024, 768)), ("syrk", "f16", (1024, 512)),
                                                  ("trmm", "f16", (768, 1024)), ("symm", "f32", (1000, 333)),
-                                                 ("syrk", "f32", (777, 1200)), ("trmm", "f32", (515, 640))])
+                                                 ("syrk", "f32", (777, 1200)), ("trmm", "f32", (515, 640)),
+                                                 ("symm", "f16", (1000, 520)), ("syrk", "f16", (1000, 136)),
+                                                 ("trmm", "f16", (520, 1000))])
 def test_sizes_that_span_many_tiles(level3_oracle, routine, dtype, shape):
     a, b = shape
     for layout, side, uplo, trans in ((C, LEFT, LO, N), (R, RIGHT, UP, T)):
