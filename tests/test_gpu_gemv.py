@@ -95,3 +95,12 @@ def test_same_result_as_the_gemm_entry_point_with_one_column(oracle):
     G.mg_sgemm(C, N, N, 777, 1, 333, 1.5, A, case.lda, x, 333, 0.25, y, 777)
     torch.cuda.synchronize()
     assert np.array_equal(H.bits(out), H.bits(y.cpu().numpy()))
+
+
+def test_benchmark_size(oracle):
+    """16384 x 16384 FP32, column-major, both orders: the calls the benchmark times, every output checked
+    (one seeded matrix serves both: it is square)"""
+    import dataclasses
+    case = W.gemv_case("f32", C, N, 16384, 16384, alpha=1.0, beta=0.0, case=41)
+    H.check_gemv(case, oracle)
+    H.check_gemv(dataclasses.replace(case, trans=T), oracle)

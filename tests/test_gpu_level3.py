@@ -104,3 +104,44 @@ def test_workspace_is_required():
     case = W.level3_case("syrk", "f16", C, 64, 64, k=8, alpha=1.0)
     st, out = H.run_level3(case, workspace=None, check=False)
     assert st == -10 and np.array_equal(H.bits(out), H.bits(case.C))
+
+
+def _columns(flat, rows, ld, cols):
+    """the chosen columns of a column-major matrix, tightly packed"""
+    return np.ascontiguousarray(np.stack([flat[c * ld: c * ld + rows] for c in cols]).reshape(-1))
+
+
+def test_benchmark_size_on_sampled_outputs(level3_oracle):
+    """4096, FP16, column-major, lower, left: the calls the benchmark times, checked on sampled outputs.
+    Columns of B (SYMM, TRMM) are independent problems, and so are the rows/columns of a rank-k update that
+    belong to a subset of indices: the oracle computes those sub-problems in full."""
+    n = 4096
+    g = np.random.default_rng(77)
+    cols = np.sort(g.choice(n, size=12, replace=False))
+    case = W.level3_case("symm", "f16", C, n, n, side=LEFT, uplo=LO, alpha=1.0, beta=0.0, case=1)
+    _, out = H.run_level3(case)
+    ref, den = level3_oracle.symm("f16", C, LEFT, LO, n, len(cols), 1.0, case.A, case.lda,
+                                  _columns(case.B, n, case.ldb, cols), n, 0.0, _columns(case.C, n, case.ldc, cols), n)
+    got = np.stack([out[c * case.ldc: c * case.ldc + n] for c in cols], axis=1)
+    assert H.rel_error(got, ref, den) <= H.TOL["f16"]
+
+    case = W.level3_case("trmm", "f16", C, n, n, side=LEFT, uplo=LO, alpha=1.0, case=3)
+    _, out = H.run_level3(case)
+    ref, den = level3_oracle.trmm("f16", C, LEFT, LO, N, NONUNIT, n, len(cols), 1.0, case.A, case.lda,
+                                  _columns(case.B, n, case.ldb, cols), n)
+    got = np.stack([out[c * case.ldb: c * case.ldb + n] for c in cols], axis=1)
+    assert H.rel_error(got, ref, den) <= H.TOL["f16"]
+
+    case = W.level3_case("syrk", "f16", C, n, n, k=n, uplo=LO, alpha=1.0, beta=0.0, case=2)
+    _, out = H.run_level3(case)
+    pick = np.sort(g.choice(n, size=96, replace=False))
+    A = W.unpack(case.A, C, n, n, case.lda)[pick]                       # the chosen rows of A: a 96 x k operand
+    sub = W.pack(A, C, N)
+    blank = np.zeros(len(pick) * len(pick), np.float16)
+    ref, den = level3_oracle.syrk("f16", C, LO, N, len(pick), n, 1.0, sub, len(pick), 0.0, blank, len(pick))
+    got = W.unpack(out, C, n, n, case.ldc)[np.ix_(pick, pick)]
+    i, j = np.indices(got.shape)
+    low = i >= j
+    assert H.rel_error(got[low], ref[low], den[low]) <= H.TOL["f16"]
+    old = W.unpack(case.C, C, n, n, case.ldc)[np.ix_(pick, pick)]
+    assert np.array_equal(H.bits(np.ascontiguousarray(got[~low])), H.bits(np.ascontiguousarray(old[~low])))
