@@ -33,6 +33,8 @@ const std::vector<KernelEntry> &table()
 bool valid_trans(int t) { return t == MG_NO_TRANS || t == MG_TRANS || t == MG_CONJ_TRANS; }
 
 // Checks everything that does not need the pointers, in status-code order.
+constexpr int64_t kShapeHintMinTiles = 384;
+
 mg_status check_shape(int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, int64_t lda, int64_t ldb,
                       int64_t ldc)
 {
@@ -64,9 +66,10 @@ mg_status check_shape(int layout, int ta, int tb, int64_t m, int64_t n, int64_t 
 // swap the operands and the roles of m and n.
 Problem canonical(int dtype, int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, float alpha,
                   const void *A, int64_t lda, const void *B, int64_t ldb, float beta, void *C, int64_t ldc,
-                  void *ws, size_t ws_bytes, void *stream)
+                  void *ws, size_t ws_bytes, void *stream, int shape = MG_SHAPE_GENERAL)
 {
     Problem p{};
+    p.shape = shape;           // already in canonical terms: the caller knows the layout
     p.dtype = dtype;
     p.k = k;
     p.alpha = alpha;
@@ -115,8 +118,15 @@ mg_status choose(const Problem &p, int64_t alignment, size_t workspace_bytes, in
 }
 
 // Selects and launches the configuration for a canonical problem with at least one output.
-mg_status run_canonical(const Problem &p)
+mg_status run_canonical(Problem p)
 {
+    // A shape hint halves the tile work but rules out the direct-to-LDS kernels and split-K, and a grid that
+    // fills the chip only once is as slow as its longest tile: below 384 tiles of 256 x 256 (about 5000^2
+    // outputs) the general path is faster (measured at 4096: 104-118 us general, 151-191 us with the hint on
+    // 128 x 128 tiles).  A forced configuration keeps the hint: the caller chose the kernel.
+    if (p.shape != MG_SHAPE_GENERAL && g_override_kernel[p.dtype] < 0 &&
+        ceil_div(p.m, 256) * ceil_div(p.n, 256) < (kShapeHintMinTiles))
+        p.shape = MG_SHAPE_GENERAL;
     int32_t kernel = -1, split = 1;
     const bool ws_usable = p.workspace != nullptr && pointer_alignment(p.workspace) >= 256;
     const mg_status s = choose(p, problem_alignment(p), ws_usable ? p.workspace_bytes : 0, &kernel, &split);
@@ -127,16 +137,17 @@ mg_status run_canonical(const Problem &p)
     return e.launch(p, split) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
 }
 
+// shape: a ProblemShape hint in terms of the canonical (column-major) problem, see canonical()
 mg_status run_gemm(int dtype, int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, float alpha,
                    const void *A, int64_t lda, const void *B, int64_t ldb, float beta, void *C, int64_t ldc,
-                   void *ws, size_t ws_bytes, void *stream)
+                   void *ws, size_t ws_bytes, void *stream, int shape = MG_SHAPE_GENERAL)
 {
     mg_status s = check_shape(layout, ta, tb, m, n, k, lda, ldb, ldc);
     if (s != MG_OK) return s;
     if (m == 0 || n == 0) return MG_OK;
     const bool reads_ab = alpha != 0.f && k != 0;
     if (C == nullptr || (reads_ab && (A == nullptr || B == nullptr))) return MG_ERR_NULL;
-    Problem p = canonical(dtype, layout, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, ws, ws_bytes, stream);
+    Problem p = canonical(dtype, layout, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, ws, ws_bytes, stream, shape);
     return run_canonical(p);
 }
 
@@ -426,8 +437,10 @@ mg_status run_syrk(int dtype, int layout, int uplo, int trans, int64_t n, int64_
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (launch_copy_triangle(dtype, n, C, ldc, aside, n, other_is_lower, st) != hipSuccess) return MG_ERR_LAUNCH;
     const bool nt = trans == MG_NO_TRANS;
+    // tiles wholly outside the referenced triangle are skipped (the triangle as the column-major view sees it)
     const mg_status g = run_gemm(dtype, layout, nt ? MG_NO_TRANS : MG_TRANS, nt ? MG_TRANS : MG_NO_TRANS, n, n, k, alpha, A, lda,
-                                 A, lda, beta, C, ldc, carve.rest(), carve.left, stream);
+                                 A, lda, beta, C, ldc, carve.rest(), carve.left, stream,
+                                 other_is_lower ? MG_SHAPE_C_UPPER : MG_SHAPE_C_LOWER);
     // put the other triangle back even if the product failed to launch: C is then as it was there
     if (launch_copy_triangle(dtype, n, aside, n, C, ldc, other_is_lower, st) != hipSuccess) return MG_ERR_LAUNCH;
     return g;
@@ -472,11 +485,19 @@ mg_status run_trmm(int dtype, int layout, int side, int uplo, int trans, int dia
     // the product cannot run in place: B is copied (tightly packed, same layout) and then overwritten
     const int64_t minor = layout == MG_COL_MAJOR ? m : n, major = layout == MG_COL_MAJOR ? n : m;
     if (launch_copy_matrix(dtype, minor, major, B, ldb, copy, minor, st) != hipSuccess) return MG_ERR_LAUNCH;
+    // Which canonical operand is triangular, and how: op(A) is lower when uplo and trans say so; a row-major
+    // call runs as the transposed product, which swaps the operands and turns lower into upper.
+    const bool op_lower = (uplo == MG_LOWER) == (trans == MG_NO_TRANS);
+    const bool col = layout == MG_COL_MAJOR;
+    const bool canonical_lower = col ? op_lower : !op_lower;
+    const bool tri_is_a = (side == MG_LEFT) == col;
+    const int shape = tri_is_a ? (canonical_lower ? MG_SHAPE_A_LOWER : MG_SHAPE_A_UPPER)
+                               : (canonical_lower ? MG_SHAPE_B_LOWER : MG_SHAPE_B_UPPER);
     if (side == MG_LEFT)
         return run_gemm(dtype, layout, trans, MG_NO_TRANS, m, n, m, alpha, full, ka, copy, minor, 0.f, B, ldb, carve.rest(),
-                        carve.left, stream);
+                        carve.left, stream, shape);
     return run_gemm(dtype, layout, MG_NO_TRANS, trans, m, n, n, alpha, copy, minor, full, ka, 0.f, B, ldb, carve.rest(),
-                    carve.left, stream);
+                    carve.left, stream, shape);
 }
 
 }  // namespace

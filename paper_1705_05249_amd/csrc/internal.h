@@ -17,6 +17,19 @@ namespace mg {
 //   op(A)(i,l) = A[i*a_sm + l*a_sk]   (a_sm == 1: contiguous along m; a_sk == 1: along k)
 //   op(B)(l,j) = B[l*b_sk + j*b_sn]
 //   C(i,j)     = C[i + j*ldc]
+// Optional knowledge about a canonical problem that lets the macro-tile kernels skip work.  The operands still
+// hold explicit zeros, and a kernel may ignore the hint: results are the same (finite data).  "Lower" for op(A)
+// (m x k, square) means entries with l > i are zero, for op(B) (k x n, square) entries with l < j are zero.
+enum ProblemShape {
+    MG_SHAPE_GENERAL = 0,
+    MG_SHAPE_A_LOWER = 1,
+    MG_SHAPE_A_UPPER = 2,
+    MG_SHAPE_B_LOWER = 3,
+    MG_SHAPE_B_UPPER = 4,
+    MG_SHAPE_C_LOWER = 5,      // only C(i, j) with i >= j is wanted; tiles wholly outside may be left untouched
+    MG_SHAPE_C_UPPER = 6
+};
+
 struct Problem {
     int dtype;                 // mg_dtype
     int64_t m, n, k;
@@ -32,6 +45,7 @@ struct Problem {
     void *workspace;
     size_t workspace_bytes;
     hipStream_t stream;
+    int shape;                 // ProblemShape: where an operand is known to hold zeros / which part of C is wanted
 
     int64_t a_sm() const { return a_trans ? lda : 1; }
     int64_t a_sk() const { return a_trans ? 1 : lda; }

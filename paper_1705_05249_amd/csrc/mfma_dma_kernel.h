@@ -134,10 +134,12 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
     lds_char *const lds3 = (lds_char *)lds;
 
     int tm, tn;
-    tile_coords(blockIdx.x, args.tiles_m, args.tiles_n, args.group_m, tm, tn);
+    if (args.shape == 0) tile_coords(blockIdx.x, args.tiles_m, args.tiles_n, args.group_m, tm, tn);
+    else tile_coords_balanced(blockIdx.x, args.tiles_m, args.tiles_n, args.group_m, args.reversed != 0, tm, tn);
     const int64_t m0 = static_cast<int64_t>(tm) * BM, n0 = static_cast<int64_t>(tn) * BN;
-    const int kb = blockIdx.z * args.k_per_split;
-    const int ke = (kb + args.k_per_split < args.k) ? kb + args.k_per_split : args.k;
+    int kb = blockIdx.z * args.k_per_split;
+    int ke = (kb + args.k_per_split < args.k) ? kb + args.k_per_split : args.k;
+    if (!narrow_to_shape<BM, BN, BK>(args.shape, m0, n0, kb, ke)) return;
     const T *__restrict__ A = static_cast<const T *>(args.A);
     const T *__restrict__ B = static_cast<const T *>(args.B);
 

@@ -27,6 +27,9 @@ hipError_t launch_tile_kernel(Kernel kernel, bool *attr_set, int lds_bytes, int 
     a.tiles_n = static_cast<int>(ceil_div(p.n, bn));
     a.k_per_split = k_per_split;
     a.group_m = 8;
+    a.shape = p.shape;
+    // K ranges that grow with the tile index: start the long ones first
+    a.reversed = p.shape == MG_SHAPE_A_LOWER || p.shape == MG_SHAPE_B_UPPER;
     hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(a.tiles_m) * a.tiles_n, 1, split), dim3(threads), lds_bytes,
                        p.stream, a);
     hipError_t e = hipGetLastError();
@@ -57,6 +60,7 @@ template <typename T, int BM, int BN, int BK, int WM, int WN, bool AK, bool BKC,
         if (p.dtype != DTYPE || p.a_trans != AK || p.b_trans == BKC) return false;
         if (p.alpha == 0.f || p.k == 0) return false;
         if (split < 1 || split > 256 || split > ceil_div(p.k, BK)) return false;
+        if (p.shape != MG_SHAPE_GENERAL && split != 1) return false;      // a narrowed K range is never sliced
         if (p.m >= (int64_t(1) << 31) || p.n >= (int64_t(1) << 31) || p.k >= (int64_t(1) << 31)) return false;
         if (ceil_div(p.m, BM) * ceil_div(p.n, BN) >= (int64_t(1) << 31)) return false;
         if (split > 1 && static_cast<int64_t>(k_per_split(p, split)) * (split - 1) >= p.k) return false;  // empty slice

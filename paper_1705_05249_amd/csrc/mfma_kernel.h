@@ -62,6 +62,8 @@ struct MfmaArgs {
     int tiles_m, tiles_n;
     int k_per_split;       // multiple of the K tile
     int group_m;           // tile rasterisation: tiles are walked in column groups of this many rows
+    int shape;             // ProblemShape: K range per tile narrowed to the non-zero part / tiles outside C's triangle skipped
+    int reversed;          // walk the tiles in reverse order (longest K ranges first)
 };
 
 template <typename T> struct ElemTraits;
@@ -321,6 +323,41 @@ __device__ inline void tile_coords(int wg, int tiles_m, int tiles_n, int group_m
     tn = in_group / size;
 }
 
+// Tile of a work-group when a shape hint makes tiles unequal (K ranges that grow along the rows or columns,
+// skipped tiles): the XCD-contiguous walk above would hand whole row bands, i.e. all long or all short tiles, to
+// one XCD.  Here work-group ids stay interleaved over the XCDs (the hardware's order) and the row inside a group
+// rotates with the column, so every XCD sees every row and column equally often; `reversed` starts at the far end
+// (the longest tiles first).
+__device__ inline void tile_coords_balanced(int wg, int tiles_m, int tiles_n, int group_m, bool reversed, int &tm, int &tn)
+{
+    const int id = reversed ? tiles_m * tiles_n - 1 - wg : wg;
+    const int per_group = group_m * tiles_n;
+    const int group = id / per_group;
+    const int first = group * group_m;
+    const int size = (tiles_m - first) < group_m ? (tiles_m - first) : group_m;
+    const int in_group = id % per_group;
+    tn = in_group / size;
+    tm = first + (in_group % size + tn) % size;
+}
+
+// A shape hint (ProblemShape) applied to one tile.  A triangular operand (its zeros are stored, so this only
+// saves work): the K range [kb, ke) of the tile shrinks to where the operand can be non-zero.  A triangular
+// result: false for tiles wholly outside it, which are skipped.  The host passes a shape only with a single K
+// slice, so the range stays non-empty and a multiple of the K tile.
+template <int BM, int BN, int BK> __device__ inline bool narrow_to_shape(int shape, int64_t m0, int64_t n0, int &kb, int &ke)
+{
+    if (shape == 0) return true;
+    const int row_end = static_cast<int>(m0) + BM, col_end = static_cast<int>(n0) + BN;
+    const int row_floor = static_cast<int>(m0) / BK * BK, col_floor = static_cast<int>(n0) / BK * BK;
+    if (shape == 1) ke = ke < row_end ? ke : row_end;               // op(A)(i, l) = 0 for l > i
+    else if (shape == 2) kb = kb > row_floor ? kb : row_floor;      // op(A)(i, l) = 0 for l < i
+    else if (shape == 3) kb = kb > col_floor ? kb : col_floor;      // op(B)(l, j) = 0 for l < j
+    else if (shape == 4) ke = ke < col_end ? ke : col_end;          // op(B)(l, j) = 0 for l > j
+    else if (shape == 5) return n0 < m0 + BM;                       // else every (i, j) of the tile has i < j
+    else if (shape == 6) return m0 < n0 + BN;                       // else every (i, j) of the tile has i > j
+    return true;
+}
+
 // first of `total` items that falls into slot `slot` of `slots` when spread evenly
 constexpr int share_begin(int slot, int total, int slots) { return slot * total / slots; }
 
@@ -458,10 +495,12 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
     int tm, tn;
-    tile_coords(blockIdx.x, args.tiles_m, args.tiles_n, args.group_m, tm, tn);
+    if (args.shape == 0) tile_coords(blockIdx.x, args.tiles_m, args.tiles_n, args.group_m, tm, tn);
+    else tile_coords_balanced(blockIdx.x, args.tiles_m, args.tiles_n, args.group_m, args.reversed != 0, tm, tn);
     const int64_t m0 = static_cast<int64_t>(tm) * BM, n0 = static_cast<int64_t>(tn) * BN;
-    const int kb = blockIdx.z * args.k_per_split;
-    const int ke = (kb + args.k_per_split < args.k) ? kb + args.k_per_split : args.k;
+    int kb = blockIdx.z * args.k_per_split;
+    int ke = (kb + args.k_per_split < args.k) ? kb + args.k_per_split : args.k;
+    if (!narrow_to_shape<BM, BN, BK>(args.shape, m0, n0, kb, ke)) return;
 
     const T *__restrict__ A = static_cast<const T *>(args.A);
     const T *__restrict__ B = static_cast<const T *>(args.B);

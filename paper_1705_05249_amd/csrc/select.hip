@@ -120,8 +120,10 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
             const int64_t blocks = ceil_div(p.m, tiles[i].bm) * ceil_div(p.n, tiles[i].bn);
             const int64_t ktiles = ceil_div(p.k, tiles[i].bk);
             const bool last = i == count - 1;
-            if (!last && (blocks < (kComputeUnits * 3) / 4 || ktiles <= 8)) continue;
-            int want = last ? pick_split(blocks, ktiles) : 1;
+            // a shape hint leaves about half of the tile work: the grid must be twice as large to fill the chip
+            const int64_t busy = p.shape != MG_SHAPE_GENERAL ? blocks / 2 : blocks;
+            if (!last && (busy < (kComputeUnits * 3) / 4 || ktiles <= 8)) continue;
+            int want = last && p.shape == MG_SHAPE_GENERAL ? pick_split(blocks, ktiles) : 1;
             // split-K needs the caller's workspace: without enough of it, run unsplit
             while (want > 1 && static_cast<size_t>(want) * p.m * p.n * sizeof(float) > workspace_bytes) want = 1;
             // FP16 and whole 256 x 256 tiles: the direct-to-LDS kernels with two wavefronts per SIMD and 16x16x32

@@ -145,3 +145,95 @@ def test_benchmark_size_on_sampled_outputs(level3_oracle):
     assert H.rel_error(got[low], ref[low], den[low]) <= H.TOL["f16"]
     old = W.unpack(case.C, C, n, n, case.ldc)[np.ix_(pick, pick)]
     assert np.array_equal(H.bits(np.ascontiguousarray(got[~low])), H.bits(np.ascontiguousarray(old[~low])))
+
+
+def _with_forced_tile_kernel(case, level3_oracle, tag=None, suffix="_edge"):
+    """Runs the case with a forced macro-tile kernel (default: the bounds-checked 64 x 64 one): a forced
+    configuration keeps the shape hint (narrowed K ranges for TRMM, skipped tiles for SYRK) that small problems
+    otherwise drop.  The operand order the call ends up with decides which of the four kernels is legal."""
+    tag = tag or ("smfma_64x64x32_w2x2" if case.dtype == "f32" else "hmfma_64x64x64_w2x2")
+    try:
+        for contig in ("mk", "kk", "mn", "kn"):
+            G.mg_override_config(G.kernel_id(f"{tag}_{contig}{suffix}"), 1)
+            st, _ = H.run_level3(case, check=False)
+            if st == 0:
+                return H.check_level3(case, level3_oracle)
+            assert st == -11
+        raise AssertionError("no macro-tile kernel accepted the problem")
+    finally:
+        G.mg_clear_override()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("layout,side,uplo,trans", list(itertools.product([C, R], [LEFT, RIGHT], [UP, LO], [N, T])))
+def test_trmm_with_narrowed_k_ranges(level3_oracle, dtype, layout, side, uplo, trans):
+    for diag, shape in ((NONUNIT, (200, 136)), (UNIT, (130, 260))):
+        case = W.level3_case("trmm", dtype, layout, *shape, side=side, uplo=uplo, trans=trans, diag=diag, alpha=1.5,
+                             pad=(1, 0, 2), case=17)
+        _with_forced_tile_kernel(case, level3_oracle)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("layout,uplo,trans", list(itertools.product([C, R], [UP, LO], [N, T])))
+def test_syrk_with_skipped_tiles(level3_oracle, dtype, layout, uplo, trans):
+    case = W.level3_case("syrk", dtype, layout, 300, 300, k=100, uplo=uplo, trans=trans, alpha=1.0, beta=-2.0,
+                         pad=(0, 0, 1), case=19)
+    _with_forced_tile_kernel(case, level3_oracle)
+
+
+@pytest.mark.parametrize("layout,side,uplo,trans", list(itertools.product([C, R], [LEFT, RIGHT], [UP, LO], [N, T])))
+def test_trmm_hint_in_the_direct_to_lds_kernel(level3_oracle, layout, side, uplo, trans):
+    """whole 256 x 256 tiles, FP16: the headline kernel family with narrowed K ranges (3 x 2 and 2 x 3 tiles)"""
+    case = W.level3_case("trmm", "f16", layout, 768, 512, side=side, uplo=uplo, trans=trans, alpha=0.75, case=31)
+    _with_forced_tile_kernel(case, level3_oracle, tag="hdma16_256x256x64_w2x4", suffix="")
+
+
+@pytest.mark.parametrize("layout,uplo,trans", list(itertools.product([C, R], [UP, LO], [N, T])))
+def test_syrk_hint_in_the_direct_to_lds_kernel(level3_oracle, layout, uplo, trans):
+    case = W.level3_case("syrk", "f16", layout, 768, 768, k=192, uplo=uplo, trans=trans, alpha=1.0, beta=0.5, case=37)
+    _with_forced_tile_kernel(case, level3_oracle, tag="hdma16_256x256x64_w2x4", suffix="")
+
+
+@pytest.mark.parametrize("dtype,layout,side,uplo,trans", [("f16", C, LEFT, LO, N), ("f32", C, RIGHT, UP, N),
+                                                          ("f16", R, LEFT, UP, T), ("f32", R, RIGHT, LO, T)])
+def test_large_trmm_on_sampled_columns(level3_oracle, dtype, layout, side, uplo, trans):
+    """large enough (6144^2 outputs) that the library keeps the shape hint by itself; 8 sampled columns (or, for
+    a product from the right, rows) of B are independent problems the oracle solves in full"""
+    n = 6144
+    case = W.level3_case("trmm", dtype, layout, n, n, side=side, uplo=uplo, trans=trans, alpha=1.0, case=23)
+    _, out = H.run_level3(case)
+    g = np.random.default_rng(5)
+    pick = np.sort(g.choice(n, size=8, replace=False))
+    Bm = W.unpack(case.B, layout, n, n, case.ldb)
+    got = W.unpack(out, layout, n, n, case.ldb)
+    if side == LEFT:
+        sub, want_shape = np.ascontiguousarray(Bm[:, pick]), (n, len(pick))
+        got = got[:, pick]
+    else:
+        sub, want_shape = np.ascontiguousarray(Bm[pick, :]), (len(pick), n)
+        got = got[pick, :]
+    ld = W.tight_ld(layout, N, *want_shape)
+    ref, den = level3_oracle.trmm(dtype, layout, side, uplo, trans, NONUNIT, *want_shape, 1.0, case.A, case.lda,
+                                  W.pack(sub, layout, N, ld), ld)
+    assert H.rel_error(got, ref, den) <= H.TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,layout,uplo,trans", [("f16", C, LO, N), ("f32", R, LO, T), ("f16", R, UP, N)])
+def test_large_syrk_on_sampled_entries(level3_oracle, dtype, layout, uplo, trans):
+    n, k = 6144, 1024
+    case = W.level3_case("syrk", dtype, layout, n, n, k=k, uplo=uplo, trans=trans, alpha=1.0, beta=0.0, case=29)
+    _, out = H.run_level3(case)
+    g = np.random.default_rng(6)
+    pick = np.sort(g.choice(n, size=128, replace=False))
+    stored = W.unpack(case.A, layout, *((n, k) if trans == N else (k, n)), case.lda)
+    rows = stored[pick] if trans == N else stored[:, pick]
+    ld = W.tight_ld(layout, N, *rows.shape)
+    blank = np.zeros(len(pick) ** 2, np.float32 if dtype == "f32" else np.float16)
+    ref, den = level3_oracle.syrk(dtype, layout, uplo, trans, len(pick), k, 1.0, W.pack(np.ascontiguousarray(rows), layout, N, ld),
+                                  ld, 0.0, blank, len(pick))
+    got = W.unpack(out, layout, n, n, case.ldc)[np.ix_(pick, pick)]
+    old = W.unpack(case.C, layout, n, n, case.ldc)[np.ix_(pick, pick)]
+    i, j = np.indices(got.shape)
+    live = (i <= j) if uplo == UP else (i >= j)
+    assert H.rel_error(got[live], ref[live], den[live]) <= H.TOL[dtype]
+    assert np.array_equal(H.bits(np.ascontiguousarray(got[~live])), H.bits(np.ascontiguousarray(old[~live])))
