@@ -25,7 +25,8 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
 # counters read for a plain copy kernel of known size (profiles/ holds the summaries these come from).
-MEASURED_TRAFFIC_BYTES = {"hgemm_4096": 235042978, "sgemm_4096": 470094977, "batched_16x10000": 43636950}
+MEASURED_TRAFFIC_BYTES = {"hgemm_4096": 235042978, "sgemm_4096": 470094977, "batched_16x10000": 43636950,
+                          "sgemv_16384_N": 1075332914, "sgemv_16384_T": 1074414473}
 
 
 def timed(fn, steps, warmup):
@@ -255,7 +256,8 @@ def main():
             extra.append({"workload": f"sgemv_f32_{size}x{size}_colmajor_{tag}", "gflops": round(2.0 * size * size / dev / 1e9, 1),
                           "ms": round(dev * 1e3, 5),
                           "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                       "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None}})
+                                       "frac": round(gbs / PEAK_HBM_GBS, 4),
+                                       "traffic": MEASURED_TRAFFIC_BYTES.get(f"sgemv_{size}_{tag}")}})
 
     # ---- next row: the GEMM-derived level-3 routines at the size of the headline product (FP16 storage);
     # flops are the useful ones of each routine (SYRK and TRMM compute a full product: twice that)
