@@ -91,78 +91,111 @@ __device__ inline typename Vec4<T>::type load4(const T *__restrict__ X, int64_t 
     return v;
 }
 
-// NS: wavefronts per instance (each takes NB_ALL / NS of the 16-column blocks)
-template <typename T, int MB, int NB_ALL, int KB, int NS, bool A_KC, bool B_KC, bool FULL>
+// NS: wavefronts per instance (each takes NB_ALL / NS of the 16-column blocks).
+// IPW: instances per wavefront (NS == 1 only).  With more instances than resident wavefronts (256 compute
+// units x 32) a second round of wavefronts pays the whole load-to-store latency chain again; a wavefront that
+// takes two neighbouring instances issues the loads of both before it waits for either.
+template <typename T, int MB, int NB_ALL, int KB, int NS, bool A_KC, bool B_KC, bool FULL, int IPW = 1>
 __global__ __launch_bounds__(256) void batched_wave_kernel(const BatchedArgs a)
 {
+    static_assert(IPW == 1 || NS == 1, "several instances per wavefront only when one wavefront covers an instance");
     using V = typename Vec4<T>::type;
     constexpr int NB = NB_ALL / NS;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
     const int64_t gw = static_cast<int64_t>(blockIdx.x) * 4 + wave;
-    const int64_t inst = gw / NS;
+    const int64_t inst0 = gw / NS * IPW;
     const int col0 = static_cast<int>(gw % NS) * NB * 16;       // first column of this wavefront's share
-    if (inst >= a.batch) return;
-    // generic form: five wave-uniform scalar loads per instance; strided form: none
-    const float alpha = a.strided ? a.alpha : a.alphas[inst], beta = a.strided ? a.beta : a.betas[inst];
-    const T *__restrict__ A = static_cast<const T *>(a.A) + (a.strided ? inst * a.stride_a : a.a_off[inst]);
-    const T *__restrict__ B = static_cast<const T *>(a.B) + (a.strided ? inst * a.stride_b : a.b_off[inst]);
-    T *__restrict__ C = static_cast<T *>(a.C) + (a.strided ? inst * a.stride_c : a.c_off[inst]);
+    if (inst0 >= a.batch) return;
     const int lane = threadIdx.x % 64, r16 = lane % 16, g = lane / 16;
 
-    floatx4 acc[NB][MB];
+    float alpha[IPW], beta[IPW];
+    const T *__restrict__ A[IPW];
+    const T *__restrict__ B[IPW];
+    T *__restrict__ C[IPW];
+    bool live[IPW];
+    // generic form: five wave-uniform scalar loads per instance; strided form: none
 #pragma unroll
-    for (int bj = 0; bj < NB; ++bj)
-#pragma unroll
-        for (int bi = 0; bi < MB; ++bi) acc[bj][bi] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int q = 0; q < IPW; ++q) {
+        live[q] = inst0 + q < a.batch;
+        const int64_t inst = live[q] ? inst0 + q : inst0;       // a missing last instance repeats the first (loaded, never stored)
+        alpha[q] = a.strided ? a.alpha : a.alphas[inst];
+        beta[q] = a.strided ? a.beta : a.betas[inst];
+        A[q] = static_cast<const T *>(a.A) + (a.strided ? inst * a.stride_a : a.a_off[inst]);
+        B[q] = static_cast<const T *>(a.B) + (a.strided ? inst * a.stride_b : a.b_off[inst]);
+        C[q] = static_cast<T *>(a.C) + (a.strided ? inst * a.stride_c : a.c_off[inst]);
+    }
 
-    // C_old first (longest latency chain ends in the store), then the operands
-    V cold[NB][MB];
-    if (beta != 0.f) {
+    floatx4 acc[IPW][NB][MB];
+#pragma unroll
+    for (int q = 0; q < IPW; ++q)
 #pragma unroll
         for (int bj = 0; bj < NB; ++bj)
 #pragma unroll
-            for (int bi = 0; bi < MB; ++bi) cold[bj][bi] = load4<T, true, FULL>(C, a.ldc, col0 + bj * 16 + r16, bi * 16 + 4 * g, a.n, a.m);
-    }
+            for (int bi = 0; bi < MB; ++bi) acc[q][bj][bi] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    if (alpha != 0.f) {     // alpha == 0: A and B are not read at all
-        V av[MB][KB], bv[NB][KB];
+    // C_old first (longest latency chain ends in the store), then the operands
+    V cold[IPW][NB][MB];
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-#pragma unroll
-            for (int bi = 0; bi < MB; ++bi) av[bi][kb] = load4<T, A_KC, FULL>(A, a.lda, bi * 16 + r16, kb * 16 + 4 * g, a.m, a.k);
-#pragma unroll
-            for (int bj = 0; bj < NB; ++bj) bv[bj][kb] = load4<T, B_KC, FULL>(B, a.ldb, col0 + bj * 16 + r16, kb * 16 + 4 * g, a.n, a.k);
-        }
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
+    for (int q = 0; q < IPW; ++q)
+        if (beta[q] != 0.f) {
 #pragma unroll
             for (int bj = 0; bj < NB; ++bj)
 #pragma unroll
-                for (int bi = 0; bi < MB; ++bi) acc[bj][bi] = block_mma(av[bi][kb], bv[bj][kb], acc[bj][bi]);
-    }
+                for (int bi = 0; bi < MB; ++bi)
+                    cold[q][bj][bi] = load4<T, true, FULL>(C[q], a.ldc, col0 + bj * 16 + r16, bi * 16 + 4 * g, a.n, a.m);
+        }
+
+    V av[IPW][MB][KB], bv[IPW][NB][KB];
+#pragma unroll
+    for (int q = 0; q < IPW; ++q)
+        if (alpha[q] != 0.f) {     // alpha == 0: A and B are not read at all
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+#pragma unroll
+                for (int bi = 0; bi < MB; ++bi)
+                    av[q][bi][kb] = load4<T, A_KC, FULL>(A[q], a.lda, bi * 16 + r16, kb * 16 + 4 * g, a.m, a.k);
+#pragma unroll
+                for (int bj = 0; bj < NB; ++bj)
+                    bv[q][bj][kb] = load4<T, B_KC, FULL>(B[q], a.ldb, col0 + bj * 16 + r16, kb * 16 + 4 * g, a.n, a.k);
+            }
+        }
+#pragma unroll
+    for (int q = 0; q < IPW; ++q)
+        if (alpha[q] != 0.f) {
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int bj = 0; bj < NB; ++bj)
+#pragma unroll
+                    for (int bi = 0; bi < MB; ++bi) acc[q][bj][bi] = block_mma(av[q][bi][kb], bv[q][bj][kb], acc[q][bj][bi]);
+        }
 
     // lane (r16, g) holds C(i = 16 bi + 4g + r, j = 16 bj + r16), r = 0..3: four consecutive rows of one column
 #pragma unroll
-    for (int bj = 0; bj < NB; ++bj)
+    for (int q = 0; q < IPW; ++q) {
+        if (!live[q]) continue;
 #pragma unroll
-        for (int bi = 0; bi < MB; ++bi) {
-            const int j = col0 + bj * 16 + r16, i0 = bi * 16 + 4 * g;
-            floatx4 o = alpha * acc[bj][bi];
-            if (beta != 0.f) o += beta * widen(cold[bj][bi]);
-            T *p = C + i0 + j * a.ldc;
-            if (FULL || (j < a.n && i0 + 3 < a.m)) {
-                *reinterpret_cast<Quad<T> *>(p) = Quad<T>{static_cast<T>(o.x), static_cast<T>(o.y), static_cast<T>(o.z), static_cast<T>(o.w)};
-            } else if (j < a.n) {
+        for (int bj = 0; bj < NB; ++bj)
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (i0 + r < a.m) p[r] = static_cast<T>(o[r]);
+            for (int bi = 0; bi < MB; ++bi) {
+                const int j = col0 + bj * 16 + r16, i0 = bi * 16 + 4 * g;
+                floatx4 o = alpha[q] * acc[q][bj][bi];
+                if (beta[q] != 0.f) o += beta[q] * widen(cold[q][bj][bi]);
+                T *p = C[q] + i0 + j * a.ldc;
+                if (FULL || (j < a.n && i0 + 3 < a.m)) {
+                    *reinterpret_cast<Quad<T> *>(p) = Quad<T>{static_cast<T>(o.x), static_cast<T>(o.y), static_cast<T>(o.z), static_cast<T>(o.w)};
+                } else if (j < a.n) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (i0 + r < a.m) p[r] = static_cast<T>(o[r]);
+                }
             }
-        }
+    }
 }
 
 // ---------------------------------------------------------------------------------- host side
 
-template <typename T, int MB, int NB, int KB, int NS, bool A_KC, bool B_KC, bool FULL> struct WaveConfig {
+template <typename T, int MB, int NB, int KB, int NS, bool A_KC, bool B_KC, bool FULL, int IPW = 1> struct WaveConfig {
     static constexpr int DTYPE = sizeof(T) == 4 ? MG_F32 : MG_F16;
     static bool legal(const BatchedProblem &p)
     {
@@ -179,8 +212,8 @@ template <typename T, int MB, int NB, int KB, int NS, bool A_KC, bool B_KC, bool
         BatchedArgs a{p.A, p.B, p.C, p.a_off, p.b_off, p.c_off, p.alphas, p.betas, p.lda, p.ldb, p.ldc,
                       static_cast<int>(p.m), static_cast<int>(p.n), static_cast<int>(p.k), p.batch,
                       p.strided ? 1 : 0, p.stride_a, p.stride_b, p.stride_c, p.alpha, p.beta};
-        hipLaunchKernelGGL((batched_wave_kernel<T, MB, NB, KB, NS, A_KC, B_KC, FULL>),
-                           dim3(static_cast<unsigned>(ceil_div(p.batch * NS, 4))), dim3(256), 0, p.stream, a);
+        hipLaunchKernelGGL((batched_wave_kernel<T, MB, NB, KB, NS, A_KC, B_KC, FULL, IPW>),
+                           dim3(static_cast<unsigned>(ceil_div(ceil_div(p.batch, IPW) * NS, 4))), dim3(256), 0, p.stream, a);
         return hipGetLastError();
     }
     static KernelEntry entry(const char *name)
@@ -204,6 +237,14 @@ template <typename T, int MB, int NB, int KB, int NS, bool A_KC, bool B_KC, bool
     table.push_back(WaveConfig<T, B, B, B, NS, false, false, false>::entry(tag "_mn"));              \
     table.push_back(WaveConfig<T, B, B, B, NS, true, false, false>::entry(tag "_kn"));
 
+// the same five kernels with two instances per wavefront
+#define MG_BATCHED_REGISTER_PAIRS(table, T, tag, B)                                                  \
+    table.push_back(WaveConfig<T, B, B, B, 1, false, true, true, 2>::entry(tag "_mk_full"));        \
+    table.push_back(WaveConfig<T, B, B, B, 1, false, true, false, 2>::entry(tag "_mk"));            \
+    table.push_back(WaveConfig<T, B, B, B, 1, true, true, false, 2>::entry(tag "_kk"));             \
+    table.push_back(WaveConfig<T, B, B, B, 1, false, false, false, 2>::entry(tag "_mn"));           \
+    table.push_back(WaveConfig<T, B, B, B, 1, true, false, false, 2>::entry(tag "_kn"));
+
 }  // namespace
 
 void register_batched(std::vector<KernelEntry> &table)
@@ -215,6 +256,8 @@ void register_batched(std::vector<KernelEntry> &table)
     MG_BATCHED_REGISTER(table, _Float16, "hbatched_wave_16", 1, 1)
     MG_BATCHED_REGISTER(table, _Float16, "hbatched_wave_32", 2, 1)
     MG_BATCHED_REGISTER(table, _Float16, "hbatched_wave_64w1", 4, 1)
+    MG_BATCHED_REGISTER_PAIRS(table, float, "batched_wave_16x2", 1)
+    MG_BATCHED_REGISTER_PAIRS(table, _Float16, "hbatched_wave_16x2", 1)
 }
 
 }  // namespace mg

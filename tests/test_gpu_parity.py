@@ -435,7 +435,7 @@ def test_every_batched_configuration_gives_parity(G, oracle):
     kernels = [t for t in G.kernel_table() if t["family"] == G.MG_FAMILY_BATCHED]
     ran = {t["name"]: 0 for t in kernels}
     try:
-        for (s, batch) in ((8, 50), (16, 70), (32, 20), (64, 9), (24, 5)):
+        for (s, batch) in ((8, 51), (16, 70), (16, 33), (32, 20), (64, 9), (24, 5)):
             for layout, ta, tb, dtype in [(*v, d) for v in ((C, N, N), (R, N, N), (C, T, T), (C, T, N), (C, N, T))
                                           for d in ("f32", "f16")]:
                 bc = W.batched_case(s, s, s, batch, case=s, layout=layout, ta=ta, tb=tb, integer=True, dtype=dtype)
