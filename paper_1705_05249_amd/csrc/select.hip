@@ -39,6 +39,9 @@ bool try_mfma(const std::vector<KernelEntry> &table, const Problem &p, int64_t a
 struct TileChoice {
     const char *tag;
     int bm, bn, bk;
+    float ceiling;       // Mflop/us per compute unit with enough resident work-groups
+    float per_group;     // ... contributed by each resident work-group
+    int resident;        // work-groups a compute unit holds at once
 };
 
 constexpr int kComputeUnits = 256;
@@ -106,36 +109,61 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
         }
     }
     if (p.m >= 16 && p.n >= 16) {
-        // Largest macro tile that still gives (nearly) every compute unit a tile of its own; short K goes
-        // to the smallest tile, whose many resident work-groups keep more of the C traffic in flight.
-        static const TileChoice f16_tiles[] = {{"hmfma_256x256x64_w2x2", 256, 256, 64},
-                                               {"hmfma_128x128x64_w2x2", 128, 128, 64},
-                                               {"hmfma_64x64x64_w2x2", 64, 64, 64}};
-        static const TileChoice f32_tiles[] = {{"smfma_256x256x32_w2x2", 256, 256, 32},
-                                               {"smfma_128x128x32_w2x2", 128, 128, 32},
-                                               {"smfma_64x64x32_w2x2", 64, 64, 32}};
+        // The macro tile with the smallest estimated time.  A compute unit works through ceil(tiles / 256) tiles
+        // at a rate that grows with the number of its resident work-groups up to the kernel's own ceiling:
+        //     time ~ ceil(tiles / 256) * 2 BM BN k / min(ceiling, per_group * min(resident_max, ceil(tiles / 256)))
+        // Rates (Mflop/us per compute unit) are fitted to a scan of every tile over square problems from 1024 to
+        // 6144 in the four operand orders; partial tiles of ragged problems count as whole ones.  Short K
+        // (<= 8 K-tiles) goes to the smallest tile, whose many resident work-groups keep the C traffic in flight.
+        static const TileChoice f16_tiles[] = {{"hdma16_256x256x64_w2x4", 256, 256, 64, 5.1f, 5.1f, 1},
+                                               {"hmfma_256x256x64_w2x2", 256, 256, 64, 4.5f, 4.5f, 1},
+                                               {"hmfma_256x128x64_w2x2", 256, 128, 64, 3.8f, 3.8f, 1},
+                                               {"hmfma_128x128x64_w2x2", 128, 128, 64, 3.3f, 1.8f, 2},
+                                               {"hmfma_128x64x64_w2x2", 128, 64, 64, 2.6f, 0.98f, 3},
+                                               {"hmfma_64x64x64_w2x2", 64, 64, 64, 1.9f, 0.6f, 5}};
+        static const TileChoice f32_tiles[] = {{"smfma_256x256x32_w2x2", 256, 256, 32, 0.577f, 0.577f, 1},
+                                               {"smfma_256x128x32_w2x2", 256, 128, 32, 0.561f, 0.561f, 1},
+                                               {"smfma_128x128x32_w2x2", 128, 128, 32, 0.574f, 0.50f, 2},
+                                               {"smfma_128x64x32_w2x2", 128, 64, 32, 0.553f, 0.45f, 3},
+                                               {"smfma_64x64x32_w2x2", 64, 64, 32, 0.52f, 0.35f, 5}};
         const TileChoice *tiles = f32 ? f32_tiles : f16_tiles;
-        const int count = 3;
-        for (int i = 0; i < count; ++i) {
-            const int64_t blocks = ceil_div(p.m, tiles[i].bm) * ceil_div(p.n, tiles[i].bn);
-            const int64_t ktiles = ceil_div(p.k, tiles[i].bk);
-            const bool last = i == count - 1;
-            // a shape hint leaves about half of the tile work: the grid must be twice as large to fill the chip
-            const int64_t busy = p.shape != MG_SHAPE_GENERAL ? blocks / 2 : blocks;
-            if (!last && (busy < (kComputeUnits * 3) / 4 || ktiles <= 8)) continue;
-            int want = last && p.shape == MG_SHAPE_GENERAL ? pick_split(blocks, ktiles) : 1;
+        const int count = f32 ? 5 : 6;
+        bool tried[6] = {false, false, false, false, false, false};
+        for (int attempt = 0; attempt < count; ++attempt) {
+            int best = -1;
+            double best_time = 0.0;
+            for (int i = 0; i < count; ++i) {
+                if (tried[i]) continue;
+                const bool last = i == count - 1;
+                if (!last && ceil_div(p.k, tiles[i].bk) <= 8) continue;
+                int64_t blocks = ceil_div(p.m, tiles[i].bm) * ceil_div(p.n, tiles[i].bn);
+                double k_each = static_cast<double>(p.k);
+                // a shape hint leaves about half of the tile work; the smallest tile may split K
+                if (p.shape != MG_SHAPE_GENERAL) blocks = (blocks + 1) / 2;
+                else if (last) {
+                    const int slices = pick_split(blocks, ceil_div(p.k, tiles[i].bk));
+                    if (static_cast<size_t>(slices) * p.m * p.n * sizeof(float) <= workspace_bytes) {
+                        blocks *= slices;
+                        k_each /= slices;
+                    }
+                }
+                const int64_t per_unit = ceil_div(blocks, kComputeUnits);
+                const double resident = static_cast<double>(per_unit < tiles[i].resident ? per_unit : tiles[i].resident);
+                const double rate = tiles[i].ceiling < tiles[i].per_group * resident ? tiles[i].ceiling : tiles[i].per_group * resident;
+                const double time = static_cast<double>(per_unit) * 2.0 * tiles[i].bm * tiles[i].bn * k_each / rate;
+                if (best < 0 || time < best_time) { best = i; best_time = time; }
+            }
+            if (best < 0) break;
+            tried[best] = true;
+            const TileChoice &tc = tiles[best];
+            const int64_t blocks = ceil_div(p.m, tc.bm) * ceil_div(p.n, tc.bn);
+            const int64_t ktiles = ceil_div(p.k, tc.bk);
+            int want = best == count - 1 && p.shape == MG_SHAPE_GENERAL ? pick_split(blocks, ktiles) : 1;
             // split-K needs the caller's workspace: without enough of it, run unsplit
             while (want > 1 && static_cast<size_t>(want) * p.m * p.n * sizeof(float) > workspace_bytes) want = 1;
-            // FP16 and whole 256 x 256 tiles: the direct-to-LDS kernels with two wavefronts per SIMD and 16x16x32
-            // MFMA blocks measured fastest for every operand order
-            if (!f32 && i == 0) {
-                char name[96];
-                const char *contig = p.a_trans ? (p.b_trans ? "kn" : "kk") : (p.b_trans ? "mn" : "mk");
-                snprintf(name, sizeof name, "hdma16_256x256x64_w2x4_%s", contig);
-                if (try_pick(table, p, alignment, name, want, kernel, split)) return;
-            }
-            if (try_mfma(table, p, alignment, tiles[i].tag, want, kernel, split)) return;
-            if (want > 1 && try_mfma(table, p, alignment, tiles[i].tag, 1, kernel, split)) return;
+            // a factor whose last slice would be empty is illegal: take the next smaller one
+            for (int w = want; w >= 1; --w)
+                if (try_mfma(table, p, alignment, tc.tag, w, kernel, split)) return;
         }
     }
     try_pick(table, p, alignment, f32 ? "direct_f32_64x64x16" : "direct_f16_64x64x16", 1, kernel, split);
