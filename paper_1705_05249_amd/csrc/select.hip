@@ -1,3 +1,4 @@
+#include <math.h>
 #include <stdio.h>
 #include <string.h>
 
@@ -115,20 +116,35 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
         // Rates (Mflop/us per compute unit) are fitted to a scan of every tile over square problems from 1024 to
         // 6144 in the four operand orders; partial tiles of ragged problems count as whole ones.  Short K
         // (<= 8 K-tiles) goes to the smallest tile, whose many resident work-groups keep the C traffic in flight.
+        // (the direct-to-LDS kernels need whole tiles and 16-byte aligned operands; else they are illegal and the
+        // next best estimate is tried)
         static const TileChoice f16_tiles[] = {{"hdma16_256x256x64_w2x4", 256, 256, 64, 5.1f, 5.1f, 1},
+                                               {"hdma16_256x128x64_w4x2", 256, 128, 64, 4.3f, 4.3f, 1},
+                                               {"hdma16_128x128x64_w2x2", 128, 128, 64, 4.1f, 2.4f, 2},
                                                {"hmfma_256x256x64_w2x2", 256, 256, 64, 4.5f, 4.5f, 1},
                                                {"hmfma_256x128x64_w2x2", 256, 128, 64, 3.8f, 3.8f, 1},
                                                {"hmfma_128x128x64_w2x2", 128, 128, 64, 3.3f, 1.8f, 2},
                                                {"hmfma_128x64x64_w2x2", 128, 64, 64, 2.6f, 0.98f, 3},
                                                {"hmfma_64x64x64_w2x2", 64, 64, 64, 1.9f, 0.6f, 5}};
+        // The register-staged FP16 kernels transpose operands that are not contiguous along k on their way to
+        // LDS; the smaller the tile, the more that shows.  Measured rates relative to the (m, k) order: both
+        // operands along k 1.3 / 1.1 / 1.0 (tiles up to 128 x 64 / up to 256 x 128 / 256 x 256), A along m and B
+        // along n 0.62 / 0.85 / 1.0.
+        auto staged_f16 = [&](const TileChoice &t) {
+            const int cls = t.bm * t.bn <= 128 * 64 ? 0 : (t.bm * t.bn <= 256 * 128 ? 1 : 2);
+            static const double both_k[3] = {1.3, 1.1, 1.0}, neither_k[3] = {0.62, 0.85, 1.0};
+            if (p.a_trans && !p.b_trans) return both_k[cls];
+            if (!p.a_trans && p.b_trans) return neither_k[cls];
+            return 1.0;
+        };
         static const TileChoice f32_tiles[] = {{"smfma_256x256x32_w2x2", 256, 256, 32, 0.577f, 0.577f, 1},
                                                {"smfma_256x128x32_w2x2", 256, 128, 32, 0.561f, 0.561f, 1},
                                                {"smfma_128x128x32_w2x2", 128, 128, 32, 0.574f, 0.50f, 2},
                                                {"smfma_128x64x32_w2x2", 128, 64, 32, 0.553f, 0.45f, 3},
                                                {"smfma_64x64x32_w2x2", 64, 64, 32, 0.52f, 0.35f, 5}};
         const TileChoice *tiles = f32 ? f32_tiles : f16_tiles;
-        const int count = f32 ? 5 : 6;
-        bool tried[6] = {false, false, false, false, false, false};
+        const int count = f32 ? 5 : 8;
+        bool tried[8] = {false, false, false, false, false, false, false, false};
         for (int attempt = 0; attempt < count; ++attempt) {
             int best = -1;
             double best_time = 0.0;
@@ -149,7 +165,17 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 }
                 const int64_t per_unit = ceil_div(blocks, kComputeUnits);
                 const double resident = static_cast<double>(per_unit < tiles[i].resident ? per_unit : tiles[i].resident);
-                const double rate = tiles[i].ceiling < tiles[i].per_group * resident ? tiles[i].ceiling : tiles[i].per_group * resident;
+                double rate = tiles[i].ceiling < tiles[i].per_group * resident ? tiles[i].ceiling : tiles[i].per_group * resident;
+                if (!f32) {
+                    if (tiles[i].tag[1] == 'm') rate *= staged_f16(tiles[i]);
+                    // the fastest kernel runs against the power limit: with fewer busy compute units each one clocks
+                    // higher (144 tiles of 256 x 256 at 3072^3: 64 us measured against 79 us at the full-chip
+                    // rate); the smaller tiles showed no such gain
+                    if (i == 0 && blocks < kComputeUnits) {
+                        const double boost = sqrt(static_cast<double>(kComputeUnits) / static_cast<double>(blocks));
+                        rate *= boost < 1.25 ? boost : 1.25;
+                    }
+                }
                 const double time = static_cast<double>(per_unit) * 2.0 * tiles[i].bm * tiles[i].bn * k_each / rate;
                 if (best < 0 || time < best_time) { best = i; best_time = time; }
             }
