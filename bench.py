@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
 # counters read for a plain copy kernel of known size (profiles/ holds the summaries these come from).
-MEASURED_TRAFFIC_BYTES = {"hgemm_4096": 235042978, "sgemm_4096": 470094977, "batched_16x10000": 43636950,
+MEASURED_TRAFFIC_BYTES = {"hgemm_4096": 235042978, "sgemm_4096": 470094977, "batched_16x10000": 42897824,
                           "sgemv_16384_N": 1075332914, "sgemv_16384_T": 1074414473}
 
 
