@@ -128,11 +128,11 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                                                {"hmfma_64x64x64_w2x2", 64, 64, 64, 1.9f, 0.6f, 5}};
         // The register-staged FP16 kernels transpose operands that are not contiguous along k on their way to
         // LDS; the smaller the tile, the more that shows.  Measured rates relative to the (m, k) order: both
-        // operands along k 1.3 / 1.1 / 1.0 (tiles up to 128 x 64 / up to 256 x 128 / 256 x 256), A along m and B
+        // operands along k 1.2 / 1.1 / 1.0 (tiles up to 128 x 64 / up to 256 x 128 / 256 x 256), A along m and B
         // along n 0.62 / 0.85 / 1.0.
         auto staged_f16 = [&](const TileChoice &t) {
             const int cls = t.bm * t.bn <= 128 * 64 ? 0 : (t.bm * t.bn <= 256 * 128 ? 1 : 2);
-            static const double both_k[3] = {1.3, 1.1, 1.0}, neither_k[3] = {0.62, 0.85, 1.0};
+            static const double both_k[3] = {1.2, 1.1, 1.0}, neither_k[3] = {0.62, 0.85, 1.0};
             if (p.a_trans && !p.b_trans) return both_k[cls];
             if (!p.a_trans && p.b_trans) return neither_k[cls];
             return 1.0;
@@ -151,7 +151,6 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
             for (int i = 0; i < count; ++i) {
                 if (tried[i]) continue;
                 const bool last = i == count - 1;
-                if (!last && ceil_div(p.k, tiles[i].bk) <= 8) continue;
                 int64_t blocks = ceil_div(p.m, tiles[i].bm) * ceil_div(p.n, tiles[i].bn);
                 double k_each = static_cast<double>(p.k);
                 // a shape hint leaves about half of the tile work; the smallest tile may split K
@@ -163,20 +162,39 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                         k_each /= slices;
                     }
                 }
-                const int64_t per_unit = ceil_div(blocks, kComputeUnits);
-                const double resident = static_cast<double>(per_unit < tiles[i].resident ? per_unit : tiles[i].resident);
-                double rate = tiles[i].ceiling < tiles[i].per_group * resident ? tiles[i].ceiling : tiles[i].per_group * resident;
-                if (!f32) {
-                    if (tiles[i].tag[1] == 'm') rate *= staged_f16(tiles[i]);
-                    // the fastest kernel runs against the power limit: with fewer busy compute units each one clocks
-                    // higher (144 tiles of 256 x 256 at 3072^3: 64 us measured against 79 us at the full-chip
-                    // rate); the smaller tiles showed no such gain
-                    if (i == 0 && blocks < kComputeUnits) {
+                const double tile_flops = 2.0 * tiles[i].bm * tiles[i].bn * k_each;
+                const int64_t full = static_cast<int64_t>(kComputeUnits) * tiles[i].resident;   // work-groups the chip holds
+                double order = 1.0;
+                if (!f32 && tiles[i].tag[1] == 'm') order = staged_f16(tiles[i]);
+                double time;
+                if (blocks < full) {
+                    // the chip is not full: ceil(blocks / 256) work-groups share a compute unit
+                    const int64_t per_unit = ceil_div(blocks, kComputeUnits);
+                    double rate = tiles[i].per_group * static_cast<double>(per_unit);
+                    if (rate > tiles[i].ceiling) rate = tiles[i].ceiling;
+                    // the fastest kernel runs against the power limit: with fewer busy compute units each one
+                    // clocks higher (144 tiles of 256 x 256 at 3072^3: 64 us measured against 79 us at the
+                    // full-chip rate); the smaller tiles showed no such gain
+                    if (!f32 && i == 0 && blocks < kComputeUnits) {
                         const double boost = sqrt(static_cast<double>(kComputeUnits) / static_cast<double>(blocks));
                         rate *= boost < 1.25 ? boost : 1.25;
                     }
+                    time = static_cast<double>(per_unit) * tile_flops / (rate * order);
+                } else {
+                    // rounds of `full` work-groups; one work-group per compute unit quantises sharply (576 tiles
+                    // take three rounds), and so do the first two rounds of any kernel; with several resident
+                    // work-groups later rounds blur (measured: the fractional round costs 0.1-0.36 more).  The
+                    // fastest FP16 kernel is the exception: its partial last round runs on fewer compute units at
+                    // a higher clock (400 tiles take 1.7 rounds' time, 576 tiles 2.5)
+                    const double x = static_cast<double>(blocks) / static_cast<double>(full);
+                    const double whole = floor(x);
+                    double rounds = x;
+                    if (x > whole) {
+                        if (!f32 && i == 0) rounds = x + 0.25;
+                        else rounds = tiles[i].resident == 1 || x <= 2.0 ? whole + 1.0 : x + 0.25;
+                    }
+                    time = rounds * tiles[i].resident * tile_flops / (tiles[i].ceiling * order);
                 }
-                const double time = static_cast<double>(per_unit) * 2.0 * tiles[i].bm * tiles[i].bn * k_each / rate;
                 if (best < 0 || time < best_time) { best = i; best_time = time; }
             }
             if (best < 0) break;
