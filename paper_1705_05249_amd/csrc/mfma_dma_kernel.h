@@ -124,6 +124,8 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
     constexpr int FM = WTM / RB, FN = WTN / RB;
     constexpr int KSTEPS = BK / ((64 / RB) * 8);
     static_assert(WTM % 64 == 0 && WTN % 64 == 0, "wavefront tile: an even number of 32-row fragments per side");
+    // the [k][row] layout XORs slot numbers up to 14 into a line of ROWS / 8 slots
+    static_assert((A_KCONTIG || BM >= 128) && (B_KCONTIG || BN >= 128), "an operand that is not contiguous along k needs 128 rows");
     using LoadA = DmaLoader<BM, NT, A_KCONTIG>;
     using LoadB = DmaLoader<BN, NT, B_KCONTIG>;
     constexpr int A_BYTES = LoadA::LDS_BYTES, B_BYTES = LoadB::LDS_BYTES;   // LDS: [A stage 0][A stage 1][B stage 0][B stage 1]
