@@ -166,6 +166,11 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 const int64_t full = static_cast<int64_t>(kComputeUnits) * tiles[i].resident;   // work-groups the chip holds
                 double order = 1.0;
                 if (!f32 && tiles[i].tag[1] == 'm') order = staged_f16(tiles[i]);
+                // ragged or unaligned FP16 problems run the bounds-checked flavour, which costs the smaller tiles more
+                // (rates against the whole-tile flavour: 0.75 for 256 x 256 and 256 x 128, about 0.5 for 128 x 128
+                // and below; FP32 loses about 0.78 on every tile, which does not change the ranking)
+                if (!f32 && (p.m % tiles[i].bm || p.n % tiles[i].bn || p.k % tiles[i].bk))
+                    order *= tiles[i].bm * tiles[i].bn < 256 * 128 ? 0.6 : 0.7;
                 double time;
                 if (blocks < full) {
                     // the chip is not full: ceil(blocks / 256) work-groups share a compute unit
