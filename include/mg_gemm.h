@@ -113,7 +113,13 @@ mg_status mg_sgemm(int layout, int trans_a, int trans_b, int64_t m, int64_t n, i
                    void *workspace, size_t workspace_bytes, void *stream);
 
 /* FP16 storage (paper Section 4.4; here with FP32 accumulation): A, B, C hold IEEE binary16
- * values (2-byte aligned device pointers); alpha, beta are FP32 host scalars. */
+ * values (2-byte aligned device pointers); alpha, beta are FP32 host scalars.
+ * Large problems that are not whole tiles, or whose operands are not 16-byte aligned (an odd
+ * leading dimension), take the indirect route of the paper's Section 3.2 when the workspace has
+ * room: A, B (and C if beta != 0) are copied into zero-padded aligned buffers in the workspace, the
+ * fast kernel runs there, the result is copied back (same arithmetic, one rounding).  With less
+ * workspace the bounds-checked kernels run on the operands in place: same result up to summation
+ * order, 1.2-2.4x slower.  mg_gemm_workspace_bytes() reports the room the indirect route needs. */
 mg_status mg_hgemm(int layout, int trans_a, int trans_b, int64_t m, int64_t n, int64_t k,
                    float alpha, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
                    float beta, uint16_t *C, int64_t ldc,
@@ -229,8 +235,10 @@ mg_status mg_hgemm_strided_batched(int layout, int trans_a, int trans_b, int64_t
                                    uint16_t *C, int64_t ldc, int64_t stride_c,
                                    int64_t batch_count, void *stream);
 
-/* Bytes of workspace the currently selected configuration needs for this problem
- * (0 for most).  dtype is an mg_dtype.  Returns 0 for invalid arguments. */
+/* Bytes of workspace with which this problem runs its preferred route: the split-K partial sums
+ * of the selected configuration, or the padded copies of the indirect FP16 route (0 for most
+ * problems).  Any smaller workspace is legal and selects a route that fits.  dtype is an mg_dtype.
+ * Returns 0 for invalid arguments. */
 size_t mg_gemm_workspace_bytes(int dtype, int layout, int trans_a, int trans_b,
                                int64_t m, int64_t n, int64_t k,
                                int64_t lda, int64_t ldb, int64_t ldc);

@@ -117,9 +117,81 @@ mg_status choose(const Problem &p, int64_t alignment, size_t workspace_bytes, in
     return MG_OK;
 }
 
+size_t round_up_256(size_t v) { return (v + 255) / 256 * 256; }
+
+// Indirect GEMM, the paper's Section 3.2 route for problems that break the fast kernel's assumptions: copy the
+// operands into zero-padded, aligned buffers whose sizes are whole tiles, run the fast kernel there, copy the
+// result back.  Here only FP16 needs it: ragged or unaligned FP16 problems otherwise run the bounds-checked
+// register-staged kernels at 0.2-0.6 of the direct-to-LDS rate (4097^3: 525 us; an odd leading dimension puts
+// every other row at 2-byte alignment), while the copies are O(n^2) (~30 us at 4097^3).  FP32 loses only ~20 % in
+// its bounds-checked flavour and has no direct-to-LDS kernel, so it stays direct.  The padded buffers live in
+// the caller's workspace; without enough of it the direct route runs.  One rounding as always: the fast
+// kernel applies alpha and beta in the padded C, whose leading part is then copied out bit for bit.
+struct IndirectPlan {
+    int64_t mp, np, kp;
+    size_t a_bytes, b_bytes, c_bytes;
+    size_t total() const { return a_bytes + b_bytes + c_bytes; }
+};
+
+bool indirect_plan(const Problem &p, bool pointers_known, IndirectPlan *plan)
+{
+    if (p.dtype != MG_F16 || p.shape != MG_SHAPE_GENERAL || p.alpha == 0.f || p.k == 0) return false;
+    if (g_override_kernel[MG_F16] >= 0) return false;                  // a forced kernel gets the problem as it is
+    // four extra launches and ~33 us of copies at 4096^2: measured a loss at 1000^3 (28 against 22 us), a gain at
+    // 2049^3 (74 against 96 us)
+    if (p.m < 1024 || p.n < 1024 || p.k < 256) return false;
+    if (static_cast<double>(p.m) * static_cast<double>(p.n) * static_cast<double>(p.k) < 2.0e9) return false;
+    const bool whole = p.m % 128 == 0 && p.n % 128 == 0 && p.k % 64 == 0;
+    const bool aligned = p.lda % 8 == 0 && p.ldb % 8 == 0 &&
+                         (!pointers_known || (pointer_alignment(p.A) >= 16 && pointer_alignment(p.B) >= 16));
+    if (whole && aligned) return false;                                // the fast kernels take it directly
+    const int64_t tile = p.m >= 2048 && p.n >= 2048 ? 256 : 128;
+    plan->mp = ceil_div(p.m, tile) * tile;
+    plan->np = ceil_div(p.n, tile) * tile;
+    plan->kp = ceil_div(p.k, 64) * 64;
+    plan->a_bytes = round_up_256(static_cast<size_t>(plan->mp) * plan->kp * 2);
+    plan->b_bytes = round_up_256(static_cast<size_t>(plan->kp) * plan->np * 2);
+    plan->c_bytes = round_up_256(static_cast<size_t>(plan->mp) * plan->np * 2);
+    return true;
+}
+
+mg_status run_canonical(Problem p);
+
+mg_status run_indirect(const Problem &p, const IndirectPlan &plan)
+{
+    char *ws = static_cast<char *>(p.workspace);
+    void *ap = ws, *bp = ws + plan.a_bytes, *cp = ws + plan.a_bytes + plan.b_bytes;
+    hipStream_t st = p.stream;
+    // an operand keeps its storage order: stored rows x columns (column-major view) = m x k or k x m
+    const int64_t a_minor = p.a_trans ? p.k : p.m, a_major = p.a_trans ? p.m : p.k;
+    const int64_t a_minor_p = p.a_trans ? plan.kp : plan.mp, a_major_p = p.a_trans ? plan.mp : plan.kp;
+    const int64_t b_minor = p.b_trans ? p.n : p.k, b_major = p.b_trans ? p.k : p.n;
+    const int64_t b_minor_p = p.b_trans ? plan.np : plan.kp, b_major_p = p.b_trans ? plan.kp : plan.np;
+    if (launch_pad_matrix(a_minor, a_major, p.A, p.lda, ap, a_minor_p, a_minor_p, a_major_p, st) != hipSuccess) return MG_ERR_LAUNCH;
+    if (launch_pad_matrix(b_minor, b_major, p.B, p.ldb, bp, b_minor_p, b_minor_p, b_major_p, st) != hipSuccess) return MG_ERR_LAUNCH;
+    if (p.beta != 0.f &&
+        launch_pad_matrix(p.m, p.n, p.C, p.ldc, cp, plan.mp, plan.mp, plan.np, st) != hipSuccess)
+        return MG_ERR_LAUNCH;
+    Problem q = p;
+    q.m = plan.mp; q.n = plan.np; q.k = plan.kp;
+    q.A = ap; q.lda = a_minor_p;
+    q.B = bp; q.ldb = b_minor_p;
+    q.C = cp; q.ldc = plan.mp;
+    const size_t used = plan.total();
+    q.workspace = p.workspace_bytes > used ? ws + used : nullptr;
+    q.workspace_bytes = p.workspace_bytes > used ? p.workspace_bytes - used : 0;
+    const mg_status s = run_canonical(q);
+    if (s != MG_OK) return s;
+    return launch_unpad_matrix(p.m, p.n, cp, plan.mp, p.C, p.ldc, st) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
+}
+
 // Selects and launches the configuration for a canonical problem with at least one output.
 mg_status run_canonical(Problem p)
 {
+    IndirectPlan plan;
+    if (indirect_plan(p, true, &plan) && p.workspace != nullptr && pointer_alignment(p.workspace) >= 256 &&
+        p.workspace_bytes >= plan.total())
+        return run_indirect(p, plan);
     // A shape hint halves the tile work but rules out the direct-to-LDS kernels and split-K, and a grid that
     // fills the chip only once is as slow as its longest tile: below 384 tiles of 256 x 256 (about 5000^2
     // outputs) the general path is faster (measured at 4096: 104-118 us general, 151-191 us with the hint on
@@ -295,7 +367,6 @@ bool conv_is_plain_gemm(const ConvShape &s)
     return s.kernel_h == 1 && s.kernel_w == 1 && s.pad_h == 0 && s.pad_w == 0 && s.stride_h == 1 && s.stride_w == 1;
 }
 
-size_t round_up_256(size_t v) { return (v + 255) / 256 * 256; }
 
 mg_status run_im2col(int dtype, const ConvShape &s, const void *im, void *col, void *stream)
 {
@@ -685,6 +756,8 @@ size_t mg_gemm_workspace_bytes(int dtype, int layout, int ta, int tb, int64_t m,
     // scalars do not change the need except through the scale-only path, which needs none
     Problem p = canonical(dtype, layout, ta, tb, m, n, k, 1.f, nullptr, lda, nullptr, ldb, 1.f, nullptr, ldc,
                           nullptr, 0, nullptr);
+    IndirectPlan plan;
+    if (indirect_plan(p, false, &plan)) return plan.total();      // (the padded problem itself never splits K: it is large)
     int32_t kernel = -1, split = 1;
     if (choose(p, 256, ~size_t(0), &kernel, &split) != MG_OK) return 0;
     return table()[kernel].workspace(p, split);

@@ -1,4 +1,6 @@
-// Support kernels of the GEMM-derived level-3 routines SYMM, SYRK and TRMM.  The paper serves its
+// Support kernels: the pre- and post-processing copies of the indirect GEMM (the paper's Section 3.2: copy and pad
+// the operands so that the main kernel's assumptions hold, O(n^2) work next to O(n^3)), and the kernels of
+// the GEMM-derived level-3 routines SYMM, SYRK and TRMM.  The paper serves its
 // other level-3 routines with the gemm kernel family plus support kernels that copy or pad
 // matrices (Section 3.1); here a symmetric or triangular operand is first written out as a general
 // dense matrix, after which the product is an ordinary GEMM, and SYRK's untouched triangle of C is
@@ -155,6 +157,58 @@ __global__ __launch_bounds__(256) void copy_triangle_kernel(int n, const U *__re
     }
 }
 
+// dst (minor_p x major_p, leading dimension ldd, 16-byte aligned columns) <- src (minor x major, leading dimension
+// lds, any element alignment) with zeros beyond src: the pre-processing step of the indirect GEMM
+template <typename U, int V>
+__global__ __launch_bounds__(256) void pad_matrix_kernel(int minor, int major, const U *__restrict__ src, int64_t lds,
+                                                         U *__restrict__ dst, int64_t ldd, int minor_p, int major_p)
+{
+    using P = Pack<U, V>;
+    struct __attribute__((packed, aligned(sizeof(U)))) Loose { U v[V]; };
+    const int i = (blockIdx.x * 256 + threadIdx.x) * V;
+    if (i >= minor_p) return;
+#pragma unroll 2
+    for (int j = blockIdx.y; j < major_p; j += gridDim.y) {
+        P out;
+        if (i + V <= minor && j < major) {
+            // one 16-byte load at element alignment (the memory pipeline splits it as needed)
+            const Loose in = *reinterpret_cast<const Loose *>(src + i + j * lds);
+#pragma unroll
+            for (int e = 0; e < V; ++e) out.v[e] = in.v[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < V; ++e) out.v[e] = (i + e < minor && j < major) ? src[i + e + j * lds] : static_cast<U>(0);
+        }
+        *reinterpret_cast<P *>(dst + i + j * ldd) = out;
+    }
+}
+
+// dst (minor x major, leading dimension ldd, any element alignment) <- the leading part of src (leading dimension
+// lds, 16-byte aligned columns): the post-processing step of the indirect GEMM
+template <typename U, int V>
+__global__ __launch_bounds__(256) void unpad_matrix_kernel(int minor, int major, const U *__restrict__ src, int64_t lds,
+                                                           U *__restrict__ dst, int64_t ldd)
+{
+    using P = Pack<U, V>;
+    struct __attribute__((packed, aligned(sizeof(U)))) Loose { U v[V]; };
+    const int i = (blockIdx.x * 256 + threadIdx.x) * V;
+    if (i >= minor) return;
+#pragma unroll 2
+    for (int j = blockIdx.y; j < major; j += gridDim.y) {
+        const P in = *reinterpret_cast<const P *>(src + i + j * lds);
+        if (i + V <= minor) {
+            Loose out;
+#pragma unroll
+            for (int e = 0; e < V; ++e) out.v[e] = in.v[e];
+            *reinterpret_cast<Loose *>(dst + i + j * ldd) = out;
+        } else {
+#pragma unroll
+            for (int e = 0; e < V; ++e)
+                if (i + e < minor) dst[i + e + j * ldd] = in.v[e];
+        }
+    }
+}
+
 dim3 column_grid(int64_t minor, int64_t major, int v)
 {
     const int64_t rows = major < kColumnsPerLaunchRow ? major : kColumnsPerLaunchRow;
@@ -243,6 +297,24 @@ hipError_t launch_copy_matrix(int dtype, int64_t minor, int64_t major, const voi
         MG_LAUNCH_COLUMNWISE(copy_matrix_kernel, uint16_t, uint16_t, minor, major, aligned, static_cast<int>(minor),
                              static_cast<int>(major), s, lds, d, ldd);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_pad_matrix(int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
+                             int64_t minor_p, int64_t major_p, hipStream_t stream)
+{
+    hipLaunchKernelGGL((pad_matrix_kernel<uint16_t, 8>), column_grid(minor_p, major_p, 8), dim3(256), 0, stream,
+                       static_cast<int>(minor), static_cast<int>(major), static_cast<const uint16_t *>(src), lds,
+                       static_cast<uint16_t *>(dst), ldd, static_cast<int>(minor_p), static_cast<int>(major_p));
+    return hipGetLastError();
+}
+
+hipError_t launch_unpad_matrix(int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
+                               hipStream_t stream)
+{
+    hipLaunchKernelGGL((unpad_matrix_kernel<uint16_t, 8>), column_grid(minor, major, 8), dim3(256), 0, stream,
+                       static_cast<int>(minor), static_cast<int>(major), static_cast<const uint16_t *>(src), lds,
+                       static_cast<uint16_t *>(dst), ldd);
     return hipGetLastError();
 }
 

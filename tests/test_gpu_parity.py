@@ -493,3 +493,43 @@ def test_calls_can_be_captured_in_a_hip_graph(G, oracle):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(C, eager_c) and torch.equal(t["C"], eager_b)
+
+
+# ------------------------------------------------------------------ indirect route (padded copies) for ragged FP16
+
+@pytest.mark.parametrize("ta,tb", [(N, N), (T, N), (N, T), (T, T)])
+def test_indirect_route_for_ragged_half_problems(G, oracle, ta, tb):
+    """large FP16 problems that are ragged or have odd leading dimensions run on zero-padded aligned copies in the
+    workspace (the paper's Section 3.2 route): checked against the oracle, bit-exact on integers, nothing outside C
+    written; without workspace, or with too little, the direct route runs and gives the same result"""
+    import torch
+    for (m, n, k), layout, beta, integer in (((1025, 2060, 1100), C, 0.0, True), ((1025, 2060, 1100), C, 0.5, False),
+                                             ((1100, 2049, 1000), R, 1.0, True), ((2048, 1024, 1088), C, 0.25, False)):
+        # the last shape is whole tiles with odd leading dimensions: only the alignment breaks the fast path
+        lds = {}
+        if (m, n, k) == (2048, 1024, 1088):
+            lds = dict(lda=W.tight_ld(layout, ta, m, k) + 1, ldb=W.tight_ld(layout, tb, k, n) + 1,
+                       ldc=W.tight_ld(layout, N, m, n) + 1)
+        case = W.hgemm_case(m, n, k, case=41, layout=layout, ta=ta, tb=tb, alpha=1.0, beta=beta, integer=integer, **lds)
+        need = G.mg_gemm_workspace_bytes(G.MG_F16, case.layout, case.ta, case.tb, m, n, k, case.lda, case.ldb, case.ldc)
+        assert need >= 2 * (m * k + k * n + m * n), "the query must ask for room for the padded copies"
+        announce(case.name, "indirect", layout, ta, tb)
+        H.check_case(case, oracle)                                  # workspace from the query: indirect route
+        _, padded = H.run_gpu(case)
+        for label, ws in (("no workspace", None), ("workspace too small for the copies", torch.empty(need - 256, dtype=torch.uint8, device="cuda"))):
+            announce(case.name, label)
+            st, direct = H.run_gpu(case, workspace=ws)
+            assert st == 0
+            H.assert_padding_untouched(case, direct)
+            if integer:
+                assert np.array_equal(H.bits(direct), H.bits(padded))
+            else:
+                live = ~W.padding_mask(case.layout, m, n, case.ldc, case.C.size)
+                a, b = direct[live].astype(np.float64), padded[live].astype(np.float64)
+                assert np.max(np.abs(a - b)) <= 4e-3 * np.max(np.abs(b)), "the two routes differ by more than rounding"
+
+
+def test_aligned_whole_tile_problems_do_not_ask_for_copies(G):
+    assert G.mg_gemm_workspace_bytes(G.MG_F16, C, N, N, 4096, 4096, 4096, 4096, 4096, 4096) == 0
+    assert G.mg_gemm_workspace_bytes(G.MG_F32, C, N, N, 4097, 4097, 4097, 4097, 4097, 4097) == 0      # FP32 stays direct
+    assert G.mg_gemm_workspace_bytes(G.MG_F16, C, N, N, 300, 300, 300, 300, 300, 300) == 0            # too small to pay
