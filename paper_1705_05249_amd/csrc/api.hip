@@ -33,8 +33,6 @@ const std::vector<KernelEntry> &table()
 bool valid_trans(int t) { return t == MG_NO_TRANS || t == MG_TRANS || t == MG_CONJ_TRANS; }
 
 // Checks everything that does not need the pointers, in status-code order.
-constexpr int64_t kShapeHintMinTiles = 384;
-
 mg_status check_shape(int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, int64_t lda, int64_t ldb,
                       int64_t ldc)
 {
@@ -192,13 +190,6 @@ mg_status run_canonical(Problem p)
     if (indirect_plan(p, true, &plan) && p.workspace != nullptr && pointer_alignment(p.workspace) >= 256 &&
         p.workspace_bytes >= plan.total())
         return run_indirect(p, plan);
-    // A shape hint halves the tile work but rules out the direct-to-LDS kernels and split-K, and a grid that
-    // fills the chip only once is as slow as its longest tile: below 384 tiles of 256 x 256 (about 5000^2
-    // outputs) the general path is faster (measured at 4096: 104-118 us general, 151-191 us with the hint on
-    // 128 x 128 tiles).  A forced configuration keeps the hint: the caller chose the kernel.
-    if (p.shape != MG_SHAPE_GENERAL && g_override_kernel[p.dtype] < 0 &&
-        ceil_div(p.m, 256) * ceil_div(p.n, 256) < (kShapeHintMinTiles))
-        p.shape = MG_SHAPE_GENERAL;
     int32_t kernel = -1, split = 1;
     const bool ws_usable = p.workspace != nullptr && pointer_alignment(p.workspace) >= 256;
     const mg_status s = choose(p, problem_alignment(p), ws_usable ? p.workspace_bytes : 0, &kernel, &split);

@@ -153,9 +153,8 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 const bool last = i == count - 1;
                 int64_t blocks = ceil_div(p.m, tiles[i].bm) * ceil_div(p.n, tiles[i].bn);
                 double k_each = static_cast<double>(p.k);
-                // a shape hint leaves about half of the tile work; the smallest tile may split K
-                if (p.shape != MG_SHAPE_GENERAL) blocks = (blocks + 1) / 2;
-                else if (last) {
+                // the smallest tile may split K (never with a shape hint)
+                if (last && p.shape == MG_SHAPE_GENERAL) {
                     const int slices = pick_split(blocks, ceil_div(p.k, tiles[i].bk));
                     if (static_cast<size_t>(slices) * p.m * p.n * sizeof(float) <= workspace_bytes) {
                         blocks *= slices;
@@ -200,9 +199,18 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                     }
                     time = rounds * tiles[i].resident * tile_flops / (tiles[i].ceiling * order);
                 }
+                // unequal tiles (shape hint) balance only when a compute unit gets several: FP32 at 4096 runs the hinted
+                // 256 x 256 grid, one tile per compute unit, as slowly as the general problem
+                if (f32 && p.shape != MG_SHAPE_GENERAL && tiles[i].resident == 1) time *= 1.3;
                 if (best < 0 || time < best_time) { best = i; best_time = time; }
             }
             if (best < 0) break;
+            // A shape hint (about half of the tile work, unequal tiles) is ranked like the general problem, with one
+            // measured exception: when the 256 x 256 direct-to-LDS grid leaves compute units idle anyway, the
+            // 128 x 128 tiles balance the unequal work better (3072: TRMM 59 against 77 us, SYRK 58 against 76)
+            if (!f32 && p.shape != MG_SHAPE_GENERAL && best == 0 && !tried[2] &&
+                ceil_div(p.m, 256) * ceil_div(p.n, 256) <= (kComputeUnits * 3) / 4)
+                best = 2;
             tried[best] = true;
             const TileChoice &tc = tiles[best];
             const int64_t blocks = ceil_div(p.m, tc.bm) * ceil_div(p.n, tc.bn);

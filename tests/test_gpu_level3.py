@@ -148,9 +148,9 @@ def test_benchmark_size_on_sampled_outputs(level3_oracle):
 
 
 def _with_forced_tile_kernel(case, level3_oracle, tag=None, suffix="_edge"):
-    """Runs the case with a forced macro-tile kernel (default: the bounds-checked 64 x 64 one): a forced
-    configuration keeps the shape hint (narrowed K ranges for TRMM, skipped tiles for SYRK) that small problems
-    otherwise drop.  The operand order the call ends up with decides which of the four kernels is legal."""
+    """Runs the case with a forced macro-tile kernel (default: the bounds-checked 64 x 64 one), so that the shape
+    hint (narrowed K ranges for TRMM, skipped tiles for SYRK) is exercised in a chosen kernel family on a problem of
+    several tiles.  The operand order the call ends up with decides which of the four kernels is legal."""
     tag = tag or ("smfma_64x64x32_w2x2" if case.dtype == "f32" else "hmfma_64x64x64_w2x2")
     try:
         for contig in ("mk", "kk", "mn", "kn"):
@@ -197,8 +197,8 @@ def test_syrk_hint_in_the_direct_to_lds_kernel(level3_oracle, layout, uplo, tran
 @pytest.mark.parametrize("dtype,layout,side,uplo,trans", [("f16", C, LEFT, LO, N), ("f32", C, RIGHT, UP, N),
                                                           ("f16", R, LEFT, UP, T), ("f32", R, RIGHT, LO, T)])
 def test_large_trmm_on_sampled_columns(level3_oracle, dtype, layout, side, uplo, trans):
-    """large enough (6144^2 outputs) that the library keeps the shape hint by itself; 8 sampled columns (or, for
-    a product from the right, rows) of B are independent problems the oracle solves in full"""
+    """many tiles of unequal work under automatic selection; 8 sampled columns (or, for a product from the right,
+    rows) of B are independent problems the oracle solves in full"""
     n = 6144
     case = W.level3_case("trmm", dtype, layout, n, n, side=side, uplo=uplo, trans=trans, alpha=1.0, case=23)
     _, out = H.run_level3(case)
