@@ -145,64 +145,79 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
         const TileChoice *tiles = f32 ? f32_tiles : f16_tiles;
         const int count = f32 ? 5 : 8;
         bool tried[8] = {false, false, false, false, false, false, false, false};
+        // estimated time (in 1e-6 us) of tile i with the sum cut into `slices`
+        auto estimate = [&](int i, int slices) {
+            const int64_t blocks = ceil_div(p.m, tiles[i].bm) * ceil_div(p.n, tiles[i].bn) * slices;
+            const double tile_flops = 2.0 * tiles[i].bm * tiles[i].bn * static_cast<double>(p.k) / slices;
+            const int64_t full = static_cast<int64_t>(kComputeUnits) * tiles[i].resident;   // work-groups the chip holds
+            double order = 1.0;
+            if (!f32 && tiles[i].tag[1] == 'm') order = staged_f16(tiles[i]);
+            // ragged or unaligned FP16 problems run the bounds-checked flavour, which costs the smaller tiles more
+            // (rates against the whole-tile flavour: 0.75 for 256 x 256 and 256 x 128, about 0.5 for 128 x 128
+            // and below; FP32 loses about 0.78 on every tile, which does not change the ranking)
+            if (!f32 && (p.m % tiles[i].bm || p.n % tiles[i].bn || p.k % tiles[i].bk))
+                order *= tiles[i].bm * tiles[i].bn < 256 * 128 ? 0.6 : 0.7;
+            double time;
+            if (blocks < full) {
+                // the chip is not full: ceil(blocks / 256) work-groups share a compute unit
+                const int64_t per_unit = ceil_div(blocks, kComputeUnits);
+                double rate = tiles[i].per_group * static_cast<double>(per_unit);
+                if (rate > tiles[i].ceiling) rate = tiles[i].ceiling;
+                // the fastest kernel runs against the power limit: with fewer busy compute units each one
+                // clocks higher (144 tiles of 256 x 256 at 3072^3: 64 us measured against 79 us at the
+                // full-chip rate); the smaller tiles showed no such gain
+                if (!f32 && i == 0 && blocks < kComputeUnits) {
+                    const double boost = sqrt(static_cast<double>(kComputeUnits) / static_cast<double>(blocks));
+                    rate *= boost < 1.25 ? boost : 1.25;
+                }
+                time = static_cast<double>(per_unit) * tile_flops / (rate * order);
+            } else {
+                // rounds of `full` work-groups; one work-group per compute unit quantises sharply (576 tiles
+                // take three rounds), and so do the first two rounds of any kernel; with several resident
+                // work-groups later rounds blur (measured: the fractional round costs 0.1-0.36 more).  The
+                // fastest FP16 kernel is the exception: its partial last round runs on fewer compute units at
+                // a higher clock (400 tiles take 1.7 rounds' time, 576 tiles 2.5)
+                const double x = static_cast<double>(blocks) / static_cast<double>(full);
+                const double whole = floor(x);
+                double rounds = x;
+                if (x > whole) {
+                    if (!f32 && i == 0) rounds = x + 0.25;
+                    else rounds = tiles[i].resident == 1 || x <= 2.0 ? whole + 1.0 : x + 0.25;
+                }
+                time = rounds * tiles[i].resident * tile_flops / (tiles[i].ceiling * order);
+            }
+            // unequal tiles (shape hint) balance only when a compute unit gets several: FP32 at 4096 runs the hinted
+            // 256 x 256 grid, one tile per compute unit, as slowly as the general problem
+            if (f32 && p.shape != MG_SHAPE_GENERAL && tiles[i].resident == 1) time *= 1.3;
+            // split-K: the partial sums are written and read back (8 bytes per slice and output at ~4 TB/s) by
+            // a second launch (~4 us)
+            if (slices > 1) time += 1.0e6 * (4.0 + (8.0 * slices + 4.0) * static_cast<double>(p.m) * static_cast<double>(p.n) / 4.0e6);
+            return time;
+        };
         for (int attempt = 0; attempt < count; ++attempt) {
-            int best = -1;
+            int best = -1, best_slices = 1;
             double best_time = 0.0;
             for (int i = 0; i < count; ++i) {
                 if (tried[i]) continue;
                 const bool last = i == count - 1;
-                int64_t blocks = ceil_div(p.m, tiles[i].bm) * ceil_div(p.n, tiles[i].bn);
-                double k_each = static_cast<double>(p.k);
-                // the smallest tile may split K (never with a shape hint)
-                if (last && p.shape == MG_SHAPE_GENERAL) {
-                    const int slices = pick_split(blocks, ceil_div(p.k, tiles[i].bk));
-                    if (static_cast<size_t>(slices) * p.m * p.n * sizeof(float) <= workspace_bytes) {
-                        blocks *= slices;
-                        k_each /= slices;
-                    }
+                const int64_t ktiles = ceil_div(p.k, tiles[i].bk);
+                const int64_t blocks = ceil_div(p.m, tiles[i].bm) * ceil_div(p.n, tiles[i].bn);
+                // slices tried: none; for the smallest tile the factor of the sweep's rule; for grids that do not
+                // fill the chip powers of two that leave every slice at least four K-tiles (never with a shape hint)
+                int options[6] = {1, 0, 0, 0, 0, 0};
+                int n_options = 1;
+                if (p.shape == MG_SHAPE_GENERAL) {
+                    if (last) options[n_options++] = pick_split(blocks, ktiles);
+                    if (blocks < 2 * kComputeUnits)
+                        for (int sl = 2; sl <= 16 && ktiles / sl >= 4; sl *= 2) options[n_options++] = sl;
                 }
-                const double tile_flops = 2.0 * tiles[i].bm * tiles[i].bn * k_each;
-                const int64_t full = static_cast<int64_t>(kComputeUnits) * tiles[i].resident;   // work-groups the chip holds
-                double order = 1.0;
-                if (!f32 && tiles[i].tag[1] == 'm') order = staged_f16(tiles[i]);
-                // ragged or unaligned FP16 problems run the bounds-checked flavour, which costs the smaller tiles more
-                // (rates against the whole-tile flavour: 0.75 for 256 x 256 and 256 x 128, about 0.5 for 128 x 128
-                // and below; FP32 loses about 0.78 on every tile, which does not change the ranking)
-                if (!f32 && (p.m % tiles[i].bm || p.n % tiles[i].bn || p.k % tiles[i].bk))
-                    order *= tiles[i].bm * tiles[i].bn < 256 * 128 ? 0.6 : 0.7;
-                double time;
-                if (blocks < full) {
-                    // the chip is not full: ceil(blocks / 256) work-groups share a compute unit
-                    const int64_t per_unit = ceil_div(blocks, kComputeUnits);
-                    double rate = tiles[i].per_group * static_cast<double>(per_unit);
-                    if (rate > tiles[i].ceiling) rate = tiles[i].ceiling;
-                    // the fastest kernel runs against the power limit: with fewer busy compute units each one
-                    // clocks higher (144 tiles of 256 x 256 at 3072^3: 64 us measured against 79 us at the
-                    // full-chip rate); the smaller tiles showed no such gain
-                    if (!f32 && i == 0 && blocks < kComputeUnits) {
-                        const double boost = sqrt(static_cast<double>(kComputeUnits) / static_cast<double>(blocks));
-                        rate *= boost < 1.25 ? boost : 1.25;
-                    }
-                    time = static_cast<double>(per_unit) * tile_flops / (rate * order);
-                } else {
-                    // rounds of `full` work-groups; one work-group per compute unit quantises sharply (576 tiles
-                    // take three rounds), and so do the first two rounds of any kernel; with several resident
-                    // work-groups later rounds blur (measured: the fractional round costs 0.1-0.36 more).  The
-                    // fastest FP16 kernel is the exception: its partial last round runs on fewer compute units at
-                    // a higher clock (400 tiles take 1.7 rounds' time, 576 tiles 2.5)
-                    const double x = static_cast<double>(blocks) / static_cast<double>(full);
-                    const double whole = floor(x);
-                    double rounds = x;
-                    if (x > whole) {
-                        if (!f32 && i == 0) rounds = x + 0.25;
-                        else rounds = tiles[i].resident == 1 || x <= 2.0 ? whole + 1.0 : x + 0.25;
-                    }
-                    time = rounds * tiles[i].resident * tile_flops / (tiles[i].ceiling * order);
+                for (int o = 0; o < n_options; ++o) {
+                    const int sl = options[o];
+                    if (sl < 1 || (o > 0 && sl == 1)) continue;
+                    if (sl > 1 && static_cast<size_t>(sl) * p.m * p.n * sizeof(float) > workspace_bytes) continue;
+                    const double time = estimate(i, sl);
+                    if (best < 0 || time < best_time) { best = i; best_slices = sl; best_time = time; }
                 }
-                // unequal tiles (shape hint) balance only when a compute unit gets several: FP32 at 4096 runs the hinted
-                // 256 x 256 grid, one tile per compute unit, as slowly as the general problem
-                if (f32 && p.shape != MG_SHAPE_GENERAL && tiles[i].resident == 1) time *= 1.3;
-                if (best < 0 || time < best_time) { best = i; best_time = time; }
             }
             if (best < 0) break;
             // A shape hint (about half of the tile work, unequal tiles) is ranked like the general problem, with one
@@ -213,11 +228,7 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 best = 2;
             tried[best] = true;
             const TileChoice &tc = tiles[best];
-            const int64_t blocks = ceil_div(p.m, tc.bm) * ceil_div(p.n, tc.bn);
-            const int64_t ktiles = ceil_div(p.k, tc.bk);
-            int want = best == count - 1 && p.shape == MG_SHAPE_GENERAL ? pick_split(blocks, ktiles) : 1;
-            // split-K needs the caller's workspace: without enough of it, run unsplit
-            while (want > 1 && static_cast<size_t>(want) * p.m * p.n * sizeof(float) > workspace_bytes) want = 1;
+            const int want = best_slices;
             // a factor whose last slice would be empty is illegal: take the next smaller one
             for (int w = want; w >= 1; --w)
                 if (try_mfma(table, p, alignment, tc.tag, w, kernel, split)) return;
