@@ -533,3 +533,28 @@ def test_aligned_whole_tile_problems_do_not_ask_for_copies(G):
     assert G.mg_gemm_workspace_bytes(G.MG_F16, C, N, N, 4096, 4096, 4096, 4096, 4096, 4096) == 0
     assert G.mg_gemm_workspace_bytes(G.MG_F32, C, N, N, 4097, 4097, 4097, 4097, 4097, 4097) == 0      # FP32 stays direct
     assert G.mg_gemm_workspace_bytes(G.MG_F16, C, N, N, 300, 300, 300, 300, 300, 300) == 0            # too small to pay
+
+
+# ------------------------------------------------------------------ seeded random shapes through automatic selection
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_random_shapes_on_sampled_entries(G, oracle, dtype):
+    """two dozen seeded shapes (skinny, ragged, long and short K, padded and odd leading dimensions, every
+    layout and operand order) through automatic selection with the workspace the query asks for: whatever
+    tile, split factor or route is chosen, sampled entries must match the oracle and nothing outside C change"""
+    g = np.random.default_rng(20251 if dtype == "f32" else 20252)
+    for index in range(24):
+        m, n = (int(g.choice([96, 129, 256, 700, 1024, 1500, 2049, 3000])) for _ in range(2))
+        k = int(g.choice([64, 100, 512, 1000, 2304, 4096]))
+        layout = int(g.choice([C, R]))
+        ta, tb = int(g.choice([N, T])), int(g.choice([N, T]))
+        beta = float(g.choice([0.0, 1.0, -0.5]))
+        extra = int(g.choice([0, 0, 1, 8]))
+        opA = W.uniform(g, (m, k)) if dtype == "f32" else (g.normal(0.0, k ** -0.5, size=(m, k))).astype(np.float16)
+        opB = W.uniform(g, (k, n)) if dtype == "f32" else (g.normal(0.0, k ** -0.5, size=(k, n))).astype(np.float16)
+        Cm = W.uniform(g, (m, n)) if dtype == "f32" else (g.normal(0.0, 1.0, size=(m, n))).astype(np.float16)
+        case = W.make_case(f"rand{index}_{m}x{n}x{k}", dtype, layout, ta, tb, opA, opB, Cm, 1.0, beta,
+                           W.tight_ld(layout, ta, m, k) + extra, W.tight_ld(layout, tb, k, n) + extra,
+                           W.tight_ld(layout, N, m, n) + extra)
+        announce(case.name, layout, ta, tb, "beta", beta, "ld +", extra)
+        H.check_case(case, oracle, sampled=True, seed=index)
