@@ -105,8 +105,10 @@ typedef struct mg_config {
 
 /* ---- GEMM (paper Section 1 / Section 3.1) --------------------------------------------
  * FP32 storage.  alpha, beta: host scalars.  A, B (read) and C (read if beta != 0, written):
- * device pointers, any 4-byte alignment.  workspace may be NULL when
- * mg_gemm_workspace_bytes() for the same arguments returns 0. */
+ * device pointers, any 4-byte alignment.  workspace may always be NULL; with
+ * mg_gemm_workspace_bytes() of workspace the call runs its preferred route (split-K partial sums,
+ * or the padded copies of the indirect route described under mg_hgemm, which FP32 takes for large
+ * problems that are not whole tiles). */
 mg_status mg_sgemm(int layout, int trans_a, int trans_b, int64_t m, int64_t n, int64_t k,
                    float alpha, const float *A, int64_t lda, const float *B, int64_t ldb,
                    float beta, float *C, int64_t ldc,

@@ -119,10 +119,10 @@ size_t round_up_256(size_t v) { return (v + 255) / 256 * 256; }
 
 // Indirect GEMM, the paper's Section 3.2 route for problems that break the fast kernel's assumptions: copy the
 // operands into zero-padded, aligned buffers whose sizes are whole tiles, run the fast kernel there, copy the
-// result back.  Here only FP16 needs it: ragged or unaligned FP16 problems otherwise run the bounds-checked
+// result back.  FP16 needs it most: ragged or unaligned FP16 problems otherwise run the bounds-checked
 // register-staged kernels at 0.2-0.6 of the direct-to-LDS rate (4097^3: 525 us; an odd leading dimension puts
-// every other row at 2-byte alignment), while the copies are O(n^2) (~30 us at 4097^3).  FP32 loses only ~20 % in
-// its bounds-checked flavour and has no direct-to-LDS kernel, so it stays direct.  The padded buffers live in
+// every other row at 2-byte alignment), while the copies are O(n^2) (~30 us at 4097^3).  FP32 loses ~20 % in
+// its bounds-checked flavour plus what ragged sizes lose to tile quantisation: large problems gain.  The padded buffers live in
 // the caller's workspace; without enough of it the direct route runs.  One rounding as always: the fast
 // kernel applies alpha and beta in the padded C, whose leading part is then copied out bit for bit.
 struct IndirectPlan {
@@ -133,23 +133,35 @@ struct IndirectPlan {
 
 bool indirect_plan(const Problem &p, bool pointers_known, IndirectPlan *plan)
 {
-    if (p.dtype != MG_F16 || p.shape != MG_SHAPE_GENERAL || p.alpha == 0.f || p.k == 0) return false;
-    if (g_override_kernel[MG_F16] >= 0) return false;                  // a forced kernel gets the problem as it is
-    // four extra launches and ~33 us of copies at 4096^2: measured a loss at 1000^3 (28 against 22 us), a gain at
-    // 2049^3 (74 against 96 us)
-    if (p.m < 1024 || p.n < 1024 || p.k < 256) return false;
-    if (static_cast<double>(p.m) * static_cast<double>(p.n) * static_cast<double>(p.k) < 2.0e9) return false;
-    const bool whole = p.m % 128 == 0 && p.n % 128 == 0 && p.k % 64 == 0;
-    const bool aligned = p.lda % 8 == 0 && p.ldb % 8 == 0 &&
-                         (!pointers_known || (pointer_alignment(p.A) >= 16 && pointer_alignment(p.B) >= 16));
-    if (whole && aligned) return false;                                // the fast kernels take it directly
-    const int64_t tile = p.m >= 2048 && p.n >= 2048 ? 256 : 128;
+    if (p.shape != MG_SHAPE_GENERAL || p.alpha == 0.f || p.k == 0) return false;
+    if (g_override_kernel[p.dtype] >= 0) return false;                 // a forced kernel gets the problem as it is
+    const double work = static_cast<double>(p.m) * static_cast<double>(p.n) * static_cast<double>(p.k);
+    const size_t elem = p.elem();
+    int64_t tile, ktile;
+    if (p.dtype == MG_F16) {
+        // four extra launches and ~33 us of copies at 4096^2: measured a loss at 1000^3 (28 against 22 us), a gain
+        // at 2049^3 (56 against 96 us)
+        if (p.m < 1024 || p.n < 1024 || p.k < 256 || work < 2.0e9) return false;
+        const bool whole = p.m % 128 == 0 && p.n % 128 == 0 && p.k % 64 == 0;
+        const bool aligned = p.lda % 8 == 0 && p.ldb % 8 == 0 &&
+                             (!pointers_known || (pointer_alignment(p.A) >= 16 && pointer_alignment(p.B) >= 16));
+        if (whole && aligned) return false;                            // the fast kernels take it directly
+        tile = p.m >= 2048 && p.n >= 2048 ? 256 : 128;
+        ktile = 64;
+    } else {
+        // FP32: the bounds-checked flavour runs at ~0.78 of the whole-tile rate and ragged sizes quantise badly
+        // on the tiles that are left; the copies cost ~70 us at 4096^2, so only large problems gain
+        if (p.m < 1536 || p.n < 1536 || p.k < 512 || work < 8.0e9) return false;
+        if (p.m % 64 == 0 && p.n % 64 == 0 && p.k % 32 == 0) return false;     // whole 64 x 64 tiles: a fast kernel is legal
+        tile = 128;
+        ktile = 32;
+    }
     plan->mp = ceil_div(p.m, tile) * tile;
     plan->np = ceil_div(p.n, tile) * tile;
-    plan->kp = ceil_div(p.k, 64) * 64;
-    plan->a_bytes = round_up_256(static_cast<size_t>(plan->mp) * plan->kp * 2);
-    plan->b_bytes = round_up_256(static_cast<size_t>(plan->kp) * plan->np * 2);
-    plan->c_bytes = round_up_256(static_cast<size_t>(plan->mp) * plan->np * 2);
+    plan->kp = ceil_div(p.k, ktile) * ktile;
+    plan->a_bytes = round_up_256(static_cast<size_t>(plan->mp) * plan->kp * elem);
+    plan->b_bytes = round_up_256(static_cast<size_t>(plan->kp) * plan->np * elem);
+    plan->c_bytes = round_up_256(static_cast<size_t>(plan->mp) * plan->np * elem);
     return true;
 }
 
@@ -165,10 +177,10 @@ mg_status run_indirect(const Problem &p, const IndirectPlan &plan)
     const int64_t a_minor_p = p.a_trans ? plan.kp : plan.mp, a_major_p = p.a_trans ? plan.mp : plan.kp;
     const int64_t b_minor = p.b_trans ? p.n : p.k, b_major = p.b_trans ? p.k : p.n;
     const int64_t b_minor_p = p.b_trans ? plan.np : plan.kp, b_major_p = p.b_trans ? plan.kp : plan.np;
-    if (launch_pad_matrix(a_minor, a_major, p.A, p.lda, ap, a_minor_p, a_minor_p, a_major_p, st) != hipSuccess) return MG_ERR_LAUNCH;
-    if (launch_pad_matrix(b_minor, b_major, p.B, p.ldb, bp, b_minor_p, b_minor_p, b_major_p, st) != hipSuccess) return MG_ERR_LAUNCH;
+    if (launch_pad_matrix(p.dtype, a_minor, a_major, p.A, p.lda, ap, a_minor_p, a_minor_p, a_major_p, st) != hipSuccess) return MG_ERR_LAUNCH;
+    if (launch_pad_matrix(p.dtype, b_minor, b_major, p.B, p.ldb, bp, b_minor_p, b_minor_p, b_major_p, st) != hipSuccess) return MG_ERR_LAUNCH;
     if (p.beta != 0.f &&
-        launch_pad_matrix(p.m, p.n, p.C, p.ldc, cp, plan.mp, plan.mp, plan.np, st) != hipSuccess)
+        launch_pad_matrix(p.dtype, p.m, p.n, p.C, p.ldc, cp, plan.mp, plan.mp, plan.np, st) != hipSuccess)
         return MG_ERR_LAUNCH;
     Problem q = p;
     q.m = plan.mp; q.n = plan.np; q.k = plan.kp;
@@ -180,7 +192,7 @@ mg_status run_indirect(const Problem &p, const IndirectPlan &plan)
     q.workspace_bytes = p.workspace_bytes > used ? p.workspace_bytes - used : 0;
     const mg_status s = run_canonical(q);
     if (s != MG_OK) return s;
-    return launch_unpad_matrix(p.m, p.n, cp, plan.mp, p.C, p.ldc, st) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
+    return launch_unpad_matrix(p.dtype, p.m, p.n, cp, plan.mp, p.C, p.ldc, st) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
 }
 
 // Selects and launches the configuration for a canonical problem with at least one output.

@@ -103,11 +103,11 @@ hipError_t launch_copy_matrix(int dtype, int64_t minor, int64_t major, const voi
 hipError_t launch_copy_triangle(int dtype, int64_t n, const void *src, int64_t lds, void *dst, int64_t ldd, bool lower,
                                 hipStream_t stream);
 
-// Indirect GEMM (FP16): zero-padded copy into 16-byte aligned columns of minor_p elements (a multiple of 8), and the
-// copy of the leading minor x major part back out.  Column-major view as above.
-hipError_t launch_pad_matrix(int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
+// Indirect GEMM: zero-padded copy into 16-byte aligned columns of minor_p elements (a multiple of 16 bytes), and the
+// copy of the leading minor x major part back out.  Column-major view as above; dtype: mg_dtype.
+hipError_t launch_pad_matrix(int dtype, int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
                              int64_t minor_p, int64_t major_p, hipStream_t stream);
-hipError_t launch_unpad_matrix(int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
+hipError_t launch_unpad_matrix(int dtype, int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
                                hipStream_t stream);
 
 // One compiled kernel (or kernel family instance) in the configuration table.

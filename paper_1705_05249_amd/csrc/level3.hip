@@ -300,21 +300,31 @@ hipError_t launch_copy_matrix(int dtype, int64_t minor, int64_t major, const voi
     return hipGetLastError();
 }
 
-hipError_t launch_pad_matrix(int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
+hipError_t launch_pad_matrix(int dtype, int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
                              int64_t minor_p, int64_t major_p, hipStream_t stream)
 {
-    hipLaunchKernelGGL((pad_matrix_kernel<uint16_t, 8>), column_grid(minor_p, major_p, 8), dim3(256), 0, stream,
-                       static_cast<int>(minor), static_cast<int>(major), static_cast<const uint16_t *>(src), lds,
-                       static_cast<uint16_t *>(dst), ldd, static_cast<int>(minor_p), static_cast<int>(major_p));
+    if (dtype == MG_F32)
+        hipLaunchKernelGGL((pad_matrix_kernel<uint32_t, 4>), column_grid(minor_p, major_p, 4), dim3(256), 0, stream,
+                           static_cast<int>(minor), static_cast<int>(major), static_cast<const uint32_t *>(src), lds,
+                           static_cast<uint32_t *>(dst), ldd, static_cast<int>(minor_p), static_cast<int>(major_p));
+    else
+        hipLaunchKernelGGL((pad_matrix_kernel<uint16_t, 8>), column_grid(minor_p, major_p, 8), dim3(256), 0, stream,
+                           static_cast<int>(minor), static_cast<int>(major), static_cast<const uint16_t *>(src), lds,
+                           static_cast<uint16_t *>(dst), ldd, static_cast<int>(minor_p), static_cast<int>(major_p));
     return hipGetLastError();
 }
 
-hipError_t launch_unpad_matrix(int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
+hipError_t launch_unpad_matrix(int dtype, int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
                                hipStream_t stream)
 {
-    hipLaunchKernelGGL((unpad_matrix_kernel<uint16_t, 8>), column_grid(minor, major, 8), dim3(256), 0, stream,
-                       static_cast<int>(minor), static_cast<int>(major), static_cast<const uint16_t *>(src), lds,
-                       static_cast<uint16_t *>(dst), ldd);
+    if (dtype == MG_F32)
+        hipLaunchKernelGGL((unpad_matrix_kernel<uint32_t, 4>), column_grid(minor, major, 4), dim3(256), 0, stream,
+                           static_cast<int>(minor), static_cast<int>(major), static_cast<const uint32_t *>(src), lds,
+                           static_cast<uint32_t *>(dst), ldd);
+    else
+        hipLaunchKernelGGL((unpad_matrix_kernel<uint16_t, 8>), column_grid(minor, major, 8), dim3(256), 0, stream,
+                           static_cast<int>(minor), static_cast<int>(major), static_cast<const uint16_t *>(src), lds,
+                           static_cast<uint16_t *>(dst), ldd);
     return hipGetLastError();
 }
 

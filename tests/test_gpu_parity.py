@@ -531,7 +531,7 @@ def test_indirect_route_for_ragged_half_problems(G, oracle, ta, tb):
 
 def test_aligned_whole_tile_problems_do_not_ask_for_copies(G):
     assert G.mg_gemm_workspace_bytes(G.MG_F16, C, N, N, 4096, 4096, 4096, 4096, 4096, 4096) == 0
-    assert G.mg_gemm_workspace_bytes(G.MG_F32, C, N, N, 4097, 4097, 4097, 4097, 4097, 4097) == 0      # FP32 stays direct
+    assert G.mg_gemm_workspace_bytes(G.MG_F32, C, N, N, 1000, 1000, 1000, 1000, 1000, 1000) == 0      # too small to pay
     assert G.mg_gemm_workspace_bytes(G.MG_F16, C, N, N, 300, 300, 300, 300, 300, 300) == 0            # too small to pay
 
 
@@ -558,3 +558,24 @@ def test_random_shapes_on_sampled_entries(G, oracle, dtype):
                            W.tight_ld(layout, N, m, n) + extra)
         announce(case.name, layout, ta, tb, "beta", beta, "ld +", extra)
         H.check_case(case, oracle, sampled=True, seed=index)
+
+
+@pytest.mark.parametrize("layout,ta,tb", [(C, N, N), (R, T, N), (C, N, T)])
+def test_indirect_route_for_large_ragged_single_problems(G, oracle, layout, ta, tb):
+    """FP32 takes the padded-copy route from about 2000^3 on when no whole-tile kernel is legal: sampled entries
+    against the oracle, padding of C untouched, and the same result (up to summation order) without workspace"""
+    m, n, k = 2049, 2050, 2001
+    g = np.random.default_rng(77)
+    case = W.make_case(f"s_{m}x{n}x{k}", "f32", layout, ta, tb, W.uniform(g, (m, k)), W.uniform(g, (k, n)),
+                       W.uniform(g, (m, n)), 1.0, 0.5, W.tight_ld(layout, ta, m, k) + 1, W.tight_ld(layout, tb, k, n) + 1,
+                       W.tight_ld(layout, N, m, n) + 1)
+    need = G.mg_gemm_workspace_bytes(G.MG_F32, layout, ta, tb, m, n, k, case.lda, case.ldb, case.ldc)
+    assert need >= 4 * (m * k + k * n + m * n)
+    H.check_case(case, oracle, sampled=True, seed=5)
+    _, padded = H.run_gpu(case)
+    st, direct = H.run_gpu(case, workspace=None)
+    assert st == 0
+    H.assert_padding_untouched(case, direct)
+    live = ~W.padding_mask(layout, m, n, case.ldc, case.C.size)
+    a, b = direct[live].astype(np.float64), padded[live].astype(np.float64)
+    assert np.max(np.abs(a - b)) <= 1e-4 * np.max(np.abs(b))
