@@ -22,6 +22,8 @@
  *     only enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = the default
  *     stream) and returns.  Scratch memory, when a configuration needs it, is the caller's
  *     `workspace` (device memory, 256-byte aligned, at least mg_gemm_workspace_bytes()).
+ *     A call may write any part of the workspace it is given and expects nothing in it; two
+ *     calls that can run at the same time (different streams) need different workspaces.
  *   - Arithmetic: products are accumulated in FP32 (also for FP16 storage); the result
  *     alpha*acc + beta*C_old is formed in FP32 and rounded once (round-to-nearest-even) to
  *     the storage type.  beta == 0 means C is not read (NaN/Inf in it do not propagate);
