@@ -110,14 +110,13 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
         }
     }
     if (p.m >= 16 && p.n >= 16) {
-        // The macro tile with the smallest estimated time.  A compute unit works through ceil(tiles / 256) tiles
-        // at a rate that grows with the number of its resident work-groups up to the kernel's own ceiling:
-        //     time ~ ceil(tiles / 256) * 2 BM BN k / min(ceiling, per_group * min(resident_max, ceil(tiles / 256)))
-        // Rates (Mflop/us per compute unit) are fitted to a scan of every tile over square problems from 1024 to
-        // 6144 in the four operand orders; partial tiles of ragged problems count as whole ones.  Short K
-        // (<= 8 K-tiles) goes to the smallest tile, whose many resident work-groups keep the C traffic in flight.
-        // (the direct-to-LDS kernels need whole tiles and 16-byte aligned operands; else they are illegal and the
-        // next best estimate is tried)
+        // The macro tile (and number of K slices) with the smallest estimated time, see `estimate` below: a chip
+        // that is not full runs ceil(tiles / 256) work-groups per compute unit at a rate that grows with them up to
+        // the kernel's ceiling; a full chip works through rounds of 256 x resident work-groups.  Rates (Mflop/us per
+        // compute unit: ceiling, per resident work-group) and the number of resident work-groups are fitted to a
+        // scan of every tile over square problems from 1024 to 6144 in the four operand orders; partial tiles of
+        // ragged problems count as whole ones.  The direct-to-LDS kernels need whole tiles and 16-byte aligned
+        // operands; where they are illegal the next best estimate is tried.
         static const TileChoice f16_tiles[] = {{"hdma16_256x256x64_w2x4", 256, 256, 64, 5.1f, 5.1f, 1},
                                                {"hdma16_256x128x64_w4x2", 256, 128, 64, 4.3f, 4.3f, 1},
                                                {"hdma16_128x128x64_w2x2", 128, 128, 64, 4.1f, 2.4f, 2},
