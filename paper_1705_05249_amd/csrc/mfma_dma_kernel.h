@@ -123,7 +123,7 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int FM = WTM / RB, FN = WTN / RB;
     constexpr int KSTEPS = BK / ((64 / RB) * 8);
-    static_assert(WTM % 64 == 0 && WTN % 64 == 0, "wavefront tile: an even number of 32-row fragments per side");
+    static_assert(WTM % (2 * RB) == 0 && WTN % (2 * RB) == 0, "wavefront tile: an even number of fragments per side");
     // the [k][row] layout XORs slot numbers up to 14 into a line of ROWS / 8 slots
     static_assert((A_KCONTIG || BM >= 128) && (B_KCONTIG || BN >= 128), "an operand that is not contiguous along k needs 128 rows");
     using LoadA = DmaLoader<BM, NT, A_KCONTIG>;

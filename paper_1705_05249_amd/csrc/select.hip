@@ -119,7 +119,7 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
         // operands; where they are illegal the next best estimate is tried.
         static const TileChoice f16_tiles[] = {{"hdma16_256x256x64_w2x4", 256, 256, 64, 5.1f, 5.1f, 1},
                                                {"hdma16_256x128x64_w4x2", 256, 128, 64, 4.3f, 4.3f, 1},
-                                               {"hdma16_128x128x64_w2x2", 128, 128, 64, 4.1f, 2.4f, 2},
+                                               {"hdma16_128x128x64_w2x4", 128, 128, 64, 4.3f, 2.6f, 2},
                                                {"hmfma_256x256x64_w2x2", 256, 256, 64, 4.5f, 4.5f, 1},
                                                {"hmfma_256x128x64_w2x2", 256, 128, 64, 3.8f, 3.8f, 1},
                                                {"hmfma_128x128x64_w2x2", 128, 128, 64, 3.3f, 1.8f, 2},
