@@ -50,6 +50,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 struct MfmaArgs {
     const void *A;
@@ -80,21 +81,22 @@ template <int N, typename F> __device__ inline void static_for(F &&f)
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-// ---- row i of a transposed CH x CH block -------------------------------------------------------
-// in[j] = CH consecutive row elements (m or n direction) for k = j; result = CH consecutive k for row i.
-template <int I> __device__ inline u32x4 transposed_row(const u32x4 *in, _Float16)
+// ---- row i of a transposed CH x KU block ---------------------------------------------------------
+// in[j] = CH consecutive row elements (m or n direction) for k = j < KU; result = KU consecutive k for row i
+// in the low KU * sizeof(T) bytes.
+template <int I, int KU> __device__ inline u32x4 transposed_row(const u32x4 *in, _Float16)
 {
     constexpr uint32_t sel = (I & 1) ? 0x07060302u : 0x05040100u;
-    u32x4 out;
+    u32x4 out{0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int d = 0; d < 4; ++d) out[d] = __builtin_amdgcn_perm(in[2 * d + 1][I >> 1], in[2 * d][I >> 1], sel);
+    for (int d = 0; d < KU / 2; ++d) out[d] = __builtin_amdgcn_perm(in[2 * d + 1][I >> 1], in[2 * d][I >> 1], sel);
     return out;
 }
-template <int I> __device__ inline u32x4 transposed_row(const u32x4 *in, float)
+template <int I, int KU> __device__ inline u32x4 transposed_row(const u32x4 *in, float)
 {
-    u32x4 out;
+    u32x4 out{0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int d = 0; d < 4; ++d) out[d] = in[d][I];
+    for (int d = 0; d < KU; ++d) out[d] = in[d][I];
     return out;
 }
 
@@ -128,8 +130,13 @@ template <typename T> __device__ inline u32x4 gather_chunk(const T *p, int valid
 
 // ---- one operand tile: global -> registers -> LDS ---------------------------------------------
 // The tile has ROWS rows (m or n index) and BK values of k.  Global element (row r, k index l) is at
-// X[l + r*ld] when KCONTIG, else at X[r + l*ld].  Each thread moves COUNT 16-byte pieces; piece Q can
-// be loaded and stored on its own so that the kernel can place every instruction in its pipeline.
+// X[l + r*ld] when KCONTIG, else at X[r + l*ld].  Each thread loads LOADS 16-byte pieces and makes STORES
+// LDS stores; every piece can be loaded and stored on its own so that the kernel can place every instruction
+// in its pipeline.
+// Transposing path (!KCONTIG): a unit is CH rows x KU values of k: KU loads of CH consecutive rows, turned in
+// registers into CH stores of KU consecutive k.  KU = CH (whole 16-byte LDS chunks) when the tile has a unit of
+// that size for every thread; smaller tiles cut the units along k (SPLIT parts, stores of 16/SPLIT bytes) so
+// that every thread of the work-group takes part: with half of the wavefronts idle the 64-row tiles lost 20 %.
 template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct TileLoader {
     static constexpr int CH = ElemTraits<T>::CH;
     static constexpr int CPR = BK / CH;                                // 16-byte chunks per LDS row
@@ -137,33 +144,55 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
     static constexpr int RCH = ROWS / CH;                               // row chunks per tile column
     static constexpr int CHUNKS = ROWS * CPR;
     static constexpr int BLOCKS = CHUNKS / CH;                         // CH x CH blocks (transposing path)
-    static constexpr int COUNT = KCONTIG ? (CHUNKS + NT - 1) / NT : ((BLOCKS + NT - 1) / NT) * CH;
-    static constexpr bool PARTIAL = KCONTIG ? (CHUNKS % NT != 0) : (BLOCKS % NT != 0);
+    static constexpr int SPLIT = (KCONTIG || BLOCKS >= NT) ? 1 : (NT / BLOCKS < 4 ? NT / BLOCKS : 4);
+    static constexpr int KU = CH / SPLIT;                               // k values per unit
+    static constexpr int UNITS = BLOCKS * SPLIT;
+    static constexpr int UPT = (UNITS + NT - 1) / NT;                   // units per thread
+    static constexpr int LOADS = KCONTIG ? (CHUNKS + NT - 1) / NT : UPT * KU;
+    static constexpr int STORES = KCONTIG ? LOADS : UPT * CH;
+    // the pipeline takes a loader's work in groups: GROUP_STORES stores (tile t+1), then GROUP_LOADS loads
+    // (tile t+2) into the registers those stores have freed; a transposing group is one unit
+    static constexpr int GROUP_LOADS = KCONTIG ? (LOADS % 4 == 0 ? 4 : (LOADS % 2 == 0 ? 2 : 1)) : KU;
+    static constexpr int GROUP_STORES = KCONTIG ? GROUP_LOADS : CH;
+    static constexpr bool PARTIAL = KCONTIG ? (CHUNKS % NT != 0) : (UNITS % NT != 0);
     static constexpr int LDS_BYTES = ROWS * RS;
     static_assert(CPR == 8 && ROWS % 8 == 0, "LDS rows are 128 bytes (eight swizzled 16-byte chunks)");
+    static_assert(CH % SPLIT == 0 && KU * sizeof(T) >= 4 && (BLOCKS >= NT || NT % BLOCKS == 0), "unit shape");
 
     // byte offset of logical chunk c of row r inside the operand's LDS tile
     __device__ static inline int lds_offset(int r, int c) { return r * RS + ((c ^ ((r ^ (r >> 3)) & 7)) << 4); }
 
-    u32x4 regs[COUNT];
+    u32x4 regs[LOADS];
     // fast path: byte offset of each piece from the tile's first element, fixed for the whole kernel; a load is
     // a buffer load "tile descriptor (scalar registers) + 32-bit lane offset" and costs no vector arithmetic
     // inside the K loop
-    uint32_t goff[EDGE ? 1 : COUNT];
+    uint32_t goff[EDGE ? 1 : LOADS];
     __amdgpu_buffer_rsrc_t rsrc;
+
+    // transposing path: unit u of this thread -> row chunk mc, k chunk kc, part s of the chunk
+    struct Unit {
+        int mc, kc, s;
+        bool valid;
+    };
+    __device__ static inline Unit unit_of(int u)
+    {
+        const int idx = static_cast<int>(threadIdx.x) + u * NT;
+        const int rest = idx / RCH;
+        return Unit{idx % RCH, rest / SPLIT, rest % SPLIT, !PARTIAL || idx < UNITS};
+    }
 
     __device__ inline void prepare(int64_t ld_)
     {
         if constexpr (!EDGE) {
             const int t = threadIdx.x;
-            static_for<COUNT>([&](auto Qc) {
+            static_for<LOADS>([&](auto Qc) {
                 constexpr int Q = decltype(Qc)::value;
                 if constexpr (KCONTIG) {
                     const int idx = t + Q * NT;
                     goff[Q] = static_cast<uint32_t>(((idx / CPR) * ld_ + (idx % CPR) * CH) * sizeof(T));
                 } else {
-                    const int idx = t + (Q / CH) * NT;
-                    goff[Q] = static_cast<uint32_t>(((idx % RCH) * CH + ((idx / RCH) * CH + Q % CH) * ld_) * sizeof(T));
+                    const Unit u = unit_of(Q / KU);
+                    goff[Q] = static_cast<uint32_t>((u.mc * CH + (u.kc * CH + u.s * KU + Q % KU) * ld_) * sizeof(T));
                 }
             });
         }
@@ -207,16 +236,15 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
                 else regs[Q] = gather_chunk<T>(p, kv);
             }
         } else {
-            constexpr int b = Q / CH, j = Q % CH;
-            const int idx = t + b * NT;
-            const int mc = idx % RCH, kc = idx / RCH;
-            if (PARTIAL && idx >= BLOCKS) return;
-            const T *p = base + mc * CH + (kc * CH + j) * ld;
+            const Unit u = unit_of(Q / KU);
+            if (!u.valid) return;
+            const int l = u.kc * CH + u.s * KU + Q % KU;
             if constexpr (!EDGE) {
                 regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
             } else {
-                const int rv = rows_left - mc * CH;
-                if (kc * CH + j >= k_left || rv <= 0) regs[Q] = u32x4{0u, 0u, 0u, 0u};
+                const T *p = base + u.mc * CH + l * ld;
+                const int rv = rows_left - u.mc * CH;
+                if (l >= k_left || rv <= 0) regs[Q] = u32x4{0u, 0u, 0u, 0u};
                 else if (vec_ok && rv >= CH) regs[Q] = *reinterpret_cast<const u32x4 *>(p);
                 else if (rv >= CH) regs[Q] = load_unaligned_chunk<T>(p);
                 else regs[Q] = gather_chunk<T>(p, rv);
@@ -224,7 +252,7 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
         }
     }
 
-    // Piece Q -> LDS.  On the transposing path piece Q = b*CH + i is row i of block b after the turn.
+    // Store Q -> LDS.  On the transposing path store Q = u*CH + i is row i of unit u after the turn.
     template <int Q> __device__ inline void store_one(char *lds) const
     {
         const int t = threadIdx.x;
@@ -234,18 +262,21 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
             if (PARTIAL && idx >= CHUNKS) return;
             *reinterpret_cast<u32x4 *>(lds + lds_offset(r, c)) = regs[Q];
         } else {
-            constexpr int b = Q / CH, i = Q % CH;
-            const int idx = t + b * NT;
-            const int mc = idx % RCH, kc = idx / RCH;
-            if (PARTIAL && idx >= BLOCKS) return;
-            *reinterpret_cast<u32x4 *>(lds + lds_offset(mc * CH + i, kc)) = transposed_row<i>(&regs[b * CH], T{});
+            constexpr int i = Q % CH;
+            const Unit u = unit_of(Q / CH);
+            if (!u.valid) return;
+            char *dst = lds + lds_offset(u.mc * CH + i, u.kc) + u.s * (16 / SPLIT);
+            const u32x4 row = transposed_row<i, KU>(&regs[(Q / CH) * KU], T{});
+            if constexpr (SPLIT == 1) *reinterpret_cast<u32x4 *>(dst) = row;
+            else if constexpr (SPLIT == 2) *reinterpret_cast<u32x2 *>(dst) = u32x2{row[0], row[1]};
+            else *reinterpret_cast<uint32_t *>(dst) = row[0];
         }
     }
 
-    __device__ inline void load_all() { static_for<COUNT>([&](auto q) { load_one<decltype(q)::value>(); }); }
+    __device__ inline void load_all() { static_for<LOADS>([&](auto q) { load_one<decltype(q)::value>(); }); }
     __device__ inline void store_all(char *lds) const
     {
-        static_for<COUNT>([&](auto q) { store_one<decltype(q)::value>(lds); });
+        static_for<STORES>([&](auto q) { store_one<decltype(q)::value>(lds); });
     }
 };
 
@@ -490,7 +521,6 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
     constexpr int A_BYTES = LoadA::LDS_BYTES, B_BYTES = LoadB::LDS_BYTES;
     constexpr int SLOTS = FM * FN;                      // MFMA groups per K-step
     constexpr int FRAGS = FM + FN;
-    constexpr int PIECES = LoadA::COUNT + LoadB::COUNT;
 
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
@@ -575,10 +605,10 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
         static_for<FRAGS>([&](auto F) { read_frag(F, Stage0{}, 0, 0); });
     }
 
-    // Event e of an operand's loader: the store of a staged piece (tile t+1) or its reload (tile t+2), in
-    // groups: the stores of a few pieces, then their reloads.  Transposing loader: a group is a CH x CH block
-    // (each store needs all CH registers of the block).
-    constexpr int EV_A = 2 * LoadA::COUNT, EVENTS = 2 * PIECES;
+    // Event e of an operand's loader: the store of a staged piece (tile t+1) or a reload (tile t+2), in
+    // groups: the stores of a few pieces, then the reloads of their registers.  Transposing loader: a group is
+    // one unit (each store needs all registers of the unit).
+    constexpr int EV_A = LoadA::LOADS + LoadA::STORES, EVENTS = EV_A + LoadB::LOADS + LoadB::STORES;
     // the last TAIL slots of the K-tile come behind the barrier and carry no staging traffic
     constexpr int TAIL = (SLOTS * MG_TAIL_SIXTEENTHS / 16) > 0 ? (SLOTS * MG_TAIL_SIXTEENTHS / 16) : 1;
     constexpr int EVENT_SLOTS = KSTEPS * SLOTS - TAIL;
@@ -589,13 +619,13 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
         constexpr bool is_a = e < EV_A;
         constexpr int le = is_a ? e : e - EV_A;
         constexpr bool kcontig = is_a ? A_KCONTIG : B_KCONTIG;
-        constexpr int count = is_a ? LoadA::COUNT : LoadB::COUNT;
-        // group size of the row-wise loader: GK stores (youngest piece first, so that the one wait in front
-        // of the first store covers the whole group: loads return in order), then the GK reloads
-        constexpr int GK = kcontig ? (count % 4 == 0 ? 4 : (count % 2 == 0 ? 2 : 1)) : CH;
-        constexpr int w = le % (2 * GK);
-        constexpr bool is_load = w >= GK;
-        constexpr int piece = (le / (2 * GK)) * GK + (is_load ? w - GK : (kcontig ? GK - 1 - w : w));
+        // GS stores (row-wise loader: youngest piece first, so that the one wait in front of the first store
+        // covers the whole group: loads return in order), then the GL reloads
+        constexpr int GS = is_a ? LoadA::GROUP_STORES : LoadB::GROUP_STORES;
+        constexpr int GL = is_a ? LoadA::GROUP_LOADS : LoadB::GROUP_LOADS;
+        constexpr int grp = le / (GS + GL), w = le % (GS + GL);
+        constexpr bool is_load = w >= GS;
+        constexpr int piece = is_load ? grp * GL + (w - GS) : grp * GS + (kcontig ? GS - 1 - w : w);
         if constexpr (is_a) {
             if constexpr (is_load) la.template load_one<piece>();
             else la.template store_one<piece>(lds + par * A_BYTES);

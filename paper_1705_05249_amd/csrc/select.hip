@@ -114,24 +114,25 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
         // that is not full runs ceil(tiles / 256) work-groups per compute unit at a rate that grows with them up to
         // the kernel's ceiling; a full chip works through rounds of 256 x resident work-groups.  Rates (Mflop/us per
         // compute unit: ceiling, per resident work-group) and the number of resident work-groups are fitted to a
-        // scan of every tile over square problems from 1024 to 6144 in the four operand orders; partial tiles of
-        // ragged problems count as whole ones.  The direct-to-LDS kernels need whole tiles and 16-byte aligned
+        // scan of every tile over problems of 256 to 4608 tiles in the four operand orders, less 2.5 us per launch
+        // (what a run of any length costs on top; common to all candidates, so not part of the estimate); partial
+        // tiles of ragged problems count as whole ones.  The direct-to-LDS kernels need whole tiles and 16-byte aligned
         // operands; where they are illegal the next best estimate is tried.
-        static const TileChoice f16_tiles[] = {{"hdma16_256x256x64_w2x4", 256, 256, 64, 5.1f, 5.1f, 1},
-                                               {"hdma16_256x128x64_w4x2", 256, 128, 64, 4.3f, 4.3f, 1},
-                                               {"hdma16_128x128x64_w2x4", 128, 128, 64, 4.3f, 2.6f, 2},
-                                               {"hmfma_256x256x64_w2x2", 256, 256, 64, 4.5f, 4.5f, 1},
-                                               {"hmfma_256x128x64_w2x2", 256, 128, 64, 3.8f, 3.8f, 1},
-                                               {"hmfma_128x128x64_w2x2", 128, 128, 64, 3.3f, 1.8f, 2},
-                                               {"hmfma_128x64x64_w2x2", 128, 64, 64, 2.6f, 0.98f, 3},
-                                               {"hmfma_64x64x64_w2x2", 64, 64, 64, 1.9f, 0.6f, 5}};
+        static const TileChoice f16_tiles[] = {{"hdma16_256x256x64_w2x4", 256, 256, 64, 4.88f, 4.83f, 1},
+                                               {"hdma16_256x128x64_w4x2", 256, 128, 64, 3.93f, 3.65f, 1},
+                                               {"hdma16_128x128x64_w2x4", 128, 128, 64, 4.07f, 2.75f, 2},
+                                               {"hmfma_256x256x64_w2x2", 256, 256, 64, 4.54f, 4.40f, 1},
+                                               {"hmfma_256x128x64_w2x2", 256, 128, 64, 3.72f, 3.72f, 1},
+                                               {"hmfma_128x128x64_w2x2", 128, 128, 64, 3.61f, 3.0f, 2},
+                                               {"hmfma_128x64x64_w2x2", 128, 64, 64, 2.85f, 1.87f, 3},
+                                               {"hmfma_64x64x64_w2x2", 64, 64, 64, 2.30f, 1.65f, 5}};
         // The register-staged FP16 kernels transpose operands that are not contiguous along k on their way to
-        // LDS; the smaller the tile, the more that shows.  Measured rates relative to the (m, k) order: both
-        // operands along k 1.2 / 1.1 / 1.0 (tiles up to 128 x 64 / up to 256 x 128 / 256 x 256), A along m and B
-        // along n 0.62 / 0.85 / 1.0.
+        // LDS; the smaller the tile, the more that shows.  Measured rates relative to the (m, k) order (A along m,
+        // B along k; tiles up to 128 x 64 / up to 256 x 128 / 256 x 256): both operands along k 1.10 / 1.06 / 1.02,
+        // A along m and B along n 0.93 / 0.97 / 0.98.
         auto staged_f16 = [&](const TileChoice &t) {
             const int cls = t.bm * t.bn <= 128 * 64 ? 0 : (t.bm * t.bn <= 256 * 128 ? 1 : 2);
-            static const double both_k[3] = {1.2, 1.1, 1.0}, neither_k[3] = {0.62, 0.85, 1.0};
+            static const double both_k[3] = {1.10, 1.06, 1.02}, neither_k[3] = {0.93, 0.97, 0.98};
             if (p.a_trans && !p.b_trans) return both_k[cls];
             if (!p.a_trans && p.b_trans) return neither_k[cls];
             return 1.0;
@@ -139,8 +140,8 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
         static const TileChoice f32_tiles[] = {{"smfma_256x256x32_w2x2", 256, 256, 32, 0.577f, 0.577f, 1},
                                                {"smfma_256x128x32_w2x2", 256, 128, 32, 0.561f, 0.561f, 1},
                                                {"smfma_128x128x32_w2x2", 128, 128, 32, 0.574f, 0.50f, 2},
-                                               {"smfma_128x64x32_w2x2", 128, 64, 32, 0.553f, 0.45f, 3},
-                                               {"smfma_64x64x32_w2x2", 64, 64, 32, 0.52f, 0.35f, 5}};
+                                               {"smfma_128x64x32_w2x2", 128, 64, 32, 0.553f, 0.47f, 3},
+                                               {"smfma_64x64x32_w2x2", 64, 64, 32, 0.52f, 0.45f, 5}};
         const TileChoice *tiles = f32 ? f32_tiles : f16_tiles;
         const int count = f32 ? 5 : 8;
         bool tried[8] = {false, false, false, false, false, false, false, false};
@@ -151,39 +152,66 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
             const int64_t full = static_cast<int64_t>(kComputeUnits) * tiles[i].resident;   // work-groups the chip holds
             double order = 1.0;
             if (!f32 && tiles[i].tag[1] == 'm') order = staged_f16(tiles[i]);
+            // the 128 x 128 direct-to-LDS tile is slower with A along k (3.7-3.8 against 4.0)
+            if (!f32 && i == 2 && p.a_trans) order = 0.94;
             // ragged or unaligned FP16 problems run the bounds-checked flavour, which costs the smaller tiles more
             // (rates against the whole-tile flavour: 0.75 for 256 x 256 and 256 x 128, about 0.5 for 128 x 128
             // and below; FP32 loses about 0.78 on every tile, which does not change the ranking)
-            if (!f32 && (p.m % tiles[i].bm || p.n % tiles[i].bn || p.k % tiles[i].bk))
-                order *= tiles[i].bm * tiles[i].bn < 256 * 128 ? 0.6 : 0.7;
+            const bool ragged = p.m % tiles[i].bm || p.n % tiles[i].bn || p.k % tiles[i].bk;
+            if (!f32 && ragged) order *= tiles[i].bm * tiles[i].bn < 256 * 128 ? 0.6 : 0.7;
+            // rate of a compute unit that holds u work-groups at once: ceiling * (1 - (1 - per_group / ceiling)^u)
+            // (measured on the 64 x 64 FP16 tile: 1.33 / 1.85 / 2.02 / 2.11 for u = 1..4, the formula gives
+            // 1.31 / 1.86 / 2.09 / 2.18)
+            auto shared_rate = [&](int64_t u) {
+                const double idle = 1.0 - (tiles[i].per_group < tiles[i].ceiling ? tiles[i].per_group / tiles[i].ceiling : 1.0);
+                return tiles[i].ceiling * (1.0 - pow(idle, static_cast<double>(u)));
+            };
             double time;
             if (blocks < full) {
                 // the chip is not full: ceil(blocks / 256) work-groups share a compute unit
                 const int64_t per_unit = ceil_div(blocks, kComputeUnits);
-                double rate = tiles[i].per_group * static_cast<double>(per_unit);
-                if (rate > tiles[i].ceiling) rate = tiles[i].ceiling;
-                // the fastest kernel runs against the power limit: with fewer busy compute units each one
-                // clocks higher (144 tiles of 256 x 256 at 3072^3: 64 us measured against 79 us at the
-                // full-chip rate); the smaller tiles showed no such gain
-                if (!f32 && i == 0 && blocks < kComputeUnits) {
-                    const double boost = sqrt(static_cast<double>(kComputeUnits) / static_cast<double>(blocks));
-                    rate *= boost < 1.25 ? boost : 1.25;
+                double rate = shared_rate(per_unit);
+                // FP16 runs against the power limit: when some compute units hold fewer work-groups than the
+                // busiest ones (or none), the busy ones clock higher.  With `load` = the chip's summed rate as a
+                // fraction of the rate with every compute unit as busy as the busiest, the gain is load^-e, at
+                // most 1.4; e fitted per kernel: 256 x 256 direct-to-LDS 0.55 (144 tiles at 3072^3 run at 6.7
+                // Mflop/us per compute unit against 4.8 on a full chip), 256 x 128 0.3 (direct-to-LDS and
+                // register-staged), 128 x 128 direct-to-LDS 1.3 when the busiest compute units hold two work-groups
+                // (324 tiles at 2304^3: 4.8 Mflop/us against 3.6) but 0.1 with one, the smaller register-staged
+                // kernels 0.1; the bounds-checked flavour shows no gain; the 128 x 128 direct-to-LDS tile at most 1.2
+                if (!f32 && !ragged) {
+                    const int64_t busiest = blocks - static_cast<int64_t>(kComputeUnits) * (per_unit - 1);
+                    const double lower = per_unit > 1 ? shared_rate(per_unit - 1) : 0.0;
+                    const double load = (static_cast<double>(busiest) * rate + static_cast<double>(kComputeUnits - busiest) * lower) /
+                                        (static_cast<double>(kComputeUnits) * rate);
+                    const double exponent = i == 0 ? 0.55 : (i == 2 ? (per_unit > 1 ? 1.3 : 0.1) : (tiles[i].bm == 256 ? 0.3 : 0.1));
+                    const double boost = pow(load, -exponent);
+                    const double most = i == 2 ? 1.2 : 1.4;
+                    rate *= boost < most ? boost : most;
                 }
                 time = static_cast<double>(per_unit) * tile_flops / (rate * order);
             } else {
-                // rounds of `full` work-groups; one work-group per compute unit quantises sharply (576 tiles
-                // take three rounds), and so do the first two rounds of any kernel; with several resident
-                // work-groups later rounds blur (measured: the fractional round costs 0.1-0.36 more).  The
-                // fastest FP16 kernel is the exception: its partial last round runs on fewer compute units at
-                // a higher clock (400 tiles take 1.7 rounds' time, 576 tiles 2.5)
+                // whole rounds of `full` work-groups at the ceiling, then the rest.  One work-group per compute
+                // unit quantises sharply (576 tiles take three rounds).  FP16 kernels with several resident
+                // work-groups: the rest is a round of its own with u = ceil(rest / 256) work-groups per compute
+                // unit at their shared rate, four fifths of it exposed (it starts while the round before drains);
+                // measured at k = 2048, 512 / 768 / 1024 / 1280 tiles: 128 x 128 direct-to-LDS 37 / 59 / 70 / 91 us
+                // (this model: 34 / 57 / 68 / 91), register-staged 41 / 61 / 83 / 104 (38 / 58 / 76 / 96).  FP32
+                // shows whole rounds for the first two and blurred ones beyond (the fractional round costs 0.1-0.36
+                // more).  The fastest FP16 kernel is an exception of its own: its partial last round runs on fewer
+                // compute units at a higher clock (400 tiles take 1.7 rounds' time, 576 tiles 2.5)
                 const double x = static_cast<double>(blocks) / static_cast<double>(full);
                 const double whole = floor(x);
-                double rounds = x;
-                if (x > whole) {
-                    if (!f32 && i == 0) rounds = x + 0.25;
-                    else rounds = tiles[i].resident == 1 || x <= 2.0 ? whole + 1.0 : x + 0.25;
+                const double round_time = tiles[i].resident * tile_flops / (tiles[i].ceiling * order);
+                if (x == whole) time = x * round_time;
+                else if (!f32 && i == 0) time = (x + 0.25) * round_time;
+                else if (tiles[i].resident == 1) time = (whole + 1.0) * round_time;
+                else if (f32) time = (x <= 2.0 ? whole + 1.0 : x + 0.25) * round_time;
+                else {
+                    const int64_t rest = blocks - static_cast<int64_t>(whole) * full;
+                    const int64_t u = ceil_div(rest, kComputeUnits);
+                    time = whole * round_time + 0.8 * static_cast<double>(u) * tile_flops / (shared_rate(u) * order);
                 }
-                time = rounds * tiles[i].resident * tile_flops / (tiles[i].ceiling * order);
             }
             // unequal tiles (shape hint) balance only when a compute unit gets several: FP32 at 4096 runs the hinted
             // 256 x 256 grid, one tile per compute unit, as slowly as the general problem
