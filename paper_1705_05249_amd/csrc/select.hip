@@ -137,11 +137,17 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
             if (!p.a_trans && p.b_trans) return neither_k[cls];
             return 1.0;
         };
+        // FP32: a single work-group keeps the MFMA pipes of its compute unit nearly busy, so work-groups that share
+        // a compute unit take turns rather than overlap (128 x 128 at k = 2048: 256 / 288 / 512 / 768 / 1024 tiles
+        // take 128 / 233 / 249 / 368 / 474 us): rounds of 256 tiles whatever the tile, at a rate that rises from
+        // `per_group` (one round) towards `ceiling` (many), plus what a round of small tiles costs on top
+        // (0 / 0 / 1 / 2 / 2.8 us from the largest tile to the smallest: first loads and the epilogue).
         static const TileChoice f32_tiles[] = {{"smfma_256x256x32_w2x2", 256, 256, 32, 0.577f, 0.577f, 1},
-                                               {"smfma_256x128x32_w2x2", 256, 128, 32, 0.561f, 0.561f, 1},
-                                               {"smfma_128x128x32_w2x2", 128, 128, 32, 0.574f, 0.50f, 2},
-                                               {"smfma_128x64x32_w2x2", 128, 64, 32, 0.553f, 0.47f, 3},
-                                               {"smfma_64x64x32_w2x2", 64, 64, 32, 0.52f, 0.45f, 5}};
+                                               {"smfma_256x128x32_w2x2", 256, 128, 32, 0.565f, 0.487f, 1},
+                                               {"smfma_128x128x32_w2x2", 128, 128, 32, 0.575f, 0.541f, 2},
+                                               {"smfma_128x64x32_w2x2", 128, 64, 32, 0.56f, 0.517f, 3},
+                                               {"smfma_64x64x32_w2x2", 64, 64, 32, 0.555f, 0.533f, 5}};
+        static const double f32_round_cost[5] = {0.0, 0.0, 1.0e6, 2.0e6, 2.8e6};
         const TileChoice *tiles = f32 ? f32_tiles : f16_tiles;
         const int count = f32 ? 5 : 8;
         bool tried[8] = {false, false, false, false, false, false, false, false};
@@ -156,7 +162,7 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
             if (!f32 && i == 2 && p.a_trans) order = 0.94;
             // ragged or unaligned FP16 problems run the bounds-checked flavour, which costs the smaller tiles more
             // (rates against the whole-tile flavour: 0.75 for 256 x 256 and 256 x 128, about 0.5 for 128 x 128
-            // and below; FP32 loses about 0.78 on every tile, which does not change the ranking)
+            // and below; FP32: see below)
             const bool ragged = p.m % tiles[i].bm || p.n % tiles[i].bn || p.k % tiles[i].bk;
             if (!f32 && ragged) order *= tiles[i].bm * tiles[i].bn < 256 * 128 ? 0.6 : 0.7;
             // rate of a compute unit that holds u work-groups at once: ceiling * (1 - (1 - per_group / ceiling)^u)
@@ -167,7 +173,26 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 return tiles[i].ceiling * (1.0 - pow(idle, static_cast<double>(u)));
             };
             double time;
-            if (blocks < full) {
+            if (f32) {
+                // a chip that is not full spreads its work-groups (ceil(blocks / 256) turns); beyond that, compute
+                // units are refilled as their work-groups retire, and whether the last, partial refill is spread
+                // or packed `resident` to a compute unit depends on the shape (768 tiles of 128 x 128 took three
+                // turns as 16 x 48 tiles and four as 48 x 16): the mean of the two is charged
+                double rounds;
+                if (blocks <= full) {
+                    rounds = static_cast<double>(ceil_div(blocks, kComputeUnits));
+                } else {
+                    const int64_t fills = blocks / full, rest = blocks - fills * full;
+                    rounds = static_cast<double>(fills * tiles[i].resident);
+                    if (rest > 0) rounds += 0.5 * static_cast<double>(tiles[i].resident + ceil_div(rest, kComputeUnits));
+                }
+                const double up = ceil(rounds);
+                // (the bounds-checked flavour runs at 0.5-0.8 of these rates; the same for every tile, but it
+                // decides between one long turn and several slices: (4097, 129, 4095) takes 132 us unsplit on 195
+                // tiles of 64 x 64 and 74 us in five slices)
+                const double rate = (tiles[i].ceiling - (tiles[i].ceiling - tiles[i].per_group) / up) * (ragged ? 0.6 : 1.0);
+                time = rounds * (tile_flops / rate + f32_round_cost[i]);
+            } else if (blocks < full) {
                 // the chip is not full: ceil(blocks / 256) work-groups share a compute unit
                 const int64_t per_unit = ceil_div(blocks, kComputeUnits);
                 double rate = shared_rate(per_unit);
@@ -179,7 +204,7 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 // register-staged), 128 x 128 direct-to-LDS 1.3 when the busiest compute units hold two work-groups
                 // (324 tiles at 2304^3: 4.8 Mflop/us against 3.6) but 0.1 with one, the smaller register-staged
                 // kernels 0.1; the bounds-checked flavour shows no gain; the 128 x 128 direct-to-LDS tile at most 1.2
-                if (!f32 && !ragged) {
+                if (!ragged) {
                     const int64_t busiest = blocks - static_cast<int64_t>(kComputeUnits) * (per_unit - 1);
                     const double lower = per_unit > 1 ? shared_rate(per_unit - 1) : 0.0;
                     const double load = (static_cast<double>(busiest) * rate + static_cast<double>(kComputeUnits - busiest) * lower) /
@@ -196,26 +221,21 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 // work-groups: the rest is a round of its own with u = ceil(rest / 256) work-groups per compute
                 // unit at their shared rate, four fifths of it exposed (it starts while the round before drains);
                 // measured at k = 2048, 512 / 768 / 1024 / 1280 tiles: 128 x 128 direct-to-LDS 37 / 59 / 70 / 91 us
-                // (this model: 34 / 57 / 68 / 91), register-staged 41 / 61 / 83 / 104 (38 / 58 / 76 / 96).  FP32
-                // shows whole rounds for the first two and blurred ones beyond (the fractional round costs 0.1-0.36
-                // more).  The fastest FP16 kernel is an exception of its own: its partial last round runs on fewer
-                // compute units at a higher clock (400 tiles take 1.7 rounds' time, 576 tiles 2.5)
+                // (this model: 34 / 57 / 68 / 91), register-staged 41 / 61 / 83 / 104 (38 / 58 / 76 / 96).  The
+                // fastest FP16 kernel is an exception of its own: its partial last round runs on fewer compute
+                // units at a higher clock (400 tiles take 1.7 rounds' time, 576 tiles 2.5)
                 const double x = static_cast<double>(blocks) / static_cast<double>(full);
                 const double whole = floor(x);
                 const double round_time = tiles[i].resident * tile_flops / (tiles[i].ceiling * order);
                 if (x == whole) time = x * round_time;
-                else if (!f32 && i == 0) time = (x + 0.25) * round_time;
+                else if (i == 0) time = (x + 0.25) * round_time;
                 else if (tiles[i].resident == 1) time = (whole + 1.0) * round_time;
-                else if (f32) time = (x <= 2.0 ? whole + 1.0 : x + 0.25) * round_time;
                 else {
                     const int64_t rest = blocks - static_cast<int64_t>(whole) * full;
                     const int64_t u = ceil_div(rest, kComputeUnits);
                     time = whole * round_time + 0.8 * static_cast<double>(u) * tile_flops / (shared_rate(u) * order);
                 }
             }
-            // unequal tiles (shape hint) balance only when a compute unit gets several: FP32 at 4096 runs the hinted
-            // 256 x 256 grid, one tile per compute unit, as slowly as the general problem
-            if (f32 && p.shape != MG_SHAPE_GENERAL && tiles[i].resident == 1) time *= 1.3;
             // split-K: the partial sums are written and read back (8 bytes per slice and output at ~4 TB/s) by
             // a second launch (~4 us)
             if (slices > 1) time += 1.0e6 * (4.0 + (8.0 * slices + 4.0) * static_cast<double>(p.m) * static_cast<double>(p.n) / 4.0e6);
@@ -257,6 +277,19 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
             if (!f32 && p.shape != MG_SHAPE_GENERAL && best == 0 && !tried[2] &&
                 ceil_div(p.m, 256) * ceil_div(p.n, 256) <= (kComputeUnits * 3) / 4)
                 best = 2;
+            // FP32 work-groups take turns on a compute unit, so unequal tiles (skipped ones, narrowed K ranges)
+            // only pay off when a compute unit gets many of them: the small tiles win at every size measured
+            // (SYRK 4096: 974 / 923 / 695 / 618 us from the 256 x 256 to the 64 x 64 tile, TRMM 950 / 614 / 596 / 541;
+            // SYRK 8192: 4958 / 4690 / 5044 us on 128 x 128 / 128 x 64 / 64 x 64)
+            // (a triangular operand beyond 6144 x 6144 outputs is ranked like the general problem: TRMM 8192 takes
+            // 4342 us that way, 4723 us on 64 x 64 tiles)
+            if (f32 && p.shape != MG_SHAPE_GENERAL &&
+                (p.shape == MG_SHAPE_C_LOWER || p.shape == MG_SHAPE_C_UPPER || p.m * p.n <= int64_t(6144) * 6144)) {
+                const bool c_shape = p.shape == MG_SHAPE_C_LOWER || p.shape == MG_SHAPE_C_UPPER;
+                const int small = c_shape && p.m * p.n > int64_t(4096) * 4096 ? 3 : 4;
+                if (!tried[small]) best = small;
+                else if (!tried[7 - small]) best = 7 - small;
+            }
             tried[best] = true;
             const TileChoice &tc = tiles[best];
             const int want = best_slices;
