@@ -62,8 +62,9 @@ def rel_error(got, c_ref, d_ref):
     return float(err.max())
 
 
-def check_case(case, oracle, sampled=False, workspace="auto", offset_elems=(0, 0, 0), seed=1):
-    """Full (or sampled) element-by-element comparison of one case against the oracle."""
+def check_case(case, oracle, sampled=False, workspace="auto", offset_elems=(0, 0, 0), seed=1, sample=None):
+    """Full (or sampled) element-by-element comparison of one case against the oracle; `sample`: keyword
+    arguments for the choice of sampled entries (fewer complete rows and columns on the largest problems)."""
     st, out = run_gpu(case, workspace=workspace, offset_elems=offset_elems)
     assert st == 0
     assert_padding_untouched(case, out)
@@ -71,7 +72,7 @@ def check_case(case, oracle, sampled=False, workspace="auto", offset_elems=(0, 0
     args = (case.dtype, case.layout, case.ta, case.tb, case.m, case.n, case.k, case.alpha, case.A, case.lda,
             case.B, case.ldb, case.beta, case.C, case.ldc)
     if sampled:
-        rows, cols = W.sample_entries(case.m, case.n, seed=seed)
+        rows, cols = W.sample_entries(case.m, case.n, seed=seed, **(sample or {}))
         c_ref, d_ref = oracle.gemm_entries(*args, rows, cols)
         got = got[rows, cols]
     else:
