@@ -237,8 +237,8 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 }
             }
             // split-K: the partial sums are written and read back (8 bytes per slice and output at ~4 TB/s) by
-            // a second launch (~4 us)
-            if (slices > 1) time += 1.0e6 * (4.0 + (8.0 * slices + 4.0) * static_cast<double>(p.m) * static_cast<double>(p.n) / 4.0e6);
+            // a second launch (~3 us)
+            if (slices > 1) time += 1.0e6 * (3.0 + (8.0 * slices + 4.0) * static_cast<double>(p.m) * static_cast<double>(p.n) / 4.0e6);
             return time;
         };
         for (int attempt = 0; attempt < count; ++attempt) {
