@@ -163,16 +163,17 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
     // byte offset of logical chunk c of row r inside the operand's LDS tile
     __device__ static inline int lds_offset(int r, int c) { return r * RS + ((c ^ ((r ^ (r >> 3)) & 7)) << 4); }
 
-    u32x4 regs[LOADS];
-    // fast path: byte offset of each piece from the tile's first element, fixed for the whole kernel; a load is
-    // a buffer load "tile descriptor (scalar registers) + 32-bit lane offset" and costs no vector arithmetic
-    // inside the K loop
     // Bounds-checked flavour, FP32: whole K-tiles of tiles that have all their rows are loaded like the fast
     // flavour's (ragged problems of 2049^3 to 4104^3: 3-13 % faster; the FP16 kernels lost 10-17 % with the second
     // code path in their loop and keep to the checked loads).
     static constexpr bool INTERIOR_FAST = EDGE && sizeof(T) == 4;
-    // (the bounds-checked flavour keeps the offset of its first piece only: the others differ from it by a
-    // multiple of the leading dimension that is the same for every lane, which goes into the scalar offset)
+
+    u32x4 regs[LOADS];
+    // fast path: byte offset of each piece from the tile's first element, fixed for the whole kernel; a load is
+    // a buffer load "tile descriptor (scalar registers) + 32-bit lane offset" and costs no vector arithmetic
+    // inside the K loop (the bounds-checked flavour keeps the offset of its first piece only: the others differ
+    // from it by a multiple of the leading dimension that is the same for every lane, which goes into the
+    // scalar offset)
     uint32_t goff[EDGE ? 1 : LOADS];
     uint32_t ld_bytes;
     __amdgpu_buffer_rsrc_t rsrc;
