@@ -35,9 +35,15 @@ hipError_t launch_tile_kernel(Kernel kernel, bool *attr_set, int lds_bytes, int 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || split == 1) return e;
     const int64_t total = p.m * p.n;
-    const unsigned blocks = static_cast<unsigned>(total / 256 + 1 < 4096 ? total / 256 + 1 : 4096);
-    hipLaunchKernelGGL(splitk_reduce_kernel<T>, dim3(blocks), dim3(256), 0, p.stream, a.partial, split, a.m, a.n,
-                       static_cast<T *>(p.C), p.ldc, p.alpha, p.beta);
+    const bool wide = p.m % 4 == 0 && reinterpret_cast<uintptr_t>(a.partial) % 16 == 0;
+    const int64_t groups = wide ? total / 4 : total;
+    const unsigned blocks = static_cast<unsigned>(groups / 256 + 1 < 4096 ? groups / 256 + 1 : 4096);
+    if (wide)
+        hipLaunchKernelGGL((splitk_reduce_kernel<T, 4>), dim3(blocks), dim3(256), 0, p.stream, a.partial, split, a.m, a.n,
+                           static_cast<T *>(p.C), p.ldc, p.alpha, p.beta);
+    else
+        hipLaunchKernelGGL((splitk_reduce_kernel<T, 1>), dim3(blocks), dim3(256), 0, p.stream, a.partial, split, a.m, a.n,
+                           static_cast<T *>(p.C), p.ldc, p.alpha, p.beta);
     return hipGetLastError();
 }
 

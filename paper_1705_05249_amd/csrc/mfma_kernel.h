@@ -722,20 +722,46 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
     tile_epilogue<T, RB, FM, FN, WTM, WTN, EDGE>(acc, args, lds, m0, n0, wm, wn, wave, lane);
 }
 
-// C <- alpha * sum_z partial[z] + beta * C   (finishes a split-K product)
-template <typename T>
+// C <- alpha * sum_z partial[z] + beta * C   (finishes a split-K product).  A thread takes V consecutive
+// elements of a column (V = 4 when m is a multiple of 4 and the partial sums are 16-byte aligned: one 16-byte
+// load per slice; C is accessed at element alignment).
+template <typename T, int V>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partial, int split, int m, int n,
                                                              T *__restrict__ C, int64_t ldc, float alpha, float beta)
 {
+    typedef float floatv __attribute__((ext_vector_type(V)));
     const int64_t total = static_cast<int64_t>(m) * n;
-    for (int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; e < total;
-         e += static_cast<int64_t>(gridDim.x) * 256) {
-        float s = 0.f;
-        for (int z = 0; z < split; ++z) s += partial[z * total + e];
-        T *p = C + (e % m) + (e / m) * ldc;
-        float o = alpha * s;
-        if (beta != 0.f) o = fmaf(beta, load_as_float(p), o);
-        store_from_float(p, o);
+    const int64_t groups = total / V;
+    for (int64_t g = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; g < groups;
+         g += static_cast<int64_t>(gridDim.x) * 256) {
+        const int64_t e = g * V;
+        float s[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) s[i] = 0.f;
+        for (int z = 0; z < split; ++z) {
+            if constexpr (V == 1) {
+                s[0] += partial[z * total + e];
+            } else {
+                const floatv x = *reinterpret_cast<const floatv *>(partial + z * total + e);
+#pragma unroll
+                for (int i = 0; i < V; ++i) s[i] += x[i];
+            }
+        }
+        Pack<T, V> *p = reinterpret_cast<Pack<T, V> *>(C + (e % m) + (e / m) * ldc);
+        Pack<T, V> out;
+        if (beta != 0.f) {
+            const Pack<T, V> old = *p;
+#pragma unroll
+            for (int i = 0; i < V; ++i) {
+                float o = alpha * s[i];
+                o = fmaf(beta, static_cast<float>(old.v[i]), o);
+                out.v[i] = static_cast<T>(o);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < V; ++i) out.v[i] = static_cast<T>(alpha * s[i]);
+        }
+        *p = out;
     }
 }
 
