@@ -158,6 +158,9 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
             const int64_t full = static_cast<int64_t>(kComputeUnits) * tiles[i].resident;   // work-groups the chip holds
             double order = 1.0;
             if (!f32 && tiles[i].tag[1] == 'm') order = staged_f16(tiles[i]);
+            // sliced sums run the large register-staged tiles about a tenth below their rate (256 x 8192 x 8192 with
+            // both operands along k in four slices: 53-55 us against 48 us on the direct-to-LDS tile of that size)
+            if (!f32 && tiles[i].tag[1] == 'm' && slices > 1 && tiles[i].bm * tiles[i].bn >= 256 * 128) order *= 0.9;
             // the 128 x 128 direct-to-LDS tile is slower with A along k (3.7-3.8 against 4.0)
             if (!f32 && i == 2 && p.a_trans) order = 0.94;
             // ragged or unaligned FP16 problems run the bounds-checked flavour, which costs the smaller tiles more
@@ -190,7 +193,8 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 // (the bounds-checked flavour runs at 0.5-0.8 of these rates; the same for every tile, but it
                 // decides between one long turn and several slices: (4097, 129, 4095) takes 132 us unsplit on 195
                 // tiles of 64 x 64 and 74 us in five slices)
-                const double rate = (tiles[i].ceiling - (tiles[i].ceiling - tiles[i].per_group) / up) * (ragged ? 0.6 : 1.0);
+                // (a single turn of it has no other work-group's arithmetic to hide its checked loads behind: 0.45)
+                const double rate = (tiles[i].ceiling - (tiles[i].ceiling - tiles[i].per_group) / up) * (ragged ? (up <= 1.0 ? 0.45 : 0.6) : 1.0);
                 time = rounds * (tile_flops / rate + f32_round_cost[i]);
             } else if (blocks < full) {
                 // the chip is not full: ceil(blocks / 256) work-groups share a compute unit
