@@ -137,7 +137,7 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
 
     int tm, tn;
     if (args.shape == 0) tile_coords(blockIdx.x, args.tiles_m, args.tiles_n, args.group_m, tm, tn);
-    else tile_coords_balanced(blockIdx.x, args.tiles_m, args.tiles_n, args.group_m, args.reversed != 0, tm, tn);
+    else tile_coords_balanced(blockIdx.x, args.tiles_m, args.tiles_n, args.group_m, args.reversed != 0, args.shape == MG_SHAPE_C_UPPER, tm, tn);
     const int64_t m0 = static_cast<int64_t>(tm) * BM, n0 = static_cast<int64_t>(tn) * BN;
     int kb = blockIdx.z * args.k_per_split;
     int ke = (kb + args.k_per_split < args.k) ? kb + args.k_per_split : args.k;

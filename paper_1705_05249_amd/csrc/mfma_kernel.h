@@ -385,8 +385,12 @@ __device__ inline void tile_coords(int wg, int tiles_m, int tiles_n, int group_m
 // skipped tiles): the XCD-contiguous walk above would hand whole row bands, i.e. all long or all short tiles, to
 // one XCD.  Here work-group ids stay interleaved over the XCDs (the hardware's order) and the row inside a group
 // rotates with the column, so every XCD sees every row and column equally often; `reversed` starts at the far end
-// (the longest tiles first).
-__device__ inline void tile_coords_balanced(int wg, int tiles_m, int tiles_n, int group_m, bool reversed, int &tm, int &tn)
+// (the longest tiles first).  Where a group of rows crosses the diagonal of C, an XCD's share of the tiles on one
+// side of it depends on its place in the rotation (1 to 8 of the 8 x 8 block), so odd groups run the rotation
+// the other way round and the upper triangle starts it one row on (`upper`): every XCD then gets 9 tiles of two
+// such blocks (SYRK: a 20 x 20 grid gave one XCD 34 of the 210 wanted tiles for its 32 compute units, now 27).
+__device__ inline void tile_coords_balanced(int wg, int tiles_m, int tiles_n, int group_m, bool reversed, bool upper, int &tm,
+                                            int &tn)
 {
     const int id = reversed ? tiles_m * tiles_n - 1 - wg : wg;
     const int per_group = group_m * tiles_n;
@@ -394,14 +398,11 @@ __device__ inline void tile_coords_balanced(int wg, int tiles_m, int tiles_n, in
     const int first = group * group_m;
     const int size = (tiles_m - first) < group_m ? (tiles_m - first) : group_m;
     const int in_group = id % per_group;
+    const int r = in_group % size;
     tn = in_group / size;
-    tm = first + (in_group % size + tn) % size;
+    tm = first + (((group & 1) ? size - 1 - r : r) + tn + (upper ? 1 : 0)) % size;
 }
 
-// A shape hint (ProblemShape) applied to one tile.  A triangular operand (its zeros are stored, so this only
-// saves work): the K range [kb, ke) of the tile shrinks to where the operand can be non-zero.  A triangular
-// result: false for tiles wholly outside it, which are skipped.  The host passes a shape only with a single K
-// slice, so the range stays non-empty and a multiple of the K tile.
 template <int BM, int BN, int BK> __device__ inline bool narrow_to_shape(int shape, int64_t m0, int64_t n0, int &kb, int &ke)
 {
     if (shape == 0) return true;
@@ -553,7 +554,7 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
 
     int tm, tn;
     if (args.shape == 0) tile_coords(blockIdx.x, args.tiles_m, args.tiles_n, args.group_m, tm, tn);
-    else tile_coords_balanced(blockIdx.x, args.tiles_m, args.tiles_n, args.group_m, args.reversed != 0, tm, tn);
+    else tile_coords_balanced(blockIdx.x, args.tiles_m, args.tiles_n, args.group_m, args.reversed != 0, args.shape == MG_SHAPE_C_UPPER, tm, tn);
     const int64_t m0 = static_cast<int64_t>(tm) * BM, n0 = static_cast<int64_t>(tn) * BN;
     int kb = blockIdx.z * args.k_per_split;
     int ke = (kb + args.k_per_split < args.k) ? kb + args.k_per_split : args.k;
