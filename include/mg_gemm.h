@@ -313,6 +313,29 @@ mg_status mg_override_batched_config(int32_t kernel_id);
 /* Back to automatic selection (both overrides). */
 void mg_clear_override(void);
 
+/* ---- local-memory layout of the FP16 macro-tile kernels (paper Section 3.2: the layout of the
+ * tiles in local memory is a tunable because bank conflicts cost) ----------------------------
+ * Host-only introspection, no GPU involved: the functions evaluate the address formulas the
+ * kernels are built from, so that a checker can run a bank model over them.
+ * An operand tile has tile_rows rows (m index for A, n index for B; 64..256) and 64 values of k.
+ * k_contiguous != 0: the operand is contiguous along k in memory and sits in local memory as
+ * [row][k]; else it sits as [k][row], as in memory.  fragment_rows is 32 or 16 (rows of one
+ * MFMA operand).  All offsets are bytes from the start of one operand stage; -1 for invalid
+ * arguments. */
+/* Where FP16 element (row, k) of the tile is stored. */
+int32_t mg_lds_store_offset(int32_t k_contiguous, int32_t fragment_rows, int32_t tile_rows,
+                            int32_t row, int32_t k);
+/* What lane `lane` (0..63) reads for fragment `fragment` of K-step `k_step` of a wavefront
+ * tile that starts at row wave_row (a multiple of 64): one 16-byte read when k_contiguous
+ * (half is ignored), else the transposing 8-byte read number `half` (0 or 1).  After it the
+ * lane holds the 8 (16-byte read) or 4 values of k
+ *     8 * ((64 / fragment_rows) * k_step + lane / fragment_rows) [+ 4 * half] + 0..
+ * of row wave_row + fragment_rows * fragment + lane % fragment_rows; a transposing read hands lane
+ * 16 g + 4 a + b element b of what lanes 16 g + a, + 4, + 8, + 12 fetched. */
+int32_t mg_lds_read_offset(int32_t k_contiguous, int32_t fragment_rows, int32_t tile_rows,
+                           int32_t wave_row, int32_t lane, int32_t fragment, int32_t k_step,
+                           int32_t half);
+
 const char *mg_status_string(mg_status status);
 /* "major.minor" of this ABI. */
 const char *mg_version(void);

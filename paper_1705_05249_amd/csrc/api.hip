@@ -7,6 +7,7 @@
 
 #include "internal.h"
 #include "select.h"
+#include "lds_layout.h"
 
 namespace mg {
 namespace {
@@ -818,6 +819,35 @@ mg_status mg_kernel_info(int32_t kernel_id, mg_config *out)
     if (kernel_id < 0 || kernel_id >= mg_kernel_count() || out == nullptr) return MG_ERR_CONFIG;
     *out = table()[kernel_id].cfg;
     return MG_OK;
+}
+
+int32_t mg_lds_store_offset(int32_t k_contiguous, int32_t fragment_rows, int32_t tile_rows, int32_t row, int32_t k)
+{
+    if ((fragment_rows != 16 && fragment_rows != 32) || tile_rows < 64 || tile_rows > 256 || tile_rows % 64 != 0) return -1;
+    if (row < 0 || row >= tile_rows || k < 0 || k >= 64) return -1;
+    if (k_contiguous)
+        return (fragment_rows == 16 ? mg::ldsmap::kcontig_slot<16>(row, k / 8) : mg::ldsmap::kcontig_slot<32>(row, k / 8)) + 2 * (k % 8);
+    if (tile_rows < 128) return -1;
+    return mg::ldsmap::transposed_slot(tile_rows, k, row / 8) + 2 * (row % 8);
+}
+
+int32_t mg_lds_read_offset(int32_t k_contiguous, int32_t fragment_rows, int32_t tile_rows, int32_t wave_row, int32_t lane,
+                           int32_t fragment, int32_t k_step, int32_t half)
+{
+    if ((fragment_rows != 16 && fragment_rows != 32) || tile_rows < 64 || tile_rows > 256 || tile_rows % 64 != 0) return -1;
+    const int steps = fragment_rows / 8;                        // K-steps per 64 values of k: 4 (32 rows) or 2
+    if (wave_row < 0 || wave_row % 64 != 0 || lane < 0 || lane > 63 || fragment < 0 || k_step < 0 || k_step >= steps) return -1;
+    if (wave_row + fragment_rows * (fragment + 1) > tile_rows || fragment > 7) return -1;
+    if (k_contiguous) {
+        if (fragment_rows == 16)
+            return (mg::ldsmap::kcontig_base<16>(lane, wave_row) ^ mg::ldsmap::kcontig_xor<16>(fragment, k_step)) + fragment * 16 * 128;
+        return (mg::ldsmap::kcontig_base<32>(lane, wave_row) ^ mg::ldsmap::kcontig_xor<32>(fragment, k_step)) + fragment * 32 * 128;
+    }
+    if (tile_rows < 128 || half < 0 || half > 1) return -1;
+    const int line = 2 * tile_rows;
+    const int base = fragment_rows == 16 ? (mg::ldsmap::transposed_base<16>(lane, wave_row, tile_rows) ^ mg::ldsmap::transposed_xor<16>(fragment))
+                                         : (mg::ldsmap::transposed_base<32>(lane, wave_row, tile_rows) ^ mg::ldsmap::transposed_xor<32>(fragment));
+    return base + k_step * (512 / fragment_rows) * line + half * 4 * line;
 }
 
 const char *mg_kernel_name(int32_t kernel_id)

@@ -10,6 +10,7 @@ void register_hmfma_128x64x64_w2x2(std::vector<KernelEntry> &table);
 void register_hmfma_64x64x64_w2x2(std::vector<KernelEntry> &table);
 void register_hdma16_256x256x64(std::vector<KernelEntry> &table);
 void register_hdma16_small(std::vector<KernelEntry> &table);
+void register_hpp16_256x256x64(std::vector<KernelEntry> &table);
 void register_hdma_256x256x64_w2x2(std::vector<KernelEntry> &table);
 void register_hdma_256x256x64_w2x4(std::vector<KernelEntry> &table);
 void register_smfma_256x256x32_w2x2(std::vector<KernelEntry> &table);
@@ -28,6 +29,7 @@ void register_mfma(std::vector<KernelEntry> &table)
     register_hmfma_64x64x64_w2x2(table);
     register_hdma16_256x256x64(table);
     register_hdma16_small(table);
+    register_hpp16_256x256x64(table);
     register_hdma_256x256x64_w2x2(table);
     register_hdma_256x256x64_w2x4(table);
     register_smfma_256x256x32_w2x2(table);

@@ -2,6 +2,7 @@
 #pragma once
 
 #include "mfma_dma_kernel.h"
+#include "mfma_pp_kernel.h"
 #include "mfma_host.h"
 
 namespace mg {
@@ -31,6 +32,28 @@ template <int BM, int BN, int WM, int WN, bool AK, bool BKC, int RB = 32> struct
     {
         KernelEntry e = Staged::entry(name);
         e.legal = legal;
+        e.launch = launch;
+        return e;
+    }
+};
+
+// The kernel whose wavefronts take turns (mfma_pp_kernel.h): 256 x 256 tiles, 2 x 4 wavefronts, 16x16x32 blocks,
+// B contiguous along k.  Same legality as the direct-to-LDS kernels; 1 KB more LDS (the dump area).
+template <bool AK> struct MfmaPpConfig {
+    using Dma = MfmaDmaConfig<256, 256, 2, 4, AK, true, 16>;
+    static constexpr int LDS = Dma::LDS + 1024;
+
+    static hipError_t launch(const Problem &p, int split)
+    {
+        static bool attr_set = false;
+        return launch_tile_kernel<_Float16>(hgemm_pp_kernel<256, 256, 2, 4, AK, true, 16, 1, 8>, &attr_set, LDS, Dma::NT, 256,
+                                            256, Dma::Staged::k_per_split(p, split), p, split);
+    }
+
+    static KernelEntry entry(const char *name)
+    {
+        KernelEntry e = Dma::entry(name);
+        e.cfg.lds_bytes = LDS;
         e.launch = launch;
         return e;
     }

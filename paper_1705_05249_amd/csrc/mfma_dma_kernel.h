@@ -45,7 +45,7 @@ typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
 
 // One operand tile (ROWS rows x 64 k, FP16): global -> LDS.  A wavefront owns COUNT consecutive 1 KB blocks.
-template <int ROWS, int NT, bool KCONTIG> struct DmaLoader {
+template <int ROWS, int NT, bool KCONTIG, int RB = 32> struct DmaLoader {
     static constexpr int LDS_BYTES = ROWS * 128;
     static constexpr int COUNT = LDS_BYTES / (NT * 16);
     static_assert(COUNT >= 1 && COUNT * NT * 16 == LDS_BYTES && (COUNT % 4 == 0 || COUNT < 4), "tile / work-group size");
@@ -62,10 +62,10 @@ template <int ROWS, int NT, bool KCONTIG> struct DmaLoader {
             int64_t g;
             if constexpr (KCONTIG) {
                 const int r = o / 128, slot = (o / 16) % 8;
-                g = r * ld * 2 + ((slot ^ ((r ^ (r >> 3)) & 7)) << 4);
+                g = r * ld * 2 + ((slot ^ ldsmap::swizzle<RB>(r)) << 4);
             } else {
                 const int kl = o / (2 * ROWS), slot = (o / 16) % (ROWS / 8);
-                g = kl * ld * 2 + ((slot ^ (4 * (kl & 3) + 2 * ((kl >> 3) & 1))) << 4);
+                g = kl * ld * 2 + ((slot ^ ldsmap::line_swizzle(kl)) << 4);
             }
             goff[Q] = static_cast<uint32_t>(g - imm(Q));
         });
@@ -114,7 +114,7 @@ __device__ inline u32x4 read_operand(lds_char *lds3, const int (&frag)[8])
     }
 }
 
-template <int BM, int BN, int WM, int WN, bool A_KCONTIG, bool B_KCONTIG, int RB = 32>
+template <int BM, int BN, int WM, int WN, bool A_KCONTIG, bool B_KCONTIG, int RB = 32, int PROBE = 0>
 __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs args)
 {
 #if defined(__HIP_DEVICE_COMPILE__)      // the host pass needs the kernel's symbol only (LDS address-space code is device code)
@@ -124,10 +124,13 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
     constexpr int FM = WTM / RB, FN = WTN / RB;
     constexpr int KSTEPS = BK / ((64 / RB) * 8);
     static_assert(WTM % (2 * RB) == 0 && WTN % (2 * RB) == 0, "wavefront tile: an even number of fragments per side");
+    // the reads issued behind the barrier (next tile, step 0) go to fragment buffer 0 while the MFMAs of the last
+    // step still read their operands: that must be buffer 1
+    static_assert(KSTEPS % 2 == 0, "fragment double buffering needs an even number of K-steps");
     // the [k][row] layout XORs slot numbers up to 14 into a line of ROWS / 8 slots
     static_assert((A_KCONTIG || BM >= 128) && (B_KCONTIG || BN >= 128), "an operand that is not contiguous along k needs 128 rows");
-    using LoadA = DmaLoader<BM, NT, A_KCONTIG>;
-    using LoadB = DmaLoader<BN, NT, B_KCONTIG>;
+    using LoadA = DmaLoader<BM, NT, A_KCONTIG, RB>;
+    using LoadB = DmaLoader<BN, NT, B_KCONTIG, RB>;
     constexpr int A_BYTES = LoadA::LDS_BYTES, B_BYTES = LoadB::LDS_BYTES;   // LDS: [A stage 0][A stage 1][B stage 0][B stage 1]
     constexpr int SLOTS = FM * FN, FRAGS = FM + FN;
     constexpr int PIECES = LoadA::COUNT + LoadB::COUNT;
@@ -154,19 +157,12 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
     int frag_a[8], frag_b[8];          // k-contiguous form: four addresses cover every (fragment, step); else one per fragment
     auto frag_setup = [&](bool kcontig, int wrow, int operand_base, int rows, int (&frag)[8]) {
         if (kcontig) {
-            const int x = frag_lane_x<RB>(lane, wrow);
-            for (int kx = 0; kx < 4; ++kx) frag[kx] = operand_base + (wrow + lane % RB) * 128 + (x ^ (32 * kx));
+            const int p = operand_base + ldsmap::kcontig_base<RB>(lane, wrow);
+            for (int kx = 0; kx < 4; ++kx) frag[kx] = p ^ (32 * kx);
             for (int kx = 4; kx < 8; ++kx) frag[kx] = 0;
         } else {
-            // fetch role inside the group of 16 lanes: rows 4a .. 4a+3 of the group's 16 rows, k line j.
-            // RB = 32: groups 2c, 2c+1 are the two row halves of k chunk c; RB = 16: group g is k chunk g.
-            const int i = lane % 16, a = i % 4, j = i / 4, g = lane / 16;
-            const int chunk = RB == 32 ? g / 2 : g;
-            const int kl = 8 * chunk + j;                                     // + (512 / RB) s + 4 h
-            const int row8 = wrow / 8 + (RB == 32 ? 2 * (g % 2) : 0) + a / 2; // 16-byte slot of the rows; + (RB / 8) f
-            const int slot = row8 ^ (4 * j + 2 * (chunk & 1));
-            const int p = operand_base + kl * (2 * rows) + slot * 16 + 8 * (a % 2);
-            for (int f = 0; f < 8; ++f) frag[f] = p ^ (2 * RB * f);           // fragment f: (RB / 8) f under the same XOR
+            const int p = operand_base + ldsmap::transposed_base<RB>(lane, wrow, rows);
+            for (int f = 0; f < 8; ++f) frag[f] = p ^ ldsmap::transposed_xor<RB>(f);
         }
     };
     frag_setup(A_KCONTIG, wm * WTM, 0, BM, frag_a);
@@ -227,6 +223,7 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
     if (ktiles > 0) {
         aim_tile(0);
         static_for<PIECES>([&](auto P) { issue_piece(P, Stage0{}); });
+        if constexpr ((PROBE & 1) != 0) static_for<PIECES>([&](auto P) { issue_piece(P, Stage1{}); });
         wait_loads();
         __syncthreads();
         static_for<FRAGS>([&](auto F) { read_frag(F, Stage0{}, Step0{}, 0); });
@@ -238,6 +235,19 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
     constexpr int TAIL_READ_SLOTS = TAIL >= 4 ? TAIL * 3 / 4 : TAIL;
     static_assert(PIECES * MG_DMA_SPACING <= BARRIER_SLOT, "loads must be issued before the barrier");
 
+    // PROBE (diagnostic builds only; 0 in every registered kernel): 1 = no global loads in the K loop, 2 = no
+    // fragment reads in the K loop, 4 = cycle stamps around the per-tile wait and barrier, written to args.partial
+    constexpr bool STAMPS = (PROBE & 4) != 0;
+    uint64_t stamp_a = 0, stamp_b = 0, stamp_c = 0, sum_wait = 0, sum_barrier = 0, t_begin = 0, rt_begin = 0;
+    if constexpr (STAMPS) {
+        t_begin = __builtin_amdgcn_s_memtime();
+        rt_begin = __builtin_amdgcn_s_memrealtime();
+    }
+    if constexpr ((PROBE & 2) != 0) {
+        static_for<FM>([&](auto F) { fa[1][decltype(F)::value] = fa[0][decltype(F)::value]; });
+        static_for<FN>([&](auto F) { fb[1][decltype(F)::value] = fb[0][decltype(F)::value]; });
+    }
+
     auto tile_body = [&](auto CUR, int t) {
         using Cur = decltype(CUR);
         using Nxt = std::integral_constant<int, 1 - Cur::value>;
@@ -248,12 +258,20 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
                 constexpr int q = decltype(Q)::value;
                 constexpr int g = s * SLOTS + q;
                 if constexpr (g == BARRIER_SLOT) {
+                    if constexpr (STAMPS) stamp_a = __builtin_amdgcn_s_memtime();
                     wait_loads();
+                    if constexpr (STAMPS) stamp_b = __builtin_amdgcn_s_memtime();
                     __syncthreads();                     // tile t+1 is complete in the other stage
+                    if constexpr (STAMPS) stamp_c = __builtin_amdgcn_s_memtime();
                 }
                 if constexpr (q == 0) wait_fragments();  // this step's operands, read during the previous step
+                if constexpr (STAMPS && g == 0) {
+                    sum_wait += stamp_b - stamp_a;
+                    sum_barrier += stamp_c - stamp_b;
+                }
                 mma(acc[q / FM][q % FM], fb[s & 1][q / FM], fa[s & 1][q % FM], T{});
-                if constexpr (s + 1 < KSTEPS) {
+                if constexpr ((PROBE & 2) != 0) {
+                } else if constexpr (s + 1 < KSTEPS) {
                     if constexpr (q < READ_SLOTS)
                         static_for<share_begin(q + 1, FRAGS, READ_SLOTS) - share_begin(q, FRAGS, READ_SLOTS)>([&](auto R) {
                             constexpr int o = share_begin(q, FRAGS, READ_SLOTS) + decltype(R)::value;
@@ -268,7 +286,7 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
                         read_frag(std::integral_constant<int, f>{}, Nxt{}, Step0{}, 0);
                     });
                 }
-                if constexpr (g % MG_DMA_SPACING == 0 && g / MG_DMA_SPACING < PIECES)
+                if constexpr ((PROBE & 1) == 0 && g % MG_DMA_SPACING == 0 && g / MG_DMA_SPACING < PIECES)
                     issue_piece(std::integral_constant<int, g / MG_DMA_SPACING>{}, Nxt{});
                 __builtin_amdgcn_sched_barrier(0);
             });
@@ -281,8 +299,28 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
     }
     if (t < ktiles) tile_body(Stage0{}, t);
 
+    wait_fragments();       // the reads issued behind the last barrier still write registers: let them land
     __syncthreads();        // all loads have landed (waited for before the last barrier) and all fragment reads are done
-    tile_epilogue<T, RB, FM, FN, WTM, WTN, false>(acc, args, lds, m0, n0, wm, wn, wave, lane);
+    if constexpr (STAMPS) {
+        MfmaArgs plain = args;
+        plain.partial = nullptr;
+        const uint64_t t_loop = __builtin_amdgcn_s_memtime();
+        tile_epilogue<T, RB, FM, FN, WTM, WTN, false>(acc, plain, lds, m0, n0, wm, wn, wave, lane);
+        const uint64_t t_end = __builtin_amdgcn_s_memtime(), rt_end = __builtin_amdgcn_s_memrealtime();
+        if (lane == 0) {
+            uint64_t *out = reinterpret_cast<uint64_t *>(args.partial) + (static_cast<size_t>(blockIdx.x) * (WM * WN) + wave) * 8;
+            out[0] = t_loop - t_begin;
+            out[1] = t_end - t_loop;
+            out[2] = rt_end - rt_begin;
+            out[3] = sum_wait;
+            out[4] = sum_barrier;
+            out[5] = rt_begin;
+            out[6] = rt_end;
+            out[7] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));     // HW_ID
+        }
+    } else {
+        tile_epilogue<T, RB, FM, FN, WTM, WTN, false>(acc, args, lds, m0, n0, wm, wn, wave, lane);
+    }
 #else
     (void)args;
 #endif

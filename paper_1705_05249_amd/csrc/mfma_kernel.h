@@ -39,6 +39,7 @@
 #include <utility>
 
 #include "internal.h"
+#include "lds_layout.h"
 
 #ifndef MG_TAIL_SIXTEENTHS
 #define MG_TAIL_SIXTEENTHS 8   // share (in 1/16) of the last K-step that runs behind the per-tile barrier
@@ -161,7 +162,7 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
     static_assert(NT % CPR == 0 && NT % RCH == 0 && (UPT == 1 || SPLIT == 1), "pieces of a thread are whole lines apart");
 
     // byte offset of logical chunk c of row r inside the operand's LDS tile
-    __device__ static inline int lds_offset(int r, int c) { return r * RS + ((c ^ ((r ^ (r >> 3)) & 7)) << 4); }
+    __device__ static inline int lds_offset(int r, int c) { return ldsmap::kcontig_slot<32>(r, c); }
 
     // Bounds-checked flavour, FP32: whole K-tiles of tiles that have all their rows are loaded like the fast
     // flavour's (ragged problems of 2049^3 to 4104^3: 3-13 % faster; the FP16 kernels lost 10-17 % with the second
@@ -341,19 +342,14 @@ template <int RB> struct BlockAcc;
 template <> struct BlockAcc<32> { using type = floatx16; };
 template <> struct BlockAcc<16> { using type = floatx4; };
 
-// Fragment f of K-step s: row = wrow + RB f + l % RB, logical chunk (64/RB) s + l / RB.  With the swizzle the
-// chunk's byte offset inside the row is frag_lane_x ^ (32 * frag_select): the first is per lane, the second
-// takes four values only, so four addresses per operand cover every fragment (the rest is an immediate
-// offset of f * RB rows).  wrow: first row of the wavefront's tile, a multiple of its power-of-two height.
+// Fragment f of K-step s: row = wrow + RB f + l % RB, logical chunk (64/RB) s + l / RB (lds_layout.h): the
+// lane's address for fragment 0 of step 0, XORed with one of four constants (so four addresses per operand cover
+// every fragment and step), plus an immediate offset of f * RB rows.
 template <int RB> __device__ inline int frag_lane_x(int lane, int wrow)
 {
-    const int lr = lane % RB;
-    return ((lane / RB) ^ (lr & 7) ^ (lr >> 3) ^ ((wrow >> 3) & 7)) << 4;
+    return ldsmap::kcontig_base<RB>(lane, wrow) - (wrow + lane % RB) * 128;
 }
-template <int RB> constexpr int frag_select(int f, int s)
-{
-    return RB == 32 ? ((s ^ (2 * (f & 1))) & 3) : (((2 * s) ^ (f & 3)) & 3);
-}
+template <int RB> constexpr int frag_select(int f, int s) { return ldsmap::kcontig_xor<RB>(f, s) / 32; }
 
 // N elements at element alignment
 template <typename U, int N> struct __attribute__((packed, aligned(sizeof(U)))) Pack {
@@ -543,6 +539,8 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
     static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % ((128 / RB) * CH) == 0 && KSTEPS >= 2, "tile shape");
     static_assert(RB == 32 || (RB == 16 && sizeof(T) == 2 && WTM % 64 == 0 && WTN % 64 == 0), "MFMA block shape");
     static_assert((WTM & (WTM - 1)) == 0 && (WTN & (WTN - 1)) == 0, "wavefront tile sides are powers of two");
+    // the first fragments of the next tile go to fragment buffer 0 while the last step still uses its operands
+    static_assert(KSTEPS % 2 == 0, "fragment double buffering needs an even number of K-steps");
     using LoadA = TileLoader<T, BM, BK, NT, A_KCONTIG, EDGE>;
     using LoadB = TileLoader<T, BN, BK, NT, B_KCONTIG, EDGE>;
     // LDS: [A stage 0][A stage 1][B stage 0][B stage 1]; stage offsets are compile-time in the unrolled K loop

@@ -27,7 +27,8 @@ EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemv", "mg_hgemv", "mg_gemv_workspace_by
            "mg_sim2col", "mg_him2col", "mg_sconv2d", "mg_hconv2d", "mg_conv2d_workspace_bytes", "mg_conv2d_out_extent",
            "mg_kernel_count",
            "mg_kernel_info", "mg_kernel_name", "mg_query_selected", "mg_override_config",
-           "mg_override_batched_config", "mg_clear_override", "mg_status_string", "mg_version")
+           "mg_override_batched_config", "mg_clear_override", "mg_lds_store_offset", "mg_lds_read_offset",
+           "mg_status_string", "mg_version")
 
 
 class mg_config(ctypes.Structure):
@@ -130,6 +131,10 @@ def lib():
         L.mg_override_batched_config.restype = i32
         L.mg_clear_override.argtypes = []
         L.mg_clear_override.restype = None
+        L.mg_lds_store_offset.argtypes = [ctypes.c_int32] * 5
+        L.mg_lds_store_offset.restype = ctypes.c_int32
+        L.mg_lds_read_offset.argtypes = [ctypes.c_int32] * 8
+        L.mg_lds_read_offset.restype = ctypes.c_int32
         L.mg_status_string.argtypes = [i32]
         L.mg_status_string.restype = ctypes.c_char_p
         L.mg_version.argtypes = []
@@ -380,6 +385,14 @@ def mg_kernel_info(kernel_id: int) -> dict:
 
 def mg_kernel_name(kernel_id: int) -> str:
     return lib().mg_kernel_name(kernel_id).decode()
+
+
+def mg_lds_store_offset(k_contiguous, fragment_rows, tile_rows, row, k) -> int:
+    return lib().mg_lds_store_offset(int(bool(k_contiguous)), fragment_rows, tile_rows, row, k)
+
+
+def mg_lds_read_offset(k_contiguous, fragment_rows, tile_rows, wave_row, lane, fragment, k_step, half=0) -> int:
+    return lib().mg_lds_read_offset(int(bool(k_contiguous)), fragment_rows, tile_rows, wave_row, lane, fragment, k_step, half)
 
 
 def mg_query_selected(dtype, layout, trans_a, trans_b, m, n, k, lda, ldb, ldc, alpha=1.0, beta=0.0,

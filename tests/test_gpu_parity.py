@@ -419,7 +419,7 @@ def test_direct_to_lds_kernels(G, oracle, shape):
     """every direct-to-LDS kernel, all operand orders: one K-tile, an odd number of K-tiles, several tiles of C;
     bit-exact on integers (beta = 1) and within tolerance on random data"""
     m, n, k = shape
-    names = [t["name"] for t in G.kernel_table() if t["name"].startswith("hdma")]
+    names = [t["name"] for t in G.kernel_table() if t["name"].startswith(("hdma", "hpp"))]
     assert names
     orders = {"mk": (N, N), "kk": (T, N), "mn": (N, T), "kn": (T, T)}
     try:
