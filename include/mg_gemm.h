@@ -239,6 +239,22 @@ mg_status mg_hgemm_strided_batched(int layout, int trans_a, int trans_b, int64_t
                                    uint16_t *C, int64_t ldc, int64_t stride_c,
                                    int64_t batch_count, void *stream);
 
+/* mg_sgemm for callers that can neither allocate nor own a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The scratch memory (split-K
+ * partial sums, padded copies of the indirect route) is an array of MG_STATIC_SCRATCH_BYTES inside
+ * the library, one per GPU, held until the process ends; the call allocates and frees nothing.
+ * Arguments, results and errors as mg_sgemm, with these differences: a problem whose preferred
+ * route needs more scratch than the array holds (mg_gemm_workspace_bytes() > MG_STATIC_SCRATCH_BYTES)
+ * is refused with MG_ERR_WORKSPACE and nothing is launched; MG_ERR_LAUNCH if the array's address
+ * on the current device cannot be had.  Every call on a GPU uses that GPU's one array: calls that
+ * overlap in time on one GPU (different streams, different threads) race on it and must be
+ * ordered by the caller.  Nothing in the array has to start at zero (every slice of the sum
+ * writes all its partial sums before they are read), and nothing in it outlives a call. */
+#define MG_STATIC_SCRATCH_BYTES (16u << 20)
+mg_status mg_sgemm_static(int layout, int trans_a, int trans_b, int64_t m, int64_t n, int64_t k,
+                          float alpha, const float *A, int64_t lda, const float *B, int64_t ldb,
+                          float beta, float *C, int64_t ldc, void *stream);
+
 /* Bytes of workspace with which this problem runs its preferred route: the split-K partial sums
  * of the selected configuration, or the padded copies of the indirect FP16 route (0 for most
  * problems).  Any smaller workspace is legal and selects a route that fits.  dtype is an mg_dtype.

@@ -580,7 +580,46 @@ mg_status run_trmm(int dtype, int layout, int side, int uplo, int trans, int dia
 
 using namespace mg;
 
+// ---- the entry point that brings its own scratch memory --------------------------------------------------
+// Device memory of the library itself, one copy per GPU, held until the process ends.  In host code the array's
+// name is a stand-in, not a device address: the address on the current device comes from hipGetSymbolAddress,
+// once per device, and only that pointer is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[MG_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_address[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+mg_status static_scratch(void **out)
+{
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return MG_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_address[device] == nullptr) {
+        void *address = nullptr;
+        if (hipGetSymbolAddress(&address, HIP_SYMBOL(scratch)) != hipSuccess || address == nullptr) return MG_ERR_LAUNCH;
+        g_scratch_address[device] = address;
+    }
+    *out = g_scratch_address[device];
+    return MG_OK;
+}
+}  // namespace
+
 extern "C" {
+
+mg_status mg_sgemm_static(int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, float alpha, const float *A,
+                          int64_t lda, const float *B, int64_t ldb, float beta, float *C, int64_t ldc, void *stream)
+{
+    // what the preferred route of this problem would use (0 for invalid arguments: run_gemm names the error)
+    if (mg_gemm_workspace_bytes(MG_F32, layout, ta, tb, m, n, k, lda, ldb, ldc) > MG_STATIC_SCRATCH_BYTES)
+        return MG_ERR_WORKSPACE;
+    void *ws = nullptr;
+    const mg_status s = static_scratch(&ws);
+    if (s != MG_OK) return s;
+    return run_gemm(MG_F32, layout, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, ws, MG_STATIC_SCRATCH_BYTES,
+                    stream);
+}
 
 mg_status mg_sgemm(int layout, int ta, int tb, int64_t m, int64_t n, int64_t k, float alpha, const float *A,
                    int64_t lda, const float *B, int64_t ldb, float beta, float *C, int64_t ldc, void *workspace,

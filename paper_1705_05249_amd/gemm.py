@@ -20,7 +20,7 @@ MG_LEFT, MG_RIGHT = 141, 142
 MG_OK = 0
 MG_FAMILY_DIRECT, MG_FAMILY_MFMA, MG_FAMILY_GEMV, MG_FAMILY_SCALE, MG_FAMILY_BATCHED = 0, 1, 2, 3, 4
 
-EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemv", "mg_hgemv", "mg_gemv_workspace_bytes",
+EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemm_static", "mg_sgemv", "mg_hgemv", "mg_gemv_workspace_bytes",
            "mg_ssymm", "mg_hsymm", "mg_ssyrk", "mg_hsyrk", "mg_strmm", "mg_htrmm", "mg_symm_workspace_bytes",
            "mg_syrk_workspace_bytes", "mg_trmm_workspace_bytes", "mg_sgemm_batched", "mg_sgemm_strided_batched", "mg_hgemm_batched",
            "mg_hgemm_strided_batched", "mg_gemm_workspace_bytes",
@@ -70,6 +70,8 @@ def lib():
         L.mg_sgemm.restype = i32
         L.mg_hgemm.argtypes = gemm_args
         L.mg_hgemm.restype = i32
+        L.mg_sgemm_static.argtypes = gemm_args[:14] + [vp]
+        L.mg_sgemm_static.restype = i32
         gemv_args = [i32, i32, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64, vp, sz, vp]
         L.mg_sgemv.argtypes = gemv_args
         L.mg_sgemv.restype = i32
@@ -175,6 +177,17 @@ def mg_sgemm(layout, trans_a, trans_b, m, n, k, alpha, A, lda, B, ldb, beta, C, 
                         ldc, ws, ws_bytes, _stream(stream))
     if check and st != MG_OK:
         raise MgError(st, "mg_sgemm")
+    return st
+
+
+MG_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def mg_sgemm_static(layout, trans_a, trans_b, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream=None, check=True) -> int:
+    st = lib().mg_sgemm_static(layout, trans_a, trans_b, m, n, k, alpha, _addr(A), lda, _addr(B), ldb, beta, _addr(C),
+                               ldc, _stream(stream))
+    if check and st != MG_OK:
+        raise MgError(st, "mg_sgemm_static")
     return st
 
 
