@@ -1,14 +1,15 @@
 """Benchmark of the GEMM hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--only GROUP] [--no-cpu-baseline]
 
-One "step" is one mg_hgemm call on the headline workload: FP16 storage / FP32 accumulation,
-column-major, op(A)=A, op(B)=B, m=n=k=4096, alpha=1, beta=0, entries N(0, K^-1/2) rounded to
-FP16 (seeded, synthetic).  Inputs are resident in HBM before the timed region; W warm-up
-steps, then exactly K steps between two device synchronisations.  Prints ONE JSON line:
-GFLOPS = 2mnk/t, the MFMA roofline of the kernel, the CPU oracle timed on a bounded sample of
-the same workload (cpu_baseline), and -- measured the same way right after -- the other two
-workloads of the metric (SGEMM 4096^3 and batched 10000 x 16^3) under "workloads".
+One "step" is one mg_hgemm call on the headline workload: FP16 storage / FP32 accumulation, column-major,
+op(A)=A, op(B)=B, m=n=k=4096, alpha=1, beta=0, entries N(0, K^-1/2) rounded to FP16 (seeded, synthetic).  Inputs are
+resident in HBM before the timed region; W warm-up steps, then exactly K steps between two device
+synchronisations.  Prints ONE JSON line: GFLOPS = 2mnk/t, the MFMA roofline of the kernel, the CPU oracle timed on
+a bounded sample of the same workload (cpu_baseline), and under "workloads" every other workload of the five
+configurations (each with the roofline that bounds it), the cold (HBM-real) variants of the small ones, the
+launch floor, the rate of the matrix pipes alone, where the headline kernel's time goes ("accounting"), and the
+paper's own figures for context ("paper_context").
 """
 import argparse
 import json
@@ -22,86 +23,30 @@ if ROOT not in sys.path:
 
 PEAK_TFLOPS = {"f16": 2500.0, "f32": 157.3}     # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
+GROUPS = ("hgemm", "probes", "config1", "config2", "sgemm", "config3", "config4", "batched", "config5", "conv", "gemv",
+          "level3", "copy")
 
-# HBM traffic per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
-# counters read for a plain copy kernel of known size (profiles/ holds the summaries these come from).
-MEASURED_TRAFFIC_BYTES = {"hgemm_4096": 235042978, "sgemm_4096": 470094977, "batched_16x10000": 42897824,
-                          "sgemv_16384_N": 1075332914, "sgemv_16384_T": 1074414473}
-
-
-def timed(fn, steps, warmup):
-    import torch
-    for _ in range(warmup):
-        fn()
-    torch.cuda.synchronize()
-    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    wall0 = time.perf_counter()
-    start.record()
-    for _ in range(steps):
-        fn()
-    stop.record()
-    torch.cuda.synchronize()
-    wall = (time.perf_counter() - wall0) / steps
-    dev = start.elapsed_time(stop) * 1e-3 / steps          # HIP events on the stream the kernels run on
-    return dev, wall
+# What the paper itself reports for this path (its OpenCL devices of 2012-2017; context, not targets).
+PAPER_CONTEXT = [
+    "HGEMM: 'over 200 GFLOPS' on Intel Skylake ULT GT2 (peak 384 GFLOPS FP32, 30 GB/s), FP16 compute (Section 4.4)",
+    "HGEMM about 2x SGEMM on Skylake ULT GT2 and ARM Mali T628 (Section 4.4)",
+    "batched GEMM 'up to an order of magnitude' faster than a loop of small GEMMs on GTX 750Ti and Skylake ULT GT2 (Section 4.6)",
+    "generic batched up to 2x slower than strided batched on GTX 750Ti: per-instance offsets and scalars (Section 4.6)",
+    "problem-specific tuning gains up to 2x on Radeon M370X, 9 sizes x 9 parameter sets (Section 4.3)",
+    "device peaks of the paper's Table 2 (GFLOPS FP32 - GB/s): GTX 750Ti 1305-88, Titan X Pascal 10974-480, HD7970 3789-264, "
+    "M370X 1024-72, Skylake ULT GT2 384-30, Mali T628 38-15",
+]
 
 
-def graph_timed(call, c_buffer, steps, warmup, per_graph=20):
-    """Device time per call of a microsecond-scale launch: shorter than the host can issue launches (about
-    8 us per call from Python), so the call is captured once into a HIP graph of `per_graph` launches and the
-    graph is replayed; the events then bracket back-to-back kernels.  Every replay of a one-launch graph is
-    first checked against the eager result.  Returns (seconds per call from replays, from eager launches)."""
-    import torch
-    c0 = c_buffer.clone()
-    call()
-    eager = c_buffer.clone()
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):
-        call()                                       # warm-up on a capture-capable stream
-    torch.cuda.current_stream().wait_stream(side)
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
-        for _ in range(per_graph):
-            call()
-    one = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(one):
-        call()
-    for _ in range(3):
-        c_buffer.copy_(c0)
-        one.replay()
-        torch.cuda.synchronize()
-        assert torch.equal(c_buffer, eager), "graph replay differs from the eager call"
-    dev, _ = timed(graph.replay, max(1, steps // 2), max(1, warmup // 4))
-    dev_eager, _ = timed(call, steps, warmup)
-    return dev / per_graph, dev_eager
-
-
-def gemm_workload(G, case, steps, warmup):
-    import torch
-    from tests import helpers as H
-    fn = G.mg_sgemm if case.dtype == "f32" else G.mg_hgemm
-    code = G.MG_F32 if case.dtype == "f32" else G.MG_F16
-    A, B, C = H.to_gpu(case.A), H.to_gpu(case.B), H.to_gpu(case.C)
-    need = G.mg_gemm_workspace_bytes(code, case.layout, case.ta, case.tb, case.m, case.n, case.k, case.lda,
-                                     case.ldb, case.ldc)
-    ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda") if need else None
-    sel = G.mg_query_selected(code, case.layout, case.ta, case.tb, case.m, case.n, case.k, case.lda, case.ldb,
-                              case.ldc, case.alpha, case.beta)
-
-    def call():
-        fn(case.layout, case.ta, case.tb, case.m, case.n, case.k, case.alpha, A, case.lda, B, case.ldb, case.beta,
-           C, case.ldc, ws)
-
-    dev, wall = timed(call, steps, warmup)
-    return dev, wall, sel, C
-
-
-def roofline_mfma(case, seconds, key):
-    tf = case.flops / seconds / 1e12
-    peak = PEAK_TFLOPS[case.dtype]
-    return {"bound": "mfma", "achieved": round(tf, 2), "peak": peak, "unit": "TFLOP/s",
-            "frac": round(tf / peak, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(key)}
+def measured_traffic():
+    """HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, as written to profiles/traffic.json
+    together with the commit they were measured at (never measured in this run: null where the file has no entry)."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f)
+    except (OSError, ValueError):
+        return {"measured_at_commit": None, "bytes_per_launch": {}}
 
 
 def main():
@@ -110,21 +55,85 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
-    ap.add_argument("--only", default=None, help="hgemm | sgemm | batched | conv | gemv | level3 | copy: run a single workload (profiling runs)")
+    ap.add_argument("--only", default=None, help=" | ".join(GROUPS) + ": run a single group (profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+    if args.only is not None and args.only not in GROUPS:
+        sys.exit(f"--only takes one of {GROUPS}")
 
     import numpy as np
     import torch
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
-    from paper_1705_05249_amd import gemm as G, workloads as W
-    from tests import helpers as H
+    from paper_1705_05249_amd import gemm as G, measure as M, workloads as W
     G.lib()
     G.mg_clear_override()
     steps, warmup = args.steps, args.warmup
     extra = []
+    traffic = measured_traffic()
+
+    def want(*groups):
+        return args.only is None or args.only in groups
+
+    def roofline(bound, work, seconds, peak, key):
+        """work: algorithmic flops (bound mfma) or bytes (bound hbm) of one launch"""
+        if bound == "mfma":
+            achieved, unit = work / seconds / 1e12, "TFLOP/s"
+        else:
+            achieved, unit = work / seconds / 1e9, "GB/s"
+        return {"bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit, "frac": round(achieved / peak, 4),
+                "traffic": traffic["bytes_per_launch"].get(key)}
+
+    def gemm_setup(case):
+        fn = G.mg_sgemm if case.dtype == "f32" else G.mg_hgemm
+        code = G.MG_F32 if case.dtype == "f32" else G.MG_F16
+        A, B, C = M.to_gpu(case.A), M.to_gpu(case.B), M.to_gpu(case.C)
+        need = G.mg_gemm_workspace_bytes(code, case.layout, case.ta, case.tb, case.m, case.n, case.k, case.lda, case.ldb,
+                                         case.ldc)
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda") if need else None
+        sel = G.mg_query_selected(code, case.layout, case.ta, case.tb, case.m, case.n, case.k, case.lda, case.ldb, case.ldc,
+                                  case.alpha, case.beta)
+
+        def call_on(a, b, c):
+            return lambda: fn(case.layout, case.ta, case.tb, case.m, case.n, case.k, case.alpha, a, case.lda, b, case.ldb,
+                              case.beta, c, case.ldc, ws)
+
+        return A, B, C, sel, call_on
+
+    def gemm_entry(label, case, bound, key=None, small=False, cold=False, reps=None):
+        """one GEMM workload: events around back-to-back calls, or (small) graph replays; cold: also the time per call
+        when the operands come from HBM (a cycle through copies that together exceed the last-level cache four times)"""
+        A, B, C, sel, call_on = gemm_setup(case)
+        entry = {"workload": label, "kernel": sel["name"] + (f" split {sel['split_k']}" if sel["split_k"] > 1 else "")}
+        if small:
+            dev, dev_eager = M.graph_timed(call_on(A, B, C), C, steps, warmup)
+            entry["ms_eager_launches"] = round(dev_eager * 1e3, 5)
+        else:
+            dev, _ = M.timed(call_on(A, B, C), reps or max(5, steps // 5), max(1, warmup // 4))
+        entry["gflops"] = round(case.flops / dev / 1e9, 1)
+        entry["ms"] = round(dev * 1e3, 5)
+        peak = PEAK_TFLOPS[case.dtype] if bound == "mfma" else PEAK_HBM_GBS
+        work = case.flops if bound == "mfma" else case.algorithmic_bytes
+        entry["roofline"] = roofline(bound, work, dev, peak, key or label)
+        nbytes = A.numel() * A.element_size() + B.numel() * B.element_size() + C.numel() * C.element_size()
+        if nbytes < M.LAST_LEVEL_CACHE_BYTES:
+            entry["note"] = (f"{nbytes / 1e6:.1f} MB of operands: repeated calls are served by the 256 MB last-level cache"
+                             + ("; timed as replays of a HIP graph of 20 launches" if small else ""))
+        if cold:
+            copies = []
+
+            def make_call(i):
+                copies.append((A.clone(), B.clone(), C.clone()))
+                return call_on(*copies[-1])
+
+            dev_cold, sets = M.cold_timed(make_call, nbytes)
+            entry["cold"] = {"ms": round(dev_cold * 1e3, 5), "gflops": round(case.flops / dev_cold / 1e9, 1), "sets": sets,
+                             "roofline": roofline(bound, work, dev_cold, peak, None),
+                             "note": f"graph replay of one cycle over {sets} distinct copies of A, B, C ({sets * nbytes / 2**30:.2f} GiB)"}
+            del copies
+        extra.append(entry)
+        return entry
 
     if args.only == "copy":
         # calibration for the FETCH_SIZE / WRITE_SIZE counters: a plain device copy of known size
@@ -139,9 +148,10 @@ def main():
 
     # ---- headline: HGEMM 4096^3 ------------------------------------------------------------------
     head = None
-    if args.only in (None, "hgemm"):
+    if want("hgemm"):
         case = W.config3(4)
-        dev, wall, sel, C = gemm_workload(G, case, steps, warmup)
+        A, B, C, sel, call_on = gemm_setup(case)
+        dev, wall = M.timed(call_on(A, B, C), steps, warmup)
         head = {"case": case, "dev": dev, "wall": wall, "sel": sel}
         cpu = None
         if not args.no_cpu_baseline:
@@ -154,94 +164,176 @@ def main():
                                                     case.C, case.ldc, rows, cols)
             t_cpu = time.perf_counter() - t0
             got = W.unpack(C.cpu().numpy(), case.layout, case.m, case.n, case.ldc)[rows, cols]
-            err = H.rel_error(got, c_ref, d_ref)
-            assert err <= H.TOL["f16"], f"benchmark output fails parity: {err}"
+            err = M.rel_error(got, c_ref, d_ref)
+            assert err <= 2e-3, f"benchmark output fails parity: {err}"
             cpu = {"value": round(2.0 * case.k * rows.size / t_cpu / 1e9, 3), "unit": "GFLOPS",
                    "cores": gemm_oracle.threads(), "kind": "oracle",
                    "sample": f"{rows.size} of {case.m * case.n} output entries (256 full rows, 256 full columns, "
                              f"8192 scattered), each a full k={case.k} FP64 dot product; {t_cpu:.1f} s",
                    "max_rel_err_gpu_vs_oracle": float(f"{err:.3e}")}
         head["cpu"] = cpu
+        head["buffers"] = (A, B, C)
 
-    # ---- the other two workloads of the metric ----------------------------------------------------
-    if args.only in (None, "sgemm"):
-        logical = W.config2_logical(4096)
-        case = W.config2_variant(4096, W.COL_MAJOR, W.NO_TRANS, W.NO_TRANS, 0.0, logical)
-        dev, wall, sel, _ = gemm_workload(G, case, max(5, steps // 5), max(1, warmup // 2))
-        extra.append({"workload": "sgemm_f32_4096x4096x4096_colmajor_NN_beta0", "gflops": round(case.flops / dev / 1e9, 1),
-                      "ms": round(dev * 1e3, 4), "kernel": sel["name"], "roofline": roofline_mfma(case, dev, "sgemm_4096")})
-        del logical
-    if args.only in (None, "batched"):
-        bc = W.config4_fast(16, 10000)
-        t = {name: H.to_gpu(getattr(bc, name)) for name in ("A", "B", "C", "a_off", "b_off", "c_off", "alphas", "betas")}
-        stride = int(bc.a_off[1] - bc.a_off[0])
+    # ---- what the fractions are judged against: launch floor, the matrix pipes alone, where the kernel's time goes
+    probes = {}
+    if want("probes", "hgemm"):
+        flag = torch.zeros(1, dtype=torch.float32, device="cuda")
+        floor_graph, floor_eager = M.graph_timed(lambda: G.mg_probe_empty_launch(), flag, steps, warmup)
+        probes["launch_floor"] = {"us_back_to_back_in_a_graph": round(floor_graph * 1e6, 3),
+                                  "us_eager_from_python": round(floor_eager * 1e6, 3),
+                                  "note": "one empty kernel of one wavefront per launch"}
+        rounds = 128                      # 2 * 16*16*32 * 32 * rounds * 2048 wavefronts = the flops of 4096^3
+        flops = 2.0 * 16 * 16 * 32 * 32 * rounds * 2048
+        dev, _ = M.timed(lambda: G.mg_probe_mfma_only(rounds, flag), max(5, steps // 4), max(1, warmup // 4))
+        probes["mfma_pipes_alone"] = {"ms": round(dev * 1e3, 5), "tflops": round(flops / dev / 1e12, 1),
+                                      "frac_of_peak": round(flops / dev / 1e12 / PEAK_TFLOPS["f16"], 4),
+                                      "note": "v_mfma_f32_16x16x32_f16 only, register operands that change with every "
+                                              "instruction, two wavefronts per SIMD, the flops of one 4096^3 product: "
+                                              "what the part sustains at the clock it holds under this load"}
+        if head is not None:
+            A, B, C = head["buffers"]
+            case = head["case"]
+            per = 12
+            groups = (case.m // 256) * (case.n // 256)
+            stamps = [torch.zeros(groups * 8 * per, dtype=torch.int64, device="cuda") for _ in range(3)]
+            for _ in range(3):
+                G.mg_probe_hgemm_stamps(case.m, case.n, case.k, A, case.lda, B, case.ldb, C, case.ldc, stamps[0])
+            for s in stamps:               # three launches back to back
+                G.mg_probe_hgemm_stamps(case.m, case.n, case.k, A, case.lda, B, case.ldb, C, case.ldc, s)
+            torch.cuda.synchronize()
+            h = [s.cpu().numpy().reshape(groups * 8, per).astype(np.float64) for s in stamps]
+            mid = h[1]
+            ktiles = case.k // 64
+            clock = (mid[:, 0] + mid[:, 1]) / mid[:, 2] * 0.1                  # GHz per wavefront
+            by_die = {}
+            for die in sorted(set(mid[:, 10].astype(int))):
+                rows_ = mid[mid[:, 10] == die]
+                by_die[str(die)] = {"clock_ghz": round(float(((rows_[:, 0] + rows_[:, 1]) / rows_[:, 2]).mean() * 0.1), 3),
+                                    "us": round(float(rows_[:, 2].mean() * 0.01), 2)}
+            span = lambda x: (x[:, 8].min(), x[:, 8].max(), x[:, 9].min(), x[:, 9].max())
+            b0, b1, e0, e1 = span(h[1])
+            _, _, _, prev_end = span(h[0])
+            nb0, _, _, _ = span(h[2])
+            loop = mid[:, 0] - mid[:, 7]
+            probes["accounting_hgemm_4096"] = {
+                "kernel": "the selected kernel built with cycle stamps (mg_probe_hgemm_stamps), second of three back-to-back launches",
+                "us_launch_period": round(float(nb0 - b0) * 0.01, 2),
+                "us_gap_last_wavefront_end_to_next_first_start": round(float(b0 - prev_end) * 0.01, 2),
+                "us_first_to_last_wavefront_start": round(float(b1 - b0) * 0.01, 2),
+                "us_first_to_last_wavefront_end": round(float(e1 - e0) * 0.01, 2),
+                "us_wavefront_mean": round(float(mid[:, 2].mean()) * 0.01, 2),
+                "us_wavefront_slowest_die": max(v["us"] for v in by_die.values()),
+                "clock_ghz_mean": round(float(clock.mean()), 3),
+                "per_die": by_die,
+                "ticks_to_first_tile": round(float(mid[:, 7].mean())),
+                "ticks_k_loop_per_tile": round(float(loop.mean()) / ktiles, 1),
+                "ticks_mfma_run_per_tile": round(float(mid[:, 5].mean()) / ktiles, 1),
+                "ticks_lds_reads_per_tile": round(float(mid[:, 3].mean()) / ktiles, 1),
+                "ticks_barrier_waits_per_tile": round(float((mid[:, 4] + mid[:, 6]).mean()) / ktiles, 1),
+                "ticks_epilogue": round(float(mid[:, 1].mean())),
+                "ideal_ticks_per_tile": 2048,
+                "note": "ticks of the shader clock; a K-tile is 2 x 64 MFMAs of 16 cycles per SIMD = 2048 cycles at best; "
+                        "the kernel ends with its slowest die; at the mean clock and 2048 ticks per tile the K loops "
+                        f"alone take {ktiles * 2048 / float(clock.mean()) * 1e-3:.1f} us",
+            }
+            head.pop("buffers")
 
-        def generic():
-            G.mg_sgemm_batched(bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, t["alphas"], t["A"], t["a_off"], bc.lda,
-                               t["B"], t["b_off"], bc.ldb, t["betas"], t["C"], t["c_off"], bc.ldc, bc.batch)
+    # ---- configuration 1: 256^3 (launch- and latency-bound) -----------------------------------------
+    if want("config1"):
+        gemm_entry("sgemm_f32_256x256x256_colmajor_NN_alpha1.5_beta0.5", W.config1(integer=False), "mfma", small=True, cold=True)
 
-        def strided():
-            G.mg_sgemm_strided_batched(bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, 1.25, t["A"], bc.lda, stride, t["B"],
-                                       bc.ldb, stride, 0.75, t["C"], bc.ldc, stride, bc.batch)
+    # ---- configuration 2: FP32 squares, the four operand orders, both layouts -----------------------
+    if want("config2", "sgemm"):
+        N, T, CM, RM = W.NO_TRANS, W.TRANS, W.COL_MAJOR, W.ROW_MAJOR
+        sizes = (4096,) if args.only == "sgemm" else W.CONFIG2_SIZES
+        for size in sizes:
+            logical = W.config2_logical(size)
+            variants = [(CM, N, N, 0.0)]
+            if size == 4096 and args.only != "sgemm":
+                variants += [(CM, T, N, 0.7), (CM, N, T, 0.7), (CM, T, T, 0.7), (RM, N, N, 0.7)]
+            for layout, ta, tb, beta in variants:
+                case = W.config2_variant(size, layout, ta, tb, beta, logical)
+                tag = ("rowmajor" if layout == RM else "colmajor") + "_" + ("T" if ta == T else "N") + ("T" if tb == T else "N")
+                label = f"sgemm_f32_{size}x{size}x{size}_{tag}_beta{beta:g}"
+                gemm_entry(label, case, "mfma", key="sgemm_f32_4096x4096x4096_colmajor_NN_beta0" if label.endswith("4096_colmajor_NN_beta0") else None,
+                           small=size <= 1024, reps=3 if size >= 8192 else None)
+            del logical
 
-        note = ("timed as replays of a HIP graph of 20 launches (host launch rate is ~8 us/call); "
-                "41 MB working set: repeated calls are served by the 256 MB last-level cache")
-        for label, call, scalar_bytes in (("sgemm_batched_f32_10000x16x16x16_gap7", generic, 32),
-                                          ("sgemm_strided_batched_f32_10000x16x16x16_gap7", strided, 0)):
-            dev, dev_eager = graph_timed(call, t["C"], steps, warmup)
-            nbytes = bc.algorithmic_bytes - bc.batch * (32 - scalar_bytes)
-            gbs = nbytes / dev / 1e9
-            extra.append({"workload": label, "gflops": round(bc.flops / dev / 1e9, 1), "ms": round(dev * 1e3, 5),
-                          "ms_eager_launches": round(dev_eager * 1e3, 5),
-                          "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                       "frac": round(gbs / PEAK_HBM_GBS, 4),
-                                       "traffic": MEASURED_TRAFFIC_BYTES.get("batched_16x10000") if scalar_bytes else None},
-                          "note": note})
+    # ---- configuration 3: the FP16 convolution-as-GEMM shapes alone ----------------------------------
+    if want("config3"):
+        for index in range(4):
+            case = W.config3(index)
+            gemm_entry(f"hgemm_f16_{case.m}x{case.n}x{case.k}_colmajor_NN_beta0", case, "hbm", small=True, cold=True)
+            extra[-1]["roofline_mfma"] = {"bound": "mfma", "achieved": round(extra[-1]["gflops"] / 1e3, 2), "peak": PEAK_TFLOPS["f16"],
+                                          "unit": "TFLOP/s", "frac": round(extra[-1]["gflops"] / 1e3 / PEAK_TFLOPS["f16"], 4)}
 
-    # ---- next row: the batched workload in FP16 storage
-    if args.only in (None, "batched"):
-        hb = W.config4_fast(16, 10000, dtype="f16")
-        th = {name: H.to_gpu(getattr(hb, name)) for name in ("A", "B", "C", "a_off", "b_off", "c_off", "alphas", "betas")}
+    # ---- configuration 4: batched GEMM -------------------------------------------------------------
+    if want("config4", "batched"):
+        def batched_entry(label, bc, strided=False, cold_batch=None):
+            half = bc.dtype == "f16"
+            t = {name: M.to_gpu(getattr(bc, name)) for name in ("A", "B", "C", "a_off", "b_off", "c_off", "alphas", "betas")}
+            stride = int(bc.a_off[1] - bc.a_off[0])
+            generic_fn = G.mg_hgemm_batched if half else G.mg_sgemm_batched
+            strided_fn = G.mg_hgemm_strided_batched if half else G.mg_sgemm_strided_batched
+            if strided:
+                call = lambda: strided_fn(bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, 1.25, t["A"], bc.lda, stride, t["B"], bc.ldb,
+                                          stride, 0.75, t["C"], bc.ldc, stride, bc.batch)
+            else:
+                call = lambda: generic_fn(bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, t["alphas"], t["A"], t["a_off"], bc.lda,
+                                          t["B"], t["b_off"], bc.ldb, t["betas"], t["C"], t["c_off"], bc.ldc, bc.batch)
+            dev, dev_eager = M.graph_timed(call, t["C"], steps, warmup)
+            nbytes = bc.algorithmic_bytes - (bc.batch * 32 if strided else 0)
+            resident = sum(t[x].numel() * t[x].element_size() for x in ("A", "B", "C"))
+            entry = {"workload": label, "gflops": round(bc.flops / dev / 1e9, 1), "ms": round(dev * 1e3, 5),
+                     "ms_eager_launches": round(dev_eager * 1e3, 5),
+                     "roofline": roofline("hbm", nbytes, dev, PEAK_HBM_GBS, label),
+                     "note": "timed as replays of a HIP graph of 20 launches; "
+                             + (f"{resident / 1e6:.0f} MB working set: repeated calls are served by the 256 MB last-level cache"
+                                if resident < M.LAST_LEVEL_CACHE_BYTES else f"{resident / 1e6:.0f} MB working set: beyond the last-level cache, HBM-real")}
+            extra.append(entry)
 
-        def half_generic():
-            G.mg_hgemm_batched(hb.layout, hb.ta, hb.tb, hb.m, hb.n, hb.k, th["alphas"], th["A"], th["a_off"], hb.lda,
-                               th["B"], th["b_off"], hb.ldb, th["betas"], th["C"], th["c_off"], hb.ldc, hb.batch)
+        only_headline = args.only == "batched"
+        for size in ((16,) if only_headline else (8, 16, 32, 64)):
+            for batch in ((10000,) if only_headline else (1000, 10000)):
+                batched_entry(f"sgemm_batched_f32_{batch}x{size}x{size}x{size}_gap7", W.config4_fast(size, batch))
+        batched_entry("sgemm_strided_batched_f32_10000x16x16x16_gap7", W.config4_fast(16, 10000), strided=True)
+        batched_entry("hgemm_batched_f16_10000x16x16x16_gap7", W.config4_fast(16, 10000, dtype="f16"))
+        # the HBM-real variant of the headline batched workload: ten times the instances (413 MB)
+        batched_entry("sgemm_batched_f32_100000x16x16x16_gap7 (cold variant of 10000 x 16^3)", W.config4_fast(16, 100000))
 
-        dev, dev_eager = graph_timed(half_generic, th["C"], steps, warmup)
-        gbs = hb.algorithmic_bytes / dev / 1e9
-        extra.append({"workload": "hgemm_batched_f16_10000x16x16x16_gap7", "gflops": round(hb.flops / dev / 1e9, 1),
-                      "ms": round(dev * 1e3, 5), "ms_eager_launches": round(dev_eager * 1e3, 5),
-                      "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                   "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None},
-                      "note": "graph-timed; 21 MB working set, served by the last-level cache"})
+    # ---- configuration 5: irregular and skinny FP32 shapes, op(A) = A^T, padded leading dimensions, beta = 1 -----
+    if want("config5"):
+        bounds = ("mfma", "mfma", "mfma", "hbm", "hbm", "hbm")
+        for index, (m, n, k) in enumerate(W.CONFIG5_SHAPES):
+            case = W.config5(index)
+            small = m == 1 or n == 1 or m * n * k < 3e9
+            gemm_entry(f"sgemm_f32_{m}x{n}x{k}_colmajor_TN_ldpad_beta1", case, bounds[index], small=small, cold=(m == 1 or n == 1))
 
     # ---- next row: convolution as IM2COL + GEMM on the layers whose GEMMs are the FP16 shapes of the metric's
     # workload list; microsecond-scale, so graph-timed like the batched calls
-    if args.only in (None, "conv"):
+    if want("conv"):
         for index in range(len(W.CONV_LAYERS)):
             cc = W.conv_layer(index, "f16")
             geo = (cc.channels, cc.height, cc.width, cc.kernel, cc.pad, cc.stride, cc.dilation)
-            im, wt, out = H.to_gpu(cc.im), H.to_gpu(cc.weights), H.to_gpu(cc.out)
+            im, wt, out = M.to_gpu(cc.im), M.to_gpu(cc.weights), M.to_gpu(cc.out)
             oh, ow = cc.out_hw
             col = torch.empty(cc.k * oh * ow, dtype=torch.float16, device="cuda")
             ws = torch.empty(max(G.mg_conv2d_workspace_bytes(G.MG_F16, *geo, cc.filters), 256), dtype=torch.uint8, device="cuda")
-            t_unfold, _ = graph_timed(lambda: G.mg_him2col(*geo, im, col), col, steps, warmup)
-            t_conv, t_conv_eager = graph_timed(lambda: G.mg_hconv2d(*geo, cc.filters, 1.0, im, wt, 0.0, out, ws), out,
-                                               steps, warmup)
+            t_unfold, _ = M.graph_timed(lambda: G.mg_him2col(*geo, im, col), col, steps, warmup)
+            t_conv, t_conv_eager = M.graph_timed(lambda: G.mg_hconv2d(*geo, cc.filters, 1.0, im, wt, 0.0, out, ws), out,
+                                                 steps, warmup)
             unfold_bytes = 2 * (cc.k * oh * ow + cc.channels * cc.height * cc.width)
-            gbs = unfold_bytes / t_unfold / 1e9
             flops = 2.0 * cc.filters * oh * ow * cc.k
             extra.append({"workload": f"hconv2d_f16_c{cc.channels}_{cc.height}x{cc.width}_k{cc.kernel[0]}_s{cc.stride[0]}_f{cc.filters}"
                                       f" (GEMM {cc.filters}x{oh * ow}x{cc.k})",
                           "gflops": round(flops / t_conv / 1e9, 1), "ms": round(t_conv * 1e3, 5),
                           "ms_eager_launches": round(t_conv_eager * 1e3, 5), "ms_im2col": round(t_unfold * 1e3, 5),
-                          "roofline_im2col": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                              "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None},
+                          "roofline_im2col": roofline("hbm", unfold_bytes, t_unfold, PEAK_HBM_GBS, None),
                           "note": "graph-timed; working set of a few MB, served by the last-level cache"})
 
     # ---- next row: the stand-alone matrix-vector product, a 1 GiB FP32 matrix (four times the last-level
     # cache) read once per call, in both operand orders
-    if args.only in (None, "gemv"):
+    if want("gemv"):
         size = 16384
         gen = torch.Generator(device="cuda").manual_seed(W.SEED_BASE)
         mat = torch.rand(size * size, dtype=torch.float32, device="cuda", generator=gen) - 0.5
@@ -250,46 +342,49 @@ def main():
         for trans, tag in ((W.NO_TRANS, "N"), (W.TRANS, "T")):
             need = G.mg_gemv_workspace_bytes(G.MG_F32, W.COL_MAJOR, trans, size, size, size)
             ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda") if need else None
-            dev, _ = timed(lambda: G.mg_sgemv(W.COL_MAJOR, trans, size, size, 1.0, mat, size, x, 1, 0.0, y, 1, ws),
-                           steps, warmup)
-            gbs = 4.0 * size * size / dev / 1e9
-            extra.append({"workload": f"sgemv_f32_{size}x{size}_colmajor_{tag}", "gflops": round(2.0 * size * size / dev / 1e9, 1),
-                          "ms": round(dev * 1e3, 5),
-                          "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                       "frac": round(gbs / PEAK_HBM_GBS, 4),
-                                       "traffic": MEASURED_TRAFFIC_BYTES.get(f"sgemv_{size}_{tag}")}})
+            dev, _ = M.timed(lambda: G.mg_sgemv(W.COL_MAJOR, trans, size, size, 1.0, mat, size, x, 1, 0.0, y, 1, ws),
+                             max(5, steps // 4), max(1, warmup // 4))
+            label = f"sgemv_f32_{size}x{size}_colmajor_{tag}"
+            extra.append({"workload": label, "gflops": round(2.0 * size * size / dev / 1e9, 1), "ms": round(dev * 1e3, 5),
+                          "roofline": roofline("hbm", 4.0 * size * size, dev, PEAK_HBM_GBS, label)})
+        del mat
 
     # ---- next row: the GEMM-derived level-3 routines at the size of the headline product (FP16 storage);
     # flops are the useful ones of each routine (SYRK and TRMM compute a full product: twice that)
-    if args.only in (None, "level3"):
+    if want("level3"):
         size = 4096
         l3 = {"symm": W.level3_case("symm", "f16", W.COL_MAJOR, size, size, side=W.LEFT, uplo=W.LOWER, case=1),
               "syrk": W.level3_case("syrk", "f16", W.COL_MAJOR, size, size, k=size, uplo=W.LOWER, case=2),
               "trmm": W.level3_case("trmm", "f16", W.COL_MAJOR, size, size, side=W.LEFT, uplo=W.LOWER, case=3)}
         useful = {"symm": 2.0 * size ** 3, "syrk": 1.0 * size ** 3, "trmm": 1.0 * size ** 3}
         for routine, lc in l3.items():
-            A = H.to_gpu(lc.A)
-            ws = H.level3_workspace(lc)
+            A = M.to_gpu(lc.A)
             if routine == "symm":
-                B, Cd = H.to_gpu(lc.B), H.to_gpu(lc.C)
+                need = G.mg_symm_workspace_bytes(G.MG_F16, lc.layout, lc.side, size, size)
+            elif routine == "syrk":
+                need = G.mg_syrk_workspace_bytes(G.MG_F16, lc.layout, lc.trans, size, size)
+            else:
+                need = G.mg_trmm_workspace_bytes(G.MG_F16, lc.layout, lc.side, lc.trans, size, size)
+            ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+            if routine == "symm":
+                B, Cd = M.to_gpu(lc.B), M.to_gpu(lc.C)
                 call = lambda: G.mg_hsymm(lc.layout, lc.side, lc.uplo, size, size, 1.0, A, lc.lda, B, lc.ldb, 0.0, Cd, lc.ldc, ws)
             elif routine == "syrk":
-                Cd = H.to_gpu(lc.C)
+                Cd = M.to_gpu(lc.C)
                 call = lambda: G.mg_hsyrk(lc.layout, lc.uplo, lc.trans, size, size, 1.0, A, lc.lda, 0.0, Cd, lc.ldc, ws)
             else:
                 # in place: the operand shrinks or grows from call to call; the time does not depend on the values
-                B = H.to_gpu(lc.B)
+                B = M.to_gpu(lc.B)
                 call = lambda: G.mg_htrmm(lc.layout, lc.side, lc.uplo, lc.trans, lc.diag, size, size, 1.0, A, lc.lda, B, lc.ldb, ws)
-            dev, _ = timed(call, steps, warmup)
-            tf = useful[routine] / dev / 1e12
-            extra.append({"workload": f"h{routine}_f16_{size}_colmajor_lower" + ("_left" if routine != "syrk" else f"_k{size}"),
-                          "gflops": round(tf * 1e3, 1), "ms": round(dev * 1e3, 5),
-                          "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_TFLOPS["f16"], "unit": "TFLOP/s",
-                                       "frac": round(tf / PEAK_TFLOPS["f16"], 4), "traffic": None},
-                          "note": "useful flops of the routine; includes the support kernels"})
+            dev, _ = M.timed(call, max(5, steps // 4), max(1, warmup // 4))
+            label = f"h{routine}_f16_{size}_colmajor_lower" + ("_left" if routine != "syrk" else f"_k{size}")
+            entry = {"workload": label, "gflops": round(useful[routine] / dev / 1e9, 1), "ms": round(dev * 1e3, 5),
+                     "roofline": roofline("mfma", useful[routine], dev, PEAK_TFLOPS["f16"], label),
+                     "note": "useful flops of the routine; includes the support kernels"}
+            extra.append(entry)
 
     if head is None:
-        print(json.dumps({"workloads": extra}))
+        print(json.dumps({"workloads": extra, "probes": probes}))
         return
     case, dev = head["case"], head["dev"]
     line = {
@@ -307,8 +402,11 @@ def main():
         "data": "synthetic",
         "config": {"workload": "hgemm_f16_4096x4096x4096_colmajor_NN_alpha1_beta0", "kernel": head["sel"]["name"],
                    "host_ms_per_step": round(head["wall"] * 1e3, 5)},
-        "roofline": roofline_mfma(case, dev, "hgemm_4096"),
+        "roofline": roofline("mfma", case.flops, dev, PEAK_TFLOPS["f16"], "hgemm_f16_4096x4096x4096_colmajor_NN_alpha1_beta0"),
         "cpu_baseline": head["cpu"],
+        "probes": probes,
+        "traffic_measured_at_commit": traffic.get("measured_at_commit"),
+        "paper_context": PAPER_CONTEXT,
         "workloads": extra,
     }
     print(json.dumps(line))

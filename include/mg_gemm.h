@@ -352,6 +352,32 @@ int32_t mg_lds_read_offset(int32_t k_contiguous, int32_t fragment_rows, int32_t 
                            int32_t wave_row, int32_t lane, int32_t fragment, int32_t k_step,
                            int32_t half);
 
+/* ---- measuring aids (paper Section 4.1: how the numbers are taken) --------------------------
+ * Three launches that let a benchmark measure, in its own run, what its roofline fractions are
+ * judged against.  All are asynchronous on `stream` and touch nothing but what is named. */
+/* One empty kernel (one wavefront): timed back to back it gives the launch floor. */
+mg_status mg_probe_empty_launch(void *stream);
+/* The matrix pipes alone: 256 work-groups of 8 wavefronts (two per SIMD) each issue
+ * rounds x 32 independent v_mfma_f32_16x16x32_f16 on register operands that change from one
+ * instruction to the next; 2 * 16*16*32 * 32 * rounds * 2048 wavefronts flop per launch.  sink: one
+ * device float that is (practically) never written.  MG_ERR_DIM for rounds < 1 or a null sink. */
+mg_status mg_probe_mfma_only(int32_t rounds, float *sink, void *stream);
+/* C <- A * B (FP16 storage, column-major, nothing transposed, alpha 1, beta 0) on the kernel the
+ * library selects for whole 256 x 256 tiles, built with cycle stamps.  m, n multiples of 256, k a
+ * multiple of 64, operands 16-byte aligned with leading dimensions that are multiples of 8 (else
+ * MG_ERR_DIM / MG_ERR_LD* / MG_ERR_CONFIG).  stamps (device): 12 uint64 per wavefront, wavefront w of
+ * work-group g (g counts the m/256 * n/256 tiles) at stamps[(8 g + w) * 12 ...]:
+ *   [0] shader-clock ticks from the start of the wavefront to the end of its K loop, [1] ticks of the
+ *   epilogue, [2] the same whole span on the constant 100 MHz clock, [3] sum over the K-tiles of the
+ *   ticks spent reading operands from local memory, [4] of the wait at the barrier behind that,
+ *   [5] of the run of MFMAs, [6] of the wait at the barrier behind it, [7] ticks from the start to the
+ *   first turn (first tile in local memory), [8] / [9] start and end on the 100 MHz clock (absolute),
+ *   [10] number of the die (XCD) the wavefront ran on, [11] K-tiles.  [0] + [1] over [2] is the clock
+ *   the die held, in units of 100 MHz. */
+mg_status mg_probe_hgemm_stamps(int64_t m, int64_t n, int64_t k, const uint16_t *A, int64_t lda,
+                                const uint16_t *B, int64_t ldb, uint16_t *C, int64_t ldc,
+                                uint64_t *stamps, void *stream);
+
 const char *mg_status_string(mg_status status);
 /* "major.minor" of this ABI. */
 const char *mg_version(void);

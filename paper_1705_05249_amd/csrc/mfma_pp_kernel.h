@@ -371,7 +371,7 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_pp_kernel(const MfmaArgs ar
         tile_epilogue<T, RB, FM, FN, WTM, WTN, false>(acc, plain, lds, m0, n0, wm, wn, wave, lane);
         const uint64_t t_end = now(), rt_end = __builtin_amdgcn_s_memrealtime();
         if (lane == 0) {
-            uint64_t *out = reinterpret_cast<uint64_t *>(args.partial) + (static_cast<size_t>(blockIdx.x) * WAVES + wave) * 8;
+            uint64_t *out = reinterpret_cast<uint64_t *>(args.partial) + (static_cast<size_t>(blockIdx.x) * WAVES + wave) * 12;
             out[0] = t_loop - t_begin;
             out[1] = t_end - t_loop;
             out[2] = rt_end - rt_begin;
@@ -380,6 +380,10 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_pp_kernel(const MfmaArgs ar
             out[5] = sum_mma;
             out[6] = sum_bar_mma;
             out[7] = t_first - t_begin;
+            out[8] = rt_begin;
+            out[9] = rt_end;
+            out[10] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));      // XCC_ID: which of the eight dies
+            out[11] = static_cast<uint64_t>(ktiles);
         }
     } else {
         tile_epilogue<T, RB, FM, FN, WTM, WTN, false>(acc, args, lds, m0, n0, wm, wn, wave, lane);

@@ -28,6 +28,7 @@ EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemm_static", "mg_sgemv", "mg_hgemv", "m
            "mg_kernel_count",
            "mg_kernel_info", "mg_kernel_name", "mg_query_selected", "mg_override_config",
            "mg_override_batched_config", "mg_clear_override", "mg_lds_store_offset", "mg_lds_read_offset",
+           "mg_probe_empty_launch", "mg_probe_mfma_only", "mg_probe_hgemm_stamps",
            "mg_status_string", "mg_version")
 
 
@@ -137,6 +138,12 @@ def lib():
         L.mg_lds_store_offset.restype = ctypes.c_int32
         L.mg_lds_read_offset.argtypes = [ctypes.c_int32] * 8
         L.mg_lds_read_offset.restype = ctypes.c_int32
+        L.mg_probe_empty_launch.argtypes = [vp]
+        L.mg_probe_empty_launch.restype = i32
+        L.mg_probe_mfma_only.argtypes = [ctypes.c_int32, vp, vp]
+        L.mg_probe_mfma_only.restype = i32
+        L.mg_probe_hgemm_stamps.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, vp]
+        L.mg_probe_hgemm_stamps.restype = i32
         L.mg_status_string.argtypes = [i32]
         L.mg_status_string.restype = ctypes.c_char_p
         L.mg_version.argtypes = []
@@ -406,6 +413,25 @@ def mg_lds_store_offset(k_contiguous, fragment_rows, tile_rows, row, k) -> int:
 
 def mg_lds_read_offset(k_contiguous, fragment_rows, tile_rows, wave_row, lane, fragment, k_step, half=0) -> int:
     return lib().mg_lds_read_offset(int(bool(k_contiguous)), fragment_rows, tile_rows, wave_row, lane, fragment, k_step, half)
+
+
+def _checked(st, where, check):
+    if check and st != MG_OK:
+        raise MgError(st, where)
+    return st
+
+
+def mg_probe_empty_launch(stream=None, check=True) -> int:
+    return _checked(lib().mg_probe_empty_launch(_stream(stream)), "mg_probe_empty_launch", check)
+
+
+def mg_probe_mfma_only(rounds, sink, stream=None, check=True) -> int:
+    return _checked(lib().mg_probe_mfma_only(rounds, _addr(sink), _stream(stream)), "mg_probe_mfma_only", check)
+
+
+def mg_probe_hgemm_stamps(m, n, k, A, lda, B, ldb, C, ldc, stamps, stream=None, check=True) -> int:
+    return _checked(lib().mg_probe_hgemm_stamps(m, n, k, _addr(A), lda, _addr(B), ldb, _addr(C), ldc, _addr(stamps),
+                                                _stream(stream)), "mg_probe_hgemm_stamps", check)
 
 
 def mg_query_selected(dtype, layout, trans_a, trans_b, m, n, k, lda, ldb, ldc, alpha=1.0, beta=0.0,

@@ -7,9 +7,7 @@ from paper_1705_05249_amd import workloads as W
 TOL = {"f32": 1e-5, "f16": 2e-3}        # max |C - C_ref| / (|alpha| |A||B| + |beta| |C|)
 
 
-def to_gpu(arr):
-    import torch
-    return torch.from_numpy(np.ascontiguousarray(arr)).cuda()
+from paper_1705_05249_amd.measure import rel_error, to_gpu  # noqa: E402,F401  (re-exported for the tests)
 
 
 def workspace_for(case):
@@ -49,17 +47,6 @@ def assert_padding_untouched(case, out):
     mask = W.padding_mask(case.layout, case.m, case.n, case.ldc, case.C.size)
     assert np.array_equal(bits(out)[mask], bits(case.C)[mask]), f"{case.name}: bytes outside C were written"
 
-
-def rel_error(got, c_ref, d_ref):
-    """max |got - ref| / D over entries with D > 0; entries with D == 0 must be exactly 0"""
-    got = got.astype(np.float64)
-    zero = d_ref == 0
-    assert np.all(got[zero] == 0), "entries with zero denominator must be exactly zero"
-    if np.all(zero):
-        return 0.0
-    err = np.abs(got[~zero] - c_ref[~zero]) / d_ref[~zero]
-    assert not np.any(np.isnan(err)), "NaN in result"
-    return float(err.max())
 
 
 def check_case(case, oracle, sampled=False, workspace="auto", offset_elems=(0, 0, 0), seed=1, sample=None):
