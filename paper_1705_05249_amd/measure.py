@@ -72,7 +72,11 @@ def graph_timed(call, c_buffer, steps, warmup, per_graph=20):
         c_buffer.copy_(c0)
         one.replay()
         torch.cuda.synchronize()
-        assert torch.equal(c_buffer, eager), "graph replay differs from the eager call"
+        as_bits = {1: torch.uint8, 2: torch.int16, 4: torch.int32, 8: torch.int64}[c_buffer.element_size()]
+        if not torch.equal(c_buffer.view(as_bits), eager.view(as_bits)):          # bit for bit (padding may hold NaN)
+            differ = (c_buffer.view(as_bits) != eager.view(as_bits))
+            raise AssertionError(f"graph replay differs from the eager call in {int(differ.sum())} of {eager.numel()} elements "
+                                 f"(first at {int(differ.nonzero()[0])})")
     dev, _ = timed(graph.replay, max(1, steps // 2), max(1, warmup // 4))
     dev_eager, _ = timed(call, steps, warmup)
     return dev / per_graph, dev_eager
