@@ -163,9 +163,10 @@ size_t mg_gemv_workspace_bytes(int dtype, int layout, int trans_a, int64_t m, in
  *   SYMM  C = alpha*A*B + beta*C (MG_LEFT, A m x m) or alpha*B*A + beta*C (MG_RIGHT, A n x n);
  *         B, C m x n.  A symmetric; only its `uplo` triangle is read.
  *   SYRK  C = alpha*A*A^T + beta*C (MG_NO_TRANS, A n x k) or alpha*A^T*A + beta*C (MG_TRANS, A k x n);
- *         C n x n; only its `uplo` triangle is changed (the rest keeps its bytes; it is read and
- *         written back unchanged, so it must be valid memory).  Tiles wholly outside the triangle
- *         are skipped; the tiles on the diagonal are computed in full.
+ *         C n x n; only its `uplo` triangle is changed.  Where the macro-tile kernels run the product
+ *         (all but very small problems) tiles wholly outside the triangle are skipped and the tiles
+ *         on the diagonal store through a mask: nothing else of C is touched.  Otherwise the rest is
+ *         set aside in the workspace and put back bit for bit (so it must be valid memory).
  *   TRMM  B = alpha*op(A)*B (MG_LEFT, A m x m) or alpha*B*op(A) (MG_RIGHT, A n x n); B m x n, in
  *         place.  A triangular: entries outside its `uplo` triangle are not read and count as zero,
  *         with MG_UNIT the diagonal is not read and counts as one.  The zeros take part in the

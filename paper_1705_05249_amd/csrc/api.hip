@@ -200,7 +200,8 @@ mg_status run_indirect(const Problem &p, const IndirectPlan &plan)
 mg_status run_canonical(Problem p)
 {
     IndirectPlan plan;
-    if (indirect_plan(p, true, &plan) && p.workspace != nullptr && pointer_alignment(p.workspace) >= 256 &&
+    // (the copy back out of the padded result writes all of C: not for a call that may only touch a triangle)
+    if (!p.mask_c && indirect_plan(p, true, &plan) && p.workspace != nullptr && pointer_alignment(p.workspace) >= 256 &&
         p.workspace_bytes >= plan.total())
         return run_indirect(p, plan);
     int32_t kernel = -1, split = 1;
@@ -208,6 +209,7 @@ mg_status run_canonical(Problem p)
     const mg_status s = choose(p, problem_alignment(p), ws_usable ? p.workspace_bytes : 0, &kernel, &split);
     if (s != MG_OK) return s;
     const KernelEntry &e = table()[kernel];
+    if (p.mask_c && !e.masks_triangle) return MG_ERR_CONFIG;      // the caller takes the route that sets the rest of C aside
     const size_t need = e.workspace(p, split);
     if (need > 0 && !(ws_usable && p.workspace_bytes >= need)) return MG_ERR_WORKSPACE;
     return e.launch(p, split) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
@@ -503,12 +505,27 @@ mg_status run_syrk(int dtype, int layout, int uplo, int trans, int64_t n, int64_
     const bool reads_a = alpha != 0.f && k != 0;
     if (C == nullptr || (reads_a && A == nullptr)) return MG_ERR_NULL;
     const size_t elem = dtype == MG_F32 ? 4 : 2;
+    const bool other_is_lower = !lower_in_view(layout, uplo);
+    const bool nt0 = trans == MG_NO_TRANS;
     Carve carve(ws, ws_bytes);
     void *aside = carve.take(static_cast<size_t>(n) * n * elem);
-    if (aside == nullptr) return MG_ERR_WORKSPACE;
-    // the GEMM below writes all of C: the entries outside the referenced triangle are set aside first and
+    if (aside == nullptr) return MG_ERR_WORKSPACE;          // the contract is the same whichever route runs
+    // First choice: one launch of a macro-tile kernel whose epilogue writes the referenced triangle only (tiles wholly
+    // outside it are skipped, tiles on the diagonal store with a mask).  Not for problems the padded-copy route would
+    // take, and not when the kernel in charge (small problems, a forced configuration) has no such epilogue.
+    if (reads_a) {
+        Problem p = canonical(dtype, layout, nt0 ? MG_NO_TRANS : MG_TRANS, nt0 ? MG_TRANS : MG_NO_TRANS, n, n, k, alpha, A, lda, A,
+                              lda, beta, C, ldc, carve.rest(), carve.left, stream,
+                              other_is_lower ? MG_SHAPE_C_UPPER : MG_SHAPE_C_LOWER);
+        IndirectPlan plan;
+        if (!indirect_plan(p, true, &plan)) {
+            p.mask_c = true;
+            const mg_status direct = run_canonical(p);
+            if (direct != MG_ERR_CONFIG && direct != MG_ERR_WORKSPACE) return direct;
+        }
+    }
+    // Otherwise the GEMM below writes all of C: the entries outside the referenced triangle are set aside first and
     // put back afterwards, bit for bit
-    const bool other_is_lower = !lower_in_view(layout, uplo);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (launch_copy_triangle(dtype, n, C, ldc, aside, n, other_is_lower, st) != hipSuccess) return MG_ERR_LAUNCH;
     const bool nt = trans == MG_NO_TRANS;

@@ -46,6 +46,8 @@ struct Problem {
     size_t workspace_bytes;
     hipStream_t stream;
     int shape;                 // ProblemShape: where an operand is known to hold zeros / which part of C is wanted
+    bool mask_c;               // shape C_LOWER / C_UPPER only: nothing outside that triangle of C may be written (or read);
+                               // set only for kernels whose KernelEntry says masks_triangle
 
     int64_t a_sm() const { return a_trans ? lda : 1; }
     int64_t a_sk() const { return a_trans ? 1 : lda; }
@@ -120,6 +122,7 @@ struct KernelEntry {
     hipError_t (*launch)(const Problem &, int split_k);
     bool (*legal_batched)(const BatchedProblem &);
     hipError_t (*launch_batched)(const BatchedProblem &);
+    bool masks_triangle = false;                             // honours Problem::mask_c (the macro-tile kernels' epilogue)
 };
 
 // Registration functions, one per translation unit; called once, in this order.

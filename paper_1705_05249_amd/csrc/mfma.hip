@@ -11,6 +11,7 @@ void register_hmfma_64x64x64_w2x2(std::vector<KernelEntry> &table);
 void register_hdma16_256x256x64(std::vector<KernelEntry> &table);
 void register_hdma16_small(std::vector<KernelEntry> &table);
 void register_hpp16_256x256x64(std::vector<KernelEntry> &table);
+void register_tiny(std::vector<KernelEntry> &table);
 void register_hdma_256x256x64_w2x2(std::vector<KernelEntry> &table);
 void register_hdma_256x256x64_w2x4(std::vector<KernelEntry> &table);
 void register_smfma_256x256x32_w2x2(std::vector<KernelEntry> &table);
@@ -37,5 +38,6 @@ void register_mfma(std::vector<KernelEntry> &table)
     register_smfma_128x128x32_w2x2(table);
     register_smfma_128x64x32_w2x2(table);
     register_smfma_64x64x32_w2x2(table);
+    register_tiny(table);
 }
 }  // namespace mg

@@ -30,6 +30,7 @@ hipError_t launch_tile_kernel(Kernel kernel, bool *attr_set, int lds_bytes, int 
     a.shape = p.shape;
     // K ranges that grow with the tile index: start the long ones first
     a.reversed = p.shape == MG_SHAPE_A_LOWER || p.shape == MG_SHAPE_B_UPPER;
+    a.mask = p.mask_c && (p.shape == MG_SHAPE_C_LOWER || p.shape == MG_SHAPE_C_UPPER) ? 1 : 0;
     hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(a.tiles_m) * a.tiles_n, 1, split), dim3(threads), lds_bytes,
                        p.stream, a);
     hipError_t e = hipGetLastError();
@@ -106,7 +107,9 @@ template <typename T, int BM, int BN, int BK, int WM, int WN, bool AK, bool BKC,
         c.split_k = 1;
         c.threads = NT;
         c.lds_bytes = LDS;
-        return KernelEntry{name, c, legal, workspace, launch, nullptr, nullptr};
+        KernelEntry e{name, c, legal, workspace, launch, nullptr, nullptr};
+        e.masks_triangle = true;
+        return e;
     }
 };
 

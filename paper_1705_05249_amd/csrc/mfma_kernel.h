@@ -66,6 +66,7 @@ struct MfmaArgs {
     int group_m;           // tile rasterisation: tiles are walked in column groups of this many rows
     int shape;             // ProblemShape: K range per tile narrowed to the non-zero part / tiles outside C's triangle skipped
     int reversed;          // walk the tiles in reverse order (longest K ranges first)
+    int mask;              // with shape C_LOWER / C_UPPER: write (and read) nothing outside that triangle of C
 };
 
 template <typename T> struct ElemTraits;
@@ -472,10 +473,16 @@ __device__ inline void tile_epilogue(typename BlockAcc<RB>::type (&acc)[FN][FM],
         for (int pass = 0; pass < 32 / COLS; ++pass) {
             const int r = r0 + pass * COLS;            // column inside the 32-column block
             const int64_t gn = gn0 + j * 32 + r, gm = gm0 + c * PER;
-            int valid = PER;
+            int valid = PER, first = 0;          // elements first .. valid - 1 of the piece are written
             if constexpr (EDGE) {
                 const int64_t left = args.m - gm;
                 valid = gn >= args.n ? 0 : (left >= PER ? PER : (left > 0 ? static_cast<int>(left) : 0));
+            }
+            if (args.mask != 0) {
+                // only the wanted triangle of C: rows gm + e >= gn (lower) or <= gn (upper) of column gn
+                const int64_t d = gn - gm;
+                if (args.shape == MG_SHAPE_C_LOWER) first = d > 0 ? (d < PER ? static_cast<int>(d) : PER) : 0;
+                else valid = d + 1 < valid ? (d + 1 > 0 ? static_cast<int>(d + 1) : 0) : valid;
             }
             float v[PER];
 #pragma unroll
@@ -483,7 +490,7 @@ __device__ inline void tile_epilogue(typename BlockAcc<RB>::type (&acc)[FN][FM],
                 const floatx4 x = *reinterpret_cast<const floatx4 *>(region + r * ROWB + (c * PER + 4 * h) * 4);
                 v[4 * h] = x.x; v[4 * h + 1] = x.y; v[4 * h + 2] = x.z; v[4 * h + 3] = x.w;
             }
-            if (valid > 0) emit(base + gm + gn * ld, v, valid);
+            if (valid > first) emit(base + gm + gn * ld, v, first, valid);
         }
     };
 
@@ -492,16 +499,20 @@ __device__ inline void tile_epilogue(typename BlockAcc<RB>::type (&acc)[FN][FM],
 #pragma unroll
         for (int j = 0; j < NBLK; ++j) {
             stage_block(j);
-            drain_block(base, static_cast<int64_t>(args.m), j, [](float *p, const float (&v)[4], int valid) {
-                if (valid == 4) *reinterpret_cast<Pack<float, 4> *>(p) = Pack<float, 4>{{v[0], v[1], v[2], v[3]}};
-                else for (int e = 0; e < valid; ++e) p[e] = v[e];
+            drain_block(base, static_cast<int64_t>(args.m), j, [](float *p, const float (&v)[4], int first, int valid) {
+                if (first == 0 && valid == 4) *reinterpret_cast<Pack<float, 4> *>(p) = Pack<float, 4>{{v[0], v[1], v[2], v[3]}};
+                else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (e >= first && e < valid) p[e] = v[e];
+                }
             });
         }
     } else {
         constexpr int PER = 16 / static_cast<int>(sizeof(T));
         T *base = static_cast<T *>(args.C);
-        auto emit = [alpha, beta](T *p, const float (&v)[PER], int valid) {
-            if (valid == PER) {
+        auto emit = [alpha, beta](T *p, const float (&v)[PER], int first, int valid) {
+            if (first == 0 && valid == PER) {
                 Pack<T, PER> o;
                 if (beta != 0.f) {
                     const Pack<T, PER> c = *reinterpret_cast<const Pack<T, PER> *>(p);
@@ -513,11 +524,13 @@ __device__ inline void tile_epilogue(typename BlockAcc<RB>::type (&acc)[FN][FM],
                 }
                 *reinterpret_cast<Pack<T, PER> *>(p) = o;
             } else {
-                for (int e = 0; e < valid; ++e) {
-                    float o = alpha * v[e];
-                    if (beta != 0.f) o = fmaf(beta, load_as_float(p + e), o);
-                    store_from_float(p + e, o);
-                }
+#pragma unroll
+                for (int e = 0; e < PER; ++e)
+                    if (e >= first && e < valid) {
+                        float o = alpha * v[e];
+                        if (beta != 0.f) o = fmaf(beta, load_as_float(p + e), o);
+                        store_from_float(p + e, o);
+                    }
             }
         };
 #pragma unroll

@@ -115,6 +115,16 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
             return;
         }
     }
+    // Problems of at most one 32 x 32 block per compute unit and a short sum: the kernel whose eight wavefronts share
+    // the sum of one block (tiny.hip) beats the macro tiles' software pipeline, which never fills (FP32 256^3: 6.8 ->
+    // 4.8 us, 512^3: 9.7 -> 7.2 us; at 384 x 384 x 1024 the two are level, beyond that the macro tiles win)
+    const int64_t blocks32 = ceil_div(p.m, 32) * ceil_div(p.n, 32);
+    const char *order_tag = p.a_trans ? (p.b_trans ? "kn" : "kk") : (p.b_trans ? "mn" : "mk");
+    if (f32 && p.shape == MG_SHAPE_GENERAL && blocks32 <= kComputeUnits && p.k >= 64 && p.k <= 640 && p.m > 1 && p.n > 1) {
+        char name[48];
+        snprintf(name, sizeof name, "stiny_32x32_%s", order_tag);
+        if (try_pick(table, p, alignment, name, 1, kernel, split)) return;
+    }
     if (p.m >= 16 && p.n >= 16) {
         // The macro tile (and number of K slices) with the smallest estimated time, see `estimate` below: a chip
         // that is not full runs ceil(tiles / 256) work-groups per compute unit at a rate that grows with them up to
@@ -201,7 +211,8 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 // tiles of 64 x 64 and 74 us in five slices)
                 // (a single turn of it has no other work-group's arithmetic to hide its checked loads behind: 0.45)
                 const double rate = (tiles[i].ceiling - (tiles[i].ceiling - tiles[i].per_group) / up) * (ragged ? (up <= 1.0 ? 0.45 : 0.6) : 1.0);
-                time = rounds * (tile_flops / rate + f32_round_cost[i]);
+                // (work-groups that are resident together pay the fixed cost of a turn once)
+                time = rounds * tile_flops / rate + (blocks <= full ? 1.0 : rounds) * f32_round_cost[i];
             } else if (blocks < full) {
                 // the chip is not full: ceil(blocks / 256) work-groups share a compute unit
                 const int64_t per_unit = ceil_div(blocks, kComputeUnits);
@@ -248,12 +259,15 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
             }
             // split-K: the partial sums are written and read back (8 bytes per slice and output at ~4 TB/s) by
             // a second launch (~3 us)
-            if (slices > 1) time += 1.0e6 * (3.0 + (8.0 * slices + 4.0) * static_cast<double>(p.m) * static_cast<double>(p.n) / 4.0e6);
+            // (measured on 1000 x 1001 x 999 in FP32: 2 slices 32.1 us, 4 slices 31.0 us, none 36.6 us)
+            if (slices > 1) time += 1.0e6 * (2.5 + (4.0 * slices + 8.0) * static_cast<double>(p.m) * static_cast<double>(p.n) / 4.0e6);
             return time;
         };
         for (int attempt = 0; attempt < count; ++attempt) {
             int best = -1, best_slices = 1;
             double best_time = 0.0;
+            double free_time = 0.0;          // best estimate with all the workspace one could wish for, and its slices
+            int free_slices = 0;
             for (int i = 0; i < count; ++i) {
                 if (tried[i]) continue;
                 // FP32 with a very short K is bound by the traffic of C, which the large tiles overlap worst (one
@@ -275,12 +289,21 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 for (int o = 0; o < n_options; ++o) {
                     const int sl = options[o];
                     if (sl < 1 || (o > 0 && sl == 1)) continue;
-                    if (sl > 1 && static_cast<size_t>(sl) * p.m * p.n * sizeof(float) > workspace_bytes) continue;
                     const double time = estimate(i, sl);
+                    if (free_slices == 0 || time < free_time) { free_slices = sl; free_time = time; }
+                    if (sl > 1 && static_cast<size_t>(sl) * p.m * p.n * sizeof(float) > workspace_bytes) continue;
                     if (best < 0 || time < best_time) { best = i; best_slices = sl; best_time = time; }
                 }
             }
             if (best < 0) break;
+            // FP16: where the macro tiles would cut a sum of at most three 512-wide chunks into slices (a second launch
+            // that adds the partial sums), the shared-sum kernel does it in one ((256, 784, 1152): 9.7 -> 8.8 us)
+            // (whether or not the caller brought the workspace for the slices)
+            if (!f32 && attempt == 0 && free_slices > 1 && p.shape == MG_SHAPE_GENERAL && blocks32 <= kComputeUnits && p.k <= 1536) {
+                char name[48];
+                snprintf(name, sizeof name, "htiny_32x32_%s", order_tag);
+                if (try_pick(table, p, alignment, name, 1, kernel, split)) return;
+            }
             // A shape hint (about half of the tile work, unequal tiles) is ranked like the general problem, with one
             // measured exception: when the 256 x 256 direct-to-LDS grid leaves compute units idle anyway, the
             // 128 x 128 tiles balance the unequal work better (3072: TRMM 59 against 77 us, SYRK 58 against 76)

@@ -4,11 +4,16 @@ For every shape class of the five workload groups this times EVERY compiled kern
 that is legal for the shape (the exhaustive "most likely" set of the paper; the table holds a few
 dozen kernels, so no random sampling is needed) with a few split-K factors, keeps ALL timings
 (one JSON line per (shape, kernel, split) in the output file, like the paper's database that
-stores every timing, not only the best) and prints the winner per shape.  The selection table in
-csrc/select.hip is written from these winners.  An interrupted sweep resumes: lines already in
-the output file are skipped.
+stores every timing, not only the best) and prints the winner per shape.  For every shape the
+configuration the library selects by itself is timed as well, in the same run (kernel "auto"), so
+that the regret of the selection rules in csrc/select.hip can be read off the file.  Group 4 is the
+batched workload: every batched kernel on every instance size and batch count (the paper notes that
+its batched routine re-used the non-batched parameters sub-optimally, Section 4.6).  An interrupted
+sweep resumes: lines already in the output file are skipped.
 
     python -m paper_1705_05249_amd.sweep --out gpurun_out/sweep.jsonl [--group 3] [--quick]
+    python -m paper_1705_05249_amd.sweep --summary gpurun_out/sweep.jsonl      (no GPU needed: winner, selection
+                                                                                and regret per shape, as markdown)
 
 Group 6 holds nine FP32 shapes for the problem-specific tuning experiment of the paper's Section 4.3
 (Fig. 4): tune for each of nine problems, run every winner on every problem, report performance relative
@@ -142,21 +147,96 @@ def cross_matrix(path, prefix="x_"):
     return "\n".join(lines)
 
 
+def summary(path):
+    """Markdown table per shape: fastest configuration, what the library selects by itself, regret."""
+    times, auto = {}, {}
+    for line in open(path):
+        try:
+            r = json.loads(line)
+        except ValueError:
+            continue
+        if r["kernel"] == "auto":
+            auto[r["shape"]] = r
+        else:
+            times.setdefault(r["shape"], {})[(r["kernel"], r["split_k"])] = r
+    lines = ["| shape | fastest configuration | us | selected by the library | us | selected / fastest |", "|---|---|---|---|---|---|"]
+    worst = 0.0
+    for shape in times:
+        key = min(times[shape], key=lambda c: times[shape][c]["us"])
+        best = times[shape][key]
+        a = auto.get(shape)
+        if a is None:
+            lines.append(f"| {shape} | {key[0]} split {key[1]} | {best['us']:.1f} | (not timed) | | |")
+            continue
+        ratio = a["us"] / best["us"]
+        worst = max(worst, ratio)
+        lines.append(f"| {shape} | {key[0]}" + (f" split {key[1]}" if key[1] > 1 else "") + f" | {best['us']:.1f} | {a['selected']}"
+                     + (f" split {a['selected_split']}" if a["selected_split"] > 1 else "") + f" | {a['us']:.1f} | {ratio:.2f} |")
+    lines.append("")
+    lines.append(f"largest selected / fastest: {worst:.2f} over {len(auto)} shapes")
+    return "\n".join(lines)
+
+
+def sweep_batched(log, done, quick):
+    """group 4: every batched kernel on every instance size and batch count of the batched workload"""
+    import torch
+    from . import measure as M
+    table = [t for t in G.kernel_table() if t["family"] == G.MG_FAMILY_BATCHED]
+    for dtype in ("f32",) if quick else ("f32", "f16"):
+        for size in (8, 16, 32, 64):
+            for batch in (1000, 10000):
+                name = f"c4_{dtype}_s{size}_b{batch}"
+                bc = W.config4_fast(size, batch, dtype=dtype)
+                t = {x: M.to_gpu(getattr(bc, x)) for x in ("A", "B", "C", "a_off", "b_off", "c_off", "alphas", "betas")}
+                fn = G.mg_sgemm_batched if dtype == "f32" else G.mg_hgemm_batched
+                call = lambda: fn(bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, t["alphas"], t["A"], t["a_off"], bc.lda, t["B"],
+                                  t["b_off"], bc.ldb, t["betas"], t["C"], t["c_off"], bc.ldc, bc.batch, check=False)
+                code = G.MG_F32 if dtype == "f32" else G.MG_F16
+                best = None
+                for k in table:
+                    if k["dtype"] != code or (name, k["name"], 1) in done:
+                        continue
+                    G.mg_override_batched_config(k["kernel_id"])
+                    if call() != 0:
+                        continue                    # this kernel does not take this shape
+                    secs = time_call(call)
+                    rec = {"shape": name, "dtype": dtype, "m": size, "n": size, "k": size, "batch": batch, "kernel": k["name"],
+                           "split_k": 1, "us": round(secs * 1e6, 2), "gflops": round(bc.flops / secs / 1e9, 1)}
+                    log.write(json.dumps(rec) + "\n")
+                    log.flush()
+                    if best is None or secs < best[0]:
+                        best = (secs, k["name"])
+                G.mg_clear_override()
+                if (name, "auto", 1) not in done:
+                    secs = time_call(call)
+                    rec = {"shape": name, "dtype": dtype, "m": size, "n": size, "k": size, "batch": batch, "kernel": "auto",
+                           "split_k": 1, "selected": "(automatic)", "selected_split": 1, "us": round(secs * 1e6, 2),
+                           "gflops": round(bc.flops / secs / 1e9, 1)}
+                    log.write(json.dumps(rec) + "\n")
+                    log.flush()
+                    if best:
+                        print(f"{name:28s} best {best[1]:36s} {best[0] * 1e6:10.2f} us   automatic selection {secs * 1e6:10.2f} us", flush=True)
+
+
 def main():
     import torch
     ap = argparse.ArgumentParser()
     ap.add_argument("--out")
+    ap.add_argument("--summary", help="timing file to summarise: winner, selection and regret per shape (no GPU needed)")
     ap.add_argument("--cross", help="timing file to read the problem-specific tuning matrix from (no GPU needed)")
-    ap.add_argument("--group", type=int, action="append", help="workload group(s) 1,2,3,5,6 (default: all)")
+    ap.add_argument("--group", type=int, action="append", help="workload group(s) 1,2,3,4,5,6 (default: all)")
     ap.add_argument("--quick", action="store_true")
     ap.add_argument("--splits", default="1,2,4,8,16")
     args = ap.parse_args()
     if args.cross:
         print(cross_matrix(args.cross))
         return 0
+    if args.summary:
+        print(summary(args.summary))
+        return 0
     if not args.out:
         ap.error("--out or --cross is required")
-    groups = set(args.group or (1, 2, 3, 5, 6))
+    groups = set(args.group or (1, 2, 3, 4, 5, 6))
     splits = [int(x) for x in args.splits.split(",")]
     done = set()
     if os.path.exists(args.out):
@@ -170,6 +250,8 @@ def main():
     ws = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
     best = {}
     with open(args.out, "a") as log:
+        if 4 in groups:
+            sweep_batched(log, done, args.quick)
         for (name, dtype, layout, ta, tb, m, n, k, lda, ldb, ldc, alpha, beta) in shapes(groups, args.quick):
             code = G.MG_F32 if dtype == "f32" else G.MG_F16
             tdt = torch.float32 if dtype == "f32" else torch.float16
@@ -206,9 +288,19 @@ def main():
                     if name not in best or secs < best[name][0]:
                         best[name] = (secs, t["name"], split)
             G.mg_clear_override()
+            sel = G.mg_query_selected(code, layout, ta, tb, m, n, k, lda, ldb, ldc, alpha, beta, 16)
+            if (name, "auto", 1) not in done:
+                # what the library does by itself, with the workspace its preferred route asks for
+                need = G.mg_gemm_workspace_bytes(code, layout, ta, tb, m, n, k, lda, ldb, ldc)
+                auto_ws = ws[:max(need, 256)] if need else None
+                secs = time_call(lambda: fn(layout, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, Cd, ldc, auto_ws))
+                rec = {"shape": name, "dtype": dtype, "m": m, "n": n, "k": k, "kernel": "auto", "split_k": 1,
+                       "selected": sel["name"], "selected_split": sel["split_k"], "us": round(secs * 1e6, 2),
+                       "gflops": round(flops / secs / 1e9, 1)}
+                log.write(json.dumps(rec) + "\n")
+                log.flush()
             if name in best:
                 secs, kname, split = best[name]
-                sel = G.mg_query_selected(code, layout, ta, tb, m, n, k, lda, ldb, ldc, alpha, beta, 16)
                 print(f"{name:28s} best {kname:36s} split={split:<3d} {secs * 1e6:10.1f} us {flops / secs / 1e12:9.2f} TFLOPS"
                       f"   (auto-selected: {sel['name']} split={sel['split_k']})", flush=True)
     G.mg_clear_override()
