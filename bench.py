@@ -236,6 +236,18 @@ def main():
                         "the kernel ends with its slowest die; at the mean clock and 2048 ticks per tile the K loops "
                         f"alone take {ktiles * 2048 / float(clock.mean()) * 1e-3:.1f} us",
             }
+            # the kernels this one replaced, by override, in the same process (boxes differ by up to 10 %)
+            call = gemm_setup(case)[4](A, B, C)
+            beside = {}
+            for name in ("hpp16_256x256x64_w2x4_mk", "hdma16_256x256x64_w2x4_mk", "hdma_256x256x64_w2x2_mk", "hmfma_256x256x64_w2x2_mk"):
+                try:
+                    G.mg_override_config(G.kernel_id(name), 1)
+                except KeyError:
+                    continue
+                dev, _ = M.timed(call, max(5, steps // 2), max(1, warmup // 2))
+                beside[name] = round(dev * 1e3, 5)
+                G.mg_clear_override()
+            probes["hgemm_4096_ms_by_kernel"] = beside
             head.pop("buffers")
 
     # ---- configuration 1: 256^3 (launch- and latency-bound) -----------------------------------------
