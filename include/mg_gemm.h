@@ -34,8 +34,9 @@
  *     are checked on the host, in the order of the status codes below, before any GPU
  *     work; device-side contents (offset values, NaNs) are not checked.  When m == 0 or
  *     n == 0 (or batch_count == 0) the call returns MG_OK without launching anything.
- *   - The configuration override is process-global and not thread-safe; everything else
- *     may be called from several host threads.
+ *   - The configuration override is process-global (relaxed atomics: a call that races with an
+ *     override call uses either the old or the new configuration); everything may be called
+ *     from several host threads.
  */
 #ifndef MG_GEMM_H
 #define MG_GEMM_H

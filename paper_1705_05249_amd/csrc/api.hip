@@ -3,6 +3,7 @@
 // host<->device copies happen here (paper Section 3.1: device pointers in, transfers left
 // to the caller).  Validation touches no HIP API, so every error path can be exercised on
 // a machine without a GPU.
+#include <atomic>
 #include <mutex>
 
 #include "internal.h"
@@ -15,9 +16,11 @@ namespace {
 std::vector<KernelEntry> g_table;
 std::once_flag g_once;
 
-int32_t g_override_kernel[2] = {-1, -1};   // per dtype
-int32_t g_override_split[2] = {1, 1};
-int32_t g_override_batched = -1;
+// Override state: set by the tuning calls, read by every GEMM call; relaxed atomics, so that a call racing with an
+// override sees either the old or the new value of each word (kernel and split are checked together by legal()).
+std::atomic<int32_t> g_override_kernel[2] = {{-1}, {-1}};   // per dtype
+std::atomic<int32_t> g_override_split[2] = {{1}, {1}};
+std::atomic<int32_t> g_override_batched{-1};
 
 const std::vector<KernelEntry> &table()
 {
@@ -106,9 +109,10 @@ mg_status choose(const Problem &p, int64_t alignment, size_t workspace_bytes, in
     const int32_t forced = g_override_kernel[p.dtype];
     if (forced >= 0) {
         const KernelEntry &e = t[forced];
-        if (!e.legal || !e.legal(p, g_override_split[p.dtype], alignment)) return MG_ERR_CONFIG;
+        const int32_t forced_split = g_override_split[p.dtype];
+        if (!e.legal || !e.legal(p, forced_split, alignment)) return MG_ERR_CONFIG;
         *kernel = forced;
-        *split = g_override_split[p.dtype];
+        *split = forced_split;
         return MG_OK;
     }
     select_config(t, p, alignment, workspace_bytes, kernel, split);
@@ -241,6 +245,11 @@ mg_status check_gemv(int layout, int trans, int64_t m, int64_t n, int64_t lda, i
     const int64_t lead = layout == MG_COL_MAJOR ? m : n;
     if (lda < (lead > 1 ? lead : 1)) return MG_ERR_LDA;
     if (incx < 1 || incy < 1 || incx >= lim || incy >= lim) return MG_ERR_INC;
+    // the same cap as for GEMM operands: the matrix and both strided vectors stay far below 2^63 bytes
+    const int64_t other = layout == MG_COL_MAJOR ? n : m;
+    const __int128 cap = __int128(1) << 40;
+    if (__int128(lda) * other > cap || __int128(incx) * (m > n ? m : n) > cap || __int128(incy) * (m > n ? m : n) > cap)
+        return MG_ERR_DIM;
     return MG_OK;
 }
 
@@ -298,10 +307,11 @@ mg_status run_batched(BatchedProblem &p, int layout, int ta, int tb, int64_t m, 
     }
     const auto &t = table();
     int32_t kernel = -1;
-    if (g_override_batched >= 0) {
-        const KernelEntry &e = t[g_override_batched];
+    const int32_t forced = g_override_batched;
+    if (forced >= 0) {
+        const KernelEntry &e = t[forced];
         if (!e.legal_batched || !e.legal_batched(p)) return MG_ERR_CONFIG;
-        kernel = g_override_batched;
+        kernel = forced;
     } else {
         kernel = select_batched(t, p);
         if (kernel < 0) return MG_ERR_CONFIG;
@@ -360,6 +370,11 @@ mg_status check_conv(const ConvShape &s, int64_t filters, int64_t *out_h, int64_
         return MG_ERR_DIM;
     *out_h = conv_out_extent(s.height, s.kernel_h, s.pad_h, s.stride_h, s.dilation_h);
     *out_w = conv_out_extent(s.width, s.kernel_w, s.pad_w, s.stride_w, s.dilation_w);
+    // the unfold kernel indexes one image plane and the padded input window with 32-bit integers
+    if (__int128(s.height) * s.width >= lim) return MG_ERR_DIM;
+    if (s.height + 2 * s.pad_h >= lim || s.width + 2 * s.pad_w >= lim ||
+        s.pad_h + __int128(s.dilation_h) * (s.kernel_h - 1) >= lim || s.pad_w + __int128(s.dilation_w) * (s.kernel_w - 1) >= lim)
+        return MG_ERR_DIM;
     const __int128 kk = __int128(s.channels) * s.kernel_h * s.kernel_w;
     const __int128 total = kk * *out_h * *out_w;
     if (kk >= lim || total >= lim || __int128(s.channels) * s.height * s.width >= (__int128(1) << 40)) return MG_ERR_DIM;

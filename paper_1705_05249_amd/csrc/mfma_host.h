@@ -71,10 +71,12 @@ template <typename T, int BM, int BN, int BK, int WM, int WN, bool AK, bool BKC,
         if (p.m >= (int64_t(1) << 31) || p.n >= (int64_t(1) << 31) || p.k >= (int64_t(1) << 31)) return false;
         if (ceil_div(p.m, BM) * ceil_div(p.n, BN) >= (int64_t(1) << 31)) return false;
         if (split > 1 && static_cast<int64_t>(k_per_split(p, split)) * (split - 1) >= p.k) return false;  // empty slice
-        if (!EDGE) {
-            // lane offsets inside a tile are 32-bit byte offsets
+        {
+            // lane offsets inside a tile are 32-bit byte offsets (both flavours)
             const int64_t span = (BM > BN ? BM : BN) > BK ? (BM > BN ? BM : BN) : BK;
             if ((p.lda > p.ldb ? p.lda : p.ldb) * span * static_cast<int64_t>(sizeof(T)) >= (int64_t(1) << 31)) return false;
+        }
+        if (!EDGE) {
             if (p.m % BM || p.n % BN || p.k % BK) return false;
             // the 16-byte buffer loads need 4-byte aligned addresses only: rows may start anywhere on a dword
             // boundary (odd leading dimensions of FP32 matrices, even ones of FP16 matrices)

@@ -556,10 +556,14 @@ def sample_entries(m: int, n: int, seed: int, rows: int = 16, cols: int = 16, ti
     g = np.random.default_rng(seed)
     def pick(extent, count):
         fixed = {0, extent - 1}
-        for b in range(tile, extent, tile):
-            if len(fixed) >= count // 2:
-                break
-            fixed.update((b - 1, b))
+        # both sides of tile boundaries spread over the whole extent (the first, the last, evenly between), not
+        # only the first few: a mistake in the mapping of late tiles (rasterisation, XCD walk) must be seen too
+        bounds = np.arange(tile, extent, tile)
+        if bounds.size:
+            want = max(1, (count // 2 - 2) // 2)
+            chosen = bounds[np.unique(np.linspace(0, bounds.size - 1, min(want, bounds.size)).round().astype(int))]
+            for b in chosen:
+                fixed.update((int(b) - 1, int(b)))
         rest = g.integers(0, extent, size=max(0, count - len(fixed)))
         return np.unique(np.concatenate([np.fromiter(fixed, dtype=np.int64), rest.astype(np.int64)]))
     ri, cj = pick(m, min(rows, m)), pick(n, min(cols, n))

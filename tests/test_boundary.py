@@ -139,6 +139,10 @@ def test_conv_argument_errors(fn):
         assert conv(fn, **bad) == -15, bad
     assert conv(fn, filters=-1) == -15
     assert conv(fn, height=1 << 20, width=1 << 20) == -4                  # column matrix beyond 2^31 elements
+    # an image plane, a padded extent or a filter reach that a 32-bit index cannot hold (the output itself is small)
+    assert conv(fn, height=1 << 16, width=1 << 15, kernel=(1, 1), stride=(1 << 12, 1 << 12)) == -4
+    assert conv(fn, pad=((1 << 30) + 5, 0), stride=(1 << 30, 1)) == -4
+    assert conv(fn, dilation=(1 << 30, 1), pad=(1 << 30, 0), stride=(1 << 30, 1)) == -4
     assert conv(fn, im=None) == -8 and conv(fn, weights=None) == -8 and conv(fn, out=None) == -8
     assert conv(fn, ws=0) == -10 and conv(fn, ws=264) == -10 and conv(fn, ws_bytes=255) == -10
     # empty outputs launch nothing: no filters, or a filter that does not fit the image
@@ -176,6 +180,8 @@ def test_gemv_argument_errors(fn):
     assert call(m=-1) == -4 and call(n=-1) == -4 and call(m=1 << 31) == -4
     assert call(lda=3) == -5 and call(layout=R, lda=2) == -5 and call(layout=R, lda=3, m=0) == 0
     assert call(incx=0) == -16 and call(incy=0) == -16 and call(incx=-1) == -16
+    # more than 2^40 elements between the first and the last one of the matrix or of a vector
+    assert call(m=4, n=1 << 30, lda=1 << 20) == -4 and call(m=1 << 30, n=2, lda=1 << 30, incx=1 << 12) == -4
     assert call(y=None) == -8 and call(A=None) == -8 and call(x=None) == -8
     # no output: nothing to do, whatever the pointers are
     assert call(m=0, lda=1, A=None, x=None, y=None) == 0
