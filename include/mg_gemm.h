@@ -88,7 +88,8 @@ enum {
     MG_FAMILY_MFMA = 1,     /* LDS-staged MFMA macro-tile kernel (the dense-contraction path) */
     MG_FAMILY_GEMV = 2,     /* m == 1 or n == 1: streaming dot-product kernel                */
     MG_FAMILY_SCALE = 3,    /* alpha == 0 or k == 0: C <- beta*C only                        */
-    MG_FAMILY_BATCHED = 4   /* many small GEMMs per launch                                   */
+    MG_FAMILY_BATCHED = 4,  /* many small GEMMs per launch                                   */
+    MG_FAMILY_CONV = 5      /* GEMM kernels that read op(A) from an image (convolution calls) */
 };
 
 /* One kernel configuration: which compiled kernel runs and with which launch-time choices.

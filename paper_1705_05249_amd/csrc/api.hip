@@ -5,6 +5,7 @@
 // a machine without a GPU.
 #include <atomic>
 #include <mutex>
+#include <string>
 
 #include "internal.h"
 #include "select.h"
@@ -399,6 +400,52 @@ mg_status run_im2col(int dtype, const ConvShape &s, const void *im, void *col, v
     return launch_im2col(dtype, s, im, col, static_cast<hipStream_t>(stream)) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
 }
 
+// The convolution as one GEMM launch whose op(A) is gathered from the image (kernels of the family MG_FAMILY_CONV):
+// the configuration is the one automatic selection gives the GEMM on a stored column matrix, if that is a kernel
+// with such a variant (the 64 x 64 tile "mk" kernels, with their slices of the sum) and the layer is one where the
+// gather pays, or the forced configuration if that is of the family.  MG_ERR_CONFIG: no such kernel, take the unfold route.
+mg_status run_conv2d_fused(int dtype, const ConvShape &s, int64_t filters, int64_t n, int64_t k, float alpha, const void *im,
+                           const void *weights, float beta, void *out, void *ws, size_t ws_bytes, void *stream)
+{
+    const auto &t = table();
+    // canonical (column-major) form of the row-major product: m = output positions, n = filters
+    Problem p = canonical(dtype, MG_ROW_MAJOR, MG_NO_TRANS, MG_NO_TRANS, filters, n, k, alpha, weights, k, nullptr, n, beta,
+                          out, n, ws, ws_bytes, stream);
+    int32_t kernel = -1, split = 1;
+    const int32_t forced = g_override_kernel[dtype];
+    if (forced >= 0) {
+        if (t[forced].cfg.family != MG_FAMILY_CONV) return MG_ERR_CONFIG;       // a forced GEMM kernel: the unfold route
+        kernel = forced;
+        split = g_override_split[dtype];
+    } else {
+        // Measured on the four benchmark layers (FP16, us, fused / unfold route): 147 rows of the column matrix and 64
+        // filters 9.4 / 12.2; 576 rows, 128 filters 16.9 / 14.0; 1152 rows, 256 filters 30 (15.5 in four slices) /
+        // 14.9; 2304 rows, 512 filters 55 (20 in four slices) / 17.5.  A gathered K-tile takes about 1.5 us against
+        // 1.0 us for a stored one (each element is a load of its own behind index arithmetic), and every tile column
+        // of filters gathers the same elements again: the fused route pays where the sum is a few K-tiles and the
+        // filters are one tile column.
+        if (k > 256 || filters > 64) return MG_ERR_CONFIG;
+        int32_t plain = -1;
+        select_config(t, p, 256, ws_bytes, &plain, &split);
+        if (plain < 0) return MG_ERR_CONFIG;
+        const std::string name = t[plain].name;
+        const char *fused = nullptr;
+        if (name == "hmfma_64x64x64_w2x2_mk" || name == "hmfma_64x64x64_w2x2_mk_edge") fused = "hconv_64x64x64_w2x2";
+        else if (name == "smfma_64x64x32_w2x2_mk" || name == "smfma_64x64x32_w2x2_mk_edge") fused = "sconv_64x64x32_w2x2";
+        if (fused == nullptr) return MG_ERR_CONFIG;
+        for (size_t i = 0; i < t.size(); ++i)
+            if (std::string(t[i].name) == fused) kernel = static_cast<int32_t>(i);
+        if (kernel < 0) return MG_ERR_CONFIG;
+    }
+    p.A = im;
+    p.conv = &s;
+    const KernelEntry &e = t[kernel];
+    if (!e.legal || !e.legal(p, split, problem_alignment(p))) return MG_ERR_CONFIG;
+    const size_t need = e.workspace ? e.workspace(p, split) : 0;
+    if (need > 0 && (ws == nullptr || ws_bytes < need)) return forced >= 0 ? MG_ERR_WORKSPACE : MG_ERR_CONFIG;
+    return e.launch(p, split) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
+}
+
 // out (filters x OH*OW) = alpha * weights (filters x K) * col (K x OH*OW) + beta * out, all row-major; the
 // column matrix sits at the start of the workspace, the GEMM's own scratch (split-K) behind it
 mg_status run_conv2d(int dtype, const ConvShape &s, int64_t filters, float alpha, const void *im, const void *weights,
@@ -413,9 +460,18 @@ mg_status run_conv2d(int dtype, const ConvShape &s, int64_t filters, float alpha
     const size_t elem = dtype == MG_F32 ? 4 : 2;
     const void *col = im;
     size_t col_bytes = 0;
-    if (alpha != 0.f && !conv_is_plain_gemm(s)) {
-        col_bytes = round_up_256(static_cast<size_t>(k) * n * elem);
-        if (ws == nullptr || pointer_alignment(ws) < 256 || ws_bytes < col_bytes) return MG_ERR_WORKSPACE;
+    const bool plain = conv_is_plain_gemm(s);
+    const int32_t forced = g_override_kernel[dtype];
+    const bool forced_conv = forced >= 0 && table()[forced].cfg.family == MG_FAMILY_CONV;
+    if (alpha != 0.f && (!plain || forced_conv)) {
+        if (!plain) {
+            col_bytes = round_up_256(static_cast<size_t>(k) * n * elem);
+            if (ws == nullptr || pointer_alignment(ws) < 256 || ws_bytes < col_bytes) return MG_ERR_WORKSPACE;
+        }
+        // Without the unfold pass where a kernel that gathers op(A) from the image exists for the configuration the
+        // GEMM would get: the caller's workspace then only serves the slices of the sum.
+        mg_status fused = run_conv2d_fused(dtype, s, filters, n, k, alpha, im, weights, beta, out, ws, ws_bytes, stream);
+        if (fused != MG_ERR_CONFIG || forced_conv) return fused;
         if (launch_im2col(dtype, s, im, ws, static_cast<hipStream_t>(stream)) != hipSuccess) return MG_ERR_LAUNCH;
         col = ws;
     }

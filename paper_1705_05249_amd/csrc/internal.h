@@ -30,6 +30,8 @@ enum ProblemShape {
     MG_SHAPE_C_UPPER = 6
 };
 
+struct ConvShape;
+
 struct Problem {
     int dtype;                 // mg_dtype
     int64_t m, n, k;
@@ -48,6 +50,8 @@ struct Problem {
     int shape;                 // ProblemShape: where an operand is known to hold zeros / which part of C is wanted
     bool mask_c;               // shape C_LOWER / C_UPPER only: nothing outside that triangle of C may be written (or read);
                                // set only for kernels whose KernelEntry says masks_triangle
+    const ConvShape *conv;     // non-null: A is an image and op(A) (m x k, "along m") its column matrix, never stored;
+                               // only kernels of the family MG_FAMILY_CONV take such a problem
 
     int64_t a_sm() const { return a_trans ? lda : 1; }
     int64_t a_sk() const { return a_trans ? 1 : lda; }

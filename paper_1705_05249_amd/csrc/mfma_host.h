@@ -7,6 +7,19 @@ namespace mg {
 
 // Launches a macro-tile kernel over ceil(m/BM) x ceil(n/BN) tiles and `split` K slices, then (split > 1) the
 // kernel that sums the FP32 partials in the workspace and applies alpha and beta.
+inline ConvGeom conv_geometry(const ConvShape &s)
+{
+    ConvGeom g{};
+    g.channels = static_cast<int>(s.channels); g.h = static_cast<int>(s.height); g.w = static_cast<int>(s.width);
+    g.kh = static_cast<int>(s.kernel_h); g.kw = static_cast<int>(s.kernel_w);
+    g.pad_h = static_cast<int>(s.pad_h); g.pad_w = static_cast<int>(s.pad_w);
+    g.stride_h = static_cast<int>(s.stride_h); g.stride_w = static_cast<int>(s.stride_w);
+    g.dil_h = static_cast<int>(s.dilation_h); g.dil_w = static_cast<int>(s.dilation_w);
+    g.oh = static_cast<int>(conv_out_extent(s.height, s.kernel_h, s.pad_h, s.stride_h, s.dilation_h));
+    g.ow = static_cast<int>(conv_out_extent(s.width, s.kernel_w, s.pad_w, s.stride_w, s.dilation_w));
+    return g;
+}
+
 template <typename T, typename Kernel>
 hipError_t launch_tile_kernel(Kernel kernel, bool *attr_set, int lds_bytes, int threads, int bm, int bn, int k_per_split,
                               const Problem &p, int split)
@@ -31,6 +44,7 @@ hipError_t launch_tile_kernel(Kernel kernel, bool *attr_set, int lds_bytes, int 
     // K ranges that grow with the tile index: start the long ones first
     a.reversed = p.shape == MG_SHAPE_A_LOWER || p.shape == MG_SHAPE_B_UPPER;
     a.mask = p.mask_c && (p.shape == MG_SHAPE_C_LOWER || p.shape == MG_SHAPE_C_UPPER) ? 1 : 0;
+    if (p.conv != nullptr) a.conv = conv_geometry(*p.conv);
     hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(a.tiles_m) * a.tiles_n, 1, split), dim3(threads), lds_bytes,
                        p.stream, a);
     hipError_t e = hipGetLastError();
@@ -48,7 +62,8 @@ hipError_t launch_tile_kernel(Kernel kernel, bool *attr_set, int lds_bytes, int 
     return hipGetLastError();
 }
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, bool AK, bool BKC, bool EDGE, int RB = 32> struct MfmaConfig {
+template <typename T, int BM, int BN, int BK, int WM, int WN, bool AK, bool BKC, bool EDGE, int RB = 32, bool CONV = false>
+struct MfmaConfig {
     static constexpr int CH = ElemTraits<T>::CH;
     static constexpr int NT = WM * WN * 64;
     static constexpr int STAGES_LDS = 2 * (BM + BN) * 128;                    // two operand stages
@@ -65,6 +80,7 @@ template <typename T, int BM, int BN, int BK, int WM, int WN, bool AK, bool BKC,
     static bool legal(const Problem &p, int split, int64_t alignment)
     {
         if (p.dtype != DTYPE || p.a_trans != AK || p.b_trans == BKC) return false;
+        if ((p.conv != nullptr) != CONV) return false;            // op(A) is an image's column matrix, or it is not
         if (p.alpha == 0.f || p.k == 0) return false;
         if (split < 1 || split > 256 || split > ceil_div(p.k, BK)) return false;
         if (p.shape != MG_SHAPE_GENERAL && split != 1) return false;      // a narrowed K range is never sliced
@@ -95,14 +111,14 @@ template <typename T, int BM, int BN, int BK, int WM, int WN, bool AK, bool BKC,
     static hipError_t launch(const Problem &p, int split)
     {
         static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; races are harmless
-        return launch_tile_kernel<T>(mfma_gemm_kernel<T, BM, BN, BK, WM, WN, AK, BKC, EDGE, RB>, &attr_set, LDS, NT, BM, BN,
+        return launch_tile_kernel<T>(mfma_gemm_kernel<T, BM, BN, BK, WM, WN, AK, BKC, EDGE, RB, CONV>, &attr_set, LDS, NT, BM, BN,
                                      k_per_split(p, split), p, split);
     }
 
     static KernelEntry entry(const char *name)
     {
         mg_config c{};
-        c.family = MG_FAMILY_MFMA;
+        c.family = CONV ? MG_FAMILY_CONV : MG_FAMILY_MFMA;
         c.dtype = DTYPE;
         c.tile_m = BM; c.tile_n = BN; c.tile_k = BK;
         c.waves_m = WM; c.waves_n = WN;

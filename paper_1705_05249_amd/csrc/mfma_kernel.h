@@ -53,6 +53,12 @@ typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+// Geometry of a convolution whose column matrix is op(A) without ever being stored: row l = (c, kh, kw) of the
+// unfolded image, column i = (oh, ow) (the IM2COL routine of the paper's Section 3.1, folded into the GEMM's loader).
+struct ConvGeom {
+    int channels, h, w, kh, kw, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w, oh, ow;
+};
+
 struct MfmaArgs {
     const void *A;
     const void *B;
@@ -67,6 +73,7 @@ struct MfmaArgs {
     int shape;             // ProblemShape: K range per tile narrowed to the non-zero part / tiles outside C's triangle skipped
     int reversed;          // walk the tiles in reverse order (longest K ranges first)
     int mask;              // with shape C_LOWER / C_UPPER: write (and read) nothing outside that triangle of C
+    ConvGeom conv;         // kernels built with CONV: A is the image, op(A) its column matrix (m = oh * ow positions)
 };
 
 template <typename T> struct ElemTraits;
@@ -130,6 +137,52 @@ template <typename T> __device__ inline u32x4 gather_chunk(const T *p, int valid
     return r;
 }
 
+// CH consecutive output positions i, i + 1, ... of row l of the column matrix, fetched from the image: position
+// (oh, ow) of row (c, kh, kw) is im[c][oh * stride_h - pad_h + kh * dil_h][ow * stride_w - pad_w + kw * dil_w], zero
+// outside the image; element e valid iff e < valid.  In two parts, so that the loads can be in flight while other
+// work goes on (as the 16-byte loads of a stored operand are): conv_fetch only issues them (unconditionally, at the
+// plane's first element where the tap is outside) and notes which ones count; conv_pack, called when the piece
+// is needed, makes the 16 bytes.
+template <typename T> struct ConvPiece {
+    T v[ElemTraits<T>::CH];
+    uint32_t inside;           // bit e: element e is a tap inside the image and inside the matrix
+};
+template <typename T> __device__ __forceinline__ void conv_fetch(ConvPiece<T> &piece, const T *im, const ConvGeom g, int i, int l, int valid)
+{
+    constexpr int CH = ElemTraits<T>::CH;
+    const int kw = l % g.kw, rest = l / g.kw;
+    const int kh = rest % g.kh, c = rest / g.kh;
+    const T *plane = im + static_cast<int64_t>(c) * g.h * g.w;
+    int oh = i / g.ow, ow = i % g.ow;
+    const int dh = kh * g.dil_h - g.pad_h, dw = kw * g.dil_w - g.pad_w;
+    piece.inside = 0;
+    static_for<CH>([&](auto E) {                     // (a compile-time loop: the values must stay in registers)
+        constexpr int e = decltype(E)::value;
+        const int ih = oh * g.stride_h + dh, iw = ow * g.stride_w + dw;
+        const bool in = e < valid && static_cast<unsigned>(ih) < static_cast<unsigned>(g.h) && static_cast<unsigned>(iw) < static_cast<unsigned>(g.w);
+        piece.v[e] = plane[in ? ih * g.w + iw : 0];
+        piece.inside |= in ? 1u << e : 0u;
+        if (++ow == g.ow) { ow = 0; ++oh; }
+    });
+}
+template <typename T> __device__ __forceinline__ u32x4 conv_pack(const ConvPiece<T> &piece)
+{
+    constexpr int CH = ElemTraits<T>::CH;
+    u32x4 r = {0u, 0u, 0u, 0u};
+    static_for<CH>([&](auto E) {
+        constexpr int e = decltype(E)::value;
+        const uint32_t b = (piece.inside >> e) & 1u ? elem_bits<T>(piece.v[e]) : 0u;
+        if constexpr (sizeof(T) == 4) r[e] = b; else r[e >> 1] |= b << (16 * (e & 1));
+    });
+    return r;
+}
+template <typename T> __device__ __forceinline__ u32x4 conv_gather(const T *im, const ConvGeom g, int i, int l, int valid)
+{
+    ConvPiece<T> piece;
+    conv_fetch(piece, im, g, i, l, valid);
+    return conv_pack(piece);
+}
+
 // ---- one operand tile: global -> registers -> LDS ---------------------------------------------
 // The tile has ROWS rows (m or n index) and BK values of k.  Global element (row r, k index l) is at
 // X[l + r*ld] when KCONTIG, else at X[r + l*ld].  Each thread loads LOADS 16-byte pieces and makes STORES
@@ -139,7 +192,10 @@ template <typename T> __device__ inline u32x4 gather_chunk(const T *p, int valid
 // registers into CH stores of KU consecutive k.  KU = CH (whole 16-byte LDS chunks) when the tile has a unit of
 // that size for every thread; smaller tiles cut the units along k (SPLIT parts, stores of 16/SPLIT bytes) so
 // that every thread of the work-group takes part: with half of the wavefronts idle the 64-row tiles lost 20 %.
-template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct TileLoader {
+// CONV (bounds-checked flavour of an operand along its rows only): the operand is the column matrix of an image and
+// every piece is gathered from the image (conv_gather); nothing else changes.
+template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CONV = false> struct TileLoader {
+    static_assert(!CONV || (EDGE && !KCONTIG), "the implicit column matrix is an operand along its rows, loaded with checks");
     static constexpr int CH = ElemTraits<T>::CH;
     static constexpr int CPR = BK / CH;                                // 16-byte chunks per LDS row
     static constexpr int RS = 128;                                      // LDS row stride in bytes
@@ -168,7 +224,7 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
     // Bounds-checked flavour, FP32: whole K-tiles of tiles that have all their rows are loaded like the fast
     // flavour's (ragged problems of 2049^3 to 4104^3: 3-13 % faster; the FP16 kernels lost 10-17 % with the second
     // code path in their loop and keep to the checked loads).
-    static constexpr bool INTERIOR_FAST = EDGE && sizeof(T) == 4;
+    static constexpr bool INTERIOR_FAST = EDGE && sizeof(T) == 4 && !CONV;
 
     u32x4 regs[LOADS];
     // fast path: byte offset of each piece from the tile's first element, fixed for the whole kernel; a load is
@@ -226,6 +282,20 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
     int64_t ld;
     int rows_left, k_left;
     bool vec_ok, whole;
+    ConvGeom geom;             // CONV only
+    int conv_i, conv_l;        // first output position and first row of the column matrix in the tile aimed at
+    ConvPiece<T> raw[CONV ? LOADS : 1];     // CONV: the loaded elements of each piece, packed when the piece is stored
+
+    __device__ inline void aim_conv(const T *im, int64_t r0, int64_t l0, int rows_left_, int k_left_)
+    {
+        base = im;
+        conv_i = static_cast<int>(r0);
+        conv_l = static_cast<int>(l0);
+        rows_left = rows_left_;
+        k_left = k_left_;
+        vec_ok = false;
+        whole = false;
+    }
 
     __device__ inline void aim(const T *X, int64_t ld_, int64_t r0, int64_t l0, int rows_left_, int k_left_,
                                bool vec_ok_, bool whole_)
@@ -270,6 +340,9 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
                 // unit Q / KU starts (NT / RCH) * CH values of k behind the one before it, line Q % KU of a unit
                 // that many behind the first
                 regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[0], ((Q / KU) * (NT / RCH) * CH + Q % KU) * ld_bytes, 0);
+            } else if constexpr (CONV) {
+                const int rv = l < k_left ? rows_left - u.mc * CH : 0;
+                conv_fetch<T>(raw[Q], base, geom, conv_i + u.mc * CH, l < k_left ? conv_l + l : 0, rv);
             } else {
                 const T *p = base + u.mc * CH + l * ld;
                 const int rv = rows_left - u.mc * CH;
@@ -282,7 +355,7 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
     }
 
     // Store Q -> LDS.  On the transposing path store Q = u*CH + i is row i of unit u after the turn.
-    template <int Q> __device__ inline void store_one(char *lds) const
+    template <int Q> __device__ inline void store_one(char *lds)
     {
         const int t = threadIdx.x;
         if constexpr (KCONTIG) {
@@ -294,6 +367,8 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
             constexpr int i = Q % CH;
             const Unit u = unit_of(Q / CH);
             if (!u.valid) return;
+            if constexpr (CONV && i == 0)          // first store of a unit: its pieces become 16-byte values now
+                static_for<KU>([&](auto P) { regs[(Q / CH) * KU + decltype(P)::value] = conv_pack<T>(raw[(Q / CH) * KU + decltype(P)::value]); });
             char *dst = lds + lds_offset(u.mc * CH + i, u.kc) + u.s * (16 / SPLIT);
             const u32x4 row = transposed_row<i, KU>(&regs[(Q / CH) * KU], T{});
             if constexpr (SPLIT == 1) *reinterpret_cast<u32x4 *>(dst) = row;
@@ -303,7 +378,7 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE> struct 
     }
 
     __device__ inline void load_all() { static_for<LOADS>([&](auto q) { load_one<decltype(q)::value>(); }); }
-    __device__ inline void store_all(char *lds) const
+    __device__ inline void store_all(char *lds)
     {
         static_for<STORES>([&](auto q) { store_one<decltype(q)::value>(lds); });
     }
@@ -541,7 +616,7 @@ __device__ inline void tile_epilogue(typename BlockAcc<RB>::type (&acc)[FN][FM],
     }
 }
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, bool A_KCONTIG, bool B_KCONTIG, bool EDGE, int RB = 32>
+template <typename T, int BM, int BN, int BK, int WM, int WN, bool A_KCONTIG, bool B_KCONTIG, bool EDGE, int RB = 32, bool CONV = false>
 __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs args)
 {
     constexpr int NT = WM * WN * 64;
@@ -554,7 +629,7 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
     static_assert((WTM & (WTM - 1)) == 0 && (WTN & (WTN - 1)) == 0, "wavefront tile sides are powers of two");
     // the first fragments of the next tile go to fragment buffer 0 while the last step still uses its operands
     static_assert(KSTEPS % 2 == 0, "fragment double buffering needs an even number of K-steps");
-    using LoadA = TileLoader<T, BM, BK, NT, A_KCONTIG, EDGE>;
+    using LoadA = TileLoader<T, BM, BK, NT, A_KCONTIG, EDGE, CONV>;
     using LoadB = TileLoader<T, BN, BK, NT, B_KCONTIG, EDGE>;
     // LDS: [A stage 0][A stage 1][B stage 0][B stage 1]; stage offsets are compile-time in the unrolled K loop
     constexpr int A_BYTES = LoadA::LDS_BYTES, B_BYTES = LoadB::LDS_BYTES;
@@ -617,9 +692,11 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
     auto aim_tile = [&](int t) {
         int l0 = kb + t * BK;
         if constexpr (!EDGE) l0 = l0 < ke ? l0 : ke - BK;
-        la.aim(A, args.lda, m0, l0, rows_a, ke - l0, vec_a, whole_a);
+        if constexpr (CONV) la.aim_conv(A, m0, l0, rows_a, ke - l0);
+        else la.aim(A, args.lda, m0, l0, rows_a, ke - l0, vec_a, whole_a);
         lb.aim(B, args.ldb, n0, l0, rows_b, ke - l0, vec_b, whole_b);
     };
+    if constexpr (CONV) la.geom = args.conv;
     la.prepare(args.lda);
     lb.prepare(args.ldb);
 

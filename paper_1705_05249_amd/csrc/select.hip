@@ -116,13 +116,23 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
         }
     }
     // Problems of at most one 32 x 32 block per compute unit and a short sum: the kernel whose eight wavefronts share
-    // the sum of one block (tiny.hip) beats the macro tiles' software pipeline, which never fills (FP32 256^3: 6.8 ->
-    // 4.8 us, 512^3: 9.7 -> 7.2 us; at 384 x 384 x 1024 the two are level, beyond that the macro tiles win)
+    // the sum of one block (tiny.hip) beats the macro tiles' software pipeline, which never fills, and saves the
+    // second launch of a sliced sum.  Measured, shared-sum kernel against the best macro tile (with slices), us:
+    // FP32 256^3 4.8 / 6.8, 512^3 7.0 / 9.7, (256 | 384 | 512)^2 x 768: 8.9 / 9.2 | 10.0 | 10.8, x 1024: 11.3 / 10.0 |
+    // 13.8 | 11.8, x 1536: 15.3 / 11.4 | 15.3 | 14.2; FP16 with B along k, (256^2 | 384^2 | 512^2 | 512 x 196 |
+    // 256 x 784) x 1024: 5.8 / 6.7 | 5.8 / 6.6 | 6.1 / 6.7 | 5.8 | 5.9, x 2048: 8.7 / 9.0 | 8.8 / 8.9 | 9.6 / 9.7 |
+    // 8.7 / 10.7 | 8.8 / 12.9, x 3072: 11.6 / 10.3 | 11.6 / 13.1 | 12.4 / 11.2 | 11.6 / 11.5 | 13.7 / 14.2.
     const int64_t blocks32 = ceil_div(p.m, 32) * ceil_div(p.n, 32);
     const char *order_tag = p.a_trans ? (p.b_trans ? "kn" : "kk") : (p.b_trans ? "mn" : "mk");
-    if (f32 && p.shape == MG_SHAPE_GENERAL && blocks32 <= kComputeUnits && p.k >= 64 && p.k <= 640 && p.m > 1 && p.n > 1) {
+    const bool few_blocks = p.shape == MG_SHAPE_GENERAL && blocks32 <= kComputeUnits && p.m > 1 && p.n > 1;
+    if (f32 && few_blocks && p.k >= 64 && p.k <= (blocks32 > 64 ? 1024 : 768)) {
         char name[48];
         snprintf(name, sizeof name, "stiny_32x32_%s", order_tag);
+        if (try_pick(table, p, alignment, name, 1, kernel, split)) return;
+    }
+    if (!f32 && few_blocks && !p.b_trans && p.k >= 768 && p.k <= 2560) {
+        char name[48];
+        snprintf(name, sizeof name, "htiny_32x32_%s", order_tag);
         if (try_pick(table, p, alignment, name, 1, kernel, split)) return;
     }
     if (p.m >= 16 && p.n >= 16) {
@@ -296,8 +306,8 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 }
             }
             if (best < 0) break;
-            // FP16: where the macro tiles would cut a sum of at most three 512-wide chunks into slices (a second launch
-            // that adds the partial sums), the shared-sum kernel does it in one ((256, 784, 1152): 9.7 -> 8.8 us)
+            // FP16, other orders and shorter sums: where the macro tiles would cut a sum of at most three 512-wide chunks
+            // into slices (a second launch that adds the partial sums), the shared-sum kernel does it in one
             // (whether or not the caller brought the workspace for the slices)
             if (!f32 && attempt == 0 && free_slices > 1 && p.shape == MG_SHAPE_GENERAL && blocks32 <= kComputeUnits && p.k <= 1536) {
                 char name[48];

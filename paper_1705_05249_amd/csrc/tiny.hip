@@ -48,9 +48,13 @@ __global__ __launch_bounds__(512) void tiny_gemm_kernel(const TinyArgs a)
 
     // piece q = tid + 512 i of a chunk (i = 0 .. 7): operand q / 2048; k-contiguous operand: row (q % 2048) / 64, chunk q % 64;
     // else line (q % 2048) / CPL of k, row chunk q % CPL (CPL = 32 rows / CH per line)
-    u32x4 regs[LOADS];
-    auto load_chunk = [&](int k0) {
-        static_for<LOADS>([&](auto I) {
+    // up to DEPTH chunks are on their way at once (the whole K range of most problems this kernel is selected for:
+    // one memory latency instead of one per chunk)
+    constexpr int DEPTH = 3;
+    u32x4 regs[DEPTH][LOADS];
+    auto load_chunk = [&](auto SLOT, int k0) __attribute__((always_inline)) {
+        constexpr int slot = decltype(SLOT)::value;
+        static_for<LOADS>([&](auto I) __attribute__((always_inline)) {
             constexpr int i = decltype(I)::value;
             constexpr bool is_b = i >= LOADS / 2;              // pieces 0 .. 2047 are A's, the rest B's
             const int rem = tid + 512 * (i % (LOADS / 2));
@@ -70,7 +74,10 @@ __global__ __launch_bounds__(512) void tiny_gemm_kernel(const TinyArgs a)
                 }
             } else {
                 constexpr int CPL = 32 / CH;
-                const int line = rem / CPL, c = rem % CPL;
+                // FP16: the four pieces of a thread are four consecutive k lines of the same eight rows, so that the
+                // thread can turn them in registers (store_chunk); FP32: piece rem of the panel as it lies in memory
+                const int line = sizeof(T) == 2 ? 4 * (tid / CPL) + i % (LOADS / 2) : rem / CPL;
+                const int c = sizeof(T) == 2 ? tid % CPL : rem % CPL;
                 const int64_t row = row0 + c * CH;
                 const int rv = static_cast<int>(rows - row);
                 if (k0 + line < a.k && rv > 0) {
@@ -78,11 +85,12 @@ __global__ __launch_bounds__(512) void tiny_gemm_kernel(const TinyArgs a)
                     v = rv >= CH ? load_unaligned_chunk<T>(p) : gather_chunk<T>(p, rv);
                 }
             }
-            regs[i] = v;
+            regs[slot][i] = v;
         });
     };
-    auto store_chunk = [&] {
-        static_for<LOADS>([&](auto I) {
+    auto store_chunk = [&](auto SLOT) __attribute__((always_inline)) {
+        constexpr int slot = decltype(SLOT)::value;
+        static_for<LOADS>([&](auto I) __attribute__((always_inline)) {
             constexpr int i = decltype(I)::value;
             constexpr bool is_b = i >= LOADS / 2;
             const int rem = tid + 512 * (i % (LOADS / 2));
@@ -90,20 +98,22 @@ __global__ __launch_bounds__(512) void tiny_gemm_kernel(const TinyArgs a)
             char *panel = lds + (is_b ? kPanelBytes : 0);
             if constexpr (kcontig) {
                 const int r = rem / 64, c = rem % 64;
-                *reinterpret_cast<u32x4 *>(panel + r * kRowBytes + ((c ^ (r & 15)) << 4)) = regs[i];
+                *reinterpret_cast<u32x4 *>(panel + r * kRowBytes + ((c ^ (r & 15)) << 4)) = regs[slot][i];
             } else if constexpr (sizeof(T) == 4) {
                 // FP32: the panel stays as in memory, [k][row] in lines of 128 bytes (piece rem is simply at rem * 16);
                 // the fragment reads gather their four k values (each a conflict-free read of 32 consecutive rows)
-                *reinterpret_cast<u32x4 *>(panel + rem * 16) = regs[i];
-            } else {
+                *reinterpret_cast<u32x4 *>(panel + rem * 16) = regs[slot][i];
+            } else if constexpr (i % (LOADS / 2) == 0) {
+                // FP16 along m / n: this thread holds k lines 4 g .. 4 g + 3 of rows 8 c .. 8 c + 7 (pieces i .. i + 3);
+                // turned in registers they are eight 8-byte pieces [row][4 k]
                 constexpr int CPL = 32 / CH;
-                const int line = rem / CPL, c = rem % CPL;
-                const T *e = reinterpret_cast<const T *>(&regs[i]);
-#pragma unroll
-                for (int j = 0; j < CH; ++j) {
+                const int g = tid / CPL, c = tid % CPL;
+                static_for<CH>([&](auto J) {
+                    constexpr int j = decltype(J)::value;
+                    const u32x4 t = transposed_row<j, 4>(&regs[slot][i], T{});
                     const int r = c * CH + j;
-                    *reinterpret_cast<T *>(panel + r * kRowBytes + (((line / CH) ^ (r & 15)) << 4) + (line % CH) * sizeof(T)) = e[j];
-                }
+                    *reinterpret_cast<uint2 *>(panel + r * kRowBytes + (((g / 2) ^ (r & 15)) << 4) + (g % 2) * 8) = uint2{t[0], t[1]};
+                });
             }
         });
     };
@@ -123,37 +133,43 @@ __global__ __launch_bounds__(512) void tiny_gemm_kernel(const TinyArgs a)
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     const int ln = lane % 32, lg = lane / 32;
     const int chunks = (a.k + KC - 1) / KC;
-    load_chunk(0);
-    for (int ch = 0; ch < chunks; ++ch) {
-        if (ch > 0) __syncthreads();                       // everyone is done with the chunk before
-        store_chunk();
-        __syncthreads();
-        if (ch + 1 < chunks) load_chunk((ch + 1) * KC);
-        const int left = a.k - ch * KC;
-        const int steps = left >= KC ? STEPS : (left + 2 * CH - 1) / (2 * CH);
-        // this wavefront's K-steps of the chunk: all fragments first (one LDS latency), then the chain of MFMAs
-        u32x4 fa[STEPS / 8], fb[STEPS / 8];
+    static_for<DEPTH>([&](auto D) {
+        if (decltype(D)::value < chunks) load_chunk(D, decltype(D)::value * KC);
+    });
+    for (int base = 0; base < chunks; base += DEPTH) {
+        static_for<DEPTH>([&](auto D) {
+            const int ch = base + decltype(D)::value;
+            if (ch >= chunks) return;
+            if (ch > 0) __syncthreads();                       // everyone is done with the chunk before
+            store_chunk(D);
+            __syncthreads();
+            if (ch + DEPTH < chunks) load_chunk(D, (ch + DEPTH) * KC);
+            const int left = a.k - ch * KC;
+            const int steps = left >= KC ? STEPS : (left + 2 * CH - 1) / (2 * CH);
+            // this wavefront's K-steps of the chunk: all fragments first (one LDS latency), then the chain of MFMAs
+            u32x4 fa[STEPS / 8], fb[STEPS / 8];
 #pragma unroll
-        for (int j = 0; j < STEPS / 8; ++j) {
-            const int s = wave + 8 * j;
-            const int c = 2 * s + lg;
-            const int off = ln * kRowBytes + ((c ^ (ln & 15)) << 4);
-            if (s < steps) {
-                auto fragment = [&](auto KCONTIG, const char *panel) {
-                    if constexpr (decltype(KCONTIG)::value || sizeof(T) != 4) {
-                        return *reinterpret_cast<const u32x4 *>(panel + off);
-                    } else {
-                        const uint32_t *line = reinterpret_cast<const uint32_t *>(panel + (c * 4) * 128 + ln * 4);
-                        return u32x4{line[0], line[32], line[64], line[96]};
-                    }
-                };
-                fa[j] = fragment(std::integral_constant<bool, A_KCONTIG>{}, lds);
-                fb[j] = fragment(std::integral_constant<bool, B_KCONTIG>{}, lds + kPanelBytes);
+            for (int j = 0; j < STEPS / 8; ++j) {
+                const int s = wave + 8 * j;
+                const int c = 2 * s + lg;
+                const int off = ln * kRowBytes + ((c ^ (ln & 15)) << 4);
+                if (s < steps) {
+                    auto fragment = [&](auto KCONTIG, const char *panel) {
+                        if constexpr (decltype(KCONTIG)::value || sizeof(T) != 4) {
+                            return *reinterpret_cast<const u32x4 *>(panel + off);
+                        } else {
+                            const uint32_t *line = reinterpret_cast<const uint32_t *>(panel + (c * 4) * 128 + ln * 4);
+                            return u32x4{line[0], line[32], line[64], line[96]};
+                        }
+                    };
+                    fa[j] = fragment(std::integral_constant<bool, A_KCONTIG>{}, lds);
+                    fb[j] = fragment(std::integral_constant<bool, B_KCONTIG>{}, lds + kPanelBytes);
+                }
             }
-        }
 #pragma unroll
-        for (int j = 0; j < STEPS / 8; ++j)
-            if (wave + 8 * j < steps) mma(acc, fb[j], fa[j], T{});
+            for (int j = 0; j < STEPS / 8; ++j)
+                if (wave + 8 * j < steps) mma(acc, fb[j], fa[j], T{});
+        });
     }
     // The eight partial blocks -> LDS as [wavefront][register][lane] (register 4 q + i of lane l is
     // C(8 q + 4 (l / 32) + i, l % 32)); every thread adds the eight values of two (register, lane) pairs, hands the
@@ -193,6 +209,7 @@ template <typename T, bool AK, bool BKC> struct TinyConfig {
     {
         (void)alignment;
         if (p.dtype != DTYPE || p.a_trans != AK || p.b_trans == BKC || split != 1) return false;
+        if (p.conv != nullptr) return false;
         if (p.alpha == 0.f || p.k == 0 || p.shape != MG_SHAPE_GENERAL) return false;
         if (p.m >= (int64_t(1) << 31) || p.n >= (int64_t(1) << 31) || p.k >= (int64_t(1) << 31)) return false;
         return ceil_div(p.m, 32) * ceil_div(p.n, 32) < (int64_t(1) << 31);

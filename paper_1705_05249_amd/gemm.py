@@ -18,7 +18,7 @@ MG_UPPER, MG_LOWER = 121, 122
 MG_NON_UNIT, MG_UNIT = 131, 132
 MG_LEFT, MG_RIGHT = 141, 142
 MG_OK = 0
-MG_FAMILY_DIRECT, MG_FAMILY_MFMA, MG_FAMILY_GEMV, MG_FAMILY_SCALE, MG_FAMILY_BATCHED = 0, 1, 2, 3, 4
+MG_FAMILY_DIRECT, MG_FAMILY_MFMA, MG_FAMILY_GEMV, MG_FAMILY_SCALE, MG_FAMILY_BATCHED, MG_FAMILY_CONV = 0, 1, 2, 3, 4, 5
 
 EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemm_static", "mg_sgemv", "mg_hgemv", "mg_gemv_workspace_bytes",
            "mg_ssymm", "mg_hsymm", "mg_ssyrk", "mg_hsyrk", "mg_strmm", "mg_htrmm", "mg_symm_workspace_bytes",

@@ -11,8 +11,8 @@ batched workload: every batched kernel on every instance size and batch count (t
 its batched routine re-used the non-batched parameters sub-optimally, Section 4.6).  An interrupted
 sweep resumes: lines already in the output file are skipped.
 
-    python -m paper_1705_05249_amd.sweep --out gpurun_out/sweep.jsonl [--group 3] [--quick]
-    python -m paper_1705_05249_amd.sweep --summary gpurun_out/sweep.jsonl      (no GPU needed: winner, selection
+    python -m paper_1705_05249_amd.sweep --out sweep.jsonl [--group 3] [--quick]
+    python -m paper_1705_05249_amd.sweep --summary sweep.jsonl      (no GPU needed: winner, selection
                                                                                 and regret per shape, as markdown)
 
 Group 6 holds nine FP32 shapes for the problem-specific tuning experiment of the paper's Section 4.3
@@ -20,7 +20,7 @@ Group 6 holds nine FP32 shapes for the problem-specific tuning experiment of the
 to the problem's own winner.  Because the sweep times every configuration on every shape anyway, that
 matrix is a pure read-out of the timing file:
 
-    python -m paper_1705_05249_amd.sweep --cross gpurun_out/sweep.jsonl      (no GPU needed)
+    python -m paper_1705_05249_amd.sweep --cross sweep.jsonl      (no GPU needed)
 """
 import argparse
 import ctypes

@@ -132,7 +132,7 @@ def run_conv(case, workspace="auto"):
     return out.cpu().numpy()
 
 
-def check_conv(case, conv_oracle):
+def check_conv(case, conv_oracle, workspace="auto"):
     """GPU convolution against the direct-loop oracle; returns the relative error (0 for exact cases)."""
     from paper_1705_05249_amd import gemm as G
     ref, den = conv_oracle.conv2d(case.dtype, *conv_geometry(case), case.filters, case.alpha, case.im, case.weights,
@@ -140,7 +140,7 @@ def check_conv(case, conv_oracle):
     assert ref.shape[1:] == case.out_hw
     assert tuple(G.mg_conv2d_out_extent(s, k, p, st, d) for s, k, p, st, d in
                  zip((case.height, case.width), case.kernel, case.pad, case.stride, case.dilation)) == case.out_hw
-    got = run_conv(case)
+    got = run_conv(case, workspace)
     if case.exact:
         assert np.array_equal(got.astype(np.float64), ref), f"{case.name}: not bit-exact on integer inputs"
         return 0.0

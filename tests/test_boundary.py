@@ -288,7 +288,11 @@ def test_query_selected_and_override_roundtrip():
         G.mg_clear_override()
     assert G.mg_gemm_workspace_bytes(G.MG_F32, C, N, N, 4096, 4096, 4096, 4096, 4096, 4096) == 0
     # few tiles and a long K: split-K is selected, and the query says how much scratch it needs
-    sel = G.mg_query_selected(G.MG_F16, C, N, N, 512, 196, 2304, 512, 2304, 512)
-    need = G.mg_gemm_workspace_bytes(G.MG_F16, C, N, N, 512, 196, 2304, 512, 2304, 512)
+    sel = G.mg_query_selected(G.MG_F16, C, N, N, 512, 196, 4608, 512, 4608, 512)
+    need = G.mg_gemm_workspace_bytes(G.MG_F16, C, N, N, 512, 196, 4608, 512, 4608, 512)
     assert sel["split_k"] > 1 and need == sel["split_k"] * 512 * 196 * 4
+    # a sum short enough for the kernel whose eight wavefronts share it: one launch, no scratch
+    sel = G.mg_query_selected(G.MG_F16, C, N, N, 512, 196, 2304, 512, 2304, 512)
+    assert sel["name"] == "htiny_32x32_mk" and sel["split_k"] == 1
+    assert G.mg_gemm_workspace_bytes(G.MG_F16, C, N, N, 512, 196, 2304, 512, 2304, 512) == 0
     assert G.mg_gemm_workspace_bytes(G.MG_F32, 0, N, N, 256, 256, 256, 256, 256, 256) == 0

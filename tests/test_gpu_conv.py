@@ -51,8 +51,8 @@ def run_conv(G, case, workspace="auto"):
     return H.run_conv(case, workspace)
 
 
-def check_conv(G, CO, case):
-    return H.check_conv(case, CO)
+def check_conv(G, CO, case, workspace="auto"):
+    return H.check_conv(case, CO, workspace)
 
 
 SMALL = [  # channels, height, width, kernel, pad, stride, dilation, filters
@@ -133,3 +133,48 @@ def test_conv_reports_a_short_workspace(G):
     assert G.mg_sconv2d(*geometry(case), case.filters, 1.0, im, w, 0.0, out, None, check=False) == -10
     torch.cuda.synchronize()
     assert torch.equal(out, before)
+
+
+FUSED = {"f16": ("hconv_64x64x64_w2x2",), "f32": ("sconv_64x64x32_w2x2",)}
+ROUTES_GEO = SMALL + [
+    (16, 23, 19, (3, 3), (1, 1), (1, 1), (1, 1), 70),      # several tiles of output positions and of filters, ragged
+    (3, 40, 37, (7, 7), (3, 3), (2, 2), (1, 1), 33),       # a first layer in small: stride 2, 147 rows
+    (40, 9, 9, (3, 3), (1, 1), (1, 1), (2, 2), 20),        # long sum (360), dilation
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("geo", ROUTES_GEO)
+def test_conv_every_route(G, CO, dtype, geo):
+    """the same convolution through every kernel that gathers the column matrix from the image (forced, whole sum
+    and two slices) and through the unfold route (a forced plain GEMM kernel): bit-exact on integers, within
+    tolerance on random data"""
+    import torch
+    plain = ("smfma" if dtype == "f32" else "hmfma") + ("_64x64x32" if dtype == "f32" else "_64x64x64") + "_w2x2_mk_edge"
+    ws = torch.empty(8 << 20, dtype=torch.uint8, device="cuda")     # column matrix and the slices of any forced configuration
+    try:
+        for name in FUSED[dtype] + (plain,):
+            for split in (1, 2):
+                for integer in (True, False):
+                    case = W.conv_case(dtype, *geo, alpha=1.0 if integer else 0.75, beta=1.0 if integer else -0.5, case=7,
+                                       integer=integer)
+                    if case.k < 2 * (32 if dtype == "f32" else 64) and split > 1:
+                        continue                      # too short a sum for two slices
+                    G.mg_override_config(G.kernel_id(name), split)
+                    announce("conv", name, "split", split, case.name, geo, "integer" if integer else "random")
+                    check_conv(G, CO, case, ws)
+    finally:
+        G.mg_clear_override()
+
+
+def test_conv_kernel_family(G):
+    """the kernels that read op(A) from an image are listed as a family of their own and refuse a plain GEMM"""
+    import torch
+    names = {t["name"] for t in G.kernel_table() if t["family"] == G.MG_FAMILY_CONV}
+    assert names == {"hconv_64x64x64_w2x2", "sconv_64x64x32_w2x2"}
+    A = torch.zeros(64 * 64, device="cuda")
+    try:
+        G.mg_override_config(G.kernel_id("sconv_64x64x32_w2x2"), 1)
+        assert G.mg_sgemm(W.COL_MAJOR, W.NO_TRANS, W.NO_TRANS, 64, 64, 64, 1.0, A, 64, A, 64, 0.0, A.clone(), 64, None, check=False) == -11
+    finally:
+        G.mg_clear_override()

@@ -106,7 +106,7 @@ def test_hgemm_subnormal_inputs_are_not_flushed(G, oracle):
 def test_split_k_runs_only_with_workspace(G, oracle):
     """a shape for which split-K is selected: with the workspace the query asks for it runs split, without
     any workspace it silently runs unsplit; both give parity"""
-    case = W.config3(3)
+    case = W.hgemm_case(512, 196, 4608, case=3)     # too long a sum for the kernel whose wavefronts share it
     code = G.MG_F16
     sel = G.mg_query_selected(code, case.layout, case.ta, case.tb, case.m, case.n, case.k, case.lda, case.ldb, case.ldc)
     assert sel["split_k"] > 1
@@ -389,8 +389,8 @@ def _probe_cases(dtype):
 def test_every_kernel_configuration_gives_parity(G, oracle, dtype):
     import torch
     code = G.MG_F32 if dtype == "f32" else G.MG_F16
-    kernels = [t for t in G.kernel_table() if t["dtype"] == code and t["family"] != G.MG_FAMILY_BATCHED
-               and t["family"] != G.MG_FAMILY_SCALE]
+    kernels = [t for t in G.kernel_table() if t["dtype"] == code and t["family"] not in
+               (G.MG_FAMILY_BATCHED, G.MG_FAMILY_SCALE, G.MG_FAMILY_CONV)]        # the last: tests/test_gpu_conv.py
     ran = {t["name"]: 0 for t in kernels}
     ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
     try:
@@ -412,6 +412,29 @@ def test_every_kernel_configuration_gives_parity(G, oracle, dtype):
         G.mg_clear_override()
     never = [name for name, count in ran.items() if count == 0]
     assert not never, f"kernels never exercised: {never}"
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_shared_sum_kernels_over_several_chunks(G, oracle, dtype):
+    """the kernels whose eight wavefronts share the sum of one 32 x 32 block: K ranges of one to seven 1 KB chunks per
+    row (the loads of three chunks are in flight at once, so the fourth and later ones reuse registers), ragged in
+    every direction, all operand orders; bit-exact on integers (beta = 1), within tolerance on random data"""
+    per_chunk = 256 if dtype == "f32" else 512
+    orders = {"mk": (N, N), "kk": (T, N), "mn": (N, T), "kn": (T, T)}
+    try:
+        for order, (ta, tb) in orders.items():
+            G.mg_override_config(G.kernel_id(("s" if dtype == "f32" else "h") + "tiny_32x32_" + order), 1)
+            for m, n, k in ((64, 96, per_chunk), (45, 70, 3 * per_chunk - 5), (96, 33, 4 * per_chunk + 8), (33, 64, 7 * per_chunk - 1)):
+                for integer in (True, False):
+                    if dtype == "f32":
+                        case = W.skinny_case(m, n, k, case=21, integer=integer, ta=ta, tb=tb, alpha=1.0 if integer else 0.5,
+                                             beta=1.0 if integer else -0.75)
+                    else:
+                        case = W.hgemm_case(m, n, k, case=21, ta=ta, tb=tb, beta=1.0 if integer else 0.5, integer=integer)
+                    announce("tiny", dtype, order, case.name, "integer" if integer else "random")
+                    H.check_case(case, oracle)
+    finally:
+        G.mg_clear_override()
 
 
 @pytest.mark.parametrize("shape", [(256, 256, 64), (256, 512, 128), (768, 256, 448), (512, 512, 1024)])
