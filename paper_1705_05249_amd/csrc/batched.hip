@@ -133,17 +133,25 @@ __global__ __launch_bounds__(256) void batched_wave_kernel(const BatchedArgs a)
 #pragma unroll
             for (int bi = 0; bi < MB; ++bi) acc[q][bj][bi] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    // C_old first (longest latency chain ends in the store), then the operands
+    // Small instances: C_old first (the longest latency chain ends in the store), then the operands, all in flight
+    // at once.  An instance of 64^3 per wavefront has no registers for that (A, B and C_old are 64 each): its
+    // operands go first, all of them at once, and C_old is asked for when half of the MFMAs are done and the
+    // registers of the first K blocks are free again (with C_old first the compiler kept ten operand loads in
+    // flight and every group of MFMAs waited for memory).
+    constexpr bool LATE_C = MB * NB * IPW >= 16;
     V cold[IPW][NB][MB];
+    auto fetch_c = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int q = 0; q < IPW; ++q)
-        if (beta[q] != 0.f) {
+        for (int q = 0; q < IPW; ++q)
+            if (beta[q] != 0.f) {
 #pragma unroll
-            for (int bj = 0; bj < NB; ++bj)
+                for (int bj = 0; bj < NB; ++bj)
 #pragma unroll
-                for (int bi = 0; bi < MB; ++bi)
-                    cold[q][bj][bi] = load4<T, true, FULL>(C[q], a.ldc, col0 + bj * 16 + r16, bi * 16 + 4 * g, a.n, a.m);
-        }
+                    for (int bi = 0; bi < MB; ++bi)
+                        cold[q][bj][bi] = load4<T, true, FULL>(C[q], a.ldc, col0 + bj * 16 + r16, bi * 16 + 4 * g, a.n, a.m);
+            }
+    };
+    if constexpr (!LATE_C) fetch_c();
 
     V av[IPW][MB][KB], bv[IPW][NB][KB];
 #pragma unroll
@@ -159,16 +167,25 @@ __global__ __launch_bounds__(256) void batched_wave_kernel(const BatchedArgs a)
                     bv[q][bj][kb] = load4<T, B_KC, FULL>(B[q], a.ldb, col0 + bj * 16 + r16, kb * 16 + 4 * g, a.n, a.k);
             }
         }
+    if constexpr (LATE_C) __builtin_amdgcn_sched_barrier(0);      // every operand load is issued before the first MFMA
 #pragma unroll
-    for (int q = 0; q < IPW; ++q)
-        if (alpha[q] != 0.f) {
+    for (int kb = 0; kb < KB; ++kb) {
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb)
+        for (int q = 0; q < IPW; ++q)
+            if (alpha[q] != 0.f) {
 #pragma unroll
                 for (int bj = 0; bj < NB; ++bj)
 #pragma unroll
                     for (int bi = 0; bi < MB; ++bi) acc[q][bj][bi] = block_mma(av[q][bi][kb], bv[q][bj][kb], acc[q][bj][bi]);
+            }
+        if constexpr (LATE_C) {
+            if (kb == (KB - 1) / 2) {
+                __builtin_amdgcn_sched_barrier(0);
+                fetch_c();
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
+    }
 
     // lane (r16, g) holds C(i = 16 bi + 4g + r, j = 16 bj + r16), r = 0..3: four consecutive rows of one column
 #pragma unroll
