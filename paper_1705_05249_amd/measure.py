@@ -43,6 +43,20 @@ def timed(fn, steps, warmup):
     return start.elapsed_time(stop) * 1e-3 / steps, wall
 
 
+def fastest_single(fn, calls=20):
+    """device seconds of the fastest of `calls` launches, each between its own pair of events"""
+    import torch
+    best = float("inf")
+    for _ in range(calls):
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record()
+        fn()
+        stop.record()
+        torch.cuda.synchronize()
+        best = min(best, start.elapsed_time(stop) * 1e-3)
+    return best
+
+
 def _capture(calls):
     import torch
     side = torch.cuda.Stream()
