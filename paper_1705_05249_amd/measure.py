@@ -26,6 +26,22 @@ def rel_error(got, c_ref, d_ref):
     return float(err.max())
 
 
+def ramp(fn, seconds=0.05, calls_at_least=3):
+    """untimed launches for about `seconds` of device time: after an idle spell (host-side input generation) the
+    part needs some ten milliseconds of load before it holds its steady clock"""
+    import torch
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(calls_at_least):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    per_call = max(start.elapsed_time(stop) * 1e-3 / calls_at_least, 1e-6)
+    for _ in range(min(2000, int(seconds / per_call))):
+        fn()
+    torch.cuda.synchronize()
+
+
 def timed(fn, steps, warmup):
     """(device seconds per call from HIP events on the stream the launches go to, host seconds per call)"""
     import torch
