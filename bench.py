@@ -55,6 +55,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--no-probes", action="store_true", help="skip the measuring aids (profiling runs of a single kernel)")
     ap.add_argument("--only", default=None, help=" | ".join(GROUPS) + ": run a single group (profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -178,7 +179,7 @@ def main():
 
     # ---- what the fractions are judged against: launch floor, the matrix pipes alone, where the kernel's time goes
     probes = {}
-    if want("probes", "hgemm"):
+    if want("probes", "hgemm") and not args.no_probes:
         flag = torch.zeros(1, dtype=torch.float32, device="cuda")
         floor_graph, floor_eager = M.graph_timed(lambda: G.mg_probe_empty_launch(), flag, steps, warmup)
         probes["launch_floor"] = {"us_back_to_back_in_a_graph": round(floor_graph * 1e6, 3),
