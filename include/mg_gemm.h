@@ -34,6 +34,9 @@
  *     are checked on the host, in the order of the status codes below, before any GPU
  *     work; device-side contents (offset values, NaNs) are not checked.  When m == 0 or
  *     n == 0 (or batch_count == 0) the call returns MG_OK without launching anything.
+ *   - Errors outside the list each routine gives: MG_ERR_DIM also covers extents whose
+ *     products leave the index range of the kernels (2^40 elements per operand, 2^31 per
+ *     image plane and per column matrix).
  *   - The configuration override is process-global (relaxed atomics: a call that races with an
  *     override call uses either the old or the new configuration); everything may be called
  *     from several host threads.
@@ -293,7 +296,12 @@ mg_status mg_him2col(MG_CONV_GEOMETRY, const uint16_t *im, uint16_t *col, void *
 
 /* Convolution = IM2COL into the workspace, then the GEMM of this library on it.  The
  * workspace (device, 256-byte aligned) must hold mg_conv2d_workspace_bytes(); a 1x1 filter
- * with unit stride and no padding needs no column matrix (the image is the matrix). */
+ * with unit stride and no padding needs no column matrix (the image is the matrix).  Layers
+ * with few rows in the column matrix and at most 64 filters run as one launch of a GEMM
+ * kernel that gathers the column matrix from the image (kernels of the family
+ * MG_FAMILY_CONV; same result, the workspace is required all the same); forcing such a
+ * kernel with mg_override_config takes that route for any layer, forcing a GEMM kernel the
+ * IM2COL route. */
 mg_status mg_sconv2d(MG_CONV_GEOMETRY, int64_t filters, float alpha, const float *im,
                      const float *weights, float beta, float *out,
                      void *workspace, size_t workspace_bytes, void *stream);

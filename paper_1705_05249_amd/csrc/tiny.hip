@@ -12,8 +12,9 @@
 //
 // LDS: [A rows 0..31][B rows 0..31], 1 KB per row, the 16-byte chunk c of row r at slot c ^ (r % 16) (a fragment
 // read is 16 rows at one chunk per pass: 16 different slots).  An operand that is not contiguous along k: FP32 stays
-// as in memory ([k][row], 128 bytes per k) and a fragment is four 4-byte reads; FP16 is turned element by element on
-// its way into LDS (it is a few KB).
+// as in memory ([k][row], 128 bytes per k) and a fragment is four 4-byte reads; FP16 is turned in registers on its
+// way into LDS (a thread loads four k lines of eight rows and stores eight 8-byte pieces [row][4 k]).  Up to three
+// chunks are on their way from memory at once.
 #include "mfma_host.h"
 
 namespace mg {
