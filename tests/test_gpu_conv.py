@@ -140,6 +140,9 @@ ROUTES_GEO = SMALL + [
     (16, 23, 19, (3, 3), (1, 1), (1, 1), (1, 1), 70),      # several tiles of output positions and of filters, ragged
     (3, 40, 37, (7, 7), (3, 3), (2, 2), (1, 1), 33),       # a first layer in small: stride 2, 147 rows
     (40, 9, 9, (3, 3), (1, 1), (1, 1), (2, 2), 20),        # long sum (360), dilation
+    (2, 6, 10, (3, 5), (2, 4), (1, 1), (1, 1), 4),         # rows of ten positions: a piece of eight wraps; wide padding both sides
+    (1, 3, 8, (3, 3), (1, 1), (2, 1), (1, 1), 3),          # one channel, eight positions per row: every load near the image's ends
+    (3, 12, 13, (2, 4), (0, 3), (1, 1), (2, 1), 5),        # no padding above, wide to the left, dilation down
 ]
 
 
