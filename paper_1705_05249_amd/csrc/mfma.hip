@@ -15,6 +15,8 @@ void register_tiny(std::vector<KernelEntry> &table);
 void register_hdma_256x256x64_w2x2(std::vector<KernelEntry> &table);
 void register_hdma_256x256x64_w2x4(std::vector<KernelEntry> &table);
 void register_smfma_256x256x32_w2x2(std::vector<KernelEntry> &table);
+void register_smfma_256x256x32_w2x4(std::vector<KernelEntry> &table);
+void register_smfma_256x128x32_w4x2(std::vector<KernelEntry> &table);
 void register_smfma_256x128x32_w2x2(std::vector<KernelEntry> &table);
 void register_smfma_128x128x32_w2x2(std::vector<KernelEntry> &table);
 void register_smfma_128x64x32_w2x2(std::vector<KernelEntry> &table);
@@ -34,6 +36,8 @@ void register_mfma(std::vector<KernelEntry> &table)
     register_hdma_256x256x64_w2x2(table);
     register_hdma_256x256x64_w2x4(table);
     register_smfma_256x256x32_w2x2(table);
+    register_smfma_256x256x32_w2x4(table);
+    register_smfma_256x128x32_w4x2(table);
     register_smfma_256x128x32_w2x2(table);
     register_smfma_128x128x32_w2x2(table);
     register_smfma_128x64x32_w2x2(table);

@@ -168,8 +168,11 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
         // take 128 / 233 / 249 / 368 / 474 us): rounds of 256 tiles whatever the tile, at a rate that rises from
         // `per_group` (one round) towards `ceiling` (many), plus what a round of small tiles costs on top
         // (0 / 0 / 1 / 2 / 2.8 us from the largest tile to the smallest: first loads and the epilogue).
-        static const TileChoice f32_tiles[] = {{"smfma_256x256x32_w2x2", 256, 256, 32, 0.577f, 0.577f, 1},
-                                               {"smfma_256x128x32_w2x2", 256, 128, 32, 0.565f, 0.487f, 1},
+        // The two tiles of which a compute unit holds a single work-group run with eight wavefronts (two per SIMD:
+        // one hides the other's barrier and LDS waits; 4096^3 in the steady power state 1036 -> 932 us for 256 x 256,
+        // 973 -> 950 us for 256 x 128; the four-wavefront variants stay in the table).
+        static const TileChoice f32_tiles[] = {{"smfma_256x256x32_w2x4", 256, 256, 32, 0.577f, 0.577f, 1},
+                                               {"smfma_256x128x32_w4x2", 256, 128, 32, 0.565f, 0.487f, 1},
                                                {"smfma_128x128x32_w2x2", 128, 128, 32, 0.575f, 0.541f, 2},
                                                {"smfma_128x64x32_w2x2", 128, 64, 32, 0.56f, 0.517f, 3},
                                                {"smfma_64x64x32_w2x2", 64, 64, 32, 0.555f, 0.533f, 5}};

@@ -92,9 +92,14 @@ def graph_time(fn, per_graph=20, replays=10):
 
 
 def time_call(fn, min_seconds=2e-3, max_reps=200):
+    """seconds per call in the steady power state: after an idle spell the part needs some ten milliseconds of load
+    before it holds its clock (and the first launches can be faster or slower than the steady ones), so untimed
+    launches come first"""
     import torch
+    from .measure import ramp
     fn()
     torch.cuda.synchronize()
+    ramp(fn, 0.04)
     reps = 3
     while True:
         start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
