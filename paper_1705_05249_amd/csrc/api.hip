@@ -183,11 +183,10 @@ mg_status run_indirect(const Problem &p, const IndirectPlan &plan)
     const int64_t a_minor_p = p.a_trans ? plan.kp : plan.mp, a_major_p = p.a_trans ? plan.mp : plan.kp;
     const int64_t b_minor = p.b_trans ? p.n : p.k, b_major = p.b_trans ? p.k : p.n;
     const int64_t b_minor_p = p.b_trans ? plan.np : plan.kp, b_major_p = p.b_trans ? plan.kp : plan.np;
-    if (launch_pad_matrix(p.dtype, a_minor, a_major, p.A, p.lda, ap, a_minor_p, a_minor_p, a_major_p, st) != hipSuccess) return MG_ERR_LAUNCH;
-    if (launch_pad_matrix(p.dtype, b_minor, b_major, p.B, p.ldb, bp, b_minor_p, b_minor_p, b_major_p, st) != hipSuccess) return MG_ERR_LAUNCH;
-    if (p.beta != 0.f &&
-        launch_pad_matrix(p.dtype, p.m, p.n, p.C, p.ldc, cp, plan.mp, plan.mp, plan.np, st) != hipSuccess)
-        return MG_ERR_LAUNCH;
+    const PadCopy copies[3] = {{a_minor, a_major, p.A, p.lda, ap, a_minor_p, a_minor_p, a_major_p},
+                               {b_minor, b_major, p.B, p.ldb, bp, b_minor_p, b_minor_p, b_major_p},
+                               {p.m, p.n, p.C, p.ldc, cp, plan.mp, plan.mp, plan.np}};
+    if (launch_pad_matrices(p.dtype, copies, p.beta != 0.f ? 3 : 2, st) != hipSuccess) return MG_ERR_LAUNCH;
     Problem q = p;
     q.m = plan.mp; q.n = plan.np; q.k = plan.kp;
     q.A = ap; q.lda = a_minor_p;

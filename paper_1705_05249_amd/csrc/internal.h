@@ -115,6 +115,15 @@ hipError_t launch_pad_matrix(int dtype, int64_t minor, int64_t major, const void
                              int64_t minor_p, int64_t major_p, hipStream_t stream);
 hipError_t launch_unpad_matrix(int dtype, int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
                                hipStream_t stream);
+// one to three zero-padded copies (as launch_pad_matrix) in a single launch
+struct PadCopy {
+    int64_t minor, major;
+    const void *src;
+    int64_t lds;
+    void *dst;
+    int64_t ldd, minor_p, major_p;
+};
+hipError_t launch_pad_matrices(int dtype, const PadCopy *copies, int count, hipStream_t stream);
 
 // One compiled kernel (or kernel family instance) in the configuration table.
 struct KernelEntry {

@@ -183,6 +183,48 @@ __global__ __launch_bounds__(256) void pad_matrix_kernel(int minor, int major, c
     }
 }
 
+// Up to three such copies in one launch (blockIdx.z picks the job): the operands of one indirect GEMM are padded
+// together, which saves the gaps between dependent launches (3.5-4 us each, a tenth of a 2049^3 FP16 call).
+template <typename U> struct PadJob {
+    int minor, major, minor_p, major_p;
+    const U *src;
+    int64_t lds;
+    U *dst;
+    int64_t ldd;
+};
+template <typename U> struct PadJobs {
+    PadJob<U> job[3];
+};
+template <typename U, int V>
+__global__ __launch_bounds__(256) void pad_matrices_kernel(const PadJobs<U> jobs)
+{
+    using P = Pack<U, V>;
+    struct __attribute__((packed, aligned(sizeof(U)))) Loose { U v[V]; };
+    // (selected field by field: indexing the argument structure with blockIdx.z would put it on the stack)
+    const int z = blockIdx.z;
+    const PadJob<U> &a = jobs.job[0], &b = jobs.job[1], &c = jobs.job[2];
+    const int minor = z == 0 ? a.minor : (z == 1 ? b.minor : c.minor), major = z == 0 ? a.major : (z == 1 ? b.major : c.major);
+    const int minor_p = z == 0 ? a.minor_p : (z == 1 ? b.minor_p : c.minor_p), major_p = z == 0 ? a.major_p : (z == 1 ? b.major_p : c.major_p);
+    const U *__restrict__ src = z == 0 ? a.src : (z == 1 ? b.src : c.src);
+    U *__restrict__ dst = z == 0 ? a.dst : (z == 1 ? b.dst : c.dst);
+    const int64_t lds = z == 0 ? a.lds : (z == 1 ? b.lds : c.lds), ldd = z == 0 ? a.ldd : (z == 1 ? b.ldd : c.ldd);
+    const int i = (blockIdx.x * 256 + threadIdx.x) * V;
+    if (i >= minor_p) return;
+#pragma unroll 2
+    for (int j = blockIdx.y; j < major_p; j += gridDim.y) {
+        P out;
+        if (i + V <= minor && j < major) {
+            const Loose in = *reinterpret_cast<const Loose *>(src + i + j * lds);
+#pragma unroll
+            for (int e = 0; e < V; ++e) out.v[e] = in.v[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < V; ++e) out.v[e] = (i + e < minor && j < major) ? src[i + e + j * lds] : static_cast<U>(0);
+        }
+        *reinterpret_cast<P *>(dst + i + j * ldd) = out;
+    }
+}
+
 // dst (minor x major, leading dimension ldd, any element alignment) <- the leading part of src (leading dimension
 // lds, 16-byte aligned columns): the post-processing step of the indirect GEMM
 template <typename U, int V>
@@ -312,6 +354,28 @@ hipError_t launch_pad_matrix(int dtype, int64_t minor, int64_t major, const void
                            static_cast<int>(minor), static_cast<int>(major), static_cast<const uint16_t *>(src), lds,
                            static_cast<uint16_t *>(dst), ldd, static_cast<int>(minor_p), static_cast<int>(major_p));
     return hipGetLastError();
+}
+
+template <typename U, int V> static hipError_t launch_pads(const PadCopy *copies, int count, hipStream_t stream)
+{
+    PadJobs<U> jobs{};
+    unsigned gx = 1, gy = 1;
+    for (int q = 0; q < count; ++q) {
+        const PadCopy &c = copies[q];
+        jobs.job[q] = PadJob<U>{static_cast<int>(c.minor), static_cast<int>(c.major), static_cast<int>(c.minor_p),
+                                static_cast<int>(c.major_p), static_cast<const U *>(c.src), c.lds, static_cast<U *>(c.dst), c.ldd};
+        const dim3 g = column_grid(c.minor_p, c.major_p, V);
+        gx = g.x > gx ? g.x : gx;
+        gy = g.y > gy ? g.y : gy;
+    }
+    hipLaunchKernelGGL((pad_matrices_kernel<U, V>), dim3(gx, gy, static_cast<unsigned>(count)), dim3(256), 0, stream, jobs);
+    return hipGetLastError();
+}
+
+hipError_t launch_pad_matrices(int dtype, const PadCopy *copies, int count, hipStream_t stream)
+{
+    if (count < 1 || count > 3) return hipErrorInvalidValue;
+    return dtype == MG_F32 ? launch_pads<uint32_t, 4>(copies, count, stream) : launch_pads<uint16_t, 8>(copies, count, stream);
 }
 
 hipError_t launch_unpad_matrix(int dtype, int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
