@@ -340,7 +340,7 @@ mg_status mg_override_batched_config(int32_t kernel_id);
 /* Back to automatic selection (both overrides). */
 void mg_clear_override(void);
 
-/* ---- local-memory layout of the FP16 macro-tile kernels (paper Section 3.2: the layout of the
+/* ---- local-memory layout of the macro-tile kernels (paper Section 3.2: the layout of the
  * tiles in local memory is a tunable because bank conflicts cost) ----------------------------
  * Host-only introspection, no GPU involved: the functions evaluate the address formulas the
  * kernels are built from, so that a checker can run a bank model over them.
@@ -362,6 +362,16 @@ int32_t mg_lds_store_offset(int32_t k_contiguous, int32_t fragment_rows, int32_t
 int32_t mg_lds_read_offset(int32_t k_contiguous, int32_t fragment_rows, int32_t tile_rows,
                            int32_t wave_row, int32_t lane, int32_t fragment, int32_t k_step,
                            int32_t half);
+
+/* The same for the FP32 macro-tile kernels: an operand tile has tile_rows rows (64..256) and 32
+ * values of k; fragments are 32 rows.  k_contiguous != 0: [row][k] as above, one 16-byte read
+ * per lane and K-step (element selects the float inside it); else [k][row] as in memory, and the
+ * lane reads its four floats of the K-step one at a time (element 0..3).  Either way the lane
+ * then holds k = 8 * k_step + 4 * (lane / 32) + element of row
+ * wave_row + 32 * fragment + lane % 32; wave_row is a multiple of 32. */
+int32_t mg_lds_f32_store_offset(int32_t k_contiguous, int32_t tile_rows, int32_t row, int32_t k);
+int32_t mg_lds_f32_read_offset(int32_t k_contiguous, int32_t tile_rows, int32_t wave_row,
+                               int32_t lane, int32_t fragment, int32_t k_step, int32_t element);
 
 /* ---- measuring aids (paper Section 4.1: how the numbers are taken) --------------------------
  * Three launches that let a benchmark measure, in its own run, what its roofline fractions are

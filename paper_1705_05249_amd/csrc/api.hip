@@ -976,6 +976,25 @@ int32_t mg_lds_read_offset(int32_t k_contiguous, int32_t fragment_rows, int32_t 
     return base + k_step * (512 / fragment_rows) * line + half * 4 * line;
 }
 
+int32_t mg_lds_f32_store_offset(int32_t k_contiguous, int32_t tile_rows, int32_t row, int32_t k)
+{
+    if (tile_rows < 64 || tile_rows > 256 || tile_rows % 64 != 0 || row < 0 || row >= tile_rows || k < 0 || k >= 32) return -1;
+    if (k_contiguous) return mg::ldsmap::kcontig_slot<32>(row, k / 4) + 4 * (k % 4);
+    return mg::ldsmap::native_slot(tile_rows, k, row / 4) + 4 * (row % 4);
+}
+
+int32_t mg_lds_f32_read_offset(int32_t k_contiguous, int32_t tile_rows, int32_t wave_row, int32_t lane, int32_t fragment,
+                               int32_t k_step, int32_t element)
+{
+    if (tile_rows < 64 || tile_rows > 256 || tile_rows % 64 != 0) return -1;
+    if (wave_row < 0 || wave_row % 32 != 0 || lane < 0 || lane > 63 || fragment < 0 || k_step < 0 || k_step >= 4) return -1;
+    if (wave_row + 32 * (fragment + 1) > tile_rows || element < 0 || element > 3) return -1;
+    if (k_contiguous)
+        return (mg::ldsmap::kcontig_base<32>(lane, wave_row) ^ mg::ldsmap::kcontig_xor<32>(fragment, k_step)) + fragment * 32 * 128 +
+               4 * element;
+    return mg::ldsmap::native_base(tile_rows, lane, wave_row, fragment) + (8 * k_step + element) * 4 * tile_rows;
+}
+
 const char *mg_kernel_name(int32_t kernel_id)
 {
     if (kernel_id < 0 || kernel_id >= mg_kernel_count()) return "?";

@@ -2,7 +2,7 @@
 // an MFMA operand.  The local-memory layout is one of the tunables of the paper's gemm kernel (Section 3.2)
 // because bank conflicts cost; here it is a fixed, conflict-free choice per fragment shape.  These functions are
 // plain host + device code: the kernels use them to set up their addresses, and the library exports them
-// (mg_lds_read_offset, mg_lds_slot) so that a host-side checker can run the bank model over the very formulas the
+// (mg_lds_read_offset, mg_lds_store_offset and their FP32 counterparts) so that a host-side checker can run the bank model over the very formulas the
 // kernels use.
 //
 // Bank model of gfx950 (measured by timing reads in which one lane takes another lane's bank): 64 banks of 4
@@ -66,6 +66,20 @@ template <int RB> MG_HD constexpr int transposed_base(int lane, int wrow, int ro
     return transposed_slot(rows, k, row / 8) + 8 * ((row / 4) % 2);
 }
 template <int RB> MG_HD constexpr int transposed_xor(int f) { return 2 * RB * f; }
+
+// ---- [k][row] layout, FP32: as in memory, one line of `rows` floats per k (rows >= 64: a line is a whole number of
+// 256-byte bank rows).  An MFMA operand (v_mfma_f32_32x32x2_f32) is one float per lane: lanes 0-31 hold rows 0-31
+// at one k, lanes 32-63 the same rows at another; a K-step (8 values of k) is four such MFMAs with lanes 0-31 at
+// k = 8 s + j and lanes 32-63 at k = 8 s + 4 + j (j = 0..3), the assignment the [row][k] layout's 16-byte fragments
+// give.  A 4-byte read serves all 64 lanes in one clock when they hit 64 different banks: the two halves read the
+// same rows of two lines, so lines whose k has bit 2 set are shifted by half a bank row (chunk ^ 8).
+MG_HD constexpr int native_slot(int rows, int k, int chunk) { return k * 4 * rows + ((chunk ^ (8 * ((k >> 2) & 1))) << 4); }
+// Lane's read address for element j = 0 of fragment f, K-step 0; element j of K-step s is (8 s + j) lines on.
+MG_HD constexpr int native_base(int rows, int lane, int wrow, int f)
+{
+    const int m = wrow + 32 * f + lane % 32;
+    return native_slot(rows, 4 * (lane / 32), m / 4) + 4 * (m % 4);
+}
 
 }  // namespace ldsmap
 }  // namespace mg

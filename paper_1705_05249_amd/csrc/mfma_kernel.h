@@ -202,21 +202,27 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
     static constexpr int RCH = ROWS / CH;                               // row chunks per tile column
     static constexpr int CHUNKS = ROWS * CPR;
     static constexpr int BLOCKS = CHUNKS / CH;                         // CH x CH blocks (transposing path)
-    static constexpr int SPLIT = (KCONTIG || BLOCKS >= NT) ? 1 : (NT / BLOCKS < 4 ? NT / BLOCKS : 4);
+    // FP32 operands that are contiguous along their row index sit in LDS as they sit in memory, [k][row], and the
+    // MFMA operands are read one float at a time: a piece is stored as loaded (no turn in registers, no VALU work,
+    // which left the matrix pipes of the "mk" kernels 93 % busy against 97 % for operands along k)
+    static constexpr bool NATIVE = !KCONTIG && sizeof(T) == 4 && !CONV;
+    static constexpr bool PLAIN = KCONTIG || NATIVE;                    // one 16-byte store per 16-byte load
+    static constexpr int SPLIT = (PLAIN || BLOCKS >= NT) ? 1 : (NT / BLOCKS < 4 ? NT / BLOCKS : 4);
     static constexpr int KU = CH / SPLIT;                               // k values per unit
     static constexpr int UNITS = BLOCKS * SPLIT;
     static constexpr int UPT = (UNITS + NT - 1) / NT;                   // units per thread
-    static constexpr int LOADS = KCONTIG ? (CHUNKS + NT - 1) / NT : UPT * KU;
-    static constexpr int STORES = KCONTIG ? LOADS : UPT * CH;
+    static constexpr int LOADS = PLAIN ? (CHUNKS + NT - 1) / NT : UPT * KU;
+    static constexpr int STORES = PLAIN ? LOADS : UPT * CH;
     // the pipeline takes a loader's work in groups: GROUP_STORES stores (tile t+1), then GROUP_LOADS loads
     // (tile t+2) into the registers those stores have freed; a transposing group is one unit
-    static constexpr int GROUP_LOADS = KCONTIG ? (LOADS % 4 == 0 ? 4 : (LOADS % 2 == 0 ? 2 : 1)) : KU;
-    static constexpr int GROUP_STORES = KCONTIG ? GROUP_LOADS : CH;
-    static constexpr bool PARTIAL = KCONTIG ? (CHUNKS % NT != 0) : (UNITS % NT != 0);
+    static constexpr int GROUP_LOADS = PLAIN ? (LOADS % 4 == 0 ? 4 : (LOADS % 2 == 0 ? 2 : 1)) : KU;
+    static constexpr int GROUP_STORES = PLAIN ? GROUP_LOADS : CH;
+    static constexpr bool PARTIAL = PLAIN ? (CHUNKS % NT != 0) : (UNITS % NT != 0);
     static constexpr int LDS_BYTES = ROWS * RS;
     static_assert(CPR == 8 && ROWS % 8 == 0, "LDS rows are 128 bytes (eight swizzled 16-byte chunks)");
     static_assert(CH % SPLIT == 0 && KU * sizeof(T) >= 4 && (BLOCKS >= NT || NT % BLOCKS == 0), "unit shape");
     static_assert(NT % CPR == 0 && NT % RCH == 0 && (UPT == 1 || SPLIT == 1), "pieces of a thread are whole lines apart");
+    static_assert(!NATIVE || ROWS % 64 == 0, "a line of the [k][row] layout is a whole number of bank rows");
 
     // byte offset of logical chunk c of row r inside the operand's LDS tile
     __device__ static inline int lds_offset(int r, int c) { return ldsmap::kcontig_slot<32>(r, c); }
@@ -255,6 +261,8 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
             const int t = threadIdx.x;
             if constexpr (KCONTIG) {
                 goff[0] = static_cast<uint32_t>(((t / CPR) * ld_ + (t % CPR) * CH) * sizeof(T));
+            } else if constexpr (NATIVE) {
+                goff[0] = static_cast<uint32_t>(((t % RCH) * CH + (t / RCH) * ld_) * sizeof(T));
             } else {
                 const Unit u = unit_of(0);
                 goff[0] = static_cast<uint32_t>((u.mc * CH + (u.kc * CH + u.s * KU) * ld_) * sizeof(T));
@@ -266,6 +274,9 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
                 if constexpr (KCONTIG) {
                     const int idx = t + Q * NT;
                     goff[Q] = static_cast<uint32_t>(((idx / CPR) * ld_ + (idx % CPR) * CH) * sizeof(T));
+                } else if constexpr (NATIVE) {
+                    const int idx = t + Q * NT;
+                    goff[Q] = static_cast<uint32_t>(((idx % RCH) * CH + (idx / RCH) * ld_) * sizeof(T));
                 } else {
                     const Unit u = unit_of(Q / KU);
                     goff[Q] = static_cast<uint32_t>((u.mc * CH + (u.kc * CH + u.s * KU + Q % KU) * ld_) * sizeof(T));
@@ -330,6 +341,23 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
                 else if (kv >= CH) regs[Q] = load_unaligned_chunk<T>(p);
                 else regs[Q] = gather_chunk<T>(p, kv);
             }
+        } else if constexpr (NATIVE) {
+            // piece idx: row chunk idx % RCH of line idx / RCH; piece Q of a thread is NT / RCH lines behind piece 0
+            const int idx = t + Q * NT;
+            const int mc = idx % RCH, l = idx / RCH;
+            if (PARTIAL && idx >= CHUNKS) return;
+            if constexpr (!EDGE) {
+                regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
+            } else if (INTERIOR_FAST && whole && k_left >= BK) {
+                regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[0], (Q * (NT / RCH)) * ld_bytes, 0);
+            } else {
+                const T *p = base + mc * CH + l * ld;
+                const int rv = rows_left - mc * CH;
+                if (l >= k_left || rv <= 0) regs[Q] = u32x4{0u, 0u, 0u, 0u};
+                else if (vec_ok && rv >= CH) regs[Q] = *reinterpret_cast<const u32x4 *>(p);
+                else if (rv >= CH) regs[Q] = load_unaligned_chunk<T>(p);
+                else regs[Q] = gather_chunk<T>(p, rv);
+            }
         } else {
             const Unit u = unit_of(Q / KU);
             if (!u.valid) return;
@@ -363,6 +391,10 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
             const int c = idx % CPR, r = idx / CPR;
             if (PARTIAL && idx >= CHUNKS) return;
             *reinterpret_cast<u32x4 *>(lds + lds_offset(r, c)) = regs[Q];
+        } else if constexpr (NATIVE) {
+            const int idx = t + Q * NT;
+            if (PARTIAL && idx >= CHUNKS) return;
+            *reinterpret_cast<u32x4 *>(lds + ldsmap::native_slot(ROWS, idx / RCH, idx % RCH)) = regs[Q];
         } else {
             constexpr int i = Q % CH;
             const Unit u = unit_of(Q / CH);
@@ -675,6 +707,17 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
         }
     }
 
+    // operands in the [k][row] layout: the lane's address of element 0 of each fragment at K-step 0
+    int nat_a[FM], nat_b[FN];
+    if constexpr (LoadA::NATIVE) {
+#pragma unroll
+        for (int f = 0; f < FM; ++f) nat_a[f] = ldsmap::native_base(BM, lane, wm * WTM, f);
+    }
+    if constexpr (LoadB::NATIVE) {
+#pragma unroll
+        for (int f = 0; f < FN; ++f) nat_b[f] = 2 * A_BYTES + ldsmap::native_base(BN, lane, wn * WTN, f);
+    }
+
     using Acc = typename BlockAcc<RB>::type;
     Acc acc[FN][FM];
 #pragma unroll
@@ -704,11 +747,20 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
     // fragment F of K-step s in LDS stage `par`: F < FM -> A fragment F, else B fragment F - FM
     auto read_frag = [&](auto F, auto PAR, int s, int buf) {
         constexpr int f = decltype(F)::value, par = decltype(PAR)::value;
-        if constexpr (f < FM)
-            fa[buf][f] = *reinterpret_cast<const u32x4 *>(lds + frag_a[frag_select<RB>(f, s)] + f * RB * 128 + par * A_BYTES);
-        else
-            fb[buf][f - FM] = *reinterpret_cast<const u32x4 *>(lds + frag_b[frag_select<RB>(f - FM, s)] +
-                                                               (f - FM) * RB * 128 + par * B_BYTES);
+        // [k][row] layout: the four floats of the K-step, one line (rows * 4 bytes) apart
+        auto read_lines = [&](int at, int line) {
+            const char *p = lds + at + 8 * s * line;
+            return u32x4{*reinterpret_cast<const uint32_t *>(p), *reinterpret_cast<const uint32_t *>(p + line),
+                         *reinterpret_cast<const uint32_t *>(p + 2 * line), *reinterpret_cast<const uint32_t *>(p + 3 * line)};
+        };
+        if constexpr (f < FM) {
+            if constexpr (LoadA::NATIVE) fa[buf][f] = read_lines(nat_a[f] + par * A_BYTES, BM * 4);
+            else fa[buf][f] = *reinterpret_cast<const u32x4 *>(lds + frag_a[frag_select<RB>(f, s)] + f * RB * 128 + par * A_BYTES);
+        } else {
+            if constexpr (LoadB::NATIVE) fb[buf][f - FM] = read_lines(nat_b[f - FM] + par * B_BYTES, BN * 4);
+            else fb[buf][f - FM] = *reinterpret_cast<const u32x4 *>(lds + frag_b[frag_select<RB>(f - FM, s)] +
+                                                                    (f - FM) * RB * 128 + par * B_BYTES);
+        }
     };
     using Stage0 = std::integral_constant<int, 0>;
     using Stage1 = std::integral_constant<int, 1>;
@@ -740,7 +792,7 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
         constexpr int e = decltype(E)::value, par = decltype(PAR)::value;
         constexpr bool is_a = e < EV_A;
         constexpr int le = is_a ? e : e - EV_A;
-        constexpr bool kcontig = is_a ? A_KCONTIG : B_KCONTIG;
+        constexpr bool kcontig = is_a ? LoadA::PLAIN : LoadB::PLAIN;       // pieces stored as loaded
         // GS stores (row-wise loader: youngest piece first, so that the one wait in front of the first store
         // covers the whole group: loads return in order), then the GL reloads
         constexpr int GS = is_a ? LoadA::GROUP_STORES : LoadB::GROUP_STORES;

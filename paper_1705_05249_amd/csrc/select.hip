@@ -167,16 +167,19 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
         // a compute unit take turns rather than overlap (128 x 128 at k = 2048: 256 / 288 / 512 / 768 / 1024 tiles
         // take 128 / 233 / 249 / 368 / 474 us): rounds of 256 tiles whatever the tile, at a rate that rises from
         // `per_group` (one round) towards `ceiling` (many), plus what a round of small tiles costs on top
-        // (0 / 0 / 1 / 2 / 2.8 us from the largest tile to the smallest: first loads and the epilogue).
+        // (0 / 0 / 1 / 2 / 1.8 us from the largest tile to the smallest: first loads and the epilogue).
         // The two tiles of which a compute unit holds a single work-group run with eight wavefronts (two per SIMD:
         // one hides the other's barrier and LDS waits; 4096^3 in the steady power state 1036 -> 932 us for 256 x 256,
         // 973 -> 950 us for 256 x 128; the four-wavefront variants stay in the table).
-        static const TileChoice f32_tiles[] = {{"smfma_256x256x32_w2x4", 256, 256, 32, 0.577f, 0.577f, 1},
-                                               {"smfma_256x128x32_w4x2", 256, 128, 32, 0.565f, 0.487f, 1},
-                                               {"smfma_128x128x32_w2x2", 128, 128, 32, 0.575f, 0.541f, 2},
-                                               {"smfma_128x64x32_w2x2", 128, 64, 32, 0.56f, 0.517f, 3},
-                                               {"smfma_64x64x32_w2x2", 64, 64, 32, 0.555f, 0.533f, 5}};
-        static const double f32_round_cost[5] = {0.0, 0.0, 1.0e6, 2.0e6, 2.8e6};
+        // Rates: turns * tile flops / time of every tile on the squares 1024^3 to 6144^3 (the four operand orders run
+        // alike since the operands along m / n keep their memory layout in LDS): one turn gives `per_group`, many
+        // turns `ceiling`.
+        static const TileChoice f32_tiles[] = {{"smfma_256x256x32_w2x4", 256, 256, 32, 0.591f, 0.591f, 1},
+                                               {"smfma_256x128x32_w4x2", 256, 128, 32, 0.587f, 0.583f, 1},
+                                               {"smfma_128x128x32_w2x2", 128, 128, 32, 0.588f, 0.566f, 2},
+                                               {"smfma_128x64x32_w2x2", 128, 64, 32, 0.582f, 0.54f, 3},
+                                               {"smfma_64x64x32_w2x2", 64, 64, 32, 0.571f, 0.565f, 5}};
+        static const double f32_round_cost[5] = {0.0, 0.0, 1.0e6, 2.0e6, 1.8e6};
         const TileChoice *tiles = f32 ? f32_tiles : f16_tiles;
         const int count = f32 ? 5 : 8;
         bool tried[8] = {false, false, false, false, false, false, false, false};
@@ -206,18 +209,10 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
             };
             double time;
             if (f32) {
-                // a chip that is not full spreads its work-groups (ceil(blocks / 256) turns); beyond that, compute
-                // units are refilled as their work-groups retire, and whether the last, partial refill is spread
-                // or packed `resident` to a compute unit depends on the shape (768 tiles of 128 x 128 took three
-                // turns as 16 x 48 tiles and four as 48 x 16): the mean of the two is charged
-                double rounds;
-                if (blocks <= full) {
-                    rounds = static_cast<double>(ceil_div(blocks, kComputeUnits));
-                } else {
-                    const int64_t fills = blocks / full, rest = blocks - fills * full;
-                    rounds = static_cast<double>(fills * tiles[i].resident);
-                    if (rest > 0) rounds += 0.5 * static_cast<double>(tiles[i].resident + ceil_div(rest, kComputeUnits));
-                }
+                // work-groups take turns on a compute unit: ceil(blocks / 256) turns of one tile each, whether the
+                // compute units hold them all at once or are refilled as work-groups retire (squares of 1024 to 6144
+                // on every tile: within 6 % of this, the small tiles a little better where the last turn is thin)
+                const double rounds = static_cast<double>(ceil_div(blocks, kComputeUnits));
                 const double up = ceil(rounds);
                 // (the bounds-checked flavour runs at 0.5-0.8 of these rates; the same for every tile, but it
                 // decides between one long turn and several slices: (4097, 129, 4095) takes 132 us unsplit on 195

@@ -27,7 +27,7 @@ EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemm_static", "mg_sgemv", "mg_hgemv", "m
            "mg_sim2col", "mg_him2col", "mg_sconv2d", "mg_hconv2d", "mg_conv2d_workspace_bytes", "mg_conv2d_out_extent",
            "mg_kernel_count",
            "mg_kernel_info", "mg_kernel_name", "mg_query_selected", "mg_override_config",
-           "mg_override_batched_config", "mg_clear_override", "mg_lds_store_offset", "mg_lds_read_offset",
+           "mg_override_batched_config", "mg_clear_override", "mg_lds_store_offset", "mg_lds_read_offset", "mg_lds_f32_store_offset", "mg_lds_f32_read_offset",
            "mg_probe_empty_launch", "mg_probe_mfma_only", "mg_probe_hgemm_stamps",
            "mg_status_string", "mg_version")
 
@@ -138,6 +138,10 @@ def lib():
         L.mg_lds_store_offset.restype = ctypes.c_int32
         L.mg_lds_read_offset.argtypes = [ctypes.c_int32] * 8
         L.mg_lds_read_offset.restype = ctypes.c_int32
+        L.mg_lds_f32_store_offset.argtypes = [ctypes.c_int32] * 4
+        L.mg_lds_f32_store_offset.restype = ctypes.c_int32
+        L.mg_lds_f32_read_offset.argtypes = [ctypes.c_int32] * 7
+        L.mg_lds_f32_read_offset.restype = ctypes.c_int32
         L.mg_probe_empty_launch.argtypes = [vp]
         L.mg_probe_empty_launch.restype = i32
         L.mg_probe_mfma_only.argtypes = [ctypes.c_int32, vp, vp]
@@ -413,6 +417,14 @@ def mg_lds_store_offset(k_contiguous, fragment_rows, tile_rows, row, k) -> int:
 
 def mg_lds_read_offset(k_contiguous, fragment_rows, tile_rows, wave_row, lane, fragment, k_step, half=0) -> int:
     return lib().mg_lds_read_offset(int(bool(k_contiguous)), fragment_rows, tile_rows, wave_row, lane, fragment, k_step, half)
+
+
+def mg_lds_f32_store_offset(k_contiguous, tile_rows, row, k) -> int:
+    return lib().mg_lds_f32_store_offset(int(bool(k_contiguous)), tile_rows, row, k)
+
+
+def mg_lds_f32_read_offset(k_contiguous, tile_rows, wave_row, lane, fragment, k_step, element=0) -> int:
+    return lib().mg_lds_f32_read_offset(int(bool(k_contiguous)), tile_rows, wave_row, lane, fragment, k_step, element)
 
 
 def _checked(st, where, check):

@@ -1,12 +1,12 @@
-"""Host-only checks of the local-memory layout of the FP16 macro-tile kernels (paper Section 3.2: the layout of
+"""Host-only checks of the local-memory layout of the macro-tile kernels (paper Section 3.2: the layout of
 the tiles in local memory is tuned because bank conflicts cost).  The library exports the address formulas its
 kernels are built from; here they are run through (1) the definition of what a lane must receive and (2) a model
 of the LDS banks of gfx950.
 
 Bank model (measured on the GPU by timing reads in which one lane was given another lane's bank): 64 banks of 4
 bytes; lanes that read the same address share one access; an 8-byte read is served 32 consecutive lanes at a
-time; a 16-byte read 16 lanes at a time, namely lanes {0-3, 12-15, 20-27}, then {4-11, 16-19, 28-31}, and the
-same in the upper half of the wavefront."""
+time; a 16-byte access 16 lanes at a time, namely lanes {0-3, 12-15, 20-27}, then {4-11, 16-19, 28-31}, and the
+same in the upper half of the wavefront; a 4-byte read all 64 lanes at once."""
 import itertools
 
 import pytest
@@ -77,6 +77,56 @@ def test_transposing_fragment_reads_fetch_the_right_elements_without_conflicts(f
         assert cycles(addr, 8, PASSES_8B) == 2, (fragment_rows, tile_rows, wave_row, f, s, half)
 
 
+PASS_4B = [list(range(64))]
+
+
+@pytest.mark.parametrize("tile_rows", [64, 128, 256])
+def test_fp32_fragment_reads_fetch_the_right_elements_without_conflicts(tile_rows):
+    """FP32 tiles: [row][k] is read 16 bytes per lane, [k][row] one float at a time (all 64 lanes in one clock when
+    they hit 64 different banks)"""
+    for wave_row in range(0, tile_rows, 32):
+        for f, s in itertools.product(range((tile_rows - wave_row) // 32), range(4)):
+            addr = [G.mg_lds_f32_read_offset(True, tile_rows, wave_row, lane, f, s) for lane in range(64)]
+            for lane in range(64):
+                row, k0 = wave_row + 32 * f + lane % 32, 8 * s + 4 * (lane // 32)
+                for e in range(4):
+                    assert G.mg_lds_f32_store_offset(True, tile_rows, row, k0 + e) == addr[lane] + 4 * e
+                    assert G.mg_lds_f32_read_offset(True, tile_rows, wave_row, lane, f, s, e) == addr[lane] + 4 * e
+            assert cycles(addr, 16, PASSES_16B) == 4, (tile_rows, wave_row, f, s)
+            for e in range(4):
+                addr = [G.mg_lds_f32_read_offset(False, tile_rows, wave_row, lane, f, s, e) for lane in range(64)]
+                for lane in range(64):
+                    row, k = wave_row + 32 * f + lane % 32, 8 * s + 4 * (lane // 32) + e
+                    assert G.mg_lds_f32_store_offset(False, tile_rows, row, k) == addr[lane]
+                assert cycles(addr, 4, PASS_4B) == 1, (tile_rows, wave_row, f, s, e)
+
+
+@pytest.mark.parametrize("tile_rows,threads", [(64, 256), (128, 256), (256, 256), (256, 512)])
+def test_fp32_loader_stores_are_conflict_free(tile_rows, threads):
+    """the loaders' 16-byte stores: thread t + Q * threads holds piece number idx of the tile; [row][k]: row idx / 8,
+    chunk idx % 8; [k][row]: line idx / (rows / 4), row chunk idx % (rows / 4)"""
+    for first in range(0, tile_rows * 8, 64):             # one wavefront's store instruction
+        by_k, by_row = [], []
+        for idx in range(first, first + 64):
+            by_k.append(G.mg_lds_f32_store_offset(True, tile_rows, idx // 8, 4 * (idx % 8)))
+            by_row.append(G.mg_lds_f32_store_offset(False, tile_rows, 4 * (idx % (tile_rows // 4)), idx // (tile_rows // 4)))
+        assert cycles(by_k, 16, PASSES_16B) == 4 and cycles(by_row, 16, PASSES_16B) == 4, (tile_rows, first)
+
+
+def test_fp32_every_element_has_its_own_place():
+    for k_contiguous, tile_rows in itertools.product((True, False), (64, 128, 256)):
+        seen = {G.mg_lds_f32_store_offset(k_contiguous, tile_rows, row, k) for row in range(tile_rows) for k in range(32)}
+        assert len(seen) == tile_rows * 32 and min(seen) == 0 and max(seen) == tile_rows * 128 - 4
+        assert all(o % 4 == 0 for o in seen)
+
+
+def test_the_bank_model_sees_the_conflict_of_unshifted_lines():
+    """[k][row] without the half-bank-row shift of every other group of four lines: the two halves of the
+    wavefront read the same rows of two lines, i.e. the same banks"""
+    addr = [(4 * (lane // 32)) * 4 * 128 + 4 * (lane % 32) for lane in range(64)]
+    assert cycles(addr, 4, PASS_4B) == 2
+
+
 def test_every_element_has_its_own_place():
     for k_contiguous, fragment_rows, tile_rows in ((True, 32, 64), (True, 32, 256), (True, 16, 256), (False, 32, 256),
                                                    (False, 16, 128)):
@@ -107,3 +157,8 @@ def test_invalid_arguments():
     assert G.mg_lds_read_offset(True, 16, 256, 0, 64, 0, 0) == -1
     assert G.mg_lds_read_offset(True, 16, 256, 0, 0, 0, 2) == -1
     assert G.mg_lds_read_offset(False, 32, 256, 0, 0, 0, 0, 2) == -1
+    assert G.mg_lds_f32_store_offset(True, 96, 0, 0) == -1
+    assert G.mg_lds_f32_store_offset(False, 64, 0, 32) == -1
+    assert G.mg_lds_f32_read_offset(False, 64, 32, 0, 1, 0, 0) == -1
+    assert G.mg_lds_f32_read_offset(False, 64, 16, 0, 0, 0, 0) == -1
+    assert G.mg_lds_f32_read_offset(True, 64, 0, 0, 0, 4, 0) == -1
