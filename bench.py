@@ -108,8 +108,11 @@ def main():
         A, B, C, sel, call_on = gemm_setup(case)
         entry = {"workload": label, "kernel": sel["name"] + (f" split {sel['split_k']}" if sel["split_k"] > 1 else "")}
         if small:
-            dev, dev_eager = M.graph_timed(call_on(A, B, C), C, steps, warmup)
+            dev_graph, dev_eager = M.graph_timed(call_on(A, B, C), C, steps, warmup)
+            entry["ms_graph_replays"] = round(dev_graph * 1e3, 5)
             entry["ms_eager_launches"] = round(dev_eager * 1e3, 5)
+            # calls the host can issue faster than they run are back to back either way; a replay adds its own start-up
+            dev = min(dev_graph, dev_eager)
         else:
             M.ramp(call_on(A, B, C))
             dev, _ = M.timed(call_on(A, B, C), reps or max(5, steps // 5), max(1, warmup // 4))
@@ -121,7 +124,7 @@ def main():
         nbytes = A.numel() * A.element_size() + B.numel() * B.element_size() + C.numel() * C.element_size()
         if nbytes < M.LAST_LEVEL_CACHE_BYTES:
             entry["note"] = (f"{nbytes / 1e6:.1f} MB of operands: repeated calls are served by the 256 MB last-level cache"
-                             + ("; timed as replays of a HIP graph of 20 launches" if small else ""))
+                             + ("; the faster of eager launches and replays of a HIP graph of 20 launches" if small else ""))
         if cold:
             copies = []
 
@@ -316,13 +319,14 @@ def main():
             else:
                 call = lambda: generic_fn(bc.layout, bc.ta, bc.tb, bc.m, bc.n, bc.k, t["alphas"], t["A"], t["a_off"], bc.lda,
                                           t["B"], t["b_off"], bc.ldb, t["betas"], t["C"], t["c_off"], bc.ldc, bc.batch)
-            dev, dev_eager = M.graph_timed(call, t["C"], steps, warmup)
+            dev_graph, dev_eager = M.graph_timed(call, t["C"], steps, warmup)
+            dev = min(dev_graph, dev_eager)
             nbytes = bc.algorithmic_bytes - (bc.batch * 32 if strided else 0)
             resident = sum(t[x].numel() * t[x].element_size() for x in ("A", "B", "C"))
             entry = {"workload": label, "gflops": round(bc.flops / dev / 1e9, 1), "ms": round(dev * 1e3, 5),
-                     "ms_eager_launches": round(dev_eager * 1e3, 5),
+                     "ms_graph_replays": round(dev_graph * 1e3, 5), "ms_eager_launches": round(dev_eager * 1e3, 5),
                      "roofline": roofline("hbm", nbytes, dev, PEAK_HBM_GBS, label),
-                     "note": "timed as replays of a HIP graph of 20 launches; "
+                     "note": "the faster of eager launches and replays of a HIP graph of 20 launches; "
                              + (f"{resident / 1e6:.0f} MB working set: repeated calls are served by the 256 MB last-level cache"
                                 if resident < M.LAST_LEVEL_CACHE_BYTES else f"{resident / 1e6:.0f} MB working set: beyond the last-level cache, HBM-real")}
             extra.append(entry)

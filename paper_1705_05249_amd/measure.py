@@ -27,19 +27,24 @@ def rel_error(got, c_ref, d_ref):
 
 
 def ramp(fn, seconds=0.05, calls_at_least=3):
-    """untimed launches for about `seconds` of device time: after an idle spell (host-side input generation) the
-    part needs some ten milliseconds of load before it holds its steady clock"""
+    """untimed launches for at least `seconds` of device time: after an idle spell (host-side input generation) the
+    part needs some ten milliseconds of load before it holds its steady clock.  The first call is left out of the
+    count (it carries one-time costs: code upload, attribute calls), the rest is measured batch by batch until the
+    device has been busy that long."""
     import torch
-    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    start.record()
-    for _ in range(calls_at_least):
-        fn()
-    stop.record()
+    fn()
     torch.cuda.synchronize()
-    per_call = max(start.elapsed_time(stop) * 1e-3 / calls_at_least, 1e-6)
-    for _ in range(min(2000, int(seconds / per_call))):
-        fn()
-    torch.cuda.synchronize()
+    busy, batch = 0.0, calls_at_least
+    while busy < seconds:
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record()
+        for _ in range(batch):
+            fn()
+        stop.record()
+        torch.cuda.synchronize()
+        spent = max(start.elapsed_time(stop) * 1e-3, 1e-6)
+        busy += spent
+        batch = min(2000, max(calls_at_least, int((seconds - busy) / (spent / batch)) + 1))
 
 
 def timed(fn, steps, warmup):
