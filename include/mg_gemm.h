@@ -107,7 +107,9 @@ typedef struct mg_config {
     int32_t split_k;               /* >= 1; > 1 needs workspace                              */
     int32_t threads;               /* work-group size                                        */
     int32_t lds_bytes;             /* LDS per work-group                                     */
-    int32_t reserved;
+    int32_t fringe;                /* mg_query_selected only: 16 * r_m + r_n when the last r_m rows and
+                                      r_n columns of C (of the column-major view of the call) are computed
+                                      beside the tiles, see mg_override_fringe; else 0        */
 } mg_config;
 
 /* ---- GEMM (paper Section 1 / Section 3.1) --------------------------------------------
@@ -337,7 +339,18 @@ mg_status mg_query_selected(int dtype, int layout, int trans_a, int trans_b,
 mg_status mg_override_config(int32_t kernel_id, int32_t split_k);
 /* Same for the batched routine: kernel_id must be of family MG_FAMILY_BATCHED. */
 mg_status mg_override_batched_config(int32_t kernel_id);
-/* Back to automatic selection (both overrides). */
+/* Fringe of ragged FP32 problems (paper Section 4.2: sizes just above a multiple of the tile,
+ * the multiples of 129, are where tiled kernels lose most).  When m or n of the column-major view
+ * of a call is 1 to 4 more than a multiple of 64, the bounds-checked FP32 macro-tile kernels can
+ * leave those last rows / columns of C to extra work-groups of the same launch, which compute
+ * them as matrix-vector products on the vector ALUs, and tile only the rest.
+ * mode: MG_FRINGE_AUTO (default: where the selection expects a gain and no kernel is forced),
+ * MG_FRINGE_OFF (never), MG_FRINGE_ON (whenever a dimension qualifies, also with a forced kernel;
+ * a forced kernel that cannot do it then makes the call fail with MG_ERR_CONFIG).
+ * Other values: MG_ERR_CONFIG.  Results are the same up to summation order. */
+enum { MG_FRINGE_AUTO = 0, MG_FRINGE_OFF = 1, MG_FRINGE_ON = 2 };
+mg_status mg_override_fringe(int32_t mode);
+/* Back to automatic selection (all overrides). */
 void mg_clear_override(void);
 
 /* ---- local-memory layout of the macro-tile kernels (paper Section 3.2: the layout of the

@@ -22,6 +22,7 @@ std::once_flag g_once;
 std::atomic<int32_t> g_override_kernel[2] = {{-1}, {-1}};   // per dtype
 std::atomic<int32_t> g_override_split[2] = {{1}, {1}};
 std::atomic<int32_t> g_override_batched{-1};
+std::atomic<int32_t> g_fringe_mode{MG_FRINGE_AUTO};
 
 const std::vector<KernelEntry> &table()
 {
@@ -104,10 +105,32 @@ int64_t problem_alignment(const Problem &p)
 
 // Picks the configuration for a canonical problem: the override if one is active, else the
 // heuristic table.  Returns MG_OK and fills kernel/split, or an error.
-mg_status choose(const Problem &p, int64_t alignment, size_t workspace_bytes, int32_t *kernel, int32_t *split)
+// Fringe rows / columns of a ragged FP32 problem (fringe.h): a dimension that is 1 to 4 more than a multiple of
+// the smallest tile.  Automatic mode takes them off where that saves at least ~1.5 % of the tiles and the sum is long
+// enough for the problem to be bound by the matrix pipes rather than by memory (the fringe reads the other operand
+// once more).  Measured on (4097, 129, 4095) with both operands along k: 67 -> 47 us.
+void plan_fringe(Problem &p, bool forced)
+{
+    p.fringe_m = p.fringe_n = 0;
+    const int mode = g_fringe_mode;
+    if (mode == MG_FRINGE_OFF || (forced && mode != MG_FRINGE_ON)) return;
+    if (p.dtype != MG_F32 || p.shape != MG_SHAPE_GENERAL || p.mask_c || p.conv != nullptr || p.alpha == 0.f || p.k == 0) return;
+    if (p.m < 64 || p.n < 64) return;
+    if (mode == MG_FRINGE_AUTO && p.k < 256) return;
+    auto extra = [&](int64_t d) {
+        const int64_t r = d % 64;
+        return r >= 1 && r <= 4 && (mode == MG_FRINGE_ON || d <= 4160) ? static_cast<int>(r) : 0;
+    };
+    p.fringe_m = extra(p.m);
+    p.fringe_n = extra(p.n);
+}
+
+// Also decides the problem's fringe (p.fringe_m, p.fringe_n).
+mg_status choose(Problem &p, int64_t alignment, size_t workspace_bytes, int32_t *kernel, int32_t *split)
 {
     const auto &t = table();
     const int32_t forced = g_override_kernel[p.dtype];
+    plan_fringe(p, forced >= 0);
     if (forced >= 0) {
         const KernelEntry &e = t[forced];
         const int32_t forced_split = g_override_split[p.dtype];
@@ -117,6 +140,10 @@ mg_status choose(const Problem &p, int64_t alignment, size_t workspace_bytes, in
         return MG_OK;
     }
     select_config(t, p, alignment, workspace_bytes, kernel, split);
+    if (*kernel < 0 && (p.fringe_m != 0 || p.fringe_n != 0)) {
+        p.fringe_m = p.fringe_n = 0;                   // no kernel for the problem less its fringe: the whole problem
+        select_config(t, p, alignment, workspace_bytes, kernel, split);
+    }
     if (*kernel < 0) return MG_ERR_CONFIG;
     return MG_OK;
 }
@@ -278,7 +305,7 @@ mg_status run_gemv(int dtype, int layout, int trans, int64_t m, int64_t n, float
 {
     const mg_status s = check_gemv(layout, trans, m, n, lda, incx, incy);
     if (s != MG_OK) return s;
-    const Problem p = gemv_problem(dtype, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy, ws, ws_bytes, stream);
+    Problem p = gemv_problem(dtype, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy, ws, ws_bytes, stream);
     if (p.n == 0) return MG_OK;
     const bool reads = alpha != 0.f && p.k != 0;
     if (y == nullptr || (reads && (A == nullptr || x == nullptr))) return MG_ERR_NULL;
@@ -744,7 +771,7 @@ size_t mg_gemv_workspace_bytes(int dtype, int layout, int trans_a, int64_t m, in
 {
     if (dtype != MG_F32 && dtype != MG_F16) return 0;
     if (check_gemv(layout, trans_a, m, n, lda, 1, 1) != MG_OK) return 0;
-    const Problem p = gemv_problem(dtype, layout, trans_a, m, n, 1.f, nullptr, lda, nullptr, 1, 1.f, nullptr, 1, nullptr,
+    Problem p = gemv_problem(dtype, layout, trans_a, m, n, 1.f, nullptr, lda, nullptr, 1, 1.f, nullptr, 1, nullptr,
                                    0, nullptr);
     if (p.n == 0) return 0;
     int32_t kernel = -1, split = 1;
@@ -1019,6 +1046,7 @@ mg_status mg_query_selected(int dtype, int layout, int ta, int tb, int64_t m, in
     if (s != MG_OK) return s;
     *out = table()[kernel].cfg;
     out->split_k = split;
+    out->fringe = 16 * p.fringe_m + p.fringe_n;
     return MG_OK;
 }
 
@@ -1040,8 +1068,16 @@ mg_status mg_override_batched_config(int32_t kernel_id)
     return MG_OK;
 }
 
+mg_status mg_override_fringe(int32_t mode)
+{
+    if (mode != MG_FRINGE_AUTO && mode != MG_FRINGE_OFF && mode != MG_FRINGE_ON) return MG_ERR_CONFIG;
+    g_fringe_mode = mode;
+    return MG_OK;
+}
+
 void mg_clear_override(void)
 {
+    g_fringe_mode = MG_FRINGE_AUTO;
     g_override_kernel[0] = g_override_kernel[1] = -1;
     g_override_split[0] = g_override_split[1] = 1;
     g_override_batched = -1;

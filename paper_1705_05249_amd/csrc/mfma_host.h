@@ -22,7 +22,7 @@ inline ConvGeom conv_geometry(const ConvShape &s)
 
 template <typename T, typename Kernel>
 hipError_t launch_tile_kernel(Kernel kernel, bool *attr_set, int lds_bytes, int threads, int bm, int bn, int k_per_split,
-                              const Problem &p, int split)
+                              const Problem &p, int split, int64_t fringe_groups = 0)
 {
     if (!*attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -35,9 +35,10 @@ hipError_t launch_tile_kernel(Kernel kernel, bool *attr_set, int lds_bytes, int 
     a.partial = split > 1 ? static_cast<float *>(p.workspace) : nullptr;
     a.lda = p.lda; a.ldb = p.ldb; a.ldc = p.ldc;
     a.m = static_cast<int>(p.m); a.n = static_cast<int>(p.n); a.k = static_cast<int>(p.k);
+    a.m_main = static_cast<int>(p.m - p.fringe_m); a.n_main = static_cast<int>(p.n - p.fringe_n);
     a.alpha = p.alpha; a.beta = p.beta;
-    a.tiles_m = static_cast<int>(ceil_div(p.m, bm));
-    a.tiles_n = static_cast<int>(ceil_div(p.n, bn));
+    a.tiles_m = static_cast<int>(ceil_div(a.m_main, bm));
+    a.tiles_n = static_cast<int>(ceil_div(a.n_main, bn));
     a.k_per_split = k_per_split;
     a.group_m = 8;
     a.shape = p.shape;
@@ -45,8 +46,12 @@ hipError_t launch_tile_kernel(Kernel kernel, bool *attr_set, int lds_bytes, int 
     a.reversed = p.shape == MG_SHAPE_A_LOWER || p.shape == MG_SHAPE_B_UPPER;
     a.mask = p.mask_c && (p.shape == MG_SHAPE_C_LOWER || p.shape == MG_SHAPE_C_UPPER) ? 1 : 0;
     if (p.conv != nullptr) a.conv = conv_geometry(*p.conv);
-    hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(a.tiles_m) * a.tiles_n, 1, split), dim3(threads), lds_bytes,
-                       p.stream, a);
+    a.slices = split;
+    a.fringe_groups = static_cast<int>(fringe_groups);
+    // (the fringe work-groups of all slices fill whole grid layers behind the tiles')
+    const int64_t tiles = static_cast<int64_t>(a.tiles_m) * a.tiles_n;
+    const unsigned layers = static_cast<unsigned>(split + ceil_div(fringe_groups * split, tiles));
+    hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(tiles), 1, layers), dim3(threads), lds_bytes, p.stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || split == 1) return e;
     const int64_t total = p.m * p.n;
@@ -77,15 +82,31 @@ struct MfmaConfig {
         return static_cast<int>(ceil_div(ktiles, split) * BK);
     }
 
+    // the fringe rows and columns of a problem (fringe.h) are computed by the bounds-checked FP32 kernels only
+    static constexpr bool FRINGE = EDGE && sizeof(T) == 4 && !CONV;
+    static int64_t fringe_groups(const Problem &p)
+    {
+        int64_t groups = 0;
+        if (p.fringe_n > 0) groups += ceil_div(p.m, fringe_outputs_per_group(NT / 64, AK));
+        if (p.fringe_m > 0) groups += ceil_div(p.n - p.fringe_n, fringe_outputs_per_group(NT / 64, BKC));
+        return groups;
+    }
+
     static bool legal(const Problem &p, int split, int64_t alignment)
     {
         if (p.dtype != DTYPE || p.a_trans != AK || p.b_trans == BKC) return false;
+        if (p.fringe_m != 0 || p.fringe_n != 0) {
+            if (!FRINGE || p.shape != MG_SHAPE_GENERAL || p.mask_c) return false;
+            if (p.fringe_m < 0 || p.fringe_m > FRINGE_MAX || p.fringe_n < 0 || p.fringe_n > FRINGE_MAX) return false;
+            if (p.m - p.fringe_m < 1 || p.n - p.fringe_n < 1) return false;
+        }
         if ((p.conv != nullptr) != CONV) return false;            // op(A) is an image's column matrix, or it is not
         if (p.alpha == 0.f || p.k == 0) return false;
         if (split < 1 || split > 256 || split > ceil_div(p.k, BK)) return false;
         if (p.shape != MG_SHAPE_GENERAL && split != 1) return false;      // a narrowed K range is never sliced
         if (p.m >= (int64_t(1) << 31) || p.n >= (int64_t(1) << 31) || p.k >= (int64_t(1) << 31)) return false;
         if (ceil_div(p.m, BM) * ceil_div(p.n, BN) >= (int64_t(1) << 31)) return false;
+        if (split + ceil_div(fringe_groups(p) * split, ceil_div(p.m - p.fringe_m, BM) * ceil_div(p.n - p.fringe_n, BN)) > 65535) return false;
         if (split > 1 && static_cast<int64_t>(k_per_split(p, split)) * (split - 1) >= p.k) return false;  // empty slice
         {
             // lane offsets inside a tile are 32-bit byte offsets (both flavours)
@@ -112,7 +133,7 @@ struct MfmaConfig {
     {
         static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; races are harmless
         return launch_tile_kernel<T>(mfma_gemm_kernel<T, BM, BN, BK, WM, WN, AK, BKC, EDGE, RB, CONV>, &attr_set, LDS, NT, BM, BN,
-                                     k_per_split(p, split), p, split);
+                                     k_per_split(p, split), p, split, FRINGE ? fringe_groups(p) : 0);
     }
 
     static KernelEntry entry(const char *name)

@@ -40,6 +40,7 @@
 
 #include "internal.h"
 #include "lds_layout.h"
+#include "fringe.h"
 
 #ifndef MG_TAIL_SIXTEENTHS
 #define MG_TAIL_SIXTEENTHS 8   // share (in 1/16) of the last K-step that runs behind the per-tile barrier
@@ -66,6 +67,10 @@ struct MfmaArgs {
     float *partial;        // split-K partial sums [split][n][m] (FP32), or nullptr
     int64_t lda, ldb, ldc;
     int m, n, k;
+    int m_main, n_main;    // rows / columns of C that the tiles cover; the last m - m_main rows and n - n_main columns
+                           // (at most FRINGE_MAX each) are the fringe, computed by extra work-groups of the same launch
+    int slices;            // K slices (grid.z layers of tiles); the layers behind them hold the fringe work-groups
+    int fringe_groups;     // fringe work-groups per K slice
     float alpha, beta;
     int tiles_m, tiles_n;
     int k_per_split;       // multiple of the K tile
@@ -582,8 +587,8 @@ __device__ inline void tile_epilogue(typename BlockAcc<RB>::type (&acc)[FN][FM],
             const int64_t gn = gn0 + j * 32 + r, gm = gm0 + c * PER;
             int valid = PER, first = 0;          // elements first .. valid - 1 of the piece are written
             if constexpr (EDGE) {
-                const int64_t left = args.m - gm;
-                valid = gn >= args.n ? 0 : (left >= PER ? PER : (left > 0 ? static_cast<int>(left) : 0));
+                const int64_t left = args.m_main - gm;
+                valid = gn >= args.n_main ? 0 : (left >= PER ? PER : (left > 0 ? static_cast<int>(left) : 0));
             }
             if (args.mask != 0) {
                 // only the wanted triangle of C: rows gm + e >= gn (lower) or <= gn (upper) of column gn
@@ -648,6 +653,52 @@ __device__ inline void tile_epilogue(typename BlockAcc<RB>::type (&acc)[FN][FM],
     }
 }
 
+// Work-group `block` of the fringe (fringe.h) of K slice `slice`: the fringe columns of C take the first
+// ceil(m / outputs per group) work-groups, the fringe rows (over the columns the tiles cover) the rest.
+template <int NT, bool A_KCONTIG, bool B_KCONTIG> __device__ inline void fringe_group(const MfmaArgs &args, int block, int slice, char *lds)
+{
+    constexpr int WAVES = NT / 64;
+    constexpr int PER_A = fringe_outputs_per_group(WAVES, A_KCONTIG);
+    const float *A = static_cast<const float *>(args.A), *B = static_cast<const float *>(args.B);
+    const int fringe_n = args.n - args.n_main, fringe_m = args.m - args.m_main;
+    const int col_groups = fringe_n > 0 ? (args.m + PER_A - 1) / PER_A : 0;
+    FringeView v;
+    v.kb = slice * args.k_per_split;
+    v.ke = (v.kb + args.k_per_split < args.k) ? v.kb + args.k_per_split : args.k;
+    v.raw = args.partial != nullptr;
+    v.alpha = args.alpha;
+    v.beta = args.beta;
+    float *out = v.raw ? args.partial + static_cast<int64_t>(slice) * args.n * args.m : static_cast<float *>(args.C);
+    const int64_t ld_out = v.raw ? static_cast<int64_t>(args.m) : args.ldc;
+    if (block < col_groups) {
+        v.wide = A;
+        v.w_so = A_KCONTIG ? args.lda : 1;
+        v.w_sl = A_KCONTIG ? 1 : args.lda;
+        v.narrow = B + static_cast<int64_t>(args.n_main) * (B_KCONTIG ? args.ldb : 1);
+        v.n_sf = B_KCONTIG ? args.ldb : 1;
+        v.n_sl = B_KCONTIG ? 1 : args.ldb;
+        v.outputs = args.m;
+        v.count = fringe_n;
+        v.out = out + static_cast<int64_t>(args.n_main) * ld_out;
+        v.o_so = 1;
+        v.o_sf = ld_out;
+        fringe_run<WAVES, A_KCONTIG>(v, block, lds);
+    } else {
+        v.wide = B;
+        v.w_so = B_KCONTIG ? args.ldb : 1;
+        v.w_sl = B_KCONTIG ? 1 : args.ldb;
+        v.narrow = A + static_cast<int64_t>(args.m_main) * (A_KCONTIG ? args.lda : 1);
+        v.n_sf = A_KCONTIG ? args.lda : 1;
+        v.n_sl = A_KCONTIG ? 1 : args.lda;
+        v.outputs = args.n_main;
+        v.count = fringe_m;
+        v.out = out + args.m_main;
+        v.o_so = ld_out;
+        v.o_sf = 1;
+        fringe_run<WAVES, B_KCONTIG>(v, block - col_groups, lds);
+    }
+}
+
 template <typename T, int BM, int BN, int BK, int WM, int WN, bool A_KCONTIG, bool B_KCONTIG, bool EDGE, int RB = 32, bool CONV = false>
 __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs args)
 {
@@ -670,6 +721,18 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
 
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
+    if constexpr (EDGE && sizeof(T) == 4 && !CONV) {
+        // Grid layers behind the K slices compute the fringe rows and columns.  They come last in the launch order on
+        // purpose: mixed in with the tiles of each slice they shift which compute unit a tile lands on, and a grid of
+        // exactly two tiles per compute unit then puts three on some ((4097, 128, 4095) in four slices: 42 -> 57 us).
+        if (static_cast<int>(blockIdx.z) >= args.slices) {
+            const int g = (static_cast<int>(blockIdx.z) - args.slices) * static_cast<int>(gridDim.x) + static_cast<int>(blockIdx.x);
+            if (g < args.fringe_groups * args.slices)
+                fringe_group<NT, A_KCONTIG, B_KCONTIG>(args, g % args.fringe_groups, g / args.fringe_groups, lds);
+            return;
+        }
+    }
+
     int tm, tn;
     if (args.shape == 0) tile_coords(blockIdx.x, args.tiles_m, args.tiles_n, args.group_m, tm, tn);
     else tile_coords_balanced(blockIdx.x, args.tiles_m, args.tiles_n, args.group_m, args.reversed != 0, args.shape == MG_SHAPE_C_UPPER, tm, tn);
@@ -680,8 +743,8 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
 
     const T *__restrict__ A = static_cast<const T *>(args.A);
     const T *__restrict__ B = static_cast<const T *>(args.B);
-    const int rows_a = static_cast<int>(args.m - m0 < BM ? args.m - m0 : BM);
-    const int rows_b = static_cast<int>(args.n - n0 < BN ? args.n - n0 : BN);
+    const int rows_a = static_cast<int>(args.m_main - m0 < BM ? args.m_main - m0 : BM);
+    const int rows_b = static_cast<int>(args.n_main - n0 < BN ? args.n_main - n0 : BN);
     bool vec_a = true, vec_b = true, whole_a = true, whole_b = true;
     if constexpr (EDGE) {
         vec_a = (args.lda % CH == 0) && (reinterpret_cast<uintptr_t>(A) % 16 == 0);

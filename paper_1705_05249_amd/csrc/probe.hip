@@ -89,6 +89,8 @@ mg_status mg_probe_hgemm_stamps(int64_t m, int64_t n, int64_t k, const uint16_t 
     a.partial = reinterpret_cast<float *>(stamps);       // the stamped build writes its record here, not partial sums
     a.lda = lda; a.ldb = ldb; a.ldc = ldc;
     a.m = static_cast<int>(m); a.n = static_cast<int>(n); a.k = static_cast<int>(k);
+    a.m_main = a.m; a.n_main = a.n;
+    a.slices = 1;
     a.alpha = 1.f; a.beta = 0.f;
     a.tiles_m = static_cast<int>(m / 256); a.tiles_n = static_cast<int>(n / 256);
     a.k_per_split = static_cast<int>(k);

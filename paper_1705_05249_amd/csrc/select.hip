@@ -122,6 +122,8 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
     // 13.8 | 11.8, x 1536: 15.3 / 11.4 | 15.3 | 14.2; FP16 with B along k, (256^2 | 384^2 | 512^2 | 512 x 196 |
     // 256 x 784) x 1024: 5.8 / 6.7 | 5.8 / 6.6 | 6.1 / 6.7 | 5.8 | 5.9, x 2048: 8.7 / 9.0 | 8.8 / 8.9 | 9.6 / 9.7 |
     // 8.7 / 10.7 | 8.8 / 12.9, x 3072: 11.6 / 10.3 | 11.6 / 13.1 | 12.4 / 11.2 | 11.6 / 11.5 | 13.7 / 14.2.
+    // (with fringe rows / columns taken off, the tiles cover tm x tn of C)
+    const int64_t tm = p.m - p.fringe_m, tn = p.n - p.fringe_n;
     const int64_t blocks32 = ceil_div(p.m, 32) * ceil_div(p.n, 32);
     const char *order_tag = p.a_trans ? (p.b_trans ? "kn" : "kk") : (p.b_trans ? "mn" : "mk");
     const bool few_blocks = p.shape == MG_SHAPE_GENERAL && blocks32 <= kComputeUnits && p.m > 1 && p.n > 1;
@@ -185,7 +187,7 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
         bool tried[8] = {false, false, false, false, false, false, false, false};
         // estimated time (in 1e-6 us) of tile i with the sum cut into `slices`
         auto estimate = [&](int i, int slices) {
-            const int64_t blocks = ceil_div(p.m, tiles[i].bm) * ceil_div(p.n, tiles[i].bn) * slices;
+            const int64_t blocks = ceil_div(tm, tiles[i].bm) * ceil_div(tn, tiles[i].bn) * slices;
             const double tile_flops = 2.0 * tiles[i].bm * tiles[i].bn * static_cast<double>(p.k) / slices;
             const int64_t full = static_cast<int64_t>(kComputeUnits) * tiles[i].resident;   // work-groups the chip holds
             double order = 1.0;
@@ -198,7 +200,7 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
             // ragged or unaligned FP16 problems run the bounds-checked flavour, which costs the smaller tiles more
             // (rates against the whole-tile flavour: 0.75 for 256 x 256 and 256 x 128, about 0.5 for 128 x 128
             // and below; FP32: see below)
-            const bool ragged = p.m % tiles[i].bm || p.n % tiles[i].bn || p.k % tiles[i].bk;
+            const bool ragged = tm % tiles[i].bm || tn % tiles[i].bn || p.k % tiles[i].bk || tm != p.m || tn != p.n;
             if (!f32 && ragged) order *= tiles[i].bm * tiles[i].bn < 256 * 128 ? 0.6 : 0.7;
             // rate of a compute unit that holds u work-groups at once: ceiling * (1 - (1 - per_group / ceiling)^u)
             // (measured on the 64 x 64 FP16 tile: 1.33 / 1.85 / 2.02 / 2.11 for u = 1..4, the formula gives
@@ -284,7 +286,7 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 if (f32 && p.k <= 128 && tiles[i].bm * tiles[i].bn > 128 * 64) continue;
                 const bool last = i == count - 1;
                 const int64_t ktiles = ceil_div(p.k, tiles[i].bk);
-                const int64_t blocks = ceil_div(p.m, tiles[i].bm) * ceil_div(p.n, tiles[i].bn);
+                const int64_t blocks = ceil_div(tm, tiles[i].bm) * ceil_div(tn, tiles[i].bn);
                 // slices tried: none; for the smallest tile the factor of the sweep's rule; for grids that do not
                 // fill the chip powers of two that leave every slice at least four K-tiles (never with a shape hint)
                 int options[6] = {1, 0, 0, 0, 0, 0};

@@ -27,7 +27,7 @@ EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemm_static", "mg_sgemv", "mg_hgemv", "m
            "mg_sim2col", "mg_him2col", "mg_sconv2d", "mg_hconv2d", "mg_conv2d_workspace_bytes", "mg_conv2d_out_extent",
            "mg_kernel_count",
            "mg_kernel_info", "mg_kernel_name", "mg_query_selected", "mg_override_config",
-           "mg_override_batched_config", "mg_clear_override", "mg_lds_store_offset", "mg_lds_read_offset", "mg_lds_f32_store_offset", "mg_lds_f32_read_offset",
+           "mg_override_batched_config", "mg_override_fringe", "mg_clear_override", "mg_lds_store_offset", "mg_lds_read_offset", "mg_lds_f32_store_offset", "mg_lds_f32_read_offset",
            "mg_probe_empty_launch", "mg_probe_mfma_only", "mg_probe_hgemm_stamps",
            "mg_status_string", "mg_version")
 
@@ -35,7 +35,7 @@ EXPORTS = ("mg_sgemm", "mg_hgemm", "mg_sgemm_static", "mg_sgemv", "mg_hgemv", "m
 class mg_config(ctypes.Structure):
     _fields_ = [(name, ctypes.c_int32) for name in
                 ("kernel_id", "family", "dtype", "tile_m", "tile_n", "tile_k", "waves_m", "waves_n",
-                 "split_k", "threads", "lds_bytes", "reserved")]
+                 "split_k", "threads", "lds_bytes", "fringe")]
 
     def as_dict(self):
         return {name: getattr(self, name) for name, _ in self._fields_}
@@ -132,6 +132,8 @@ def lib():
         L.mg_override_config.restype = i32
         L.mg_override_batched_config.argtypes = [ctypes.c_int32]
         L.mg_override_batched_config.restype = i32
+        L.mg_override_fringe.argtypes = [ctypes.c_int32]
+        L.mg_override_fringe.restype = i32
         L.mg_clear_override.argtypes = []
         L.mg_clear_override.restype = None
         L.mg_lds_store_offset.argtypes = [ctypes.c_int32] * 5
@@ -192,6 +194,7 @@ def mg_sgemm(layout, trans_a, trans_b, m, n, k, alpha, A, lda, B, ldb, beta, C, 
 
 
 MG_STATIC_SCRATCH_BYTES = 16 << 20
+MG_FRINGE_AUTO, MG_FRINGE_OFF, MG_FRINGE_ON = 0, 1, 2
 
 
 def mg_sgemm_static(layout, trans_a, trans_b, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream=None, check=True) -> int:
@@ -469,6 +472,13 @@ def mg_override_batched_config(kernel_id: int, check=True) -> int:
     st = lib().mg_override_batched_config(kernel_id)
     if check and st != MG_OK:
         raise MgError(st, "mg_override_batched_config")
+    return st
+
+
+def mg_override_fringe(mode: int, check=True) -> int:
+    st = lib().mg_override_fringe(mode)
+    if check and st != MG_OK:
+        raise MgError(st, "mg_override_fringe")
     return st
 
 

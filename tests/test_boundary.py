@@ -296,3 +296,38 @@ def test_query_selected_and_override_roundtrip():
     assert sel["name"] == "htiny_32x32_mk" and sel["split_k"] == 1
     assert G.mg_gemm_workspace_bytes(G.MG_F16, C, N, N, 512, 196, 2304, 512, 2304, 512) == 0
     assert G.mg_gemm_workspace_bytes(G.MG_F32, 0, N, N, 256, 256, 256, 256, 256, 256) == 0
+
+
+def test_fringe_planning_and_override():
+    """the fringe (last rows / columns of C computed beside the tiles) is a property of the column-major view of an
+    FP32 call; the query reports it, the override switches it"""
+    def q(layout, m, n, k, **kw):
+        lda, ldb, ldc = (k, n, n) if layout == R else (k, k, m)          # A transposed (col) / plain (row), tight
+        return G.mg_query_selected(kw.get("dtype", G.MG_F32), layout, T if layout == C else N, N, m, n, k, lda, ldb, ldc, 1.0, 1.0)
+    try:
+        G.mg_clear_override()
+        sel = q(C, 4097, 129, 4095)
+        assert sel["fringe"] == 16 * 1 + 1 and sel["name"].endswith("_edge") and sel["family"] == G.MG_FAMILY_MFMA
+        assert q(R, 4096, 131, 4096)["fringe"] == 16 * 3             # row-major: the columns of C are the view's rows
+        assert q(C, 4096, 4096, 4096)["fringe"] == 0                 # whole tiles
+        assert q(C, 4101, 129, 4095)["fringe"] == 1                  # five beyond a multiple of 64: tiled
+        assert q(C, 4097, 129, 128)["fringe"] == 0                   # short sum: bound by memory, not worth it
+        assert q(C, 8193, 129, 4096)["fringe"] == 1                  # one tile row in 129: too small a saving
+        assert q(C, 4097, 129, 4095, dtype=G.MG_F16)["fringe"] == 0  # FP32 only
+        need_auto = G.mg_gemm_workspace_bytes(G.MG_F32, C, T, N, 4097, 129, 4095, 4095, 4095, 4097)
+        G.mg_override_fringe(G.MG_FRINGE_OFF)
+        assert q(C, 4097, 129, 4095)["fringe"] == 0
+        G.mg_override_fringe(G.MG_FRINGE_ON)
+        assert q(C, 4097, 129, 128)["fringe"] == 17 and q(C, 8193, 129, 4096)["fringe"] == 17
+        assert q(C, 4097, 40, 4096)["fringe"] == 0                   # fewer than 64 columns: nothing left to tile
+        # a forced kernel that cannot leave a fringe aside refuses the call instead of dropping it silently
+        G.mg_override_config(G.kernel_id("direct_f32_64x64x16"), 1)
+        cfg = G.mg_config()
+        st = G.lib().mg_query_selected(G.MG_F32, C, T, N, 4097, 129, 4095, 4095, 4095, 4097, 1.0, 1.0, 256, ctypes.byref(cfg))
+        assert st == -11
+        G.mg_override_fringe(G.MG_FRINGE_AUTO)
+        assert q(C, 4097, 129, 4095)["fringe"] == 0                  # automatic mode leaves a forced kernel's problem whole
+        assert G.mg_override_fringe(3, check=False) == -11 and G.mg_override_fringe(-1, check=False) == -11
+    finally:
+        G.mg_clear_override()
+    assert need_auto % (4097 * 129 * 4) == 0                         # partial sums cover all of C, fringe included

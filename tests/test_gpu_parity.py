@@ -363,6 +363,81 @@ def test_one_or_two_beyond_a_tile_multiple(G, oracle, dtype, layout, ta, tb):
         H.check_case(case, oracle)
 
 
+# ------------------------------------------------------------------ fringe rows / columns beside the tiles
+
+def _fringe_of(layout, m, n):
+    """16 * rows + columns that the column-major view of an m x n problem leaves to the fringe work-groups"""
+    def extra(d):
+        return d % 64 if d >= 64 and 1 <= d % 64 <= 4 else 0
+    vm, vn = (m, n) if layout == C else (n, m)
+    return (16 * extra(vm) + extra(vn)) if vm >= 64 and vn >= 64 else 0
+
+
+@pytest.mark.parametrize("layout,ta,tb", VARIANTS)
+def test_fringe_rows_and_columns(G, oracle, layout, ta, tb):
+    """FP32 problems that are 1 to 4 rows and / or columns more than a multiple of 64: those rows and columns are
+    computed by the work-groups appended to the tile grid (matrix-vector products, both of their forms), the tiles
+    cover the rest.  Every bounds-checked FP32 tile, unsplit and with a split sum (raw partial sums from both kinds
+    of work-group); fringe on one side, on both, of every width; outputs that end inside a work-group's share; sums
+    that end inside a 16-byte piece; bit-exact on integers, padding untouched, and one random case per shape."""
+    import torch
+    code = G.MG_F32
+    edge = [t for t in G.kernel_table() if t["dtype"] == code and t["family"] == G.MG_FAMILY_MFMA and t["name"].endswith("_edge")]
+    shapes = ((129, 193, 70), (65, 260, 301), (258, 67, 129), (131, 132, 64), (300, 65, 1003), (68, 64, 33), (1027, 129, 518),
+              (64, 577, 96))
+    ran = 0
+    ws = torch.empty(32 << 20, dtype=torch.uint8, device="cuda")
+    try:
+        G.mg_override_fringe(G.MG_FRINGE_ON)
+        for (m, n, k) in shapes:
+            cases = [W.skinny_case(m, n, k, case=31, integer=True, layout=layout, ta=ta, tb=tb, alpha=1.5, beta=0.5),
+                     W.skinny_case(m, n, k, case=32, integer=False, layout=layout, ta=ta, tb=tb, alpha=-0.75, beta=1.25)]
+            for t in edge:
+                for split in (1, 3):
+                    G.mg_override_config(t["kernel_id"], split)
+                    cfg = G.mg_config()
+                    q = G.lib().mg_query_selected(code, layout, ta, tb, m, n, k, cases[0].lda, cases[0].ldb, cases[0].ldc,
+                                                  1.5, 0.5, 256, ctypes.byref(cfg))
+                    if q != 0:
+                        continue                     # this tile does not take this operand order, or the split is too fine
+                    assert cfg.fringe == _fringe_of(layout, m, n) != 0
+                    for case in cases[: 1 if t["tile_m"] * t["tile_n"] > 128 * 64 else 2]:
+                        announce("fringe", t["name"], "split", split, case.name, layout, ta, tb, "exact" if case.exact else "random")
+                        H.check_case(case, oracle, workspace=ws)
+                        ran += 1
+        # beta == 0 with NaN in C: the fringe work-groups must not read C either
+        G.mg_clear_override()
+        G.mg_override_fringe(G.MG_FRINGE_ON)
+        case = W.skinny_case(130, 195, 80, case=33, integer=True, layout=layout, ta=ta, tb=tb, alpha=2.0, beta=0.0)
+        mask = ~W.padding_mask(layout, case.m, case.n, case.ldc, case.C.size)
+        case.C[mask] = np.nan
+        announce("fringe beta 0", case.name, layout, ta, tb)
+        H.check_case(case, oracle, workspace=ws)
+    finally:
+        G.mg_clear_override()
+    assert ran >= 2 * len(shapes)
+
+
+def test_fringe_automatic_equals_tiled(G, oracle):
+    """automatic mode on a shape of the irregular workload group's kind: the selected route leaves a fringe, and
+    its result agrees with the oracle and (on integers, bit for bit) with the all-tiles route"""
+    case = W.skinny_case(1025, 129, 1030, case=34, integer=True)
+    sel = G.mg_query_selected(G.MG_F32, case.layout, case.ta, case.tb, case.m, case.n, case.k, case.lda, case.ldb, case.ldc,
+                              case.alpha, case.beta)
+    assert sel["fringe"] == 17, sel
+    announce("fringe auto", case.name, sel["name"], sel["split_k"])
+    H.check_case(case, oracle)
+    _, with_fringe = H.run_gpu(case)
+    try:
+        G.mg_override_fringe(G.MG_FRINGE_OFF)
+        assert G.mg_query_selected(G.MG_F32, case.layout, case.ta, case.tb, case.m, case.n, case.k, case.lda, case.ldb,
+                                   case.ldc, case.alpha, case.beta)["fringe"] == 0
+        _, tiled = H.run_gpu(case)
+    finally:
+        G.mg_clear_override()
+    assert np.array_equal(H.bits(with_fringe), H.bits(tiled))
+
+
 # ------------------------------------------------------------------ every compiled configuration is result-neutral
 
 def _probe_cases(dtype):
