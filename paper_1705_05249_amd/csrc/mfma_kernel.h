@@ -232,10 +232,16 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
     // byte offset of logical chunk c of row r inside the operand's LDS tile
     __device__ static inline int lds_offset(int r, int c) { return ldsmap::kcontig_slot<32>(r, c); }
 
-    // Bounds-checked flavour, FP32: whole K-tiles of tiles that have all their rows are loaded like the fast
-    // flavour's (ragged problems of 2049^3 to 4104^3: 3-13 % faster; the FP16 kernels lost 10-17 % with the second
-    // code path in their loop and keep to the checked loads).
+    // Bounds-checked flavour, FP32: whole K-tiles are loaded like the fast flavour's, with buffer loads (ragged
+    // problems of 2049^3 to 4104^3: 3-13 % faster; the FP16 kernels lost 10-17 % with the second code path in their
+    // loop and keep to the checked loads).  Tiles that lack rows at the matrix's edge do so too: their buffer
+    // descriptor ends with the last row that exists (operand along k) resp. with the matrix (operand along its
+    // rows), and a buffer load returns zero for every dword past the descriptor's range without touching memory;
+    // lanes whose whole piece lies in missing rows are sent out of range on purpose (offset 2^31), a piece that
+    // straddles the last row is cut when it is stored.  Only the K-tile that holds the end of the sum takes the
+    // checked loads.
     static constexpr bool INTERIOR_FAST = EDGE && sizeof(T) == 4 && !CONV;
+    static constexpr uint32_t OUT_OF_RANGE = 0x80000000u;
 
     u32x4 regs[LOADS];
     // fast path: byte offset of each piece from the tile's first element, fixed for the whole kernel; a load is
@@ -291,9 +297,9 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
     }
 
     // Tile position for the loads that follow.  rows_left / k_left: rows / k values from (r0, l0) on that
-    // are inside the matrix (used by EDGE only); vec_ok: 16-byte loads are allowed; whole (EDGE only): the tile
-    // has all its rows and they start on dword boundaries, so that its whole K-tiles can be loaded like the fast
-    // flavour's (most tiles of a large ragged problem are such tiles).
+    // are inside the matrix (used by EDGE only); vec_ok: 16-byte loads are allowed; whole (EDGE only): the tile's
+    // rows start on dword boundaries and its lane offsets fit 31 bits, so that its whole K-tiles can be loaded with
+    // buffer loads like the fast flavour's.
     const T *base;
     int64_t ld;
     int rows_left, k_left;
@@ -317,9 +323,16 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
                                bool vec_ok_, bool whole_)
     {
         base = KCONTIG ? X + r0 * ld_ + l0 : X + r0 + l0 * ld_;
-        // raw buffer descriptor over the tile (no stride, no effective range limit: these loads are in bounds
-        // by construction; 0x00020000 = untyped 32-bit data format of this GPU family)
-        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(base), 0, 0x7fffffff, 0x00020000);
+        // raw buffer descriptor over the tile (no stride; 0x00020000 = untyped 32-bit data format of this GPU
+        // family).  No effective range limit for tiles that have all their rows: their loads are in bounds by
+        // construction.  A tile that lacks rows: the bytes from its first element to the end of its last row
+        // (operand along k: later rows are out of range) resp. to the matrix's last element (operand along its rows)
+        int range = 0x7fffffff;
+        if constexpr (INTERIOR_FAST) {
+            if (whole_ && rows_left_ < ROWS && k_left_ >= BK)
+                range = static_cast<int>((KCONTIG ? (rows_left_ - 1) * ld_ + k_left_ : (k_left_ - 1) * ld_ + rows_left_) * static_cast<int64_t>(sizeof(T)));
+        }
+        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(base), 0, range, 0x00020000);
         ld = ld_;
         rows_left = rows_left_;
         k_left = k_left_;
@@ -338,7 +351,8 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
             if constexpr (!EDGE) {
                 regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
             } else if (INTERIOR_FAST && whole && k_left >= BK) {
-                regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[0], (Q * (NT / CPR)) * ld_bytes, 0);
+                if (rows_left >= ROWS) regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[0], (Q * (NT / CPR)) * ld_bytes, 0);
+                else regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[0] + (Q * (NT / CPR)) * ld_bytes, 0, 0);
             } else {
                 const int kv = k_left - c * CH;
                 if (r >= rows_left || kv <= 0) regs[Q] = u32x4{0u, 0u, 0u, 0u};
@@ -354,7 +368,8 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
             if constexpr (!EDGE) {
                 regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
             } else if (INTERIOR_FAST && whole && k_left >= BK) {
-                regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[0], (Q * (NT / RCH)) * ld_bytes, 0);
+                if (rows_left >= ROWS) regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[0], (Q * (NT / RCH)) * ld_bytes, 0);
+                else regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (mc * CH < rows_left ? goff[0] : OUT_OF_RANGE) + (Q * (NT / RCH)) * ld_bytes, 0, 0);
             } else {
                 const T *p = base + mc * CH + l * ld;
                 const int rv = rows_left - mc * CH;
@@ -399,6 +414,13 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
         } else if constexpr (NATIVE) {
             const int idx = t + Q * NT;
             if (PARTIAL && idx >= CHUNKS) return;
+            if constexpr (INTERIOR_FAST) {
+                if (rows_left < ROWS) {                 // a piece that straddles the matrix's last row: cut what is beyond
+                    const int rv = rows_left - (idx % RCH) * CH;
+#pragma unroll
+                    for (int e = 1; e < CH; ++e) regs[Q][e] = e < rv ? regs[Q][e] : 0u;
+                }
+            }
             *reinterpret_cast<u32x4 *>(lds + ldsmap::native_slot(ROWS, idx / RCH, idx % RCH)) = regs[Q];
         } else {
             constexpr int i = Q % CH;
@@ -749,11 +771,11 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
     if constexpr (EDGE) {
         vec_a = (args.lda % CH == 0) && (reinterpret_cast<uintptr_t>(A) % 16 == 0);
         vec_b = (args.ldb % CH == 0) && (reinterpret_cast<uintptr_t>(B) % 16 == 0);
-        // whole tiles whose rows start on dword boundaries and whose lane offsets fit 31 bits
+        // rows that start on dword boundaries and lane offsets that fit 31 bits: whole K-tiles go through buffer loads
         constexpr int64_t SPAN_A = BM > BK ? BM : BK, SPAN_B = BN > BK ? BN : BK;
-        whole_a = rows_a == BM && (args.lda * sizeof(T)) % 4 == 0 && reinterpret_cast<uintptr_t>(A) % 4 == 0 &&
+        whole_a = (args.lda * sizeof(T)) % 4 == 0 && reinterpret_cast<uintptr_t>(A) % 4 == 0 &&
                   args.lda * SPAN_A * static_cast<int64_t>(sizeof(T)) < (int64_t(1) << 31);
-        whole_b = rows_b == BN && (args.ldb * sizeof(T)) % 4 == 0 && reinterpret_cast<uintptr_t>(B) % 4 == 0 &&
+        whole_b = (args.ldb * sizeof(T)) % 4 == 0 && reinterpret_cast<uintptr_t>(B) % 4 == 0 &&
                   args.ldb * SPAN_B * static_cast<int64_t>(sizeof(T)) < (int64_t(1) << 31);
     }
 

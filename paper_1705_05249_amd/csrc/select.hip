@@ -216,11 +216,12 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 // on every tile: within 6 % of this, the small tiles a little better where the last turn is thin)
                 const double rounds = static_cast<double>(ceil_div(blocks, kComputeUnits));
                 const double up = ceil(rounds);
-                // (the bounds-checked flavour runs at 0.5-0.8 of these rates; the same for every tile, but it
-                // decides between one long turn and several slices: (4097, 129, 4095) takes 132 us unsplit on 195
-                // tiles of 64 x 64 and 74 us in five slices)
-                // (a single turn of it has no other work-group's arithmetic to hide its checked loads behind: 0.45)
-                const double rate = (tiles[i].ceiling - (tiles[i].ceiling - tiles[i].per_group) / up) * (ragged ? (up <= 1.0 ? 0.45 : 0.6) : 1.0);
+                // (the bounds-checked flavour runs at 0.55-0.75 of these rates; the same for every tile, but it decides
+                // between one long turn and several slices.  A single turn has no other work-group's arithmetic to
+                // hide its loads behind: 0.58; two or more work-groups per compute unit: 0.70.  From 64 x 64 tiles,
+                // us measured / this estimate: (1000, 1001, 999) unsplit 26.4 / 26.8, two slices 28.4 / 28.9;
+                // (4097, 129, 4095) less its fringe unsplit 99 / 101, two slices 60 / 58, four 49 / 50, eight 56 / 52)
+                const double rate = (tiles[i].ceiling - (tiles[i].ceiling - tiles[i].per_group) / up) * (ragged ? (up <= 1.0 ? 0.58 : 0.70) : 1.0);
                 // (work-groups that are resident together pay the fixed cost of a turn once)
                 time = rounds * tile_flops / rate + (blocks <= full ? 1.0 : rounds) * f32_round_cost[i];
             } else if (blocks < full) {

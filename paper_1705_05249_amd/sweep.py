@@ -6,7 +6,9 @@ dozen kernels, so no random sampling is needed) with a few split-K factors, keep
 (one JSON line per (shape, kernel, split) in the output file, like the paper's database that
 stores every timing, not only the best) and prints the winner per shape.  For every shape the
 configuration the library selects by itself is timed as well, in the same run (kernel "auto"), so
-that the regret of the selection rules in csrc/select.hip can be read off the file.  Group 4 is the
+that the regret of the selection rules in csrc/select.hip can be read off the file.  FP32 shapes with a
+dimension 1 to 4 beyond a multiple of 64 are timed a second time with the fringe rows / columns taken off the
+tiles (kernel name + "+fringe").  Group 4 is the
 batched workload: every batched kernel on every instance size and batch count (the paper notes that
 its batched routine re-used the non-batched parameters sub-optimally, Section 4.6).  An interrupted
 sweep resumes: lines already in the output file are skipped.
@@ -299,6 +301,20 @@ def main():
                     log.flush()
                     if name not in best or secs < best[name][0]:
                         best[name] = (secs, t["name"], split)
+                    # the same configuration with the fringe rows / columns left to the extra work-groups
+                    if dtype != "f32" or (name, t["name"] + "+fringe", split) in done:
+                        continue
+                    G.mg_override_fringe(G.MG_FRINGE_ON)
+                    ok = G.lib().mg_query_selected(code, layout, ta, tb, m, n, k, lda, ldb, ldc, alpha, beta, 16, ctypes.byref(cfg)) == 0
+                    if ok and cfg.fringe != 0:
+                        secs = time_call(lambda: fn(layout, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, Cd, ldc, ws))
+                        rec = {"shape": name, "dtype": dtype, "m": m, "n": n, "k": k, "kernel": t["name"] + "+fringe",
+                               "split_k": split, "us": round(secs * 1e6, 2), "gflops": round(flops / secs / 1e9, 1)}
+                        log.write(json.dumps(rec) + "\n")
+                        log.flush()
+                        if secs < best[name][0]:
+                            best[name] = (secs, t["name"] + "+fringe", split)
+                    G.mg_override_fringe(G.MG_FRINGE_AUTO)
             G.mg_clear_override()
             sel = G.mg_query_selected(code, layout, ta, tb, m, n, k, lda, ldb, ldc, alpha, beta, 16)
             if (name, "auto", 1) not in done:
@@ -307,8 +323,8 @@ def main():
                 auto_ws = ws[:max(need, 256)] if need else None
                 secs = time_call(lambda: fn(layout, ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, Cd, ldc, auto_ws))
                 rec = {"shape": name, "dtype": dtype, "m": m, "n": n, "k": k, "kernel": "auto", "split_k": 1,
-                       "selected": sel["name"], "selected_split": sel["split_k"], "us": round(secs * 1e6, 2),
-                       "gflops": round(flops / secs / 1e9, 1)}
+                       "selected": sel["name"] + ("+fringe" if sel["fringe"] else ""), "selected_split": sel["split_k"],
+                       "us": round(secs * 1e6, 2), "gflops": round(flops / secs / 1e9, 1)}
                 log.write(json.dumps(rec) + "\n")
                 log.flush()
             if name in best:
