@@ -115,9 +115,9 @@ typedef struct mg_config {
 /* ---- GEMM (paper Section 1 / Section 3.1) --------------------------------------------
  * FP32 storage.  alpha, beta: host scalars.  A, B (read) and C (read if beta != 0, written):
  * device pointers, any 4-byte alignment.  workspace may always be NULL; with
- * mg_gemm_workspace_bytes() of workspace the call runs its preferred route (split-K partial sums,
- * or the padded copies of the indirect route described under mg_hgemm, which FP32 takes for large
- * problems that are not whole tiles). */
+ * mg_gemm_workspace_bytes() of workspace the call runs its preferred route (split-K partial sums;
+ * FP32 problems that are not whole tiles or not aligned run in place on bounds-checked kernels and
+ * need no copies, unlike FP16's indirect route described under mg_hgemm). */
 mg_status mg_sgemm(int layout, int trans_a, int trans_b, int64_t m, int64_t n, int64_t k,
                    float alpha, const float *A, int64_t lda, const float *B, int64_t ldb,
                    float beta, float *C, int64_t ldc,
@@ -249,7 +249,7 @@ mg_status mg_hgemm_strided_batched(int layout, int trans_a, int trans_b, int64_t
 
 /* mg_sgemm for callers that can neither allocate nor own a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  The scratch memory (split-K
- * partial sums, padded copies of the indirect route) is an array of MG_STATIC_SCRATCH_BYTES inside
+ * partial sums) is an array of MG_STATIC_SCRATCH_BYTES inside
  * the library, one per GPU, held until the process ends; the call allocates and frees nothing.
  * Arguments, results and errors as mg_sgemm, with these differences: a problem whose preferred
  * route needs more scratch than the array holds (mg_gemm_workspace_bytes() > MG_STATIC_SCRATCH_BYTES)

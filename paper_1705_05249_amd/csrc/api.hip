@@ -170,7 +170,7 @@ bool indirect_plan(const Problem &p, bool pointers_known, IndirectPlan *plan)
     if (g_override_kernel[p.dtype] >= 0) return false;                 // a forced kernel gets the problem as it is
     const double work = static_cast<double>(p.m) * static_cast<double>(p.n) * static_cast<double>(p.k);
     const size_t elem = p.elem();
-    int64_t tile, ktile;
+    int64_t tile = 0, ktile = 0;
     if (p.dtype == MG_F16) {
         // four extra launches and ~33 us of copies at 4096^2: measured a loss at 1000^3 (28 against 22 us), a gain
         // at 2049^3 (56 against 96 us)
@@ -182,12 +182,12 @@ bool indirect_plan(const Problem &p, bool pointers_known, IndirectPlan *plan)
         tile = p.m >= 2048 && p.n >= 2048 ? 256 : 128;
         ktile = 64;
     } else {
-        // FP32: the bounds-checked flavour runs at ~0.78 of the whole-tile rate and ragged sizes quantise badly
-        // on the tiles that are left; the copies cost ~70 us at 4096^2, so only large problems gain
-        if (p.m < 1536 || p.n < 1536 || p.k < 512 || work < 8.0e9) return false;
-        if (p.m % 64 == 0 && p.n % 64 == 0 && p.k % 32 == 0) return false;     // whole 64 x 64 tiles: a fast kernel is legal
-        tile = 128;
-        ktile = 32;
+        // FP32 does not take this route.  It did while the bounds-checked flavour ran at ~0.78 of the whole-tile rate
+        // (4000^3: 1150 us direct, 978 us through the copies); since that flavour runs its whole K-tiles on the fast
+        // flavour's schedule, partial tiles included, the direct route wins: 2049^3 195 / 138 us (A along m / k)
+        // against 200, 3000^3 430 / 417 against 473, 4000^3 927 / 896 against 977, 4097^3 1020 / 945 against 1139,
+        // 5001^3 1990 / 1940 against 2068 (the copies cost ~70 us at 4096^2).
+        return false;
     }
     plan->mp = ceil_div(p.m, tile) * tile;
     plan->np = ceil_div(p.n, tile) * tile;

@@ -17,8 +17,12 @@
 // Two forms by how the wide operand lies in memory (as for the stand-alone matrix-vector kernels):
 //   dot   wide(o, .) contiguous along l: a wavefront takes four outputs at once, lanes stride over l in 16-byte
 //         pieces (element alignment), cross-lane sums at the end;
-//   axpy  wide(., l) contiguous along o: a work-group owns 256 consecutive outputs, each lane four of them; its
-//         wavefronts take every WAVES-th l and meet in LDS.
+//   axpy  wide(., l) contiguous along o: a work-group owns 32 consecutive outputs; eight lanes side by side cover
+//         them (16 bytes each, one 128-byte line per term of the sum), the eight lane groups of a wavefront and
+//         the wavefronts of the work-group take different terms, eight loads in flight per lane; shuffles, then LDS,
+//         bring the shares together.  (Few outputs per work-group on purpose: the sum is long, and what bounds this
+//         form is how many loads the whole chip has in flight.  With 256 outputs per work-group and the wavefronts
+//         alone sharing the sum, the fringe of 2049^3 with A along m took 60 us longer than the tiles.)
 #pragma once
 
 #include <stdint.h>
@@ -26,7 +30,7 @@
 namespace mg {
 
 constexpr int FRINGE_MAX = 4;
-constexpr int FRINGE_AXPY_OUTPUTS = 256;       // outputs per work-group, axpy form
+constexpr int FRINGE_AXPY_OUTPUTS = 32;        // outputs per work-group, axpy form
 constexpr int FRINGE_DOT_ROWS = 4;             // outputs per wavefront, dot form
 
 struct FringeView {
@@ -124,9 +128,13 @@ template <int FR, int WAVES> __device__ inline void fringe_dot(const FringeView 
 template <int FR, int WAVES> __device__ inline void fringe_axpy(const FringeView &v, int block, int lane, int wave, char *lds)
 {
     constexpr int OB = FRINGE_AXPY_OUTPUTS;
-    constexpr int U = 4;                               // values of l in flight per wavefront
+    constexpr int OL = OB / 4;                         // lanes side by side along the outputs (16 bytes each)
+    constexpr int LQ = 64 / OL;                        // terms of the sum a wavefront's load instruction covers
+    constexpr int U = 8;                               // load instructions in flight per wavefront
+    constexpr int STEP = WAVES * LQ;
+    const int oc = lane % OL, lq = lane / OL;
     const int first = block * OB;
-    const int o = first + lane * 4;
+    const int o = first + oc * 4;
     float acc[4][FR];
 #pragma unroll
     for (int e = 0; e < 4; ++e)
@@ -134,15 +142,15 @@ template <int FR, int WAVES> __device__ inline void fringe_axpy(const FringeView
         for (int f = 0; f < FR; ++f) acc[e][f] = 0.f;
     if (o + 4 <= v.outputs) {
         const float *__restrict__ col = v.wide + o;
-        int l = v.kb + wave;
-        for (; l + WAVES * (U - 1) < v.ke; l += WAVES * U) {
+        int l = v.kb + wave * LQ + lq;
+        for (; l + STEP * (U - 1) < v.ke; l += STEP * U) {
             FringeQuad a[U];
             float x[U][FR];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                a[u] = *reinterpret_cast<const FringeQuad *>(col + (l + WAVES * u) * v.w_sl);
+                a[u] = *reinterpret_cast<const FringeQuad *>(col + (l + STEP * u) * v.w_sl);
 #pragma unroll
-                for (int f = 0; f < FR; ++f) x[u][f] = v.narrow[f * v.n_sf + (l + WAVES * u) * v.n_sl];
+                for (int f = 0; f < FR; ++f) x[u][f] = v.narrow[f * v.n_sf + (l + STEP * u) * v.n_sl];
             }
 #pragma unroll
             for (int u = 0; u < U; ++u)
@@ -151,7 +159,7 @@ template <int FR, int WAVES> __device__ inline void fringe_axpy(const FringeView
 #pragma unroll
                     for (int f = 0; f < FR; ++f) acc[e][f] = fmaf(a[u].v[e], x[u][f], acc[e][f]);
         }
-        for (; l < v.ke; l += WAVES) {
+        for (; l < v.ke; l += STEP) {
             const FringeQuad a = *reinterpret_cast<const FringeQuad *>(col + l * v.w_sl);
 #pragma unroll
             for (int f = 0; f < FR; ++f) {
@@ -162,7 +170,7 @@ template <int FR, int WAVES> __device__ inline void fringe_axpy(const FringeView
         }
     } else if (o < v.outputs) {
         // the ragged last run of outputs: element by element
-        for (int l = v.kb + wave; l < v.ke; l += WAVES)
+        for (int l = v.kb + wave * LQ + lq; l < v.ke; l += STEP)
 #pragma unroll
             for (int f = 0; f < FR; ++f) {
                 const float x = v.narrow[f * v.n_sf + l * v.n_sl];
@@ -171,16 +179,25 @@ template <int FR, int WAVES> __device__ inline void fringe_axpy(const FringeView
                     if (o + e < v.outputs) acc[e][f] = fmaf(v.wide[o + e + l * v.w_sl], x, acc[e][f]);
             }
     }
+    // the LQ lane groups of a wavefront hold different terms of the same outputs
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int f = 0; f < FR; ++f)
+#pragma unroll
+            for (int off = OL; off < 64; off <<= 1) acc[e][f] += __shfl_xor(acc[e][f], off, 64);
     // the wavefronts' shares of each output meet in LDS, one fringe vector at a time
     float *part = reinterpret_cast<float *>(lds);      // [WAVES][OB]
 #pragma unroll
     for (int f = 0; f < FR; ++f) {
         __syncthreads();
+        if (lq == 0) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) part[wave * OB + lane * 4 + e] = acc[e][f];
+            for (int e = 0; e < 4; ++e) part[wave * OB + oc * 4 + e] = acc[e][f];
+        }
         __syncthreads();
-        for (int i = wave * 64 + lane; i < OB; i += WAVES * 64) {
-            if (first + i >= v.outputs) break;
+        const int i = wave * 64 + lane;
+        if (i < OB && first + i < v.outputs) {
             float s = 0.f;
 #pragma unroll
             for (int w = 0; w < WAVES; ++w) s += part[w * OB + i];

@@ -238,8 +238,9 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
     // descriptor ends with the last row that exists (operand along k) resp. with the matrix (operand along its
     // rows), and a buffer load returns zero for every dword past the descriptor's range without touching memory;
     // lanes whose whole piece lies in missing rows are sent out of range on purpose (offset 2^31), a piece that
-    // straddles the last row is cut when it is stored.  Only the K-tile that holds the end of the sum takes the
-    // checked loads.
+    // straddles the last row is cut when it is stored.  The kernel runs its K loop in two parts: K-tiles whose
+    // reloads are all whole K-tiles take the fast flavour's schedule with these loads (load_one<Q, true>), the last
+    // few, which hold the end of the sum, the checked loads.
     static constexpr bool INTERIOR_FAST = EDGE && sizeof(T) == 4 && !CONV;
     static constexpr uint32_t OUT_OF_RANGE = 0x80000000u;
 
@@ -249,7 +250,8 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
     // inside the K loop (the bounds-checked flavour keeps the offset of its first piece only: the others differ
     // from it by a multiple of the leading dimension that is the same for every lane, which goes into the
     // scalar offset)
-    uint32_t goff[EDGE ? 1 : LOADS];
+    uint32_t goff[(EDGE && !INTERIOR_FAST) ? 1 : LOADS];
+    bool keep[CH];             // INTERIOR_FAST, operand along its rows: element e of this lane's pieces is a row that exists
     uint32_t ld_bytes;
     __amdgpu_buffer_rsrc_t rsrc;
 
@@ -265,10 +267,21 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
         return Unit{idx % RCH, rest / SPLIT, rest % SPLIT, !PARTIAL || idx < UNITS};
     }
 
-    __device__ inline void prepare(int64_t ld_)
+    // rows: rows of the tile that exist (the bounds-checked FP32 flavour marks the lanes whose pieces lie beyond them)
+    __device__ inline void prepare(int64_t ld_, int rows = ROWS)
     {
         ld_bytes = static_cast<uint32_t>(ld_ * sizeof(T));
-        if constexpr (EDGE) {
+        if constexpr (INTERIOR_FAST) {
+            const int t = threadIdx.x;
+            static_for<LOADS>([&](auto Qc) {
+                constexpr int Q = decltype(Qc)::value;
+                const int idx = t + Q * NT;
+                if constexpr (KCONTIG) goff[Q] = static_cast<uint32_t>(((idx / CPR) * ld_ + (idx % CPR) * CH) * sizeof(T));
+                else goff[Q] = (idx % RCH) * CH < rows ? static_cast<uint32_t>(((idx % RCH) * CH + (idx / RCH) * ld_) * sizeof(T)) : OUT_OF_RANGE;
+            });
+#pragma unroll
+            for (int e = 0; e < CH; ++e) keep[e] = KCONTIG || (t % RCH) * CH + e < rows;
+        } else if constexpr (EDGE) {
             const int t = threadIdx.x;
             if constexpr (KCONTIG) {
                 goff[0] = static_cast<uint32_t>(((t / CPR) * ld_ + (t % CPR) * CH) * sizeof(T));
@@ -329,7 +342,7 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
         // (operand along k: later rows are out of range) resp. to the matrix's last element (operand along its rows)
         int range = 0x7fffffff;
         if constexpr (INTERIOR_FAST) {
-            if (whole_ && rows_left_ < ROWS && k_left_ >= BK)
+            if (whole_ && rows_left_ < ROWS && k_left_ >= BK)      // (k_left_ < BK: the checked loads, no descriptor)
                 range = static_cast<int>((KCONTIG ? (rows_left_ - 1) * ld_ + k_left_ : (k_left_ - 1) * ld_ + rows_left_) * static_cast<int64_t>(sizeof(T)));
         }
         rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(base), 0, range, 0x00020000);
@@ -340,10 +353,16 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
         whole = whole_;
     }
 
-    template <int Q> __device__ inline void load_one()
+    // FAST (INTERIOR_FAST only): the caller knows that the tile aimed at is a whole K-tile of an operand with
+    // `whole` set; no checks in the instruction stream
+    template <int Q, bool FAST = false> __device__ inline void load_one()
     {
+        static_assert(!FAST || INTERIOR_FAST, "unchecked loads in the bounds-checked flavour: FP32 only");
         const int t = threadIdx.x;
-        if constexpr (KCONTIG) {
+        if constexpr (FAST) {
+            if (PARTIAL && t + Q * NT >= CHUNKS) return;
+            regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
+        } else if constexpr (KCONTIG) {
             const int idx = t + Q * NT;
             const int c = idx % CPR, r = idx / CPR;
             if (PARTIAL && idx >= CHUNKS) return;
@@ -351,8 +370,7 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
             if constexpr (!EDGE) {
                 regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
             } else if (INTERIOR_FAST && whole && k_left >= BK) {
-                if (rows_left >= ROWS) regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[0], (Q * (NT / CPR)) * ld_bytes, 0);
-                else regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[0] + (Q * (NT / CPR)) * ld_bytes, 0, 0);
+                if constexpr (INTERIOR_FAST) regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
             } else {
                 const int kv = k_left - c * CH;
                 if (r >= rows_left || kv <= 0) regs[Q] = u32x4{0u, 0u, 0u, 0u};
@@ -368,8 +386,7 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
             if constexpr (!EDGE) {
                 regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
             } else if (INTERIOR_FAST && whole && k_left >= BK) {
-                if (rows_left >= ROWS) regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[0], (Q * (NT / RCH)) * ld_bytes, 0);
-                else regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (mc * CH < rows_left ? goff[0] : OUT_OF_RANGE) + (Q * (NT / RCH)) * ld_bytes, 0, 0);
+                if constexpr (INTERIOR_FAST) regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
             } else {
                 const T *p = base + mc * CH + l * ld;
                 const int rv = rows_left - mc * CH;
@@ -384,10 +401,6 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
             const int l = u.kc * CH + u.s * KU + Q % KU;
             if constexpr (!EDGE) {
                 regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
-            } else if (INTERIOR_FAST && whole && k_left >= BK) {
-                // unit Q / KU starts (NT / RCH) * CH values of k behind the one before it, line Q % KU of a unit
-                // that many behind the first
-                regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[0], ((Q / KU) * (NT / RCH) * CH + Q % KU) * ld_bytes, 0);
             } else if constexpr (CONV) {
                 const int rv = l < k_left ? rows_left - u.mc * CH : 0;
                 conv_fetch<T>(raw[Q], base, geom, conv_i + u.mc * CH, l < k_left ? conv_l + l : 0, rv);
@@ -414,12 +427,9 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
         } else if constexpr (NATIVE) {
             const int idx = t + Q * NT;
             if (PARTIAL && idx >= CHUNKS) return;
-            if constexpr (INTERIOR_FAST) {
-                if (rows_left < ROWS) {                 // a piece that straddles the matrix's last row: cut what is beyond
-                    const int rv = rows_left - (idx % RCH) * CH;
+            if constexpr (INTERIOR_FAST) {              // a piece that straddles the matrix's last row: cut what is beyond
 #pragma unroll
-                    for (int e = 1; e < CH; ++e) regs[Q][e] = e < rv ? regs[Q][e] : 0u;
-                }
+                for (int e = 1; e < CH; ++e) regs[Q][e] = keep[e] ? regs[Q][e] : 0u;
             }
             *reinterpret_cast<u32x4 *>(lds + ldsmap::native_slot(ROWS, idx / RCH, idx % RCH)) = regs[Q];
         } else {
@@ -825,8 +835,8 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
         lb.aim(B, args.ldb, n0, l0, rows_b, ke - l0, vec_b, whole_b);
     };
     if constexpr (CONV) la.geom = args.conv;
-    la.prepare(args.lda);
-    lb.prepare(args.ldb);
+    la.prepare(args.lda, rows_a);
+    lb.prepare(args.ldb, rows_b);
 
     u32x4 fa[2][FM], fb[2][FN];
     // fragment F of K-step s in LDS stage `par`: F < FM -> A fragment F, else B fragment F - FM
@@ -873,8 +883,9 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
     constexpr int EVENT_SLOTS = KSTEPS * SLOTS - TAIL;
     constexpr int READ_SLOTS = SLOTS >= 4 ? SLOTS * 3 / 4 : SLOTS;           // slots of a step that issue LDS reads
     constexpr int TAIL_READ_SLOTS = TAIL >= 4 ? TAIL * 3 / 4 : TAIL;
-    auto run_event = [&](auto E, auto PAR) {              // PAR: the LDS stage the stores go to
+    auto run_event = [&](auto E, auto PAR, auto FASTLOADS) {              // PAR: the LDS stage the stores go to
         constexpr int e = decltype(E)::value, par = decltype(PAR)::value;
+        constexpr bool fast = decltype(FASTLOADS)::value;
         constexpr bool is_a = e < EV_A;
         constexpr int le = is_a ? e : e - EV_A;
         constexpr bool kcontig = is_a ? LoadA::PLAIN : LoadB::PLAIN;       // pieces stored as loaded
@@ -886,18 +897,21 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
         constexpr bool is_load = w >= GS;
         constexpr int piece = is_load ? grp * GL + (w - GS) : grp * GS + (kcontig ? GS - 1 - w : w);
         if constexpr (is_a) {
-            if constexpr (is_load) la.template load_one<piece>();
+            if constexpr (is_load) la.template load_one<piece, fast>();
             else la.template store_one<piece>(lds + par * A_BYTES);
         } else {
-            if constexpr (is_load) lb.template load_one<piece>();
+            if constexpr (is_load) lb.template load_one<piece, fast>();
             else lb.template store_one<piece>(lds + 2 * A_BYTES + par * B_BYTES);
         }
     };
 
     // One K-tile.  CUR: the LDS stage the MFMAs read (compile time, the K loop being unrolled by two, so that
     // every LDS address is a loop-invariant register plus an immediate); the other stage receives tile t+1.
-    auto tile_body = [&](auto CUR, int t) {
+    // FASTLOADS (bounds-checked FP32 flavour): the K-tile reloaded here, t + 2, is a whole one and both operands can
+    // be loaded with buffer loads: the fast flavour's instruction stream, pinned the same way.
+    auto tile_body = [&](auto CUR, auto FASTLOADS, int t) {
         using Cur = decltype(CUR);
+        constexpr bool pinned = !EDGE || decltype(FASTLOADS)::value;
         using Nxt = std::integral_constant<int, 1 - Cur::value>;
         aim_tile(t + 2);
         static_for<KSTEPS>([&](auto S) {
@@ -930,19 +944,27 @@ __global__ __launch_bounds__(WM *WN * 64) void mfma_gemm_kernel(const MfmaArgs a
                 // memory (tile t+2) -> the same registers
                 if constexpr (g < EVENT_SLOTS) {
                     static_for<share_begin(g + 1, EVENTS, EVENT_SLOTS) - share_begin(g, EVENTS, EVENT_SLOTS)>([&](auto R) {
-                        run_event(std::integral_constant<int, share_begin(g, EVENTS, EVENT_SLOTS) + decltype(R)::value>{}, Nxt{});
+                        run_event(std::integral_constant<int, share_begin(g, EVENTS, EVENT_SLOTS) + decltype(R)::value>{}, Nxt{}, FASTLOADS);
                     });
                 }
-                if constexpr (!EDGE) __builtin_amdgcn_sched_barrier(0);
+                if constexpr (pinned) __builtin_amdgcn_sched_barrier(0);
             });
         });
     };
     int t = 0;
-    for (; t + 1 < ktiles; t += 2) {
-        tile_body(Stage0{}, t);
-        tile_body(Stage1{}, t + 1);
+    if constexpr (LoadA::INTERIOR_FAST) {
+        // K-tiles 0 .. fast_tiles - 1 are whole; the body of tile t reloads tile t + 2
+        const int fast_tiles = (whole_a && whole_b) ? (ke - kb) / BK : 0;
+        for (; t + 3 < fast_tiles; t += 2) {
+            tile_body(Stage0{}, std::true_type{}, t);
+            tile_body(Stage1{}, std::true_type{}, t + 1);
+        }
     }
-    if (t < ktiles) tile_body(Stage0{}, t);
+    for (; t + 1 < ktiles; t += 2) {
+        tile_body(Stage0{}, std::false_type{}, t);
+        tile_body(Stage1{}, std::false_type{}, t + 1);
+    }
+    if (t < ktiles) tile_body(Stage0{}, std::false_type{}, t);
 
     __syncthreads();                                   // every wavefront is done reading the operand stages
     tile_epilogue<T, RB, FM, FN, WTM, WTN, EDGE>(acc, args, lds, m0, n0, wm, wn, wave, lane);

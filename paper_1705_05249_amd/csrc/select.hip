@@ -216,14 +216,16 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 // on every tile: within 6 % of this, the small tiles a little better where the last turn is thin)
                 const double rounds = static_cast<double>(ceil_div(blocks, kComputeUnits));
                 const double up = ceil(rounds);
-                // (the bounds-checked flavour runs at 0.55-0.75 of these rates; the same for every tile, but it decides
-                // between one long turn and several slices.  A single turn has no other work-group's arithmetic to
-                // hide its loads behind: 0.58; two or more work-groups per compute unit: 0.70.  From 64 x 64 tiles,
-                // us measured / this estimate: (1000, 1001, 999) unsplit 26.4 / 26.8, two slices 28.4 / 28.9;
-                // (4097, 129, 4095) less its fringe unsplit 99 / 101, two slices 60 / 58, four 49 / 50, eight 56 / 52)
-                const double rate = (tiles[i].ceiling - (tiles[i].ceiling - tiles[i].per_group) / up) * (ragged ? (up <= 1.0 ? 0.58 : 0.70) : 1.0);
+                // (the bounds-checked flavour runs its whole K-tiles on the fast flavour's schedule and the last few on
+                // checked loads: 0.75 of these rates for a single turn, which has no other work-group's arithmetic to hide
+                // the checked part behind, 0.85 for two or more work-groups per compute unit; and every further work-group
+                // of a compute unit adds half a turn's fixed cost.  From 64 x 64 tiles, us measured / this estimate:
+                // (1000, 1001, 999) unsplit 21.5 / 21.1, two slices 27.0 / 26.7; (4097, 129, 4095) less its fringe unsplit
+                // 71 / 81, two slices 46.7 / 47.5, four 46.2 / 44.7, eight 54.9 / 48.4; (1025, 1030, 1000) less its fringe
+                // row unsplit 36.3 / 36.6, two slices 35.2 / 37.1, four 38.1 / 36.8)
+                const double rate = (tiles[i].ceiling - (tiles[i].ceiling - tiles[i].per_group) / up) * (ragged ? (up <= 1.0 ? 0.75 : 0.85) : 1.0);
                 // (work-groups that are resident together pay the fixed cost of a turn once)
-                time = rounds * tile_flops / rate + (blocks <= full ? 1.0 : rounds) * f32_round_cost[i];
+                time = rounds * tile_flops / rate + (blocks <= full ? (ragged ? 1.0 + 0.5 * (rounds - 1.0) : 1.0) : rounds) * f32_round_cost[i];
             } else if (blocks < full) {
                 // the chip is not full: ceil(blocks / 256) work-groups share a compute unit
                 const int64_t per_unit = ceil_div(blocks, kComputeUnits);
@@ -269,9 +271,8 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 }
             }
             // split-K: the partial sums are written and read back (8 bytes per slice and output at ~4 TB/s) by
-            // a second launch (~3 us)
-            // (measured on 1000 x 1001 x 999 in FP32: 2 slices 32.1 us, 4 slices 31.0 us, none 36.6 us)
-            if (slices > 1) time += 1.0e6 * (2.5 + (4.0 * slices + 8.0) * static_cast<double>(p.m) * static_cast<double>(p.n) / 4.0e6);
+            // a second launch (2.5 us; 4 us behind the bounds-checked FP32 flavour, fitted with the rates above)
+            if (slices > 1) time += 1.0e6 * ((f32 && ragged ? 4.0 : 2.5) + (4.0 * slices + 8.0) * static_cast<double>(p.m) * static_cast<double>(p.n) / 4.0e6);
             return time;
         };
         for (int attempt = 0; attempt < count; ++attempt) {

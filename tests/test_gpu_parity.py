@@ -663,21 +663,29 @@ def test_random_shapes_on_sampled_entries(G, oracle, dtype):
 
 
 @pytest.mark.parametrize("layout,ta,tb", [(C, N, N), (R, T, N), (C, N, T)])
-def test_indirect_route_for_large_ragged_single_problems(G, oracle, layout, ta, tb):
-    """FP32 takes the padded-copy route from about 2000^3 on when no whole-tile kernel is legal: sampled entries
-    against the oracle, padding of C untouched, and the same result (up to summation order) without workspace"""
+def test_large_ragged_single_problems_run_without_copies(G, oracle, layout, ta, tb):
+    """a large ragged FP32 problem (a fringe row, partial last tiles, a ragged sum) needs no workspace: the
+    bounds-checked tiles take it as it is (FP32 left the padded-copy route when they became faster than the copies);
+    sampled entries against the oracle, padding of C untouched, the same bits with and without a workspace, and the
+    same result up to summation order with the fringe switched off"""
     m, n, k = 2049, 2050, 2001
     g = np.random.default_rng(77)
     case = W.make_case(f"s_{m}x{n}x{k}", "f32", layout, ta, tb, W.uniform(g, (m, k)), W.uniform(g, (k, n)),
                        W.uniform(g, (m, n)), 1.0, 0.5, W.tight_ld(layout, ta, m, k) + 1, W.tight_ld(layout, tb, k, n) + 1,
                        W.tight_ld(layout, N, m, n) + 1)
-    need = G.mg_gemm_workspace_bytes(G.MG_F32, layout, ta, tb, m, n, k, case.lda, case.ldb, case.ldc)
-    assert need >= 4 * (m * k + k * n + m * n)
+    assert G.mg_gemm_workspace_bytes(G.MG_F32, layout, ta, tb, m, n, k, case.lda, case.ldb, case.ldc) == 0
     H.check_case(case, oracle, sampled=True, seed=5)
-    _, padded = H.run_gpu(case)
+    import torch
+    _, with_ws = H.run_gpu(case, workspace=torch.empty(64 << 20, dtype=torch.uint8, device="cuda"))
     st, direct = H.run_gpu(case, workspace=None)
     assert st == 0
     H.assert_padding_untouched(case, direct)
+    assert np.array_equal(H.bits(with_ws), H.bits(direct))
+    try:
+        G.mg_override_fringe(G.MG_FRINGE_OFF)
+        _, tiled = H.run_gpu(case, workspace=None)
+    finally:
+        G.mg_clear_override()
     live = ~W.padding_mask(layout, m, n, case.ldc, case.C.size)
-    a, b = direct[live].astype(np.float64), padded[live].astype(np.float64)
+    a, b = direct[live].astype(np.float64), tiled[live].astype(np.float64)
     assert np.max(np.abs(a - b)) <= 1e-4 * np.max(np.abs(b))

@@ -54,7 +54,7 @@ def test_static_scratch_entry_point_matches_the_workspace_one(oracle):
 def test_static_scratch_entry_point_refuses_what_does_not_fit():
     G.lib()
     G.mg_clear_override()
-    m = n = k = 3001          # ragged and large: the preferred route copies the operands into padded scratch buffers
+    m, n, k = 1536, 1024, 32768          # a long sum in eight slices: 48 MiB of partial sums
     need = G.mg_gemm_workspace_bytes(G.MG_F32, W.COL_MAJOR, W.NO_TRANS, W.NO_TRANS, m, n, k, m, k, m)
     assert need > G.MG_STATIC_SCRATCH_BYTES
     # refused on the host before any pointer is looked at
