@@ -106,7 +106,8 @@ def main():
         """one GEMM workload: events around back-to-back calls, or (small) graph replays; cold: also the time per call
         when the operands come from HBM (a cycle through copies that together exceed the last-level cache four times)"""
         A, B, C, sel, call_on = gemm_setup(case)
-        entry = {"workload": label, "kernel": sel["name"] + (f" split {sel['split_k']}" if sel["split_k"] > 1 else "")}
+        entry = {"workload": label, "kernel": sel["name"] + (f" split {sel['split_k']}" if sel["split_k"] > 1 else "")
+                 + (f" + fringe of {sel['fringe'] // 16} row(s), {sel['fringe'] % 16} column(s)" if sel["fringe"] else "")}
         if small:
             dev_graph, dev_eager = M.graph_timed(call_on(A, B, C), C, steps, warmup)
             entry["ms_graph_replays"] = round(dev_graph * 1e3, 5)
