@@ -342,8 +342,12 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
         // (operand along k: later rows are out of range) resp. to the matrix's last element (operand along its rows)
         int range = 0x7fffffff;
         if constexpr (INTERIOR_FAST) {
-            if (whole_ && rows_left_ < ROWS && k_left_ >= BK)      // (k_left_ < BK: the checked loads, no descriptor)
-                range = static_cast<int>((KCONTIG ? (rows_left_ - 1) * ld_ + k_left_ : (k_left_ - 1) * ld_ + rows_left_) * static_cast<int64_t>(sizeof(T)));
+            if (whole_ && rows_left_ < ROWS && k_left_ >= BK) {    // (k_left_ < BK: the checked loads, no descriptor)
+                // (far from the end of a long sum the matrix ends beyond 2^31 bytes: no limit needed, the tile's
+                // own offsets stay below that)
+                const int64_t bytes = (KCONTIG ? (rows_left_ - 1) * ld_ + k_left_ : (k_left_ - 1) * ld_ + rows_left_) * static_cast<int64_t>(sizeof(T));
+                range = bytes < 0x7fffffff ? static_cast<int>(bytes) : 0x7fffffff;
+            }
         }
         rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(base), 0, range, 0x00020000);
         ld = ld_;

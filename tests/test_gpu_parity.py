@@ -438,6 +438,20 @@ def test_fringe_automatic_equals_tiled(G, oracle):
     assert np.array_equal(H.bits(with_fringe), H.bits(tiled))
 
 
+@pytest.mark.parametrize("ta,tb", [(N, N), (T, T)])
+def test_partial_tiles_whose_operand_ends_beyond_two_gib(G, oracle, ta, tb):
+    """a partial tile of the bounds-checked FP32 flavour limits its buffer descriptor to the end of the matrix; with a
+    leading dimension of 66000 and a sum of 8200 terms the operand along its rows ends 2.16 GB behind the tile's first
+    element, more than a descriptor's 2^31 - 1 bytes: the limit must saturate, not wrap (rows beyond the matrix and
+    the padding hold NaN)"""
+    m, n, k, ld = 70, 70, 8200, 66000
+    g = W.rng_for(9, 4242)
+    case = W.make_case(f"wide_ld_{m}x{n}x{k}", "f32", C, ta, tb, W.small_ints(g, (m, k), 2), W.small_ints(g, (k, n), 2),
+                       W.small_ints(g, (m, n)), 1.0, 1.0, lda=ld if ta == N else None, ldb=ld if tb == T else None, exact=True)
+    announce(case.name, ta, tb, "bytes of the wide operand:", (case.A if ta == N else case.B).nbytes)
+    H.check_case(case, oracle)
+
+
 # ------------------------------------------------------------------ every compiled configuration is result-neutral
 
 def _probe_cases(dtype):
