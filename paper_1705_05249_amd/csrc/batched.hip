@@ -213,22 +213,25 @@ __global__ __launch_bounds__(256) void batched_wave_kernel(const BatchedArgs a)
 // 64 x 64 x 64 FP32 instances with A contiguous along m and B along k (column-major N/N, the workload's case), one
 // wavefront per instance.  What bounds such an instance is how the memory system is asked: in the kernel above a
 // wavefront's load of an operand along m is four runs of 64 bytes, C four consecutive rows of sixteen columns (sixteen
-// runs of 64 bytes), and runs of 64 bytes reach 4.2 TB/s where whole lines reach 6.5.  Here the MFMA's lane index is
-// mapped to ROWS of C: lane (c, g) holds rows 4c .. 4c+3, so
-//   * A is a 16-byte load per lane of those four rows of column l = 16 t + 4 g + s: sixteen lanes read one whole
-//     column of the instance (256 bytes), a wavefront instruction four columns;
-//   * the four loaded rows go to four MFMAs (e = 0..3), each over the sixteen rows 4c + e: a block of C is a
-//     strided set of rows, and the four blocks of a lane are again four consecutive rows of one column, so
-//   * C is read and written as 16 bytes per lane, sixteen lanes one whole column (256 bytes), four columns
-//     (4 g + r of a 16-column block) per instruction;
-//   * B (one 16-byte load of four consecutive l per lane, as above) is the MFMA's other operand, lane index = column.
-// The sum over l pairs A's value at l = 16 t + 4 g + s with B's at the same l: both operands use that order.
-// All operand loads are issued before the first MFMA, the old C after half of them (when the registers of the first
-// two K blocks are free), as in the kernel above.
-// (C is written with streaming stores: 134 -> 132 us for 10000 instances; streaming loads of A and B change nothing,
-// a streaming load of the old C costs 4 %.)
+// runs of 64 bytes), and runs of 64 bytes reach 4.2 TB/s where runs of 1 KB reach 6.5.  Here every instruction of a
+// wavefront asks for four whole columns (256 bytes each; with the usual leading dimension of 64 they are adjacent:
+// 1 KB in one piece), for all three matrices:
+//   * the MFMA's lane index is mapped to ROWS of C: lane (c, g) holds rows 4c .. 4c+3.  A is one 16-byte load per lane
+//     of those rows of column l = 4t + g; the four loaded rows go to four MFMAs (e = 0..3), each over the sixteen rows
+//     4c + e: a block of C is a strided set of rows, and the four blocks of a lane are again four consecutive rows of one
+//     column, so C is read and written 16 bytes per lane, sixteen lanes a whole column;
+//   * which column of a 16-column block an MFMA lane of the other operand stands for is free: lane 4g + r stands for
+//     column 4r + g, so that the four lane groups of a C access are four ADJACENT columns;
+//   * B is loaded the same way (16 bytes of four consecutive l per lane, sixteen lanes a whole column, four adjacent
+//     columns per instruction), which is not the order an MFMA operand wants (lane = column, lane group = l); it is
+//     turned through a 16 KB LDS region of the wavefront's own: 16-byte writes, the sixteen chunks of a column
+//     XORed with the column number, and one 4-byte read per MFMA group (lane: its column, l = 4t + g), both free of
+//     bank conflicts.  Only this wavefront touches the region and a wavefront's LDS operations execute in order.
+// The sum over l pairs A's value at l = 4t + g with B's at the same l.  All operand loads are issued at once, the old
+// C after a quarter of the MFMAs (into the registers B was staged in); C is written with streaming stores.
 __global__ __launch_bounds__(256) void batched_rows64_kernel(const BatchedArgs a)
 {
+    __shared__ __attribute__((aligned(16))) char turn[4][64 * 256];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
     const int64_t inst = static_cast<int64_t>(blockIdx.x) * 4 + wave;
     if (inst >= a.batch) return;
@@ -239,47 +242,60 @@ __global__ __launch_bounds__(256) void batched_rows64_kernel(const BatchedArgs a
     const float *__restrict__ B = static_cast<const float *>(a.B) + (a.strided ? inst * a.stride_b : a.b_off[inst]);
     float *__restrict__ C = static_cast<float *>(a.C) + (a.strided ? inst * a.stride_c : a.c_off[inst]);
     const int lda = static_cast<int>(a.lda), ldb = static_cast<int>(a.ldb), ldc = static_cast<int>(a.ldc);
+    char *region = turn[wave];
 
     typedef floatx4 UnalignedQuad __attribute__((aligned(4)));
     auto quad = [](const float *p) {
         const Quad<float> u = *reinterpret_cast<const Quad<float> *>(p);
         return floatx4{u.x, u.y, u.z, u.w};
     };
-    floatx4 acc[4][4];                       // [e][bj]: rows 4c + e, columns 16 bj + 4g + r (r = register)
+    floatx4 acc[4][4];                       // [e][bj]: rows 4c + e, columns 16 bj + 4r + g (r = register)
 #pragma unroll
     for (int e = 0; e < 4; ++e)
 #pragma unroll
         for (int bj = 0; bj < 4; ++bj) acc[e][bj] = floatx4{0.f, 0.f, 0.f, 0.f};
-    floatx4 aq[4][4], bq[4][4], cold[4][4];  // aq[t][s]: rows 4c.., l = 16t + 4g + s; bq[bj][t]: l = 16t + 4g .., column 16bj + c
-    if (alpha != 0.f) {                      // alpha == 0: A and B are not read at all
+    floatx4 aq[16], stage[16];               // aq[t]: rows 4c.., l = 4t + g; stage[t]: B, l = 4c.., column 4t + g; later the old C
+    const bool reads = alpha != 0.f;         // alpha == 0: A and B are not read at all
+    if (reads) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int t = 0; t < 16; ++t) stage[t] = quad(B + 4 * c + (4 * t + g) * ldb);
 #pragma unroll
-            for (int s = 0; s < 4; ++s) aq[t][s] = quad(A + 4 * c + (16 * t + 4 * g + s) * lda);
+        for (int t = 0; t < 16; ++t) aq[t] = quad(A + 4 * c + (4 * t + g) * lda);
+        // B -> LDS: column col = 4t + g at byte col * 256, its chunk c (l = 4c .. 4c+3) at ((c ^ col % 16) * 16)
 #pragma unroll
-            for (int bj = 0; bj < 4; ++bj) bq[bj][t] = quad(B + 16 * t + 4 * g + (16 * bj + c) * ldb);
+        for (int t = 0; t < 16; ++t) {
+            const int col = 4 * t + g;
+            *reinterpret_cast<floatx4 *>(region + col * 256 + ((c ^ (col & 15)) << 4)) = stage[t];
         }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     }
-    __builtin_amdgcn_sched_barrier(0);       // every operand load is issued before the first MFMA
+    // MFMA lane c of the B operand stands for column 16 bj + 4 (c % 4) + c / 4; its value for l = 4t + g is float g of
+    // chunk t of that column
+    const int mycol = 4 * (c & 3) + (c >> 2);
+    const char *mine = region + mycol * 256 + 4 * g;
+    const int twist = mycol << 4;
+    auto fetch_c = [&]() __attribute__((always_inline)) {
+        if (beta != 0.f) {
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        if (alpha != 0.f) {
+            for (int bj = 0; bj < 4; ++bj)
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
-#pragma unroll
-                for (int bj = 0; bj < 4; ++bj)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        acc[e][bj] = __builtin_amdgcn_mfma_f32_16x16x4f32(bq[bj][t][s], aq[t][s][e], acc[e][bj], 0, 0, 0);
+                for (int r = 0; r < 4; ++r) stage[4 * bj + r] = quad(C + 4 * c + (16 * bj + 4 * r + g) * ldc);
         }
-        if (t == 1) {
-            __builtin_amdgcn_sched_barrier(0);
-            if (beta != 0.f) {
+    };
 #pragma unroll
-                for (int bj = 0; bj < 4; ++bj)
+    for (int t = 0; t < 16; ++t) {
+        if (reads) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) cold[bj][r] = quad(C + 4 * c + (16 * bj + 4 * g + r) * ldc);
+            for (int bj = 0; bj < 4; ++bj) {
+                const float b = *reinterpret_cast<const float *>(mine + bj * (16 * 256) + (twist ^ (t << 4)));
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e][bj] = __builtin_amdgcn_mfma_f32_16x16x4f32(b, aq[t][e], acc[e][bj], 0, 0, 0);
             }
+        }
+        if (t == 3) {
+            __builtin_amdgcn_sched_barrier(0);
+            fetch_c();
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -288,8 +304,8 @@ __global__ __launch_bounds__(256) void batched_rows64_kernel(const BatchedArgs a
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             floatx4 o = alpha * floatx4{acc[0][bj][r], acc[1][bj][r], acc[2][bj][r], acc[3][bj][r]};
-            if (beta != 0.f) o += beta * cold[bj][r];
-            __builtin_nontemporal_store(o, reinterpret_cast<UnalignedQuad *>(C + 4 * c + (16 * bj + 4 * g + r) * ldc));
+            if (beta != 0.f) o += beta * stage[4 * bj + r];
+            __builtin_nontemporal_store(o, reinterpret_cast<UnalignedQuad *>(C + 4 * c + (16 * bj + 4 * r + g) * ldc));
         }
 }
 
