@@ -228,7 +228,8 @@ __global__ __launch_bounds__(256) void batched_wave_kernel(const BatchedArgs a)
 //     XORed with the column number, and one 4-byte read per MFMA group (lane: its column, l = 4t + g), both free of
 //     bank conflicts.  Only this wavefront touches the region and a wavefront's LDS operations execute in order.
 // The sum over l pairs A's value at l = 4t + g with B's at the same l.  All operand loads are issued at once, the old
-// C after a quarter of the MFMAs (into the registers B was staged in); C is written with streaming stores.
+// C behind the first group of MFMAs (into the registers B was staged in; asked for later, after a quarter or half of
+// the MFMAs, it costs 2 %); C is written with streaming stores.
 __global__ __launch_bounds__(256) void batched_rows64_kernel(const BatchedArgs a)
 {
     __shared__ __attribute__((aligned(16))) char turn[4][64 * 256];
@@ -293,7 +294,7 @@ __global__ __launch_bounds__(256) void batched_rows64_kernel(const BatchedArgs a
                 for (int e = 0; e < 4; ++e) acc[e][bj] = __builtin_amdgcn_mfma_f32_16x16x4f32(b, aq[t][e], acc[e][bj], 0, 0, 0);
             }
         }
-        if (t == 3) {
+        if (t == 0) {
             __builtin_amdgcn_sched_barrier(0);
             fetch_c();
             __builtin_amdgcn_sched_barrier(0);
