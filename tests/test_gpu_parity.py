@@ -171,6 +171,34 @@ def test_batched_alpha_zero_and_beta_zero_per_instance(G, oracle):
     assert H.rel_error(mats, c_ref, d_ref) <= H.TOL["f32"]
 
 
+def test_batched_whole_column_kernel_conventions(G, oracle):
+    """the 64^3 FP32 kernel whose lanes are rows of C (A along m, B along k; B goes through LDS): padded leading
+    dimensions (columns no longer adjacent in memory), shuffled offsets, alpha == 0 and beta == 0 per instance with NaN
+    where nothing may be read, an odd batch count (a work-group with idle wavefronts); bit-exact on integers; padding
+    between columns and the gaps between instances untouched; the row-major N/N call is the same canonical problem"""
+    try:
+        G.mg_override_batched_config(G.kernel_id("batched_rows_64_mk_full"))      # (a shape it does not take would be an error)
+        for layout, lda, ldb, ldc in ((C, 70, 67, 65), (C, None, None, None), (R, 66, 71, 64)):
+            bc = W.batched_case(64, 64, 64, 7, case=64, layout=layout, ta=N, tb=N, integer=True, lda=lda, ldb=ldb, ldc=ldc,
+                                shuffle_offsets=True)
+            bc.alphas[1] = 0.0
+            bc.betas[2] = 0.0
+            bc.alphas[5] = 0.0
+            bc.betas[5] = 0.0
+            la = W.storage_len(layout, N, 64, 64, bc.lda)
+            lc = W.storage_len(layout, N, 64, 64, bc.ldc)
+            for i in (1, 5):
+                bc.A[bc.a_off[i]: bc.a_off[i] + la] = np.nan         # must not be used: alpha == 0
+            for i in (2, 5):
+                live = ~W.padding_mask(layout, 64, 64, bc.ldc, lc)
+                view = bc.C[bc.c_off[i]: bc.c_off[i] + lc]
+                view[live] = np.nan                                  # must not be read: beta == 0
+            announce("rows64", bc.name, layout, bc.lda, bc.ldb, bc.ldc)
+            H.check_batched(bc, oracle, exact=True)
+    finally:
+        G.mg_clear_override()
+
+
 # ------------------------------------------------------------------ FP16-storage batched GEMM
 
 @pytest.mark.parametrize("size", W.CONFIG4_SIZES)
