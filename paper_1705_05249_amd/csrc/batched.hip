@@ -310,20 +310,110 @@ __global__ __launch_bounds__(256) void batched_rows64_kernel(const BatchedArgs a
         }
 }
 
-bool rows64_legal(const BatchedProblem &p)
+// The same for FP16 storage (v_mfma_f32_16x16x16_f16: an operand is four consecutive l of one row or column per lane).
+// Lane (c, g) loads rows 4c .. 4c+3 (8 bytes) of the four columns l = 16t + 4g + s of A; a 4 x 4 turn in registers (byte
+// permutes) makes the four operands "row 4c + e, l = 16t + 4g .. + 3".  B: 8 bytes of four consecutive l per lane, sixteen
+// lanes a whole column (128 bytes), four adjacent columns per instruction, through an 8 KB LDS region (8-byte writes, the
+// chunk index XORed with twice bits 1-3 of the column number: a half-wavefront's writes and its 8-byte reads, lane =
+// column, both cover all banks once).  C: 8 bytes of four consecutive rows per lane, whole adjacent columns.
+__global__ __launch_bounds__(256) void hbatched_rows64_kernel(const BatchedArgs a)
 {
-    if (p.dtype != MG_F32 || p.a_trans || p.b_trans) return false;
+    __shared__ __attribute__((aligned(16))) char turn[4][64 * 128];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+    const int64_t inst = static_cast<int64_t>(blockIdx.x) * 4 + wave;
+    if (inst >= a.batch) return;
+    const int lane = threadIdx.x % 64, c = lane % 16, g = lane / 16;
+    const float alpha = a.strided ? a.alpha : a.alphas[inst];
+    const float beta = a.strided ? a.beta : a.betas[inst];
+    const _Float16 *__restrict__ A = static_cast<const _Float16 *>(a.A) + (a.strided ? inst * a.stride_a : a.a_off[inst]);
+    const _Float16 *__restrict__ B = static_cast<const _Float16 *>(a.B) + (a.strided ? inst * a.stride_b : a.b_off[inst]);
+    _Float16 *__restrict__ C = static_cast<_Float16 *>(a.C) + (a.strided ? inst * a.stride_c : a.c_off[inst]);
+    const int lda = static_cast<int>(a.lda), ldb = static_cast<int>(a.ldb), ldc = static_cast<int>(a.ldc);
+    char *region = turn[wave];
+
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    auto quad = [](const _Float16 *p) {                       // four halves at element alignment, as two dwords
+        return __builtin_bit_cast(u32x2, *reinterpret_cast<const Quad<_Float16> *>(p));
+    };
+    floatx4 acc[4][4];                       // [e][bj]: rows 4c + e, columns 16 bj + 4r + g (r = register)
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int bj = 0; bj < 4; ++bj) acc[e][bj] = floatx4{0.f, 0.f, 0.f, 0.f};
+    u32x2 aq[4][4], stage[16];               // aq[t][s]: rows 4c.., l = 16t + 4g + s; stage[t]: B, l = 4c.., column 4t + g; later the old C
+    const bool reads = alpha != 0.f;         // alpha == 0: A and B are not read at all
+    if (reads) {
+#pragma unroll
+        for (int t = 0; t < 16; ++t) stage[t] = quad(B + 4 * c + (4 * t + g) * ldb);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) aq[t][s] = quad(A + 4 * c + (16 * t + 4 * g + s) * lda);
+        // B -> LDS: column col at byte col * 128, its chunk c (l = 4c .. 4c+3) at ((c ^ 2 * (col / 2 % 8)) * 8)
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const int col = 4 * t + g;
+            *reinterpret_cast<u32x2 *>(region + col * 128 + ((c ^ (((col >> 1) & 7) << 1)) << 3)) = stage[t];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+    // MFMA lane c of the B operand stands for column 16 bj + 4 (c % 4) + c / 4; its operand of K block t is chunk 4t + g
+    const int mycol = 4 * (c & 3) + (c >> 2);
+    const char *mine = region + mycol * 128;
+    const int twist = ((mycol >> 1) & 7) << 1;             // (the same for the four column blocks: 16 bj is a multiple of 16)
+    if (beta != 0.f) {
+#pragma unroll
+        for (int bj = 0; bj < 4; ++bj)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) stage[4 * bj + r] = quad(C + 4 * c + (16 * bj + 4 * r + g) * ldc);
+    }
+    if (reads) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            // rows 4c + e, l = 16t + 4g .. + 3: element e of the four loaded columns
+            halfx4 row[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+                const u32x2 v = {__builtin_amdgcn_perm(aq[t][1][e >> 1], aq[t][0][e >> 1], sel),
+                                 __builtin_amdgcn_perm(aq[t][3][e >> 1], aq[t][2][e >> 1], sel)};
+                row[e] = __builtin_bit_cast(halfx4, v);
+            }
+#pragma unroll
+            for (int bj = 0; bj < 4; ++bj) {
+                const halfx4 b = __builtin_bit_cast(halfx4, *reinterpret_cast<const u32x2 *>(mine + bj * (16 * 128) + (((4 * t + g) ^ twist) << 3)));
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e][bj] = __builtin_amdgcn_mfma_f32_16x16x16f16(b, row[e], acc[e][bj], 0, 0, 0);
+            }
+        }
+    }
+#pragma unroll
+    for (int bj = 0; bj < 4; ++bj)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            floatx4 o = alpha * floatx4{acc[0][bj][r], acc[1][bj][r], acc[2][bj][r], acc[3][bj][r]};
+            if (beta != 0.f) o += beta * widen(__builtin_bit_cast(halfx4, stage[4 * bj + r]));
+            *reinterpret_cast<Quad<_Float16> *>(C + 4 * c + (16 * bj + 4 * r + g) * ldc) =
+                Quad<_Float16>{static_cast<_Float16>(o.x), static_cast<_Float16>(o.y), static_cast<_Float16>(o.z), static_cast<_Float16>(o.w)};
+        }
+}
+
+template <int DTYPE> bool rows64_legal(const BatchedProblem &p)
+{
+    if (p.dtype != DTYPE || p.a_trans || p.b_trans) return false;
     if (p.m != 64 || p.n != 64 || p.k != 64 || p.batch >= (int64_t(1) << 32)) return false;
     const int64_t lim = int64_t(1) << 24;                    // offsets inside one instance are 32-bit in the kernel
     return p.lda < lim && p.ldb < lim && p.ldc < lim;
 }
 
-hipError_t rows64_launch(const BatchedProblem &p)
+template <int DTYPE> hipError_t rows64_launch(const BatchedProblem &p)
 {
     BatchedArgs a{p.A, p.B, p.C, p.a_off, p.b_off, p.c_off, p.alphas, p.betas, p.lda, p.ldb, p.ldc,
                   static_cast<int>(p.m), static_cast<int>(p.n), static_cast<int>(p.k), p.batch,
                   p.strided ? 1 : 0, p.stride_a, p.stride_b, p.stride_c, p.alpha, p.beta};
-    hipLaunchKernelGGL(batched_rows64_kernel, dim3(static_cast<unsigned>(ceil_div(p.batch, 4))), dim3(256), 0, p.stream, a);
+    if (DTYPE == MG_F32) hipLaunchKernelGGL(batched_rows64_kernel, dim3(static_cast<unsigned>(ceil_div(p.batch, 4))), dim3(256), 0, p.stream, a);
+    else hipLaunchKernelGGL(hbatched_rows64_kernel, dim3(static_cast<unsigned>(ceil_div(p.batch, 4))), dim3(256), 0, p.stream, a);
     return hipGetLastError();
 }
 
@@ -400,7 +490,11 @@ void register_batched(std::vector<KernelEntry> &table)
         c.waves_m = c.waves_n = 1;
         c.split_k = 1;
         c.threads = 256;
-        table.push_back(KernelEntry{"batched_rows_64_mk_full", c, nullptr, nullptr, nullptr, rows64_legal, rows64_launch});
+        c.lds_bytes = 4 * 64 * 256;
+        table.push_back(KernelEntry{"batched_rows_64_mk_full", c, nullptr, nullptr, nullptr, rows64_legal<MG_F32>, rows64_launch<MG_F32>});
+        c.dtype = MG_F16;
+        c.lds_bytes = 4 * 64 * 128;
+        table.push_back(KernelEntry{"hbatched_rows_64_mk_full", c, nullptr, nullptr, nullptr, rows64_legal<MG_F16>, rows64_launch<MG_F16>});
     }
 }
 

@@ -362,8 +362,8 @@ int32_t select_batched(const std::vector<KernelEntry> &table, const BatchedProbl
     const char *contig = p.a_trans ? (p.b_trans ? "kn" : "kk") : (p.b_trans ? "mn" : "mk");
     // whole 64^3 FP32 instances with A along m and B along k: the kernel whose lanes are rows of C reads A and moves C in
     // whole columns (256-byte runs instead of 64-byte ones): 10000 instances 155 -> 132 us, 1000 instances 14.5 -> 13.6 us
-    {
-        const int32_t id = find(table, "batched_rows_64_mk_full");
+    for (const char *name : {"batched_rows_64_mk_full", "hbatched_rows_64_mk_full"}) {
+        const int32_t id = find(table, name);
         if (id >= 0 && table[id].legal_batched(p)) return id;
     }
     for (int t = 0; t < 3; ++t) {
