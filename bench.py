@@ -338,6 +338,9 @@ def main():
                 batched_entry(f"sgemm_batched_f32_{batch}x{size}x{size}x{size}_gap7", W.config4_fast(size, batch))
         batched_entry("sgemm_strided_batched_f32_10000x16x16x16_gap7", W.config4_fast(16, 10000), strided=True)
         batched_entry("hgemm_batched_f16_10000x16x16x16_gap7", W.config4_fast(16, 10000, dtype="f16"))
+        if not only_headline:
+            batched_entry("hgemm_batched_f16_10000x64x64x64_gap7 (next row: FP16 storage; 328 MB moved, HBM-real)",
+                          W.config4_fast(64, 10000, dtype="f16"))
         # the HBM-real variant of the headline batched workload: ten times the instances (413 MB)
         batched_entry("sgemm_batched_f32_100000x16x16x16_gap7 (cold variant of 10000 x 16^3)", W.config4_fast(16, 100000))
 
