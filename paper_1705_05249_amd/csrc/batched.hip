@@ -230,11 +230,17 @@ __global__ __launch_bounds__(256) void batched_wave_kernel(const BatchedArgs a)
 // The sum over l pairs A's value at l = 4t + g with B's at the same l.  All operand loads are issued at once, the old
 // C behind the first group of MFMAs (into the registers B was staged in; asked for later, after a quarter or half of
 // the MFMAs, it costs 2 %); C is written with streaming stores.
-__global__ __launch_bounds__(256) void batched_rows64_kernel(const BatchedArgs a)
+// NS: wavefronts per instance.  With few instances (fewer wavefronts than the chip has SIMDs) an instance is cut into
+// four blocks of sixteen columns, one per wavefront of a work-group: each wavefront loads all of A (the L1 serves three
+// of the four), a quarter of B and C, and has a quarter of the MFMAs in its dependent chain.
+template <int NS> __global__ __launch_bounds__(256) void batched_rows64_kernel(const BatchedArgs a)
 {
-    __shared__ __attribute__((aligned(16))) char turn[4][64 * 256];
+    constexpr int NBJ = 4 / NS;              // 16-column blocks of this wavefront
+    __shared__ __attribute__((aligned(16))) char turn[4][NBJ * 16 * 256];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
-    const int64_t inst = static_cast<int64_t>(blockIdx.x) * 4 + wave;
+    const int64_t gw = static_cast<int64_t>(blockIdx.x) * 4 + wave;
+    const int64_t inst = gw / NS;
+    const int col0 = static_cast<int>(gw % NS) * NBJ * 16;       // first column of this wavefront's share
     if (inst >= a.batch) return;
     const int lane = threadIdx.x % 64, c = lane % 16, g = lane / 16;
     const float alpha = a.strided ? a.alpha : a.alphas[inst];
@@ -250,21 +256,21 @@ __global__ __launch_bounds__(256) void batched_rows64_kernel(const BatchedArgs a
         const Quad<float> u = *reinterpret_cast<const Quad<float> *>(p);
         return floatx4{u.x, u.y, u.z, u.w};
     };
-    floatx4 acc[4][4];                       // [e][bj]: rows 4c + e, columns 16 bj + 4r + g (r = register)
+    floatx4 acc[4][NBJ];                     // [e][bj]: rows 4c + e, columns col0 + 16 bj + 4r + g (r = register)
 #pragma unroll
     for (int e = 0; e < 4; ++e)
 #pragma unroll
-        for (int bj = 0; bj < 4; ++bj) acc[e][bj] = floatx4{0.f, 0.f, 0.f, 0.f};
-    floatx4 aq[16], stage[16];               // aq[t]: rows 4c.., l = 4t + g; stage[t]: B, l = 4c.., column 4t + g; later the old C
+        for (int bj = 0; bj < NBJ; ++bj) acc[e][bj] = floatx4{0.f, 0.f, 0.f, 0.f};
+    floatx4 aq[16], stage[4 * NBJ];               // aq[t]: rows 4c.., l = 4t + g; stage[t]: B, l = 4c.., column 4t + g; later the old C
     const bool reads = alpha != 0.f;         // alpha == 0: A and B are not read at all
     if (reads) {
 #pragma unroll
-        for (int t = 0; t < 16; ++t) stage[t] = quad(B + 4 * c + (4 * t + g) * ldb);
+        for (int t = 0; t < 4 * NBJ; ++t) stage[t] = quad(B + 4 * c + (col0 + 4 * t + g) * ldb);
 #pragma unroll
         for (int t = 0; t < 16; ++t) aq[t] = quad(A + 4 * c + (4 * t + g) * lda);
-        // B -> LDS: column col = 4t + g at byte col * 256, its chunk c (l = 4c .. 4c+3) at ((c ^ col % 16) * 16)
+        // B -> LDS: column col0 + col, col = 4t + g, at byte col * 256, its chunk c (l = 4c .. 4c+3) at ((c ^ col % 16) * 16)
 #pragma unroll
-        for (int t = 0; t < 16; ++t) {
+        for (int t = 0; t < 4 * NBJ; ++t) {
             const int col = 4 * t + g;
             *reinterpret_cast<floatx4 *>(region + col * 256 + ((c ^ (col & 15)) << 4)) = stage[t];
         }
@@ -279,16 +285,16 @@ __global__ __launch_bounds__(256) void batched_rows64_kernel(const BatchedArgs a
     auto fetch_c = [&]() __attribute__((always_inline)) {
         if (beta != 0.f) {
 #pragma unroll
-            for (int bj = 0; bj < 4; ++bj)
+            for (int bj = 0; bj < NBJ; ++bj)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) stage[4 * bj + r] = quad(C + 4 * c + (16 * bj + 4 * r + g) * ldc);
+                for (int r = 0; r < 4; ++r) stage[4 * bj + r] = quad(C + 4 * c + (col0 + 16 * bj + 4 * r + g) * ldc);
         }
     };
 #pragma unroll
     for (int t = 0; t < 16; ++t) {
         if (reads) {
 #pragma unroll
-            for (int bj = 0; bj < 4; ++bj) {
+            for (int bj = 0; bj < NBJ; ++bj) {
                 const float b = *reinterpret_cast<const float *>(mine + bj * (16 * 256) + (twist ^ (t << 4)));
 #pragma unroll
                 for (int e = 0; e < 4; ++e) acc[e][bj] = __builtin_amdgcn_mfma_f32_16x16x4f32(b, aq[t][e], acc[e][bj], 0, 0, 0);
@@ -301,12 +307,12 @@ __global__ __launch_bounds__(256) void batched_rows64_kernel(const BatchedArgs a
         }
     }
 #pragma unroll
-    for (int bj = 0; bj < 4; ++bj)
+    for (int bj = 0; bj < NBJ; ++bj)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             floatx4 o = alpha * floatx4{acc[0][bj][r], acc[1][bj][r], acc[2][bj][r], acc[3][bj][r]};
             if (beta != 0.f) o += beta * stage[4 * bj + r];
-            __builtin_nontemporal_store(o, reinterpret_cast<UnalignedQuad *>(C + 4 * c + (16 * bj + 4 * r + g) * ldc));
+            __builtin_nontemporal_store(o, reinterpret_cast<UnalignedQuad *>(C + 4 * c + (col0 + 16 * bj + 4 * r + g) * ldc));
         }
 }
 
@@ -402,17 +408,17 @@ __global__ __launch_bounds__(256) void hbatched_rows64_kernel(const BatchedArgs 
 template <int DTYPE> bool rows64_legal(const BatchedProblem &p)
 {
     if (p.dtype != DTYPE || p.a_trans || p.b_trans) return false;
-    if (p.m != 64 || p.n != 64 || p.k != 64 || p.batch >= (int64_t(1) << 32)) return false;
+    if (p.m != 64 || p.n != 64 || p.k != 64 || p.batch >= (int64_t(1) << 30)) return false;
     const int64_t lim = int64_t(1) << 24;                    // offsets inside one instance are 32-bit in the kernel
     return p.lda < lim && p.ldb < lim && p.ldc < lim;
 }
 
-template <int DTYPE> hipError_t rows64_launch(const BatchedProblem &p)
+template <int DTYPE, int NS = 1> hipError_t rows64_launch(const BatchedProblem &p)
 {
     BatchedArgs a{p.A, p.B, p.C, p.a_off, p.b_off, p.c_off, p.alphas, p.betas, p.lda, p.ldb, p.ldc,
                   static_cast<int>(p.m), static_cast<int>(p.n), static_cast<int>(p.k), p.batch,
                   p.strided ? 1 : 0, p.stride_a, p.stride_b, p.stride_c, p.alpha, p.beta};
-    if (DTYPE == MG_F32) hipLaunchKernelGGL(batched_rows64_kernel, dim3(static_cast<unsigned>(ceil_div(p.batch, 4))), dim3(256), 0, p.stream, a);
+    if (DTYPE == MG_F32) hipLaunchKernelGGL(batched_rows64_kernel<NS>, dim3(static_cast<unsigned>(ceil_div(p.batch * NS, 4))), dim3(256), 0, p.stream, a);
     else hipLaunchKernelGGL(hbatched_rows64_kernel, dim3(static_cast<unsigned>(ceil_div(p.batch, 4))), dim3(256), 0, p.stream, a);
     return hipGetLastError();
 }
@@ -492,6 +498,10 @@ void register_batched(std::vector<KernelEntry> &table)
         c.threads = 256;
         c.lds_bytes = 4 * 64 * 256;
         table.push_back(KernelEntry{"batched_rows_64_mk_full", c, nullptr, nullptr, nullptr, rows64_legal<MG_F32>, rows64_launch<MG_F32>});
+        c.waves_n = 4;
+        c.lds_bytes = 4 * 16 * 256;
+        table.push_back(KernelEntry{"batched_rows_64w4_mk_full", c, nullptr, nullptr, nullptr, rows64_legal<MG_F32>, rows64_launch<MG_F32, 4>});
+        c.waves_n = 1;
         c.dtype = MG_F16;
         c.lds_bytes = 4 * 64 * 128;
         table.push_back(KernelEntry{"hbatched_rows_64_mk_full", c, nullptr, nullptr, nullptr, rows64_legal<MG_F16>, rows64_launch<MG_F16>});

@@ -360,9 +360,11 @@ int32_t select_batched(const std::vector<KernelEntry> &table, const BatchedProbl
     const char *const *tags = p.batch >= 32 * kComputeUnits && (p.dtype != MG_F32 || whole16 || p.m > 16 || p.n > 16 || p.k > 16) ? many : few;
     const char *prefix = p.dtype == MG_F32 ? "" : "h";
     const char *contig = p.a_trans ? (p.b_trans ? "kn" : "kk") : (p.b_trans ? "mn" : "mk");
-    // whole 64^3 FP32 instances with A along m and B along k: the kernel whose lanes are rows of C reads A and moves C in
-    // whole columns (256-byte runs instead of 64-byte ones): 10000 instances 155 -> 132 us, 1000 instances 14.5 -> 13.6 us
-    for (const char *name : {"batched_rows_64_mk_full", "hbatched_rows_64_mk_full"}) {
+    // whole 64^3 instances with A along m and B along k: the kernels whose lanes are rows of C ask for A, B and C in whole
+    // adjacent columns (1 KB runs instead of 64-byte ones): FP32 10000 instances 155 -> 116 us, FP16 85 -> 49 us.  FP32 with
+    // four wavefronts per instance (a quarter of the columns each) is never slower than one and faster for few
+    // instances (us, one / four: 200 instances 8.9 / 6.0, 500: 9.8 / 7.8, 1000: 14.4 / 14.2, 4000: 43.3 / 41.6, 10000: 116.6 / 116.3)
+    for (const char *name : {"batched_rows_64w4_mk_full", "batched_rows_64_mk_full", "hbatched_rows_64_mk_full"}) {
         const int32_t id = find(table, name);
         if (id >= 0 && table[id].legal_batched(p)) return id;
     }
