@@ -106,7 +106,12 @@ struct MfmaConfig {
         if (p.shape != MG_SHAPE_GENERAL && split != 1) return false;      // a narrowed K range is never sliced
         if (p.m >= (int64_t(1) << 31) || p.n >= (int64_t(1) << 31) || p.k >= (int64_t(1) << 31)) return false;
         if (ceil_div(p.m, BM) * ceil_div(p.n, BN) >= (int64_t(1) << 31)) return false;
-        if (split + ceil_div(fringe_groups(p) * split, ceil_div(p.m - p.fringe_m, BM) * ceil_div(p.n - p.fringe_n, BN)) > 65535) return false;
+        {
+            // the fringe work-groups of all slices fill grid layers behind the tiles'; the kernel numbers them in 32 bits
+            const int64_t tiles = ceil_div(p.m - p.fringe_m, BM) * ceil_div(p.n - p.fringe_n, BN);
+            const int64_t layers = split + ceil_div(fringe_groups(p) * split, tiles);
+            if (layers > 65535 || layers * tiles >= (int64_t(1) << 31)) return false;
+        }
         if (split > 1 && static_cast<int64_t>(k_per_split(p, split)) * (split - 1) >= p.k) return false;  // empty slice
         {
             // lane offsets inside a tile are 32-bit byte offsets (both flavours)
