@@ -3,6 +3,6 @@
 namespace mg {
 void register_hmfma_256x256x64_w2x2(std::vector<KernelEntry> &table)
 {
-    MG_MFMA_REGISTER(table, _Float16, "hmfma_256x256x64_w2x2", 256, 256, 64, 2, 2)
+    MG_MFMA_REGISTER_WHOLE(table, _Float16, "hmfma_256x256x64_w2x2", 256, 256, 64, 2, 2)
 }
 }  // namespace mg

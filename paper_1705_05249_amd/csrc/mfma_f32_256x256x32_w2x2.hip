@@ -3,6 +3,6 @@
 namespace mg {
 void register_smfma_256x256x32_w2x2(std::vector<KernelEntry> &table)
 {
-    MG_MFMA_REGISTER(table, float, "smfma_256x256x32_w2x2", 256, 256, 32, 2, 2)
+    MG_MFMA_REGISTER_WHOLE(table, float, "smfma_256x256x32_w2x2", 256, 256, 32, 2, 2)
 }
 }  // namespace mg

@@ -159,12 +159,17 @@ struct MfmaConfig {
 
 // The four operand-contiguity cases of one tile shape, in the fast (aligned, whole tiles) and the
 // edge (anything) flavour.  Names: <t>mfma_<BM>x<BN>x<BK>_w<WM>x<WN>_<a><b>[_edge], a/b = k or m/n:
-// which direction the operand is contiguous in.
-#define MG_MFMA_REGISTER(table, T, tag, BM, BN, BK, WM, WN)                                                        \
+// which direction the operand is contiguous in.  (_WHOLE: the fast flavours alone, for the 256 x 256 tile on four
+// wavefronts, whose 256 accumulators per lane leave the bounds-checked loads no registers: that flavour would keep
+// 1.3 KB per lane in scratch memory and run an order of magnitude slower than the next tile down.)
+#define MG_MFMA_REGISTER_WHOLE(table, T, tag, BM, BN, BK, WM, WN)                                                  \
     table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, false, true, false>::entry(tag "_mk"));                      \
     table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, true, true, false>::entry(tag "_kk"));                       \
     table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, false, false, false>::entry(tag "_mn"));                     \
-    table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, true, false, false>::entry(tag "_kn"));                      \
+    table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, true, false, false>::entry(tag "_kn"));
+
+#define MG_MFMA_REGISTER(table, T, tag, BM, BN, BK, WM, WN)                                                        \
+    MG_MFMA_REGISTER_WHOLE(table, T, tag, BM, BN, BK, WM, WN)                                                      \
     table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, false, true, true>::entry(tag "_mk_edge"));                  \
     table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, true, true, true>::entry(tag "_kk_edge"));                   \
     table.push_back(MfmaConfig<T, BM, BN, BK, WM, WN, false, false, true>::entry(tag "_mn_edge"));                 \

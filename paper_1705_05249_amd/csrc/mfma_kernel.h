@@ -232,16 +232,15 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
     // byte offset of logical chunk c of row r inside the operand's LDS tile
     __device__ static inline int lds_offset(int r, int c) { return ldsmap::kcontig_slot<32>(r, c); }
 
-    // Bounds-checked flavour, FP32: whole K-tiles are loaded like the fast flavour's, with buffer loads (ragged
-    // problems of 2049^3 to 4104^3: 3-13 % faster; the FP16 kernels lost 10-17 % with the second code path in their
-    // loop and keep to the checked loads).  Tiles that lack rows at the matrix's edge do so too: their buffer
+    // Bounds-checked flavour: whole K-tiles are loaded like the fast flavour's, with buffer loads, where the operand's
+    // rows start on dword boundaries (FP16: an even leading dimension).  Tiles that lack rows at the matrix's edge do so too: their buffer
     // descriptor ends with the last row that exists (operand along k) resp. with the matrix (operand along its
     // rows), and a buffer load returns zero for every dword past the descriptor's range without touching memory;
     // lanes whose whole piece lies in missing rows are sent out of range on purpose (offset 2^31), a piece that
     // straddles the last row is cut when it is stored.  The kernel runs its K loop in two parts: K-tiles whose
     // reloads are all whole K-tiles take the fast flavour's schedule with these loads (load_one<Q, true>), the last
     // few, which hold the end of the sum, the checked loads.
-    static constexpr bool INTERIOR_FAST = EDGE && sizeof(T) == 4 && !CONV;
+    static constexpr bool INTERIOR_FAST = EDGE && !CONV;
     static constexpr uint32_t OUT_OF_RANGE = 0x80000000u;
 
     u32x4 regs[LOADS];
@@ -276,8 +275,14 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
             static_for<LOADS>([&](auto Qc) {
                 constexpr int Q = decltype(Qc)::value;
                 const int idx = t + Q * NT;
-                if constexpr (KCONTIG) goff[Q] = static_cast<uint32_t>(((idx / CPR) * ld_ + (idx % CPR) * CH) * sizeof(T));
-                else goff[Q] = (idx % RCH) * CH < rows ? static_cast<uint32_t>(((idx % RCH) * CH + (idx / RCH) * ld_) * sizeof(T)) : OUT_OF_RANGE;
+                if constexpr (KCONTIG) {
+                    goff[Q] = static_cast<uint32_t>(((idx / CPR) * ld_ + (idx % CPR) * CH) * sizeof(T));
+                } else if constexpr (NATIVE) {
+                    goff[Q] = (idx % RCH) * CH < rows ? static_cast<uint32_t>(((idx % RCH) * CH + (idx / RCH) * ld_) * sizeof(T)) : OUT_OF_RANGE;
+                } else {
+                    const Unit u = unit_of(Q / KU);
+                    goff[Q] = u.mc * CH < rows ? static_cast<uint32_t>((u.mc * CH + (u.kc * CH + u.s * KU + Q % KU) * ld_) * sizeof(T)) : OUT_OF_RANGE;
+                }
             });
 #pragma unroll
             for (int e = 0; e < CH; ++e) keep[e] = KCONTIG || (t % RCH) * CH + e < rows;
@@ -345,7 +350,9 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
             if (whole_ && rows_left_ < ROWS && k_left_ >= BK) {    // (k_left_ < BK: the checked loads, no descriptor)
                 // (far from the end of a long sum the matrix ends beyond 2^31 bytes: no limit needed, the tile's
                 // own offsets stay below that)
-                const int64_t bytes = (KCONTIG ? (rows_left_ - 1) * ld_ + k_left_ : (k_left_ - 1) * ld_ + rows_left_) * static_cast<int64_t>(sizeof(T));
+                // (whole dwords: the range check is per dword, and a dword that holds a valid FP16 element lies in the
+                // page of that element)
+                const int64_t bytes = ((KCONTIG ? (rows_left_ - 1) * ld_ + k_left_ : (k_left_ - 1) * ld_ + rows_left_) * static_cast<int64_t>(sizeof(T)) + 3) / 4 * 4;
                 range = bytes < 0x7fffffff ? static_cast<int>(bytes) : 0x7fffffff;
             }
         }
@@ -361,10 +368,14 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
     // `whole` set; no checks in the instruction stream
     template <int Q, bool FAST = false> __device__ inline void load_one()
     {
-        static_assert(!FAST || INTERIOR_FAST, "unchecked loads in the bounds-checked flavour: FP32 only");
+        static_assert(!FAST || INTERIOR_FAST, "unchecked loads in the bounds-checked flavour: not for the image gather");
         const int t = threadIdx.x;
         if constexpr (FAST) {
-            if (PARTIAL && t + Q * NT >= CHUNKS) return;
+            if constexpr (PLAIN) {
+                if (PARTIAL && t + Q * NT >= CHUNKS) return;
+            } else {
+                if (!unit_of(Q / KU).valid) return;
+            }
             regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
         } else if constexpr (KCONTIG) {
             const int idx = t + Q * NT;
@@ -405,6 +416,8 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
             const int l = u.kc * CH + u.s * KU + Q % KU;
             if constexpr (!EDGE) {
                 regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
+            } else if (INTERIOR_FAST && whole && k_left >= BK) {
+                if constexpr (INTERIOR_FAST) regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
             } else if constexpr (CONV) {
                 const int rv = l < k_left ? rows_left - u.mc * CH : 0;
                 conv_fetch<T>(raw[Q], base, geom, conv_i + u.mc * CH, l < k_left ? conv_l + l : 0, rv);
@@ -443,7 +456,10 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
             if constexpr (CONV && i == 0)          // first store of a unit: its pieces become 16-byte values now
                 static_for<KU>([&](auto P) { regs[(Q / CH) * KU + decltype(P)::value] = conv_pack<T>(raw[(Q / CH) * KU + decltype(P)::value]); });
             char *dst = lds + lds_offset(u.mc * CH + i, u.kc) + u.s * (16 / SPLIT);
-            const u32x4 row = transposed_row<i, KU>(&regs[(Q / CH) * KU], T{});
+            u32x4 row = transposed_row<i, KU>(&regs[(Q / CH) * KU], T{});
+            if constexpr (INTERIOR_FAST) {              // a row beyond the matrix's last one (its pieces may hold anything)
+                if (!keep[i]) row = u32x4{0u, 0u, 0u, 0u};
+            }
             if constexpr (SPLIT == 1) *reinterpret_cast<u32x4 *>(dst) = row;
             else if constexpr (SPLIT == 2) *reinterpret_cast<u32x2 *>(dst) = u32x2{row[0], row[1]};
             else *reinterpret_cast<uint32_t *>(dst) = row[0];

@@ -39,6 +39,11 @@ bool try_mfma(const std::vector<KernelEntry> &table, const Problem &p, int64_t a
     }
     snprintf(name, sizeof name, "%s_%s", tag, contig);
     if (try_pick(table, p, alignment, name, split, kernel, out_split)) return true;
+    // the register-staged 256 x 256 tile has its bounds-checked flavour on eight wavefronts only (on four, 256
+    // accumulators per lane leave the checked loads no registers).  Ragged FP16 cubes in place, us, this flavour /
+    // the best smaller tile: 3000 66-94 / 91-94, 5002 255-308 / 342-357, 4104 198-248 / 200-202, 2050 52-67 / 38-43
+    // (the estimate below ranks all four the right way round)
+    if (strcmp(tag, "hmfma_256x256x64_w2x2") == 0) tag = "hmfma_256x256x64_w2x4";
     snprintf(name, sizeof name, "%s_%s_edge", tag, contig);
     return try_pick(table, p, alignment, name, split, kernel, out_split);
 }
