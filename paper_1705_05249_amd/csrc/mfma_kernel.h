@@ -241,6 +241,11 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
     // reloads are all whole K-tiles take the fast flavour's schedule with these loads (load_one<Q, true>), the last
     // few, which hold the end of the sum, the checked loads.
     static constexpr bool INTERIOR_FAST = EDGE && !CONV;
+    // FP32 only: a whole K-tile that one of the checked bodies reloads takes the buffer loads as well.  The FP16 kernels
+    // are better off without that case at their checked load sites: with it, problems whose rows start at odd elements
+    // (which run every K-tile on the checked loads) lost 10-30 % ((1000, 1001, 999): 12.6 -> 15.2 us with A along m,
+    // 13.9 -> 18.1 us along k), and the others gained little from it (2050^3: 47 -> 43 us, 1000^3: 9.8 -> 10.1 us).
+    static constexpr bool CHECKED_WHOLE = INTERIOR_FAST && sizeof(T) == 4;
     static constexpr uint32_t OUT_OF_RANGE = 0x80000000u;
 
     u32x4 regs[LOADS];
@@ -384,8 +389,8 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
             const T *p = base + r * ld + c * CH;
             if constexpr (!EDGE) {
                 regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
-            } else if (INTERIOR_FAST && whole && k_left >= BK) {
-                if constexpr (INTERIOR_FAST) regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
+            } else if (CHECKED_WHOLE && whole && k_left >= BK) {
+                if constexpr (CHECKED_WHOLE) regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
             } else {
                 const int kv = k_left - c * CH;
                 if (r >= rows_left || kv <= 0) regs[Q] = u32x4{0u, 0u, 0u, 0u};
@@ -400,8 +405,8 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
             if (PARTIAL && idx >= CHUNKS) return;
             if constexpr (!EDGE) {
                 regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
-            } else if (INTERIOR_FAST && whole && k_left >= BK) {
-                if constexpr (INTERIOR_FAST) regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
+            } else if (CHECKED_WHOLE && whole && k_left >= BK) {
+                if constexpr (CHECKED_WHOLE) regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
             } else {
                 const T *p = base + mc * CH + l * ld;
                 const int rv = rows_left - mc * CH;
@@ -416,8 +421,8 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
             const int l = u.kc * CH + u.s * KU + Q % KU;
             if constexpr (!EDGE) {
                 regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
-            } else if (INTERIOR_FAST && whole && k_left >= BK) {
-                if constexpr (INTERIOR_FAST) regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
+            } else if (CHECKED_WHOLE && whole && k_left >= BK) {
+                if constexpr (CHECKED_WHOLE) regs[Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[Q], 0, 0);
             } else if constexpr (CONV) {
                 const int rv = l < k_left ? rows_left - u.mc * CH : 0;
                 conv_fetch<T>(raw[Q], base, geom, conv_i + u.mc * CH, l < k_left ? conv_l + l : 0, rv);
