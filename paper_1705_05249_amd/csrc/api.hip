@@ -179,6 +179,18 @@ bool indirect_plan(const Problem &p, bool pointers_known, IndirectPlan *plan)
         const bool aligned = p.lda % 8 == 0 && p.ldb % 8 == 0 &&
                              (!pointers_known || (pointer_alignment(p.A) >= 16 && pointer_alignment(p.B) >= 16));
         if (whole && aligned) return false;                            // the fast kernels take it directly
+        // Operands whose rows start on dwords run most of their K-tiles on the fast flavour's schedule inside the
+        // bounds-checked kernels, and the copies pay only where the product is long next to the matrices: below about
+        // 1000 multiply-adds per element moved the direct route wins.  Even leading dimensions, us direct / through
+        // the copies (A along m | along k): 1300^3 17.6 / 25.0 | 15.6 / 23.5, 1800^3 25.9 / 32.6 | 24.7 / 30.8, 2050^3
+        // 46.5 / 46.4 | 46.2 / 45.8, 2500^3 62.2 / 55.4 | 55.5 / 55.3, 3000^3 81.7 / 74.7 | 65.4 / 74.2, 3500^3 115 / 98 |
+        // 96 / 97, 4104^3 205 / 196, 6002^3 533 / 442 | 572 / 441; (4100, 4100, 512) 43.7 / 52.0 | 36.5 / 50.0,
+        // (8200, 1030, 2050) 60.9 / 78.1 | 53.9 / 81.5, (2050, 2050, 8200) 126 / 126 | 120 / 123.  (Without the
+        // pointers, for the workspace query, the copies are assumed: an upper bound.)
+        const bool dword_rows = p.lda % 2 == 0 && p.ldb % 2 == 0 && pointers_known && pointer_alignment(p.A) >= 4 &&
+                                pointer_alignment(p.B) >= 4;
+        const double moved = static_cast<double>(p.m) * p.k + static_cast<double>(p.k) * p.n + static_cast<double>(p.m) * p.n;
+        if (dword_rows && work < 1000.0 * moved) return false;
         tile = p.m >= 2048 && p.n >= 2048 ? 256 : 128;
         ktile = 64;
     } else {
