@@ -125,12 +125,15 @@ mg_status mg_sgemm(int layout, int trans_a, int trans_b, int64_t m, int64_t n, i
 
 /* FP16 storage (paper Section 4.4; here with FP32 accumulation): A, B, C hold IEEE binary16
  * values (2-byte aligned device pointers); alpha, beta are FP32 host scalars.
- * Large problems that are not whole tiles, or whose operands are not 16-byte aligned (an odd
- * leading dimension), take the indirect route of the paper's Section 3.2 when the workspace has
- * room: A, B (and C if beta != 0) are copied into zero-padded aligned buffers in the workspace, the
- * fast kernel runs there, the result is copied back (same arithmetic, one rounding).  With less
- * workspace the bounds-checked kernels run on the operands in place: same result up to summation
- * order, 1.2-2.4x slower.  mg_gemm_workspace_bytes() reports the room the indirect route needs. */
+ * Large problems that are not whole tiles, or whose operands are not 16-byte aligned, take the
+ * indirect route of the paper's Section 3.2 when it pays and the workspace has room: A, B (and C
+ * if beta != 0) are copied into zero-padded aligned buffers in the workspace, the fast kernel runs
+ * there, the result is copied back (same arithmetic, one rounding).  It pays from about 1300^3 when
+ * rows of A or B start at odd elements (an odd leading dimension) and from about 3000^3 when they
+ * start on 4-byte boundaries.  Otherwise, and with less workspace, the bounds-checked kernels run on
+ * the operands in place: same result up to summation order; rows at odd elements then cost up to
+ * 1.6x.  mg_gemm_workspace_bytes() reports the room the indirect route would need (it does not see
+ * the pointers: an upper bound). */
 mg_status mg_hgemm(int layout, int trans_a, int trans_b, int64_t m, int64_t n, int64_t k,
                    float alpha, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
                    float beta, uint16_t *C, int64_t ldc,
