@@ -64,6 +64,27 @@ def timed(fn, steps, warmup):
     return start.elapsed_time(stop) * 1e-3 / steps, wall
 
 
+def timed_each(fn, before, steps, warmup):
+    """device seconds per call of `fn`, each call between its own pair of events, with `before()` run untimed in
+    front of every call (an in-place routine gets its operand back that way: called over and over on its own
+    result, the values would overflow or die out within a few calls and the launches be timed on other data)"""
+    import torch
+    for _ in range(warmup):
+        before()
+        fn()
+    torch.cuda.synchronize()
+    pairs = []
+    for _ in range(steps):
+        before()
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record()
+        fn()
+        stop.record()
+        pairs.append((start, stop))
+    torch.cuda.synchronize()
+    return sum(a.elapsed_time(b) for a, b in pairs) * 1e-3 / steps
+
+
 def fastest_single(fn, calls=20):
     """device seconds of the fastest of `calls` launches, each between its own pair of events"""
     import torch
