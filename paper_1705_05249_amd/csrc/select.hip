@@ -362,7 +362,14 @@ int32_t select_batched(const std::vector<KernelEntry> &table, const BatchedProbl
     // (FP32 instances smaller than 16^3 take the bounds-checked flavour, which gains nothing from the second
     // instance: 10000 x 8^3 5.5 us one per wavefront, 5.9 us two)
     const bool whole16 = p.m == 16 && p.n == 16 && p.k == 16;
-    const char *const *tags = p.batch >= 32 * kComputeUnits && (p.dtype != MG_F32 || whole16 || p.m > 16 || p.n > 16 || p.k > 16) ? many : few;
+    // FP32 instances whose operands no longer fit the last-level cache by a wide margin (HBM-real calls) are faster one
+    // per wavefront again; 16^3, us one / two per wavefront: 120000 instances (379 MB of operands) 82.3 / 79.5, 140000
+    // (442 MB) 101.2 / 107.9, 160000 117.3 / 131.6, 200000 (631 MB) 145.6 / 162.7.  FP16 stays with two (320000 instances,
+    // 505 MB: 141.0 / 122.5).
+    const double operand_bytes = static_cast<double>(p.batch) * static_cast<double>(p.m * p.k + p.k * p.n + p.m * p.n) * (p.dtype == MG_F32 ? 4.0 : 2.0);
+    const bool streams_from_hbm = p.dtype == MG_F32 && operand_bytes > 410.0e6;
+    const char *const *tags = p.batch >= 32 * kComputeUnits && !streams_from_hbm &&
+                              (p.dtype != MG_F32 || whole16 || p.m > 16 || p.n > 16 || p.k > 16) ? many : few;
     const char *prefix = p.dtype == MG_F32 ? "" : "h";
     const char *contig = p.a_trans ? (p.b_trans ? "kn" : "kk") : (p.b_trans ? "mn" : "mk");
     // whole 64^3 instances with A along m and B along k: the kernels whose lanes are rows of C ask for A, B and C in whole
