@@ -237,9 +237,9 @@ template <typename T, int ROWS, int BK, int NT, bool KCONTIG, bool EDGE, bool CO
     // descriptor ends with the last row that exists (operand along k) resp. with the matrix (operand along its
     // rows), and a buffer load returns zero for every dword past the descriptor's range without touching memory;
     // lanes whose whole piece lies in missing rows are sent out of range on purpose (offset 2^31), a piece that
-    // straddles the last row is cut when it is stored.  The kernel runs its K loop in two parts: K-tiles whose
-    // reloads are all whole K-tiles take the fast flavour's schedule with these loads (load_one<Q, true>), the last
-    // few, which hold the end of the sum, the checked loads.
+    // straddles the last row is cut when it is stored.  The kernel's K loop: a body whose reload is a whole K-tile
+    // takes the fast flavour's schedule with these loads (load_one<Q, true>), the body that reloads the partial last
+    // K-tile the checked loads, and the last two bodies, with nothing left to reload, no loads.
     static constexpr bool INTERIOR_FAST = EDGE && !CONV;
     // FP32 only: a whole K-tile that one of the checked bodies reloads takes the buffer loads as well.  The FP16 kernels
     // are better off without that case at their checked load sites: with it, problems whose rows start at odd elements

@@ -221,7 +221,7 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 // on every tile: within 6 % of this, the small tiles a little better where the last turn is thin)
                 const double rounds = static_cast<double>(ceil_div(blocks, kComputeUnits));
                 const double up = ceil(rounds);
-                // (the bounds-checked flavour runs its whole K-tiles on the fast flavour's schedule and the last few on
+                // (the bounds-checked flavour runs its whole K-tiles on the fast flavour's schedule and the end of the sum on
                 // checked loads: 0.75 of these rates for a single turn, which has no other work-group's arithmetic to hide
                 // the checked part behind, 0.85 for two or more work-groups per compute unit; and every further work-group
                 // of a compute unit adds half a turn's fixed cost.  From 64 x 64 tiles, us measured / this estimate:
