@@ -391,6 +391,45 @@ def test_one_or_two_beyond_a_tile_multiple(G, oracle, dtype, layout, ta, tb):
         H.check_case(case, oracle)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("ta,tb", [(N, N), (T, N), (N, T), (T, T)])
+def test_bounds_checked_k_loop_ends(G, oracle, dtype, ta, tb):
+    """the bounds-checked tile kernels choose per K-tile how the staging registers are reloaded (the fast flavour's
+    loads, checked loads for the partial last K-tile, none for the last two tiles): sums of zero to six whole K-tiles
+    with and without a partial one, on the smallest bounds-checked tile (forced), rows on dword boundaries and (FP16)
+    at odd elements, ragged m and n, also cut into two slices; exact on integers"""
+    import torch
+    bk = 32 if dtype == "f32" else 64
+    tag = ("smfma_64x64x32_w2x2" if dtype == "f32" else "hmfma_64x64x64_w2x2")
+    contig = {(N, N): "mk", (T, N): "kk", (N, T): "mn", (T, T): "kn"}[(ta, tb)]
+    ws = torch.empty(8 << 20, dtype=torch.uint8, device="cuda")
+    m, n = 150, 70
+    try:
+        for whole in range(0, 7):
+            for rest in (0, 7, bk - 1):
+                k = whole * bk + rest
+                if k == 0:
+                    continue
+                for odd in ((0,) if dtype == "f32" else (0, 1)):
+                    for split in ((1, 2) if whole >= 4 else (1,)):
+                        # an even k keeps FP16 rows along k on dwords; `odd` moves them off
+                        kk = k + (k % 2 if dtype == "f16" else 0)
+                        lds = dict(lda=W.tight_ld(C, ta, m, kk) + 2 + odd, ldb=W.tight_ld(C, tb, kk, n) + 2 + odd,
+                                   ldc=W.tight_ld(C, N, m, n) + 1)
+                        if dtype == "f32":
+                            g = W.rng_for(11, 100 * whole + rest)
+                            case = W.make_case(f"kends_{m}x{n}x{kk}", "f32", C, ta, tb, W.small_ints(g, (m, kk)),
+                                               W.small_ints(g, (kk, n)), W.small_ints(g, (m, n)), 1.0, 1.0, exact=True, **lds)
+                        else:
+                            case = W.hgemm_case(m, n, kk, case=100 * whole + rest, layout=C, ta=ta, tb=tb, alpha=1.0, beta=1.0,
+                                                integer=True, **lds)
+                        G.mg_override_config(G.kernel_id(f"{tag}_{contig}_edge"), split)
+                        announce(case.name, "split", split, "ld +", 2 + odd, ta, tb)
+                        H.check_case(case, oracle, workspace=ws)
+    finally:
+        G.mg_clear_override()
+
+
 # ------------------------------------------------------------------ fringe rows / columns beside the tiles
 
 def _fringe_of(layout, m, n):
