@@ -206,7 +206,19 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
             // (rates against the whole-tile flavour: 0.75 for 256 x 256 and 256 x 128, about 0.5 for 128 x 128
             // and below; FP32: see below)
             const bool ragged = tm % tiles[i].bm || tn % tiles[i].bn || p.k % tiles[i].bk || tm != p.m || tn != p.n;
-            if (!f32 && ragged) order *= tiles[i].bm * tiles[i].bn < 256 * 128 ? 0.6 : 0.7;
+            // (operands whose rows start on dwords run their whole K-tiles on the fast schedule: fitted to ragged cubes of
+            // 1300 to 5002, (4100, 4100, 512) and (8200, 1030, 2050), every bounds-checked tile forced: the eight-wavefront
+            // 256 x 256 tile at its whole-tile rate, 256 x 128 at 0.77, 128 x 128 at 0.75 alone on a compute unit and 0.9
+            // with a second work-group to hide the checked part behind)
+            const bool dword_rows = !f32 && p.lda % 2 == 0 && p.ldb % 2 == 0;
+            if (!f32 && ragged) {
+                const int area = tiles[i].bm * tiles[i].bn;
+                if (!dword_rows) order *= area < 256 * 128 ? 0.6 : 0.7;
+                else if (area >= 256 * 256) order *= 1.0;
+                else if (area >= 256 * 128) order *= 0.77;
+                else if (area >= 128 * 128) order *= blocks > kComputeUnits ? 0.9 : 0.75;
+                else order *= 0.6;
+            }
             // rate of a compute unit that holds u work-groups at once: ceiling * (1 - (1 - per_group / ceiling)^u)
             // (measured on the 64 x 64 FP16 tile: 1.33 / 1.85 / 2.02 / 2.11 for u = 1..4, the formula gives
             // 1.31 / 1.86 / 2.09 / 2.18)
@@ -243,7 +255,7 @@ void select_config(const std::vector<KernelEntry> &table, const Problem &p, int6
                 // register-staged), 128 x 128 direct-to-LDS 1.3 when the busiest compute units hold two work-groups
                 // (324 tiles at 2304^3: 4.8 Mflop/us against 3.6) but 0.1 with one, the smaller register-staged
                 // kernels 0.1; the bounds-checked flavour shows no gain; the 128 x 128 direct-to-LDS tile at most 1.2
-                if (!ragged) {
+                if (!ragged || (dword_rows && i == 3)) {
                     const int64_t busiest = blocks - static_cast<int64_t>(kComputeUnits) * (per_unit - 1);
                     const double lower = per_unit > 1 ? shared_rate(per_unit - 1) : 0.0;
                     const double load = (static_cast<double>(busiest) * rate + static_cast<double>(kComputeUnits - busiest) * lower) /
