@@ -681,11 +681,12 @@ mg_status run_trmm(int dtype, int layout, int side, int uplo, int trans, int dia
     void *copy = carve.take(static_cast<size_t>(m) * n * elem);
     if (full == nullptr || copy == nullptr) return MG_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (launch_expand_triangular(dtype, ka, A, lda, lower_in_view(layout, uplo), diag == MG_UNIT, full, st) != hipSuccess)
-        return MG_ERR_LAUNCH;
-    // the product cannot run in place: B is copied (tightly packed, same layout) and then overwritten
+    // the product cannot run in place: B is copied (tightly packed, same layout) and then overwritten; the copy and
+    // the expansion of the triangular matrix go out as one launch
     const int64_t minor = layout == MG_COL_MAJOR ? m : n, major = layout == MG_COL_MAJOR ? n : m;
-    if (launch_copy_matrix(dtype, minor, major, B, ldb, copy, minor, st) != hipSuccess) return MG_ERR_LAUNCH;
+    if (launch_trmm_prepare(dtype, ka, A, lda, lower_in_view(layout, uplo), diag == MG_UNIT, full, minor, major, B, ldb, copy,
+                            minor, st) != hipSuccess)
+        return MG_ERR_LAUNCH;
     // Which canonical operand is triangular, and how: op(A) is lower when uplo and trans say so; a row-major
     // call runs as the transposed product, which swaps the operands and turns lower into upper.
     const bool op_lower = (uplo == MG_LOWER) == (trans == MG_NO_TRANS);

@@ -101,12 +101,11 @@ hipError_t launch_im2col(int dtype, const ConvShape &s, const void *im, void *co
 // dst <- the whole symmetric n x n matrix from its stored lower (i >= j) or upper triangle
 hipError_t launch_expand_symmetric(int dtype, int64_t n, const void *src, int64_t ld, bool lower, void *dst,
                                    hipStream_t stream);
-// dst <- the triangular n x n matrix with zeros outside the triangle and ones on a unit diagonal
-hipError_t launch_expand_triangular(int dtype, int64_t n, const void *src, int64_t ld, bool lower, bool unit, void *dst,
-                                    hipStream_t stream);
-// dst <- src: `major` runs of `minor` contiguous elements
-hipError_t launch_copy_matrix(int dtype, int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
-                              hipStream_t stream);
+// full <- the triangular n x n matrix with zeros outside the triangle and ones on a unit diagonal, and dst <- src
+// (`major` runs of `minor` contiguous elements), in one launch
+hipError_t launch_trmm_prepare(int dtype, int64_t n, const void *tri, int64_t ld, bool lower, bool unit, void *full,
+                               int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
+                               hipStream_t stream);
 // dst <- src on the strictly lower (i > j) or strictly upper entries of an n x n matrix
 hipError_t launch_copy_triangle(int dtype, int64_t n, const void *src, int64_t lds, void *dst, int64_t ldd, bool lower,
                                 hipStream_t stream);

@@ -89,14 +89,25 @@ __global__ __launch_bounds__(256) void expand_symmetric_kernel(int n, const U *_
 // that the row count is a multiple of V).  A thread owns rows [i, i + V) and walks columns
 // j = blockIdx.y, blockIdx.y + gridDim.y, ...
 
-// dst (n x n, leading dimension n) <- the triangular matrix: zero outside the stored triangle, one on
-// a unit diagonal; neither the other triangle of src nor (unit) its diagonal is read
+// The two passes in front of a triangular product as one launch (a dependent launch costs a 3.5-4 us gap).
+// blockIdx.z == 0: full (n x n, leading dimension n) <- the triangular matrix: zero outside the stored triangle, one
+// on a unit diagonal; neither the other triangle of tri nor (unit) its diagonal is read.  blockIdx.z == 1: dst
+// (leading dimension ldd) <- src (leading dimension lds), `minor` contiguous elements in each of `major` runs.  The
+// grid covers the larger of the two.
 template <typename T, int V>
-__global__ __launch_bounds__(256) void expand_triangular_kernel(int n, const T *__restrict__ src, int64_t ld, bool lower,
-                                                                bool unit, T *__restrict__ dst)
+__global__ __launch_bounds__(256) void trmm_prepare_kernel(int n, const T *__restrict__ tri, int64_t ld, bool lower, bool unit,
+                                                           T *__restrict__ full, int minor, int major,
+                                                           const T *__restrict__ src, int64_t lds, T *__restrict__ dst, int64_t ldd)
 {
     using P = Pack<T, V>;
     const int i = (blockIdx.x * 256 + threadIdx.x) * V;
+    if (blockIdx.z == 1) {
+        if (i >= minor) return;
+#pragma unroll 4
+        for (int j = blockIdx.y; j < major; j += gridDim.y)
+            *reinterpret_cast<P *>(dst + i + j * ldd) = *reinterpret_cast<const P *>(src + i + j * lds);
+        return;
+    }
     if (i >= n) return;
 #pragma unroll 4
     for (int j = blockIdx.y; j < n; j += gridDim.y) {
@@ -104,33 +115,19 @@ __global__ __launch_bounds__(256) void expand_triangular_kernel(int n, const T *
         const bool all_in = lower ? i > j : i + V - 1 < j;            // strictly inside: no diagonal element either
         const bool all_out = lower ? i + V - 1 < j : i > j;
         if (all_in) {
-            out = *reinterpret_cast<const P *>(src + i + j * ld);
+            out = *reinterpret_cast<const P *>(tri + i + j * ld);
         } else {
 #pragma unroll
             for (int e = 0; e < V; ++e) {
                 const int r = i + e;
                 const bool in = lower ? r >= j : r <= j;
                 T v = static_cast<T>(0.f);
-                if (!all_out && in) v = (unit && r == j) ? static_cast<T>(1.f) : src[r + j * ld];
+                if (!all_out && in) v = (unit && r == j) ? static_cast<T>(1.f) : tri[r + j * ld];
                 out.v[e] = v;
             }
         }
-        *reinterpret_cast<P *>(dst + i + static_cast<int64_t>(j) * n) = out;
+        *reinterpret_cast<P *>(full + i + static_cast<int64_t>(j) * n) = out;
     }
-}
-
-// dst (leading dimension ldd) <- src (leading dimension lds), `minor` contiguous elements in each of
-// `major` runs
-template <typename U, int V>
-__global__ __launch_bounds__(256) void copy_matrix_kernel(int minor, int major, const U *__restrict__ src, int64_t lds,
-                                                          U *__restrict__ dst, int64_t ldd)
-{
-    using P = Pack<U, V>;
-    const int i = (blockIdx.x * 256 + threadIdx.x) * V;
-    if (i >= minor) return;
-#pragma unroll 4
-    for (int j = blockIdx.y; j < major; j += gridDim.y)
-        *reinterpret_cast<P *>(dst + i + j * ldd) = *reinterpret_cast<const P *>(src + i + j * lds);
 }
 
 // the strictly lower (i > j) or strictly upper entries of an n x n matrix, src -> dst
@@ -307,37 +304,25 @@ hipError_t launch_expand_symmetric(int dtype, int64_t n, const void *src, int64_
         }                                                                                                             \
     } while (0)
 
-hipError_t launch_expand_triangular(int dtype, int64_t n, const void *src, int64_t ld, bool lower, bool unit, void *dst,
-                                    hipStream_t stream)
+hipError_t launch_trmm_prepare(int dtype, int64_t n, const void *tri, int64_t ld, bool lower, bool unit, void *full,
+                               int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
+                               hipStream_t stream)
 {
-    const bool aligned = runs_aligned(n, src, ld, dst, n, dtype == MG_F32 ? 4 : 2);
+    const int elem = dtype == MG_F32 ? 4 : 2;
+    const int v = runs_aligned(n, tri, ld, full, n, elem) && runs_aligned(minor, src, lds, dst, ldd, elem) ? 16 / elem : 1;
+    const dim3 a = column_grid(n, n, v), b = column_grid(minor, major, v);
+    const dim3 grid(a.x > b.x ? a.x : b.x, a.y > b.y ? a.y : b.y, 2);
+    const int nn = static_cast<int>(n), mi = static_cast<int>(minor), ma = static_cast<int>(major);
     if (dtype == MG_F32) {
-        const float *s = static_cast<const float *>(src);
-        float *d = static_cast<float *>(dst);
-        MG_LAUNCH_COLUMNWISE(expand_triangular_kernel, float, float, n, n, aligned, static_cast<int>(n), s, ld, lower, unit, d);
+        const float *t = static_cast<const float *>(tri), *s = static_cast<const float *>(src);
+        float *f = static_cast<float *>(full), *d = static_cast<float *>(dst);
+        if (v > 1) hipLaunchKernelGGL((trmm_prepare_kernel<float, 4>), grid, dim3(256), 0, stream, nn, t, ld, lower, unit, f, mi, ma, s, lds, d, ldd);
+        else hipLaunchKernelGGL((trmm_prepare_kernel<float, 1>), grid, dim3(256), 0, stream, nn, t, ld, lower, unit, f, mi, ma, s, lds, d, ldd);
     } else {
-        const _Float16 *s = static_cast<const _Float16 *>(src);
-        _Float16 *d = static_cast<_Float16 *>(dst);
-        MG_LAUNCH_COLUMNWISE(expand_triangular_kernel, _Float16, _Float16, n, n, aligned, static_cast<int>(n), s, ld, lower,
-                             unit, d);
-    }
-    return hipGetLastError();
-}
-
-hipError_t launch_copy_matrix(int dtype, int64_t minor, int64_t major, const void *src, int64_t lds, void *dst, int64_t ldd,
-                              hipStream_t stream)
-{
-    const bool aligned = runs_aligned(minor, src, lds, dst, ldd, dtype == MG_F32 ? 4 : 2);
-    if (dtype == MG_F32) {
-        const uint32_t *s = static_cast<const uint32_t *>(src);
-        uint32_t *d = static_cast<uint32_t *>(dst);
-        MG_LAUNCH_COLUMNWISE(copy_matrix_kernel, uint32_t, uint32_t, minor, major, aligned, static_cast<int>(minor),
-                             static_cast<int>(major), s, lds, d, ldd);
-    } else {
-        const uint16_t *s = static_cast<const uint16_t *>(src);
-        uint16_t *d = static_cast<uint16_t *>(dst);
-        MG_LAUNCH_COLUMNWISE(copy_matrix_kernel, uint16_t, uint16_t, minor, major, aligned, static_cast<int>(minor),
-                             static_cast<int>(major), s, lds, d, ldd);
+        const _Float16 *t = static_cast<const _Float16 *>(tri), *s = static_cast<const _Float16 *>(src);
+        _Float16 *f = static_cast<_Float16 *>(full), *d = static_cast<_Float16 *>(dst);
+        if (v > 1) hipLaunchKernelGGL((trmm_prepare_kernel<_Float16, 8>), grid, dim3(256), 0, stream, nn, t, ld, lower, unit, f, mi, ma, s, lds, d, ldd);
+        else hipLaunchKernelGGL((trmm_prepare_kernel<_Float16, 1>), grid, dim3(256), 0, stream, nn, t, ld, lower, unit, f, mi, ma, s, lds, d, ldd);
     }
     return hipGetLastError();
 }
