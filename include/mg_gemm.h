@@ -128,8 +128,9 @@ mg_status mg_sgemm(int layout, int trans_a, int trans_b, int64_t m, int64_t n, i
  * Large problems that are not whole tiles, or whose operands are not 16-byte aligned, take the
  * indirect route of the paper's Section 3.2 when it pays and the workspace has room: A, B (and C
  * if beta != 0) are copied into zero-padded aligned buffers in the workspace, the fast kernel runs
- * there, the result is copied back (same arithmetic, one rounding).  It pays from about 1300^3 when
- * rows of A or B start at odd elements (an odd leading dimension) and from about 3000^3 when they
+ * there, the result is copied back (same arithmetic, one rounding; large problems skip the copies
+ * of C: the kernel then reads and writes the caller's C itself).  It pays from about 1300^3 when
+ * rows of A or B start at odd elements (an odd leading dimension) and from about 2700^3 when they
  * start on 4-byte boundaries.  Otherwise, and with less workspace, the bounds-checked kernels run on
  * the operands in place: same result up to summation order; rows at odd elements then cost up to
  * 1.6x.  mg_gemm_workspace_bytes() reports the room the indirect route would need (it does not see

@@ -181,7 +181,9 @@ bool indirect_plan(const Problem &p, bool pointers_known, IndirectPlan *plan)
         if (whole && aligned) return false;                            // the fast kernels take it directly
         // Operands whose rows start on dwords run most of their K-tiles on the fast flavour's schedule inside the
         // bounds-checked kernels, and the copies pay only where the product is long next to the matrices: below about
-        // 1000 multiply-adds per element moved the direct route wins.  Even leading dimensions, us direct / through
+        // 900 multiply-adds per element moved the direct route wins (re-measured with the copies of C gone from the
+        // larger problems, direct / through the copies: 2051^3 42-44 / 47, 2501^3 56 / 57, 2801^3 66-68 / 69-71, 3001^3
+        // 73-86 / 71-73, (2051, 2051, 8201) 142-161 / 126-127).  Even leading dimensions, us direct / through
         // the copies (A along m | along k): 1300^3 17.6 / 25.0 | 15.6 / 23.5, 1800^3 25.9 / 32.6 | 24.7 / 30.8, 2050^3
         // 46.5 / 46.4 | 46.2 / 45.8, 2500^3 62.2 / 55.4 | 55.5 / 55.3, 3000^3 81.7 / 74.7 | 65.4 / 74.2, 3500^3 115 / 98 |
         // 96 / 97, 4104^3 205 / 196, 6002^3 533 / 442 | 572 / 441; (4100, 4100, 512) 43.7 / 52.0 | 36.5 / 50.0,
@@ -190,7 +192,7 @@ bool indirect_plan(const Problem &p, bool pointers_known, IndirectPlan *plan)
         const bool dword_rows = p.lda % 2 == 0 && p.ldb % 2 == 0 && pointers_known && pointer_alignment(p.A) >= 4 &&
                                 pointer_alignment(p.B) >= 4;
         const double moved = static_cast<double>(p.m) * p.k + static_cast<double>(p.k) * p.n + static_cast<double>(p.m) * p.n;
-        if (dword_rows && work < 1000.0 * moved) return false;
+        if (dword_rows && work < 900.0 * moved) return false;
         tile = p.m >= 2048 && p.n >= 2048 ? 256 : 128;
         ktile = 64;
     } else {
@@ -225,11 +227,33 @@ mg_status run_indirect(const Problem &p, const IndirectPlan &plan)
     const PadCopy copies[3] = {{a_minor, a_major, p.A, p.lda, ap, a_minor_p, a_minor_p, a_major_p},
                                {b_minor, b_major, p.B, p.ldb, bp, b_minor_p, b_minor_p, b_major_p},
                                {p.m, p.n, p.C, p.ldc, cp, plan.mp, plan.mp, plan.np}};
-    if (launch_pad_matrices(p.dtype, copies, p.beta != 0.f ? 3 : 2, st) != hipSuccess) return MG_ERR_LAUNCH;
     Problem q = p;
     q.m = plan.mp; q.n = plan.np; q.k = plan.kp;
     q.A = ap; q.lda = a_minor_p;
     q.B = bp; q.ldb = b_minor_p;
+    {
+        // Where a kernel with direct-to-LDS loads and a bounds-checked epilogue takes the padded product, only A and B
+        // are copied and C stays where it is: no copy of C in (beta != 0) and none out (each ~12 us at 4097^2 FP16, plus
+        // the 3.5-4 us gap of a dependent launch).
+        Problem direct_c = q;
+        direct_c.clip_m = p.m;
+        direct_c.clip_n = p.n;
+        direct_c.workspace = nullptr;
+        direct_c.workspace_bytes = 0;
+        // (only where the padded product would run on the 256 x 256 direct-to-LDS tile anyway, the one tile with such
+        // a flavour: at 2051^3, where it prefers smaller tiles, that flavour took 53.7 us against 46 us with the copies)
+        Problem padded = q;
+        padded.C = cp;
+        padded.ldc = plan.mp;
+        int32_t wanted = -1, wanted_split = 1, kernel = -1, split = 1;
+        const bool large_tile = choose(padded, problem_alignment(padded), 0, &wanted, &wanted_split) == MG_OK && wanted_split == 1 &&
+                                table()[wanted].cfg.tile_m == 256 && table()[wanted].cfg.tile_n == 256;
+        if (large_tile && choose(direct_c, problem_alignment(direct_c), 0, &kernel, &split) == MG_OK && split == 1) {
+            if (launch_pad_matrices(p.dtype, copies, 2, st) != hipSuccess) return MG_ERR_LAUNCH;
+            return table()[kernel].launch(direct_c, 1) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
+        }
+    }
+    if (launch_pad_matrices(p.dtype, copies, p.beta != 0.f ? 3 : 2, st) != hipSuccess) return MG_ERR_LAUNCH;
     q.C = cp; q.ldc = plan.mp;
     const size_t used = plan.total();
     q.workspace = p.workspace_bytes > used ? ws + used : nullptr;

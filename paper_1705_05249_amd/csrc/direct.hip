@@ -133,7 +133,7 @@ __global__ __launch_bounds__(256) void direct_batched_kernel(int64_t m, int64_t 
 
 bool always_legal(const Problem &p, int split_k, int64_t)
 {
-    return split_k == 1 && p.fringe_m == 0 && p.fringe_n == 0 && ceil_div(p.m, DT) * ceil_div(p.n, DT) < (int64_t(1) << 31);
+    return split_k == 1 && p.fringe_m == 0 && p.fringe_n == 0 && p.clip_m == 0 && p.clip_n == 0 && ceil_div(p.m, DT) * ceil_div(p.n, DT) < (int64_t(1) << 31);
 }
 size_t no_workspace(const Problem &, int) { return 0; }
 
@@ -157,7 +157,7 @@ template <typename T> hipError_t launch_scale(const Problem &p, int)
 
 bool scale_legal(const Problem &p, int split_k, int64_t)
 {
-    return split_k == 1 && p.fringe_m == 0 && p.fringe_n == 0 && (p.alpha == 0.f || p.k == 0) && ceil_div(p.m, 256) < (int64_t(1) << 31);
+    return split_k == 1 && p.fringe_m == 0 && p.fringe_n == 0 && p.clip_m == 0 && p.clip_n == 0 && (p.alpha == 0.f || p.k == 0) && ceil_div(p.m, 256) < (int64_t(1) << 31);
 }
 
 template <typename T> bool batched_direct_legal(const BatchedProblem &p)

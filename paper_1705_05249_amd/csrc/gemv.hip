@@ -251,7 +251,7 @@ template <typename T, int R> struct GemvShape {
 
 template <typename T, int R> bool gemv_legal(const Problem &p, int split, int64_t)
 {
-    if ((p.m != 1 && p.n != 1) || p.alpha == 0.f || p.k == 0 || p.fringe_m != 0 || p.fringe_n != 0) return false;
+    if ((p.m != 1 && p.n != 1) || p.alpha == 0.f || p.k == 0 || p.fringe_m != 0 || p.fringe_n != 0 || p.clip_m != 0 || p.clip_n != 0) return false;
     if (split < 1 || split > 256 || split > p.k) return false;
     if (p.dtype != (sizeof(T) == 4 ? MG_F32 : MG_F16)) return false;
     const View v = view_of(p);

@@ -50,7 +50,10 @@ struct Problem {
     int shape;                 // ProblemShape: where an operand is known to hold zeros / which part of C is wanted
     bool mask_c;               // shape C_LOWER / C_UPPER only: nothing outside that triangle of C may be written (or read);
                                // set only for kernels whose KernelEntry says masks_triangle
-    int fringe_m = 0, fringe_n = 0;   // the last rows / columns of C (at most 4 each) go to the fringe work-groups of a
+    int fringe_m = 0, fringe_n = 0;
+    // Rows and columns of C that exist when the tiles cover more (operands padded to whole tiles in a workspace, C
+    // the caller's own): the epilogue of a kernel that knows about it writes only those; 0: all of m x n.
+    int64_t clip_m = 0, clip_n = 0;   // the last rows / columns of C (at most 4 each) go to the fringe work-groups of a
                                // bounds-checked FP32 macro-tile launch, the tiles cover the rest; other kernels refuse
     const ConvShape *conv;     // non-null: A is an image and op(A) (m x k, "along m") its column matrix, never stored;
                                // only kernels of the family MG_FAMILY_CONV take such a problem

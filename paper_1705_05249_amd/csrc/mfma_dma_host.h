@@ -7,7 +7,9 @@
 
 namespace mg {
 
-template <int BM, int BN, int WM, int WN, bool AK, bool BKC, int RB = 32> struct MfmaDmaConfig {
+// CLIP: the flavour for operands padded to whole tiles in a workspace and the caller's own C (Problem::clip_m, clip_n):
+// its epilogue is the bounds-checked one, so the padded product needs no copy of C in and out.
+template <int BM, int BN, int WM, int WN, bool AK, bool BKC, int RB = 32, bool CLIP = false> struct MfmaDmaConfig {
     using Staged = MfmaConfig<_Float16, BM, BN, 64, WM, WN, AK, BKC, false>;   // same legality and split-K rules
     static constexpr int NT = WM * WN * 64;
     static constexpr int LDS = Staged::LDS;
@@ -15,7 +17,12 @@ template <int BM, int BN, int WM, int WN, bool AK, bool BKC, int RB = 32> struct
     // the direct-to-LDS loads keep the 16-byte alignment of whole chunks
     static bool legal(const Problem &p, int split, int64_t alignment)
     {
-        if (!Staged::legal(p, split, alignment)) return false;
+        if ((p.clip_m != 0 || p.clip_n != 0) != CLIP) return false;
+        Problem whole = p;
+        whole.clip_m = whole.clip_n = 0;
+        if (!Staged::legal(whole, split, alignment)) return false;
+        // (the partial sums of a sliced product have the padded extents, which the caller's C has not)
+        if (CLIP && (split != 1 || p.clip_m < 1 || p.clip_m > p.m || p.clip_n < 1 || p.clip_n > p.n || p.shape != MG_SHAPE_GENERAL)) return false;
         if (p.lda % 8 || p.ldb % 8) return false;
         if (pointer_alignment(p.A) < 16 || pointer_alignment(p.B) < 16) return false;
         return p.A != nullptr || alignment >= 16;
@@ -24,7 +31,7 @@ template <int BM, int BN, int WM, int WN, bool AK, bool BKC, int RB = 32> struct
     static hipError_t launch(const Problem &p, int split)
     {
         static bool attr_set = false;   // raising the dynamic LDS limit is idempotent; races are harmless
-        return launch_tile_kernel<_Float16>(hgemm_dma_kernel<BM, BN, WM, WN, AK, BKC, RB>, &attr_set, LDS, NT, BM, BN,
+        return launch_tile_kernel<_Float16>(hgemm_dma_kernel<BM, BN, WM, WN, AK, BKC, RB, 0, CLIP>, &attr_set, LDS, NT, BM, BN,
                                             Staged::k_per_split(p, split), p, split);
     }
 
@@ -39,14 +46,14 @@ template <int BM, int BN, int WM, int WN, bool AK, bool BKC, int RB = 32> struct
 
 // The kernel whose wavefronts take turns (mfma_pp_kernel.h): 256 x 256 tiles, 2 x 4 wavefronts, 16x16x32 blocks,
 // B contiguous along k.  Same legality as the direct-to-LDS kernels; 1 KB more LDS (the dump area).
-template <bool AK> struct MfmaPpConfig {
-    using Dma = MfmaDmaConfig<256, 256, 2, 4, AK, true, 16>;
+template <bool AK, bool CLIP = false> struct MfmaPpConfig {
+    using Dma = MfmaDmaConfig<256, 256, 2, 4, AK, true, 16, CLIP>;
     static constexpr int LDS = Dma::LDS + 1024;
 
     static hipError_t launch(const Problem &p, int split)
     {
         static bool attr_set = false;
-        return launch_tile_kernel<_Float16>(hgemm_pp_kernel<256, 256, 2, 4, AK, true, 16, 1, 8>, &attr_set, LDS, Dma::NT, 256,
+        return launch_tile_kernel<_Float16>(hgemm_pp_kernel<256, 256, 2, 4, AK, true, 16, 1, 8, CLIP>, &attr_set, LDS, Dma::NT, 256,
                                             256, Dma::Staged::k_per_split(p, split), p, split);
     }
 

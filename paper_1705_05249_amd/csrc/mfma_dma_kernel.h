@@ -114,7 +114,7 @@ __device__ inline u32x4 read_operand(lds_char *lds3, const int (&frag)[8])
     }
 }
 
-template <int BM, int BN, int WM, int WN, bool A_KCONTIG, bool B_KCONTIG, int RB = 32, int PROBE = 0>
+template <int BM, int BN, int WM, int WN, bool A_KCONTIG, bool B_KCONTIG, int RB = 32, int PROBE = 0, bool CLIP = false>
 __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs args)
 {
 #if defined(__HIP_DEVICE_COMPILE__)      // the host pass needs the kernel's symbol only (LDS address-space code is device code)
@@ -319,7 +319,7 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_dma_kernel(const MfmaArgs a
             out[7] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));     // HW_ID
         }
     } else {
-        tile_epilogue<T, RB, FM, FN, WTM, WTN, false>(acc, args, lds, m0, n0, wm, wn, wave, lane);
+        tile_epilogue<T, RB, FM, FN, WTM, WTN, CLIP>(acc, args, lds, m0, n0, wm, wn, wave, lane);       // CLIP: C may end inside the tile
     }
 #else
     (void)args;

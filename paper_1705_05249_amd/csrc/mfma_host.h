@@ -35,7 +35,8 @@ hipError_t launch_tile_kernel(Kernel kernel, bool *attr_set, int lds_bytes, int 
     a.partial = split > 1 ? static_cast<float *>(p.workspace) : nullptr;
     a.lda = p.lda; a.ldb = p.ldb; a.ldc = p.ldc;
     a.m = static_cast<int>(p.m); a.n = static_cast<int>(p.n); a.k = static_cast<int>(p.k);
-    a.m_main = static_cast<int>(p.m - p.fringe_m); a.n_main = static_cast<int>(p.n - p.fringe_n);
+    a.m_main = static_cast<int>(p.clip_m > 0 ? p.clip_m : p.m - p.fringe_m);
+    a.n_main = static_cast<int>(p.clip_n > 0 ? p.clip_n : p.n - p.fringe_n);
     a.alpha = p.alpha; a.beta = p.beta;
     a.tiles_m = static_cast<int>(ceil_div(a.m_main, bm));
     a.tiles_n = static_cast<int>(ceil_div(a.n_main, bn));
@@ -95,6 +96,7 @@ struct MfmaConfig {
     static bool legal(const Problem &p, int split, int64_t alignment)
     {
         if (p.dtype != DTYPE || p.a_trans != AK || p.b_trans == BKC) return false;
+        if (p.clip_m != 0 || p.clip_n != 0) return false;          // only kernels built for it (mfma_dma_host.h)
         if (p.fringe_m != 0 || p.fringe_n != 0) {
             if (!FRINGE || p.shape != MG_SHAPE_GENERAL || p.mask_c) return false;
             if (p.fringe_m < 0 || p.fringe_m > FRINGE_MAX || p.fringe_n < 0 || p.fringe_n > FRINGE_MAX) return false;

@@ -118,7 +118,7 @@ __device__ inline void mma_in_place(floatx16 &acc, const u32x4 &frag_n, const u3
 }
 
 // OPT bits: 1 = raise the wavefront's priority for the run of MFMAs; 2 = cycle stamps (diagnostic builds)
-template <int BM, int BN, int WM, int WN, bool A_KCONTIG, bool B_KCONTIG, int RB = 16, int OPT = 1, int NM = 2>
+template <int BM, int BN, int WM, int WN, bool A_KCONTIG, bool B_KCONTIG, int RB = 16, int OPT = 1, int NM = 2, bool CLIP = false>
 __global__ __launch_bounds__(WM *WN * 64) void hgemm_pp_kernel(const MfmaArgs args)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -386,7 +386,7 @@ __global__ __launch_bounds__(WM *WN * 64) void hgemm_pp_kernel(const MfmaArgs ar
             out[11] = static_cast<uint64_t>(ktiles);
         }
     } else {
-        tile_epilogue<T, RB, FM, FN, WTM, WTN, false>(acc, args, lds, m0, n0, wm, wn, wave, lane);
+        tile_epilogue<T, RB, FM, FN, WTM, WTN, CLIP>(acc, args, lds, m0, n0, wm, wn, wave, lane);      // CLIP: C may end inside the tile
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);        // unwanted loads of the last tiles may still be on their way to the dump area
 #else

@@ -31,6 +31,13 @@ bool try_mfma(const std::vector<KernelEntry> &table, const Problem &p, int64_t a
 {
     char name[96];
     const char *contig = p.a_trans ? (p.b_trans ? "kn" : "kk") : (p.b_trans ? "mn" : "mk");
+    // operands padded to whole tiles and the caller's own C (Problem::clip_m, clip_n): the 256 x 256 direct-to-LDS
+    // kernels have a flavour whose epilogue checks bounds, nothing else has
+    if (p.clip_m != 0 || p.clip_n != 0) {
+        if (strcmp(tag, "hdma16_256x256x64_w2x4") != 0) return false;
+        snprintf(name, sizeof name, "%s_256x256x64_w2x4_%s", p.b_trans ? "hdma16c" : "hpp16c", contig);
+        return try_pick(table, p, alignment, name, split, kernel, out_split);
+    }
     // with B contiguous along k the 256 x 256 direct-to-LDS tile has a faster schedule (wavefronts taking turns:
     // 4096^3 102 -> 99 us, 8192^3 820 -> 747 us, 2048^3 42 -> 38 us)
     if (!p.b_trans && strcmp(tag, "hdma16_256x256x64_w2x4") == 0) {

@@ -210,7 +210,7 @@ template <typename T, bool AK, bool BKC> struct TinyConfig {
     {
         (void)alignment;
         if (p.dtype != DTYPE || p.a_trans != AK || p.b_trans == BKC || split != 1) return false;
-        if (p.conv != nullptr || p.fringe_m != 0 || p.fringe_n != 0) return false;
+        if (p.conv != nullptr || p.fringe_m != 0 || p.fringe_n != 0 || p.clip_m != 0 || p.clip_n != 0) return false;
         if (p.alpha == 0.f || p.k == 0 || p.shape != MG_SHAPE_GENERAL) return false;
         if (p.m >= (int64_t(1) << 31) || p.n >= (int64_t(1) << 31) || p.k >= (int64_t(1) << 31)) return false;
         return ceil_div(p.m, 32) * ceil_div(p.n, 32) < (int64_t(1) << 31);

@@ -545,8 +545,11 @@ def _probe_cases(dtype):
 def test_every_kernel_configuration_gives_parity(G, oracle, dtype):
     import torch
     code = G.MG_F32 if dtype == "f32" else G.MG_F16
+    # (not here: the convolution kernels, tests/test_gpu_conv.py, and the flavour for padded operands with the caller's
+    # own C, which only the indirect route can call: test_indirect_route_for_ragged_half_problems)
     kernels = [t for t in G.kernel_table() if t["dtype"] == code and t["family"] not in
-               (G.MG_FAMILY_BATCHED, G.MG_FAMILY_SCALE, G.MG_FAMILY_CONV)]        # the last: tests/test_gpu_conv.py
+               (G.MG_FAMILY_BATCHED, G.MG_FAMILY_SCALE, G.MG_FAMILY_CONV) and
+               not t["name"].startswith(("hpp16c_", "hdma16c_"))]
     ran = {t["name"]: 0 for t in kernels}
     ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
     try:
@@ -598,7 +601,8 @@ def test_direct_to_lds_kernels(G, oracle, shape):
     """every direct-to-LDS kernel, all operand orders: one K-tile, an odd number of K-tiles, several tiles of C;
     bit-exact on integers (beta = 1) and within tolerance on random data"""
     m, n, k = shape
-    names = [t["name"] for t in G.kernel_table() if t["name"].startswith(("hdma", "hpp"))]
+    names = [t["name"] for t in G.kernel_table() if t["name"].startswith(("hdma", "hpp")) and
+             not t["name"].startswith(("hpp16c_", "hdma16c_"))]              # (those: the indirect route's own)
     assert names
     orders = {"mk": (N, N), "kk": (T, N), "mn": (N, T), "kn": (T, T)}
     try:
@@ -686,12 +690,20 @@ def test_indirect_route_for_ragged_half_problems(G, oracle, ta, tb):
     written; without workspace, or with too little, the direct route runs and gives the same result"""
     import torch
     for (m, n, k), layout, beta, integer in (((1025, 2060, 1100), C, 0.0, True), ((1025, 2060, 1100), C, 0.5, False),
-                                             ((1100, 2049, 1000), R, 1.0, True), ((2048, 1024, 1088), C, 0.25, False)):
+                                             ((1100, 2049, 1000), R, 1.0, True), ((2817, 3001, 500), C, 0.5, False),
+                                             ((2817, 3001, 500), R, 1.0, True), ((2048, 1024, 1088), C, 0.25, False)):
+        # (2817, 3001, 500) pads to 3072 x 3072 x 512, which runs on 256 x 256 direct-to-LDS tiles: their flavour with a
+        # bounds-checked epilogue writes the caller's C directly (no copy of C in or out); odd leading dimensions in
+        # every operand order, so that all four kernels of that flavour run
         # the last shape is whole tiles with odd leading dimensions: only the alignment breaks the fast path
         lds = {}
         if (m, n, k) == (2048, 1024, 1088):
             lds = dict(lda=W.tight_ld(layout, ta, m, k) + 1, ldb=W.tight_ld(layout, tb, k, n) + 1,
                        ldc=W.tight_ld(layout, N, m, n) + 1)
+        if (m, n, k) == (2817, 3001, 500):
+            odd = lambda ld: ld + 1 - ld % 2
+            lds = dict(lda=odd(W.tight_ld(layout, ta, m, k)), ldb=odd(W.tight_ld(layout, tb, k, n)),
+                       ldc=odd(W.tight_ld(layout, N, m, n)))
         case = W.hgemm_case(m, n, k, case=41, layout=layout, ta=ta, tb=tb, alpha=1.0, beta=beta, integer=integer, **lds)
         need = G.mg_gemm_workspace_bytes(G.MG_F16, case.layout, case.ta, case.tb, m, n, k, case.lda, case.ldb, case.ldc)
         assert need >= 2 * (m * k + k * n + m * n), "the query must ask for room for the padded copies"
