@@ -240,15 +240,16 @@ mg_status run_indirect(const Problem &p, const IndirectPlan &plan)
         direct_c.clip_n = p.n;
         direct_c.workspace = nullptr;
         direct_c.workspace_bytes = 0;
-        // (only where the padded product would run on the 256 x 256 direct-to-LDS tile anyway, the one tile with such
-        // a flavour: at 2051^3, where it prefers smaller tiles, that flavour took 53.7 us against 46 us with the copies)
+        // (only where the padded product would run on a tile that has such a flavour anyway: forced onto the 256 x 256
+        // tile, 2051^3, which prefers smaller ones, took 53.7 us against 46 us with the copies)
         Problem padded = q;
         padded.C = cp;
         padded.ldc = plan.mp;
         int32_t wanted = -1, wanted_split = 1, kernel = -1, split = 1;
-        const bool large_tile = choose(padded, problem_alignment(padded), 0, &wanted, &wanted_split) == MG_OK && wanted_split == 1 &&
-                                table()[wanted].cfg.tile_m == 256 && table()[wanted].cfg.tile_n == 256;
-        if (large_tile && choose(direct_c, problem_alignment(direct_c), 0, &kernel, &split) == MG_OK && split == 1) {
+        const bool unsplit = choose(padded, problem_alignment(padded), 0, &wanted, &wanted_split) == MG_OK && wanted_split == 1;
+        if (unsplit && choose(direct_c, problem_alignment(direct_c), 0, &kernel, &split) == MG_OK && split == 1 &&
+            table()[kernel].cfg.tile_m == table()[wanted].cfg.tile_m && table()[kernel].cfg.tile_n == table()[wanted].cfg.tile_n &&
+            table()[kernel].cfg.waves_m * table()[kernel].cfg.waves_n == table()[wanted].cfg.waves_m * table()[wanted].cfg.waves_n) {
             if (launch_pad_matrices(p.dtype, copies, 2, st) != hipSuccess) return MG_ERR_LAUNCH;
             return table()[kernel].launch(direct_c, 1) == hipSuccess ? MG_OK : MG_ERR_LAUNCH;
         }

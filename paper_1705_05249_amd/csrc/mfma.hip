@@ -11,7 +11,7 @@ void register_hmfma_64x64x64_w2x2(std::vector<KernelEntry> &table);
 void register_hdma16_256x256x64(std::vector<KernelEntry> &table);
 void register_hdma16_small(std::vector<KernelEntry> &table);
 void register_hpp16_256x256x64(std::vector<KernelEntry> &table);
-void register_hclip_256x256x64(std::vector<KernelEntry> &table);
+void register_hclip(std::vector<KernelEntry> &table);
 void register_tiny(std::vector<KernelEntry> &table);
 void register_hdma_256x256x64_w2x2(std::vector<KernelEntry> &table);
 void register_hdma_256x256x64_w2x4(std::vector<KernelEntry> &table);
@@ -34,7 +34,7 @@ void register_mfma(std::vector<KernelEntry> &table)
     register_hdma16_256x256x64(table);
     register_hdma16_small(table);
     register_hpp16_256x256x64(table);
-    register_hclip_256x256x64(table);
+    register_hclip(table);
     register_hdma_256x256x64_w2x2(table);
     register_hdma_256x256x64_w2x4(table);
     register_smfma_256x256x32_w2x2(table);

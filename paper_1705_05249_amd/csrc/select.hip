@@ -31,11 +31,15 @@ bool try_mfma(const std::vector<KernelEntry> &table, const Problem &p, int64_t a
 {
     char name[96];
     const char *contig = p.a_trans ? (p.b_trans ? "kn" : "kk") : (p.b_trans ? "mn" : "mk");
-    // operands padded to whole tiles and the caller's own C (Problem::clip_m, clip_n): the 256 x 256 direct-to-LDS
-    // kernels have a flavour whose epilogue checks bounds, nothing else has
+    // operands padded to whole tiles and the caller's own C (Problem::clip_m, clip_n): the 256 x 256 and the 128 x 128
+    // direct-to-LDS kernels have a flavour whose epilogue checks bounds, nothing else has
     if (p.clip_m != 0 || p.clip_n != 0) {
-        if (strcmp(tag, "hdma16_256x256x64_w2x4") != 0) return false;
-        snprintf(name, sizeof name, "%s_256x256x64_w2x4_%s", p.b_trans ? "hdma16c" : "hpp16c", contig);
+        if (strcmp(tag, "hdma16_256x256x64_w2x4") == 0)
+            snprintf(name, sizeof name, "%s_256x256x64_w2x4_%s", p.b_trans ? "hdma16c" : "hpp16c", contig);
+        else if (strcmp(tag, "hdma16_128x128x64_w2x4") == 0)
+            snprintf(name, sizeof name, "hdma16c_128x128x64_w2x4_%s", contig);
+        else
+            return false;
         return try_pick(table, p, alignment, name, split, kernel, out_split);
     }
     // with B contiguous along k the 256 x 256 direct-to-LDS tile has a faster schedule (wavefronts taking turns:
